@@ -1,0 +1,143 @@
+"""ctypes front end of the CPU oracle (oracle/adacc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+the cpu_baseline leg of bench.py.  The product package never imports this module
+and this module never imports the product package.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+from .build import build as _build, LIB as _LIB
+
+OUT_NONE, OUT_ABS, OUT_STD, OUT_TOPK = 0, 1, 2, 3
+RULE_PAPER, RULE_FULLRANGE = 0, 1
+
+
+class _CMethod(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_uint32), ("quant_group", ctypes.c_uint32), ("asym", ctypes.c_uint32),
+                ("scale_rule", ctypes.c_uint32), ("outlier_mode", ctypes.c_uint32),
+                ("stat_group", ctypes.c_uint32), ("thresh", ctypes.c_float), ("topk", ctypes.c_uint32)]
+
+
+@dataclass
+class Method:
+    bits: int = 8
+    quant_group: int = 64
+    asym: int = 0
+    scale_rule: int = RULE_PAPER
+    outlier_mode: int = OUT_NONE
+    stat_group: int = 0
+    thresh: float = 0.0
+    topk: int = 0
+
+    def c(self):
+        return _CMethod(self.bits, self.quant_group, self.asym, self.scale_rule, self.outlier_mode,
+                        self.stat_group, float(self.thresh), self.topk)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            _build(force=True)
+        L = ctypes.CDLL(_LIB)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.oracle_select_outliers.argtypes = [ctypes.POINTER(_CMethod), vp, sz, vp]
+        L.oracle_select_outliers.restype = ctypes.c_int
+        L.oracle_compress.argtypes = [ctypes.POINTER(_CMethod), vp, sz, vp, vp, vp, vp, vp, vp, sz,
+                                      ctypes.POINTER(sz)]
+        L.oracle_compress.restype = ctypes.c_int
+        L.oracle_decompress.argtypes = [ctypes.POINTER(_CMethod), vp, vp, vp, vp, vp, sz, sz, vp, vp]
+        L.oracle_decompress.restype = ctypes.c_int
+        L.oracle_logical_bytes.argtypes = [ctypes.POINTER(_CMethod), sz, sz]
+        L.oracle_logical_bytes.restype = ctypes.c_uint64
+        L.oracle_pairwise_sum.argtypes = [vp, sz]
+        L.oracle_pairwise_sum.restype = ctypes.c_float
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def _as_u16(x):
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.uint16:
+        raise TypeError("oracle input is an array of bf16 bit patterns (uint16)")
+    return x.reshape(-1)
+
+
+@dataclass
+class Compressed:
+    method: Method
+    n: int
+    codes: np.ndarray      # int8 [n]
+    packed: np.ndarray     # uint8 [n*bits/8]
+    scale: np.ndarray      # float32 [n/Gq]
+    zp: np.ndarray         # float32 [n/Gq] (asym) or empty
+    out_idx: np.ndarray    # int32 [min(n_out, cap)]
+    out_val: np.ndarray    # uint16 [min(n_out, cap)]
+    n_out: int
+
+
+def select_outliers(m: Method, x_bits) -> np.ndarray:
+    x = _as_u16(x_bits)
+    out = np.zeros(x.size, dtype=np.uint8)
+    cm = m.c()
+    rc = lib().oracle_select_outliers(ctypes.byref(cm), _p(x), x.size, _p(out))
+    if rc != 0:
+        raise ValueError("oracle: malformed method")
+    return out
+
+
+def compress(m: Method, x_bits, cap=None) -> Compressed:
+    x = _as_u16(x_bits)
+    n = x.size
+    cap = n if cap is None else int(cap)
+    groups = n // m.quant_group if m.quant_group else 0
+    codes = np.zeros(n, dtype=np.int8)
+    packed = np.zeros((n * m.bits + 7) // 8, dtype=np.uint8)
+    scale = np.zeros(groups, dtype=np.float32)
+    zp = np.zeros(groups if m.asym else 0, dtype=np.float32)
+    oi = np.zeros(max(cap, 1), dtype=np.int32)
+    ov = np.zeros(max(cap, 1), dtype=np.uint16)
+    n_out = ctypes.c_size_t(0)
+    cm = m.c()
+    rc = lib().oracle_compress(ctypes.byref(cm), _p(x), n, _p(codes), _p(packed), _p(scale),
+                               _p(zp) if m.asym else None, _p(oi), _p(ov), cap, ctypes.byref(n_out))
+    if rc != 0:
+        raise ValueError("oracle: malformed method")
+    k = min(n_out.value, cap)
+    return Compressed(m, n, codes, packed, scale, zp, oi[:k].copy(), ov[:k].copy(), n_out.value)
+
+
+def decompress(c: Compressed):
+    """Returns (xhat_f32, xhat_bf16_bits)."""
+    f = np.zeros(c.n, dtype=np.float32)
+    b = np.zeros(c.n, dtype=np.uint16)
+    cm = c.method.c()
+    oi = np.ascontiguousarray(c.out_idx)
+    ov = np.ascontiguousarray(c.out_val)
+    rc = lib().oracle_decompress(ctypes.byref(cm), _p(c.packed), _p(c.scale),
+                                 _p(c.zp) if c.method.asym else None, _p(oi), _p(ov), oi.size, c.n,
+                                 _p(f), _p(b))
+    if rc != 0:
+        raise ValueError("oracle: decompress failed")
+    return f, b
+
+
+def logical_bytes(m: Method, n: int, n_out: int) -> int:
+    cm = m.c()
+    return int(lib().oracle_logical_bytes(ctypes.byref(cm), n, n_out))
+
+
+def pairwise_sum(v) -> np.float32:
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    return np.float32(lib().oracle_pairwise_sum(_p(v), v.size))

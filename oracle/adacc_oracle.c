@@ -1,0 +1,287 @@
+/*
+ * CPU oracle for outlier-separated activation compression (Adacc, arXiv 2508.00806).
+ * TEST INFRASTRUCTURE ONLY - see adacc_oracle.h.
+ *
+ * What is computed, in the order Section 3.2 and Fig. 3(c) give it:
+ *   1. choose the outliers                      ("Outlier-separated activation compression")
+ *   2. keep them, value and index, uncompressed
+ *   3. set them to zero in the activation
+ *   4. quantise what is left, group by group, in its original memory order
+ *      (Eq. 2 symmetric, Eq. 3 asymmetric)
+ *   5. decompression: code * S (+ O), then the outliers are put back.
+ *
+ * Readings taken where the paper is silent (each is listed in the design notes):
+ *   - input is bf16, arithmetic is binary32, the bit width b generalises the
+ *     paper's 4 (divisor 8 -> 2^(b-1), divisor 16 -> 2^b, clip [-2^(b-1), 2^(b-1)-1]);
+ *   - outliers are single elements picked by |x| > tau, by x^2 > k^2 * var of the
+ *     statistics group, or as the k largest magnitudes of the group (the paper
+ *     picks whole channels by Z-score; same extract / zero / quantise structure);
+ *   - X / S is evaluated as X * (D / max): one division per group;
+ *   - "nearest rounding" is round-half-to-even;
+ *   - sums for the variance are canonical pairwise (binary tree) binary32 sums;
+ *   - Inf and NaN are always outliers when outliers are kept; they never enter
+ *     a scale; a negative zero counts as zero.
+ *
+ * Build: gcc -std=c11 -O2 -ffp-contract=off -fno-fast-math (x86-64 SSE2: strict binary32).
+ */
+#include "adacc_oracle.h"
+
+#include <float.h>
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------- bf16 <-> binary32 ---------- */
+
+static float bf16_to_f32(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+static uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u); /* NaN stays NaN */
+  u += 0x7FFFu + ((u >> 16) & 1u); /* ties go to the even 16-bit pattern */
+  return (uint16_t)(u >> 16);
+}
+
+static int is_nonfinite_bf16(uint16_t b) { return (b & 0x7FFFu) >= 0x7F80u; }
+
+/* ---------- canonical pairwise sum ----------
+ * Pad with +0 to the next power of two, then add neighbours until one value is left:
+ * level 1 adds (v0,v1), (v2,v3), ...; level 2 adds those sums two by two; and so on. */
+float oracle_pairwise_sum(const float *v, size_t n) {
+  size_t p = 1;
+  while (p < n) p <<= 1;
+  float *s = (float *)malloc(p * sizeof(float));
+  for (size_t i = 0; i < p; ++i) s[i] = (i < n) ? v[i] : 0.0f;
+  while (p > 1) {
+    for (size_t j = 0; j < p / 2; ++j) s[j] = s[2 * j] + s[2 * j + 1];
+    p /= 2;
+  }
+  float r = s[0];
+  free(s);
+  return r;
+}
+
+static int method_ok(const oracle_method *m, size_t n) {
+  if (m->bits != 4 && m->bits != 8) return 0;
+  if (m->quant_group == 0 || n % m->quant_group != 0) return 0;
+  if (m->outlier_mode > ORACLE_OUT_TOPK) return 0;
+  if (m->outlier_mode == ORACLE_OUT_STD || m->outlier_mode == ORACLE_OUT_TOPK) {
+    if (m->stat_group == 0 || n % m->stat_group != 0) return 0;
+  }
+  if (m->outlier_mode == ORACLE_OUT_TOPK && (m->topk == 0 || m->topk > m->stat_group)) return 0;
+  return 1;
+}
+
+/* ---------- step 1: outlier selection ---------- */
+
+/* |x| > tau, compared in binary32. */
+static void select_abs(const oracle_method *m, const uint16_t *x, size_t n, uint8_t *out) {
+  for (size_t i = 0; i < n; ++i) out[i] = fabsf(bf16_to_f32(x[i])) > m->thresh;
+}
+
+/* x^2 > k^2 * var, var = population variance of the statistics group about its mean.
+ * The group's own outliers are part of the statistics (one pass, nothing is removed first). */
+static void select_std(const oracle_method *m, const uint16_t *x, size_t n, uint8_t *out) {
+  const size_t gs = m->stat_group;
+  const float k2 = m->thresh * m->thresh;
+  float *v = (float *)malloc(gs * sizeof(float));
+  float *v2 = (float *)malloc(gs * sizeof(float));
+  for (size_t g = 0; g < n / gs; ++g) {
+    const uint16_t *xg = x + g * gs;
+    for (size_t i = 0; i < gs; ++i) {
+      v[i] = bf16_to_f32(xg[i]);
+      v2[i] = v[i] * v[i]; /* exact: two 8-bit significands */
+    }
+    float s1 = oracle_pairwise_sum(v, gs);
+    float s2 = oracle_pairwise_sum(v2, gs);
+    float mean = s1 / (float)gs;
+    float var = fmaf(-mean, mean, s2 / (float)gs);
+    if (var < 0.0f) var = 0.0f; /* a NaN (non-finite input) stays NaN: nothing then passes the test */
+    float limit = k2 * var;
+    for (size_t i = 0; i < gs; ++i) out[g * gs + i] = v2[i] > limit;
+  }
+  free(v);
+  free(v2);
+}
+
+/* The k largest magnitudes of each statistics group.  Magnitudes are compared as
+ * the 15 low bits of the bf16 pattern (monotone in |x|); equal magnitudes are
+ * ranked by position, the earlier one first. */
+static void select_topk(const oracle_method *m, const uint16_t *x, size_t n, uint8_t *out) {
+  const size_t gs = m->stat_group;
+  for (size_t g = 0; g < n / gs; ++g) {
+    const uint16_t *xg = x + g * gs;
+    uint8_t *og = out + g * gs;
+    memset(og, 0, gs);
+    for (uint32_t r = 0; r < m->topk; ++r) {
+      size_t best = gs;
+      for (size_t i = 0; i < gs; ++i) {
+        if (og[i]) continue;
+        if (best == gs || (xg[i] & 0x7FFFu) > (xg[best] & 0x7FFFu)) best = i;
+      }
+      og[best] = 1;
+    }
+  }
+}
+
+int oracle_select_outliers(const oracle_method *m, const uint16_t *x, size_t n, uint8_t *out) {
+  if (!method_ok(m, n)) return -1;
+  switch (m->outlier_mode) {
+    case ORACLE_OUT_NONE: memset(out, 0, n); return 0; /* nothing is kept aside */
+    case ORACLE_OUT_ABS: select_abs(m, x, n, out); break;
+    case ORACLE_OUT_STD: select_std(m, x, n, out); break;
+    case ORACLE_OUT_TOPK: select_topk(m, x, n, out); break;
+  }
+  /* a value that cannot be quantised at all is always kept exactly */
+  for (size_t i = 0; i < n; ++i)
+    if (is_nonfinite_bf16(x[i])) out[i] = 1;
+  return 0;
+}
+
+/* ---------- step 4: quantisation of one group ---------- */
+
+static int8_t clip_code(float r, int q) {
+  /* written so that a NaN lands on the lower bound */
+  if (!(r >= (float)(-q))) r = (float)(-q);
+  if (r > (float)(q - 1)) r = (float)(q - 1);
+  return (int8_t)r;
+}
+
+/* Eq. 2:  S = max|X| / D,  code = clip(round(X / S), -Q, Q-1),  D = Q (paper) or Q-1. */
+static void quant_sym(const oracle_method *m, const float *y, size_t g, int8_t *codes, float *scale) {
+  const int q = 1 << (m->bits - 1);
+  const float d = (m->scale_rule == ORACLE_RULE_PAPER) ? (float)q : (float)(q - 1);
+  float a = 0.0f;
+  for (size_t i = 0; i < g; ++i)
+    if (fabsf(y[i]) > a) a = fabsf(y[i]);
+  *scale = a / d;
+  float inv = 0.0f;
+  if (a != 0.0f) {
+    inv = d / a;
+    if (inv > FLT_MAX) inv = FLT_MAX; /* a is so small that D/a overflows */
+  }
+  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(rintf(y[i] * inv), q);
+}
+
+/* Eq. 3:  O = (max+min)/2,  S = (max-min)/D2,  code = clip(round((X-O)/S), -Q, Q-1),
+ * D2 = 2Q (paper: 16 for 4 bits) or 2Q-1. */
+static void quant_asym(const oracle_method *m, const float *y, size_t g, int8_t *codes, float *scale,
+                       float *zp) {
+  const int q = 1 << (m->bits - 1);
+  const float d2 = (m->scale_rule == ORACLE_RULE_PAPER) ? (float)(2 * q) : (float)(2 * q - 1);
+  float hi = y[0], lo = y[0];
+  for (size_t i = 1; i < g; ++i) {
+    if (y[i] > hi) hi = y[i];
+    if (y[i] < lo) lo = y[i];
+  }
+  float o = (hi + lo) * 0.5f;
+  float r = hi - lo;
+  *zp = o;
+  *scale = r / d2;
+  float inv = 0.0f;
+  if (r != 0.0f) {
+    inv = d2 / r;
+    if (inv > FLT_MAX) inv = FLT_MAX;
+  }
+  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(rintf((y[i] - o) * inv), q);
+}
+
+/* ---------- steps 1-4 ---------- */
+
+int oracle_compress(const oracle_method *m, const uint16_t *x, size_t n, int8_t *codes, uint8_t *packed,
+                    float *scale, float *zp, int32_t *out_idx, uint16_t *out_val, size_t cap,
+                    size_t *n_out) {
+  if (!method_ok(m, n)) return -1;
+  if (m->asym && !zp) return -1;
+  uint8_t *out = (uint8_t *)malloc(n ? n : 1);
+  float *y = (float *)malloc((n ? n : 1) * sizeof(float));
+
+  /* 1. which elements are outliers */
+  oracle_select_outliers(m, x, n, out);
+
+  /* 2. keep them, in ascending index order, exactly as they are */
+  size_t cnt = 0;
+  for (size_t i = 0; i < n; ++i) {
+    if (!out[i]) continue;
+    if (cnt < cap) {
+      out_idx[cnt] = (int32_t)i;
+      out_val[cnt] = x[i];
+    }
+    ++cnt;
+  }
+  if (n_out) *n_out = cnt;
+
+  /* 3. zero them in the activation; a value that is not finite, or a negative
+   *    zero, also counts as zero from here on */
+  for (size_t i = 0; i < n; ++i) {
+    float f = bf16_to_f32(x[i]);
+    if (out[i] || is_nonfinite_bf16(x[i]) || f == 0.0f) f = 0.0f;
+    y[i] = f;
+  }
+
+  /* 4. quantise every group of the flat array */
+  const size_t gq = m->quant_group;
+  for (size_t h = 0; h < n / gq; ++h) {
+    if (m->asym)
+      quant_asym(m, y + h * gq, gq, codes + h * gq, scale + h, zp + h);
+    else
+      quant_sym(m, y + h * gq, gq, codes + h * gq, scale + h);
+  }
+
+  /* pack */
+  if (packed) {
+    if (m->bits == 8) {
+      for (size_t i = 0; i < n; ++i) packed[i] = (uint8_t)codes[i];
+    } else {
+      for (size_t j = 0; j < (n + 1) / 2; ++j) {
+        int lo = codes[2 * j] & 0xF;
+        int hi = (2 * j + 1 < n) ? (codes[2 * j + 1] & 0xF) : 0; /* odd n: last high nibble is 0 */
+        packed[j] = (uint8_t)(lo | (hi << 4));
+      }
+    }
+  }
+  free(out);
+  free(y);
+  return 0;
+}
+
+/* ---------- step 5 ---------- */
+
+static int unpack_code(const oracle_method *m, const uint8_t *packed, size_t i) {
+  if (m->bits == 8) return (int8_t)packed[i];
+  int nib = (packed[i / 2] >> ((i & 1) ? 4 : 0)) & 0xF;
+  return (nib >= 8) ? nib - 16 : nib;
+}
+
+int oracle_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, const float *zp,
+                      const int32_t *out_idx, const uint16_t *out_val, size_t n_out, size_t n,
+                      float *xhat_f32, uint16_t *xhat_bf16) {
+  if (!method_ok(m, n)) return -1;
+  if (m->asym && !zp) return -1;
+  const size_t gq = m->quant_group;
+  for (size_t i = 0; i < n; ++i) {
+    float c = (float)unpack_code(m, packed, i);
+    float s = scale[i / gq];
+    float v = m->asym ? fmaf(c, s, zp[i / gq]) : c * s; /* X^ = code * S (+ O) */
+    if (xhat_f32) xhat_f32[i] = v;
+    if (xhat_bf16) xhat_bf16[i] = f32_to_bf16_rne(v);
+  }
+  for (size_t j = 0; j < n_out; ++j) {
+    size_t i = (size_t)out_idx[j];
+    if (i >= n) return -1;
+    if (xhat_f32) xhat_f32[i] = bf16_to_f32(out_val[j]);
+    if (xhat_bf16) xhat_bf16[i] = out_val[j];
+  }
+  return 0;
+}
+
+uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out) {
+  uint64_t groups = n / m->quant_group;
+  return (uint64_t)n * m->bits / 8 + 4ull * groups * (m->asym ? 2 : 1) + 6ull * n_out;
+}
