@@ -1,0 +1,160 @@
+/*
+ * adacc.h - C ABI of libadacc: outlier-separated quantising compression of saved
+ * bf16 activation tensors on AMD MI355X (gfx950), after Adacc (arXiv 2508.00806),
+ * Section 3.2 "Layer-specific Compression".
+ *
+ * What the library computes (Section 3.2, Fig. 3(c), Eq. 2 and Eq. 3):
+ *   compress   : choose the outliers of the tensor, keep them (value + index)
+ *                uncompressed, treat them as zero, and quantise everything else
+ *                group by group in its original memory order to b-bit codes with
+ *                one binary32 scale S (and, asymmetric, one offset O) per group;
+ *   decompress : code * S (+ O), then the outliers are written back.
+ * The paper quantises FP16 to INT4 and picks whole outlier channels; this
+ * library takes bf16, b in {4, 8}, and picks single elements by one of three
+ * rules (absolute threshold, multiple of the group's standard deviation, k
+ * largest magnitudes).  All arithmetic is binary32 in a fixed order, so a
+ * compressed tensor is a pure function of the input bits.
+ *
+ * Conventions
+ *   - Every pointer named src/dst/blob/workspace is DEVICE memory owned by the
+ *     caller; the library never allocates, frees or keeps device memory.
+ *     adacc_method / adacc_layout / arrays of them and the pointer arrays of the
+ *     batch calls are HOST memory, read before the call returns.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call except adacc_read_status only enqueues work and returns.
+ *   - Return value: ADACC_OK (0) or a negative ADACC_E* code.  Errors that the
+ *     host can detect are returned before anything is enqueued.
+ *   - Tensors are flat, contiguous, row-major; numel counts elements.
+ */
+#ifndef ADACC_H
+#define ADACC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- error codes ---- */
+#define ADACC_OK 0
+#define ADACC_EINVAL (-1) /* malformed method or sizes                                */
+#define ADACC_ENULL (-2)  /* a required pointer is NULL                               */
+#define ADACC_ESIZE (-3)  /* blob or workspace smaller than the layout requires       */
+#define ADACC_EALIGN (-4) /* a device pointer is not 16-byte aligned                  */
+#define ADACC_EHIP (-5)   /* a HIP runtime call failed (no device, launch failure)    */
+
+/* ---- method descriptor ---- */
+#define ADACC_KIND_NOOP 0  /* tensor is retained as it is: nothing is read or written */
+#define ADACC_KIND_QUANT 1 /* outlier-separated group quantisation                    */
+
+#define ADACC_OUTLIER_NONE 0 /* plain group quantisation (Section 3.2, per-token / QKV scheme) */
+#define ADACC_OUTLIER_ABS 1  /* |x| > thresh                                          */
+#define ADACC_OUTLIER_STD 2  /* x*x > thresh^2 * var(stat group), population variance about the mean */
+#define ADACC_OUTLIER_TOPK 3 /* the topk largest |x| of every stat group, ties to the lower index */
+
+#define ADACC_SCALE_PAPER 0     /* Eq. 2: S = max|X| / 2^(b-1);  Eq. 3: S = (max-min) / 2^b */
+#define ADACC_SCALE_FULLRANGE 1 /* S = max|X| / (2^(b-1)-1);     S = (max-min) / (2^b-1)    */
+
+typedef struct adacc_method {
+  uint32_t kind;         /* ADACC_KIND_*                                                     */
+  uint32_t bits;         /* 4 or 8                                                           */
+  uint32_t quant_group;  /* Gq, elements per scale: a power of two in [8, 4096] dividing numel */
+  uint32_t asym;         /* 0: symmetric (Eq. 2), 1: asymmetric (Eq. 3, adds one offset per group) */
+  uint32_t scale_rule;   /* ADACC_SCALE_*                                                    */
+  uint32_t outlier_mode; /* ADACC_OUTLIER_*                                                  */
+  uint32_t stat_group;   /* Gs, STD/TOPK only: power of two, multiple of Gq, <= 4096, divides numel */
+  float thresh;          /* ABS: tau >= 0.  STD: k >= 0 (the library forms k*k in binary32)  */
+  uint32_t topk;         /* TOPK: 1..32 outliers per stat group                              */
+  uint32_t max_outliers; /* capacity of the outlier stream of the blob (0 allowed for NONE)  */
+} adacc_method;
+
+/* ---- blob layout ----
+ * A compressed tensor ("blob") is one caller-owned device buffer cut into
+ * sections, each starting on a 256-byte boundary:
+ *   codes    numel*bits/8 bytes.  b=8: one two's-complement byte per element.
+ *            b=4: element 2j in the low nibble of byte j, 2j+1 in the high nibble.
+ *   scales   numel/Gq binary32, S of Eq. 2 / Eq. 3.
+ *   zp       numel/Gq binary32, O of Eq. 3 (asym only, else empty).
+ *   tile_ptr (n_tiles+1) uint32: tile t (elements [t*tile_elems, (t+1)*tile_elems))
+ *            owns outliers [tile_ptr[t], tile_ptr[t+1]) of the stream; tile_ptr[n_tiles]
+ *            is the total count.  Empty for ADACC_OUTLIER_NONE.
+ *   idx,val  max_outliers int32 flat indices, ascending, and the bf16 bit patterns at
+ *            those indices (structure of arrays).  Entries past the count are unspecified.
+ *   status   4 uint32: [0] number of outliers found, [1] 1 if it exceeds max_outliers
+ *            (the stream then holds the first max_outliers; the blob is not usable),
+ *            [2] 1 if the kernel gave up waiting on another tile (blob not usable), [3] 0.
+ */
+typedef struct adacc_layout {
+  uint64_t codes_off, scales_off, zp_off, tile_ptr_off, idx_off, val_off, status_off;
+  uint64_t total_bytes; /* size the blob must have                                       */
+  uint32_t tile_elems;  /* elements per tile: max(2048, Gq, Gs)                          */
+  uint32_t n_tiles;     /* ceil(numel / tile_elems)                                      */
+} adacc_layout;
+
+/* Host only, pure.  Validates the method for this numel and fills *out.
+ * NOOP: all zero.  Errors: ENULL, EINVAL. */
+int adacc_layout_of(const adacc_method *method, uint64_t numel, adacc_layout *out);
+
+/* ---- workspace ----
+ * Compression with outliers orders the outlier stream across tiles with a
+ * single-pass chained scan; its per-tile state lives in a caller-owned device
+ * workspace.  A workspace must be cleared once with adacc_workspace_init before
+ * its first use; after that any number of compress calls may reuse it, one at a
+ * time (calls that overlap on the GPU must use different workspaces). */
+uint64_t adacc_workspace_bytes(const adacc_method *method, uint64_t numel);
+int adacc_workspace_init(void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* ---- single tensor ----
+ * adacc_compress: Section 3.2 / Fig. 3(c) compression workflow.
+ *   src   numel bf16, 16-byte aligned, never modified (the zeroing of outliers happens in registers)
+ *   blob  at least adacc_layout_of(...).total_bytes, 256-byte aligned
+ *   workspace  at least adacc_workspace_bytes(...); may be NULL for ADACC_OUTLIER_NONE
+ * numel == 0 or NOOP: returns ADACC_OK without touching anything.
+ * Errors: ENULL, EINVAL, ESIZE, EALIGN, EHIP. */
+int adacc_compress(const adacc_method *method, const void *src, uint64_t numel, void *blob,
+                   uint64_t blob_bytes, void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* adacc_decompress: Section 3.2 dequantisation (X^ = code*S, resp. code*S+O) followed by
+ * the write-back of the outliers (Fig. 3(c) decompression workflow).
+ *   dst_dtype 0: bf16 (round-to-nearest-even of the binary32 result; outliers bit-exact)
+ *             1: binary32
+ *   dst   numel elements of that type, 16-byte aligned */
+#define ADACC_DST_BF16 0
+#define ADACC_DST_F32 1
+int adacc_decompress(const adacc_method *method, const void *blob, uint64_t blob_bytes, uint64_t numel,
+                     void *dst, int dst_dtype, void *hip_stream);
+
+/* ---- batch: one launch for a table of tensors (the per-tensor policy of Section 3.3,
+ * R_{i,t}: compress or retain) ----
+ * methods[i], srcs[i], numels[i], blobs[i], blob_bytes[i] describe tensor i; NOOP entries
+ * are skipped.  The workspace holds the scan state of all tensors plus a device copy of the
+ * table (adacc_batch_workspace_bytes); same init/reuse rules as above.
+ * adacc_decompress_batch restores every non-NOOP tensor i into dsts[i]. */
+uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method *methods, const uint64_t *numels);
+int adacc_compress_batch(uint32_t n, const adacc_method *methods, const void *const *srcs,
+                         const uint64_t *numels, void *const *blobs, const uint64_t *blob_bytes,
+                         void *workspace, uint64_t workspace_bytes, void *hip_stream);
+int adacc_decompress_batch(uint32_t n, const adacc_method *methods, const void *const *blobs,
+                           const uint64_t *blob_bytes, const uint64_t *numels, void *const *dsts,
+                           int dst_dtype, void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/* Copies the 4 status words of a blob to host memory and waits for the stream:
+ * the only call that synchronises.  (The outlier count is what the policy
+ * evolution of Section 3.4 tracks.) */
+int adacc_read_status(const void *blob, const adacc_layout *layout, void *hip_stream, uint32_t status_out[4]);
+
+/* Plain streaming copy of `bytes` (multiple of 16) from src to dst: the practical HBM
+ * ceiling the compression kernels are measured against, and the calibration
+ * kernel for hardware byte counters. */
+int adacc_hbm_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream);
+
+/* Text for an error code; for ADACC_EHIP, the last HIP error string seen by this thread. */
+const char *adacc_strerror(int code);
+
+/* Library version, "major.minor". */
+const char *adacc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADACC_H */

@@ -1,0 +1,266 @@
+"""Thin Python binding of libadacc (see include/adacc.h).
+
+Argument marshalling only: every step of compression and decompression runs in the
+HIP kernels of libadacc.so.  PyTorch tensors are used as device buffers; the current
+torch stream is the stream the work is enqueued on.  There is no CPU fallback: if the
+shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadacc.so")
+
+# ---- constants of include/adacc.h
+OK, EINVAL, ENULL, ESIZE, EALIGN, EHIP = 0, -1, -2, -3, -4, -5
+KIND_NOOP, KIND_QUANT = 0, 1
+OUTLIER_NONE, OUTLIER_ABS, OUTLIER_STD, OUTLIER_TOPK = 0, 1, 2, 3
+SCALE_PAPER, SCALE_FULLRANGE = 0, 1
+DST_BF16, DST_F32 = 0, 1
+
+EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "adacc_compress",
+           "adacc_decompress", "adacc_batch_workspace_bytes", "adacc_compress_batch",
+           "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
+           "adacc_version")
+
+
+class CMethod(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_uint32), ("bits", ctypes.c_uint32), ("quant_group", ctypes.c_uint32),
+                ("asym", ctypes.c_uint32), ("scale_rule", ctypes.c_uint32), ("outlier_mode", ctypes.c_uint32),
+                ("stat_group", ctypes.c_uint32), ("thresh", ctypes.c_float), ("topk", ctypes.c_uint32),
+                ("max_outliers", ctypes.c_uint32)]
+
+
+class CLayout(ctypes.Structure):
+    _fields_ = [("codes_off", ctypes.c_uint64), ("scales_off", ctypes.c_uint64), ("zp_off", ctypes.c_uint64),
+                ("tile_ptr_off", ctypes.c_uint64), ("idx_off", ctypes.c_uint64), ("val_off", ctypes.c_uint64),
+                ("status_off", ctypes.c_uint64), ("total_bytes", ctypes.c_uint64),
+                ("tile_elems", ctypes.c_uint32), ("n_tiles", ctypes.c_uint32)]
+
+
+@dataclass
+class Method:
+    kind: int = KIND_QUANT
+    bits: int = 8
+    quant_group: int = 64
+    asym: int = 0
+    scale_rule: int = SCALE_PAPER
+    outlier_mode: int = OUTLIER_NONE
+    stat_group: int = 0
+    thresh: float = 0.0
+    topk: int = 0
+    max_outliers: int = 0
+
+    def c(self) -> CMethod:
+        return CMethod(self.kind, self.bits, self.quant_group, self.asym, self.scale_rule, self.outlier_mode,
+                       self.stat_group, float(self.thresh), self.topk, self.max_outliers)
+
+
+NOOP = Method(kind=KIND_NOOP, bits=0, quant_group=0)
+
+
+class AdaccError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libadacc.so (built by paper_2508_00806_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2508_00806_amd.build` first "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u64, u32, ci = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
+        pm, pl = ctypes.POINTER(CMethod), ctypes.POINTER(CLayout)
+        L.adacc_layout_of.argtypes = [pm, u64, pl]
+        L.adacc_layout_of.restype = ci
+        L.adacc_workspace_bytes.argtypes = [pm, u64]
+        L.adacc_workspace_bytes.restype = u64
+        L.adacc_workspace_init.argtypes = [vp, u64, vp]
+        L.adacc_workspace_init.restype = ci
+        L.adacc_compress.argtypes = [pm, vp, u64, vp, u64, vp, u64, vp]
+        L.adacc_compress.restype = ci
+        L.adacc_decompress.argtypes = [pm, vp, u64, u64, vp, ci, vp]
+        L.adacc_decompress.restype = ci
+        pvp, pu64 = ctypes.POINTER(vp), ctypes.POINTER(u64)
+        L.adacc_batch_workspace_bytes.argtypes = [u32, pm, pu64]
+        L.adacc_batch_workspace_bytes.restype = u64
+        L.adacc_compress_batch.argtypes = [u32, pm, pvp, pu64, pvp, pu64, vp, u64, vp]
+        L.adacc_compress_batch.restype = ci
+        L.adacc_decompress_batch.argtypes = [u32, pm, pvp, pu64, pu64, pvp, ci, vp, u64, vp]
+        L.adacc_decompress_batch.restype = ci
+        L.adacc_read_status.argtypes = [vp, pl, vp, ctypes.POINTER(u32 * 4)]
+        L.adacc_read_status.restype = ci
+        L.adacc_hbm_copy.argtypes = [vp, vp, u64, vp]
+        L.adacc_hbm_copy.restype = ci
+        L.adacc_strerror.argtypes = [ci]
+        L.adacc_strerror.restype = ctypes.c_char_p
+        L.adacc_version.argtypes = []
+        L.adacc_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().adacc_strerror(int(code)).decode()
+
+
+def version() -> str:
+    return lib().adacc_version().decode()
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise AdaccError(rc, where)
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or an int / None passed through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ---------------------------------------------------------------- host-only helpers
+def layout_of(method: Method, numel: int) -> CLayout:
+    L = CLayout()
+    cm = method.c()
+    _check(lib().adacc_layout_of(ctypes.byref(cm), numel, ctypes.byref(L)), "adacc_layout_of")
+    return L
+
+
+def workspace_bytes(method: Method, numel: int) -> int:
+    cm = method.c()
+    return int(lib().adacc_workspace_bytes(ctypes.byref(cm), numel))
+
+
+def batch_workspace_bytes(methods, numels) -> int:
+    n = len(methods)
+    cms = (CMethod * n)(*[m.c() for m in methods])
+    cn = (ctypes.c_uint64 * n)(*numels)
+    return int(lib().adacc_batch_workspace_bytes(n, cms, cn))
+
+
+# ---------------------------------------------------------------- device calls
+def workspace_init(workspace, stream=None):
+    _check(lib().adacc_workspace_init(_ptr(workspace), _nbytes(workspace), _stream(stream)), "adacc_workspace_init")
+
+
+def compress(method: Method, src, blob, workspace=None, numel=None, stream=None):
+    numel = src.numel() if numel is None else numel
+    cm = method.c()
+    _check(lib().adacc_compress(ctypes.byref(cm), _ptr(src), numel, _ptr(blob), _nbytes(blob), _ptr(workspace),
+                                _nbytes(workspace) if workspace is not None else 0, _stream(stream)),
+           "adacc_compress")
+
+
+def decompress(method: Method, blob, dst, numel=None, stream=None):
+    import torch
+    numel = dst.numel() if numel is None else numel
+    dtype = DST_F32 if dst.dtype == torch.float32 else DST_BF16
+    if dst.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("dst must be bfloat16 or float32")
+    cm = method.c()
+    _check(lib().adacc_decompress(ctypes.byref(cm), _ptr(blob), _nbytes(blob), numel, _ptr(dst), dtype,
+                                  _stream(stream)), "adacc_decompress")
+
+
+def _batch_args(methods, tensors_a, numels, tensors_b):
+    n = len(methods)
+    cms = (CMethod * n)(*[m.c() for m in methods])
+    pa = (ctypes.c_void_p * n)(*[_ptr(t) for t in tensors_a])
+    pb = (ctypes.c_void_p * n)(*[_ptr(t) for t in tensors_b])
+    cn = (ctypes.c_uint64 * n)(*numels)
+    return n, cms, pa, cn, pb
+
+
+def compress_batch(methods, srcs, blobs, workspace, stream=None):
+    numels = [0 if s is None else s.numel() for s in srcs]
+    n, cms, ps, cn, pb = _batch_args(methods, srcs, numels, blobs)
+    bb = (ctypes.c_uint64 * n)(*[0 if b is None else _nbytes(b) for b in blobs])
+    _check(lib().adacc_compress_batch(n, cms, ps, cn, pb, bb, _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "adacc_compress_batch")
+
+
+def decompress_batch(methods, blobs, dsts, workspace, stream=None):
+    import torch
+    numels = [0 if d is None else d.numel() for d in dsts]
+    n, cms, pb, cn, pd = _batch_args(methods, blobs, numels, dsts)
+    bb = (ctypes.c_uint64 * n)(*[0 if b is None else _nbytes(b) for b in blobs])
+    kinds = {d.dtype for d in dsts if d is not None}
+    if len(kinds) > 1:
+        raise TypeError("all dsts of a batch share one dtype")
+    dtype = DST_F32 if kinds == {torch.float32} else DST_BF16
+    _check(lib().adacc_decompress_batch(n, cms, pb, bb, cn, pd, dtype, _ptr(workspace), _nbytes(workspace),
+                                        _stream(stream)), "adacc_decompress_batch")
+
+
+def read_status(blob, layout: CLayout, stream=None):
+    """(n_outliers, overflow, aborted, 0) - waits for the stream."""
+    out = (ctypes.c_uint32 * 4)()
+    _check(lib().adacc_read_status(_ptr(blob), ctypes.byref(layout), _stream(stream), ctypes.byref(out)),
+           "adacc_read_status")
+    return tuple(int(v) for v in out)
+
+
+def hbm_copy(dst, src, nbytes=None, stream=None):
+    nbytes = _nbytes(src) if nbytes is None else nbytes
+    _check(lib().adacc_hbm_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "adacc_hbm_copy")
+
+
+# ---------------------------------------------------------------- buffer helpers (allocation = plumbing)
+def alloc_blob(method: Method, numel: int, device="cuda"):
+    import torch
+    L = layout_of(method, numel)
+    return torch.empty(max(int(L.total_bytes), 256), dtype=torch.uint8, device=device), L
+
+
+def alloc_workspace(nbytes: int, device="cuda", stream=None):
+    """A cleared scan workspace of at least nbytes."""
+    import torch
+    ws = torch.empty(max((int(nbytes) + 255) // 256 * 256, 512), dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def blob_sections(blob, layout: CLayout, method: Method, numel: int):
+    """Typed views of the sections of a blob (no copies)."""
+    import torch
+    groups = numel // method.quant_group
+    has_out = method.outlier_mode != OUTLIER_NONE
+
+    def view(off, nbytes, dtype):
+        return blob[off:off + nbytes].view(dtype)
+
+    sec = {
+        "codes": view(layout.codes_off, numel * method.bits // 8, torch.uint8),
+        "scales": view(layout.scales_off, 4 * groups, torch.float32),
+        "status": view(layout.status_off, 16, torch.int32),
+    }
+    if method.asym:
+        sec["zp"] = view(layout.zp_off, 4 * groups, torch.float32)
+    if has_out:
+        sec["tile_ptr"] = view(layout.tile_ptr_off, 4 * (layout.n_tiles + 1), torch.int32)
+        sec["idx"] = view(layout.idx_off, 4 * method.max_outliers, torch.int32)
+        sec["val"] = view(layout.val_off, 2 * method.max_outliers, torch.int16)
+    return sec

@@ -1,0 +1,608 @@
+// libadacc: kernels and C ABI (see include/adacc.h).  gfx950 only.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "adacc.h"
+#include "adacc_common.hpp"
+#include "adacc_compress.hpp"
+#include "adacc_decompress.hpp"
+
+namespace adacc {
+
+// ===================================================================== kernels
+
+__device__ __forceinline__ uint32_t take_ticket(WsHeader* hdr) {
+  // one atomic per tile; lane 0 carries the result
+  uint32_t t = 0u;
+  if (__lane_id() == 0)
+    t = __hip_atomic_fetch_add(&hdr->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return t;
+}
+
+// Every wavefront calls this once when it has no more tiles.  The last one to arrive puts
+// the header back into its between-launches state and advances the epoch, which turns
+// every state word of this launch into "empty" for the next one without clearing memory.
+__device__ __forceinline__ void leave_scan(WsHeader* hdr, uint64_t* state) {
+  uint32_t last = 0u;
+  if (__lane_id() == 0) {
+    const uint32_t waves = gridDim.x * kWavesPerWg;
+    const uint32_t old = __hip_atomic_fetch_add(&hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last = (old + 1u == waves) ? 1u : 0u;
+  }
+  last = __builtin_amdgcn_readfirstlane(last);
+  if (!last) return;
+  uint32_t e = __hip_atomic_load(&hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+  if (e >= kEpochWrap) {  // once in ~10^9 launches: really clear the words and start over
+    const uint32_t cap = hdr->capacity;
+    for (uint32_t i = __lane_id(); i < cap; i += kWave)
+      __hip_atomic_store(&state[i], (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    e = 0u;
+  }
+  if (__lane_id() == 0) {
+    __hip_atomic_store(&hdr->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&hdr->done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&hdr->epoch, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+__device__ __forceinline__ ScanCtx open_scan(WsHeader* hdr, uint64_t* state, uint32_t spin_limit) {
+  ScanCtx sc;
+  sc.hdr = hdr;
+  sc.state = state;
+  sc.spin_limit = spin_limit;
+  const uint32_t e = __hip_atomic_load(&hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  sc.tag = (e + 1u) << 2;
+  return sc;
+}
+
+// ---- single tensor, compress.  Outlier modes: persistent wavefronts pull tiles from the
+// ticket counter (tile order = ticket order, which the chained scan needs).  NONE: tiles
+// are independent, plain grid-stride loop, workspace untouched.
+template <int MODE, int BITS, bool ASYM, int E>
+__global__ __launch_bounds__(kThreads) void compress_kernel(TensorDesc d, WsHeader* hdr, uint64_t* state,
+                                                            uint32_t spin_limit) {
+  const uint32_t wave = threadIdx.x / kWave;
+  if constexpr (MODE == kModeNone) {
+    ScanCtx sc{};
+    for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
+      compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
+  } else {
+    const ScanCtx sc = open_scan(hdr, state, spin_limit);
+    uint32_t t = __builtin_amdgcn_readfirstlane(take_ticket(hdr));
+    while (t < d.n_tiles) {
+      const uint32_t next = take_ticket(hdr);  // in flight while this tile is processed
+      compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
+      t = __builtin_amdgcn_readfirstlane(next);
+    }
+    leave_scan(hdr, state);
+  }
+}
+
+template <int BITS, bool ASYM, int E, bool F32>
+__global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint32_t has_outliers) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<E, F32>()];
+  const uint32_t wave = threadIdx.x / kWave;
+  unsigned char* slice = lds + wave * decompress_lds_per_wave<E, F32>();
+  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
+    decompress_tile<BITS, ASYM, E, F32>(d, t, has_outliers != 0u, slice);
+}
+
+// ---- batch: a launch-wide tile numbering over all tensors of the table
+__device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_t n, uint32_t gtile) {
+  uint32_t lo = 0u, hi = n;  // first_tile is ascending; find the last entry with first_tile <= gtile
+  while (hi - lo > 1u) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (table[mid].first_tile <= gtile) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <int MODE>
+__device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t tile, const ScanCtx& sc) {
+  switch (d.variant & 7u) {
+    case 0: compress_tile<MODE, 4, false, 4>(d, tile, sc); break;
+    case 1: compress_tile<MODE, 4, false, 8>(d, tile, sc); break;
+    case 2: compress_tile<MODE, 4, true, 4>(d, tile, sc); break;
+    case 3: compress_tile<MODE, 4, true, 8>(d, tile, sc); break;
+    case 4: compress_tile<MODE, 8, false, 4>(d, tile, sc); break;
+    case 5: compress_tile<MODE, 8, false, 8>(d, tile, sc); break;
+    case 6: compress_tile<MODE, 8, true, 4>(d, tile, sc); break;
+    default: compress_tile<MODE, 8, true, 8>(d, tile, sc); break;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
+                                                                  uint32_t total_tiles, WsHeader* hdr,
+                                                                  uint64_t* state, uint32_t spin_limit) {
+  const ScanCtx sc = open_scan(hdr, state, spin_limit);
+  uint32_t g = __builtin_amdgcn_readfirstlane(take_ticket(hdr));
+  while (g < total_tiles) {
+    const uint32_t next = take_ticket(hdr);
+    const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor(table, n, g));
+    const TensorDesc d = table[ti];
+    const uint32_t tile = g - d.first_tile;
+    switch (d.variant >> 3) {
+      case kModeNone: compress_dispatch_mode<kModeNone>(d, tile, sc); break;
+      case kModeAbs: compress_dispatch_mode<kModeAbs>(d, tile, sc); break;
+      case kModeStd: compress_dispatch_mode<kModeStd>(d, tile, sc); break;
+      default: compress_dispatch_mode<kModeTopk>(d, tile, sc); break;
+    }
+    g = __builtin_amdgcn_readfirstlane(next);
+  }
+  leave_scan(hdr, state);
+}
+
+template <bool F32>
+__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, uint32_t n,
+                                                                    uint32_t total_tiles) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<8, F32>()];
+  const uint32_t wave = threadIdx.x / kWave;
+  unsigned char* slice = lds + wave * decompress_lds_per_wave<8, F32>();
+  for (uint32_t g = blockIdx.x * kWavesPerWg + wave; g < total_tiles; g += gridDim.x * kWavesPerWg) {
+    const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor(table, n, g));
+    const TensorDesc d = table[ti];
+    const uint32_t tile = g - d.first_tile;
+    const bool ho = (d.variant >> 3) != kModeNone;
+    switch (d.variant & 7u) {
+      case 0: decompress_tile<4, false, 4, F32>(d, tile, ho, slice); break;
+      case 1: decompress_tile<4, false, 8, F32>(d, tile, ho, slice); break;
+      case 2: decompress_tile<4, true, 4, F32>(d, tile, ho, slice); break;
+      case 3: decompress_tile<4, true, 8, F32>(d, tile, ho, slice); break;
+      case 4: decompress_tile<8, false, 4, F32>(d, tile, ho, slice); break;
+      case 5: decompress_tile<8, false, 8, F32>(d, tile, ho, slice); break;
+      case 6: decompress_tile<8, true, 4, F32>(d, tile, ho, slice); break;
+      default: decompress_tile<8, true, 8, F32>(d, tile, ho, slice); break;
+    }
+  }
+}
+
+// ---- utilities
+// clears a workspace; the first 16 bytes are the header words {epoch, ticket, done, capacity}
+__global__ __launch_bounds__(kThreads) void workspace_clear_kernel(uint4* p, uint64_t n16, uint32_t capacity) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+    p[i] = make_uint4(0, 0, 0, i == 0 ? capacity : 0u);
+}
+
+__global__ __launch_bounds__(kThreads) void hbm_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                            uint64_t n16) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// ===================================================================== host side
+
+static thread_local char g_hip_err[256] = "no HIP error recorded";
+
+static int hip_fail(hipError_t e, const char* what) {
+  std::snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
+  return ADACC_EHIP;
+}
+
+static int env_int(const char* name, int dflt) {
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  const long v = std::strtol(s, nullptr, 10);
+  return v > 0 ? (int)v : dflt;
+}
+
+static int device_cus(int* cus) {
+  static int cached[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev >= 0 && dev < 64 && cached[dev] > 0) { *cus = cached[dev]; return ADACC_OK; }
+  int n = 0;
+  e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute");
+  if (dev >= 0 && dev < 64) cached[dev] = n;
+  *cus = n;
+  return ADACC_OK;
+}
+
+static bool is_pow2(uint64_t v) { return v && !(v & (v - 1)); }
+static uint32_t ilog2(uint64_t v) { uint32_t l = 0; while ((1ull << l) < v) ++l; return l; }
+static uint64_t align256(uint64_t v) { return (v + 255ull) & ~255ull; }
+
+struct Plan {  // everything derived from (method, numel)
+  bool noop;
+  bool outliers;
+  uint32_t tile_elems, n_tiles, lgq, lgs, variant;
+  float param, divisor;
+};
+
+static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
+  std::memset(p, 0, sizeof *p);
+  if (m->kind == ADACC_KIND_NOOP) { p->noop = true; return ADACC_OK; }
+  if (m->kind != ADACC_KIND_QUANT) return ADACC_EINVAL;
+  if (m->bits != 4 && m->bits != 8) return ADACC_EINVAL;
+  if (m->asym > 1 || m->scale_rule > 1 || m->outlier_mode > ADACC_OUTLIER_TOPK) return ADACC_EINVAL;
+  if (!is_pow2(m->quant_group) || m->quant_group < 8 || m->quant_group > 4096) return ADACC_EINVAL;
+  if (numel % m->quant_group != 0) return ADACC_EINVAL;
+  uint32_t gs = m->quant_group;
+  const bool stat = m->outlier_mode == ADACC_OUTLIER_STD || m->outlier_mode == ADACC_OUTLIER_TOPK;
+  if (stat) {
+    if (!is_pow2(m->stat_group) || m->stat_group < m->quant_group || m->stat_group > 4096) return ADACC_EINVAL;
+    if (numel % m->stat_group != 0) return ADACC_EINVAL;
+    gs = m->stat_group;
+  }
+  if (m->outlier_mode == ADACC_OUTLIER_TOPK && (m->topk < 1 || m->topk > 32 || m->topk > gs)) return ADACC_EINVAL;
+  if (m->outlier_mode == ADACC_OUTLIER_ABS || m->outlier_mode == ADACC_OUTLIER_STD) {
+    if (!(m->thresh >= 0.0f) || std::isinf(m->thresh)) return ADACC_EINVAL;
+  }
+  p->outliers = m->outlier_mode != ADACC_OUTLIER_NONE;
+  if (p->outliers && numel >= (1ull << 31)) return ADACC_EINVAL;  // 32-bit signed flat indices
+  if (numel >= (1ull << 42)) return ADACC_EINVAL;
+  p->tile_elems = gs > 2048 ? 4096u : 2048u;
+  p->n_tiles = (uint32_t)((numel + p->tile_elems - 1) / p->tile_elems);
+  p->lgq = ilog2(m->quant_group);
+  p->lgs = ilog2(gs);
+  p->variant = variant_index(m->outlier_mode, m->bits, m->asym, p->tile_elems == 4096 ? 1u : 0u);
+  const float q = (float)(1u << (m->bits - 1));
+  if (m->asym) p->divisor = m->scale_rule == ADACC_SCALE_PAPER ? 2.0f * q : 2.0f * q - 1.0f;
+  else p->divisor = m->scale_rule == ADACC_SCALE_PAPER ? q : q - 1.0f;
+  if (m->outlier_mode == ADACC_OUTLIER_ABS) p->param = m->thresh;
+  if (m->outlier_mode == ADACC_OUTLIER_STD) p->param = m->thresh * m->thresh;
+  return ADACC_OK;
+}
+
+static void fill_layout(const adacc_method* m, uint64_t numel, const Plan& p, adacc_layout* L) {
+  std::memset(L, 0, sizeof *L);
+  if (p.noop) return;
+  const uint64_t groups = numel / m->quant_group;
+  uint64_t off = 0;
+  L->codes_off = off;   off = align256(off + numel * m->bits / 8);
+  L->scales_off = off;  off = align256(off + 4 * groups);
+  L->zp_off = off;      off = align256(off + (m->asym ? 4 * groups : 0));
+  L->tile_ptr_off = off; off = align256(off + (p.outliers ? 4ull * ((uint64_t)p.n_tiles + 1) : 0));
+  L->idx_off = off;     off = align256(off + (p.outliers ? 4ull * m->max_outliers : 0));
+  L->val_off = off;     off = align256(off + (p.outliers ? 2ull * m->max_outliers : 0));
+  L->status_off = off;  off = align256(off + 16);
+  L->total_bytes = off;
+  L->tile_elems = p.tile_elems;
+  L->n_tiles = p.n_tiles;
+}
+
+static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
+                      void* blob, void* dst, int dst_dtype, uint32_t first_tile, TensorDesc* d) {
+  std::memset(d, 0, sizeof *d);
+  unsigned char* b = static_cast<unsigned char*>(blob);
+  d->src = static_cast<const uint16_t*>(src);
+  d->dst = dst;
+  d->codes = b + L.codes_off;
+  d->scales = reinterpret_cast<float*>(b + L.scales_off);
+  d->zp = reinterpret_cast<float*>(b + L.zp_off);
+  d->tile_ptr = reinterpret_cast<uint32_t*>(b + L.tile_ptr_off);
+  d->idx = reinterpret_cast<int32_t*>(b + L.idx_off);
+  d->val = reinterpret_cast<uint16_t*>(b + L.val_off);
+  d->status = reinterpret_cast<uint32_t*>(b + L.status_off);
+  d->numel = numel;
+  d->n_tiles = p.n_tiles;
+  d->first_tile = first_tile;
+  d->lgq = p.lgq;
+  d->lgs = p.lgs;
+  d->cap = m->max_outliers;
+  d->topk = m->topk;
+  d->param = p.param;
+  d->divisor = p.divisor;
+  d->variant = p.variant;
+  d->dst_f32 = dst_dtype == ADACC_DST_F32 ? 1u : 0u;
+}
+
+static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+static uint32_t spin_limit() { return (uint32_t)env_int("ADACC_SPIN_LIMIT", 1 << 22); }
+
+static int grid_for(uint32_t n_tiles, uint32_t* grid) {
+  int cus = 0;
+  const int rc = device_cus(&cus);
+  if (rc != ADACC_OK) return rc;
+  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_WGS_PER_CU", 8);
+  const uint64_t want = ((uint64_t)n_tiles + kWavesPerWg - 1) / kWavesPerWg;
+  *grid = (uint32_t)(want < cap ? want : cap);
+  if (*grid == 0) *grid = 1;
+  return ADACC_OK;
+}
+
+typedef void (*CompressFn)(TensorDesc, WsHeader*, uint64_t*, uint32_t);
+typedef void (*DecompressFn)(TensorDesc, uint32_t);
+
+template <int MODE, int BITS, bool ASYM>
+static CompressFn compress_fn_e(bool e8) {
+  return e8 ? compress_kernel<MODE, BITS, ASYM, 8> : compress_kernel<MODE, BITS, ASYM, 4>;
+}
+template <int MODE>
+static CompressFn compress_fn_m(uint32_t bits, uint32_t asym, bool e8) {
+  if (bits == 4) return asym ? compress_fn_e<MODE, 4, true>(e8) : compress_fn_e<MODE, 4, false>(e8);
+  return asym ? compress_fn_e<MODE, 8, true>(e8) : compress_fn_e<MODE, 8, false>(e8);
+}
+static CompressFn compress_fn(const adacc_method* m, bool e8) {
+  switch (m->outlier_mode) {
+    case ADACC_OUTLIER_NONE: return compress_fn_m<kModeNone>(m->bits, m->asym, e8);
+    case ADACC_OUTLIER_ABS: return compress_fn_m<kModeAbs>(m->bits, m->asym, e8);
+    case ADACC_OUTLIER_STD: return compress_fn_m<kModeStd>(m->bits, m->asym, e8);
+    default: return compress_fn_m<kModeTopk>(m->bits, m->asym, e8);
+  }
+}
+template <int BITS, bool ASYM>
+static DecompressFn decompress_fn_e(bool e8, bool f32) {
+  if (e8) return f32 ? decompress_kernel<BITS, ASYM, 8, true> : decompress_kernel<BITS, ASYM, 8, false>;
+  return f32 ? decompress_kernel<BITS, ASYM, 4, true> : decompress_kernel<BITS, ASYM, 4, false>;
+}
+static DecompressFn decompress_fn(const adacc_method* m, bool e8, bool f32) {
+  if (m->bits == 4) return m->asym ? decompress_fn_e<4, true>(e8, f32) : decompress_fn_e<4, false>(e8, f32);
+  return m->asym ? decompress_fn_e<8, true>(e8, f32) : decompress_fn_e<8, false>(e8, f32);
+}
+
+static int launch_check(const char* what) {
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? ADACC_OK : hip_fail(e, what);
+}
+
+// batch workspace: [header 256][state 8*total_tiles, padded][table n*sizeof(TensorDesc)]
+struct BatchPlan {
+  uint32_t total_tiles;
+  uint64_t table_off, bytes;
+};
+static BatchPlan batch_plan(uint32_t total_tiles, uint32_t n_active) {
+  BatchPlan b;
+  b.total_tiles = total_tiles;
+  b.table_off = align256(sizeof(WsHeader) + 8ull * total_tiles);
+  b.bytes = align256(b.table_off + (uint64_t)(n_active ? n_active : 1) * sizeof(TensorDesc));
+  return b;
+}
+
+}  // namespace adacc
+
+using namespace adacc;
+
+// ===================================================================== C ABI
+
+extern "C" {
+
+const char* adacc_version(void) { return "0.1"; }
+
+const char* adacc_strerror(int code) {
+  switch (code) {
+    case ADACC_OK: return "ok";
+    case ADACC_EINVAL: return "invalid method or size";
+    case ADACC_ENULL: return "null pointer";
+    case ADACC_ESIZE: return "blob or workspace too small";
+    case ADACC_EALIGN: return "device pointer not aligned";
+    case ADACC_EHIP: return g_hip_err;
+    default: return "unknown error code";
+  }
+}
+
+int adacc_layout_of(const adacc_method* method, uint64_t numel, adacc_layout* out) {
+  if (!method || !out) return ADACC_ENULL;
+  Plan p;
+  const int rc = make_plan(method, numel, &p);
+  if (rc != ADACC_OK) return rc;
+  fill_layout(method, numel, p, out);
+  return ADACC_OK;
+}
+
+uint64_t adacc_workspace_bytes(const adacc_method* method, uint64_t numel) {
+  if (!method) return 0;
+  Plan p;
+  if (make_plan(method, numel, &p) != ADACC_OK || p.noop || !p.outliers) return 0;
+  return align256(sizeof(WsHeader) + 8ull * p.n_tiles);
+}
+
+int adacc_workspace_init(void* workspace, uint64_t workspace_bytes, void* hip_stream) {
+  if (!workspace) return ADACC_ENULL;
+  if (workspace_bytes < sizeof(WsHeader) + 8 || workspace_bytes % 16 != 0) return ADACC_ESIZE;
+  if (misaligned(workspace, 256)) return ADACC_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint64_t n16 = workspace_bytes / 16;
+  uint32_t grid = (uint32_t)((n16 + kThreads - 1) / kThreads);
+  if (grid > 4096) grid = 4096;
+  // capacity = the number of state words that are now known to be clear
+  const uint64_t words = (workspace_bytes - sizeof(WsHeader)) / 8;
+  const uint32_t capacity = words > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)words;
+  hipLaunchKernelGGL(workspace_clear_kernel, dim3(grid), dim3(kThreads), 0, s, static_cast<uint4*>(workspace), n16,
+                     capacity);
+  return launch_check("workspace_clear_kernel");
+}
+
+int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
+                   void* workspace, uint64_t workspace_bytes, void* hip_stream) {
+  if (!method) return ADACC_ENULL;
+  Plan p;
+  int rc = make_plan(method, numel, &p);
+  if (rc != ADACC_OK) return rc;
+  if (p.noop || numel == 0) return ADACC_OK;
+  if (!src || !blob) return ADACC_ENULL;
+  adacc_layout L;
+  fill_layout(method, numel, p, &L);
+  if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
+  if (misaligned(src, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
+  if (p.outliers) {
+    if (!workspace) return ADACC_ENULL;
+    if (workspace_bytes < align256(sizeof(WsHeader) + 8ull * p.n_tiles)) return ADACC_ESIZE;
+    if (misaligned(workspace, 256)) return ADACC_EALIGN;
+  }
+  TensorDesc d;
+  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, &d);
+  uint32_t grid = 0;
+  rc = grid_for(p.n_tiles, &grid);
+  if (rc != ADACC_OK) return rc;
+  WsHeader* hdr = static_cast<WsHeader*>(workspace);
+  uint64_t* state = workspace ? reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + sizeof(WsHeader)) : nullptr;
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, hdr, state, spin_limit());
+  return launch_check("compress_kernel");
+}
+
+int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob_bytes, uint64_t numel, void* dst,
+                     int dst_dtype, void* hip_stream) {
+  if (!method) return ADACC_ENULL;
+  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  Plan p;
+  int rc = make_plan(method, numel, &p);
+  if (rc != ADACC_OK) return rc;
+  if (p.noop || numel == 0) return ADACC_OK;
+  if (!blob || !dst) return ADACC_ENULL;
+  adacc_layout L;
+  fill_layout(method, numel, p, &L);
+  if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
+  if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
+  TensorDesc d;
+  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, &d);
+  uint32_t grid = 0;
+  rc = grid_for(p.n_tiles, &grid);
+  if (rc != ADACC_OK) return rc;
+  DecompressFn fn = decompress_fn(method, p.tile_elems == 4096, dst_dtype == ADACC_DST_F32);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, p.outliers ? 1u : 0u);
+  return launch_check("decompress_kernel");
+}
+
+static int batch_prepare(uint32_t n, const adacc_method* methods, const uint64_t* numels, std::vector<Plan>* plans,
+                         uint32_t* total_tiles, uint32_t* n_active) {
+  plans->resize(n);
+  uint64_t tiles = 0;
+  uint32_t act = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    const int rc = make_plan(&methods[i], numels[i], &(*plans)[i]);
+    if (rc != ADACC_OK) return rc;
+    if ((*plans)[i].noop || numels[i] == 0) { (*plans)[i].noop = true; continue; }
+    tiles += (*plans)[i].n_tiles;
+    ++act;
+  }
+  if (tiles >= (1ull << 32)) return ADACC_EINVAL;
+  *total_tiles = (uint32_t)tiles;
+  *n_active = act;
+  return ADACC_OK;
+}
+
+uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method* methods, const uint64_t* numels) {
+  if (n && (!methods || !numels)) return 0;
+  std::vector<Plan> plans;
+  uint32_t total = 0, act = 0;
+  if (batch_prepare(n, methods, numels, &plans, &total, &act) != ADACC_OK) return 0;
+  return batch_plan(total, act).bytes;
+}
+
+static int batch_table(uint32_t n, const adacc_method* methods, const std::vector<Plan>& plans, const uint64_t* numels,
+                       const void* const* srcs, void* const* blobs, const uint64_t* blob_bytes, void* const* dsts,
+                       int dst_dtype, bool compress, std::vector<TensorDesc>* table) {
+  uint32_t first = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (plans[i].noop) continue;
+    if (!blobs[i]) return ADACC_ENULL;
+    if (compress ? !srcs[i] : !dsts[i]) return ADACC_ENULL;
+    adacc_layout L;
+    fill_layout(&methods[i], numels[i], plans[i], &L);
+    if (blob_bytes[i] < L.total_bytes) return ADACC_ESIZE;
+    if (misaligned(blobs[i], 256)) return ADACC_EALIGN;
+    if (compress ? misaligned(srcs[i], 16) : misaligned(dsts[i], 16)) return ADACC_EALIGN;
+    TensorDesc d;
+    fill_desc(&methods[i], numels[i], plans[i], L, compress ? srcs[i] : nullptr, blobs[i], compress ? nullptr : dsts[i],
+              dst_dtype, first, &d);
+    table->push_back(d);
+    first += plans[i].n_tiles;
+  }
+  return ADACC_OK;
+}
+
+int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* const* srcs, const uint64_t* numels,
+                         void* const* blobs, const uint64_t* blob_bytes, void* workspace, uint64_t workspace_bytes,
+                         void* hip_stream) {
+  if (n == 0) return ADACC_OK;
+  if (!methods || !srcs || !numels || !blobs || !blob_bytes) return ADACC_ENULL;
+  std::vector<Plan> plans;
+  uint32_t total = 0, act = 0;
+  int rc = batch_prepare(n, methods, numels, &plans, &total, &act);
+  if (rc != ADACC_OK) return rc;
+  if (act == 0) return ADACC_OK;
+  if (!workspace) return ADACC_ENULL;
+  const BatchPlan bp = batch_plan(total, act);
+  if (workspace_bytes < bp.bytes) return ADACC_ESIZE;
+  if (misaligned(workspace, 256)) return ADACC_EALIGN;
+  std::vector<TensorDesc> table;
+  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, &table);
+  if (rc != ADACC_OK) return rc;
+  uint32_t grid = 0;
+  rc = grid_for(total, &grid);
+  if (rc != ADACC_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const hipError_t e = hipMemcpyAsync(ws + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
+                                      hipMemcpyHostToDevice, s);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
+  hipLaunchKernelGGL(compress_batch_kernel, dim3(grid), dim3(kThreads), 0, s,
+                     reinterpret_cast<const TensorDesc*>(ws + bp.table_off), (uint32_t)table.size(), total,
+                     reinterpret_cast<WsHeader*>(ws), reinterpret_cast<uint64_t*>(ws + sizeof(WsHeader)), spin_limit());
+  return launch_check("compress_batch_kernel");
+}
+
+int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* const* blobs, const uint64_t* blob_bytes,
+                           const uint64_t* numels, void* const* dsts, int dst_dtype, void* workspace,
+                           uint64_t workspace_bytes, void* hip_stream) {
+  if (n == 0) return ADACC_OK;
+  if (!methods || !blobs || !numels || !dsts || !blob_bytes) return ADACC_ENULL;
+  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  std::vector<Plan> plans;
+  uint32_t total = 0, act = 0;
+  int rc = batch_prepare(n, methods, numels, &plans, &total, &act);
+  if (rc != ADACC_OK) return rc;
+  if (act == 0) return ADACC_OK;
+  if (!workspace) return ADACC_ENULL;
+  const BatchPlan bp = batch_plan(total, act);
+  if (workspace_bytes < bp.bytes) return ADACC_ESIZE;
+  if (misaligned(workspace, 256)) return ADACC_EALIGN;
+  std::vector<TensorDesc> table;
+  rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
+                   false, &table);
+  if (rc != ADACC_OK) return rc;
+  uint32_t grid = 0;
+  rc = grid_for(total, &grid);
+  if (rc != ADACC_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const hipError_t e = hipMemcpyAsync(ws + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
+                                      hipMemcpyHostToDevice, s);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
+  const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(ws + bp.table_off);
+  if (dst_dtype == ADACC_DST_F32)
+    hipLaunchKernelGGL(decompress_batch_kernel<true>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
+  else
+    hipLaunchKernelGGL(decompress_batch_kernel<false>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
+  return launch_check("decompress_batch_kernel");
+}
+
+int adacc_read_status(const void* blob, const adacc_layout* layout, void* hip_stream, uint32_t status_out[4]) {
+  if (!blob || !layout || !status_out) return ADACC_ENULL;
+  if (layout->total_bytes == 0) { status_out[0] = status_out[1] = status_out[2] = status_out[3] = 0; return ADACC_OK; }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipMemcpyAsync(status_out, static_cast<const unsigned char*>(blob) + layout->status_off, 16,
+                                hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(status)");
+  e = hipStreamSynchronize(s);
+  return e == hipSuccess ? ADACC_OK : hip_fail(e, "hipStreamSynchronize");
+}
+
+int adacc_hbm_copy(void* dst, const void* src, uint64_t bytes, void* hip_stream) {
+  if (!dst || !src) return ADACC_ENULL;
+  if (bytes % 16 != 0) return ADACC_EINVAL;
+  if (misaligned(dst, 16) || misaligned(src, 16)) return ADACC_EALIGN;
+  if (bytes == 0) return ADACC_OK;
+  int cus = 0;
+  const int rc = device_cus(&cus);
+  if (rc != ADACC_OK) return rc;
+  const uint64_t n16 = bytes / 16;
+  uint64_t grid = (n16 + kThreads - 1) / kThreads;
+  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_COPY_WGS_PER_CU", 16);
+  if (grid > cap) grid = cap;
+  hipLaunchKernelGGL(hbm_copy_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+  return launch_check("hbm_copy_kernel");
+}
+
+}  // extern "C"

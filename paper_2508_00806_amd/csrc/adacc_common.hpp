@@ -1,0 +1,70 @@
+// Shared device/host definitions of libadacc (gfx950 only).
+//
+// Work decomposition used by every kernel here:
+//   - a lane owns one "octet": 8 consecutive bf16 elements = one 16-byte load;
+//   - a wavefront (64 lanes) covers one "row" of 512 consecutive elements per load
+//     instruction, fully coalesced (1 KiB);
+//   - a tile is E rows (E = 4 or 8, i.e. 2048 or 4096 elements) and belongs to ONE
+//     wavefront; every statistics / quantisation group lies inside one tile, so all
+//     reductions are wavefront-local and no kernel here needs a workgroup barrier.
+//   - a workgroup is just 4 independent wavefronts.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adacc {
+
+constexpr int kWave = 64;
+constexpr int kOct = 8;               // elements per lane per row
+constexpr int kRow = kWave * kOct;    // 512 elements
+constexpr int kWavesPerWg = 4;
+constexpr int kThreads = kWave * kWavesPerWg;
+
+enum : uint32_t { kModeNone = 0, kModeAbs = 1, kModeStd = 2, kModeTopk = 3 };
+
+// One tensor as the kernels see it.  Passed by value for single-tensor launches
+// and read from a device table for batch launches.
+struct TensorDesc {
+  const uint16_t* src;  // compress: bf16 input
+  void* dst;            // decompress: output
+  uint8_t* codes;
+  float* scales;
+  float* zp;
+  uint32_t* tile_ptr;
+  int32_t* idx;
+  uint16_t* val;
+  uint32_t* status;
+  uint64_t numel;
+  uint32_t n_tiles;
+  uint32_t first_tile;  // launch-wide id of this tensor's tile 0
+  uint32_t lgq;         // log2(quant group)
+  uint32_t lgs;         // log2(stat group) (STD / TOPK)
+  uint32_t cap;         // capacity of idx / val
+  uint32_t topk;
+  float param;          // ABS: tau.  STD: k*k
+  float divisor;        // D of Eq. 2 resp. Eq. 3 (2^(b-1), 2^b, or one less)
+  uint32_t variant;     // index into the instantiation table
+  uint32_t dst_f32;     // decompress: 1 = binary32 output
+};
+
+// Head of a scan workspace (256 bytes), followed by one 64-bit state word per tile.
+struct WsHeader {
+  uint32_t epoch;     // completed launches; state words of other epochs read as empty
+  uint32_t ticket;    // next tile to hand out (0 between launches)
+  uint32_t done;      // wavefronts that have left the kernel (0 between launches)
+  uint32_t capacity;  // state words that were cleared by adacc_workspace_init
+  uint32_t pad[60];
+};
+static_assert(sizeof(WsHeader) == 256, "header is one 256-byte block");
+
+// State word: high half = (epoch_tag << 2) | flag, low half = value.
+enum : uint32_t { kFlagEmpty = 0, kFlagAggregate = 1, kFlagPrefix = 2, kFlagAbort = 3 };
+constexpr uint32_t kEpochWrap = 0x3FFFFFF0u;
+
+// variant index: ((mode*2 + (bits==8)) * 2 + asym) * 2 + (E==8)
+__host__ __device__ inline uint32_t variant_index(uint32_t mode, uint32_t bits, uint32_t asym, uint32_t e8) {
+  return ((mode * 2 + (bits == 8 ? 1u : 0u)) * 2 + asym) * 2 + e8;
+}
+
+}  // namespace adacc

@@ -1,0 +1,124 @@
+"""Glue for the tests: the same method dictionary turned into the oracle's and the
+library's descriptor, and the element-by-element comparison of a GPU blob with the oracle."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2508_00806_amd as adacc
+
+MODE_ID = {"none": 0, "abs": 1, "std": 2, "topk": 3}
+
+
+def oracle_method(md, rule=0):
+    return oracle.Method(bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"], scale_rule=rule,
+                         outlier_mode=MODE_ID[md["outlier_mode"]], stat_group=md["stat_group"],
+                         thresh=md["thresh"], topk=md["topk"])
+
+
+def adacc_method(md, cap, rule=0):
+    if md is None:
+        return adacc.NOOP
+    return adacc.Method(kind=adacc.KIND_QUANT, bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"],
+                        scale_rule=rule, outlier_mode=MODE_ID[md["outlier_mode"]], stat_group=md["stat_group"],
+                        thresh=md["thresh"], topk=md["topk"], max_outliers=cap)
+
+
+def bits_of(t):
+    """bf16 torch tensor (any device) -> numpy uint16 bit patterns."""
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
+
+
+def from_bits(b, device="cpu"):
+    return torch.from_numpy(np.ascontiguousarray(b).view(np.int16).copy()).view(torch.bfloat16).to(device)
+
+
+def gpu_compress(x_dev, m, ws=None):
+    """x_dev: bf16 tensor on the GPU.  Returns (blob, layout, workspace)."""
+    numel = x_dev.numel()
+    blob, L = adacc.alloc_blob(m, numel)
+    if ws is None and m.outlier_mode != adacc.OUTLIER_NONE:
+        ws = adacc.alloc_workspace(adacc.workspace_bytes(m, numel))
+    adacc.compress(m, x_dev, blob, ws)
+    return blob, L, ws
+
+
+def compare_blob_with_oracle(blob, L, m, numel, oc, check_stream=True):
+    """Bit-exact comparison of every used section of a GPU blob with the oracle's result."""
+    sec = {k: v.cpu().numpy() for k, v in adacc.blob_sections(blob, L, m, numel).items()}
+    assert np.array_equal(sec["codes"], oc.packed), "packed codes differ"
+    assert np.array_equal(sec["scales"].view(np.uint32), oc.scale.view(np.uint32)), "scales differ"
+    if m.asym:
+        assert np.array_equal(sec["zp"].view(np.uint32), oc.zp.view(np.uint32)), "offsets differ"
+    st = sec["status"].view(np.uint32)
+    assert st[2] == 0, "kernel reported an aborted scan"
+    if m.outlier_mode != adacc.OUTLIER_NONE:
+        assert int(st[0]) == oc.n_out, f"outlier count {int(st[0])} != {oc.n_out}"
+        assert int(st[1]) == (1 if oc.n_out > m.max_outliers else 0)
+        k = min(oc.n_out, m.max_outliers)
+        if check_stream:
+            assert np.array_equal(sec["idx"][:k], oc.out_idx[:k]), "outlier indices differ"
+            assert np.array_equal(sec["val"][:k].view(np.uint16), oc.out_val[:k]), "outlier values differ"
+        # tile offsets = number of oracle outliers before each tile boundary
+        full = oracle_full_indices(oc)
+        bounds = np.arange(L.n_tiles + 1, dtype=np.int64) * L.tile_elems
+        want = np.searchsorted(full, bounds, side="left")
+        assert np.array_equal(sec["tile_ptr"].view(np.uint32).astype(np.int64), want), "tile offsets differ"
+    else:
+        assert int(st[0]) == 0 and int(st[1]) == 0
+    return sec
+
+
+def oracle_full_indices(oc):
+    """All outlier indices of the oracle result, also past a truncated capacity."""
+    if oc.n_out == oc.out_idx.size:
+        return oc.out_idx.astype(np.int64)
+    return oc._full_idx
+
+
+def assert_f32_matches(got, want):
+    """Within 1e-6 absolute of the oracle's binary32 result (the stated bar) and, stronger, the same
+    bits.  Where the oracle itself yields Inf/NaN (a group whose range overflows binary32) only the
+    class has to agree: NaN payloads are not part of the format."""
+    fin = np.isfinite(want)
+    assert np.array_equal(np.isfinite(got), fin)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.all(np.abs(got[fin].astype(np.float64) - want[fin].astype(np.float64)) <= 1e-6), \
+        "binary32 reconstruction differs by more than 1e-6"
+    ok = ~np.isnan(want)
+    assert np.array_equal(got.view(np.uint32)[ok], want.view(np.uint32)[ok]), "binary32 reconstruction not bit-equal"
+
+
+def assert_bf16_matches(got_bits, want_bits):
+    nan = (want_bits & 0x7FFF) > 0x7F80
+    assert np.array_equal((got_bits & 0x7FFF) > 0x7F80, nan)
+    assert np.array_equal(got_bits[~nan], want_bits[~nan]), "bf16 reconstruction differs"
+
+
+def run_parity(x_cpu_bf16, md, cap=None, rule=0, decompress=True):
+    """Compress on the GPU and in the oracle, compare everything, then decompress both ways."""
+    x_bits = bits_of(x_cpu_bf16)
+    numel = x_bits.size
+    om = oracle_method(md, rule)
+    oc_full = oracle.compress(om, x_bits)
+    if cap is None:
+        cap = max(oc_full.n_out, 1) if md["outlier_mode"] != "none" else 0
+    oc = oracle.compress(om, x_bits, cap=cap)
+    oc._full_idx = oc_full.out_idx.astype(np.int64)
+    m = adacc_method(md, cap, rule)
+    x_dev = x_cpu_bf16.contiguous().view(-1).cuda()
+    blob, L, ws = gpu_compress(x_dev, m)
+    torch.cuda.synchronize()
+    st = adacc.read_status(blob, L)
+    if md["outlier_mode"] != "none":
+        assert st[0] == oc.n_out
+    compare_blob_with_oracle(blob, L, m, numel, oc)
+    if decompress and oc.n_out <= cap:
+        of32, obf = oracle.decompress(oc)
+        d32 = torch.empty(numel, dtype=torch.float32, device="cuda")
+        dbf = torch.empty(numel, dtype=torch.bfloat16, device="cuda")
+        adacc.decompress(m, blob, d32)
+        adacc.decompress(m, blob, dbf)
+        torch.cuda.synchronize()
+        assert_f32_matches(d32.cpu().numpy(), of32)
+        assert_bf16_matches(bits_of(dbf), obf)
+    return oc, blob, L, m

@@ -1,0 +1,165 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, computes layouts, and rejects bad calls before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2508_00806_amd as adacc
+from paper_2508_00806_amd import Method
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(adacc.LIB_PATH):
+        from paper_2508_00806_amd.build import build
+        build()
+    return adacc.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adacc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adacc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_symbols()
+    assert set(names) == set(adacc.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_sizes_match_the_header(L):
+    assert ctypes.sizeof(adacc.CMethod) == 40
+    assert ctypes.sizeof(adacc.CLayout) == 72
+
+
+def test_layout_closed_form(L):
+    m = Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=2048, topk=2, max_outliers=1000)
+    n = 2048 * 37
+    lay = adacc.layout_of(m, n)
+    assert lay.tile_elems == 2048 and lay.n_tiles == 37
+    a = lambda v: (v + 255) // 256 * 256
+    assert lay.codes_off == 0
+    assert lay.scales_off == a(n // 2)
+    assert lay.zp_off == lay.scales_off + a(4 * n // 128)
+    assert lay.tile_ptr_off == lay.zp_off
+    assert lay.idx_off == lay.tile_ptr_off + a(4 * 38)
+    assert lay.val_off == lay.idx_off + a(4000)
+    assert lay.status_off == lay.val_off + a(2000)
+    assert lay.total_bytes == lay.status_off + 256
+    # stat group 4096 -> 4096-element tiles; ragged tail rounds up
+    m2 = Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=4096, thresh=3.0, max_outliers=8)
+    lay2 = adacc.layout_of(m2, 4096 * 3)
+    assert lay2.tile_elems == 4096 and lay2.n_tiles == 3
+    m3 = Method(bits=8, quant_group=64)
+    lay3 = adacc.layout_of(m3, 64 * 33)
+    assert lay3.tile_elems == 2048 and lay3.n_tiles == 2 and lay3.tile_ptr_off == lay3.idx_off == lay3.val_off
+    # no-op: nothing
+    lay0 = adacc.layout_of(adacc.NOOP, 12345)
+    assert lay0.total_bytes == 0 and lay0.n_tiles == 0
+    assert adacc.workspace_bytes(m, n) == a(256 + 8 * 37)
+    assert adacc.workspace_bytes(m3, 64 * 33) == 0
+
+
+BAD = [
+    Method(bits=5, quant_group=64),
+    Method(bits=8, quant_group=48),
+    Method(bits=8, quant_group=4),
+    Method(bits=8, quant_group=8192),
+    Method(bits=8, quant_group=64, asym=2),
+    Method(bits=8, quant_group=64, scale_rule=2),
+    Method(bits=8, quant_group=64, outlier_mode=4),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=32, thresh=1.0),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=8192, thresh=1.0),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=64, thresh=-1.0),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=float("nan")),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_TOPK, stat_group=64, topk=0),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_TOPK, stat_group=64, topk=33),
+    Method(kind=7, bits=8, quant_group=64),
+]
+
+
+@pytest.mark.parametrize("m", BAD)
+def test_malformed_methods(L, m):
+    with pytest.raises(adacc.AdaccError) as e:
+        adacc.layout_of(m, 4096)
+    assert e.value.code == adacc.EINVAL
+
+
+def test_numel_rules(L):
+    m = Method(bits=8, quant_group=64)
+    with pytest.raises(adacc.AdaccError):
+        adacc.layout_of(m, 100)  # group does not divide numel
+    mo = Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=4)
+    with pytest.raises(adacc.AdaccError):
+        adacc.layout_of(mo, 1 << 31)  # 32-bit indices
+    assert adacc.layout_of(m, 1 << 31).n_tiles == (1 << 31) // 2048
+
+
+def test_errors_are_returned_before_any_device_work(L):
+    """Fake device addresses: a call that got past validation would fault, so reaching the
+    error code proves the checks come first."""
+    m = Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=16)
+    n = 4096
+    lay = adacc.layout_of(m, n)
+    cm = m.c()
+    src, blob, ws = 0x10000, 0x20000, 0x30000
+    f = L.adacc_compress
+    assert f(None, src, n, blob, lay.total_bytes, ws, 4096, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), None, n, blob, lay.total_bytes, ws, 4096, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, None, lay.total_bytes, ws, 4096, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, None, 0, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes - 1, ws, 4096, None) == adacc.ESIZE
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, ws, 8, None) == adacc.ESIZE
+    assert f(ctypes.byref(cm), src + 2, n, blob, lay.total_bytes, ws, 4096, None) == adacc.EALIGN
+    assert f(ctypes.byref(cm), src, n, blob + 16, lay.total_bytes, ws, 4096, None) == adacc.EALIGN
+    assert f(ctypes.byref(cm), src, n + 1, blob, lay.total_bytes, ws, 4096, None) == adacc.EINVAL
+    # nothing to do: OK without looking at the pointers
+    assert f(ctypes.byref(cm), None, 0, None, 0, None, 0, None) == adacc.OK
+    noop = adacc.NOOP.c()
+    assert f(ctypes.byref(noop), None, n, None, 0, None, 0, None) == adacc.OK
+    g = L.adacc_decompress
+    assert g(ctypes.byref(cm), blob, lay.total_bytes, n, None, 0, None) == adacc.ENULL
+    assert g(ctypes.byref(cm), blob, lay.total_bytes, n, 0x40000, 2, None) == adacc.EINVAL
+    assert g(ctypes.byref(cm), blob, lay.total_bytes - 1, n, 0x40000, 0, None) == adacc.ESIZE
+    assert g(ctypes.byref(cm), blob, lay.total_bytes, n, 0x40002, 0, None) == adacc.EALIGN
+    assert L.adacc_hbm_copy(0x10000, 0x20000, 24, None) == adacc.EINVAL
+    assert L.adacc_workspace_init(None, 4096, None) == adacc.ENULL
+    assert L.adacc_workspace_init(0x10000, 8, None) == adacc.ESIZE
+
+
+def test_batch_validation(L):
+    ms = [Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=4096, topk=4, max_outliers=64),
+          adacc.NOOP, Method(bits=8, quant_group=128)]
+    numels = [4096 * 5, 999, 128 * 100]
+    need = adacc.batch_workspace_bytes(ms, numels)
+    tiles = 5 + (128 * 100 + 2047) // 2048
+    a = lambda v: (v + 255) // 256 * 256
+    assert need >= a(256 + 8 * tiles) + 2 * 128
+    n = 3
+    cms = (adacc.CMethod * n)(*[m.c() for m in ms])
+    cn = (ctypes.c_uint64 * n)(*numels)
+    srcs = (ctypes.c_void_p * n)(0x10000, None, 0x20000)
+    blobs = (ctypes.c_void_p * n)(0x100000, None, 0x200000)
+    bb = (ctypes.c_uint64 * n)(adacc.layout_of(ms[0], numels[0]).total_bytes, 0,
+                               adacc.layout_of(ms[2], numels[2]).total_bytes)
+    f = L.adacc_compress_batch
+    assert f(n, cms, srcs, cn, blobs, bb, 0x300000, need - 256, None) == adacc.ESIZE
+    assert f(n, cms, srcs, cn, blobs, bb, None, need, None) == adacc.ENULL
+    bb[2] -= 1
+    assert f(n, cms, srcs, cn, blobs, bb, 0x300000, need, None) == adacc.ESIZE
+    bb[2] += 1
+    srcs[0] = None
+    assert f(n, cms, srcs, cn, blobs, bb, 0x300000, need, None) == adacc.ENULL
+    assert f(0, None, None, None, None, None, None, 0, None) == adacc.OK
+
+
+def test_strerror_and_version(L):
+    assert adacc.strerror(0) == "ok"
+    assert "align" in adacc.strerror(adacc.EALIGN)
+    assert re.match(r"^\d+\.\d+$", adacc.version())

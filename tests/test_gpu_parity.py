@@ -1,0 +1,342 @@
+"""GPU parity: libadacc (through the C ABI) against the CPU oracle, element by element.
+Bar: bit-exact packed codes, scales, offsets, outlier indices / values / counts / tile
+offsets; decompressed binary32 within 1e-6 absolute of the oracle (checked bit-equal as
+well); decompressed bf16 equal to the oracle's bf16."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_00806_amd as adacc
+import workloads
+from helpers import (adacc_method, assert_bf16_matches, assert_f32_matches, bits_of, compare_blob_with_oracle, from_bits, gpu_compress, oracle_method,
+                     run_parity)
+
+pytestmark = pytest.mark.gpu
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+def random_bits(seed, n, heavy=True, edge=True):
+    g = np.random.default_rng(seed)
+    x = g.standard_normal(n).astype(np.float32)
+    if heavy:
+        k = max(1, n // 64)
+        x[g.choice(n, k, replace=False)] *= 30.0
+    t = torch.from_numpy(x).to(torch.bfloat16)
+    b = bits_of(t).copy()
+    if edge and n >= 64:
+        # ties in magnitude, signed zeros, denormals, the largest finite values
+        b[1] = 0x8000
+        b[2] = 0x0001
+        b[3] = 0x8001
+        b[5] = b[9] = 0x4110
+        b[11] = 0xC110
+        b[n - 1] = 0x7F7F
+        b[n - 2] = 0xFF7F
+    return b
+
+
+# ------------------------------------------------------------------ the five configurations, reduced
+@pytest.mark.parametrize("name,rows", [("c1", 67), ("c2", 37), ("c3", 5), ("c4", 2048)])
+def test_config_reduced(name, rows):
+    log(f"[parity] config {name} rows={rows}")
+    x = workloads.make(name, "cpu", rows=rows)
+    md = workloads.METHODS[name]
+    cap = workloads.outlier_capacity(md, x.numel(), x.shape[-1])
+    oc, *_ = run_parity(x, md, cap=cap)
+    log(f"[parity] {name}: numel={x.numel()} n_out={oc.n_out} cap={cap}")
+    if name == "c2":
+        assert oc.n_out == 2 * rows
+    if name == "c4":
+        assert 0 < oc.n_out <= cap
+
+
+def test_config5_layer_reduced():
+    for t, (tname, hidden, md) in enumerate(workloads.C5_LAYER):
+        if md is None:
+            continue
+        log(f"[parity] c5 {tname}")
+        x = workloads.c5_tensor(tname, "cpu", rows=24, seed=5000 + t)
+        cap = workloads.outlier_capacity(md, x.numel(), hidden)
+        run_parity(x, md, cap=cap)
+
+
+# ------------------------------------------------------------------ the whole method space on small tensors
+SWEEP = []
+for bits in (4, 8):
+    for asym in (0, 1):
+        for gq, gs in ((8, 8), (16, 64), (64, 64), (128, 512), (512, 512), (128, 1024), (1024, 1024), (256, 2048),
+                       (2048, 2048), (128, 4096), (4096, 4096)):
+            SWEEP.append((bits, asym, gq, gs))
+
+
+@pytest.mark.parametrize("mode", ["none", "abs", "std", "topk"])
+@pytest.mark.parametrize("rule", [0, 1])
+def test_method_sweep(mode, rule):
+    for bits, asym, gq, gs in SWEEP:
+        groups = 13 if gs <= 1024 else 5   # ragged last tile for most sizes
+        n = gs * groups
+        x = from_bits(random_bits(1000 * bits + 10 * gq + gs + asym, n))
+        md = dict(bits=bits, quant_group=gq, asym=asym, outlier_mode=mode, stat_group=gs,
+                  thresh={"abs": 2.5, "std": 3.0}.get(mode, 0.0), topk=3 if mode == "topk" else 0)
+        log(f"[parity] sweep mode={mode} rule={rule} bits={bits} asym={asym} gq={gq} gs={gs} n={n}")
+        run_parity(x, md, rule=rule)
+
+
+# ------------------------------------------------------------------ edge cases
+def test_degenerate_inputs():
+    z = np.zeros(4096, dtype=np.uint16)
+    const = bits_of(torch.full((4096,), 0.75, dtype=torch.bfloat16))
+    tiny = np.zeros(4096, dtype=np.uint16)
+    tiny[0], tiny[1], tiny[100] = 0x0001, 0x8001, 0x0080
+    huge = np.full(4096, 0x7F7F, dtype=np.uint16)
+    huge[::2] = 0xFF7F
+    nonfin = random_bits(5, 4096)
+    nonfin[7], nonfin[300], nonfin[2049], nonfin[4000] = 0x7F80, 0xFF80, 0x7FC0, 0xFFFF
+    for label, b in (("zeros", z), ("const", const), ("tiny", tiny), ("huge", huge), ("nonfinite", nonfin)):
+        for mode in ("none", "abs", "std", "topk"):
+            for asym in (0, 1):
+                if label == "nonfinite" and mode == "none":
+                    continue  # nothing is kept aside then: non-finite values are zeroed, covered below
+                md = dict(bits=8, quant_group=64, asym=asym, outlier_mode=mode, stat_group=256,
+                          thresh={"abs": 1.0, "std": 4.0}.get(mode, 0.0), topk=2 if mode == "topk" else 0)
+                log(f"[parity] degenerate {label} mode={mode} asym={asym}")
+                run_parity(from_bits(b), md)
+    md = dict(bits=4, quant_group=64, asym=0, outlier_mode="none", stat_group=0, thresh=0.0, topk=0)
+    run_parity(from_bits(nonfin), md)
+
+
+def test_every_element_an_outlier_and_overflow():
+    b = random_bits(77, 2048 * 3 + 512)
+    b[(b & 0x7FFF) == 0] = 0x3F80
+    md = dict(bits=8, quant_group=64, asym=0, outlier_mode="abs", stat_group=0, thresh=0.0, topk=0)
+    log("[parity] all outliers, capacity = numel")
+    oc, *_ = run_parity(from_bits(b), md, cap=b.size)
+    assert oc.n_out == b.size
+    log("[parity] all outliers, capacity 100: overflow flag")
+    oc, blob, L, m = run_parity(from_bits(b), md, cap=100, decompress=False)
+    st = adacc.read_status(blob, L)
+    assert st[0] == b.size and st[1] == 1
+
+
+def test_empty_and_single_group():
+    m = adacc.Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=4)
+    blob = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    adacc.compress(m, torch.empty(0, dtype=torch.bfloat16, device="cuda"), blob, None)
+    torch.cuda.synchronize()
+    assert int(blob.sum()) == 0
+    for gq in (8, 64, 4096):
+        md = dict(bits=4, quant_group=gq, asym=1, outlier_mode="topk", stat_group=gq, thresh=0.0, topk=1)
+        log(f"[parity] single group gq={gq}")
+        run_parity(from_bits(random_bits(gq, gq, heavy=False, edge=False)), md)
+
+
+def test_many_tiles_chained_scan():
+    """Enough tiles that the look-back crosses several 64-tile windows and every CU is busy."""
+    n = 2048 * 5000 + 1024
+    b = random_bits(123, n)
+    md = dict(bits=8, quant_group=128, asym=0, outlier_mode="std", stat_group=1024, thresh=5.0, topk=0)
+    log(f"[parity] many tiles n={n}")
+    oc, *_ = run_parity(from_bits(b), md)
+    assert oc.n_out > 10000
+    # sparse outliers: most tiles are empty, so the walk back over aggregates is long
+    b2 = bits_of(torch.from_numpy(np.random.default_rng(3).standard_normal(n).astype(np.float32)).to(torch.bfloat16))
+    md2 = dict(bits=4, quant_group=64, asym=0, outlier_mode="abs", stat_group=0, thresh=4.6, topk=0)
+    oc2, *_ = run_parity(from_bits(b2), md2)
+    log(f"[parity] sparse n_out={oc2.n_out}")
+    assert 0 < oc2.n_out < 200
+
+
+def test_deterministic_and_workspace_reuse():
+    """One workspace, many calls of different sizes and methods: every blob equals the oracle's,
+    and repeated calls give identical bytes."""
+    ws = adacc.alloc_workspace(256 + 8 * 4096)
+    cases = [(2048 * 700 + 64, dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=2.5, topk=0)),
+             (4096 * 9, dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=4096, thresh=0.0, topk=4)),
+             (2048 * 3, dict(bits=8, quant_group=2048, asym=1, outlier_mode="abs", stat_group=0, thresh=2.0, topk=0)),
+             (2048 * 1500, dict(bits=4, quant_group=32, asym=1, outlier_mode="abs", stat_group=0, thresh=3.0, topk=0))]
+    for rep in range(3):
+        for i, (n, md) in enumerate(cases):
+            b = random_bits(50 + i, n)
+            om = oracle_method(md)
+            oc = oracle.compress(om, b)
+            oc._full_idx = oc.out_idx.astype(np.int64)
+            m = adacc_method(md, max(oc.n_out, 1))
+            x = from_bits(b, "cuda")
+            log(f"[parity] reuse rep={rep} case={i} n={n}")
+            blob, L, _ = gpu_compress(x, m, ws=ws)
+            torch.cuda.synchronize()
+            compare_blob_with_oracle(blob, L, m, n, oc)
+            first = blob.clone()
+            for _ in range(5):
+                blob.zero_()
+                adacc.compress(m, x, blob, ws)
+            torch.cuda.synchronize()
+            used = int(L.status_off) + 16
+            sec_a = adacc.blob_sections(first, L, m, n)
+            sec_b = adacc.blob_sections(blob, L, m, n)
+            for k in ("codes", "scales", "tile_ptr", "status"):
+                assert torch.equal(sec_a[k], sec_b[k]), k
+            assert torch.equal(sec_a["idx"][:oc.n_out], sec_b["idx"][:oc.n_out])
+            assert torch.equal(sec_a["val"][:oc.n_out], sec_b["val"][:oc.n_out])
+            assert used <= L.total_bytes
+
+
+# ------------------------------------------------------------------ batch
+def test_batch_matches_single_calls_and_oracle():
+    rows = 12
+    table = []
+    for layer in range(2):
+        for t, (tname, hidden, md) in enumerate(workloads.C5_LAYER):
+            x = workloads.c5_tensor(tname, "cpu", rows=rows, seed=5000 + 10 * layer + t)
+            table.append((tname, hidden, md, x))
+    # an asymmetric + abs entry and a tiny ragged tensor, to mix more variants into one launch
+    table.append(("softmax", 2048, workloads.C4_METHOD, workloads.c4("cpu", rows=2048)[:64].contiguous()))
+    table.append(("small", 64, dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=2.0, topk=0),
+                  from_bits(random_bits(9, 64 * 5)).view(5, 64)))
+    methods, srcs, blobs, layouts, ocs = [], [], [], [], []
+    for tname, hidden, md, x in table:
+        n = x.numel()
+        if md is None:
+            methods.append(adacc.NOOP); srcs.append(x.cuda()); blobs.append(None); layouts.append(None); ocs.append(None)
+            continue
+        cap = workloads.outlier_capacity(md, n, hidden)
+        m = adacc_method(md, cap)
+        oc = oracle.compress(oracle_method(md), bits_of(x), cap=cap)
+        assert oc.n_out <= cap
+        oc._full_idx = oc.out_idx.astype(np.int64)
+        blob, L = adacc.alloc_blob(m, n)
+        methods.append(m); srcs.append(x.contiguous().view(-1).cuda()); blobs.append(blob); layouts.append(L); ocs.append(oc)
+    numels = [s.numel() for s in srcs]
+    ws = adacc.alloc_workspace(adacc.batch_workspace_bytes(methods, numels))
+    for rep in range(2):
+        log(f"[parity] batch compress rep={rep} tensors={len(methods)}")
+        for b in blobs:
+            if b is not None:
+                b.zero_()
+        adacc.compress_batch(methods, srcs, blobs, ws)
+        torch.cuda.synchronize()
+        for (tname, hidden, md, x), m, blob, L, oc in zip(table, methods, blobs, layouts, ocs):
+            if md is None:
+                continue
+            compare_blob_with_oracle(blob, L, m, x.numel(), oc)
+    # decompress: batch, both dtypes, against the oracle
+    for dtype in (torch.bfloat16, torch.float32):
+        dsts = [None if b is None else torch.empty(s.numel(), dtype=dtype, device="cuda") for s, b in zip(srcs, blobs)]
+        log(f"[parity] batch decompress {dtype}")
+        adacc.decompress_batch(methods, blobs, dsts, ws)
+        torch.cuda.synchronize()
+        for d, oc in zip(dsts, ocs):
+            if d is None:
+                continue
+            of32, obf = oracle.decompress(oc)
+            if dtype == torch.float32:
+                assert_f32_matches(d.cpu().numpy(), of32)
+            else:
+                assert_bf16_matches(bits_of(d), obf)
+    # the retained tensor was not touched
+    assert torch.equal(srcs[4].cpu(), table[4][3].contiguous().view(-1))
+
+
+# ------------------------------------------------------------------ full-size configurations, sampled
+def sampled_full_size(name, x_dev, md, hidden, n_samples=24):
+    """Compress the full tensor on the GPU in the launch configuration the bench uses; run the
+    oracle on sampled tiles (every group lies inside one tile, so a tile can be checked alone)."""
+    numel = x_dev.numel()
+    cap = workloads.outlier_capacity(md, numel, hidden)
+    m = adacc_method(md, cap)
+    blob, L, ws = gpu_compress(x_dev.view(-1), m)
+    torch.cuda.synchronize()
+    st = adacc.read_status(blob, L)
+    assert st[1] == 0 and st[2] == 0, st
+    sec = adacc.blob_sections(blob, L, m, numel)
+    te = int(L.tile_elems)
+    has_out = md["outlier_mode"] != "none"
+    if has_out:
+        tp = sec["tile_ptr"].cpu().numpy().view(np.uint32).astype(np.int64)
+        assert tp[0] == 0 and np.all(np.diff(tp) >= 0) and tp[-1] == st[0]
+        idx = sec["idx"][:st[0]]
+        assert bool((idx[1:] > idx[:-1]).all()), "outlier stream is not strictly ascending"
+    g = np.random.default_rng(2024)
+    tiles = sorted(set([0, L.n_tiles - 1] + g.integers(0, L.n_tiles, n_samples).tolist()))
+    om = oracle_method(md)
+    xf = x_dev.view(-1)
+    for t in tiles:
+        lo, hi = t * te, min(numel, (t + 1) * te)
+        oc = oracle.compress(om, bits_of(xf[lo:hi]))
+        cb = md["bits"]
+        got_codes = sec["codes"][lo * cb // 8: hi * cb // 8].cpu().numpy()
+        assert np.array_equal(got_codes, oc.packed), (name, t)
+        gq = md["quant_group"]
+        assert np.array_equal(sec["scales"][lo // gq: hi // gq].cpu().numpy().view(np.uint32), oc.scale.view(np.uint32)), (name, t)
+        if md["asym"]:
+            assert np.array_equal(sec["zp"][lo // gq: hi // gq].cpu().numpy().view(np.uint32), oc.zp.view(np.uint32)), (name, t)
+        if has_out:
+            p0, p1 = int(tp[t]), int(tp[t + 1])
+            assert p1 - p0 == oc.n_out, (name, t, p1 - p0, oc.n_out)
+            assert np.array_equal(sec["idx"][p0:p1].cpu().numpy().astype(np.int64), oc.out_idx.astype(np.int64) + lo)
+            assert np.array_equal(sec["val"][p0:p1].cpu().numpy().view(np.uint16), oc.out_val)
+    # round trip: bf16 output of sampled tiles equals the oracle's; outliers exact everywhere
+    dst = torch.empty(numel, dtype=torch.bfloat16, device="cuda")
+    adacc.decompress(m, blob, dst)
+    torch.cuda.synchronize()
+    for t in tiles:
+        lo, hi = t * te, min(numel, (t + 1) * te)
+        oc = oracle.compress(om, bits_of(xf[lo:hi]))
+        _, obf = oracle.decompress(oc)
+        assert np.array_equal(bits_of(dst[lo:hi]), obf), (name, t)
+    if has_out and st[0] > 0:
+        ii = sec["idx"][:st[0]].long()
+        assert torch.equal(dst[ii].view(torch.int16), xf[ii].view(torch.int16))
+    return st
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
+def test_full_size_sampled(name):
+    log(f"[parity] full size {name}")
+    x = workloads.make(name, "cuda")
+    st = sampled_full_size(name, x, workloads.METHODS[name], x.shape[-1])
+    log(f"[parity] full size {name}: n_out={st[0]}")
+    if name == "c2":
+        assert st[0] == 2 * x.shape[0]
+    del x
+    torch.cuda.empty_cache()
+
+
+def test_full_size_c5_one_layer_batch_sampled():
+    """One LLaMA-7B-shaped layer at its real shape through the batch entry point."""
+    methods, srcs, blobs, layouts, mds = [], [], [], [], []
+    for t, (tname, hidden, md) in enumerate(workloads.C5_LAYER):
+        x = workloads.c5_tensor(tname, "cuda", seed=5000 + t).view(-1)
+        n = x.numel()
+        m = adacc_method(md, workloads.outlier_capacity(md, n, hidden))
+        blob, L = (None, None) if md is None else adacc.alloc_blob(m, n)
+        methods.append(m); srcs.append(x); blobs.append(blob); layouts.append(L); mds.append(md)
+    ws = adacc.alloc_workspace(adacc.batch_workspace_bytes(methods, [s.numel() for s in srcs]))
+    log("[parity] c5 layer batch compress")
+    adacc.compress_batch(methods, srcs, blobs, ws)
+    torch.cuda.synchronize()
+    g = np.random.default_rng(7)
+    for x, m, blob, L, md in zip(srcs, methods, blobs, layouts, mds):
+        if md is None:
+            continue
+        st = adacc.read_status(blob, L)
+        assert st[1] == 0 and st[2] == 0
+        sec = adacc.blob_sections(blob, L, m, x.numel())
+        te = int(L.tile_elems)
+        om = oracle_method(md)
+        has_out = md["outlier_mode"] != "none"
+        tp = sec["tile_ptr"].cpu().numpy().view(np.uint32).astype(np.int64) if has_out else None
+        for t in sorted(set([0, L.n_tiles - 1] + g.integers(0, L.n_tiles, 8).tolist())):
+            lo, hi = t * te, min(x.numel(), (t + 1) * te)
+            oc = oracle.compress(om, bits_of(x[lo:hi]))
+            assert np.array_equal(sec["codes"][lo * md["bits"] // 8: hi * md["bits"] // 8].cpu().numpy(), oc.packed)
+            gq = md["quant_group"]
+            assert np.array_equal(sec["scales"][lo // gq: hi // gq].cpu().numpy().view(np.uint32), oc.scale.view(np.uint32))
+            if has_out:
+                p0, p1 = int(tp[t]), int(tp[t + 1])
+                assert p1 - p0 == oc.n_out
+                assert np.array_equal(sec["idx"][p0:p1].cpu().numpy().astype(np.int64), oc.out_idx.astype(np.int64) + lo)
