@@ -96,23 +96,38 @@ typedef struct adacc_layout {
 int adacc_layout_of(const adacc_method *method, uint64_t numel, adacc_layout *out);
 
 /* ---- workspace ----
- * Compression with outliers orders the outlier stream across tiles with a
- * single-pass chained scan; its per-tile state lives in a caller-owned device
- * workspace.  A workspace must be cleared once with adacc_workspace_init before
- * its first use; after that any number of compress calls may reuse it, one at a
- * time (calls that overlap on the GPU must use different workspaces). */
+ * Compression with outliers orders the outlier stream across tiles with a single-pass
+ * chained scan; its per-tile state (8 bytes per tile) lives in a caller-owned device
+ * buffer described by an adacc_workspace.  The struct is HOST memory owned by the caller;
+ * the library keeps its launch counter ("epoch") in it: state words written by earlier
+ * launches carry an older epoch and read as empty, so the buffer is cleared only by
+ * adacc_workspace_init and when the 30-bit epoch wraps, never per call.
+ * Rules: initialise once with adacc_workspace_init; afterwards any number of calls may
+ * reuse it, one at a time in stream order (calls that may overlap on the GPU, or host
+ * threads that call concurrently, must use different workspaces). */
+typedef struct adacc_workspace {
+  void *device_mem; /* caller-owned device buffer, 256-byte aligned            */
+  uint64_t bytes;   /* its size                                                */
+  uint32_t epoch;   /* launches since the last clear; maintained by the library */
+  uint32_t reserved;
+} adacc_workspace;
+
+/* Bytes of device memory a workspace needs for this tensor (0 for ADACC_OUTLIER_NONE / NOOP). */
 uint64_t adacc_workspace_bytes(const adacc_method *method, uint64_t numel);
-int adacc_workspace_init(void *workspace, uint64_t workspace_bytes, void *hip_stream);
+/* Fills *ws and enqueues the clearing of device_mem on hip_stream.
+ * Errors: ENULL, ESIZE (bytes < 256 or not a multiple of 16), EALIGN, EHIP. */
+int adacc_workspace_init(adacc_workspace *ws, void *device_mem, uint64_t bytes, void *hip_stream);
 
 /* ---- single tensor ----
  * adacc_compress: Section 3.2 / Fig. 3(c) compression workflow.
  *   src   numel bf16, 16-byte aligned, never modified (the zeroing of outliers happens in registers)
  *   blob  at least adacc_layout_of(...).total_bytes, 256-byte aligned
- *   workspace  at least adacc_workspace_bytes(...); may be NULL for ADACC_OUTLIER_NONE
+ *   ws    an initialised workspace of at least adacc_workspace_bytes(...); may be NULL for
+ *         ADACC_OUTLIER_NONE
  * numel == 0 or NOOP: returns ADACC_OK without touching anything.
  * Errors: ENULL, EINVAL, ESIZE, EALIGN, EHIP. */
 int adacc_compress(const adacc_method *method, const void *src, uint64_t numel, void *blob,
-                   uint64_t blob_bytes, void *workspace, uint64_t workspace_bytes, void *hip_stream);
+                   uint64_t blob_bytes, adacc_workspace *ws, void *hip_stream);
 
 /* adacc_decompress: Section 3.2 dequantisation (X^ = code*S, resp. code*S+O) followed by
  * the write-back of the outliers (Fig. 3(c) decompression workflow).
@@ -128,15 +143,15 @@ int adacc_decompress(const adacc_method *method, const void *blob, uint64_t blob
  * R_{i,t}: compress or retain) ----
  * methods[i], srcs[i], numels[i], blobs[i], blob_bytes[i] describe tensor i; NOOP entries
  * are skipped.  The workspace holds the scan state of all tensors plus a device copy of the
- * table (adacc_batch_workspace_bytes); same init/reuse rules as above.
+ * table (adacc_batch_workspace_bytes device bytes); same init/reuse rules as above.
  * adacc_decompress_batch restores every non-NOOP tensor i into dsts[i]. */
 uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method *methods, const uint64_t *numels);
 int adacc_compress_batch(uint32_t n, const adacc_method *methods, const void *const *srcs,
                          const uint64_t *numels, void *const *blobs, const uint64_t *blob_bytes,
-                         void *workspace, uint64_t workspace_bytes, void *hip_stream);
+                         adacc_workspace *ws, void *hip_stream);
 int adacc_decompress_batch(uint32_t n, const adacc_method *methods, const void *const *blobs,
                            const uint64_t *blob_bytes, const uint64_t *numels, void *const *dsts,
-                           int dst_dtype, void *workspace, uint64_t workspace_bytes, void *hip_stream);
+                           int dst_dtype, adacc_workspace *ws, void *hip_stream);
 
 /* Copies the 4 status words of a blob to host memory and waits for the stream:
  * the only call that synchronises.  (The outlier count is what the policy

@@ -39,6 +39,11 @@ class CLayout(ctypes.Structure):
                 ("tile_elems", ctypes.c_uint32), ("n_tiles", ctypes.c_uint32)]
 
 
+class CWorkspace(ctypes.Structure):
+    _fields_ = [("device_mem", ctypes.c_void_p), ("bytes", ctypes.c_uint64), ("epoch", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
+
+
 @dataclass
 class Method:
     kind: int = KIND_QUANT
@@ -83,18 +88,19 @@ def lib():
         L.adacc_layout_of.restype = ci
         L.adacc_workspace_bytes.argtypes = [pm, u64]
         L.adacc_workspace_bytes.restype = u64
-        L.adacc_workspace_init.argtypes = [vp, u64, vp]
+        pw = ctypes.POINTER(CWorkspace)
+        L.adacc_workspace_init.argtypes = [pw, vp, u64, vp]
         L.adacc_workspace_init.restype = ci
-        L.adacc_compress.argtypes = [pm, vp, u64, vp, u64, vp, u64, vp]
+        L.adacc_compress.argtypes = [pm, vp, u64, vp, u64, pw, vp]
         L.adacc_compress.restype = ci
         L.adacc_decompress.argtypes = [pm, vp, u64, u64, vp, ci, vp]
         L.adacc_decompress.restype = ci
         pvp, pu64 = ctypes.POINTER(vp), ctypes.POINTER(u64)
         L.adacc_batch_workspace_bytes.argtypes = [u32, pm, pu64]
         L.adacc_batch_workspace_bytes.restype = u64
-        L.adacc_compress_batch.argtypes = [u32, pm, pvp, pu64, pvp, pu64, vp, u64, vp]
+        L.adacc_compress_batch.argtypes = [u32, pm, pvp, pu64, pvp, pu64, pw, vp]
         L.adacc_compress_batch.restype = ci
-        L.adacc_decompress_batch.argtypes = [u32, pm, pvp, pu64, pu64, pvp, ci, vp, u64, vp]
+        L.adacc_decompress_batch.argtypes = [u32, pm, pvp, pu64, pu64, pvp, ci, pw, vp]
         L.adacc_decompress_batch.restype = ci
         L.adacc_read_status.argtypes = [vp, pl, vp, ctypes.POINTER(u32 * 4)]
         L.adacc_read_status.restype = ci
@@ -162,16 +168,29 @@ def batch_workspace_bytes(methods, numels) -> int:
 
 
 # ---------------------------------------------------------------- device calls
-def workspace_init(workspace, stream=None):
-    _check(lib().adacc_workspace_init(_ptr(workspace), _nbytes(workspace), _stream(stream)), "adacc_workspace_init")
+class Workspace:
+    """A scan workspace: the adacc_workspace struct plus the torch buffer it points to."""
+
+    def __init__(self, buffer, stream=None):
+        self.buffer = buffer  # keeps the device memory alive
+        self.c = CWorkspace()
+        _check(lib().adacc_workspace_init(ctypes.byref(self.c), _ptr(buffer), _nbytes(buffer), _stream(stream)),
+               "adacc_workspace_init")
+
+    @property
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def _ws(workspace):
+    return None if workspace is None else workspace.ref
 
 
 def compress(method: Method, src, blob, workspace=None, numel=None, stream=None):
     numel = src.numel() if numel is None else numel
     cm = method.c()
-    _check(lib().adacc_compress(ctypes.byref(cm), _ptr(src), numel, _ptr(blob), _nbytes(blob), _ptr(workspace),
-                                _nbytes(workspace) if workspace is not None else 0, _stream(stream)),
-           "adacc_compress")
+    _check(lib().adacc_compress(ctypes.byref(cm), _ptr(src), numel, _ptr(blob), _nbytes(blob), _ws(workspace),
+                                _stream(stream)), "adacc_compress")
 
 
 def decompress(method: Method, blob, dst, numel=None, stream=None):
@@ -198,7 +217,7 @@ def compress_batch(methods, srcs, blobs, workspace, stream=None):
     numels = [0 if s is None else s.numel() for s in srcs]
     n, cms, ps, cn, pb = _batch_args(methods, srcs, numels, blobs)
     bb = (ctypes.c_uint64 * n)(*[0 if b is None else _nbytes(b) for b in blobs])
-    _check(lib().adacc_compress_batch(n, cms, ps, cn, pb, bb, _ptr(workspace), _nbytes(workspace), _stream(stream)),
+    _check(lib().adacc_compress_batch(n, cms, ps, cn, pb, bb, _ws(workspace), _stream(stream)),
            "adacc_compress_batch")
 
 
@@ -211,8 +230,8 @@ def decompress_batch(methods, blobs, dsts, workspace, stream=None):
     if len(kinds) > 1:
         raise TypeError("all dsts of a batch share one dtype")
     dtype = DST_F32 if kinds == {torch.float32} else DST_BF16
-    _check(lib().adacc_decompress_batch(n, cms, pb, bb, cn, pd, dtype, _ptr(workspace), _nbytes(workspace),
-                                        _stream(stream)), "adacc_decompress_batch")
+    _check(lib().adacc_decompress_batch(n, cms, pb, bb, cn, pd, dtype, _ws(workspace), _stream(stream)),
+           "adacc_decompress_batch")
 
 
 def read_status(blob, layout: CLayout, stream=None):
@@ -235,12 +254,11 @@ def alloc_blob(method: Method, numel: int, device="cuda"):
     return torch.empty(max(int(L.total_bytes), 256), dtype=torch.uint8, device=device), L
 
 
-def alloc_workspace(nbytes: int, device="cuda", stream=None):
+def alloc_workspace(nbytes: int, device="cuda", stream=None) -> Workspace:
     """A cleared scan workspace of at least nbytes."""
     import torch
-    ws = torch.empty(max((int(nbytes) + 255) // 256 * 256, 512), dtype=torch.uint8, device=device)
-    workspace_init(ws, stream)
-    return ws
+    buf = torch.empty(max((int(nbytes) + 255) // 256 * 256, 512), dtype=torch.uint8, device=device)
+    return Workspace(buf, stream)
 
 
 def blob_sections(blob, layout: CLayout, method: Method, numel: int):

@@ -16,70 +16,20 @@ namespace adacc {
 
 // ===================================================================== kernels
 
-__device__ __forceinline__ uint32_t take_ticket(WsHeader* hdr) {
-  // one atomic per tile; lane 0 carries the result
-  uint32_t t = 0u;
-  if (__lane_id() == 0)
-    t = __hip_atomic_fetch_add(&hdr->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return t;
-}
-
-// Every wavefront calls this once when it has no more tiles.  The last one to arrive puts
-// the header back into its between-launches state and advances the epoch, which turns
-// every state word of this launch into "empty" for the next one without clearing memory.
-__device__ __forceinline__ void leave_scan(WsHeader* hdr, uint64_t* state) {
-  uint32_t last = 0u;
-  if (__lane_id() == 0) {
-    const uint32_t waves = gridDim.x * kWavesPerWg;
-    const uint32_t old = __hip_atomic_fetch_add(&hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    last = (old + 1u == waves) ? 1u : 0u;
-  }
-  last = __builtin_amdgcn_readfirstlane(last);
-  if (!last) return;
-  uint32_t e = __hip_atomic_load(&hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
-  if (e >= kEpochWrap) {  // once in ~10^9 launches: really clear the words and start over
-    const uint32_t cap = hdr->capacity;
-    for (uint32_t i = __lane_id(); i < cap; i += kWave)
-      __hip_atomic_store(&state[i], (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    e = 0u;
-  }
-  if (__lane_id() == 0) {
-    __hip_atomic_store(&hdr->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&hdr->done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&hdr->epoch, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
-__device__ __forceinline__ ScanCtx open_scan(WsHeader* hdr, uint64_t* state, uint32_t spin_limit) {
-  ScanCtx sc;
-  sc.hdr = hdr;
-  sc.state = state;
-  sc.spin_limit = spin_limit;
-  const uint32_t e = __hip_atomic_load(&hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  sc.tag = (e + 1u) << 2;
-  return sc;
-}
-
-// ---- single tensor, compress.  Outlier modes: persistent wavefronts pull tiles from the
-// ticket counter (tile order = ticket order, which the chained scan needs).  NONE: tiles
-// are independent, plain grid-stride loop, workspace untouched.
+// ---- single tensor, compress: one tile per wavefront, tile = 4 * workgroup + wavefront.
+// With outliers the grid is exactly ceil(n_tiles / 4) workgroups: the chained scan relies on
+// tiles being started in index order.  NONE: tiles are independent, grid-stride loop.
 template <int MODE, int BITS, bool ASYM, int E>
-__global__ __launch_bounds__(kThreads) void compress_kernel(TensorDesc d, WsHeader* hdr, uint64_t* state,
+__global__ __launch_bounds__(kThreads) void compress_kernel(TensorDesc d, uint64_t* state, uint32_t tag,
                                                             uint32_t spin_limit) {
   const uint32_t wave = threadIdx.x / kWave;
+  const ScanCtx sc{state, tag, spin_limit};
   if constexpr (MODE == kModeNone) {
-    ScanCtx sc{};
     for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
       compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
   } else {
-    const ScanCtx sc = open_scan(hdr, state, spin_limit);
-    uint32_t t = __builtin_amdgcn_readfirstlane(take_ticket(hdr));
-    while (t < d.n_tiles) {
-      const uint32_t next = take_ticket(hdr);  // in flight while this tile is processed
-      compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
-      t = __builtin_amdgcn_readfirstlane(next);
-    }
-    leave_scan(hdr, state);
+    const uint32_t t = blockIdx.x * kWavesPerWg + wave;
+    if (t < d.n_tiles) compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
   }
 }
 
@@ -117,24 +67,20 @@ __device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint
 }
 
 __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                  uint32_t total_tiles, WsHeader* hdr,
-                                                                  uint64_t* state, uint32_t spin_limit) {
-  const ScanCtx sc = open_scan(hdr, state, spin_limit);
-  uint32_t g = __builtin_amdgcn_readfirstlane(take_ticket(hdr));
-  while (g < total_tiles) {
-    const uint32_t next = take_ticket(hdr);
-    const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor(table, n, g));
-    const TensorDesc d = table[ti];
-    const uint32_t tile = g - d.first_tile;
-    switch (d.variant >> 3) {
-      case kModeNone: compress_dispatch_mode<kModeNone>(d, tile, sc); break;
-      case kModeAbs: compress_dispatch_mode<kModeAbs>(d, tile, sc); break;
-      case kModeStd: compress_dispatch_mode<kModeStd>(d, tile, sc); break;
-      default: compress_dispatch_mode<kModeTopk>(d, tile, sc); break;
-    }
-    g = __builtin_amdgcn_readfirstlane(next);
+                                                                  uint32_t total_tiles, uint64_t* state,
+                                                                  uint32_t tag, uint32_t spin_limit) {
+  const ScanCtx sc{state, tag, spin_limit};
+  const uint32_t g = blockIdx.x * kWavesPerWg + threadIdx.x / kWave;
+  if (g >= total_tiles) return;
+  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor(table, n, g));
+  const TensorDesc d = table[ti];
+  const uint32_t tile = g - d.first_tile;
+  switch (d.variant >> 3) {
+    case kModeNone: compress_dispatch_mode<kModeNone>(d, tile, sc); break;
+    case kModeAbs: compress_dispatch_mode<kModeAbs>(d, tile, sc); break;
+    case kModeStd: compress_dispatch_mode<kModeStd>(d, tile, sc); break;
+    default: compress_dispatch_mode<kModeTopk>(d, tile, sc); break;
   }
-  leave_scan(hdr, state);
 }
 
 template <bool F32>
@@ -162,11 +108,11 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
 }
 
 // ---- utilities
-// clears a workspace; the first 16 bytes are the header words {epoch, ticket, done, capacity}
-__global__ __launch_bounds__(kThreads) void workspace_clear_kernel(uint4* p, uint64_t n16, uint32_t capacity) {
+// clears a workspace (a kernel rather than a memset node, so that callers may capture it in a graph)
+__global__ __launch_bounds__(kThreads) void workspace_clear_kernel(uint4* p, uint64_t n16) {
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-    p[i] = make_uint4(0, 0, 0, i == 0 ? capacity : 0u);
+    p[i] = make_uint4(0, 0, 0, 0);
 }
 
 __global__ __launch_bounds__(kThreads) void hbm_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
@@ -298,6 +244,7 @@ static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<ui
 
 static uint32_t spin_limit() { return (uint32_t)env_int("ADACC_SPIN_LIMIT", 1 << 22); }
 
+// Grid for kernels whose tiles are independent (grid-stride loop, capped per CU).
 static int grid_for(uint32_t n_tiles, uint32_t* grid) {
   int cus = 0;
   const int rc = device_cus(&cus);
@@ -309,7 +256,7 @@ static int grid_for(uint32_t n_tiles, uint32_t* grid) {
   return ADACC_OK;
 }
 
-typedef void (*CompressFn)(TensorDesc, WsHeader*, uint64_t*, uint32_t);
+typedef void (*CompressFn)(TensorDesc, uint64_t*, uint32_t, uint32_t);
 typedef void (*DecompressFn)(TensorDesc, uint32_t);
 
 template <int MODE, int BITS, bool ASYM>
@@ -339,12 +286,35 @@ static DecompressFn decompress_fn(const adacc_method* m, bool e8, bool f32) {
   return m->asym ? decompress_fn_e<8, true>(e8, f32) : decompress_fn_e<8, false>(e8, f32);
 }
 
+static int clear_device(void* mem, uint64_t bytes, hipStream_t s);
+
+// Next epoch of a workspace; clears the buffer first when the counter is about to wrap.
+static int next_tag(adacc_workspace* ws, hipStream_t s, uint32_t* tag) {
+  if (ws->epoch >= kEpochMax) {
+    const int rc = clear_device(ws->device_mem, ws->bytes, s);
+    if (rc != ADACC_OK) return rc;
+    ws->epoch = 0;
+  }
+  ws->epoch += 1;
+  *tag = ws->epoch << 2;
+  return ADACC_OK;
+}
+
 static int launch_check(const char* what) {
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? ADACC_OK : hip_fail(e, what);
 }
 
-// batch workspace: [header 256][state 8*total_tiles, padded][table n*sizeof(TensorDesc)]
+static int clear_device(void* mem, uint64_t bytes, hipStream_t s) {
+  const uint64_t n16 = bytes / 16;
+  uint32_t grid = (uint32_t)((n16 + kThreads - 1) / kThreads);
+  if (grid > 4096) grid = 4096;
+  if (grid == 0) return ADACC_OK;
+  hipLaunchKernelGGL(workspace_clear_kernel, dim3(grid), dim3(kThreads), 0, s, static_cast<uint4*>(mem), n16);
+  return launch_check("workspace_clear_kernel");
+}
+
+// batch workspace: [state 8*total_tiles, padded][table n*sizeof(TensorDesc)]
 struct BatchPlan {
   uint32_t total_tiles;
   uint64_t table_off, bytes;
@@ -352,7 +322,7 @@ struct BatchPlan {
 static BatchPlan batch_plan(uint32_t total_tiles, uint32_t n_active) {
   BatchPlan b;
   b.total_tiles = total_tiles;
-  b.table_off = align256(sizeof(WsHeader) + 8ull * total_tiles);
+  b.table_off = align256(8ull * total_tiles);
   b.bytes = align256(b.table_off + (uint64_t)(n_active ? n_active : 1) * sizeof(TensorDesc));
   return b;
 }
@@ -392,27 +362,24 @@ uint64_t adacc_workspace_bytes(const adacc_method* method, uint64_t numel) {
   if (!method) return 0;
   Plan p;
   if (make_plan(method, numel, &p) != ADACC_OK || p.noop || !p.outliers) return 0;
-  return align256(sizeof(WsHeader) + 8ull * p.n_tiles);
+  return align256(8ull * p.n_tiles);
 }
 
-int adacc_workspace_init(void* workspace, uint64_t workspace_bytes, void* hip_stream) {
-  if (!workspace) return ADACC_ENULL;
-  if (workspace_bytes < sizeof(WsHeader) + 8 || workspace_bytes % 16 != 0) return ADACC_ESIZE;
-  if (misaligned(workspace, 256)) return ADACC_EALIGN;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const uint64_t n16 = workspace_bytes / 16;
-  uint32_t grid = (uint32_t)((n16 + kThreads - 1) / kThreads);
-  if (grid > 4096) grid = 4096;
-  // capacity = the number of state words that are now known to be clear
-  const uint64_t words = (workspace_bytes - sizeof(WsHeader)) / 8;
-  const uint32_t capacity = words > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)words;
-  hipLaunchKernelGGL(workspace_clear_kernel, dim3(grid), dim3(kThreads), 0, s, static_cast<uint4*>(workspace), n16,
-                     capacity);
-  return launch_check("workspace_clear_kernel");
+int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, void* hip_stream) {
+  if (!ws || !device_mem) return ADACC_ENULL;
+  if (bytes < 256 || bytes % 16 != 0) return ADACC_ESIZE;
+  if (misaligned(device_mem, 256)) return ADACC_EALIGN;
+  const int rc = clear_device(device_mem, bytes, static_cast<hipStream_t>(hip_stream));
+  if (rc != ADACC_OK) return rc;
+  ws->device_mem = device_mem;
+  ws->bytes = bytes;
+  ws->epoch = 0;
+  ws->reserved = 0;
+  return ADACC_OK;
 }
 
 int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
-                   void* workspace, uint64_t workspace_bytes, void* hip_stream) {
+                   adacc_workspace* ws, void* hip_stream) {
   if (!method) return ADACC_ENULL;
   Plan p;
   int rc = make_plan(method, numel, &p);
@@ -424,19 +391,27 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(src, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   if (p.outliers) {
-    if (!workspace) return ADACC_ENULL;
-    if (workspace_bytes < align256(sizeof(WsHeader) + 8ull * p.n_tiles)) return ADACC_ESIZE;
-    if (misaligned(workspace, 256)) return ADACC_EALIGN;
+    if (!ws || !ws->device_mem) return ADACC_ENULL;
+    if (ws->bytes < 8ull * p.n_tiles) return ADACC_ESIZE;
+    if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   }
   TensorDesc d;
   fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, &d);
-  uint32_t grid = 0;
-  rc = grid_for(p.n_tiles, &grid);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  uint32_t grid = 0, tag = 0;
+  if (p.outliers) {
+    grid = (p.n_tiles + kWavesPerWg - 1) / kWavesPerWg;  // tiles start in index order: no grid-stride loop
+    int cus = 0;
+    rc = device_cus(&cus);                               // also: fail here rather than in the launch without a device
+    if (rc != ADACC_OK) return rc;
+    rc = next_tag(ws, s, &tag);
+  } else {
+    rc = grid_for(p.n_tiles, &grid);
+  }
   if (rc != ADACC_OK) return rc;
-  WsHeader* hdr = static_cast<WsHeader*>(workspace);
-  uint64_t* state = workspace ? reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(workspace) + sizeof(WsHeader)) : nullptr;
   CompressFn fn = compress_fn(method, p.tile_elems == 4096);
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, hdr, state, spin_limit());
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d,
+                     p.outliers ? static_cast<uint64_t*>(ws->device_mem) : nullptr, tag, spin_limit());
   return launch_check("compress_kernel");
 }
 
@@ -512,8 +487,7 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
 }
 
 int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* const* srcs, const uint64_t* numels,
-                         void* const* blobs, const uint64_t* blob_bytes, void* workspace, uint64_t workspace_bytes,
-                         void* hip_stream) {
+                         void* const* blobs, const uint64_t* blob_bytes, adacc_workspace* ws, void* hip_stream) {
   if (n == 0) return ADACC_OK;
   if (!methods || !srcs || !numels || !blobs || !blob_bytes) return ADACC_ENULL;
   std::vector<Plan> plans;
@@ -521,30 +495,34 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   int rc = batch_prepare(n, methods, numels, &plans, &total, &act);
   if (rc != ADACC_OK) return rc;
   if (act == 0) return ADACC_OK;
-  if (!workspace) return ADACC_ENULL;
+  if (!ws || !ws->device_mem) return ADACC_ENULL;
   const BatchPlan bp = batch_plan(total, act);
-  if (workspace_bytes < bp.bytes) return ADACC_ESIZE;
-  if (misaligned(workspace, 256)) return ADACC_EALIGN;
+  if (ws->bytes < bp.bytes) return ADACC_ESIZE;
+  if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   std::vector<TensorDesc> table;
   rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, &table);
   if (rc != ADACC_OK) return rc;
-  uint32_t grid = 0;
-  rc = grid_for(total, &grid);
+  int cus = 0;
+  rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  const hipError_t e = hipMemcpyAsync(ws + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
+  uint32_t tag = 0;
+  rc = next_tag(ws, s, &tag);
+  if (rc != ADACC_OK) return rc;
+  unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
+  const hipError_t e = hipMemcpyAsync(mem + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
                                       hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
+  const uint32_t grid = (total + kWavesPerWg - 1) / kWavesPerWg;
   hipLaunchKernelGGL(compress_batch_kernel, dim3(grid), dim3(kThreads), 0, s,
-                     reinterpret_cast<const TensorDesc*>(ws + bp.table_off), (uint32_t)table.size(), total,
-                     reinterpret_cast<WsHeader*>(ws), reinterpret_cast<uint64_t*>(ws + sizeof(WsHeader)), spin_limit());
+                     reinterpret_cast<const TensorDesc*>(mem + bp.table_off), (uint32_t)table.size(), total,
+                     reinterpret_cast<uint64_t*>(mem), tag, spin_limit());
   return launch_check("compress_batch_kernel");
 }
 
 int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* const* blobs, const uint64_t* blob_bytes,
-                           const uint64_t* numels, void* const* dsts, int dst_dtype, void* workspace,
-                           uint64_t workspace_bytes, void* hip_stream) {
+                           const uint64_t* numels, void* const* dsts, int dst_dtype, adacc_workspace* ws,
+                           void* hip_stream) {
   if (n == 0) return ADACC_OK;
   if (!methods || !blobs || !numels || !dsts || !blob_bytes) return ADACC_ENULL;
   if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
@@ -553,10 +531,10 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   int rc = batch_prepare(n, methods, numels, &plans, &total, &act);
   if (rc != ADACC_OK) return rc;
   if (act == 0) return ADACC_OK;
-  if (!workspace) return ADACC_ENULL;
+  if (!ws || !ws->device_mem) return ADACC_ENULL;
   const BatchPlan bp = batch_plan(total, act);
-  if (workspace_bytes < bp.bytes) return ADACC_ESIZE;
-  if (misaligned(workspace, 256)) return ADACC_EALIGN;
+  if (ws->bytes < bp.bytes) return ADACC_ESIZE;
+  if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   std::vector<TensorDesc> table;
   rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
                    false, &table);
@@ -565,11 +543,11 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   rc = grid_for(total, &grid);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  unsigned char* ws = static_cast<unsigned char*>(workspace);
-  const hipError_t e = hipMemcpyAsync(ws + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
+  unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
+  const hipError_t e = hipMemcpyAsync(mem + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
                                       hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
-  const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(ws + bp.table_off);
+  const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
   if (dst_dtype == ADACC_DST_F32)
     hipLaunchKernelGGL(decompress_batch_kernel<true>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
   else

@@ -48,19 +48,12 @@ struct TensorDesc {
   uint32_t dst_f32;     // decompress: 1 = binary32 output
 };
 
-// Head of a scan workspace (256 bytes), followed by one 64-bit state word per tile.
-struct WsHeader {
-  uint32_t epoch;     // completed launches; state words of other epochs read as empty
-  uint32_t ticket;    // next tile to hand out (0 between launches)
-  uint32_t done;      // wavefronts that have left the kernel (0 between launches)
-  uint32_t capacity;  // state words that were cleared by adacc_workspace_init
-  uint32_t pad[60];
-};
-static_assert(sizeof(WsHeader) == 256, "header is one 256-byte block");
-
-// State word: high half = (epoch_tag << 2) | flag, low half = value.
+// Scan workspace: one 64-bit state word per tile, high half = (epoch << 2) | flag, low half =
+// value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
+// words written by earlier launches carry another epoch and read as empty, so the buffer is
+// cleared only once, when it is set up, and again when the 30-bit epoch wraps.
 enum : uint32_t { kFlagEmpty = 0, kFlagAggregate = 1, kFlagPrefix = 2, kFlagAbort = 3 };
-constexpr uint32_t kEpochWrap = 0x3FFFFFF0u;
+constexpr uint32_t kEpochMax = 0x3FFFFFFFu;
 
 // variant index: ((mode*2 + (bits==8)) * 2 + asym) * 2 + (E==8)
 __host__ __device__ inline uint32_t variant_index(uint32_t mode, uint32_t bits, uint32_t asym, uint32_t e8) {

@@ -93,9 +93,8 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 
 // ------------------------------------------------------------------ chained scan across tiles
 struct ScanCtx {
-  WsHeader* hdr;
   uint64_t* state;
-  uint32_t tag;         // (epoch+1) << 2
+  uint32_t tag;         // epoch << 2
   uint32_t spin_limit;  // polls before a wavefront gives up
 };
 
@@ -106,21 +105,24 @@ __device__ __forceinline__ void st_state(uint64_t* p, uint32_t hi, uint32_t lo) 
   __hip_atomic_store(p, ((uint64_t)hi << 32) | lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Exclusive prefix of `count` over the tiles first..gtile-1 (single-pass scan with
-// decoupled look-back: publish the own aggregate, then walk back over 64 predecessors at
-// a time, one per lane, until a tile that already knows its inclusive prefix is met).
-// Tile ids come from a ticket counter, so every predecessor is owned by a wavefront that
-// is already running: the wait always ends.  The poll bound is a second line of defence;
-// when it trips the tile publishes "abort", which every later tile inherits at once.
-__device__ __forceinline__ uint32_t chained_scan(const ScanCtx& sc, uint32_t gtile, uint32_t first,
+// Single-pass scan of the per-tile outlier counts with decoupled look-back, one tile per
+// wavefront.  scan_publish makes the tile's own count visible as early as possible;
+// scan_resolve walks back over 64 predecessors at a time, one per lane, adding their counts
+// until it meets a tile that already knows its inclusive prefix, then publishes its own.
+// Tiles are numbered in launch order (workgroup index, wavefront index), and a tile only ever
+// waits for lower-numbered ones, which the hardware has dispatched earlier.  The poll bound is
+// a second line of defence: when it trips, the tile publishes "abort", which every later tile
+// inherits at once, so the kernel always drains and reports the failure in the status words.
+__device__ __forceinline__ void scan_publish(const ScanCtx& sc, uint32_t gtile, uint32_t first, uint32_t count) {
+  if (lane_id() == 0)
+    st_state(&sc.state[gtile], sc.tag | (gtile == first ? kFlagPrefix : kFlagAggregate), count);
+}
+
+__device__ __forceinline__ uint32_t scan_resolve(const ScanCtx& sc, uint32_t gtile, uint32_t first,
                                                  uint32_t count, bool& aborted) {
   const int lane = lane_id();
   aborted = false;
-  if (gtile == first) {
-    if (lane == 0) st_state(&sc.state[gtile], sc.tag | kFlagPrefix, count);
-    return 0;
-  }
-  if (lane == 0) st_state(&sc.state[gtile], sc.tag | kFlagAggregate, count);
+  if (gtile == first) return 0;
   uint32_t excl = 0;
   int64_t top = (int64_t)gtile - 1;
   while (true) {
@@ -279,6 +281,36 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
   for (int j = 0; j < E; ++j)
     if (lane_base + (uint64_t)j * kRow >= d.numel) mask[j] = 0u;
 
+  // ---- a4 (first half): count the outliers and publish the tile's count before the long
+  // quantise / store phase, so that later tiles rarely have to wait for it
+  constexpr int W = E / 2;
+  uint32_t cnt[E], lane_excl[E], row_off[E];
+  uint32_t total = 0u;
+  if constexpr (MODE != kModeNone) {
+    // inclusive scan over lanes of the per-row counts, two rows per 32-bit word
+    uint32_t packed[W];
+#pragma unroll
+    for (int j = 0; j < E; ++j) cnt[j] = __popc(mask[j]);
+#pragma unroll
+    for (int w = 0; w < W; ++w) packed[w] = cnt[2 * w] | (cnt[2 * w + 1] << 16);
+#pragma unroll
+    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) {
+        const uint32_t t = __shfl_up(packed[w], dlt);
+        packed[w] += (lane >= dlt) ? t : 0u;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t incl = (packed[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu;
+      lane_excl[j] = incl - cnt[j];
+      row_off[j] = total;
+      total += __shfl(incl, kWave - 1);
+    }
+    scan_publish(sc, d.first_tile + tile, d.first_tile, total);
+  }
+
   // ---- a5 + a6: inlier view and per-group scale (and offset)
   float y[E][kOct];
 #pragma unroll
@@ -361,35 +393,10 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
     }
   }
 
-  // ---- a4: ordered compaction of the outliers
+  // ---- a4 (second half): resolve the tile's offset in the stream and append its outliers
   if constexpr (MODE != kModeNone) {
-    // inclusive scan over lanes of the per-row counts, two rows per 32-bit word
-    constexpr int W = E / 2;
-    uint32_t cnt[E], packed[W];
-#pragma unroll
-    for (int j = 0; j < E; ++j) cnt[j] = __popc(mask[j]);
-#pragma unroll
-    for (int w = 0; w < W; ++w) packed[w] = cnt[2 * w] | (cnt[2 * w + 1] << 16);
-#pragma unroll
-    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
-#pragma unroll
-      for (int w = 0; w < W; ++w) {
-        const uint32_t t = __shfl_up(packed[w], dlt);
-        packed[w] += (lane >= dlt) ? t : 0u;
-      }
-    }
-    uint32_t lane_excl[E], row_off[E];
-    uint32_t total = 0u;
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const uint32_t incl = (packed[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu;
-      lane_excl[j] = incl - cnt[j];
-      row_off[j] = total;
-      total += __shfl(incl, kWave - 1);
-    }
-
     bool aborted;
-    const uint32_t base = chained_scan(sc, d.first_tile + tile, d.first_tile, total, aborted);
+    const uint32_t base = scan_resolve(sc, d.first_tile + tile, d.first_tile, total, aborted);
 
     if (lane == 0) {
       d.tile_ptr[tile] = base;

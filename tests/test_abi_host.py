@@ -36,6 +36,7 @@ def test_every_declared_symbol_is_exported(L):
 def test_struct_sizes_match_the_header(L):
     assert ctypes.sizeof(adacc.CMethod) == 40
     assert ctypes.sizeof(adacc.CLayout) == 72
+    assert ctypes.sizeof(adacc.CWorkspace) == 24
 
 
 def test_layout_closed_form(L):
@@ -62,7 +63,7 @@ def test_layout_closed_form(L):
     # no-op: nothing
     lay0 = adacc.layout_of(adacc.NOOP, 12345)
     assert lay0.total_bytes == 0 and lay0.n_tiles == 0
-    assert adacc.workspace_bytes(m, n) == a(256 + 8 * 37)
+    assert adacc.workspace_bytes(m, n) == a(8 * 37)
     assert adacc.workspace_bytes(m3, 64 * 33) == 0
 
 
@@ -108,29 +109,39 @@ def test_errors_are_returned_before_any_device_work(L):
     n = 4096
     lay = adacc.layout_of(m, n)
     cm = m.c()
-    src, blob, ws = 0x10000, 0x20000, 0x30000
+    src, blob = 0x10000, 0x20000
+    ws = adacc.CWorkspace(0x30000, 4096, 0, 0)
+    small = adacc.CWorkspace(0x30000, 8, 0, 0)
+    empty = adacc.CWorkspace(None, 4096, 0, 0)
+    odd = adacc.CWorkspace(0x30010, 4096, 0, 0)
+    w = ctypes.byref(ws)
     f = L.adacc_compress
-    assert f(None, src, n, blob, lay.total_bytes, ws, 4096, None) == adacc.ENULL
-    assert f(ctypes.byref(cm), None, n, blob, lay.total_bytes, ws, 4096, None) == adacc.ENULL
-    assert f(ctypes.byref(cm), src, n, None, lay.total_bytes, ws, 4096, None) == adacc.ENULL
-    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, None, 0, None) == adacc.ENULL
-    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes - 1, ws, 4096, None) == adacc.ESIZE
-    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, ws, 8, None) == adacc.ESIZE
-    assert f(ctypes.byref(cm), src + 2, n, blob, lay.total_bytes, ws, 4096, None) == adacc.EALIGN
-    assert f(ctypes.byref(cm), src, n, blob + 16, lay.total_bytes, ws, 4096, None) == adacc.EALIGN
-    assert f(ctypes.byref(cm), src, n + 1, blob, lay.total_bytes, ws, 4096, None) == adacc.EINVAL
+    assert f(None, src, n, blob, lay.total_bytes, w, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), None, n, blob, lay.total_bytes, w, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, None, lay.total_bytes, w, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, None, None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, ctypes.byref(empty), None) == adacc.ENULL
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes - 1, w, None) == adacc.ESIZE
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, ctypes.byref(small), None) == adacc.ESIZE
+    assert f(ctypes.byref(cm), src + 2, n, blob, lay.total_bytes, w, None) == adacc.EALIGN
+    assert f(ctypes.byref(cm), src, n, blob + 16, lay.total_bytes, w, None) == adacc.EALIGN
+    assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, ctypes.byref(odd), None) == adacc.EALIGN
+    assert f(ctypes.byref(cm), src, n + 1, blob, lay.total_bytes, w, None) == adacc.EINVAL
+    assert ws.epoch == 0  # a rejected call does not consume an epoch
     # nothing to do: OK without looking at the pointers
-    assert f(ctypes.byref(cm), None, 0, None, 0, None, 0, None) == adacc.OK
+    assert f(ctypes.byref(cm), None, 0, None, 0, None, None) == adacc.OK
     noop = adacc.NOOP.c()
-    assert f(ctypes.byref(noop), None, n, None, 0, None, 0, None) == adacc.OK
+    assert f(ctypes.byref(noop), None, n, None, 0, None, None) == adacc.OK
     g = L.adacc_decompress
     assert g(ctypes.byref(cm), blob, lay.total_bytes, n, None, 0, None) == adacc.ENULL
     assert g(ctypes.byref(cm), blob, lay.total_bytes, n, 0x40000, 2, None) == adacc.EINVAL
     assert g(ctypes.byref(cm), blob, lay.total_bytes - 1, n, 0x40000, 0, None) == adacc.ESIZE
     assert g(ctypes.byref(cm), blob, lay.total_bytes, n, 0x40002, 0, None) == adacc.EALIGN
     assert L.adacc_hbm_copy(0x10000, 0x20000, 24, None) == adacc.EINVAL
-    assert L.adacc_workspace_init(None, 4096, None) == adacc.ENULL
-    assert L.adacc_workspace_init(0x10000, 8, None) == adacc.ESIZE
+    assert L.adacc_workspace_init(None, 0x10000, 4096, None) == adacc.ENULL
+    assert L.adacc_workspace_init(w, None, 4096, None) == adacc.ENULL
+    assert L.adacc_workspace_init(w, 0x10000, 8, None) == adacc.ESIZE
+    assert L.adacc_workspace_init(w, 0x10010, 4096, None) == adacc.EALIGN
 
 
 def test_batch_validation(L):
@@ -140,7 +151,7 @@ def test_batch_validation(L):
     need = adacc.batch_workspace_bytes(ms, numels)
     tiles = 5 + (128 * 100 + 2047) // 2048
     a = lambda v: (v + 255) // 256 * 256
-    assert need >= a(256 + 8 * tiles) + 2 * 128
+    assert need >= a(8 * tiles) + 2 * 128
     n = 3
     cms = (adacc.CMethod * n)(*[m.c() for m in ms])
     cn = (ctypes.c_uint64 * n)(*numels)
@@ -149,14 +160,17 @@ def test_batch_validation(L):
     bb = (ctypes.c_uint64 * n)(adacc.layout_of(ms[0], numels[0]).total_bytes, 0,
                                adacc.layout_of(ms[2], numels[2]).total_bytes)
     f = L.adacc_compress_batch
-    assert f(n, cms, srcs, cn, blobs, bb, 0x300000, need - 256, None) == adacc.ESIZE
-    assert f(n, cms, srcs, cn, blobs, bb, None, need, None) == adacc.ENULL
+    ws = adacc.CWorkspace(0x300000, need, 0, 0)
+    small = adacc.CWorkspace(0x300000, need - 256, 0, 0)
+    assert f(n, cms, srcs, cn, blobs, bb, ctypes.byref(small), None) == adacc.ESIZE
+    assert f(n, cms, srcs, cn, blobs, bb, None, None) == adacc.ENULL
     bb[2] -= 1
-    assert f(n, cms, srcs, cn, blobs, bb, 0x300000, need, None) == adacc.ESIZE
+    assert f(n, cms, srcs, cn, blobs, bb, ctypes.byref(ws), None) == adacc.ESIZE
     bb[2] += 1
     srcs[0] = None
-    assert f(n, cms, srcs, cn, blobs, bb, 0x300000, need, None) == adacc.ENULL
-    assert f(0, None, None, None, None, None, None, 0, None) == adacc.OK
+    assert f(n, cms, srcs, cn, blobs, bb, ctypes.byref(ws), None) == adacc.ENULL
+    assert f(0, None, None, None, None, None, None, None) == adacc.OK
+    assert ws.epoch == 0
 
 
 def test_strerror_and_version(L):

@@ -153,7 +153,7 @@ def test_many_tiles_chained_scan():
 def test_deterministic_and_workspace_reuse():
     """One workspace, many calls of different sizes and methods: every blob equals the oracle's,
     and repeated calls give identical bytes."""
-    ws = adacc.alloc_workspace(256 + 8 * 4096)
+    ws = adacc.alloc_workspace(8 * 4096)
     cases = [(2048 * 700 + 64, dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=2.5, topk=0)),
              (4096 * 9, dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=4096, thresh=0.0, topk=4)),
              (2048 * 3, dict(bits=8, quant_group=2048, asym=1, outlier_mode="abs", stat_group=0, thresh=2.0, topk=0)),
@@ -183,6 +183,27 @@ def test_deterministic_and_workspace_reuse():
             assert torch.equal(sec_a["idx"][:oc.n_out], sec_b["idx"][:oc.n_out])
             assert torch.equal(sec_a["val"][:oc.n_out], sec_b["val"][:oc.n_out])
             assert used <= L.total_bytes
+
+
+def test_epoch_wrap_clears_the_workspace():
+    """The launch counter of a workspace is 30 bits wide: at the wrap the library clears the state
+    words and starts over.  Force the wrap from the host and check parity on both sides of it."""
+    n = 2048 * 300
+    md = dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=256, thresh=3.0, topk=0)
+    b = random_bits(31, n)
+    oc = oracle.compress(oracle_method(md), b)
+    oc._full_idx = oc.out_idx.astype(np.int64)
+    m = adacc_method(md, max(oc.n_out, 1))
+    x = from_bits(b, "cuda")
+    ws = adacc.alloc_workspace(adacc.workspace_bytes(m, n))
+    for start in (0x3FFFFFFD, None, None, None):
+        if start is not None:
+            ws.c.epoch = start
+        log(f"[parity] epoch before call = {ws.c.epoch:#x}")
+        blob, L, _ = gpu_compress(x, m, ws=ws)
+        torch.cuda.synchronize()
+        compare_blob_with_oracle(blob, L, m, n, oc)
+    assert ws.c.epoch == 2  # 0x3FFFFFFE, 0x3FFFFFFF, then cleared: 1, 2
 
 
 # ------------------------------------------------------------------ batch
