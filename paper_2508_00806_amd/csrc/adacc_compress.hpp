@@ -1,6 +1,12 @@
 // Compression of one tile by one wavefront (Section 3.2, Fig. 3(c) compression workflow):
 // load -> statistics -> outlier mask -> zero the outliers -> group scale (Eq. 2 / Eq. 3)
 // -> quantise, pack, store -> ordered append of the outliers to the (index, value) stream.
+//
+// The kernel is bound by vector-ALU issue as much as by HBM (about 20 lane-operations per
+// element are affordable at 70 % of peak bandwidth), so the common case - a row of 512
+// elements without any outlier - is kept to the operations that can not be avoided, and
+// everything that only matters when outliers are present sits behind wavefront-uniform
+// branches.
 #pragma once
 
 #include <type_traits>
@@ -33,13 +39,45 @@ struct OpAdd { __device__ __forceinline__ float operator()(float a, float b) con
 struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
 struct OpMin { __device__ __forceinline__ float operator()(float a, float b) const { return fminf(a, b); } };
 struct OpUMax { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; } };
+struct OpIMax { __device__ __forceinline__ int32_t operator()(int32_t a, int32_t b) const { return a > b ? a : b; } };
+struct OpIMin { __device__ __forceinline__ int32_t operator()(int32_t a, int32_t b) const { return a < b ? a : b; } };
 
-// xor butterfly over `lanes` adjacent lanes (power of two).  Every lane of a group ends
-// with the same value, and for sums the association is the balanced binary tree over
-// lane order, which is what makes the variance independent of the machine.
+// Order-preserving map between finite floats and signed integers (and back: it is its own
+// inverse).  Cross-lane max / min run on these integers: the integer instructions take the
+// DPP lane permute as an operand, while a float max would first have to quiet a possible NaN.
+__device__ __forceinline__ int32_t float_key(float f) {
+  const int32_t u = (int32_t)__float_as_uint(f);
+  return u ^ ((u >> 31) & 0x7FFFFFFF);
+}
+__device__ __forceinline__ float key_float(int32_t k) {
+  return __uint_as_float((uint32_t)(k ^ ((k >> 31) & 0x7FFFFFFF)));
+}
+
+// value of the partner lane of one xor-butterfly step.  Steps 1..8 are DPP lane permutes
+// (they fuse into the arithmetic instruction); 16 and 32 go through the LDS crossbar.
+// row_half_mirror / row_mirror stand in for xor 4 / xor 8: after the lower steps every
+// value is uniform within its 4 resp. 8 lanes, so reversing the order is the same exchange.
+template <int CTRL, class T>
+__device__ __forceinline__ T dpp_move(T v) {
+  const int i = __builtin_bit_cast(int, v);
+  return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(i, i, CTRL, 0xF, 0xF, true));
+}
+template <class T>
+__device__ __forceinline__ T swap16(T v) {  // lane ^ 16
+  return __builtin_bit_cast(T, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+}
+
+// all-reduce over `lanes` adjacent lanes (power of two) by xor butterfly, masks 1, 2, 4, ...
+// For sums the association is the balanced binary tree over lane order, which is what makes
+// the variance a function of the input bits alone.
 template <class T, class Op>
 __device__ __forceinline__ T lanes_reduce(T v, int lanes, Op op) {
-  for (int m = 1; m < lanes; m <<= 1) v = op(v, __shfl_xor(v, m));
+  if (lanes > 1) v = op(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+  if (lanes > 2) v = op(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+  if (lanes > 4) v = op(v, dpp_move<0x141>(v));  // row_half_mirror
+  if (lanes > 8) v = op(v, dpp_move<0x140>(v));  // row_mirror
+  if (lanes > 16) v = op(v, swap16(v));
+  if (lanes > 32) v = op(v, __shfl_xor(v, 32));
   return v;
 }
 
@@ -84,11 +122,32 @@ __device__ __forceinline__ void groups_reduce(T (&s)[E], uint32_t lg, Op op) {
     rows_broadcast<E>(s, R);
   }
 }
+// same for an order-free operation: combine the rows in the lane first, one butterfly per group
+template <int E, class T, class Op>
+__device__ __forceinline__ void groups_reduce_any_order(T (&s)[E], uint32_t lg, Op op) {
+  if (lg <= 9) {
+    const int lanes = 1 << (lg - 3);
+#pragma unroll
+    for (int j = 0; j < E; ++j) s[j] = lanes_reduce(s[j], lanes, op);
+  } else {
+    const int R = 1 << (lg - 9);
+    rows_combine<E>(s, R, op);
+#pragma unroll
+    for (int j = 0; j < E; ++j)
+      if ((j & (R - 1)) == 0) s[j] = lanes_reduce(s[j], kWave, op);
+    rows_broadcast<E>(s, R);
+  }
+}
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 #pragma unroll
   for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m);
   return v;
+}
+
+// number of set bits of a wavefront mask in the lanes below this one
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
 // ------------------------------------------------------------------ chained scan across tiles
@@ -139,21 +198,110 @@ __device__ __forceinline__ uint32_t scan_resolve(const ScanCtx& sc, uint32_t gti
         flag = ((hi & ~3u) == sc.tag) ? (hi & 3u) : (uint32_t)kFlagEmpty;
         value = (uint32_t)w;
       }
-      pm = __ballot(flag >= kFlagPrefix);
+      pm = __builtin_amdgcn_ballot_w64(flag >= kFlagPrefix);
       last = pm ? __builtin_ctzll(pm) : kWave - 1;  // nearest tile that ends the walk
       need = (last == kWave - 1) ? ~0ull : ((2ull << last) - 1ull);
-      if ((__ballot(flag == kFlagEmpty) & need) == 0) break;
+      if ((__builtin_amdgcn_ballot_w64(flag == kFlagEmpty) & need) == 0) break;
       if (++polls > sc.spin_limit) { aborted = true; break; }
       __builtin_amdgcn_s_sleep(1);
     }
     if (aborted) break;
-    if (__ballot(flag == kFlagAbort) & need) { aborted = true; break; }
+    if (__builtin_amdgcn_ballot_w64(flag == kFlagAbort) & need) { aborted = true; break; }
     excl += wave_sum_u32(lane <= last ? value : 0u);
     if (pm) break;
     top -= kWave;
   }
   if (lane == 0) st_state(&sc.state[gtile], sc.tag | (aborted ? kFlagAbort : kFlagPrefix), excl + count);
   return excl;
+}
+
+// ------------------------------------------------------------------ packing of rounded codes
+// t holds integers in [-2^(b-1), 2^(b-1)-1] as floats.  Adding 1.5 * 2^23 puts the integer, in
+// two's complement, into the low mantissa bits; the bytes / nibbles are then gathered.
+__device__ __forceinline__ uint32_t code_bits(float t) { return __float_as_uint(t + 12582912.0f); }
+
+__device__ __forceinline__ uint32_t pack_bytes4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);  // [a.0, b.0, 0, 0]
+  const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+  return ab | (cd << 16);
+}
+__device__ __forceinline__ uint32_t pack_nibbles8(const uint32_t (&c)[kOct]) {
+  uint32_t w = 0u;
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) w |= (c[e] & 0xFu) << (4 * e);
+  return w;
+}
+
+// ------------------------------------------------------------------ outlier test of the rows of a tile
+struct RowCtx {
+  uint64_t numel, lane_base;
+  float param;             // ABS: tau
+  uint32_t topk_lane_pos;  // TOPK: position of the lane's first element in its group's row
+  int topk_rows;           // TOPK: rows per group
+};
+
+// For every row j: which elements are outliers (mask[j], bit e = element e), the inlier view
+// y[j][*] (outliers, Inf and NaN as zero), the lane's max |y| (symmetric quantisation), the
+// number of outliers of the row in lower lanes, and the row's outlier count.  A row without
+// outliers - the common case - costs a compare, a select and half a max per element beyond
+// the widening; the mask and the positions are only worked out behind a wavefront-uniform branch.
+// CHECK_NONFINITE: additionally test every element for Inf / NaN (statistics were poisoned).
+template <int MODE, bool ASYM, bool CHECK_NONFINITE, int E>
+__device__ __forceinline__ void outlier_rows(const RowCtx& rc, const uint32_t (&raw)[E][4], const float (&limit)[E],
+                                             const uint32_t (&kth)[E], float (&y)[E][kOct], float (&amax)[E],
+                                             uint32_t (&mask)[E], uint32_t (&lane_excl)[E], uint32_t (&row_cnt)[E]) {
+  constexpr float kInf = __builtin_inff();
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    float x[kOct];
+    bool o[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      x[e] = ADACC_ELEM_F32(raw[j], e);
+      if constexpr (MODE == kModeNone) {
+        o[e] = !(fabsf(x[e]) < kInf);            // Inf / NaN: nothing is kept aside, the value counts as zero
+      } else if constexpr (MODE == kModeAbs) {
+        o[e] = !(fabsf(x[e]) <= rc.param);       // |x| > tau, and also Inf / NaN
+      } else if constexpr (MODE == kModeStd) {
+        o[e] = x[e] * x[e] > limit[j];
+      } else {
+        const bool valid = (rc.lane_base + (uint64_t)j * kRow) < rc.numel;
+        const uint32_t row_pos = ((uint32_t)(j & (rc.topk_rows - 1)) << 9) | rc.topk_lane_pos;
+        const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
+        o[e] = (key >= kth[j]) && valid;         // rows past the end hold zeros, which TOPK would rank too
+      }
+      if constexpr (CHECK_NONFINITE) o[e] = o[e] || (ADACC_ELEM_MAG(raw[j], e) >= 0x7F80u);
+    }
+    // y and the lane's max |y| are computed without a branch (a select and half a max3 per
+    // element); only the bookkeeping of rows that do have outliers is conditional
+    float am = 0.0f;
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      y[j][e] = o[e] ? 0.0f : x[e];
+      if constexpr (!ASYM) am = fmaxf(am, fabsf(y[j][e]));
+    }
+    amax[j] = am;
+    uint64_t b[kOct];
+    uint64_t any = 0ull;
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) { b[e] = __builtin_amdgcn_ballot_w64(o[e]); any |= b[e]; }
+    if (any != 0ull) {
+      uint32_t m = 0u, below = 0u, cnt = 0u;
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        m |= o[e] ? (1u << e) : 0u;
+        below += lanes_below(b[e]);
+        cnt += (uint32_t)__popcll(b[e]);
+      }
+      mask[j] = m;
+      lane_excl[j] = below;
+      row_cnt[j] = cnt;
+    } else {
+      mask[j] = 0u;
+      lane_excl[j] = 0u;
+      row_cnt[j] = 0u;
+    }
+  }
 }
 
 // ------------------------------------------------------------------ one tile
@@ -177,20 +325,13 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
     }
   }
 
-  // ---- a2 + a3: statistics and outlier mask (bit e of mask[j] = element e of row j)
-  uint32_t mask[E];
-#pragma unroll
-  for (int j = 0; j < E; ++j) mask[j] = 0u;
-
-  if constexpr (MODE == kModeAbs) {
-    const float tau = d.param;
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-#pragma unroll
-      for (int e = 0; e < kOct; ++e)
-        mask[j] |= (fabsf(ADACC_ELEM_F32(raw[j], e)) > tau) ? (1u << e) : 0u;
-    }
-  } else if constexpr (MODE == kModeStd) {
+  // ---- a2: statistics of the statistics groups
+  float limit[E];    // STD: k^2 * var of the row's group
+  uint32_t kth[E];   // TOPK: the k-th largest key of the row's group
+  bool poisoned = false;  // uniform: some group's statistics met Inf / NaN (or more than k of them)
+  uint32_t topk_lane_pos = 0u;
+  int topk_rows = 1;
+  if constexpr (MODE == kModeStd) {
     float s1[E], s2[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
@@ -206,32 +347,31 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
     groups_reduce<E>(s2, d.lgs, OpAdd());
     const float inv_gs = __uint_as_float((127u - d.lgs) << 23);  // 2^-lgs, exact
     const float k2 = d.param;
+    bool nan_seen = false;
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       const float mean = s1[j] * inv_gs;
       float var = __fmaf_rn(-mean, mean, s2[j] * inv_gs);
       var = (var < 0.0f) ? 0.0f : var;  // a NaN stays a NaN: then nothing passes the test
-      const float limit = k2 * var;
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) {
-        const float xe = ADACC_ELEM_F32(raw[j], e);
-        mask[j] |= (xe * xe > limit) ? (1u << e) : 0u;
-      }
+      limit[j] = k2 * var;
+      nan_seen |= (limit[j] != limit[j]);
     }
+    // an Inf or NaN anywhere in a group makes its limit NaN; only then is the per-element
+    // test for non-finite values needed
+    poisoned = __builtin_amdgcn_ballot_w64(nan_seen) != 0ull;
   } else if constexpr (MODE == kModeTopk) {
     // key = magnitude bits above, reversed position in the group below: the k largest keys
     // are the k largest magnitudes with ties going to the lower index; keys are unique.
     const uint32_t lgs = d.lgs;
-    const int R = (lgs > 9) ? (1 << (lgs - 9)) : 1;
-    const uint32_t lane_pos = (lgs > 9) ? ((uint32_t)lane << 3) : (((uint32_t)lane & ((1u << (lgs - 3)) - 1u)) << 3);
-    uint32_t kth[E];
+    topk_rows = (lgs > 9) ? (1 << (lgs - 9)) : 1;
+    topk_lane_pos = (lgs > 9) ? ((uint32_t)lane << 3) : (((uint32_t)lane & ((1u << (lgs - 3)) - 1u)) << 3);
 #pragma unroll
     for (int j = 0; j < E; ++j) kth[j] = 0xFFFFFFFFu;
     for (uint32_t r = 0; r < d.topk; ++r) {
       uint32_t best[E];
 #pragma unroll
       for (int j = 0; j < E; ++j) {
-        const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
+        const uint32_t row_pos = ((uint32_t)(j & (topk_rows - 1)) << 9) | topk_lane_pos;
         uint32_t m = 0u;
 #pragma unroll
         for (int e = 0; e < kOct; ++e) {
@@ -241,116 +381,70 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
         }
         best[j] = m;
       }
-      if (lgs <= 9) {
-        const int lanes = 1 << (lgs - 3);
-#pragma unroll
-        for (int j = 0; j < E; ++j) best[j] = lanes_reduce(best[j], lanes, OpUMax());
-      } else {
-        rows_combine<E>(best, R, OpUMax());
-#pragma unroll
-        for (int j = 0; j < E; ++j)
-          if ((j & (R - 1)) == 0) best[j] = lanes_reduce(best[j], kWave, OpUMax());
-        rows_broadcast<E>(best, R);
-      }
+      groups_reduce_any_order<E>(best, lgs, OpUMax());
 #pragma unroll
       for (int j = 0; j < E; ++j) kth[j] = best[j];
     }
+    // if even the k-th largest is Inf / NaN there may be more of them than k: check every element
+    bool many = false;
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) {
-        const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
-        mask[j] |= (key >= kth[j]) ? (1u << e) : 0u;
-      }
-    }
+    for (int j = 0; j < E; ++j) many |= (kth[j] >> 16) >= 0x7F80u;
+    poisoned = __builtin_amdgcn_ballot_w64(many) != 0ull;
   }
 
-  // Inf / NaN can not be quantised: always an outlier (when outliers are kept), never in a scale
-  uint32_t nonfinite[E];
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    uint32_t nf = 0u;
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) nf |= (ADACC_ELEM_MAG(raw[j], e) >= 0x7F80u) ? (1u << e) : 0u;
-    nonfinite[j] = nf;
-    if constexpr (MODE != kModeNone) mask[j] |= nf;
+  // ---- a3 + a5: outlier test and inlier view y, row by row
+  float y[E][kOct];
+  float amax[E];        // symmetric: max |y| over the lane's octet
+  uint32_t mask[E], lane_excl[E];
+  uint32_t row_cnt[E];  // uniform
+  const RowCtx rc{d.numel, lane_base, d.param, topk_lane_pos, topk_rows};
+  if constexpr (MODE == kModeStd || MODE == kModeTopk) {
+    // the variant that also tests every element for Inf / NaN is a separate copy of the loop, so
+    // that the common one carries no trace of it
+    if (poisoned) outlier_rows<MODE, ASYM, true, E>(rc, raw, limit, kth, y, amax, mask, lane_excl, row_cnt);
+    else outlier_rows<MODE, ASYM, false, E>(rc, raw, limit, kth, y, amax, mask, lane_excl, row_cnt);
+  } else {
+    outlier_rows<MODE, ASYM, false, E>(rc, raw, limit, kth, y, amax, mask, lane_excl, row_cnt);
   }
-  // rows past the end of the tensor hold zeros; they must never yield outliers (TOPK ranks zeros too)
-#pragma unroll
-  for (int j = 0; j < E; ++j)
-    if (lane_base + (uint64_t)j * kRow >= d.numel) mask[j] = 0u;
 
-  // ---- a4 (first half): count the outliers and publish the tile's count before the long
-  // quantise / store phase, so that later tiles rarely have to wait for it
-  constexpr int W = E / 2;
-  uint32_t cnt[E], lane_excl[E], row_off[E];
+  // ---- a4 (first half): publish the tile's outlier count before the quantise / store phase
+  uint32_t row_off[E];
   uint32_t total = 0u;
   if constexpr (MODE != kModeNone) {
-    // inclusive scan over lanes of the per-row counts, two rows per 32-bit word
-    uint32_t packed[W];
 #pragma unroll
-    for (int j = 0; j < E; ++j) cnt[j] = __popc(mask[j]);
-#pragma unroll
-    for (int w = 0; w < W; ++w) packed[w] = cnt[2 * w] | (cnt[2 * w + 1] << 16);
-#pragma unroll
-    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
-#pragma unroll
-      for (int w = 0; w < W; ++w) {
-        const uint32_t t = __shfl_up(packed[w], dlt);
-        packed[w] += (lane >= dlt) ? t : 0u;
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const uint32_t incl = (packed[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu;
-      lane_excl[j] = incl - cnt[j];
-      row_off[j] = total;
-      total += __shfl(incl, kWave - 1);
-    }
+    for (int j = 0; j < E; ++j) { row_off[j] = total; total += row_cnt[j]; }
     scan_publish(sc, d.first_tile + tile, d.first_tile, total);
   }
 
-  // ---- a5 + a6: inlier view and per-group scale (and offset)
-  float y[E][kOct];
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const uint32_t zero = mask[j] | nonfinite[j];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) y[j][e] = ((zero >> e) & 1u) ? 0.0f : ADACC_ELEM_F32(raw[j], e);
-  }
-
+  // ---- a6: per-group scale (and offset)
   float inv[E], off[E], scl[E];
   if constexpr (!ASYM) {
-    float a[E];
+    uint32_t a[E];  // max |y| as bit patterns: for non-negative floats the integer order is the float order
+#pragma unroll
+    for (int j = 0; j < E; ++j) a[j] = __float_as_uint(amax[j]);
+    groups_reduce_any_order<E>(a, d.lgq, OpUMax());
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-      float m = 0.0f;
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) m = fmaxf(m, fabsf(y[j][e]));
-      a[j] = m;
-    }
-    groups_reduce<E>(a, d.lgq, OpMax());
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      scl[j] = a[j] / d.divisor;                                           // Eq. 2: S = max|X| / D
-      inv[j] = (a[j] != 0.0f) ? fminf(d.divisor / a[j], 3.402823466e+38f) : 0.0f;  // one division per group
+      const float am = __uint_as_float(a[j]);
+      scl[j] = am / d.divisor;                                                 // Eq. 2: S = max|X| / D
+      inv[j] = (am != 0.0f) ? fminf(d.divisor / am, 3.402823466e+38f) : 0.0f;  // one division per group
       off[j] = 0.0f;
     }
   } else {
-    float hi[E], lo[E];
+    int32_t hi[E], lo[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       float mx = y[j][0], mn = y[j][0];
 #pragma unroll
       for (int e = 1; e < kOct; ++e) { mx = fmaxf(mx, y[j][e]); mn = fminf(mn, y[j][e]); }
-      hi[j] = mx; lo[j] = mn;
+      hi[j] = float_key(mx); lo[j] = float_key(mn);
     }
-    groups_reduce<E>(hi, d.lgq, OpMax());
-    groups_reduce<E>(lo, d.lgq, OpMin());
+    groups_reduce_any_order<E>(hi, d.lgq, OpIMax());
+    groups_reduce_any_order<E>(lo, d.lgq, OpIMin());
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-      const float h = hi[j] + 0.0f, l = lo[j] + 0.0f;  // a zero extreme is +0 whatever signs the zeros had
+      // a zero extreme is +0 whatever signs the zeros had
+      const float h = key_float(hi[j]) + 0.0f, l = key_float(lo[j]) + 0.0f;
       const float o = (h + l) * 0.5f;                   // Eq. 3: O = (max+min)/2
       const float r = h - l;
       off[j] = o;
@@ -366,25 +460,22 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
   for (int j = 0; j < E; ++j) {
     const uint64_t e0 = lane_base + (uint64_t)j * kRow;
     if (e0 >= d.numel) continue;
-    int c[kOct];
+    uint32_t c[kOct];
 #pragma unroll
     for (int e = 0; e < kOct; ++e) {
-      const float t = ASYM ? (y[j][e] - off[j]) * inv[j] : y[j][e] * inv[j];
-      float r = __builtin_rintf(t);          // nearest, ties to even
-      r = fmaxf(r, (float)(-Q));             // a NaN lands on the lower bound
-      r = fminf(r, (float)(Q - 1));          // "values greater than 7 are capped at 7"
-      c[e] = (int)r;
+      float t = ASYM ? (y[j][e] - off[j]) * inv[j] : y[j][e] * inv[j];
+      // clip first, then round: the bounds are integers, so this equals round-then-clip
+      // ("values greater than 7 are capped at 7"); a NaN lands on the lower bound
+      t = fminf(fmaxf(t, (float)(-Q)), (float)(Q - 1));
+      c[e] = code_bits(t);  // the addition rounds to nearest, ties to even
     }
     if constexpr (BITS == 8) {
       uint2 w;
-      w.x = (uint32_t)(c[0] & 0xFF) | ((uint32_t)(c[1] & 0xFF) << 8) | ((uint32_t)(c[2] & 0xFF) << 16) | ((uint32_t)c[3] << 24);
-      w.y = (uint32_t)(c[4] & 0xFF) | ((uint32_t)(c[5] & 0xFF) << 8) | ((uint32_t)(c[6] & 0xFF) << 16) | ((uint32_t)c[7] << 24);
+      w.x = pack_bytes4(c[0], c[1], c[2], c[3]);
+      w.y = pack_bytes4(c[4], c[5], c[6], c[7]);
       *reinterpret_cast<uint2*>(d.codes + e0) = w;
     } else {
-      uint32_t w = 0u;
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) w |= (uint32_t)(c[e] & 0xF) << (4 * e);
-      *reinterpret_cast<uint32_t*>(d.codes + (e0 >> 1)) = w;
+      *reinterpret_cast<uint32_t*>(d.codes + (e0 >> 1)) = pack_nibbles8(c);
     }
     if (((uint32_t)lane & q_lanes_mask) == 0u && ((uint32_t)j & q_rows_mask) == 0u) {
       const uint64_t g = e0 >> d.lgq;
@@ -413,19 +504,21 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
     if (total != 0u && !aborted) {
       static_for<E>([&](auto J) {
         constexpr int j = decltype(J)::value;
-        uint32_t bits = mask[j];
-        uint32_t pos = base + row_off[j] + lane_excl[j];
-        const uint32_t i0 = (uint32_t)(lane_base + (uint64_t)j * kRow);
-        while (bits) {
-          const int e = __builtin_ctz(bits);
-          bits &= bits - 1u;
-          // element e of the octet by shifting (an indexed read would push the octets to scratch)
-          const uint64_t half = (e < 4) ? (((uint64_t)raw[j][1] << 32) | raw[j][0]) : (((uint64_t)raw[j][3] << 32) | raw[j][2]);
-          if (pos < d.cap) {
-            d.idx[pos] = (int32_t)(i0 + (uint32_t)e);
-            d.val[pos] = (uint16_t)(half >> (16 * (e & 3)));
+        if (row_cnt[j] != 0u) {
+          uint32_t bits = mask[j];
+          uint32_t pos = base + row_off[j] + lane_excl[j];
+          const uint32_t i0 = (uint32_t)(lane_base + (uint64_t)j * kRow);
+          while (bits) {
+            const int e = __builtin_ctz(bits);
+            bits &= bits - 1u;
+            // element e of the octet by shifting (an indexed read would push the octets to scratch)
+            const uint64_t half = (e < 4) ? (((uint64_t)raw[j][1] << 32) | raw[j][0]) : (((uint64_t)raw[j][3] << 32) | raw[j][2]);
+            if (pos < d.cap) {
+              d.idx[pos] = (int32_t)(i0 + (uint32_t)e);
+              d.val[pos] = (uint16_t)(half >> (16 * (e & 3)));
+            }
+            ++pos;
           }
-          ++pos;
         }
       });
     }
