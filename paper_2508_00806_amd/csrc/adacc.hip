@@ -16,20 +16,21 @@ namespace adacc {
 
 // ===================================================================== kernels
 
-// ---- single tensor, compress: one tile per wavefront, tile = 4 * workgroup + wavefront.
-// With outliers the grid is exactly ceil(n_tiles / 4) workgroups: the chained scan relies on
-// tiles being started in index order.  NONE: tiles are independent, grid-stride loop.
+// ---- single tensor, compress.  With outliers: run = 4 * workgroup + wavefront, and the grid is
+// exactly ceil(n_units / 4) workgroups, because the chained scan relies on runs being started
+// in index order.  NONE: tiles are independent, grid-stride loop over tiles.
 template <int MODE, int BITS, bool ASYM, int E>
 __global__ __launch_bounds__(kThreads) void compress_kernel(TensorDesc d, uint64_t* state, uint32_t tag,
                                                             uint32_t spin_limit) {
   const uint32_t wave = threadIdx.x / kWave;
-  const ScanCtx sc{state, tag, spin_limit};
   if constexpr (MODE == kModeNone) {
     for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-      compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
+      compress_tile_plain<BITS, ASYM, E>(d, t);
   } else {
-    const uint32_t t = blockIdx.x * kWavesPerWg + wave;
-    if (t < d.n_tiles) compress_tile<MODE, BITS, ASYM, E>(d, t, sc);
+    __shared__ WaveStage stage[kWavesPerWg];
+    const ScanCtx sc{state, tag, spin_limit};
+    const uint32_t u = blockIdx.x * kWavesPerWg + wave;
+    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E>(d, u, sc, &stage[wave]);
   }
 }
 
@@ -43,43 +44,68 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint
 }
 
 // ---- batch: a launch-wide tile numbering over all tensors of the table
-__device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_t n, uint32_t gtile) {
-  uint32_t lo = 0u, hi = n;  // first_tile is ascending; find the last entry with first_tile <= gtile
+template <bool BY_UNIT>
+__device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_t n, uint32_t g) {
+  uint32_t lo = 0u, hi = n;  // first_tile / first_unit ascend; find the last entry that starts at or before g
   while (hi - lo > 1u) {
     const uint32_t mid = (lo + hi) >> 1;
-    if (table[mid].first_tile <= gtile) lo = mid; else hi = mid;
+    const uint32_t first = BY_UNIT ? table[mid].first_unit : table[mid].first_tile;
+    if (first <= g) lo = mid; else hi = mid;
   }
   return lo;
 }
 
 template <int MODE>
-__device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t tile, const ScanCtx& sc) {
+__device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
+                                                       WaveStage* stage) {
   switch (d.variant & 7u) {
-    case 0: compress_tile<MODE, 4, false, 4>(d, tile, sc); break;
-    case 1: compress_tile<MODE, 4, false, 8>(d, tile, sc); break;
-    case 2: compress_tile<MODE, 4, true, 4>(d, tile, sc); break;
-    case 3: compress_tile<MODE, 4, true, 8>(d, tile, sc); break;
-    case 4: compress_tile<MODE, 8, false, 4>(d, tile, sc); break;
-    case 5: compress_tile<MODE, 8, false, 8>(d, tile, sc); break;
-    case 6: compress_tile<MODE, 8, true, 4>(d, tile, sc); break;
-    default: compress_tile<MODE, 8, true, 8>(d, tile, sc); break;
+    case 0: compress_run<MODE, 4, false, 4>(d, unit, sc, stage); break;
+    case 1: compress_run<MODE, 4, false, 8>(d, unit, sc, stage); break;
+    case 2: compress_run<MODE, 4, true, 4>(d, unit, sc, stage); break;
+    case 3: compress_run<MODE, 4, true, 8>(d, unit, sc, stage); break;
+    case 4: compress_run<MODE, 8, false, 4>(d, unit, sc, stage); break;
+    case 5: compress_run<MODE, 8, false, 8>(d, unit, sc, stage); break;
+    case 6: compress_run<MODE, 8, true, 4>(d, unit, sc, stage); break;
+    default: compress_run<MODE, 8, true, 8>(d, unit, sc, stage); break;
   }
 }
 
+template <int BITS, bool ASYM, int E>
+__device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t unit) {
+  const uint32_t t0 = unit * d.tiles_per_unit;
+  const uint32_t t1 = (t0 + d.tiles_per_unit < d.n_tiles) ? t0 + d.tiles_per_unit : d.n_tiles;
+  for (uint32_t t = t0; t < t1; ++t) compress_tile_plain<BITS, ASYM, E>(d, t);
+}
+
+// One launch for a table of tensors: runs are numbered across the table; a wavefront finds
+// its tensor by binary search and dispatches on that tensor's method.
 __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                  uint32_t total_tiles, uint64_t* state,
+                                                                  uint32_t total_units, uint64_t* state,
                                                                   uint32_t tag, uint32_t spin_limit) {
+  __shared__ WaveStage stage[kWavesPerWg];
+  const uint32_t wave = threadIdx.x / kWave;
   const ScanCtx sc{state, tag, spin_limit};
-  const uint32_t g = blockIdx.x * kWavesPerWg + threadIdx.x / kWave;
-  if (g >= total_tiles) return;
-  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor(table, n, g));
+  const uint32_t g = blockIdx.x * kWavesPerWg + wave;
+  if (g >= total_units) return;
+  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<true>(table, n, g));
   const TensorDesc d = table[ti];
-  const uint32_t tile = g - d.first_tile;
+  const uint32_t unit = g - d.first_unit;
   switch (d.variant >> 3) {
-    case kModeNone: compress_dispatch_mode<kModeNone>(d, tile, sc); break;
-    case kModeAbs: compress_dispatch_mode<kModeAbs>(d, tile, sc); break;
-    case kModeStd: compress_dispatch_mode<kModeStd>(d, tile, sc); break;
-    default: compress_dispatch_mode<kModeTopk>(d, tile, sc); break;
+    case kModeNone:
+      switch (d.variant & 7u) {
+        case 0: compress_plain_run<4, false, 4>(d, unit); break;
+        case 1: compress_plain_run<4, false, 8>(d, unit); break;
+        case 2: compress_plain_run<4, true, 4>(d, unit); break;
+        case 3: compress_plain_run<4, true, 8>(d, unit); break;
+        case 4: compress_plain_run<8, false, 4>(d, unit); break;
+        case 5: compress_plain_run<8, false, 8>(d, unit); break;
+        case 6: compress_plain_run<8, true, 4>(d, unit); break;
+        default: compress_plain_run<8, true, 8>(d, unit); break;
+      }
+      break;
+    case kModeAbs: compress_dispatch_mode<kModeAbs>(d, unit, sc, &stage[wave]); break;
+    case kModeStd: compress_dispatch_mode<kModeStd>(d, unit, sc, &stage[wave]); break;
+    default: compress_dispatch_mode<kModeTopk>(d, unit, sc, &stage[wave]); break;
   }
 }
 
@@ -90,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
   const uint32_t wave = threadIdx.x / kWave;
   unsigned char* slice = lds + wave * decompress_lds_per_wave<8, F32>();
   for (uint32_t g = blockIdx.x * kWavesPerWg + wave; g < total_tiles; g += gridDim.x * kWavesPerWg) {
-    const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor(table, n, g));
+    const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<false>(table, n, g));
     const TensorDesc d = table[ti];
     const uint32_t tile = g - d.first_tile;
     const bool ho = (d.variant >> 3) != kModeNone;
@@ -214,8 +240,21 @@ static void fill_layout(const adacc_method* m, uint64_t numel, const Plan& p, ad
   L->n_tiles = p.n_tiles;
 }
 
+// Tiles per run: enough runs to fill the machine a few times over, few enough that the
+// look-back (whose reach grows with the number of runs in flight) stays short.
+static uint32_t tiles_per_unit(uint64_t tiles_in_launch, int cus) {
+  const uint64_t target = (uint64_t)cus * (uint64_t)env_int("ADACC_UNITS_PER_CU", 32);
+  uint64_t t = (tiles_in_launch + target - 1) / target;
+  const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 16);
+  if (t > tmax) t = tmax;
+  if (t > 32) t = 32;
+  if (t < 1) t = 1;
+  return (uint32_t)t;
+}
+
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
-                      void* blob, void* dst, int dst_dtype, uint32_t first_tile, TensorDesc* d) {
+                      void* blob, void* dst, int dst_dtype, uint32_t first_tile, uint32_t tpu, uint32_t first_unit,
+                      TensorDesc* d) {
   std::memset(d, 0, sizeof *d);
   unsigned char* b = static_cast<unsigned char*>(blob);
   d->src = static_cast<const uint16_t*>(src);
@@ -230,6 +269,9 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
   d->numel = numel;
   d->n_tiles = p.n_tiles;
   d->first_tile = first_tile;
+  d->tiles_per_unit = tpu;
+  d->n_units = (p.n_tiles + tpu - 1) / tpu;
+  d->first_unit = first_unit;
   d->lgq = p.lgq;
   d->lgs = p.lgs;
   d->cap = m->max_outliers;
@@ -395,15 +437,15 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
     if (ws->bytes < 8ull * p.n_tiles) return ADACC_ESIZE;
     if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   }
+  int cus = 0;
+  rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
+  if (rc != ADACC_OK) return rc;
   TensorDesc d;
-  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, &d);
+  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, p.outliers ? tiles_per_unit(p.n_tiles, cus) : 1u, 0, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t grid = 0, tag = 0;
   if (p.outliers) {
-    grid = (p.n_tiles + kWavesPerWg - 1) / kWavesPerWg;  // tiles start in index order: no grid-stride loop
-    int cus = 0;
-    rc = device_cus(&cus);                               // also: fail here rather than in the launch without a device
-    if (rc != ADACC_OK) return rc;
+    grid = (d.n_units + kWavesPerWg - 1) / kWavesPerWg;  // runs start in index order: no grid-stride loop
     rc = next_tag(ws, s, &tag);
   } else {
     rc = grid_for(p.n_tiles, &grid);
@@ -429,7 +471,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, &d);
+  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, &d);
   uint32_t grid = 0;
   rc = grid_for(p.n_tiles, &grid);
   if (rc != ADACC_OK) return rc;
@@ -466,8 +508,9 @@ uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method* methods, co
 
 static int batch_table(uint32_t n, const adacc_method* methods, const std::vector<Plan>& plans, const uint64_t* numels,
                        const void* const* srcs, void* const* blobs, const uint64_t* blob_bytes, void* const* dsts,
-                       int dst_dtype, bool compress, std::vector<TensorDesc>* table) {
-  uint32_t first = 0;
+                       int dst_dtype, bool compress, uint32_t tpu, std::vector<TensorDesc>* table,
+                       uint32_t* total_units) {
+  uint32_t first = 0, first_unit = 0;
   for (uint32_t i = 0; i < n; ++i) {
     if (plans[i].noop) continue;
     if (!blobs[i]) return ADACC_ENULL;
@@ -479,10 +522,12 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
     if (compress ? misaligned(srcs[i], 16) : misaligned(dsts[i], 16)) return ADACC_EALIGN;
     TensorDesc d;
     fill_desc(&methods[i], numels[i], plans[i], L, compress ? srcs[i] : nullptr, blobs[i], compress ? nullptr : dsts[i],
-              dst_dtype, first, &d);
+              dst_dtype, first, tpu, first_unit, &d);
     table->push_back(d);
     first += plans[i].n_tiles;
+    first_unit += d.n_units;
   }
+  if (total_units) *total_units = first_unit;
   return ADACC_OK;
 }
 
@@ -500,10 +545,15 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   if (ws->bytes < bp.bytes) return ADACC_ESIZE;
   if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   std::vector<TensorDesc> table;
-  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, &table);
-  if (rc != ADACC_OK) return rc;
+  uint32_t total_units = 0;
+  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, 1u, &table, &total_units);
+  if (rc != ADACC_OK) return rc;  // every argument is checked before the device is touched
   int cus = 0;
   rc = device_cus(&cus);
+  if (rc != ADACC_OK) return rc;
+  table.clear();
+  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, tiles_per_unit(total, cus),
+                   &table, &total_units);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t tag = 0;
@@ -513,9 +563,9 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   const hipError_t e = hipMemcpyAsync(mem + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
                                       hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
-  const uint32_t grid = (total + kWavesPerWg - 1) / kWavesPerWg;
+  const uint32_t grid = (total_units + kWavesPerWg - 1) / kWavesPerWg;
   hipLaunchKernelGGL(compress_batch_kernel, dim3(grid), dim3(kThreads), 0, s,
-                     reinterpret_cast<const TensorDesc*>(mem + bp.table_off), (uint32_t)table.size(), total,
+                     reinterpret_cast<const TensorDesc*>(mem + bp.table_off), (uint32_t)table.size(), total_units,
                      reinterpret_cast<uint64_t*>(mem), tag, spin_limit());
   return launch_check("compress_batch_kernel");
 }
@@ -537,7 +587,7 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   std::vector<TensorDesc> table;
   rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
-                   false, &table);
+                   false, 1u, &table, nullptr);
   if (rc != ADACC_OK) return rc;
   uint32_t grid = 0;
   rc = grid_for(total, &grid);

@@ -37,7 +37,11 @@ struct TensorDesc {
   uint32_t* status;
   uint64_t numel;
   uint32_t n_tiles;
-  uint32_t first_tile;  // launch-wide id of this tensor's tile 0
+  uint32_t first_tile;      // launch-wide id of this tensor's tile 0 (batch decompress)
+  uint32_t tiles_per_unit;  // compress: tiles one wavefront handles one after the other ("run")
+  uint32_t n_units;         // ceil(n_tiles / tiles_per_unit)
+  uint32_t first_unit;      // launch-wide id of this tensor's run 0 (compress)
+  uint32_t pad0;
   uint32_t lgq;         // log2(quant group)
   uint32_t lgs;         // log2(stat group) (STD / TOPK)
   uint32_t cap;         // capacity of idx / val
@@ -48,7 +52,7 @@ struct TensorDesc {
   uint32_t dst_f32;     // decompress: 1 = binary32 output
 };
 
-// Scan workspace: one 64-bit state word per tile, high half = (epoch << 2) | flag, low half =
+// Scan workspace: one 64-bit state word per run of tiles, high half = (epoch << 2) | flag, low half =
 // value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
 // words written by earlier launches carry another epoch and read as empty, so the buffer is
 // cleared only once, when it is set up, and again when the 30-bit epoch wraps.

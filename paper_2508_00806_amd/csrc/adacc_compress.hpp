@@ -164,54 +164,79 @@ __device__ __forceinline__ void st_state(uint64_t* p, uint32_t hi, uint32_t lo) 
   __hip_atomic_store(p, ((uint64_t)hi << 32) | lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Single-pass scan of the per-tile outlier counts with decoupled look-back, one tile per
-// wavefront.  scan_publish makes the tile's own count visible as early as possible;
-// scan_resolve walks back over 64 predecessors at a time, one per lane, adding their counts
-// until it meets a tile that already knows its inclusive prefix, then publishes its own.
-// Tiles are numbered in launch order (workgroup index, wavefront index), and a tile only ever
-// waits for lower-numbered ones, which the hardware has dispatched earlier.  The poll bound is
-// a second line of defence: when it trips, the tile publishes "abort", which every later tile
-// inherits at once, so the kernel always drains and reports the failure in the status words.
-__device__ __forceinline__ void scan_publish(const ScanCtx& sc, uint32_t gtile, uint32_t first, uint32_t count) {
-  if (lane_id() == 0)
-    st_state(&sc.state[gtile], sc.tag | (gtile == first ? kFlagPrefix : kFlagAggregate), count);
+// Single-pass scan of outlier counts with decoupled look-back.  The scan unit is a "run": the
+// kTilesPerUnit consecutive tiles that one wavefront compresses one after the other.  A run
+// publishes its total when it is done (flag "aggregate"), looks back over its predecessors -
+// 128 of them per memory round trip, two per lane - adding their totals until it meets a run
+// that already knows its inclusive prefix, then publishes its own prefix.  Runs are numbered
+// in launch order (workgroup index, wavefront index) and a run only ever waits for
+// lower-numbered ones, which the hardware has dispatched earlier.  The poll bound is a second
+// line of defence: when it trips, the run publishes "abort", which every later run inherits
+// at once, so the kernel always drains and reports the failure in the status words.
+__device__ __forceinline__ void scan_publish(const ScanCtx& sc, uint32_t unit, uint32_t flag, uint32_t value) {
+  if (lane_id() == 0) st_state(&sc.state[unit], sc.tag | flag, value);
 }
 
-__device__ __forceinline__ uint32_t scan_resolve(const ScanCtx& sc, uint32_t gtile, uint32_t first,
-                                                 uint32_t count, bool& aborted) {
+// Sum of the totals of runs first..unit-1.
+__device__ __forceinline__ uint32_t scan_lookback(const ScanCtx& sc, uint32_t unit, uint32_t first, bool& aborted) {
   const int lane = lane_id();
   aborted = false;
-  if (gtile == first) return 0;
+  if (unit == first) return 0;
   uint32_t excl = 0;
-  int64_t top = (int64_t)gtile - 1;
+  int64_t top = (int64_t)unit - 1;
   while (true) {
-    const int64_t p = top - lane;
-    const bool in_range = p >= (int64_t)first;
-    uint32_t flag = kFlagPrefix, value = 0;
+    const int64_t pa = top - lane, pb = top - kWave - lane;  // nearer and farther window
+    const bool in_a = pa >= (int64_t)first, in_b = pb >= (int64_t)first;
+    uint32_t fa = kFlagPrefix, va = 0, fb = kFlagPrefix, vb = 0;  // before the first run: prefix 0
     uint32_t polls = 0;
-    uint64_t pm, need;
-    int last;
+    uint64_t need_a, need_b;
+    bool found;
     while (true) {
-      if (in_range) {
-        const uint64_t w = ld_state(&sc.state[p]);
-        const uint32_t hi = (uint32_t)(w >> 32);
-        flag = ((hi & ~3u) == sc.tag) ? (hi & 3u) : (uint32_t)kFlagEmpty;
-        value = (uint32_t)w;
+      uint64_t wa = 0, wb = 0;
+      if (in_a) wa = ld_state(&sc.state[pa]);
+      if (in_b) wb = ld_state(&sc.state[pb]);
+      if (in_a) {
+        const uint32_t hi = (uint32_t)(wa >> 32);
+        fa = ((hi & ~3u) == sc.tag) ? (hi & 3u) : (uint32_t)kFlagEmpty;
+        va = (uint32_t)wa;
       }
-      pm = __builtin_amdgcn_ballot_w64(flag >= kFlagPrefix);
-      last = pm ? __builtin_ctzll(pm) : kWave - 1;  // nearest tile that ends the walk
-      need = (last == kWave - 1) ? ~0ull : ((2ull << last) - 1ull);
-      if ((__builtin_amdgcn_ballot_w64(flag == kFlagEmpty) & need) == 0) break;
+      if (in_b) {
+        const uint32_t hi = (uint32_t)(wb >> 32);
+        fb = ((hi & ~3u) == sc.tag) ? (hi & 3u) : (uint32_t)kFlagEmpty;
+        vb = (uint32_t)wb;
+      }
+      const uint64_t pm_a = __builtin_amdgcn_ballot_w64(fa >= kFlagPrefix);
+      const uint64_t pm_b = __builtin_amdgcn_ballot_w64(fb >= kFlagPrefix);
+      if (pm_a) {         // the walk ends in the nearer window
+        const int last = __builtin_ctzll(pm_a);
+        need_a = (last == kWave - 1) ? ~0ull : ((2ull << last) - 1ull);
+        need_b = 0ull;
+        found = true;
+      } else if (pm_b) {  // all of the nearer window, part of the farther one
+        const int last = __builtin_ctzll(pm_b);
+        need_a = ~0ull;
+        need_b = (last == kWave - 1) ? ~0ull : ((2ull << last) - 1ull);
+        found = true;
+      } else {
+        need_a = need_b = ~0ull;
+        found = false;
+      }
+      const uint64_t empty = (__builtin_amdgcn_ballot_w64(fa == kFlagEmpty) & need_a) |
+                             (__builtin_amdgcn_ballot_w64(fb == kFlagEmpty) & need_b);
+      if (empty == 0ull) break;
       if (++polls > sc.spin_limit) { aborted = true; break; }
-      __builtin_amdgcn_s_sleep(1);
+      __builtin_amdgcn_s_sleep(2);
     }
     if (aborted) break;
-    if (__builtin_amdgcn_ballot_w64(flag == kFlagAbort) & need) { aborted = true; break; }
-    excl += wave_sum_u32(lane <= last ? value : 0u);
-    if (pm) break;
-    top -= kWave;
+    if ((__builtin_amdgcn_ballot_w64(fa == kFlagAbort) & need_a) | (__builtin_amdgcn_ballot_w64(fb == kFlagAbort) & need_b)) {
+      aborted = true;
+      break;
+    }
+    const uint32_t mine = (((need_a >> lane) & 1ull) ? va : 0u) + (((need_b >> lane) & 1ull) ? vb : 0u);
+    excl += wave_sum_u32(mine);
+    if (found) break;
+    top -= 2 * kWave;
   }
-  if (lane == 0) st_state(&sc.state[gtile], sc.tag | (aborted ? kFlagAbort : kFlagPrefix), excl + count);
   return excl;
 }
 
@@ -305,15 +330,10 @@ __device__ __forceinline__ void outlier_rows(const RowCtx& rc, const uint32_t (&
 }
 
 // ------------------------------------------------------------------ one tile
-template <int MODE, int BITS, bool ASYM, int E>
-__device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile, const ScanCtx& sc) {
-  constexpr int Q = 1 << (BITS - 1);
-  const int lane = lane_id();
-  const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
-  const uint64_t lane_base = tile_base + (uint64_t)lane * kOct;
-
-  // ---- a1: load (16 bytes per lane per row; rows past the end read as zero)
-  uint32_t raw[E][4];
+// ---- a1: load (16 bytes per lane per row; rows past the end of the tensor read as zero)
+template <int E>
+__device__ __forceinline__ void load_tile(const TensorDesc& d, uint32_t tile, uint32_t (&raw)[E][4]) {
+  const uint64_t lane_base = (uint64_t)tile * (uint64_t)(E * kRow) + (uint64_t)lane_id() * kOct;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const uint64_t e0 = lane_base + (uint64_t)j * kRow;
@@ -324,6 +344,26 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
       raw[j][0] = raw[j][1] = raw[j][2] = raw[j][3] = 0u;
     }
   }
+}
+
+// What a tile leaves behind for the outlier stream.
+template <int E>
+struct TileOutliers {
+  uint32_t mask[E];       // bit e of mask[j]: element e of this lane's octet in row j is an outlier
+  uint32_t lane_excl[E];  // outliers of row j in lower lanes
+  uint32_t row_off[E];    // outliers of the tile in rows before j (uniform)
+  uint32_t row_cnt[E];    // outliers of row j (uniform)
+  uint32_t total;         // outliers of the tile (uniform)
+};
+
+// ---- a2 .. a8 for one tile: everything except the placement of the outliers in the stream.
+template <int MODE, int BITS, bool ASYM, int E>
+__device__ __forceinline__ void encode_tile(const TensorDesc& d, uint32_t tile, const uint32_t (&raw)[E][4],
+                                            TileOutliers<E>& out) {
+  constexpr int Q = 1 << (BITS - 1);
+  const int lane = lane_id();
+  const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
+  const uint64_t lane_base = tile_base + (uint64_t)lane * kOct;
 
   // ---- a2: statistics of the statistics groups
   float limit[E];    // STD: k^2 * var of the row's group
@@ -395,8 +435,9 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
   // ---- a3 + a5: outlier test and inlier view y, row by row
   float y[E][kOct];
   float amax[E];        // symmetric: max |y| over the lane's octet
-  uint32_t mask[E], lane_excl[E];
-  uint32_t row_cnt[E];  // uniform
+  uint32_t (&mask)[E] = out.mask;
+  uint32_t (&lane_excl)[E] = out.lane_excl;
+  uint32_t (&row_cnt)[E] = out.row_cnt;
   const RowCtx rc{d.numel, lane_base, d.param, topk_lane_pos, topk_rows};
   if constexpr (MODE == kModeStd || MODE == kModeTopk) {
     // the variant that also tests every element for Inf / NaN is a separate copy of the loop, so
@@ -407,14 +448,9 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
     outlier_rows<MODE, ASYM, false, E>(rc, raw, limit, kth, y, amax, mask, lane_excl, row_cnt);
   }
 
-  // ---- a4 (first half): publish the tile's outlier count before the quantise / store phase
-  uint32_t row_off[E];
-  uint32_t total = 0u;
-  if constexpr (MODE != kModeNone) {
+  out.total = 0u;
 #pragma unroll
-    for (int j = 0; j < E; ++j) { row_off[j] = total; total += row_cnt[j]; }
-    scan_publish(sc, d.first_tile + tile, d.first_tile, total);
-  }
+  for (int j = 0; j < E; ++j) { out.row_off[j] = out.total; out.total += row_cnt[j]; }
 
   // ---- a6: per-group scale (and offset)
   float inv[E], off[E], scl[E];
@@ -484,48 +520,143 @@ __device__ __forceinline__ void compress_tile(const TensorDesc& d, uint32_t tile
     }
   }
 
-  // ---- a4 (second half): resolve the tile's offset in the stream and append its outliers
-  if constexpr (MODE != kModeNone) {
-    bool aborted;
-    const uint32_t base = scan_resolve(sc, d.first_tile + tile, d.first_tile, total, aborted);
+}
 
-    if (lane == 0) {
-      d.tile_ptr[tile] = base;
-      if (tile == d.n_tiles - 1) {
-        const uint32_t n_out = base + total;
-        d.tile_ptr[d.n_tiles] = n_out;
-        d.status[0] = n_out;
-        d.status[1] = (n_out > d.cap) ? 1u : 0u;
-        d.status[3] = 0u;
-        if (!aborted) d.status[2] = 0u;
+// ---- a4: append a tile's outliers, in ascending index order, to `idx_out` / `val_out` starting
+// at position pos0 (entries at or past `limit` are dropped).  The destination is either the
+// stream in global memory or the wavefront's staging area in LDS.
+template <int E, class IdxPtr, class ValPtr>
+__device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const TileOutliers<E>& out, uint32_t tile,
+                                              IdxPtr idx_out, ValPtr val_out, uint32_t pos0, uint32_t limit) {
+  const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
+  static_for<E>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    if (out.row_cnt[j] != 0u) {
+      uint32_t bits = out.mask[j];
+      uint32_t pos = pos0 + out.row_off[j] + out.lane_excl[j];
+      const uint32_t i0 = lane_first + (uint32_t)(j * kRow);
+      while (bits) {
+        const int e = __builtin_ctz(bits);
+        bits &= bits - 1u;
+        // element e of the octet by shifting (an indexed read would push the octets to scratch)
+        const uint64_t half = (e < 4) ? (((uint64_t)raw[j][1] << 32) | raw[j][0]) : (((uint64_t)raw[j][3] << 32) | raw[j][2]);
+        if (pos < limit) {
+          idx_out[pos] = (int32_t)(i0 + (uint32_t)e);
+          val_out[pos] = (uint16_t)(half >> (16 * (e & 3)));
+        }
+        ++pos;
       }
-      if (aborted) d.status[2] = 1u;
     }
-    if (total != 0u && !aborted) {
-      static_for<E>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        if (row_cnt[j] != 0u) {
-          uint32_t bits = mask[j];
-          uint32_t pos = base + row_off[j] + lane_excl[j];
-          const uint32_t i0 = (uint32_t)(lane_base + (uint64_t)j * kRow);
-          while (bits) {
-            const int e = __builtin_ctz(bits);
-            bits &= bits - 1u;
-            // element e of the octet by shifting (an indexed read would push the octets to scratch)
-            const uint64_t half = (e < 4) ? (((uint64_t)raw[j][1] << 32) | raw[j][0]) : (((uint64_t)raw[j][3] << 32) | raw[j][2]);
-            if (pos < d.cap) {
-              d.idx[pos] = (int32_t)(i0 + (uint32_t)e);
-              d.val[pos] = (uint16_t)(half >> (16 * (e & 3)));
-            }
-            ++pos;
+  });
+}
+
+// ------------------------------------------------------------------ one run of tiles (outlier modes)
+constexpr int kStageCap = 256;  // outliers a wavefront can hold back in LDS while its offset is unknown
+struct WaveStage {
+  int32_t idx[kStageCap];
+  uint16_t val[kStageCap];
+};
+
+// One wavefront compresses the tiles [unit*T, unit*T + T) of a tensor one after the other.  The
+// outliers of the run are collected in LDS; when the run is done its total is published, the
+// offset of the run in the stream is resolved by look-back, and the staged outliers are
+// copied out in one coalesced sweep.  A run whose outliers do not fit the staging area
+// resolves its offset early (it only has to wait for lower-numbered runs) and from then on
+// appends straight to the stream.
+template <int MODE, int BITS, bool ASYM, int E>
+__device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit, const ScanCtx& sc, WaveStage* stage) {
+  static_assert(MODE != kModeNone, "runs exist for the scan only");
+  const int lane = lane_id();
+  const uint32_t T = d.tiles_per_unit;
+  const uint32_t t0 = unit * T;
+  const uint32_t t1 = (t0 + T < d.n_tiles) ? t0 + T : d.n_tiles;
+  const uint32_t gunit = d.first_unit + unit;
+
+  bool base_known = false, aborted = false;
+  uint32_t excl = 0u;       // outliers of the tensor before this run
+  uint32_t run_total = 0u;  // outliers of the run so far
+  uint32_t staged = 0u;     // of which are waiting in LDS
+  uint32_t tile_off = 0u;   // lane k: outliers of the run before its k-th tile
+
+  uint32_t raw[E][4];
+  load_tile<E>(d, t0, raw);
+  for (uint32_t t = t0; t < t1; ++t) {
+    uint32_t nxt[E][4];
+    if (t + 1 < t1) load_tile<E>(d, t + 1, nxt);  // in flight while this tile is encoded
+
+    TileOutliers<E> out;
+    encode_tile<MODE, BITS, ASYM, E>(d, t, raw, out);
+    if ((uint32_t)lane == t - t0) tile_off = run_total;
+
+    if (out.total != 0u) {
+      if (!base_known && staged + out.total > (uint32_t)kStageCap) {
+        // no room: find the run's offset now and empty the staging area
+        excl = scan_lookback(sc, gunit, d.first_unit, aborted);
+        base_known = true;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (!aborted) {
+          for (uint32_t i = (uint32_t)lane; i < staged; i += kWave) {
+            const uint32_t p = excl + i;
+            if (p < d.cap) { d.idx[p] = stage->idx[i]; d.val[p] = stage->val[i]; }
           }
         }
-      });
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        staged = 0u;
+      }
+      if (base_known) {
+        if (!aborted) emit_outliers<E>(raw, out, t, d.idx, d.val, excl + run_total, d.cap);
+      } else {
+        emit_outliers<E>(raw, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
+        staged += out.total;
+      }
+      run_total += out.total;
     }
-  } else {
-    if (tile == 0 && lane == 0) {
-      d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;
+    if (t + 1 < t1) {
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
+      }
     }
+  }
+
+  // the run is complete: make its total visible, resolve its offset, publish the prefix
+  if (!base_known) {
+    scan_publish(sc, gunit, unit == 0u ? kFlagPrefix : kFlagAggregate, run_total);
+    excl = scan_lookback(sc, gunit, d.first_unit, aborted);
+  }
+  if (unit != 0u || base_known) scan_publish(sc, gunit, aborted ? kFlagAbort : kFlagPrefix, excl + run_total);
+
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  if (!aborted) {
+    for (uint32_t i = (uint32_t)lane; i < staged; i += kWave) {
+      const uint32_t p = excl + i;
+      if (p < d.cap) { d.idx[p] = stage->idx[i]; d.val[p] = stage->val[i]; }
+    }
+    if ((uint32_t)lane < t1 - t0) d.tile_ptr[t0 + (uint32_t)lane] = excl + tile_off;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the staging area is reused by the next run
+  if (lane == 0) {
+    if (t1 == d.n_tiles) {
+      const uint32_t n_out = excl + run_total;
+      d.tile_ptr[d.n_tiles] = n_out;
+      d.status[0] = n_out;
+      d.status[1] = (n_out > d.cap) ? 1u : 0u;
+      d.status[3] = 0u;
+      if (!aborted) d.status[2] = 0u;
+    }
+    if (aborted) d.status[2] = 1u;
+  }
+}
+
+// ------------------------------------------------------------------ one tile without outliers (NONE)
+template <int BITS, bool ASYM, int E>
+__device__ __forceinline__ void compress_tile_plain(const TensorDesc& d, uint32_t tile) {
+  uint32_t raw[E][4];
+  load_tile<E>(d, tile, raw);
+  TileOutliers<E> out;
+  encode_tile<kModeNone, BITS, ASYM, E>(d, tile, raw, out);
+  if (tile == 0 && lane_id() == 0) {
+    d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;
   }
 }
 
