@@ -16,7 +16,9 @@
  *   - outliers are single elements picked by |x| > tau, by x^2 > k^2 * var of the
  *     statistics group, or as the k largest magnitudes of the group (the paper
  *     picks whole channels by Z-score; same extract / zero / quantise structure);
- *   - X / S is evaluated as X * (D / max): one division per group;
+ *   - X / S is evaluated as X * (D / max): one binary32 division per group; the product itself is
+ *     not rounded before it is rounded to the nearest integer (binary64 holds the product of two
+ *     binary32 numbers exactly), so the code is the integer nearest to X * inv;
  *   - "nearest rounding" is round-half-to-even;
  *   - sums for the variance are canonical pairwise (binary tree) binary32 sums;
  *   - Inf and NaN are always outliers when outliers are kept; they never enter
@@ -146,12 +148,15 @@ int oracle_select_outliers(const oracle_method *m, const uint16_t *x, size_t n, 
 
 /* ---------- step 4: quantisation of one group ---------- */
 
-static int8_t clip_code(float r, int q) {
+static int8_t clip_code(double r, int q) {
   /* written so that a NaN lands on the lower bound */
-  if (!(r >= (float)(-q))) r = (float)(-q);
-  if (r > (float)(q - 1)) r = (float)(q - 1);
+  if (!(r >= (double)(-q))) r = (double)(-q);
+  if (r > (double)(q - 1)) r = (double)(q - 1);
   return (int8_t)r;
 }
+
+/* nearest integer (ties to even) of the exact product of two binary32 numbers */
+static double round_product(float x, float inv) { return rint((double)x * (double)inv); }
 
 /* Eq. 2:  S = max|X| / D,  code = clip(round(X / S), -Q, Q-1),  D = Q (paper) or Q-1. */
 static void quant_sym(const oracle_method *m, const float *y, size_t g, int8_t *codes, float *scale) {
@@ -166,7 +171,7 @@ static void quant_sym(const oracle_method *m, const float *y, size_t g, int8_t *
     inv = d / a;
     if (inv > FLT_MAX) inv = FLT_MAX; /* a is so small that D/a overflows */
   }
-  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(rintf(y[i] * inv), q);
+  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(round_product(y[i], inv), q);
 }
 
 /* Eq. 3:  O = (max+min)/2,  S = (max-min)/D2,  code = clip(round((X-O)/S), -Q, Q-1),
@@ -189,7 +194,7 @@ static void quant_asym(const oracle_method *m, const float *y, size_t g, int8_t 
     inv = d2 / r;
     if (inv > FLT_MAX) inv = FLT_MAX;
   }
-  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(rintf((y[i] - o) * inv), q);
+  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(round_product(y[i] - o, inv), q);
 }
 
 /* ---------- steps 1-4 ---------- */

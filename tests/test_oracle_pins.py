@@ -279,8 +279,13 @@ def test_sym_codes_are_nearest_in_exact_arithmetic(bits, rule):
             nearest = math.floor(target + Fraction(1, 2))
             if target + Fraction(1, 2) == nearest and nearest % 2 == 1:
                 nearest -= 1  # half goes to even
-            exact_match += (nearest == code)
-    assert exact_match >= 0.999 * x.size
+            if nearest == code:
+                exact_match += 1
+            else:
+                # only an exact or near tie may go to the other neighbour (bf16 inputs make exact
+                # ties common, and D / max carries one rounding when D is not a power of two)
+                assert abs(abs(target - math.floor(target)) - Fraction(1, 2)) <= abs(r) * Fraction(1, 2 ** 22)
+    assert exact_match >= 0.99 * x.size
 
 
 @pytest.mark.parametrize("bits", [4, 8])
