@@ -83,6 +83,7 @@ typedef struct adacc_method {
  *   status   4 uint32: [0] number of outliers found, [1] 1 if it exceeds max_outliers
  *            (the stream then holds the first max_outliers; the blob is not usable),
  *            [2] 1 if the kernel gave up waiting on another tile (blob not usable), [3] 0.
+ *            The rest of the 256-byte status block is scrap space of the kernels.
  */
 typedef struct adacc_layout {
   uint64_t codes_off, scales_off, zp_off, tile_ptr_off, idx_off, val_off, status_off;

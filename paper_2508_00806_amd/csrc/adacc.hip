@@ -19,16 +19,20 @@ namespace adacc {
 // ---- single tensor, compress.  With outliers: run = 4 * workgroup + wavefront, and the grid is
 // exactly ceil(n_units / 4) workgroups, because the chained scan relies on runs being started
 // in index order.  NONE: tiles are independent, grid-stride loop over tiles.
+#ifndef ADACC_COMPRESS_MIN_WAVES
+#define ADACC_COMPRESS_MIN_WAVES 1
+#endif
 template <int MODE, int BITS, bool ASYM, int E>
-__global__ __launch_bounds__(kThreads) void compress_kernel(TensorDesc d, uint64_t* state, uint32_t tag,
-                                                            uint32_t spin_limit) {
+__global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
+                                                                                      uint64_t* state2, uint32_t tag,
+                                                                                      uint32_t spin_limit) {
   const uint32_t wave = threadIdx.x / kWave;
   if constexpr (MODE == kModeNone) {
     for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
       compress_tile_plain<BITS, ASYM, E>(d, t);
   } else {
     __shared__ WaveStage stage[kWavesPerWg];
-    const ScanCtx sc{state, tag, spin_limit};
+    const ScanCtx sc{state1, state2, tag, spin_limit};
     const uint32_t u = blockIdx.x * kWavesPerWg + wave;
     if (u < d.n_units) compress_run<MODE, BITS, ASYM, E>(d, u, sc, &stage[wave]);
   }
@@ -80,11 +84,12 @@ __device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t
 // One launch for a table of tensors: runs are numbered across the table; a wavefront finds
 // its tensor by binary search and dispatches on that tensor's method.
 __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                  uint32_t total_units, uint64_t* state,
-                                                                  uint32_t tag, uint32_t spin_limit) {
+                                                                  uint32_t total_units, uint64_t* state1,
+                                                                  uint64_t* state2, uint32_t tag,
+                                                                  uint32_t spin_limit) {
   __shared__ WaveStage stage[kWavesPerWg];
   const uint32_t wave = threadIdx.x / kWave;
-  const ScanCtx sc{state, tag, spin_limit};
+  const ScanCtx sc{state1, state2, tag, spin_limit};
   const uint32_t g = blockIdx.x * kWavesPerWg + wave;
   if (g >= total_units) return;
   const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<true>(table, n, g));
@@ -240,21 +245,32 @@ static void fill_layout(const adacc_method* m, uint64_t numel, const Plan& p, ad
   L->n_tiles = p.n_tiles;
 }
 
-// Tiles per run: enough runs to fill the machine a few times over, few enough that the
-// look-back (whose reach grows with the number of runs in flight) stays short.
-static uint32_t tiles_per_unit(uint64_t tiles_in_launch, int cus) {
-  const uint64_t target = (uint64_t)cus * (uint64_t)env_int("ADACC_UNITS_PER_CU", 32);
-  uint64_t t = (tiles_in_launch + target - 1) / target;
-  const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 16);
-  if (t > tmax) t = tmax;
-  if (t > 32) t = 32;
-  if (t < 1) t = 1;
-  return (uint32_t)t;
+// Wavefronts of `kernel` that the device can hold at once.
+static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
+  int wgs = 0;
+  const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs, kernel, kThreads, 0);
+  if (e != hipSuccess) return hip_fail(e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+  if (wgs < 1) wgs = 1;
+  *waves = (uint32_t)(cus * wgs * kWavesPerWg);
+  return ADACC_OK;
+}
+
+// Tiles per run.  All runs take about the same time, so the launch proceeds in rounds of as many
+// runs as the device holds wavefronts; a last round that is only partly filled is wasted time.
+// The tiles are therefore cut into a whole number of full rounds (one, unless a run would get
+// longer than the limit), which also keeps the look-back short: its reach grows with the
+// number of runs in flight, not with the number of tiles.
+static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
+  const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64) > 64 ? 64 : (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64);
+  if (tiles_in_launch <= capacity) return 1u;
+  const uint64_t rounds = (tiles_in_launch + (uint64_t)capacity * tmax - 1) / ((uint64_t)capacity * tmax);
+  const uint64_t units = (uint64_t)capacity * rounds;
+  return (uint32_t)((tiles_in_launch + units - 1) / units);
 }
 
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
                       void* blob, void* dst, int dst_dtype, uint32_t first_tile, uint32_t tpu, uint32_t first_unit,
-                      TensorDesc* d) {
+                      uint32_t first_block, TensorDesc* d) {
   std::memset(d, 0, sizeof *d);
   unsigned char* b = static_cast<unsigned char*>(blob);
   d->src = static_cast<const uint16_t*>(src);
@@ -272,12 +288,17 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
   d->tiles_per_unit = tpu;
   d->n_units = (p.n_tiles + tpu - 1) / tpu;
   d->first_unit = first_unit;
+  d->first_block = first_block;
   d->lgq = p.lgq;
   d->lgs = p.lgs;
   d->cap = m->max_outliers;
   d->topk = m->topk;
   d->param = p.param;
   d->divisor = p.divisor;
+  {
+    int ex = 0;
+    d->inv_divisor = (std::frexp(p.divisor, &ex) == 0.5f) ? 1.0f / p.divisor : 0.0f;  // exact for a power of two
+  }
   d->variant = p.variant;
   d->dst_f32 = dst_dtype == ADACC_DST_F32 ? 1u : 0u;
 }
@@ -298,7 +319,7 @@ static int grid_for(uint32_t n_tiles, uint32_t* grid) {
   return ADACC_OK;
 }
 
-typedef void (*CompressFn)(TensorDesc, uint64_t*, uint32_t, uint32_t);
+typedef void (*CompressFn)(TensorDesc, uint64_t*, uint64_t*, uint32_t, uint32_t);
 typedef void (*DecompressFn)(TensorDesc, uint32_t);
 
 template <int MODE, int BITS, bool ASYM>
@@ -356,7 +377,12 @@ static int clear_device(void* mem, uint64_t bytes, hipStream_t s) {
   return launch_check("workspace_clear_kernel");
 }
 
-// batch workspace: [state 8*total_tiles, padded][table n*sizeof(TensorDesc)]
+// scan state of a launch over `tiles` tiles: [state1: one word per run, at most one per tile]
+// [state2: one word per block of 64 runs]; every tensor of a batch starts a new block
+static uint64_t state1_bytes(uint64_t tiles) { return align256(8ull * tiles); }
+static uint64_t state2_bytes(uint64_t tiles, uint64_t tensors) { return align256(8ull * (tiles / kWave + tensors + 1)); }
+
+// batch workspace: [state1][state2][table n*sizeof(TensorDesc)]
 struct BatchPlan {
   uint32_t total_tiles;
   uint64_t table_off, bytes;
@@ -364,7 +390,7 @@ struct BatchPlan {
 static BatchPlan batch_plan(uint32_t total_tiles, uint32_t n_active) {
   BatchPlan b;
   b.total_tiles = total_tiles;
-  b.table_off = align256(8ull * total_tiles);
+  b.table_off = state1_bytes(total_tiles) + state2_bytes(total_tiles, n_active);
   b.bytes = align256(b.table_off + (uint64_t)(n_active ? n_active : 1) * sizeof(TensorDesc));
   return b;
 }
@@ -404,7 +430,7 @@ uint64_t adacc_workspace_bytes(const adacc_method* method, uint64_t numel) {
   if (!method) return 0;
   Plan p;
   if (make_plan(method, numel, &p) != ADACC_OK || p.noop || !p.outliers) return 0;
-  return align256(8ull * p.n_tiles);
+  return state1_bytes(p.n_tiles) + state2_bytes(p.n_tiles, 1);
 }
 
 int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, void* hip_stream) {
@@ -434,14 +460,22 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   if (misaligned(src, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   if (p.outliers) {
     if (!ws || !ws->device_mem) return ADACC_ENULL;
-    if (ws->bytes < 8ull * p.n_tiles) return ADACC_ESIZE;
+    if (ws->bytes < state1_bytes(p.n_tiles) + state2_bytes(p.n_tiles, 1)) return ADACC_ESIZE;
     if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   }
   int cus = 0;
   rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
   if (rc != ADACC_OK) return rc;
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096);
+  uint32_t tpu = 1u;
+  if (p.outliers) {
+    uint32_t capacity = 0;
+    rc = wave_capacity(reinterpret_cast<const void*>(fn), cus, &capacity);
+    if (rc != ADACC_OK) return rc;
+    tpu = tiles_per_unit(p.n_tiles, capacity);
+  }
   TensorDesc d;
-  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, p.outliers ? tiles_per_unit(p.n_tiles, cus) : 1u, 0, &d);
+  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, tpu, 0, 0, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t grid = 0, tag = 0;
   if (p.outliers) {
@@ -451,9 +485,9 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
     rc = grid_for(p.n_tiles, &grid);
   }
   if (rc != ADACC_OK) return rc;
-  CompressFn fn = compress_fn(method, p.tile_elems == 4096);
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d,
-                     p.outliers ? static_cast<uint64_t*>(ws->device_mem) : nullptr, tag, spin_limit());
+  uint64_t* state1 = p.outliers ? static_cast<uint64_t*>(ws->device_mem) : nullptr;
+  uint64_t* state2 = p.outliers ? state1 + state1_bytes(p.n_tiles) / 8 : nullptr;
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, state1, state2, tag, spin_limit());
   return launch_check("compress_kernel");
 }
 
@@ -471,7 +505,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, &d);
+  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, 0, &d);
   uint32_t grid = 0;
   rc = grid_for(p.n_tiles, &grid);
   if (rc != ADACC_OK) return rc;
@@ -510,7 +544,7 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
                        const void* const* srcs, void* const* blobs, const uint64_t* blob_bytes, void* const* dsts,
                        int dst_dtype, bool compress, uint32_t tpu, std::vector<TensorDesc>* table,
                        uint32_t* total_units) {
-  uint32_t first = 0, first_unit = 0;
+  uint32_t first = 0, first_unit = 0, first_block = 0;
   for (uint32_t i = 0; i < n; ++i) {
     if (plans[i].noop) continue;
     if (!blobs[i]) return ADACC_ENULL;
@@ -522,10 +556,11 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
     if (compress ? misaligned(srcs[i], 16) : misaligned(dsts[i], 16)) return ADACC_EALIGN;
     TensorDesc d;
     fill_desc(&methods[i], numels[i], plans[i], L, compress ? srcs[i] : nullptr, blobs[i], compress ? nullptr : dsts[i],
-              dst_dtype, first, tpu, first_unit, &d);
+              dst_dtype, first, tpu, first_unit, first_block, &d);
     table->push_back(d);
     first += plans[i].n_tiles;
     first_unit += d.n_units;
+    first_block += (d.n_units + kWave - 1) / kWave;
   }
   if (total_units) *total_units = first_unit;
   return ADACC_OK;
@@ -551,9 +586,12 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   int cus = 0;
   rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
+  uint32_t capacity = 0;
+  rc = wave_capacity(reinterpret_cast<const void*>(compress_batch_kernel), cus, &capacity);
+  if (rc != ADACC_OK) return rc;
   table.clear();
-  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, tiles_per_unit(total, cus),
-                   &table, &total_units);
+  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true,
+                   tiles_per_unit(total, capacity), &table, &total_units);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t tag = 0;
@@ -566,7 +604,8 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   const uint32_t grid = (total_units + kWavesPerWg - 1) / kWavesPerWg;
   hipLaunchKernelGGL(compress_batch_kernel, dim3(grid), dim3(kThreads), 0, s,
                      reinterpret_cast<const TensorDesc*>(mem + bp.table_off), (uint32_t)table.size(), total_units,
-                     reinterpret_cast<uint64_t*>(mem), tag, spin_limit());
+                     reinterpret_cast<uint64_t*>(mem), reinterpret_cast<uint64_t*>(mem + state1_bytes(total)), tag,
+                     spin_limit());
   return launch_check("compress_batch_kernel");
 }
 

@@ -41,19 +41,21 @@ struct TensorDesc {
   uint32_t tiles_per_unit;  // compress: tiles one wavefront handles one after the other ("run")
   uint32_t n_units;         // ceil(n_tiles / tiles_per_unit)
   uint32_t first_unit;      // launch-wide id of this tensor's run 0 (compress)
-  uint32_t pad0;
+  uint32_t first_block;     // launch-wide id of this tensor's first block of 64 runs (compress)
   uint32_t lgq;         // log2(quant group)
   uint32_t lgs;         // log2(stat group) (STD / TOPK)
   uint32_t cap;         // capacity of idx / val
   uint32_t topk;
   float param;          // ABS: tau.  STD: k*k
   float divisor;        // D of Eq. 2 resp. Eq. 3 (2^(b-1), 2^b, or one less)
+  float inv_divisor;    // 1/D when D is a power of two (the paper's rule), else 0
+  uint32_t pad1;
   uint32_t variant;     // index into the instantiation table
   uint32_t dst_f32;     // decompress: 1 = binary32 output
 };
 
-// Scan workspace: one 64-bit state word per run of tiles, high half = (epoch << 2) | flag, low half =
-// value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
+// Scan workspace: one 64-bit state word per run of tiles and one per block of 64 runs, high half
+// = (epoch << 2) | flag, low half = value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
 // words written by earlier launches carry another epoch and read as empty, so the buffer is
 // cleared only once, when it is set up, and again when the 30-bit epoch wraps.
 enum : uint32_t { kFlagEmpty = 0, kFlagAggregate = 1, kFlagPrefix = 2, kFlagAbort = 3 };

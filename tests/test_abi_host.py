@@ -63,7 +63,7 @@ def test_layout_closed_form(L):
     # no-op: nothing
     lay0 = adacc.layout_of(adacc.NOOP, 12345)
     assert lay0.total_bytes == 0 and lay0.n_tiles == 0
-    assert adacc.workspace_bytes(m, n) == a(8 * 37)
+    assert adacc.workspace_bytes(m, n) == a(8 * 37) + a(8 * 2)
     assert adacc.workspace_bytes(m3, 64 * 33) == 0
 
 
@@ -151,7 +151,7 @@ def test_batch_validation(L):
     need = adacc.batch_workspace_bytes(ms, numels)
     tiles = 5 + (128 * 100 + 2047) // 2048
     a = lambda v: (v + 255) // 256 * 256
-    assert need >= a(8 * tiles) + 2 * 128
+    assert need >= a(8 * tiles) + a(8 * 3) + 2 * 128
     n = 3
     cms = (adacc.CMethod * n)(*[m.c() for m in ms])
     cn = (ctypes.c_uint64 * n)(*numels)
