@@ -22,19 +22,19 @@ namespace adacc {
 #ifndef ADACC_COMPRESS_MIN_WAVES
 #define ADACC_COMPRESS_MIN_WAVES 1
 #endif
-template <int MODE, int BITS, bool ASYM, int E>
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
 __global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
                                                                                       uint64_t* state2, uint32_t tag,
                                                                                       uint32_t spin_limit) {
   const uint32_t wave = threadIdx.x / kWave;
   if constexpr (MODE == kModeNone) {
     for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-      compress_tile_plain<BITS, ASYM, E>(d, t);
+      compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
   } else {
     __shared__ WaveStage stage[kWavesPerWg];
     const ScanCtx sc{state1, state2, tag, spin_limit};
     const uint32_t u = blockIdx.x * kWavesPerWg + wave;
-    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E>(d, u, sc, &stage[wave]);
+    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E, ROWWISE>(d, u, sc, &stage[wave]);
   }
 }
 
@@ -62,23 +62,32 @@ __device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_
 template <int MODE>
 __device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
                                                        WaveStage* stage) {
+  if (d.rowwise) {  // groups inside a row: E is always 4
+    switch (d.variant & 7u) {
+      case 0: compress_run<MODE, 4, false, 4, true>(d, unit, sc, stage); break;
+      case 2: compress_run<MODE, 4, true, 4, true>(d, unit, sc, stage); break;
+      case 4: compress_run<MODE, 8, false, 4, true>(d, unit, sc, stage); break;
+      default: compress_run<MODE, 8, true, 4, true>(d, unit, sc, stage); break;
+    }
+    return;
+  }
   switch (d.variant & 7u) {
-    case 0: compress_run<MODE, 4, false, 4>(d, unit, sc, stage); break;
-    case 1: compress_run<MODE, 4, false, 8>(d, unit, sc, stage); break;
-    case 2: compress_run<MODE, 4, true, 4>(d, unit, sc, stage); break;
-    case 3: compress_run<MODE, 4, true, 8>(d, unit, sc, stage); break;
-    case 4: compress_run<MODE, 8, false, 4>(d, unit, sc, stage); break;
-    case 5: compress_run<MODE, 8, false, 8>(d, unit, sc, stage); break;
-    case 6: compress_run<MODE, 8, true, 4>(d, unit, sc, stage); break;
-    default: compress_run<MODE, 8, true, 8>(d, unit, sc, stage); break;
+    case 0: compress_run<MODE, 4, false, 4, false>(d, unit, sc, stage); break;
+    case 1: compress_run<MODE, 4, false, 8, false>(d, unit, sc, stage); break;
+    case 2: compress_run<MODE, 4, true, 4, false>(d, unit, sc, stage); break;
+    case 3: compress_run<MODE, 4, true, 8, false>(d, unit, sc, stage); break;
+    case 4: compress_run<MODE, 8, false, 4, false>(d, unit, sc, stage); break;
+    case 5: compress_run<MODE, 8, false, 8, false>(d, unit, sc, stage); break;
+    case 6: compress_run<MODE, 8, true, 4, false>(d, unit, sc, stage); break;
+    default: compress_run<MODE, 8, true, 8, false>(d, unit, sc, stage); break;
   }
 }
 
-template <int BITS, bool ASYM, int E>
+template <int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t unit) {
   const uint32_t t0 = unit * d.tiles_per_unit;
   const uint32_t t1 = (t0 + d.tiles_per_unit < d.n_tiles) ? t0 + d.tiles_per_unit : d.n_tiles;
-  for (uint32_t t = t0; t < t1; ++t) compress_tile_plain<BITS, ASYM, E>(d, t);
+  for (uint32_t t = t0; t < t1; ++t) compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
 }
 
 // One launch for a table of tensors: runs are numbered across the table; a wavefront finds
@@ -97,15 +106,24 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDe
   const uint32_t unit = g - d.first_unit;
   switch (d.variant >> 3) {
     case kModeNone:
+      if (d.rowwise) {
+        switch (d.variant & 7u) {
+          case 0: compress_plain_run<4, false, 4, true>(d, unit); break;
+          case 2: compress_plain_run<4, true, 4, true>(d, unit); break;
+          case 4: compress_plain_run<8, false, 4, true>(d, unit); break;
+          default: compress_plain_run<8, true, 4, true>(d, unit); break;
+        }
+        break;
+      }
       switch (d.variant & 7u) {
-        case 0: compress_plain_run<4, false, 4>(d, unit); break;
-        case 1: compress_plain_run<4, false, 8>(d, unit); break;
-        case 2: compress_plain_run<4, true, 4>(d, unit); break;
-        case 3: compress_plain_run<4, true, 8>(d, unit); break;
-        case 4: compress_plain_run<8, false, 4>(d, unit); break;
-        case 5: compress_plain_run<8, false, 8>(d, unit); break;
-        case 6: compress_plain_run<8, true, 4>(d, unit); break;
-        default: compress_plain_run<8, true, 8>(d, unit); break;
+        case 0: compress_plain_run<4, false, 4, false>(d, unit); break;
+        case 1: compress_plain_run<4, false, 8, false>(d, unit); break;
+        case 2: compress_plain_run<4, true, 4, false>(d, unit); break;
+        case 3: compress_plain_run<4, true, 8, false>(d, unit); break;
+        case 4: compress_plain_run<8, false, 4, false>(d, unit); break;
+        case 5: compress_plain_run<8, false, 8, false>(d, unit); break;
+        case 6: compress_plain_run<8, true, 4, false>(d, unit); break;
+        default: compress_plain_run<8, true, 8, false>(d, unit); break;
       }
       break;
     case kModeAbs: compress_dispatch_mode<kModeAbs>(d, unit, sc, &stage[wave]); break;
@@ -190,6 +208,7 @@ struct Plan {  // everything derived from (method, numel)
   bool noop;
   bool outliers;
   uint32_t tile_elems, n_tiles, lgq, lgs, variant;
+  bool rowwise;  // every group lies inside a 512-element row and both kinds of group coincide
   float param, divisor;
 };
 
@@ -220,6 +239,8 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   p->lgq = ilog2(m->quant_group);
   p->lgs = ilog2(gs);
   p->variant = variant_index(m->outlier_mode, m->bits, m->asym, p->tile_elems == 4096 ? 1u : 0u);
+  p->rowwise = m->outlier_mode != ADACC_OUTLIER_TOPK && m->quant_group <= 512 &&
+               (m->outlier_mode != ADACC_OUTLIER_STD || m->stat_group == m->quant_group);
   const float q = (float)(1u << (m->bits - 1));
   if (m->asym) p->divisor = m->scale_rule == ADACC_SCALE_PAPER ? 2.0f * q : 2.0f * q - 1.0f;
   else p->divisor = m->scale_rule == ADACC_SCALE_PAPER ? q : q - 1.0f;
@@ -252,6 +273,9 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
   if (e != hipSuccess) return hip_fail(e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
   if (wgs < 1) wgs = 1;
   *waves = (uint32_t)(cus * wgs * kWavesPerWg);
+  const int pct = env_int("ADACC_CAPACITY_PCT", 100);  // experiment knob
+  *waves = (uint32_t)((uint64_t)*waves * (uint64_t)pct / 100u);
+  if (*waves < (uint32_t)kWavesPerWg) *waves = kWavesPerWg;
   return ADACC_OK;
 }
 
@@ -300,6 +324,7 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
     d->inv_divisor = (std::frexp(p.divisor, &ex) == 0.5f) ? 1.0f / p.divisor : 0.0f;  // exact for a power of two
   }
   d->variant = p.variant;
+  d->rowwise = p.rowwise ? 1u : 0u;
   d->dst_f32 = dst_dtype == ADACC_DST_F32 ? 1u : 0u;
 }
 
@@ -323,20 +348,21 @@ typedef void (*CompressFn)(TensorDesc, uint64_t*, uint64_t*, uint32_t, uint32_t)
 typedef void (*DecompressFn)(TensorDesc, uint32_t);
 
 template <int MODE, int BITS, bool ASYM>
-static CompressFn compress_fn_e(bool e8) {
-  return e8 ? compress_kernel<MODE, BITS, ASYM, 8> : compress_kernel<MODE, BITS, ASYM, 4>;
+static CompressFn compress_fn_e(bool e8, bool rowwise) {
+  if (rowwise) return compress_kernel<MODE, BITS, ASYM, 4, true>;
+  return e8 ? compress_kernel<MODE, BITS, ASYM, 8, false> : compress_kernel<MODE, BITS, ASYM, 4, false>;
 }
 template <int MODE>
-static CompressFn compress_fn_m(uint32_t bits, uint32_t asym, bool e8) {
-  if (bits == 4) return asym ? compress_fn_e<MODE, 4, true>(e8) : compress_fn_e<MODE, 4, false>(e8);
-  return asym ? compress_fn_e<MODE, 8, true>(e8) : compress_fn_e<MODE, 8, false>(e8);
+static CompressFn compress_fn_m(uint32_t bits, uint32_t asym, bool e8, bool rowwise) {
+  if (bits == 4) return asym ? compress_fn_e<MODE, 4, true>(e8, rowwise) : compress_fn_e<MODE, 4, false>(e8, rowwise);
+  return asym ? compress_fn_e<MODE, 8, true>(e8, rowwise) : compress_fn_e<MODE, 8, false>(e8, rowwise);
 }
-static CompressFn compress_fn(const adacc_method* m, bool e8) {
+static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise) {
   switch (m->outlier_mode) {
-    case ADACC_OUTLIER_NONE: return compress_fn_m<kModeNone>(m->bits, m->asym, e8);
-    case ADACC_OUTLIER_ABS: return compress_fn_m<kModeAbs>(m->bits, m->asym, e8);
-    case ADACC_OUTLIER_STD: return compress_fn_m<kModeStd>(m->bits, m->asym, e8);
-    default: return compress_fn_m<kModeTopk>(m->bits, m->asym, e8);
+    case ADACC_OUTLIER_NONE: return compress_fn_m<kModeNone>(m->bits, m->asym, e8, rowwise);
+    case ADACC_OUTLIER_ABS: return compress_fn_m<kModeAbs>(m->bits, m->asym, e8, rowwise);
+    case ADACC_OUTLIER_STD: return compress_fn_m<kModeStd>(m->bits, m->asym, e8, rowwise);
+    default: return compress_fn_m<kModeTopk>(m->bits, m->asym, e8, false);
   }
 }
 template <int BITS, bool ASYM>
@@ -466,7 +492,7 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   int cus = 0;
   rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
   if (rc != ADACC_OK) return rc;
-  CompressFn fn = compress_fn(method, p.tile_elems == 4096);
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise);
   uint32_t tpu = 1u;
   if (p.outliers) {
     uint32_t capacity = 0;

@@ -49,7 +49,7 @@ struct TensorDesc {
   float param;          // ABS: tau.  STD: k*k
   float divisor;        // D of Eq. 2 resp. Eq. 3 (2^(b-1), 2^b, or one less)
   float inv_divisor;    // 1/D when D is a power of two (the paper's rule), else 0
-  uint32_t pad1;
+  uint32_t rowwise;     // compress: 1 = every group lies inside a row (row-at-a-time encoder)
   uint32_t variant;     // index into the instantiation table
   uint32_t dst_f32;     // decompress: 1 = binary32 output
 };

@@ -24,19 +24,6 @@ __device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w
 #define ADACC_ELEM_F32(oct, e) (((e)&1) ? widen_hi((oct)[(e) >> 1]) : widen_lo((oct)[(e) >> 1]))
 #define ADACC_ELEM_MAG(oct, e) ((((e)&1) ? ((oct)[(e) >> 1] >> 16) : (oct)[(e) >> 1]) & 0x7FFFu)
 
-// Tells the compiler that the values may have changed, so that anything derived from them (the
-// squares, the keys) is formed again where it is next needed instead of being kept in
-// registers across a whole phase: a multiply is one instruction, a live register costs
-// occupancy.  No instruction is emitted.
-template <int E>
-__device__ __forceinline__ void forget_derived(float (&x)[E][kOct]) {
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) asm volatile("" : "+v"(x[j][e]));
-  }
-}
-
 // compile-time loop: body(std::integral_constant<int, J>) for J = 0..N-1.  Used where a
 // data-dependent inner loop would otherwise keep the compiler from unrolling, which would
 // turn the per-row register arrays into scratch memory.
@@ -225,7 +212,10 @@ __device__ __forceinline__ uint32_t scan_poll_sum(const ScanCtx& sc, const uint6
       }
       if (__builtin_amdgcn_ballot_w64(flag == kFlagEmpty) == 0ull) break;
       if (++polls > sc.spin_limit) { aborted = true; break; }
-      __builtin_amdgcn_s_sleep(2);
+#ifndef ADACC_POLL_SLEEP
+#define ADACC_POLL_SLEEP 4
+#endif
+      __builtin_amdgcn_s_sleep(ADACC_POLL_SLEEP);  // a short pause between polls (units of 64 clocks)
     }
     if (__builtin_amdgcn_ballot_w64(flag == kFlagAbort) != 0ull) aborted = true;
     sum += value;
@@ -257,126 +247,92 @@ __device__ __forceinline__ uint32_t pack_nibbles8(const uint32_t (&c)[kOct]) {
   return w;
 }
 
-// ------------------------------------------------------------------ outlier test of the rows of a tile
-struct RowCtx {
-  uint64_t numel, lane_base;
-  float param;             // ABS: tau
-  uint32_t topk_lane_pos;  // TOPK: position of the lane's first element in its group's row
-  int topk_rows;           // TOPK: rows per group
+// ------------------------------------------------------------------ tile geometry, loads and stores
+// A tile is addressed as a wavefront-uniform base (kept in scalar registers) plus a 32-bit
+// lane offset, so that address arithmetic costs no vector instructions.
+template <int E>
+struct TileGeo {
+  uint64_t base;      // uniform: index of the tile's first element
+  uint32_t rem;       // uniform: elements of the tensor from `base` on, at most E*512 (a multiple of 8, > 0)
+  uint32_t lane_off;  // lane * 8
+  bool full;          // uniform: rem == E*512
 };
-
-// For every row j: which elements are outliers (mask[j], bit e = element e), the lane's extreme
-// values of the inlier view y (outliers, Inf and NaN count as zero), the number of outliers of
-// the row in lower lanes, and the row's outlier count.  A row without outliers - the common
-// case - costs a compare and half a max per element beyond the widening; the mask, the
-// positions and the exact extremes are only worked out behind a wavefront-uniform branch.
-// y itself is not kept: the quantisation step forms it again from x and the mask.
-// In NONE mode the "outliers" are the Inf / NaN elements: they are zeroed but reported nowhere.
-// CHECK_NONFINITE: additionally test every element for Inf / NaN (statistics were poisoned).
-// ext0 / ext1: symmetric: ext0 = max |y|.  asymmetric: ext0 = max y, ext1 = min y.
-template <int MODE, bool ASYM, bool CHECK_NONFINITE, int E>
-__device__ __forceinline__ void outlier_rows(const RowCtx& rc, const float (&xs)[E][kOct], const float (&limit)[E],
-                                             const uint32_t (&kth)[E], float (&ext0)[E], float (&ext1)[E],
-                                             uint32_t (&mask)[E], uint32_t (&lane_excl)[E], uint32_t (&row_cnt)[E]) {
-  constexpr float kInf = __builtin_inff();
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    float x[kOct];
-    bool o[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) {
-      x[e] = xs[j][e];
-      if constexpr (MODE == kModeNone) {
-        o[e] = !(fabsf(x[e]) < kInf);            // Inf / NaN: nothing is kept aside, the value counts as zero
-      } else if constexpr (MODE == kModeAbs) {
-        o[e] = !(fabsf(x[e]) <= rc.param);       // |x| > tau, and also Inf / NaN
-      } else if constexpr (MODE == kModeStd) {
-        o[e] = x[e] * x[e] > limit[j];
-      } else {
-        const bool valid = (rc.lane_base + (uint64_t)j * kRow) < rc.numel;
-        const uint32_t row_pos = ((uint32_t)(j & (rc.topk_rows - 1)) << 9) | rc.topk_lane_pos;
-        const uint32_t key = (__float_as_uint(x[e]) & 0x7FFF0000u) | (0xFFFFu - (row_pos | (uint32_t)e));
-        o[e] = (key >= kth[j]) && valid;         // rows past the end hold zeros, which TOPK would rank too
-      }
-      if constexpr (CHECK_NONFINITE) o[e] = o[e] || ((__float_as_uint(x[e]) & 0x7FFFFFFFu) >= 0x7F800000u);
-    }
-    uint64_t b[kOct];
-    uint64_t any = 0ull;
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) { b[e] = __builtin_amdgcn_ballot_w64(o[e]); any |= b[e]; }
-    if (any != 0ull) {
-      uint32_t m = 0u, below = 0u, cnt = 0u;
-      float y0 = o[0] ? 0.0f : x[0];
-      float mx = ASYM ? y0 : fabsf(y0), mn = y0;
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) {
-        m |= o[e] ? (1u << e) : 0u;
-        below += lanes_below(b[e]);
-        cnt += (uint32_t)__popcll(b[e]);
-        const float ye = o[e] ? 0.0f : x[e];
-        if constexpr (ASYM) { mx = fmaxf(mx, ye); mn = fminf(mn, ye); }
-        else mx = fmaxf(mx, fabsf(ye));
-      }
-      mask[j] = m;
-      lane_excl[j] = below;
-      row_cnt[j] = cnt;
-      ext0[j] = mx;
-      ext1[j] = mn;
-    } else {
-      // no outlier in the row, hence every element is finite and y = x
-      float mx = ASYM ? x[0] : fabsf(x[0]), mn = x[0];
-#pragma unroll
-      for (int e = 1; e < kOct; ++e) {
-        if constexpr (ASYM) { mx = fmaxf(mx, x[e]); mn = fminf(mn, x[e]); }
-        else mx = fmaxf(mx, fabsf(x[e]));
-      }
-      mask[j] = 0u;
-      lane_excl[j] = 0u;
-      row_cnt[j] = 0u;
-      ext0[j] = mx;
-      ext1[j] = mn;
-    }
-  }
+template <int E>
+__device__ __forceinline__ TileGeo<E> tile_geo(const TensorDesc& d, uint32_t tile) {
+  TileGeo<E> g;
+  g.base = (uint64_t)tile * (uint64_t)(E * kRow);
+  const uint64_t left = d.numel - g.base;
+  g.rem = left < (uint64_t)(E * kRow) ? (uint32_t)left : (uint32_t)(E * kRow);
+  g.lane_off = (uint32_t)lane_id() * kOct;
+  g.full = g.rem == (uint32_t)(E * kRow);
+  return g;
 }
 
-// ------------------------------------------------------------------ one tile
-// ---- a1: load (16 bytes per lane per row; rows past the end of the tensor read as zero).
-// The loads are issued unconditionally (octets past the end re-read the tensor's last octet
-// and are blanked afterwards): a load under a branch would make the number of loads in flight
-// unknown to the compiler's wait-count bookkeeping, which then waits for the prefetched tile
-// together with the current one.
+// ---- a1: load (16 bytes per lane per row).  The loads are issued unconditionally (octets past
+// the end of the tensor re-read its last octet and are blanked afterwards): a load under a
+// branch would make the number of loads in flight unknown to the compiler's wait-count
+// bookkeeping, which then waits for the prefetched tile together with the current one.
 template <int E>
 __device__ __forceinline__ void load_tile(const TensorDesc& d, uint32_t tile, uint32_t (&raw)[E][4]) {
-  const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
-  const uint64_t lane_base = tile_base + (uint64_t)lane_id() * kOct;
-  const uint64_t last = d.numel - kOct;  // numel is a positive multiple of 8
+  const TileGeo<E> g = tile_geo<E>(d, tile);
+  const uint16_t* sp = d.src + g.base;
+  const uint32_t last = g.rem - kOct;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-    uint64_t e0 = lane_base + (uint64_t)j * kRow;
-    e0 = e0 < last ? e0 : last;
-    const uint4 v = *reinterpret_cast<const uint4*>(d.src + e0);
+    uint32_t off = g.lane_off + (uint32_t)(j * kRow);
+    off = off < last ? off : last;
+    const uint4 v = *reinterpret_cast<const uint4*>(sp + off);
     raw[j][0] = v.x; raw[j][1] = v.y; raw[j][2] = v.z; raw[j][3] = v.w;
   }
 }
-// blank the octets of a tile that lie past the end of the tensor (uniform test: only a tensor's last tile)
+// blank the octets of a tile that lie past the end of the tensor (only a tensor's last tile can have any)
 template <int E>
-__device__ __forceinline__ void blank_tail(const TensorDesc& d, uint32_t tile, uint32_t (&raw)[E][4]) {
-  const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
-  if (tile_base + (uint64_t)(E * kRow) <= d.numel) return;
-  const uint64_t lane_base = tile_base + (uint64_t)lane_id() * kOct;
+__device__ __forceinline__ void blank_tail(const TileGeo<E>& g, uint32_t (&raw)[E][4]) {
+  if (g.full) return;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-    if (lane_base + (uint64_t)j * kRow >= d.numel) raw[j][0] = raw[j][1] = raw[j][2] = raw[j][3] = 0u;
+    if (g.lane_off + (uint32_t)(j * kRow) >= g.rem) raw[j][0] = raw[j][1] = raw[j][2] = raw[j][3] = 0u;
   }
 }
 
 // bf16 -> binary32 (exact): the 16 bits become the upper half of the word
-template <int E>
-__device__ __forceinline__ void widen_tile(const uint32_t (&raw)[E][4], float (&x)[E][kOct]) {
+__device__ __forceinline__ void widen_row(const uint32_t (&oct)[4], float (&x)[kOct]) {
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) x[j][e] = ADACC_ELEM_F32(raw[j], e);
+  for (int e = 0; e < kOct; ++e) x[e] = ADACC_ELEM_F32(oct, e);
+}
+
+// ---- a8: store the codes of one octet and the scale (offset) of its group.  Every lane stores,
+// always: a store under a branch would make the number of stores in flight unknown to the
+// compiler's wait-count bookkeeping, and the wait for the prefetched tile would then also wait
+// for these stores.  In a tensor's last tile, octets past the end go to a scrap area in the
+// unused part of the blob's status block; all lanes of a group store their (identical) scale.
+template <int BITS, bool ASYM, int E>
+__device__ __forceinline__ void store_row(const TensorDesc& d, const TileGeo<E>& g, int j, const uint32_t (&c)[kOct],
+                                          float scl, float off) {
+  const uint32_t eo = g.lane_off + (uint32_t)(j * kRow);  // element offset in the tile
+  unsigned char* cp = d.codes + g.base * BITS / 8;         // uniform
+  float* sp = d.scales + (g.base >> d.lgq);                // uniform
+  const uint32_t gl = eo >> d.lgq;
+  uint2 w8;
+  uint32_t w4 = 0u;
+  if constexpr (BITS == 8) {
+    w8.x = pack_bytes4(c[0], c[1], c[2], c[3]);
+    w8.y = pack_bytes4(c[4], c[5], c[6], c[7]);
+  } else {
+    w4 = pack_nibbles8(c);
+  }
+  if (g.full) {
+    if constexpr (BITS == 8) *reinterpret_cast<uint2*>(cp + eo) = w8;
+    else *reinterpret_cast<uint32_t*>(cp + (eo >> 1)) = w4;
+    sp[gl] = scl;
+    if constexpr (ASYM) (d.zp + (g.base >> d.lgq))[gl] = off;
+  } else {
+    const bool valid = eo < g.rem;
+    unsigned char* scrap = reinterpret_cast<unsigned char*>(d.status) + 64;
+    if constexpr (BITS == 8) *reinterpret_cast<uint2*>(valid ? cp + eo : scrap) = w8;
+    else *reinterpret_cast<uint32_t*>(valid ? cp + (eo >> 1) : scrap) = w4;
+    *(valid ? sp + gl : reinterpret_cast<float*>(scrap + 16)) = scl;
+    if constexpr (ASYM) *(valid ? d.zp + (g.base >> d.lgq) + gl : reinterpret_cast<float*>(scrap + 32)) = off;
   }
 }
 
@@ -390,98 +346,386 @@ struct TileOutliers {
   uint32_t total;         // outliers of the tile (uniform)
 };
 
-// ---- a2 .. a8 for one tile: everything except the placement of the outliers in the stream.
-template <int MODE, int BITS, bool ASYM, int E>
-__device__ __forceinline__ void encode_tile(const TensorDesc& d, uint32_t tile, float (&x)[E][kOct],
+// ------------------------------------------------------------------ per-row pieces shared by both tile encoders
+constexpr float kFltMax = 3.402823466e+38f;
+
+// STD: limit = k^2 * var from the group's sums (population variance about the mean).
+__device__ __forceinline__ float std_limit(float s1, float s2, float inv_gs, float k2) {
+  const float mean = s1 * inv_gs;
+  float var = __fmaf_rn(-mean, mean, s2 * inv_gs);
+  var = (var < 0.0f) ? 0.0f : var;  // a NaN stays a NaN: then nothing passes the test
+  return k2 * var;
+}
+
+// Bookkeeping of one row from the ballots of its 8 outlier tests: per-lane mask, number of the
+// row's outliers in lower lanes, row count.  Only rows that have outliers do the work.
+__device__ __forceinline__ void row_bookkeeping(const bool (&o)[kOct], uint32_t& mask, uint32_t& lane_excl,
+                                                uint32_t& row_cnt, bool& any_out) {
+  uint64_t b[kOct];
+  uint64_t any = 0ull;
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) { b[e] = __builtin_amdgcn_ballot_w64(o[e]); any |= b[e]; }
+  any_out = any != 0ull;
+  if (any_out) {
+    uint32_t m = 0u, below = 0u, cnt = 0u;
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      m |= o[e] ? (1u << e) : 0u;
+      below += lanes_below(b[e]);
+      cnt += (uint32_t)__popcll(b[e]);
+    }
+    mask = m; lane_excl = below; row_cnt = cnt;
+  } else {
+    mask = 0u; lane_excl = 0u; row_cnt = 0u;
+  }
+}
+
+// extremes of the inlier view of one octet: symmetric ext0 = max |y|; asymmetric ext0 = max y, ext1 = min y
+template <bool ASYM>
+__device__ __forceinline__ void row_extremes(const float (&y)[kOct], float& ext0, float& ext1) {
+  float mx = ASYM ? y[0] : fabsf(y[0]), mn = y[0];
+#pragma unroll
+  for (int e = 1; e < kOct; ++e) {
+    if constexpr (ASYM) { mx = fmaxf(mx, y[e]); mn = fminf(mn, y[e]); }
+    else mx = fmaxf(mx, fabsf(y[e]));
+  }
+  ext0 = mx; ext1 = mn;
+}
+
+// ---- a6: scale, reciprocal and offset of a group from its reduced extremes (Eq. 2 / Eq. 3)
+template <bool ASYM>
+__device__ __forceinline__ void group_scale(const TensorDesc& d, uint32_t r0, int32_t k0, int32_t k1, float& scl,
+                                            float& inv, float& off) {
+  if constexpr (!ASYM) {
+    const float am = __uint_as_float(r0);
+    // Eq. 2: S = max|X| / D.  For a power-of-two D the division is a multiplication by 1/D, same bits
+    scl = d.inv_divisor != 0.0f ? am * d.inv_divisor : am / d.divisor;
+    inv = (am != 0.0f) ? fminf(d.divisor / am, kFltMax) : 0.0f;  // one division per group
+    off = 0.0f;
+  } else {
+    // a zero extreme is +0 whatever signs the zeros had
+    const float h = key_float(k0) + 0.0f, l = key_float(k1) + 0.0f;
+    off = (h + l) * 0.5f;  // Eq. 3: O = (max+min)/2
+    const float r = h - l;
+    scl = d.inv_divisor != 0.0f ? r * d.inv_divisor : r / d.divisor;  // Eq. 3: S = (max-min) / D2
+    inv = (r != 0.0f) ? fminf(d.divisor / r, kFltMax) : 0.0f;
+  }
+}
+
+template <int MODE>
+__device__ __forceinline__ bool outlier_test(float x, float param_or_limit) {
+  if constexpr (MODE == kModeNone) return !(fabsf(x) < __builtin_inff());  // Inf / NaN: zeroed, reported nowhere
+  else if constexpr (MODE == kModeAbs) return !(fabsf(x) <= param_or_limit);  // |x| > tau, and also Inf / NaN
+  else return x * x > param_or_limit;                                         // STD
+}
+__device__ __forceinline__ bool is_nonfinite(float x) { return (__float_as_uint(x) & 0x7FFFFFFFu) >= 0x7F800000u; }
+
+// ------------------------------------------------------------------ tile encoder for groups inside a row
+// Used when every group (statistics and quantisation) lies inside one 512-element row and both
+// kinds have the same size: each row is taken from the raw octets to its stored codes in one
+// go, so nothing but the raw octets lives across rows.  LANES = lanes per group.
+template <int MODE, int BITS, bool ASYM, int E, int LANES>
+__device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
                                             TileOutliers<E>& out) {
   constexpr int Q = 1 << (BITS - 1);
-  const int lane = lane_id();
-  const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
-  const uint64_t lane_base = tile_base + (uint64_t)lane * kOct;
+  const float inv_gs = __uint_as_float((127u - d.lgs) << 23);  // 2^-lgs, exact
+  out.total = 0u;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    float x[kOct];
+    widen_row(raw[j], x);
+    bool o[kOct];
+    if constexpr (MODE == kModeStd) {
+      float q[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) q[e] = x[e] * x[e];  // exact: two 8-bit significands
+      float s1 = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
+      float s2 = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+      s1 = lanes_reduce<LANES>(s1, OpAdd());
+      s2 = lanes_reduce<LANES>(s2, OpAdd());
+      const float limit = std_limit(s1, s2, inv_gs, d.param);
+      // an Inf or NaN anywhere in a group makes its limit NaN; only then is the per-element test needed
+      const bool poisoned = __builtin_amdgcn_ballot_w64(limit != limit) != 0ull;
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) o[e] = q[e] > limit;
+      if (poisoned) {
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) o[e] = (q[e] > limit) || is_nonfinite(x[e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) o[e] = outlier_test<MODE>(x[e], d.param);
+    }
+    bool any;
+    row_bookkeeping(o, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
+    out.row_off[j] = out.total;
+    if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
+    float y[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) y[e] = o[e] ? 0.0f : x[e];
+    float ext0, ext1;
+    row_extremes<ASYM>(y, ext0, ext1);
+    float scl, inv, off;
+    if constexpr (!ASYM) {
+      const uint32_t r0 = lanes_reduce<LANES>(__float_as_uint(ext0), OpUMax());
+      group_scale<false>(d, r0, 0, 0, scl, inv, off);
+    } else {
+      const int32_t k0 = lanes_reduce<LANES>(float_key(ext0), OpIMax());
+      const int32_t k1 = lanes_reduce<LANES>(float_key(ext1), OpIMin());
+      group_scale<true>(d, 0u, k0, k1, scl, inv, off);
+    }
+    uint32_t c[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off : y[e], inv);
+    store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
+  }
+}
 
+template <int MODE, int BITS, bool ASYM, int E>
+__device__ __forceinline__ void encode_tile_rowwise(const TensorDesc& d, const TileGeo<E>& g,
+                                                    const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
+  switch (d.lgq) {  // one switch per tile selects straight-line code for the group size
+    case 3: encode_rows<MODE, BITS, ASYM, E, 1>(d, g, raw, out); break;
+    case 4: encode_rows<MODE, BITS, ASYM, E, 2>(d, g, raw, out); break;
+    case 5: encode_rows<MODE, BITS, ASYM, E, 4>(d, g, raw, out); break;
+    case 6: encode_rows<MODE, BITS, ASYM, E, 8>(d, g, raw, out); break;
+    case 7: encode_rows<MODE, BITS, ASYM, E, 16>(d, g, raw, out); break;
+    case 8: encode_rows<MODE, BITS, ASYM, E, 32>(d, g, raw, out); break;
+    default: encode_rows<MODE, BITS, ASYM, E, 64>(d, g, raw, out); break;
+  }
+}
+
+// ------------------------------------------------------------------ TOPK selection
+// Keys: magnitude bits above, a position code below, larger = earlier, so that the k largest keys
+// are the k largest magnitudes with ties going to the lower index; keys are unique and never 0.
+//
+// Fast path (k <= K, K = 2 or 4): every lane keeps the K largest "local" keys of its own elements
+// of a group, sorted (local position code = 64 - (8 * row in group + e), in [1, 64]).  Then k
+// times: the lanes' heads, extended by the lane position, are max-reduced over the group; the
+// winning lane pops its head.  A lane's selected elements are exactly those whose local key is
+// at least the last head it popped.
+template <int K>
+__device__ __forceinline__ void list_insert(uint32_t (&m)[K], uint32_t key) {
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    const uint32_t hi = m[i] > key ? m[i] : key;
+    key = m[i] > key ? key : m[i];
+    m[i] = hi;
+  }
+}
+
+// local key of element e of row j (rg = row index inside its group)
+__device__ __forceinline__ uint32_t local_key(const uint32_t (&oct)[4], int e, uint32_t rg) {
+  const uint32_t w = oct[e >> 1];
+  const uint32_t mag = (e & 1) ? (w & 0x7FFF0000u) : ((w << 16) & 0x7FFF0000u);
+  return mag | (64u - (rg * 8u + (uint32_t)e));
+}
+
+// thr[j]: smallest selected local key of the lane in row j's group (0xFFFFFFFF: nothing selected).
+// Returns (uniform) whether some group's k-th largest is Inf / NaN: then there may be more than k.
+template <int K, int E>
+__device__ __forceinline__ bool topk_select(const TensorDesc& d, const uint32_t (&raw)[E][4], uint32_t (&thr)[E]) {
+  const uint32_t lgs = d.lgs;
+  const int R = (lgs > 9) ? (1 << (lgs - 9)) : 1;  // rows per group
+  const uint32_t lane = (uint32_t)lane_id();
+  const uint32_t lane_pos = (lgs > 9) ? (lane << 3) : ((lane & ((1u << (lgs - 3)) - 1u)) << 3);
+  uint32_t L[E][K];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+#pragma unroll
+    for (int i = 0; i < K; ++i) L[j][i] = 0u;
+    const uint32_t rg = (uint32_t)(j & (R - 1));
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) list_insert<K>(L[j], local_key(raw[j], e, rg));
+  }
+  // merge the rows of a group into the group's first row
+#pragma unroll
+  for (int r = 1; r < E; r <<= 1) {
+    if (r < R) {
+#pragma unroll
+      for (int j = 0; j < E; j += 2 * r) {
+#pragma unroll
+        for (int i = 0; i < K; ++i) list_insert<K>(L[j], L[j + r][i]);
+      }
+    }
+  }
+  uint32_t last[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) { thr[j] = 0xFFFFFFFFu; last[j] = 0u; }
+  for (uint32_t r = 0; r < d.topk; ++r) {
+    uint32_t full[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t head = L[j][0];
+      const uint32_t lp = 64u - (head & 0x7Fu);                   // 8 * row in group + e
+      const uint32_t pos = ((lp >> 3) << 9) | lane_pos | (lp & 7u);  // position in the group
+      // after the merge only the list of a group's first row is live
+      full[j] = (head != 0u && (j & (R - 1)) == 0) ? ((head & 0x7FFF0000u) | (0xFFFFu - pos)) : 0u;
+    }
+    uint32_t win[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) win[j] = full[j];
+    groups_reduce_any_order<E>(win, lgs, OpUMax());  // rows of a multi-row group: only the first row's list is live
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      if ((j & (R - 1)) != 0) continue;  // uniform
+      const bool won = (full[j] == win[j]) && (win[j] != 0u);
+      thr[j] = won ? L[j][0] : thr[j];
+#pragma unroll
+      for (int i = 0; i + 1 < K; ++i) L[j][i] = won ? L[j][i + 1] : L[j][i];
+      L[j][K - 1] = won ? 0u : L[j][K - 1];
+      last[j] = win[j];
+    }
+  }
+  bool many = false;
+#pragma unroll
+  for (int j = 0; j < E; ++j) many |= ((last[j] >> 16) >= 0x7F80u);
+  // every row of a group uses the group's threshold
+#pragma unroll
+  for (int r = E / 2; r >= 1; r >>= 1) {
+    if (r < R) {
+#pragma unroll
+      for (int j = 0; j < E; j += 2 * r) thr[j + r] = thr[j];
+    }
+  }
+  return __builtin_amdgcn_ballot_w64(many) != 0ull;
+}
+
+// General k (up to 32): k rounds, each a max-reduction over the keys below the previous winner.
+// thr[j] then holds the k-th largest *full* key of row j's group.
+template <int E>
+__device__ __forceinline__ bool topk_select_rounds(const TensorDesc& d, const uint32_t (&raw)[E][4], uint32_t (&kth)[E],
+                                                   uint32_t lane_pos, int R) {
+#pragma unroll
+  for (int j = 0; j < E; ++j) kth[j] = 0xFFFFFFFFu;
+  for (uint32_t r = 0; r < d.topk; ++r) {
+    uint32_t best[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
+      uint32_t m = 0u;
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
+        const uint32_t cand = (key < kth[j]) ? key : 0u;
+        m = (cand > m) ? cand : m;
+      }
+      best[j] = m;
+    }
+    groups_reduce_any_order<E>(best, d.lgs, OpUMax());
+#pragma unroll
+    for (int j = 0; j < E; ++j) kth[j] = best[j];
+  }
+  bool many = false;
+#pragma unroll
+  for (int j = 0; j < E; ++j) many |= (kth[j] >> 16) >= 0x7F80u;
+  return __builtin_amdgcn_ballot_w64(many) != 0ull;
+}
+
+// ------------------------------------------------------------------ general tile encoder
+// Groups of any supported size (up to the whole tile).  Works in phases over all rows; between
+// the phases only the raw octets and a few values per row stay in registers, the widened
+// values are formed again where needed (one instruction each).
+template <int MODE, bool ASYM, bool CHECK_NONFINITE, int TOPK_LISTS, int E>
+__device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
+                                              const float (&limit)[E], const uint32_t (&thr)[E], uint32_t lane_pos, int R,
+                                              float (&ext0)[E], float (&ext1)[E], TileOutliers<E>& out) {
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    float x[kOct];
+    widen_row(raw[j], x);
+    bool o[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      if constexpr (MODE == kModeTopk) {
+        const bool valid = g.lane_off + (uint32_t)(j * kRow) < g.rem;  // blanked octets would be ranked too
+        if constexpr (TOPK_LISTS != 0) {
+          o[e] = (local_key(raw[j], e, (uint32_t)(j & (R - 1))) >= thr[j]) && valid;
+        } else {
+          const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
+          const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
+          o[e] = (key >= thr[j]) && valid;
+        }
+      } else if constexpr (MODE == kModeStd) {
+        o[e] = outlier_test<MODE>(x[e], limit[j]);
+      } else {
+        o[e] = outlier_test<MODE>(x[e], d.param);
+      }
+      if constexpr (CHECK_NONFINITE) o[e] = o[e] || is_nonfinite(x[e]);
+    }
+    bool any;
+    row_bookkeeping(o, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
+    float y[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) y[e] = o[e] ? 0.0f : x[e];
+    row_extremes<ASYM>(y, ext0[j], ext1[j]);
+  }
+}
+
+template <int MODE, int BITS, bool ASYM, int E>
+__device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const TileGeo<E>& g,
+                                                    const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
+  constexpr int Q = 1 << (BITS - 1);
   // ---- a2: statistics of the statistics groups
-  float limit[E];    // STD: k^2 * var of the row's group
-  uint32_t kth[E];   // TOPK: the k-th largest key of the row's group
-  bool poisoned = false;  // uniform: some group's statistics met Inf / NaN (or more than k of them)
-  uint32_t topk_lane_pos = 0u;
-  int topk_rows = 1;
+  float limit[E];   // STD: k^2 * var of the row's group
+  uint32_t thr[E];  // TOPK: selection threshold of the row's group
+  bool poisoned = false;  // uniform: Inf / NaN met in some group's statistics
+  int topk_lists = 0;     // TOPK: 0 = general rounds, else the sorted-list path was used
+  uint32_t lane_pos = 0u;
+  int R = 1;
   if constexpr (MODE == kModeStd) {
     float s1[E], s2[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-      const float (&r)[kOct] = x[j];
-      s1[j] = ((r[0] + r[1]) + (r[2] + r[3])) + ((r[4] + r[5]) + (r[6] + r[7]));
+      float x[kOct];
+      widen_row(raw[j], x);
+      s1[j] = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
       // squares of bf16 values are exact in binary32
-      s2[j] = ((r[0] * r[0] + r[1] * r[1]) + (r[2] * r[2] + r[3] * r[3])) +
-              ((r[4] * r[4] + r[5] * r[5]) + (r[6] * r[6] + r[7] * r[7]));
+      s2[j] = ((x[0] * x[0] + x[1] * x[1]) + (x[2] * x[2] + x[3] * x[3])) +
+              ((x[4] * x[4] + x[5] * x[5]) + (x[6] * x[6] + x[7] * x[7]));
     }
     groups_reduce<E>(s1, d.lgs, OpAdd());
     groups_reduce<E>(s2, d.lgs, OpAdd());
     const float inv_gs = __uint_as_float((127u - d.lgs) << 23);  // 2^-lgs, exact
-    const float k2 = d.param;
     bool nan_seen = false;
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-      const float mean = s1[j] * inv_gs;
-      float var = __fmaf_rn(-mean, mean, s2[j] * inv_gs);
-      var = (var < 0.0f) ? 0.0f : var;  // a NaN stays a NaN: then nothing passes the test
-      limit[j] = k2 * var;
+      limit[j] = std_limit(s1[j], s2[j], inv_gs, d.param);
       nan_seen |= (limit[j] != limit[j]);
     }
-    // an Inf or NaN anywhere in a group makes its limit NaN; only then is the per-element
-    // test for non-finite values needed
     poisoned = __builtin_amdgcn_ballot_w64(nan_seen) != 0ull;
   } else if constexpr (MODE == kModeTopk) {
-    // key = magnitude bits above, reversed position in the group below: the k largest keys
-    // are the k largest magnitudes with ties going to the lower index; keys are unique.
-    const uint32_t lgs = d.lgs;
-    topk_rows = (lgs > 9) ? (1 << (lgs - 9)) : 1;
-    topk_lane_pos = (lgs > 9) ? ((uint32_t)lane << 3) : (((uint32_t)lane & ((1u << (lgs - 3)) - 1u)) << 3);
-#pragma unroll
-    for (int j = 0; j < E; ++j) kth[j] = 0xFFFFFFFFu;
-    for (uint32_t r = 0; r < d.topk; ++r) {
-      uint32_t best[E];
-#pragma unroll
-      for (int j = 0; j < E; ++j) {
-        const uint32_t row_pos = ((uint32_t)(j & (topk_rows - 1)) << 9) | topk_lane_pos;
-        uint32_t m = 0u;
-#pragma unroll
-        for (int e = 0; e < kOct; ++e) {
-          const uint32_t key = (__float_as_uint(x[j][e]) & 0x7FFF0000u) | (0xFFFFu - (row_pos | (uint32_t)e));
-          const uint32_t cand = (key < kth[j]) ? key : 0u;
-          m = (cand > m) ? cand : m;
-        }
-        best[j] = m;
-      }
-      groups_reduce_any_order<E>(best, lgs, OpUMax());
-#pragma unroll
-      for (int j = 0; j < E; ++j) kth[j] = best[j];
-    }
-    // if even the k-th largest is Inf / NaN there may be more of them than k: check every element
-    bool many = false;
-#pragma unroll
-    for (int j = 0; j < E; ++j) many |= (kth[j] >> 16) >= 0x7F80u;
-    poisoned = __builtin_amdgcn_ballot_w64(many) != 0ull;
+    const uint32_t lane = (uint32_t)lane_id();
+    R = (d.lgs > 9) ? (1 << (d.lgs - 9)) : 1;
+    lane_pos = (d.lgs > 9) ? (lane << 3) : ((lane & ((1u << (d.lgs - 3)) - 1u)) << 3);
+    if (d.topk <= 2u) { poisoned = topk_select<2, E>(d, raw, thr); topk_lists = 1; }
+    else if (d.topk <= 4u) { poisoned = topk_select<4, E>(d, raw, thr); topk_lists = 1; }
+    else poisoned = topk_select_rounds<E>(d, raw, thr, lane_pos, R);
   }
 
-  // ---- a3 + a5: outlier test row by row; extremes of the inlier view per lane
-  forget_derived<E>(x);
+  // ---- a3 + a5: outlier test row by row; extremes of the inlier view per lane.  The copies that
+  // also test every element for Inf / NaN are separate, so that the common one carries no trace of it.
   float ext0[E], ext1[E];
-  uint32_t (&mask)[E] = out.mask;
-  uint32_t (&lane_excl)[E] = out.lane_excl;
-  uint32_t (&row_cnt)[E] = out.row_cnt;
-  const RowCtx rc{d.numel, lane_base, d.param, topk_lane_pos, topk_rows};
-  if constexpr (MODE == kModeStd || MODE == kModeTopk) {
-    // the variant that also tests every element for Inf / NaN is a separate copy of the loop, so
-    // that the common one carries no trace of it
-    if (poisoned) outlier_rows<MODE, ASYM, true, E>(rc, x, limit, kth, ext0, ext1, mask, lane_excl, row_cnt);
-    else outlier_rows<MODE, ASYM, false, E>(rc, x, limit, kth, ext0, ext1, mask, lane_excl, row_cnt);
+  if constexpr (MODE == kModeTopk) {
+    if (topk_lists) {
+      if (poisoned) outlier_phase<MODE, ASYM, true, 1, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+      else outlier_phase<MODE, ASYM, false, 1, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+    } else {
+      if (poisoned) outlier_phase<MODE, ASYM, true, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+      else outlier_phase<MODE, ASYM, false, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+    }
+  } else if constexpr (MODE == kModeStd) {
+    if (poisoned) outlier_phase<MODE, ASYM, true, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+    else outlier_phase<MODE, ASYM, false, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
   } else {
-    outlier_rows<MODE, ASYM, false, E>(rc, x, limit, kth, ext0, ext1, mask, lane_excl, row_cnt);
+    outlier_phase<MODE, ASYM, false, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
   }
   out.total = 0u;
 #pragma unroll
-  for (int j = 0; j < E; ++j) { out.row_off[j] = out.total; out.total += row_cnt[j]; }
+  for (int j = 0; j < E; ++j) {
+    out.row_off[j] = out.total;
+    if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
+  }
 
   // ---- a6: per-group scale (and offset).  Cross-lane max / min run on integer images of the floats.
   float inv[E], off[E], scl[E];
@@ -491,13 +735,7 @@ __device__ __forceinline__ void encode_tile(const TensorDesc& d, uint32_t tile, 
     for (int j = 0; j < E; ++j) a[j] = __float_as_uint(ext0[j]);
     groups_reduce_any_order<E>(a, d.lgq, OpUMax());
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const float am = __uint_as_float(a[j]);
-      // Eq. 2: S = max|X| / D.  For a power-of-two D the division is a multiplication by 1/D, same bits
-      scl[j] = d.inv_divisor != 0.0f ? am * d.inv_divisor : am / d.divisor;
-      inv[j] = (am != 0.0f) ? fminf(d.divisor / am, 3.402823466e+38f) : 0.0f;  // one division per group
-      off[j] = 0.0f;
-    }
+    for (int j = 0; j < E; ++j) group_scale<false>(d, a[j], 0, 0, scl[j], inv[j], off[j]);
   } else {
     int32_t hi[E], lo[E];
 #pragma unroll
@@ -505,58 +743,39 @@ __device__ __forceinline__ void encode_tile(const TensorDesc& d, uint32_t tile, 
     groups_reduce_any_order<E>(hi, d.lgq, OpIMax());
     groups_reduce_any_order<E>(lo, d.lgq, OpIMin());
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      // a zero extreme is +0 whatever signs the zeros had
-      const float h = key_float(hi[j]) + 0.0f, l = key_float(lo[j]) + 0.0f;
-      const float o = (h + l) * 0.5f;                   // Eq. 3: O = (max+min)/2
-      const float r = h - l;
-      off[j] = o;
-      scl[j] = d.inv_divisor != 0.0f ? r * d.inv_divisor : r / d.divisor;  // Eq. 3: S = (max-min) / D2
-      inv[j] = (r != 0.0f) ? fminf(d.divisor / r, 3.402823466e+38f) : 0.0f;
-    }
+    for (int j = 0; j < E; ++j) group_scale<true>(d, 0u, hi[j], lo[j], scl[j], inv[j], off[j]);
   }
 
   // ---- a7 + a8: quantise, pack, store codes and scales
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-    const uint64_t e0 = lane_base + (uint64_t)j * kRow;
-    // the inlier view: x, or zero where the mask says so
     float y[kOct];
+    widen_row(raw[j], y);
+    if (out.row_cnt[j] != 0u) {  // uniform: the inlier view is zero where the mask says so
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) y[e] = x[j][e];
-    if (row_cnt[j] != 0u) {  // uniform
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) y[e] = ((mask[j] >> e) & 1u) ? 0.0f : y[e];
+      for (int e = 0; e < kOct; ++e) y[e] = ((out.mask[j] >> e) & 1u) ? 0.0f : y[e];
     }
     uint32_t c[kOct];
 #pragma unroll
     for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off[j] : y[e], inv[j]);
-    // Every lane stores, always: a store under a branch would make the number of stores in flight
-    // unknown to the compiler's wait-count bookkeeping, and the wait for the prefetched tile would
-    // then also wait for these stores.  Octets past the end of the tensor go to a scrap area in the
-    // unused part of the blob's status block; all lanes of a group store their (identical) scale.
-    const bool valid = e0 < d.numel;
-    unsigned char* scrap = reinterpret_cast<unsigned char*>(d.status) + 64;
-    if constexpr (BITS == 8) {
-      uint2 w;
-      w.x = pack_bytes4(c[0], c[1], c[2], c[3]);
-      w.y = pack_bytes4(c[4], c[5], c[6], c[7]);
-      *reinterpret_cast<uint2*>(valid ? d.codes + e0 : scrap) = w;
-    } else {
-      *reinterpret_cast<uint32_t*>(valid ? d.codes + (e0 >> 1) : scrap) = pack_nibbles8(c);
-    }
-    const uint64_t g = e0 >> d.lgq;
-    *(valid ? d.scales + g : reinterpret_cast<float*>(scrap + 16)) = scl[j];
-    if constexpr (ASYM) *(valid ? d.zp + g : reinterpret_cast<float*>(scrap + 32)) = off[j];
+    store_row<BITS, ASYM, E>(d, g, j, c, scl[j], off[j]);
   }
+}
+
+// ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
+__device__ __forceinline__ void encode_tile(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
+                                            TileOutliers<E>& out) {
+  if constexpr (ROWWISE) encode_tile_rowwise<MODE, BITS, ASYM, E>(d, g, raw, out);
+  else encode_tile_general<MODE, BITS, ASYM, E>(d, g, raw, out);
 }
 
 // ---- a4: append a tile's outliers, in ascending index order, to `idx_out` / `val_out` starting
 // at position pos0 (entries at or past `limit` are dropped).  The destination is either the
 // stream in global memory or the wavefront's staging area in LDS.  Only rows that have
-// outliers are visited; the original bf16 pattern is the upper half of the widened value.
+// outliers are visited.
 template <int E, class IdxPtr, class ValPtr>
-__device__ __forceinline__ void emit_outliers(const float (&x)[E][kOct], const TileOutliers<E>& out, uint32_t tile,
+__device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const TileOutliers<E>& out, uint32_t tile,
                                               IdxPtr idx_out, ValPtr val_out, uint32_t pos0, uint32_t limit) {
   const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
   static_for<E>([&](auto J) {
@@ -570,7 +789,7 @@ __device__ __forceinline__ void emit_outliers(const float (&x)[E][kOct], const T
         if ((bits >> e) & 1u) {
           if (pos < limit) {
             idx_out[pos] = (int32_t)(i0 + (uint32_t)e);
-            val_out[pos] = (uint16_t)(__float_as_uint(x[j][e]) >> 16);
+            val_out[pos] = (uint16_t)((e & 1) ? (raw[j][e >> 1] >> 16) : (raw[j][e >> 1] & 0xFFFFu));
           }
           ++pos;
         }
@@ -592,7 +811,7 @@ struct WaveStage {
 // copied out in one coalesced sweep.  A run whose outliers do not fit the staging area
 // resolves its offset early (it only has to wait for lower-numbered runs) and from then on
 // appends straight to the stream.
-template <int MODE, int BITS, bool ASYM, int E>
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit, const ScanCtx& sc, WaveStage* stage) {
   static_assert(MODE != kModeNone, "runs exist for the scan only");
   const int lane = lane_id();
@@ -631,11 +850,10 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
     load_tile<E>(d, t, raw);
 #endif
 
-    blank_tail<E>(d, t, raw);
-    float x[E][kOct];
-    widen_tile<E>(raw, x);
+    const TileGeo<E> g = tile_geo<E>(d, t);
+    blank_tail<E>(g, raw);
     TileOutliers<E> out;
-    encode_tile<MODE, BITS, ASYM, E>(d, t, x, out);
+    encode_tile<MODE, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
     if ((uint32_t)lane == t - t0) tile_off = run_total;
 
     if (out.total != 0u) {
@@ -655,12 +873,12 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
         staged = 0u;
       }
       if (base_known) {
-        if (!aborted) emit_outliers<E>(x, out, t, d.idx, d.val, excl + run_total, d.cap);
+        if (!aborted) emit_outliers<E>(raw, out, t, d.idx, d.val, excl + run_total, d.cap);
         // rare path with a data-dependent number of stores: drain it, so that the common path's
         // wait counts stay exact
         __builtin_amdgcn_s_waitcnt(0);
       } else {
-        emit_outliers<E>(x, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
+        emit_outliers<E>(raw, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
         staged += out.total;
       }
       run_total += out.total;
@@ -673,15 +891,20 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
 #endif
   }
 
-  // the run is complete: make its total visible, then find its offset in the stream
+  // The run is complete: make its total visible, then find its offset in the stream.  The last
+  // run of a block closes the block as soon as it knows the totals of the block's other runs,
+  // BEFORE it looks at earlier blocks: no block's total depends on another block's, so the
+  // longest chain of waits is two (a run's total -> its block's total -> every later run).
   scan_publish(sc.state1, gunit, sc.tag | (aborted ? kFlagAbort : kFlagAggregate), run_total);
+  const bool closes_block = (unit % kWave) == kWave - 1;
+  if (!base_known) in_block = scan_poll_sum(sc, sc.state1, gunit_block0, gunit, aborted);
+  if (closes_block)
+    scan_publish(sc.state2, gblock0 + block, sc.tag | (aborted ? kFlagAbort : kFlagAggregate), in_block + run_total);
   if (!base_known) {
-    in_block = scan_poll_sum(sc, sc.state1, gunit_block0, gunit, aborted);
     excl = in_block;
     if (!aborted) excl += scan_poll_sum(sc, sc.state2, gblock0, gblock0 + block, aborted);
+    if (aborted && closes_block) scan_publish(sc.state2, gblock0 + block, sc.tag | kFlagAbort, 0u);
   }
-  if ((unit % kWave) == kWave - 1)  // last run of a full block: close the block
-    scan_publish(sc.state2, gblock0 + block, sc.tag | (aborted ? kFlagAbort : kFlagAggregate), in_block + run_total);
   if (aborted) scan_publish(sc.state1, gunit, sc.tag | kFlagAbort, 0u);
 
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -707,15 +930,14 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
 }
 
 // ------------------------------------------------------------------ one tile without outliers (NONE)
-template <int BITS, bool ASYM, int E>
+template <int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_tile_plain(const TensorDesc& d, uint32_t tile) {
   uint32_t raw[E][4];
   load_tile<E>(d, tile, raw);
-  blank_tail<E>(d, tile, raw);
-  float x[E][kOct];
-  widen_tile<E>(raw, x);
+  const TileGeo<E> g = tile_geo<E>(d, tile);
+  blank_tail<E>(g, raw);
   TileOutliers<E> out;
-  encode_tile<kModeNone, BITS, ASYM, E>(d, tile, x, out);
+  encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
   if (tile == 0 && lane_id() == 0) {
     d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;
   }
