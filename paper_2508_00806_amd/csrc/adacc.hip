@@ -273,9 +273,6 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
   if (e != hipSuccess) return hip_fail(e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
   if (wgs < 1) wgs = 1;
   *waves = (uint32_t)(cus * wgs * kWavesPerWg);
-  const int pct = env_int("ADACC_CAPACITY_PCT", 100);  // experiment knob
-  *waves = (uint32_t)((uint64_t)*waves * (uint64_t)pct / 100u);
-  if (*waves < (uint32_t)kWavesPerWg) *waves = kWavesPerWg;
   return ADACC_OK;
 }
 

@@ -295,6 +295,19 @@ __device__ __forceinline__ void blank_tail(const TileGeo<E>& g, uint32_t (&raw)[
   }
 }
 
+// Makes the compiler forget everything it derived from the raw octets (their values do not
+// change).  Between two phases that both widen the octets this keeps the 8 widened values per
+// row from staying in registers all the way: forming them again costs one instruction each,
+// keeping them costs a quarter of the wavefronts a SIMD can hold.
+template <int E>
+__device__ __forceinline__ void forget_derived(const uint32_t (&raw)[E][4]) {
+  uint32_t(&r)[E][4] = const_cast<uint32_t(&)[E][4]>(raw);
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    asm volatile("" : "+v"(r[j][0]), "+v"(r[j][1]), "+v"(r[j][2]), "+v"(r[j][3]));
+  }
+}
+
 // bf16 -> binary32 (exact): the 16 bits become the upper half of the word
 __device__ __forceinline__ void widen_row(const uint32_t (&oct)[4], float (&x)[kOct]) {
 #pragma unroll
@@ -358,19 +371,19 @@ __device__ __forceinline__ float std_limit(float s1, float s2, float inv_gs, flo
 }
 
 // Bookkeeping of one row from the ballots of its 8 outlier tests: per-lane mask, number of the
-// row's outliers in lower lanes, row count.  Only rows that have outliers do the work.
-__device__ __forceinline__ void row_bookkeeping(const bool (&o)[kOct], uint32_t& mask, uint32_t& lane_excl,
+// row's outliers in lower lanes, row count.  Only rows that have outliers do the work.  The
+// ballots live in scalar registers; a lane reads its own bit back as a select condition.
+__device__ __forceinline__ void row_bookkeeping(const uint64_t (&b)[kOct], uint32_t& mask, uint32_t& lane_excl,
                                                 uint32_t& row_cnt, bool& any_out) {
-  uint64_t b[kOct];
   uint64_t any = 0ull;
 #pragma unroll
-  for (int e = 0; e < kOct; ++e) { b[e] = __builtin_amdgcn_ballot_w64(o[e]); any |= b[e]; }
+  for (int e = 0; e < kOct; ++e) any |= b[e];
   any_out = any != 0ull;
   if (any_out) {
     uint32_t m = 0u, below = 0u, cnt = 0u;
 #pragma unroll
     for (int e = 0; e < kOct; ++e) {
-      m |= o[e] ? (1u << e) : 0u;
+      m |= __builtin_amdgcn_inverse_ballot_w64(b[e]) ? (1u << e) : 0u;
       below += lanes_below(b[e]);
       cnt += (uint32_t)__popcll(b[e]);
     }
@@ -378,6 +391,13 @@ __device__ __forceinline__ void row_bookkeeping(const bool (&o)[kOct], uint32_t&
   } else {
     mask = 0u; lane_excl = 0u; row_cnt = 0u;
   }
+}
+__device__ __forceinline__ void row_bookkeeping(const bool (&o)[kOct], uint32_t& mask, uint32_t& lane_excl,
+                                                uint32_t& row_cnt, bool& any_out) {
+  uint64_t b[kOct];
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(o[e]);
+  row_bookkeeping(b, mask, lane_excl, row_cnt, any_out);
 }
 
 // extremes of the inlier view of one octet: symmetric ext0 = max |y|; asymmetric ext0 = max y, ext1 = min y
@@ -496,109 +516,82 @@ __device__ __forceinline__ void encode_tile_rowwise(const TensorDesc& d, const T
 }
 
 // ------------------------------------------------------------------ TOPK selection
-// Keys: magnitude bits above, a position code below, larger = earlier, so that the k largest keys
-// are the k largest magnitudes with ties going to the lower index; keys are unique and never 0.
+// Magnitudes are the 15 low bits of the bf16 patterns.  Two ways to find a group's k largest:
 //
-// Fast path (k <= K, K = 2 or 4): every lane keeps the K largest "local" keys of its own elements
-// of a group, sorted (local position code = 64 - (8 * row in group + e), in [1, 64]).  Then k
-// times: the lanes' heads, extended by the lane position, are max-reduced over the group; the
-// winning lane pops its head.  A lane's selected elements are exactly those whose local key is
-// at least the last head it popped.
-template <int K>
-__device__ __forceinline__ void list_insert(uint32_t (&m)[K], uint32_t key) {
-#pragma unroll
-  for (int i = 0; i < K; ++i) {
-    const uint32_t hi = m[i] > key ? m[i] : key;
-    key = m[i] > key ? key : m[i];
-    m[i] = hi;
-  }
+// By lane maxima (groups of whole rows, small k): every lane takes the largest magnitude among
+// its own elements of the group, and the k-th largest of these lane maxima, w, is found by k
+// max-reductions over the lanes.  At least k elements are >= w.  If exactly k are, they are the
+// k largest of the group whatever their order, and the selection is the plain test |x| >= w.
+// Otherwise (two of the largest in one lane, or a tie at the boundary) the caller falls back to
+// the rounds below.
+//
+// By rounds (any group, any k): k max-reductions over keys (magnitude above, inverted position
+// below, so ties go to the lower index), each restricted to the keys below the previous winner.
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t,
+                            __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
 }
 
-// local key of element e of row j (rg = row index inside its group)
-__device__ __forceinline__ uint32_t local_key(const uint32_t (&oct)[4], int e, uint32_t rg) {
-  const uint32_t w = oct[e >> 1];
-  const uint32_t mag = (e & 1) ? (w & 0x7FFF0000u) : ((w << 16) & 0x7FFF0000u);
-  return mag | (64u - (rg * 8u + (uint32_t)e));
-}
-
-// thr[j]: smallest selected local key of the lane in row j's group (0xFFFFFFFF: nothing selected).
-// Returns (uniform) whether some group's k-th largest is Inf / NaN: then there may be more than k.
-template <int K, int E>
-__device__ __forceinline__ bool topk_select(const TensorDesc& d, const uint32_t (&raw)[E][4], uint32_t (&thr)[E]) {
-  const uint32_t lgs = d.lgs;
-  const int R = (lgs > 9) ? (1 << (lgs - 9)) : 1;  // rows per group
-  const uint32_t lane = (uint32_t)lane_id();
-  const uint32_t lane_pos = (lgs > 9) ? (lane << 3) : ((lane & ((1u << (lgs - 3)) - 1u)) << 3);
-  uint32_t L[E][K];
+// thrf[j] <- the k-th largest lane maximum of row j's group, as a binary32 value.  Returns
+// (uniform) false when the tile holds an Inf or NaN (then the magnitude test is no float compare).
+template <int E>
+__device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint32_t (&raw)[E][4], float (&thrf)[E]) {
+  const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
+  uint32_t m[E];
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-#pragma unroll
-    for (int i = 0; i < K; ++i) L[j][i] = 0u;
-    const uint32_t rg = (uint32_t)(j & (R - 1));
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) list_insert<K>(L[j], local_key(raw[j], e, rg));
+    constexpr uint32_t kMag2 = 0x7FFF7FFFu;
+    m[j] = pk_max_u16(pk_max_u16(raw[j][0] & kMag2, raw[j][1] & kMag2), pk_max_u16(raw[j][2] & kMag2, raw[j][3] & kMag2));
   }
-  // merge the rows of a group into the group's first row
+  // rows of a group -> its first row
 #pragma unroll
   for (int r = 1; r < E; r <<= 1) {
     if (r < R) {
 #pragma unroll
-      for (int j = 0; j < E; j += 2 * r) {
-#pragma unroll
-        for (int i = 0; i < K; ++i) list_insert<K>(L[j], L[j + r][i]);
-      }
+      for (int j = 0; j < E; j += 2 * r) m[j] = pk_max_u16(m[j], m[j + r]);
     }
   }
-  uint32_t last[E];
+  const uint32_t lane = (uint32_t)lane_id();
+  uint32_t cur[E], win[E];
+  bool nonfinite = false;
 #pragma unroll
-  for (int j = 0; j < E; ++j) { thr[j] = 0xFFFFFFFFu; last[j] = 0u; }
+  for (int j = 0; j < E; ++j) {
+    const uint32_t hi = m[j] >> 16, lo = m[j] & 0xFFFFu;
+    const uint32_t mx = hi > lo ? hi : lo;
+    nonfinite |= mx >= 0x7F80u;
+    cur[j] = (mx << 6) | lane;  // unique per lane: equal maxima are taken one after the other
+    win[j] = 0u;
+  }
   for (uint32_t r = 0; r < d.topk; ++r) {
-    uint32_t full[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-      const uint32_t head = L[j][0];
-      const uint32_t lp = 64u - (head & 0x7Fu);                   // 8 * row in group + e
-      const uint32_t pos = ((lp >> 3) << 9) | lane_pos | (lp & 7u);  // position in the group
-      // after the merge only the list of a group's first row is live
-      full[j] = (head != 0u && (j & (R - 1)) == 0) ? ((head & 0x7FFF0000u) | (0xFFFFu - pos)) : 0u;
-    }
-    uint32_t win[E];
-#pragma unroll
-    for (int j = 0; j < E; ++j) win[j] = full[j];
-    groups_reduce_any_order<E>(win, lgs, OpUMax());  // rows of a multi-row group: only the first row's list is live
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      if ((j & (R - 1)) != 0) continue;  // uniform
-      const bool won = (full[j] == win[j]) && (win[j] != 0u);
-      thr[j] = won ? L[j][0] : thr[j];
-#pragma unroll
-      for (int i = 0; i + 1 < K; ++i) L[j][i] = won ? L[j][i + 1] : L[j][i];
-      L[j][K - 1] = won ? 0u : L[j][K - 1];
-      last[j] = win[j];
+      if ((j & (R - 1)) != 0) continue;  // uniform: a group's state lives in its first row
+      win[j] = lanes_reduce<kWave>(cur[j], OpUMax());
+      cur[j] = (cur[j] == win[j]) ? 0u : cur[j];
     }
   }
-  bool many = false;
-#pragma unroll
-  for (int j = 0; j < E; ++j) many |= ((last[j] >> 16) >= 0x7F80u);
-  // every row of a group uses the group's threshold
 #pragma unroll
   for (int r = E / 2; r >= 1; r >>= 1) {
     if (r < R) {
 #pragma unroll
-      for (int j = 0; j < E; j += 2 * r) thr[j + r] = thr[j];
+      for (int j = 0; j < E; j += 2 * r) win[j + r] = win[j];
     }
   }
-  return __builtin_amdgcn_ballot_w64(many) != 0ull;
+#pragma unroll
+  for (int j = 0; j < E; ++j) thrf[j] = __uint_as_float((win[j] >> 6) << 16);
+  return __builtin_amdgcn_ballot_w64(nonfinite) == 0ull;
 }
 
-// General k (up to 32): k rounds, each a max-reduction over the keys below the previous winner.
-// thr[j] then holds the k-th largest *full* key of row j's group.
+// Rounds: thr[j] <- the k-th largest key of row j's group.  Returns (uniform) whether some group's
+// k-th largest is Inf / NaN: then there may be more than k outliers.
 template <int E>
 __device__ __forceinline__ bool topk_select_rounds(const TensorDesc& d, const uint32_t (&raw)[E][4], uint32_t (&kth)[E],
                                                    uint32_t lane_pos, int R) {
 #pragma unroll
   for (int j = 0; j < E; ++j) kth[j] = 0xFFFFFFFFu;
   for (uint32_t r = 0; r < d.topk; ++r) {
+    forget_derived<E>(raw);  // the keys are formed again in every round: holding them would cost 8 registers per row
     uint32_t best[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
@@ -626,39 +619,56 @@ __device__ __forceinline__ bool topk_select_rounds(const TensorDesc& d, const ui
 // Groups of any supported size (up to the whole tile).  Works in phases over all rows; between
 // the phases only the raw octets and a few values per row stay in registers, the widened
 // values are formed again where needed (one instruction each).
-template <int MODE, bool ASYM, bool CHECK_NONFINITE, int TOPK_LISTS, int E>
+// a3 + a5 for all rows of a tile: the outlier tests (as wavefront ballots, which live in scalar
+// registers, so the run-time choices between tests are uniform branches that cost no vector
+// registers), the bookkeeping of the rows that have outliers, and the per-lane extremes of the
+// inlier view.  `by_magnitude` (TOPK): thr[j] holds the bits of a binary32 magnitude threshold,
+// else the smallest selected key.  `poisoned`: every element is also tested for Inf / NaN.
+template <int MODE, bool ASYM, int E>
 __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
-                                              const float (&limit)[E], const uint32_t (&thr)[E], uint32_t lane_pos, int R,
-                                              float (&ext0)[E], float (&ext1)[E], TileOutliers<E>& out) {
+                                              const float (&limit)[E], const uint32_t (&thr)[E], bool by_magnitude,
+                                              bool poisoned, uint32_t lane_pos, int R, float (&ext0)[E],
+                                              float (&ext1)[E], TileOutliers<E>& out) {
+  forget_derived<E>(raw);  // nothing formed from the octets so far is worth its registers
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     float x[kOct];
     widen_row(raw[j], x);
-    bool o[kOct];
+    uint64_t b[kOct];
+    if constexpr (MODE == kModeTopk) {
+      if (by_magnitude) {
+        // rows past the end of the tensor are all selected here, which the caller's count check rejects
+        const float t = __uint_as_float(thr[j]);
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) {
-      if constexpr (MODE == kModeTopk) {
-        const bool valid = g.lane_off + (uint32_t)(j * kRow) < g.rem;  // blanked octets would be ranked too
-        if constexpr (TOPK_LISTS != 0) {
-          o[e] = (local_key(raw[j], e, (uint32_t)(j & (R - 1))) >= thr[j]) && valid;
-        } else {
-          const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
-          const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
-          o[e] = (key >= thr[j]) && valid;
-        }
-      } else if constexpr (MODE == kModeStd) {
-        o[e] = outlier_test<MODE>(x[e], limit[j]);
+        for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(fabsf(x[e]) >= t);
       } else {
-        o[e] = outlier_test<MODE>(x[e], d.param);
+        const bool valid = g.lane_off + (uint32_t)(j * kRow) < g.rem;  // blanked octets would be ranked too
+        const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) {
+          const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
+          b[e] = __builtin_amdgcn_ballot_w64((key >= thr[j]) && valid);
+        }
       }
-      if constexpr (CHECK_NONFINITE) o[e] = o[e] || is_nonfinite(x[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < kOct; ++e)
+        b[e] = __builtin_amdgcn_ballot_w64(outlier_test<MODE>(x[e], MODE == kModeStd ? limit[j] : d.param));
+    }
+    if (poisoned) {
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) b[e] |= __builtin_amdgcn_ballot_w64(is_nonfinite(x[e]));
     }
     bool any;
-    row_bookkeeping(o, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
-    float y[kOct];
+    row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
+    if (any) {
+      float y[kOct];
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) y[e] = o[e] ? 0.0f : x[e];
-    row_extremes<ASYM>(y, ext0[j], ext1[j]);
+      for (int e = 0; e < kOct; ++e) y[e] = __builtin_amdgcn_inverse_ballot_w64(b[e]) ? 0.0f : x[e];
+      row_extremes<ASYM>(y, ext0[j], ext1[j]);
+    } else {
+      row_extremes<ASYM>(x, ext0[j], ext1[j]);
+    }
   }
 }
 
@@ -670,7 +680,6 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
   float limit[E];   // STD: k^2 * var of the row's group
   uint32_t thr[E];  // TOPK: selection threshold of the row's group
   bool poisoned = false;  // uniform: Inf / NaN met in some group's statistics
-  int topk_lists = 0;     // TOPK: 0 = general rounds, else the sorted-list path was used
   uint32_t lane_pos = 0u;
   int R = 1;
   if constexpr (MODE == kModeStd) {
@@ -698,27 +707,40 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     const uint32_t lane = (uint32_t)lane_id();
     R = (d.lgs > 9) ? (1 << (d.lgs - 9)) : 1;
     lane_pos = (d.lgs > 9) ? (lane << 3) : ((lane & ((1u << (d.lgs - 3)) - 1u)) << 3);
-    if (d.topk <= 2u) { poisoned = topk_select<2, E>(d, raw, thr); topk_lists = 1; }
-    else if (d.topk <= 4u) { poisoned = topk_select<4, E>(d, raw, thr); topk_lists = 1; }
-    else poisoned = topk_select_rounds<E>(d, raw, thr, lane_pos, R);
   }
 
-  // ---- a3 + a5: outlier test row by row; extremes of the inlier view per lane.  The copies that
-  // also test every element for Inf / NaN are separate, so that the common one carries no trace of it.
+  // ---- a3 + a5: outlier test row by row; extremes of the inlier view per lane
   float ext0[E], ext1[E];
   if constexpr (MODE == kModeTopk) {
-    if (topk_lists) {
-      if (poisoned) outlier_phase<MODE, ASYM, true, 1, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
-      else outlier_phase<MODE, ASYM, false, 1, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
-    } else {
-      if (poisoned) outlier_phase<MODE, ASYM, true, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
-      else outlier_phase<MODE, ASYM, false, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+    // First the selection by lane maxima where it applies; if it does not stand, once more by rounds.
+    // One copy of the code in a loop (rather than two in a row) keeps the registers of the rare second
+    // pass from adding to those of the first.
+    bool try_maxima = d.lgs >= 9u && d.topk <= 8u;
+#pragma nounroll
+    while (true) {
+      bool by_magnitude = false;
+      if (try_maxima) {
+        float thrf[E];
+        by_magnitude = topk_lane_maxima<E>(d, raw, thrf);
+#pragma unroll
+        for (int j = 0; j < E; ++j) thr[j] = __float_as_uint(thrf[j]);
+      }
+      if (!by_magnitude) poisoned = topk_select_rounds<E>(d, raw, thr, lane_pos, R);
+      outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, by_magnitude, poisoned, lane_pos, R, ext0, ext1, out);
+      if (!by_magnitude) break;
+      // the selection stands if every group has exactly k elements at or above its threshold
+      bool exact = true;
+      uint32_t in_group = 0u;
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        in_group += out.row_cnt[j];
+        if ((j & (R - 1)) == R - 1) { exact = exact && (in_group == d.topk); in_group = 0u; }
+      }
+      if (exact) break;
+      try_maxima = false;
     }
-  } else if constexpr (MODE == kModeStd) {
-    if (poisoned) outlier_phase<MODE, ASYM, true, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
-    else outlier_phase<MODE, ASYM, false, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
   } else {
-    outlier_phase<MODE, ASYM, false, 0, E>(d, g, raw, limit, thr, lane_pos, R, ext0, ext1, out);
+    outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, false, poisoned, lane_pos, R, ext0, ext1, out);
   }
   out.total = 0u;
 #pragma unroll

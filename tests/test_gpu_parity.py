@@ -109,6 +109,38 @@ def test_degenerate_inputs():
     run_parity(from_bits(nonfin), md)
 
 
+def test_topk_selection_corner_cases():
+    """TOPK over groups of whole rows: the largest values share a lane, tie at the k-th place, sit in
+    a constant group, or come with Inf / NaN, next to groups where the k largest are clear-cut."""
+    rng = np.random.default_rng(99)
+    for gs in (512, 2048, 4096):
+        for k in (1, 2, 4, 8, 9):
+            n_groups = 7
+            v = rng.normal(0.0, 1.0, size=gs * n_groups).astype(np.float32)
+            b = bits_of(torch.from_numpy(v).to(torch.bfloat16)).copy()
+            big = int(bits_of(torch.tensor([50.0], dtype=torch.bfloat16))[0])
+            g = lambda i: slice(i * gs, (i + 1) * gs)
+            # group 0: the k+1 largest next to each other (one lane holds most of them)
+            b[g(0)][8:8 + k + 1] = [big + i for i in range(k + 1)]
+            # group 1: k+2 equal maxima spread over the group, negative ones included
+            pos = np.sort(rng.choice(gs, size=k + 2, replace=False))
+            b[g(1)][pos] = big
+            b[g(1)][pos[::2]] |= 0x8000
+            # group 2: constant; group 3: all zero with one -0
+            b[g(2)] = 0x3F80
+            b[g(3)] = 0
+            b[g(3)][5] = 0x8000
+            # group 4: Inf, NaN and large values together
+            b[g(4)][[3, 200, 300, 301]] = [0x7F80, 0xFFC1, big, big + 1]
+            # group 5: more Inf / NaN than k
+            b[g(5)][rng.choice(gs, size=k + 3, replace=False)] = 0xFF80
+            # group 6 stays plain random
+            for bits, gq, asym in ((4, 128, 0), (8, gs, 1)):
+                md = dict(bits=bits, quant_group=gq, asym=asym, outlier_mode="topk", stat_group=gs, thresh=0.0, topk=k)
+                log(f"[parity] topk corner cases gs={gs} k={k} bits={bits} gq={gq} asym={asym}")
+                run_parity(from_bits(b), md)
+
+
 def test_every_element_an_outlier_and_overflow():
     b = random_bits(77, 2048 * 3 + 512)
     b[(b & 0x7FFF) == 0] = 0x3F80
