@@ -26,7 +26,7 @@ template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
 __global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
                                                                                       uint64_t* state2, uint32_t tag,
                                                                                       uint32_t spin_limit) {
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
   if constexpr (MODE == kModeNone) {
     for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
       compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_k
 template <int BITS, bool ASYM, int E, bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint32_t has_outliers) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<E, F32>()];
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
   unsigned char* slice = lds + wave * decompress_lds_per_wave<E, F32>();
   for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
     decompress_tile<BITS, ASYM, E, F32>(d, t, has_outliers != 0u, slice);
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDe
                                                                   uint64_t* state2, uint32_t tag,
                                                                   uint32_t spin_limit) {
   __shared__ WaveStage stage[kWavesPerWg];
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
   const ScanCtx sc{state1, state2, tag, spin_limit};
   const uint32_t g = blockIdx.x * kWavesPerWg + wave;
   if (g >= total_units) return;
@@ -136,7 +136,7 @@ template <bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, uint32_t n,
                                                                     uint32_t total_tiles) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<8, F32>()];
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
   unsigned char* slice = lds + wave * decompress_lds_per_wave<8, F32>();
   for (uint32_t g = blockIdx.x * kWavesPerWg + wave; g < total_tiles; g += gridDim.x * kWavesPerWg) {
     const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<false>(table, n, g));
@@ -283,6 +283,7 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
 // number of runs in flight, not with the number of tiles.
 static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
   const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64) > 64 ? 64 : (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64);
+  if (env_int("ADACC_FORCE_TILES_PER_UNIT", 0) > 0) return (uint32_t)env_int("ADACC_FORCE_TILES_PER_UNIT", 0);  // experiment knob
   if (tiles_in_launch <= capacity) return 1u;
   const uint64_t rounds = (tiles_in_launch + (uint64_t)capacity * tmax - 1) / ((uint64_t)capacity * tmax);
   const uint64_t units = (uint64_t)capacity * rounds;

@@ -444,7 +444,7 @@ __device__ __forceinline__ bool is_nonfinite(float x) { return (__float_as_uint(
 // Used when every group (statistics and quantisation) lies inside one 512-element row and both
 // kinds have the same size: each row is taken from the raw octets to its stored codes in one
 // go, so nothing but the raw octets lives across rows.  LANES = lanes per group.
-template <int MODE, int BITS, bool ASYM, int E, int LANES>
+template <int MODE, int BITS, bool ASYM, int E, int LANES, bool STORE>
 __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
                                             TileOutliers<E>& out) {
   constexpr int Q = 1 << (BITS - 1);
@@ -480,38 +480,40 @@ __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E
     row_bookkeeping(o, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
     out.row_off[j] = out.total;
     if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
-    float y[kOct];
+    if constexpr (STORE) {
+      float y[kOct];
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) y[e] = o[e] ? 0.0f : x[e];
-    float ext0, ext1;
-    row_extremes<ASYM>(y, ext0, ext1);
-    float scl, inv, off;
-    if constexpr (!ASYM) {
-      const uint32_t r0 = lanes_reduce<LANES>(__float_as_uint(ext0), OpUMax());
-      group_scale<false>(d, r0, 0, 0, scl, inv, off);
-    } else {
-      const int32_t k0 = lanes_reduce<LANES>(float_key(ext0), OpIMax());
-      const int32_t k1 = lanes_reduce<LANES>(float_key(ext1), OpIMin());
-      group_scale<true>(d, 0u, k0, k1, scl, inv, off);
+      for (int e = 0; e < kOct; ++e) y[e] = o[e] ? 0.0f : x[e];
+      float ext0, ext1;
+      row_extremes<ASYM>(y, ext0, ext1);
+      float scl, inv, off;
+      if constexpr (!ASYM) {
+        const uint32_t r0 = lanes_reduce<LANES>(__float_as_uint(ext0), OpUMax());
+        group_scale<false>(d, r0, 0, 0, scl, inv, off);
+      } else {
+        const int32_t k0 = lanes_reduce<LANES>(float_key(ext0), OpIMax());
+        const int32_t k1 = lanes_reduce<LANES>(float_key(ext1), OpIMin());
+        group_scale<true>(d, 0u, k0, k1, scl, inv, off);
+      }
+      uint32_t c[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off : y[e], inv);
+      store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
     }
-    uint32_t c[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off : y[e], inv);
-    store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
   }
 }
 
-template <int MODE, int BITS, bool ASYM, int E>
+template <int MODE, int BITS, bool ASYM, int E, bool STORE>
 __device__ __forceinline__ void encode_tile_rowwise(const TensorDesc& d, const TileGeo<E>& g,
                                                     const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
   switch (d.lgq) {  // one switch per tile selects straight-line code for the group size
-    case 3: encode_rows<MODE, BITS, ASYM, E, 1>(d, g, raw, out); break;
-    case 4: encode_rows<MODE, BITS, ASYM, E, 2>(d, g, raw, out); break;
-    case 5: encode_rows<MODE, BITS, ASYM, E, 4>(d, g, raw, out); break;
-    case 6: encode_rows<MODE, BITS, ASYM, E, 8>(d, g, raw, out); break;
-    case 7: encode_rows<MODE, BITS, ASYM, E, 16>(d, g, raw, out); break;
-    case 8: encode_rows<MODE, BITS, ASYM, E, 32>(d, g, raw, out); break;
-    default: encode_rows<MODE, BITS, ASYM, E, 64>(d, g, raw, out); break;
+    case 3: encode_rows<MODE, BITS, ASYM, E, 1, STORE>(d, g, raw, out); break;
+    case 4: encode_rows<MODE, BITS, ASYM, E, 2, STORE>(d, g, raw, out); break;
+    case 5: encode_rows<MODE, BITS, ASYM, E, 4, STORE>(d, g, raw, out); break;
+    case 6: encode_rows<MODE, BITS, ASYM, E, 8, STORE>(d, g, raw, out); break;
+    case 7: encode_rows<MODE, BITS, ASYM, E, 16, STORE>(d, g, raw, out); break;
+    case 8: encode_rows<MODE, BITS, ASYM, E, 32, STORE>(d, g, raw, out); break;
+    default: encode_rows<MODE, BITS, ASYM, E, 64, STORE>(d, g, raw, out); break;
   }
 }
 
@@ -672,7 +674,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
   }
 }
 
-template <int MODE, int BITS, bool ASYM, int E>
+template <int MODE, int BITS, bool ASYM, int E, bool STORE>
 __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const TileGeo<E>& g,
                                                     const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
   constexpr int Q = 1 << (BITS - 1);
@@ -749,6 +751,8 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
   }
 
+  if constexpr (!STORE) return;  // the caller only wants the outliers
+
   // ---- a6: per-group scale (and offset).  Cross-lane max / min run on integer images of the floats.
   float inv[E], off[E], scl[E];
   if constexpr (!ASYM) {
@@ -784,12 +788,13 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
   }
 }
 
-// ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
+// ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide.
+// STORE = false: only the outliers are found (nothing is quantised or stored).
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool STORE = true>
 __device__ __forceinline__ void encode_tile(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
                                             TileOutliers<E>& out) {
-  if constexpr (ROWWISE) encode_tile_rowwise<MODE, BITS, ASYM, E>(d, g, raw, out);
-  else encode_tile_general<MODE, BITS, ASYM, E>(d, g, raw, out);
+  if constexpr (ROWWISE) encode_tile_rowwise<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
+  else encode_tile_general<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
 }
 
 // ---- a4: append a tile's outliers, in ascending index order, to `idx_out` / `val_out` starting
@@ -829,10 +834,14 @@ struct WaveStage {
 
 // One wavefront compresses the tiles [unit*T, unit*T + T) of a tensor one after the other.  The
 // outliers of the run are collected in LDS; when the run is done its total is published, the
-// offset of the run in the stream is resolved by look-back, and the staged outliers are
-// copied out in one coalesced sweep.  A run whose outliers do not fit the staging area
-// resolves its offset early (it only has to wait for lower-numbered runs) and from then on
-// appends straight to the stream.
+// offset of the run in the stream is resolved, and the staged outliers are copied out in one
+// coalesced sweep.  No run waits for anything before it has published its own total.
+//
+// A run whose outliers do not fit the staging area keeps encoding and counting but stops
+// collecting; once its offset is known it goes over its uncollected tiles a second time
+// (load, select, nothing else) and writes their outliers straight to the stream.  Dense
+// outliers therefore cost a second read of the input, never a chain of runs waiting for each
+// other.
 template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit, const ScanCtx& sc, WaveStage* stage) {
   static_assert(MODE != kModeNone, "runs exist for the scan only");
@@ -845,32 +854,21 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   const uint32_t gblock0 = d.first_block;                    // index of the tensor's block 0 in state2
   const uint32_t gunit_block0 = d.first_unit + block * kWave;  // first run of this run's block in state1
 
-  bool base_known = false, aborted = false;
-  uint32_t in_block = 0u;   // outliers of the runs before this one in its block
-  uint32_t excl = 0u;       // outliers of the tensor before this run
-  uint32_t run_total = 0u;  // outliers of the run so far
-  uint32_t staged = 0u;     // of which are waiting in LDS
-  uint32_t tile_off = 0u;   // lane k: outliers of the run before its k-th tile
+  uint32_t run_total = 0u;   // outliers of the run so far
+  uint32_t staged = 0u;      // of which are waiting in LDS
+  uint32_t collected = t1;   // first tile whose outliers were not collected (t1: none)
+  uint32_t tile_off = 0u;    // lane k: outliers of the run before its k-th tile
 
-#ifndef ADACC_PREFETCH
-#define ADACC_PREFETCH 1
-#endif
   uint32_t raw[E][4];
-#if ADACC_PREFETCH
   load_tile<E>(d, t0, raw);
   // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
   // complete on every path, and the only wait left is the one for the prefetched tile at the end of
   // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
   __builtin_amdgcn_s_waitcnt(0x0F70);
-#endif
   for (uint32_t t = t0; t < t1; ++t) {
-#if ADACC_PREFETCH
     // the next tile is in flight while this one is encoded (the run's last tile fetches itself again)
     uint32_t nxt[E][4];
     load_tile<E>(d, (t + 1 < t1) ? t + 1 : t, nxt);
-#else
-    load_tile<E>(d, t, raw);
-#endif
 
     const TileGeo<E> g = tile_geo<E>(d, t);
     blank_tail<E>(g, raw);
@@ -879,55 +877,35 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
     if ((uint32_t)lane == t - t0) tile_off = run_total;
 
     if (out.total != 0u) {
-      if (!base_known && staged + out.total > (uint32_t)kStageCap) {
-        // no room: find the run's offset now (this waits for every earlier run) and empty the staging area
-        in_block = scan_poll_sum(sc, sc.state1, gunit_block0, gunit, aborted);
-        excl = in_block + scan_poll_sum(sc, sc.state2, gblock0, gblock0 + block, aborted);
-        base_known = true;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        if (!aborted) {
-          for (uint32_t i = (uint32_t)lane; i < staged; i += kWave) {
-            const uint32_t p = excl + i;
-            if (p < d.cap) { d.idx[p] = stage->idx[i]; d.val[p] = stage->val[i]; }
-          }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        staged = 0u;
-      }
-      if (base_known) {
-        if (!aborted) emit_outliers<E>(raw, out, t, d.idx, d.val, excl + run_total, d.cap);
-        // rare path with a data-dependent number of stores: drain it, so that the common path's
-        // wait counts stay exact
-        __builtin_amdgcn_s_waitcnt(0);
-      } else {
+      if (collected == t1 && staged + out.total > (uint32_t)kStageCap) collected = t;  // no room from here on
+      if (collected == t1) {
         emit_outliers<E>(raw, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
         staged += out.total;
       }
       run_total += out.total;
     }
-#if ADACC_PREFETCH
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
     }
-#endif
   }
 
   // The run is complete: make its total visible, then find its offset in the stream.  The last
   // run of a block closes the block as soon as it knows the totals of the block's other runs,
   // BEFORE it looks at earlier blocks: no block's total depends on another block's, so the
   // longest chain of waits is two (a run's total -> its block's total -> every later run).
-  scan_publish(sc.state1, gunit, sc.tag | (aborted ? kFlagAbort : kFlagAggregate), run_total);
+  bool aborted = false;
+  scan_publish(sc.state1, gunit, sc.tag | kFlagAggregate, run_total);
   const bool closes_block = (unit % kWave) == kWave - 1;
-  if (!base_known) in_block = scan_poll_sum(sc, sc.state1, gunit_block0, gunit, aborted);
+  const uint32_t in_block = scan_poll_sum(sc, sc.state1, gunit_block0, gunit, aborted);
   if (closes_block)
     scan_publish(sc.state2, gblock0 + block, sc.tag | (aborted ? kFlagAbort : kFlagAggregate), in_block + run_total);
-  if (!base_known) {
-    excl = in_block;
-    if (!aborted) excl += scan_poll_sum(sc, sc.state2, gblock0, gblock0 + block, aborted);
-    if (aborted && closes_block) scan_publish(sc.state2, gblock0 + block, sc.tag | kFlagAbort, 0u);
+  uint32_t excl = in_block;  // outliers of the tensor before this run
+  if (!aborted) excl += scan_poll_sum(sc, sc.state2, gblock0, gblock0 + block, aborted);
+  if (aborted) {
+    scan_publish(sc.state1, gunit, sc.tag | kFlagAbort, 0u);
+    if (closes_block) scan_publish(sc.state2, gblock0 + block, sc.tag | kFlagAbort, 0u);
   }
-  if (aborted) scan_publish(sc.state1, gunit, sc.tag | kFlagAbort, 0u);
 
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   if (!aborted) {
@@ -936,6 +914,16 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
       if (p < d.cap) { d.idx[p] = stage->idx[i]; d.val[p] = stage->val[i]; }
     }
     if ((uint32_t)lane < t1 - t0) d.tile_ptr[t0 + (uint32_t)lane] = excl + tile_off;
+    // second pass over the tiles whose outliers were only counted
+    for (uint32_t t = collected; t < t1; ++t) {
+      load_tile<E>(d, t, raw);
+      const TileGeo<E> g = tile_geo<E>(d, t);
+      blank_tail<E>(g, raw);
+      TileOutliers<E> out;
+      encode_tile<MODE, BITS, ASYM, E, ROWWISE, false>(d, g, raw, out);
+      const uint32_t before = (uint32_t)__builtin_amdgcn_readlane((int)tile_off, (int)(t - t0));
+      if (out.total != 0u) emit_outliers<E>(raw, out, t, d.idx, d.val, excl + before, d.cap);
+    }
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the staging area is reused by the next run
   if (lane == 0) {
