@@ -151,6 +151,18 @@ __device__ __forceinline__ void groups_reduce_any_order(T (&s)[E], uint32_t lg, 
   groups_reduce_impl<E, false>(s, lg, op);
 }
 
+// maximum over the whole wavefront, returned in a scalar register: four butterfly steps inside
+// the rows of 16 lanes, two row broadcasts (lane 15 of rows 0 and 2 into rows 1 and 3, then
+// lane 31 into rows 2 and 3), and lane 63 holds the result
+__device__ __forceinline__ uint32_t wave_max_u32_scalar(uint32_t v) {
+  v = lanes_reduce<16>(v, OpUMax());
+  int t = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  v = OpUMax()(v, (uint32_t)t);
+  t = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xC, 0xF, false);      // row_bcast:31
+  v = OpUMax()(v, (uint32_t)t);
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 #pragma unroll
   for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m);
@@ -240,11 +252,12 @@ __device__ __forceinline__ uint32_t pack_bytes4(uint32_t a, uint32_t b, uint32_t
   const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
   return ab | (cd << 16);
 }
+// 8 codes -> 8 nibbles, element e in nibble e: the even and the odd elements are gathered
+// byte-wise first, then one shift and one bit-select interleave them.
 __device__ __forceinline__ uint32_t pack_nibbles8(const uint32_t (&c)[kOct]) {
-  uint32_t w = 0u;
-#pragma unroll
-  for (int e = 0; e < kOct; ++e) w |= (c[e] & 0xFu) << (4 * e);
-  return w;
+  const uint32_t even = pack_bytes4(c[0], c[2], c[4], c[6]);
+  const uint32_t odd = pack_bytes4(c[1], c[3], c[5], c[7]);
+  return (even & 0x0F0F0F0Fu) | ((odd << 4) & 0xF0F0F0F0u);
 }
 
 // ------------------------------------------------------------------ tile geometry, loads and stores
@@ -357,6 +370,7 @@ struct TileOutliers {
   uint32_t row_off[E];    // outliers of the tile in rows before j (uniform)
   uint32_t row_cnt[E];    // outliers of row j (uniform)
   uint32_t total;         // outliers of the tile (uniform)
+  uint32_t sparse;        // bit j: no lane holds more than one outlier of row j (uniform)
 };
 
 // ------------------------------------------------------------------ per-row pieces shared by both tile encoders
@@ -371,35 +385,43 @@ __device__ __forceinline__ float std_limit(float s1, float s2, float inv_gs, flo
 }
 
 // Bookkeeping of one row from the ballots of its 8 outlier tests: per-lane mask, number of the
-// row's outliers in lower lanes, row count.  Only rows that have outliers do the work.  The
-// ballots live in scalar registers; a lane reads its own bit back as a select condition.
+// row's outliers in lower lanes, row count.  Only rows that have outliers do the work, and the
+// usual such row - a few outliers, no two in one lane - does it mostly in scalar registers:
+// the ballots live there, and a lane reads its own bit back as a select condition.
 __device__ __forceinline__ void row_bookkeeping(const uint64_t (&b)[kOct], uint32_t& mask, uint32_t& lane_excl,
-                                                uint32_t& row_cnt, bool& any_out) {
+                                                uint32_t& row_cnt, bool& any_out, bool& sparse) {
   uint64_t any = 0ull;
 #pragma unroll
   for (int e = 0; e < kOct; ++e) any |= b[e];
   any_out = any != 0ull;
+  sparse = true;
   if (any_out) {
-    uint32_t m = 0u, below = 0u, cnt = 0u;
+    uint32_t cnt = 0u;
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) {
-      m |= __builtin_amdgcn_inverse_ballot_w64(b[e]) ? (1u << e) : 0u;
-      below += lanes_below(b[e]);
-      cnt += (uint32_t)__popcll(b[e]);
+    for (int e = 0; e < kOct; ++e) cnt += (uint32_t)__popcll(b[e]);
+    row_cnt = cnt;
+    sparse = cnt == (uint32_t)__popcll(any);
+    uint32_t m = 0u;
+    if (sparse) {
+      lane_excl = lanes_below(any);
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        if (b[e] != 0ull) m |= __builtin_amdgcn_inverse_ballot_w64(b[e]) ? (1u << e) : 0u;  // uniform branch
+      }
+    } else {
+      uint32_t below = 0u;
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        m |= __builtin_amdgcn_inverse_ballot_w64(b[e]) ? (1u << e) : 0u;
+        below += lanes_below(b[e]);
+      }
+      lane_excl = below;
     }
-    mask = m; lane_excl = below; row_cnt = cnt;
+    mask = m;
   } else {
     mask = 0u; lane_excl = 0u; row_cnt = 0u;
   }
 }
-__device__ __forceinline__ void row_bookkeeping(const bool (&o)[kOct], uint32_t& mask, uint32_t& lane_excl,
-                                                uint32_t& row_cnt, bool& any_out) {
-  uint64_t b[kOct];
-#pragma unroll
-  for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(o[e]);
-  row_bookkeeping(b, mask, lane_excl, row_cnt, any_out);
-}
-
 // extremes of the inlier view of one octet: symmetric ext0 = max |y|; asymmetric ext0 = max y, ext1 = min y
 template <bool ASYM>
 __device__ __forceinline__ void row_extremes(const float (&y)[kOct], float& ext0, float& ext1) {
@@ -450,11 +472,13 @@ __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E
   constexpr int Q = 1 << (BITS - 1);
   const float inv_gs = __uint_as_float((127u - d.lgs) << 23);  // 2^-lgs, exact
   out.total = 0u;
+  out.sparse = 0u;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     float x[kOct];
     widen_row(raw[j], x);
-    bool o[kOct];
+    // the 8 outlier tests of the row as wavefront ballots (scalar registers)
+    uint64_t b[kOct];
     if constexpr (MODE == kModeStd) {
       float q[kOct];
 #pragma unroll
@@ -464,26 +488,30 @@ __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E
       s1 = lanes_reduce<LANES>(s1, OpAdd());
       s2 = lanes_reduce<LANES>(s2, OpAdd());
       const float limit = std_limit(s1, s2, inv_gs, d.param);
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(q[e] > limit);
       // an Inf or NaN anywhere in a group makes its limit NaN; only then is the per-element test needed
-      const bool poisoned = __builtin_amdgcn_ballot_w64(limit != limit) != 0ull;
+      if (__builtin_amdgcn_ballot_w64(limit != limit) != 0ull) {
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) o[e] = q[e] > limit;
-      if (poisoned) {
-#pragma unroll
-        for (int e = 0; e < kOct; ++e) o[e] = (q[e] > limit) || is_nonfinite(x[e]);
+        for (int e = 0; e < kOct; ++e) b[e] |= __builtin_amdgcn_ballot_w64(is_nonfinite(x[e]));
       }
     } else {
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) o[e] = outlier_test<MODE>(x[e], d.param);
+      for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(outlier_test<MODE>(x[e], d.param));
     }
-    bool any;
-    row_bookkeeping(o, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
+    bool any, sparse;
+    row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any, sparse);
+    out.sparse = sparse ? (out.sparse | (1u << j)) : (out.sparse & ~(1u << j));
     out.row_off[j] = out.total;
     if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
     if constexpr (STORE) {
       float y[kOct];
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) y[e] = o[e] ? 0.0f : x[e];
+      for (int e = 0; e < kOct; ++e) y[e] = x[e];
+      if (any) {  // uniform: the inlier view differs from the row only where the ballots say so
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) y[e] = __builtin_amdgcn_inverse_ballot_w64(b[e]) ? 0.0f : x[e];
+      }
       float ext0, ext1;
       row_extremes<ASYM>(y, ext0, ext1);
       float scl, inv, off;
@@ -555,13 +583,13 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
     }
   }
   const uint32_t lane = (uint32_t)lane_id();
-  uint32_t cur[E], win[E];
+  uint32_t cur[E], win[E];  // win[] is uniform
   bool nonfinite = false;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const uint32_t hi = m[j] >> 16, lo = m[j] & 0xFFFFu;
     const uint32_t mx = hi > lo ? hi : lo;
-    nonfinite |= mx >= 0x7F80u;
+    if ((j & (R - 1)) == 0) nonfinite |= mx >= 0x7F80u;
     cur[j] = (mx << 6) | lane;  // unique per lane: equal maxima are taken one after the other
     win[j] = 0u;
   }
@@ -569,7 +597,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       if ((j & (R - 1)) != 0) continue;  // uniform: a group's state lives in its first row
-      win[j] = lanes_reduce<kWave>(cur[j], OpUMax());
+      win[j] = wave_max_u32_scalar(cur[j]);
       cur[j] = (cur[j] == win[j]) ? 0u : cur[j];
     }
   }
@@ -631,6 +659,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
                                               const float (&limit)[E], const uint32_t (&thr)[E], bool by_magnitude,
                                               bool poisoned, uint32_t lane_pos, int R, float (&ext0)[E],
                                               float (&ext1)[E], TileOutliers<E>& out) {
+  out.sparse = 0u;
   forget_derived<E>(raw);  // nothing formed from the octets so far is worth its registers
 #pragma unroll
   for (int j = 0; j < E; ++j) {
@@ -661,8 +690,9 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
 #pragma unroll
       for (int e = 0; e < kOct; ++e) b[e] |= __builtin_amdgcn_ballot_w64(is_nonfinite(x[e]));
     }
-    bool any;
-    row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any);
+    bool any, sparse;
+    row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any, sparse);
+    out.sparse = sparse ? (out.sparse | (1u << j)) : (out.sparse & ~(1u << j));
     if (any) {
       float y[kOct];
 #pragma unroll
@@ -727,7 +757,12 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
 #pragma unroll
         for (int j = 0; j < E; ++j) thr[j] = __float_as_uint(thrf[j]);
       }
-      if (!by_magnitude) poisoned = topk_select_rounds<E>(d, raw, thr, lane_pos, R);
+      if (!by_magnitude) {
+        // nothing on this rare path may be prepared outside the loop over tiles (32 position codes
+        // would otherwise sit in registers for the whole run)
+        asm volatile("" : "+v"(lane_pos));
+        poisoned = topk_select_rounds<E>(d, raw, thr, lane_pos, R);
+      }
       outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, by_magnitude, poisoned, lane_pos, R, ext0, ext1, out);
       if (!by_magnitude) break;
       // the selection stands if every group has exactly k elements at or above its threshold
@@ -754,22 +789,52 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
   if constexpr (!STORE) return;  // the caller only wants the outliers
 
   // ---- a6: per-group scale (and offset).  Cross-lane max / min run on integer images of the floats.
+  // Every lane of a group would compute the same scale; with at least 4 lanes per group and 4 rows,
+  // lane l of every quad takes row l instead, so that one division serves the whole tile, and the
+  // results go back to the rows by a broadcast inside the quad.
   float inv[E], off[E], scl[E];
+  const bool transposed = (E == 4) && d.lgq >= 5u;
+  const bool row1 = __builtin_amdgcn_inverse_ballot_w64(0x2222222222222222ull);
+  const bool row2 = __builtin_amdgcn_inverse_ballot_w64(0x4444444444444444ull);
+  const bool row3 = __builtin_amdgcn_inverse_ballot_w64(0x8888888888888888ull);
   if constexpr (!ASYM) {
     uint32_t a[E];  // max |y| as bit patterns: for non-negative floats the integer order is the float order
 #pragma unroll
     for (int j = 0; j < E; ++j) a[j] = __float_as_uint(ext0[j]);
     groups_reduce_any_order<E>(a, d.lgq, OpUMax());
+    if (transposed) {
+      uint32_t am = row1 ? a[1 % E] : a[0];
+      am = row2 ? a[2 % E] : am;
+      am = row3 ? a[3 % E] : am;
+      float s, i, o;
+      group_scale<false>(d, am, 0, 0, s, i, o);
+      scl[0] = dpp_move<0x00>(s); scl[1 % E] = dpp_move<0x55>(s); scl[2 % E] = dpp_move<0xAA>(s); scl[3 % E] = dpp_move<0xFF>(s);
+      inv[0] = dpp_move<0x00>(i); inv[1 % E] = dpp_move<0x55>(i); inv[2 % E] = dpp_move<0xAA>(i); inv[3 % E] = dpp_move<0xFF>(i);
 #pragma unroll
-    for (int j = 0; j < E; ++j) group_scale<false>(d, a[j], 0, 0, scl[j], inv[j], off[j]);
+      for (int j = 0; j < E; ++j) off[j] = 0.0f;
+    } else {
+#pragma unroll
+      for (int j = 0; j < E; ++j) group_scale<false>(d, a[j], 0, 0, scl[j], inv[j], off[j]);
+    }
   } else {
     int32_t hi[E], lo[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) { hi[j] = float_key(ext0[j]); lo[j] = float_key(ext1[j]); }
     groups_reduce_any_order<E>(hi, d.lgq, OpIMax());
     groups_reduce_any_order<E>(lo, d.lgq, OpIMin());
+    if (transposed) {
+      int32_t h = row1 ? hi[1 % E] : hi[0], l = row1 ? lo[1 % E] : lo[0];
+      h = row2 ? hi[2 % E] : h; l = row2 ? lo[2 % E] : l;
+      h = row3 ? hi[3 % E] : h; l = row3 ? lo[3 % E] : l;
+      float s, i, o;
+      group_scale<true>(d, 0u, h, l, s, i, o);
+      scl[0] = dpp_move<0x00>(s); scl[1 % E] = dpp_move<0x55>(s); scl[2 % E] = dpp_move<0xAA>(s); scl[3 % E] = dpp_move<0xFF>(s);
+      inv[0] = dpp_move<0x00>(i); inv[1 % E] = dpp_move<0x55>(i); inv[2 % E] = dpp_move<0xAA>(i); inv[3 % E] = dpp_move<0xFF>(i);
+      off[0] = dpp_move<0x00>(o); off[1 % E] = dpp_move<0x55>(o); off[2 % E] = dpp_move<0xAA>(o); off[3 % E] = dpp_move<0xFF>(o);
+    } else {
 #pragma unroll
-    for (int j = 0; j < E; ++j) group_scale<true>(d, 0u, hi[j], lo[j], scl[j], inv[j], off[j]);
+      for (int j = 0; j < E; ++j) group_scale<true>(d, 0u, hi[j], lo[j], scl[j], inv[j], off[j]);
+    }
   }
 
   // ---- a7 + a8: quantise, pack, store codes and scales
@@ -811,21 +876,34 @@ __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const
       const uint32_t bits = out.mask[j];
       uint32_t pos = pos0 + out.row_off[j] + out.lane_excl[j];
       const uint32_t i0 = lane_first + (uint32_t)(j * kRow);
-      static_for<kOct>([&](auto Ec) {
-        constexpr int e = decltype(Ec)::value;
-        if ((bits >> e) & 1u) {
-          if (pos < limit) {
-            idx_out[pos] = (int32_t)(i0 + (uint32_t)e);
-            val_out[pos] = (uint16_t)((e & 1) ? (raw[j][e >> 1] >> 16) : (raw[j][e >> 1] & 0xFFFFu));
-          }
-          ++pos;
+      if ((out.sparse >> j) & 1u) {  // uniform: at most one outlier per lane
+        if (bits != 0u && pos < limit) {
+          const uint32_t e = (uint32_t)__builtin_ctz(bits);
+          const uint64_t lo = ((uint64_t)raw[j][1] << 32) | raw[j][0], hi = ((uint64_t)raw[j][3] << 32) | raw[j][2];
+          const uint64_t half = (e & 4u) ? hi : lo;
+          idx_out[pos] = (int32_t)(i0 + e);
+          val_out[pos] = (uint16_t)(half >> ((e & 3u) * 16u));
         }
-      });
+      } else {
+        static_for<kOct>([&](auto Ec) {
+          constexpr int e = decltype(Ec)::value;
+          if ((bits >> e) & 1u) {
+            if (pos < limit) {
+              idx_out[pos] = (int32_t)(i0 + (uint32_t)e);
+              val_out[pos] = (uint16_t)((e & 1) ? (raw[j][e >> 1] >> 16) : (raw[j][e >> 1] & 0xFFFFu));
+            }
+            ++pos;
+          }
+        });
+      }
     }
   });
 }
 
 // ------------------------------------------------------------------ one run of tiles (outlier modes)
+#ifndef ADACC_PREFETCH_DEPTH
+#define ADACC_PREFETCH_DEPTH 1
+#endif
 constexpr int kStageCap = 256;  // outliers a wavefront can hold back in LDS while its offset is unknown
 struct WaveStage {
   int32_t idx[kStageCap];
@@ -861,6 +939,10 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
 
   uint32_t raw[E][4];
   load_tile<E>(d, t0, raw);
+#if ADACC_PREFETCH_DEPTH == 2
+  uint32_t nx1[E][4];
+  load_tile<E>(d, (t0 + 1 < t1) ? t0 + 1 : t0, nx1);
+#endif
   // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
   // complete on every path, and the only wait left is the one for the prefetched tile at the end of
   // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
@@ -868,12 +950,20 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   for (uint32_t t = t0; t < t1; ++t) {
     // the next tile is in flight while this one is encoded (the run's last tile fetches itself again)
     uint32_t nxt[E][4];
+#if ADACC_PREFETCH_DEPTH == 2
+    load_tile<E>(d, (t + 2 < t1) ? t + 2 : t, nxt);
+#else
     load_tile<E>(d, (t + 1 < t1) ? t + 1 : t, nxt);
+#endif
 
     const TileGeo<E> g = tile_geo<E>(d, t);
     blank_tail<E>(g, raw);
     TileOutliers<E> out;
+#ifdef ADACC_X_NOSTORE
+    encode_tile<MODE, BITS, ASYM, E, ROWWISE, false>(d, g, raw, out);
+#else
     encode_tile<MODE, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+#endif
     if ((uint32_t)lane == t - t0) tile_off = run_total;
 
     if (out.total != 0u) {
@@ -886,7 +976,12 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
     }
 #pragma unroll
     for (int j = 0; j < E; ++j) {
+#if ADACC_PREFETCH_DEPTH == 2
+      raw[j][0] = nx1[j][0]; raw[j][1] = nx1[j][1]; raw[j][2] = nx1[j][2]; raw[j][3] = nx1[j][3];
+      nx1[j][0] = nxt[j][0]; nx1[j][1] = nxt[j][1]; nx1[j][2] = nxt[j][2]; nx1[j][3] = nxt[j][3];
+#else
       raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
+#endif
     }
   }
 
