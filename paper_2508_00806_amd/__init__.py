@@ -213,25 +213,41 @@ def _batch_args(methods, tensors_a, numels, tensors_b):
     return n, cms, pa, cn, pb
 
 
-def compress_batch(methods, srcs, blobs, workspace, stream=None):
-    numels = [0 if s is None else s.numel() for s in srcs]
-    n, cms, ps, cn, pb = _batch_args(methods, srcs, numels, blobs)
-    bb = (ctypes.c_uint64 * n)(*[0 if b is None else _nbytes(b) for b in blobs])
-    _check(lib().adacc_compress_batch(n, cms, ps, cn, pb, bb, _ws(workspace), _stream(stream)),
-           "adacc_compress_batch")
+class BatchArgs:
+    """The argument arrays of a batch call, marshalled once.  A training loop that compresses the
+    same set of buffers every step builds this once and calls it every step; the tensors are kept
+    alive by the object."""
+
+    def __init__(self, methods, tensors_a, tensors_b, numels, blobs):
+        self.n, self.methods, self.pa, self.numels, self.pb = _batch_args(methods, tensors_a, numels, tensors_b)
+        self.blob_bytes = (ctypes.c_uint64 * self.n)(*[0 if b is None else _nbytes(b) for b in blobs])
+        self.keep = (list(tensors_a), list(tensors_b))
 
 
-def decompress_batch(methods, blobs, dsts, workspace, stream=None):
+def prepare_compress_batch(methods, srcs, blobs) -> BatchArgs:
+    return BatchArgs(methods, srcs, blobs, [0 if s is None else s.numel() for s in srcs], blobs)
+
+
+def prepare_decompress_batch(methods, blobs, dsts) -> BatchArgs:
     import torch
-    numels = [0 if d is None else d.numel() for d in dsts]
-    n, cms, pb, cn, pd = _batch_args(methods, blobs, numels, dsts)
-    bb = (ctypes.c_uint64 * n)(*[0 if b is None else _nbytes(b) for b in blobs])
     kinds = {d.dtype for d in dsts if d is not None}
     if len(kinds) > 1:
         raise TypeError("all dsts of a batch share one dtype")
-    dtype = DST_F32 if kinds == {torch.float32} else DST_BF16
-    _check(lib().adacc_decompress_batch(n, cms, pb, bb, cn, pd, dtype, _ws(workspace), _stream(stream)),
-           "adacc_decompress_batch")
+    args = BatchArgs(methods, blobs, dsts, [0 if d is None else d.numel() for d in dsts], blobs)
+    args.dst_dtype = DST_F32 if kinds == {torch.float32} else DST_BF16
+    return args
+
+
+def compress_batch(methods, srcs, blobs, workspace, stream=None, prepared: BatchArgs = None):
+    a = prepared or prepare_compress_batch(methods, srcs, blobs)
+    _check(lib().adacc_compress_batch(a.n, a.methods, a.pa, a.numels, a.pb, a.blob_bytes, _ws(workspace),
+                                      _stream(stream)), "adacc_compress_batch")
+
+
+def decompress_batch(methods, blobs, dsts, workspace, stream=None, prepared: BatchArgs = None):
+    a = prepared or prepare_decompress_batch(methods, blobs, dsts)
+    _check(lib().adacc_decompress_batch(a.n, a.methods, a.pa, a.blob_bytes, a.numels, a.pb, a.dst_dtype,
+                                        _ws(workspace), _stream(stream)), "adacc_decompress_batch")
 
 
 def read_status(blob, layout: CLayout, stream=None):

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
 #include <vector>
 
 #include "adacc.h"
@@ -59,27 +60,35 @@ __device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_
   return lo;
 }
 
-template <int MODE>
+// Variants with tiles of 8 rows need about twice the registers of those with 4; a kernel that
+// held both would run everything at the occupancy of the heaviest.  So the batch comes as two
+// kernels over the same table, and a wavefront whose tensor belongs to the other one leaves.
+template <int MODE, bool EIGHT_ROWS>
 __device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
                                                        WaveStage* stage) {
-  if (d.rowwise) {  // groups inside a row: E is always 4
-    switch (d.variant & 7u) {
-      case 0: compress_run<MODE, 4, false, 4, true>(d, unit, sc, stage); break;
-      case 2: compress_run<MODE, 4, true, 4, true>(d, unit, sc, stage); break;
-      case 4: compress_run<MODE, 8, false, 4, true>(d, unit, sc, stage); break;
-      default: compress_run<MODE, 8, true, 4, true>(d, unit, sc, stage); break;
+  if constexpr (!EIGHT_ROWS) {
+    if (d.rowwise) {  // groups inside a row
+      switch (d.variant & 6u) {
+        case 0: compress_run<MODE, 4, false, 4, true>(d, unit, sc, stage); break;
+        case 2: compress_run<MODE, 4, true, 4, true>(d, unit, sc, stage); break;
+        case 4: compress_run<MODE, 8, false, 4, true>(d, unit, sc, stage); break;
+        default: compress_run<MODE, 8, true, 4, true>(d, unit, sc, stage); break;
+      }
+      return;
     }
-    return;
-  }
-  switch (d.variant & 7u) {
-    case 0: compress_run<MODE, 4, false, 4, false>(d, unit, sc, stage); break;
-    case 1: compress_run<MODE, 4, false, 8, false>(d, unit, sc, stage); break;
-    case 2: compress_run<MODE, 4, true, 4, false>(d, unit, sc, stage); break;
-    case 3: compress_run<MODE, 4, true, 8, false>(d, unit, sc, stage); break;
-    case 4: compress_run<MODE, 8, false, 4, false>(d, unit, sc, stage); break;
-    case 5: compress_run<MODE, 8, false, 8, false>(d, unit, sc, stage); break;
-    case 6: compress_run<MODE, 8, true, 4, false>(d, unit, sc, stage); break;
-    default: compress_run<MODE, 8, true, 8, false>(d, unit, sc, stage); break;
+    switch (d.variant & 6u) {
+      case 0: compress_run<MODE, 4, false, 4, false>(d, unit, sc, stage); break;
+      case 2: compress_run<MODE, 4, true, 4, false>(d, unit, sc, stage); break;
+      case 4: compress_run<MODE, 8, false, 4, false>(d, unit, sc, stage); break;
+      default: compress_run<MODE, 8, true, 4, false>(d, unit, sc, stage); break;
+    }
+  } else {
+    switch (d.variant & 6u) {
+      case 0: compress_run<MODE, 4, false, 8, false>(d, unit, sc, stage); break;
+      case 2: compress_run<MODE, 4, true, 8, false>(d, unit, sc, stage); break;
+      case 4: compress_run<MODE, 8, false, 8, false>(d, unit, sc, stage); break;
+      default: compress_run<MODE, 8, true, 8, false>(d, unit, sc, stage); break;
+    }
   }
 }
 
@@ -90,8 +99,9 @@ __device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t
   for (uint32_t t = t0; t < t1; ++t) compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
 }
 
-// One launch for a table of tensors: runs are numbered across the table; a wavefront finds
-// its tensor by binary search and dispatches on that tensor's method.
+// One launch (per register class) for a table of tensors: runs are numbered across the table; a
+// wavefront finds its tensor by binary search and dispatches on that tensor's method.
+template <bool EIGHT_ROWS>
 __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
                                                                   uint32_t total_units, uint64_t* state1,
                                                                   uint64_t* state2, uint32_t tag,
@@ -103,32 +113,38 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDe
   if (g >= total_units) return;
   const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<true>(table, n, g));
   const TensorDesc d = table[ti];
+  if (((d.variant & 1u) != 0u) != EIGHT_ROWS) return;
   const uint32_t unit = g - d.first_unit;
   switch (d.variant >> 3) {
     case kModeNone:
-      if (d.rowwise) {
-        switch (d.variant & 7u) {
-          case 0: compress_plain_run<4, false, 4, true>(d, unit); break;
-          case 2: compress_plain_run<4, true, 4, true>(d, unit); break;
-          case 4: compress_plain_run<8, false, 4, true>(d, unit); break;
-          default: compress_plain_run<8, true, 4, true>(d, unit); break;
+      if constexpr (!EIGHT_ROWS) {
+        if (d.rowwise) {
+          switch (d.variant & 6u) {
+            case 0: compress_plain_run<4, false, 4, true>(d, unit); break;
+            case 2: compress_plain_run<4, true, 4, true>(d, unit); break;
+            case 4: compress_plain_run<8, false, 4, true>(d, unit); break;
+            default: compress_plain_run<8, true, 4, true>(d, unit); break;
+          }
+          break;
         }
-        break;
-      }
-      switch (d.variant & 7u) {
-        case 0: compress_plain_run<4, false, 4, false>(d, unit); break;
-        case 1: compress_plain_run<4, false, 8, false>(d, unit); break;
-        case 2: compress_plain_run<4, true, 4, false>(d, unit); break;
-        case 3: compress_plain_run<4, true, 8, false>(d, unit); break;
-        case 4: compress_plain_run<8, false, 4, false>(d, unit); break;
-        case 5: compress_plain_run<8, false, 8, false>(d, unit); break;
-        case 6: compress_plain_run<8, true, 4, false>(d, unit); break;
-        default: compress_plain_run<8, true, 8, false>(d, unit); break;
+        switch (d.variant & 6u) {
+          case 0: compress_plain_run<4, false, 4, false>(d, unit); break;
+          case 2: compress_plain_run<4, true, 4, false>(d, unit); break;
+          case 4: compress_plain_run<8, false, 4, false>(d, unit); break;
+          default: compress_plain_run<8, true, 4, false>(d, unit); break;
+        }
+      } else {
+        switch (d.variant & 6u) {
+          case 0: compress_plain_run<4, false, 8, false>(d, unit); break;
+          case 2: compress_plain_run<4, true, 8, false>(d, unit); break;
+          case 4: compress_plain_run<8, false, 8, false>(d, unit); break;
+          default: compress_plain_run<8, true, 8, false>(d, unit); break;
+        }
       }
       break;
-    case kModeAbs: compress_dispatch_mode<kModeAbs>(d, unit, sc, &stage[wave]); break;
-    case kModeStd: compress_dispatch_mode<kModeStd>(d, unit, sc, &stage[wave]); break;
-    default: compress_dispatch_mode<kModeTopk>(d, unit, sc, &stage[wave]); break;
+    case kModeAbs: compress_dispatch_mode<kModeAbs, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
+    case kModeStd: compress_dispatch_mode<kModeStd, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
+    default: compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
   }
 }
 
@@ -138,9 +154,22 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<8, F32>()];
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
   unsigned char* slice = lds + wave * decompress_lds_per_wave<8, F32>();
-  for (uint32_t g = blockIdx.x * kWavesPerWg + wave; g < total_tiles; g += gridDim.x * kWavesPerWg) {
-    const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<false>(table, n, g));
-    const TensorDesc d = table[ti];
+  // A wavefront's tiles ascend, so the tensor of a tile is the one of the previous tile or a later
+  // one: one binary search at the start, then a walk, and the descriptor is read again only when
+  // the tensor changes.
+  uint32_t g = blockIdx.x * kWavesPerWg + wave;
+  if (g >= total_tiles) return;
+  uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<false>(table, n, g));
+  TensorDesc d = table[ti];
+  uint32_t next_first = (ti + 1u < n) ? table[ti + 1u].first_tile : 0xFFFFFFFFu;
+  for (; g < total_tiles; g += gridDim.x * kWavesPerWg) {
+    if (g >= next_first) {
+      do {
+        ++ti;
+        next_first = (ti + 1u < n) ? table[ti + 1u].first_tile : 0xFFFFFFFFu;
+      } while (g >= next_first);
+      d = table[ti];
+    }
     const uint32_t tile = g - d.first_tile;
     const bool ho = (d.variant >> 3) != kModeNone;
     switch (d.variant & 7u) {
@@ -157,6 +186,20 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
 }
 
 // ---- utilities
+// The table of a batch reaches the device as kernel arguments, a slice per launch: the runtime
+// copies kernel arguments when the launch is enqueued, so the host buffer may go away at once
+// and the host never waits for the stream (a copy from pageable memory would).
+constexpr uint32_t kDescsPerUpload = 24;
+struct DescSlice { TensorDesc d[kDescsPerUpload]; };
+static_assert(sizeof(DescSlice) <= 3968, "kernel arguments are limited to 4 KiB");
+static_assert(sizeof(TensorDesc) % 4 == 0, "copied as 32-bit words");
+__global__ __launch_bounds__(kThreads) void table_upload_kernel(DescSlice slice, TensorDesc* dst, uint32_t count) {
+  const uint32_t words = count * (uint32_t)(sizeof(TensorDesc) / 4);
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(&slice);
+  uint32_t* out = reinterpret_cast<uint32_t*>(dst);
+  for (uint32_t i = threadIdx.x; i < words; i += kThreads) out[i] = src[i];
+}
+
 // clears a workspace (a kernel rather than a memset node, so that callers may capture it in a graph)
 __global__ __launch_bounds__(kThreads) void workspace_clear_kernel(uint4* p, uint64_t n16) {
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -392,6 +435,19 @@ static int launch_check(const char* what) {
   return e == hipSuccess ? ADACC_OK : hip_fail(e, what);
 }
 
+static int upload_table(const std::vector<TensorDesc>& table, TensorDesc* dst, hipStream_t s) {
+  for (size_t i = 0; i < table.size(); i += kDescsPerUpload) {
+    DescSlice slice;
+    const uint32_t count = (uint32_t)std::min<size_t>(kDescsPerUpload, table.size() - i);
+    std::memset(&slice, 0, sizeof slice);
+    std::memcpy(slice.d, table.data() + i, count * sizeof(TensorDesc));
+    hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(kThreads), 0, s, slice, dst + i, count);
+    const int rc = launch_check("table_upload_kernel");
+    if (rc != ADACC_OK) return rc;
+  }
+  return ADACC_OK;
+}
+
 static int clear_device(void* mem, uint64_t bytes, hipStream_t s) {
   const uint64_t n16 = bytes / 16;
   uint32_t grid = (uint32_t)((n16 + kThreads - 1) / kThreads);
@@ -610,8 +666,12 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   int cus = 0;
   rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
+  bool any_four = false, any_eight = false;
+  for (const TensorDesc& t : table) ((t.variant & 1u) ? any_eight : any_four) = true;
+  // run length from the kernel that most tensors use (the other one simply takes more rounds)
   uint32_t capacity = 0;
-  rc = wave_capacity(reinterpret_cast<const void*>(compress_batch_kernel), cus, &capacity);
+  rc = wave_capacity(any_four ? reinterpret_cast<const void*>(compress_batch_kernel<false>)
+                              : reinterpret_cast<const void*>(compress_batch_kernel<true>), cus, &capacity);
   if (rc != ADACC_OK) return rc;
   table.clear();
   rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true,
@@ -622,14 +682,18 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   rc = next_tag(ws, s, &tag);
   if (rc != ADACC_OK) return rc;
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
-  const hipError_t e = hipMemcpyAsync(mem + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
-                                      hipMemcpyHostToDevice, s);
-  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
+  rc = upload_table(table, reinterpret_cast<TensorDesc*>(mem + bp.table_off), s);
+  if (rc != ADACC_OK) return rc;
   const uint32_t grid = (total_units + kWavesPerWg - 1) / kWavesPerWg;
-  hipLaunchKernelGGL(compress_batch_kernel, dim3(grid), dim3(kThreads), 0, s,
-                     reinterpret_cast<const TensorDesc*>(mem + bp.table_off), (uint32_t)table.size(), total_units,
-                     reinterpret_cast<uint64_t*>(mem), reinterpret_cast<uint64_t*>(mem + state1_bytes(total)), tag,
-                     spin_limit());
+  const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
+  uint64_t* st1 = reinterpret_cast<uint64_t*>(mem);
+  uint64_t* st2 = reinterpret_cast<uint64_t*>(mem + state1_bytes(total));
+  if (any_four)
+    hipLaunchKernelGGL(compress_batch_kernel<false>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
+                       total_units, st1, st2, tag, spin_limit());
+  if (any_eight)
+    hipLaunchKernelGGL(compress_batch_kernel<true>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
+                       total_units, st1, st2, tag, spin_limit());
   return launch_check("compress_batch_kernel");
 }
 
@@ -657,9 +721,8 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
-  const hipError_t e = hipMemcpyAsync(mem + bp.table_off, table.data(), table.size() * sizeof(TensorDesc),
-                                      hipMemcpyHostToDevice, s);
-  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(table)");
+  rc = upload_table(table, reinterpret_cast<TensorDesc*>(mem + bp.table_off), s);
+  if (rc != ADACC_OK) return rc;
   const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
   if (dst_dtype == ADACC_DST_F32)
     hipLaunchKernelGGL(decompress_batch_kernel<true>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);

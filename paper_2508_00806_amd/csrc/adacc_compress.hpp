@@ -901,9 +901,6 @@ __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const
 }
 
 // ------------------------------------------------------------------ one run of tiles (outlier modes)
-#ifndef ADACC_PREFETCH_DEPTH
-#define ADACC_PREFETCH_DEPTH 1
-#endif
 constexpr int kStageCap = 256;  // outliers a wavefront can hold back in LDS while its offset is unknown
 struct WaveStage {
   int32_t idx[kStageCap];
@@ -937,33 +934,26 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   uint32_t collected = t1;   // first tile whose outliers were not collected (t1: none)
   uint32_t tile_off = 0u;    // lane k: outliers of the run before its k-th tile
 
+  // Tiles of 4 rows: the next tile is in flight while this one is encoded.  Tiles of 8 rows are
+  // loaded when their turn comes: a second tile in registers would halve the wavefronts per SIMD.
+  constexpr bool kPrefetch = (E == 4);
   uint32_t raw[E][4];
-  load_tile<E>(d, t0, raw);
-#if ADACC_PREFETCH_DEPTH == 2
-  uint32_t nx1[E][4];
-  load_tile<E>(d, (t0 + 1 < t1) ? t0 + 1 : t0, nx1);
-#endif
-  // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
-  // complete on every path, and the only wait left is the one for the prefetched tile at the end of
-  // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
-  __builtin_amdgcn_s_waitcnt(0x0F70);
+  if constexpr (kPrefetch) {
+    load_tile<E>(d, t0, raw);
+    // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
+    // complete on every path, and the only wait left is the one for the prefetched tile at the end of
+    // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
   for (uint32_t t = t0; t < t1; ++t) {
-    // the next tile is in flight while this one is encoded (the run's last tile fetches itself again)
-    uint32_t nxt[E][4];
-#if ADACC_PREFETCH_DEPTH == 2
-    load_tile<E>(d, (t + 2 < t1) ? t + 2 : t, nxt);
-#else
-    load_tile<E>(d, (t + 1 < t1) ? t + 1 : t, nxt);
-#endif
+    uint32_t nxt[kPrefetch ? E : 1][4];
+    if constexpr (kPrefetch) load_tile<E>(d, (t + 1 < t1) ? t + 1 : t, nxt);  // the run's last tile fetches itself again
+    else load_tile<E>(d, t, raw);
 
     const TileGeo<E> g = tile_geo<E>(d, t);
     blank_tail<E>(g, raw);
     TileOutliers<E> out;
-#ifdef ADACC_X_NOSTORE
-    encode_tile<MODE, BITS, ASYM, E, ROWWISE, false>(d, g, raw, out);
-#else
     encode_tile<MODE, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
-#endif
     if ((uint32_t)lane == t - t0) tile_off = run_total;
 
     if (out.total != 0u) {
@@ -974,14 +964,11 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
       }
       run_total += out.total;
     }
+    if constexpr (kPrefetch) {
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-#if ADACC_PREFETCH_DEPTH == 2
-      raw[j][0] = nx1[j][0]; raw[j][1] = nx1[j][1]; raw[j][2] = nx1[j][2]; raw[j][3] = nx1[j][3];
-      nx1[j][0] = nxt[j][0]; nx1[j][1] = nxt[j][1]; nx1[j][2] = nxt[j][2]; nx1[j][3] = nxt[j][3];
-#else
-      raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
-#endif
+      for (int j = 0; j < E; ++j) {
+        raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
+      }
     }
   }
 
