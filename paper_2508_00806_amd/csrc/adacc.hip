@@ -148,12 +148,15 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDe
   }
 }
 
-template <bool F32>
+// Like the batch compression, in two kernels: tiles of 8 rows need twice the staging area in LDS,
+// which would limit the wavefronts per CU for every tensor of the table.
+template <bool F32, bool EIGHT_ROWS>
 __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, uint32_t n,
                                                                     uint32_t total_tiles) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<8, F32>()];
+  constexpr int kRows = EIGHT_ROWS ? 8 : 4;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<kRows, F32>()];
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<8, F32>();
+  unsigned char* slice = lds + wave * decompress_lds_per_wave<kRows, F32>();
   // A wavefront's tiles ascend, so the tensor of a tile is the one of the previous tile or a later
   // one: one binary search at the start, then a walk, and the descriptor is read again only when
   // the tensor changes.
@@ -170,17 +173,14 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
       } while (g >= next_first);
       d = table[ti];
     }
+    if (((d.variant & 1u) != 0u) != EIGHT_ROWS) continue;  // the other kernel's tensor
     const uint32_t tile = g - d.first_tile;
     const bool ho = (d.variant >> 3) != kModeNone;
-    switch (d.variant & 7u) {
-      case 0: decompress_tile<4, false, 4, F32>(d, tile, ho, slice); break;
-      case 1: decompress_tile<4, false, 8, F32>(d, tile, ho, slice); break;
-      case 2: decompress_tile<4, true, 4, F32>(d, tile, ho, slice); break;
-      case 3: decompress_tile<4, true, 8, F32>(d, tile, ho, slice); break;
-      case 4: decompress_tile<8, false, 4, F32>(d, tile, ho, slice); break;
-      case 5: decompress_tile<8, false, 8, F32>(d, tile, ho, slice); break;
-      case 6: decompress_tile<8, true, 4, F32>(d, tile, ho, slice); break;
-      default: decompress_tile<8, true, 8, F32>(d, tile, ho, slice); break;
+    switch (d.variant & 6u) {
+      case 0: decompress_tile<4, false, kRows, F32>(d, tile, ho, slice); break;
+      case 2: decompress_tile<4, true, kRows, F32>(d, tile, ho, slice); break;
+      case 4: decompress_tile<8, false, kRows, F32>(d, tile, ho, slice); break;
+      default: decompress_tile<8, true, kRows, F32>(d, tile, ho, slice); break;
     }
   }
 }
@@ -309,12 +309,29 @@ static void fill_layout(const adacc_method* m, uint64_t numel, const Plan& p, ad
   L->n_tiles = p.n_tiles;
 }
 
-// Wavefronts of `kernel` that the device can hold at once.
-static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
+// Workgroups of `kernel` that one CU holds at once (cached per kernel: the query is not free).
+static int resident_wgs(const void* kernel, int* wgs_out) {
+  struct Entry { const void* kernel; int wgs; };
+  static thread_local Entry cache[64];
+  static thread_local int used = 0;
+  for (int i = 0; i < used; ++i)
+    if (cache[i].kernel == kernel) { *wgs_out = cache[i].wgs; return ADACC_OK; }
   int wgs = 0;
   const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs, kernel, kThreads, 0);
   if (e != hipSuccess) return hip_fail(e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
   if (wgs < 1) wgs = 1;
+  if (used < 64) cache[used++] = Entry{kernel, wgs};
+  *wgs_out = wgs;
+  return ADACC_OK;
+}
+
+// Wavefronts of `kernel` that the device can hold at once.
+static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
+  int wgs = 0;
+  const int rc = resident_wgs(kernel, &wgs);
+  if (rc != ADACC_OK) return rc;
+  const int forced = env_int("ADACC_WGS_PER_CU", 0);
+  if (forced > 0) wgs = forced;
   *waves = (uint32_t)(cus * wgs * kWavesPerWg);
   return ADACC_OK;
 }
@@ -326,7 +343,6 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
 // number of runs in flight, not with the number of tiles.
 static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
   const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64) > 64 ? 64 : (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64);
-  if (env_int("ADACC_FORCE_TILES_PER_UNIT", 0) > 0) return (uint32_t)env_int("ADACC_FORCE_TILES_PER_UNIT", 0);  // experiment knob
   if (tiles_in_launch <= capacity) return 1u;
   const uint64_t rounds = (tiles_in_launch + (uint64_t)capacity * tmax - 1) / ((uint64_t)capacity * tmax);
   const uint64_t units = (uint64_t)capacity * rounds;
@@ -373,12 +389,17 @@ static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<ui
 
 static uint32_t spin_limit() { return (uint32_t)env_int("ADACC_SPIN_LIMIT", 1 << 22); }
 
-// Grid for kernels whose tiles are independent (grid-stride loop, capped per CU).
-static int grid_for(uint32_t n_tiles, uint32_t* grid) {
+// Grid for kernels whose tiles are independent (grid-stride loop): `rounds` times as many
+// workgroups as the device holds at once.  A grid that is no whole multiple of that number ends
+// in a round that keeps only part of the device busy.
+static int grid_for(uint32_t n_tiles, const void* kernel, uint32_t rounds, uint32_t* grid) {
   int cus = 0;
-  const int rc = device_cus(&cus);
+  int rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
-  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_WGS_PER_CU", 8);
+  uint32_t waves = 0;
+  rc = wave_capacity(kernel, cus, &waves);
+  if (rc != ADACC_OK) return rc;
+  const uint64_t cap = (uint64_t)(waves / kWavesPerWg) * rounds;
   const uint64_t want = ((uint64_t)n_tiles + kWavesPerWg - 1) / kWavesPerWg;
   *grid = (uint32_t)(want < cap ? want : cap);
   if (*grid == 0) *grid = 1;
@@ -562,7 +583,7 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
     grid = (d.n_units + kWavesPerWg - 1) / kWavesPerWg;  // runs start in index order: no grid-stride loop
     rc = next_tag(ws, s, &tag);
   } else {
-    rc = grid_for(p.n_tiles, &grid);
+    rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), 2u, &grid);
   }
   if (rc != ADACC_OK) return rc;
   uint64_t* state1 = p.outliers ? static_cast<uint64_t*>(ws->device_mem) : nullptr;
@@ -586,10 +607,10 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, 0, &d);
-  uint32_t grid = 0;
-  rc = grid_for(p.n_tiles, &grid);
-  if (rc != ADACC_OK) return rc;
   DecompressFn fn = decompress_fn(method, p.tile_elems == 4096, dst_dtype == ADACC_DST_F32);
+  uint32_t grid = 0;
+  rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
+  if (rc != ADACC_OK) return rc;
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, p.outliers ? 1u : 0u);
   return launch_check("decompress_kernel");
 }
@@ -716,18 +737,23 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
                    false, 1u, &table, nullptr);
   if (rc != ADACC_OK) return rc;
-  uint32_t grid = 0;
-  rc = grid_for(total, &grid);
+  bool any_four = false, any_eight = false;
+  for (const TensorDesc& t : table) ((t.variant & 1u) ? any_eight : any_four) = true;
+  typedef void (*BatchFn)(const TensorDesc*, uint32_t, uint32_t);
+  const bool f32 = dst_dtype == ADACC_DST_F32;
+  const BatchFn fn4 = f32 ? decompress_batch_kernel<true, false> : decompress_batch_kernel<false, false>;
+  const BatchFn fn8 = f32 ? decompress_batch_kernel<true, true> : decompress_batch_kernel<false, true>;
+  uint32_t grid4 = 0, grid8 = 0;
+  if (any_four) rc = grid_for(total, reinterpret_cast<const void*>(fn4), 2u, &grid4);
+  if (rc == ADACC_OK && any_eight) rc = grid_for(total, reinterpret_cast<const void*>(fn8), 2u, &grid8);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
   rc = upload_table(table, reinterpret_cast<TensorDesc*>(mem + bp.table_off), s);
   if (rc != ADACC_OK) return rc;
   const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
-  if (dst_dtype == ADACC_DST_F32)
-    hipLaunchKernelGGL(decompress_batch_kernel<true>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
-  else
-    hipLaunchKernelGGL(decompress_batch_kernel<false>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
+  if (any_four) hipLaunchKernelGGL(fn4, dim3(grid4), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
+  if (any_eight) hipLaunchKernelGGL(fn8, dim3(grid8), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
   return launch_check("decompress_batch_kernel");
 }
 
