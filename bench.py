@@ -34,8 +34,14 @@ WORKLOAD_TEXT = {
 }
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by the plain copy kernel); filled in from profiles/*.txt.
-MEASURED_TRAFFIC_BYTES = {}
+# WRITE_SIZE runs, scaled by the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); copied
+# from profiles/hbm_traffic_pmc.txt.
+MEASURED_TRAFFIC_BYTES = {
+    "c2": {"compress": 173135052, "decompress": 173083443},
+    "c3": {"compress": 826322227, "decompress": 826724659},
+    "c4": {"compress": 1631776051, "decompress": 1664996966},
+    "c5": {"compress": 23081425408, "decompress": 23155858534},
+}
 
 
 def parse():
