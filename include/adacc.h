@@ -97,9 +97,10 @@ typedef struct adacc_layout {
 int adacc_layout_of(const adacc_method *method, uint64_t numel, adacc_layout *out);
 
 /* ---- workspace ----
- * Compression with outliers orders the outlier stream across tiles with a single-pass
- * chained scan; its per-tile state (8 bytes per tile) lives in a caller-owned device
- * buffer described by an adacc_workspace.  The struct is HOST memory owned by the caller;
+ * Compression with outliers orders the outlier stream across tiles in a single pass: the
+ * wavefronts publish how many outliers their runs of tiles hold and sum the counts of the
+ * runs before their own.  These words (at most 8 bytes per tile, plus 8 per 64 tiles) live in
+ * a caller-owned device buffer described by an adacc_workspace.  The struct is HOST memory owned by the caller;
  * the library keeps its launch counter ("epoch") in it: state words written by earlier
  * launches carry an older epoch and read as empty, so the buffer is cleared only by
  * adacc_workspace_init and when the 30-bit epoch wraps, never per call.
@@ -140,8 +141,9 @@ int adacc_compress(const adacc_method *method, const void *src, uint64_t numel, 
 int adacc_decompress(const adacc_method *method, const void *blob, uint64_t blob_bytes, uint64_t numel,
                      void *dst, int dst_dtype, void *hip_stream);
 
-/* ---- batch: one launch for a table of tensors (the per-tensor policy of Section 3.3,
- * R_{i,t}: compress or retain) ----
+/* ---- batch: one call for a table of tensors (the per-tensor policy of Section 3.3,
+ * R_{i,t}: compress or retain); the whole table is served by one kernel launch, or by two when
+ * it mixes methods whose groups reach 4096 elements with smaller ones ----
  * methods[i], srcs[i], numels[i], blobs[i], blob_bytes[i] describe tensor i; NOOP entries
  * are skipped.  The workspace holds the scan state of all tensors plus a device copy of the
  * table (adacc_batch_workspace_bytes device bytes); same init/reuse rules as above.
