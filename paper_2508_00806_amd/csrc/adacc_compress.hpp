@@ -405,9 +405,7 @@ __device__ __forceinline__ void row_bookkeeping(const uint64_t (&b)[kOct], uint3
     if (sparse) {
       lane_excl = lanes_below(any);
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) {
-        if (b[e] != 0ull) m |= __builtin_amdgcn_inverse_ballot_w64(b[e]) ? (1u << e) : 0u;  // uniform branch
-      }
+      for (int e = 0; e < kOct; ++e) m = __builtin_amdgcn_inverse_ballot_w64(b[e]) ? (1u << e) : m;  // at most one bit per lane
     } else {
       uint32_t below = 0u;
 #pragma unroll
@@ -501,7 +499,7 @@ __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E
     }
     bool any, sparse;
     row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any, sparse);
-    out.sparse = sparse ? (out.sparse | (1u << j)) : (out.sparse & ~(1u << j));
+    out.sparse |= sparse ? (1u << j) : 0u;
     out.row_off[j] = out.total;
     if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
     if constexpr (STORE) {
@@ -563,34 +561,58 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
                             __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
 }
 
-// thrf[j] <- the k-th largest lane maximum of row j's group, as a binary32 value.  Returns
-// (uniform) false when the tile holds an Inf or NaN (then the magnitude test is no float compare).
+// largest magnitude (15 low bits of the bf16 patterns) among the lane's 8 elements of every row:
+// two 16-bit lanes at a time.  An Inf or NaN shows as a value >= 0x7F80.
 template <int E>
-__device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint32_t (&raw)[E][4], float (&thrf)[E]) {
-  const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
-  uint32_t m[E];
+__device__ __forceinline__ void row_magnitudes(const uint32_t (&raw)[E][4], uint32_t (&rowmag)[E]) {
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     constexpr uint32_t kMag2 = 0x7FFF7FFFu;
-    m[j] = pk_max_u16(pk_max_u16(raw[j][0] & kMag2, raw[j][1] & kMag2), pk_max_u16(raw[j][2] & kMag2, raw[j][3] & kMag2));
+    const uint32_t m =
+        pk_max_u16(pk_max_u16(raw[j][0] & kMag2, raw[j][1] & kMag2), pk_max_u16(raw[j][2] & kMag2, raw[j][3] & kMag2));
+    const uint32_t hi = m >> 16, lo = m & 0xFFFFu;
+    rowmag[j] = hi > lo ? hi : lo;
   }
+}
+
+// thr[j] <- the k-th largest lane maximum of row j's group, as the bits of a binary32 value.
+// Returns (uniform) false when the tile holds an Inf or NaN.
+template <int E>
+__device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint32_t (&rowmag)[E], uint32_t (&thr)[E]) {
+  const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
+  const uint32_t lane = (uint32_t)lane_id();
+  if (R == E) {  // the usual case, one group per tile, in straight-line code
+    uint32_t m = rowmag[0];
+#pragma unroll
+    for (int j = 1; j < E; ++j) m = m > rowmag[j] ? m : rowmag[j];
+    const bool finite = __builtin_amdgcn_ballot_w64(m >= 0x7F80u) == 0ull;
+    uint32_t cur = (m << 6) | lane;  // unique per lane: equal maxima are taken one after the other
+    uint32_t win = 0u;               // uniform
+    for (uint32_t r = 0; r < d.topk; ++r) {
+      win = wave_max_u32_scalar(cur);
+      cur = (cur == win) ? 0u : cur;
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) thr[j] = (win >> 6) << 16;
+    return finite;
+  }
+  uint32_t m[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) m[j] = rowmag[j];
   // rows of a group -> its first row
 #pragma unroll
   for (int r = 1; r < E; r <<= 1) {
     if (r < R) {
 #pragma unroll
-      for (int j = 0; j < E; j += 2 * r) m[j] = pk_max_u16(m[j], m[j + r]);
+      for (int j = 0; j < E; j += 2 * r) m[j] = m[j] > m[j + r] ? m[j] : m[j + r];
     }
   }
-  const uint32_t lane = (uint32_t)lane_id();
   uint32_t cur[E], win[E];  // win[] is uniform
   bool nonfinite = false;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-    const uint32_t hi = m[j] >> 16, lo = m[j] & 0xFFFFu;
-    const uint32_t mx = hi > lo ? hi : lo;
-    if ((j & (R - 1)) == 0) nonfinite |= mx >= 0x7F80u;
-    cur[j] = (mx << 6) | lane;  // unique per lane: equal maxima are taken one after the other
+    if ((j & (R - 1)) == 0) nonfinite |= m[j] >= 0x7F80u;
+    cur[j] = (m[j] << 6) | lane;
     win[j] = 0u;
   }
   for (uint32_t r = 0; r < d.topk; ++r) {
@@ -609,7 +631,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
     }
   }
 #pragma unroll
-  for (int j = 0; j < E; ++j) thrf[j] = __uint_as_float((win[j] >> 6) << 16);
+  for (int j = 0; j < E; ++j) thr[j] = (win[j] >> 6) << 16;
   return __builtin_amdgcn_ballot_w64(nonfinite) == 0ull;
 }
 
@@ -657,12 +679,31 @@ __device__ __forceinline__ bool topk_select_rounds(const TensorDesc& d, const ui
 template <int MODE, bool ASYM, int E>
 __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
                                               const float (&limit)[E], const uint32_t (&thr)[E], bool by_magnitude,
-                                              bool poisoned, uint32_t lane_pos, int R, float (&ext0)[E],
-                                              float (&ext1)[E], TileOutliers<E>& out) {
+                                              bool poisoned, uint32_t lane_pos, int R,
+                                              const uint32_t (&rowmag)[E], float (&ext0)[E], float (&ext1)[E],
+                                              TileOutliers<E>& out) {
   out.sparse = 0u;
   forget_derived<E>(raw);  // nothing formed from the octets so far is worth its registers
 #pragma unroll
   for (int j = 0; j < E; ++j) {
+    if constexpr (!ASYM) {
+      // Symmetric: one test of the lane's largest magnitude of the row tells whether the row can
+      // hold an outlier at all; if not, that magnitude is also the lane's share of max |y|, and
+      // neither the widened values nor the 8 tests are needed.
+      const uint32_t top = rowmag[j] << 16;  // bits of the largest |x|
+      bool maybe;
+      if constexpr (MODE == kModeTopk) maybe = top >= (by_magnitude ? thr[j] : 0u);
+      else if constexpr (MODE == kModeAbs) maybe = top > __float_as_uint(d.param);  // tau >= 0; Inf / NaN are above every tau
+      else if constexpr (MODE == kModeStd) maybe = __uint_as_float(top) * __uint_as_float(top) > limit[j];
+      else maybe = top >= 0x7F800000u;
+      if (__builtin_amdgcn_ballot_w64(maybe) == 0ull && !poisoned) {
+        out.mask[j] = 0u; out.lane_excl[j] = 0u; out.row_cnt[j] = 0u;
+        out.sparse |= 1u << j;
+        ext0[j] = __uint_as_float(top);
+        ext1[j] = 0.0f;
+        continue;
+      }
+    }
     float x[kOct];
     widen_row(raw[j], x);
     uint64_t b[kOct];
@@ -692,7 +733,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
     }
     bool any, sparse;
     row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any, sparse);
-    out.sparse = sparse ? (out.sparse | (1u << j)) : (out.sparse & ~(1u << j));
+    out.sparse |= sparse ? (1u << j) : 0u;
     if (any) {
       float y[kOct];
 #pragma unroll
@@ -714,6 +755,13 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
   bool poisoned = false;  // uniform: Inf / NaN met in some group's statistics
   uint32_t lane_pos = 0u;
   int R = 1;
+  uint32_t rowmag[E];  // symmetric only: the lane's largest magnitude of every row
+  if constexpr (!ASYM) {
+    row_magnitudes<E>(raw, rowmag);
+  } else {
+#pragma unroll
+    for (int j = 0; j < E; ++j) rowmag[j] = 0u;
+  }
   if constexpr (MODE == kModeStd) {
     float s1[E], s2[E];
 #pragma unroll
@@ -752,10 +800,8 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     while (true) {
       bool by_magnitude = false;
       if (try_maxima) {
-        float thrf[E];
-        by_magnitude = topk_lane_maxima<E>(d, raw, thrf);
-#pragma unroll
-        for (int j = 0; j < E; ++j) thr[j] = __float_as_uint(thrf[j]);
+        if constexpr (ASYM) row_magnitudes<E>(raw, rowmag);
+        by_magnitude = topk_lane_maxima<E>(d, rowmag, thr);
       }
       if (!by_magnitude) {
         // nothing on this rare path may be prepared outside the loop over tiles (32 position codes
@@ -763,7 +809,7 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
         asm volatile("" : "+v"(lane_pos));
         poisoned = topk_select_rounds<E>(d, raw, thr, lane_pos, R);
       }
-      outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, by_magnitude, poisoned, lane_pos, R, ext0, ext1, out);
+      outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, by_magnitude, poisoned, lane_pos, R, rowmag, ext0, ext1, out);
       if (!by_magnitude) break;
       // the selection stands if every group has exactly k elements at or above its threshold
       bool exact = true;
@@ -777,7 +823,7 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
       try_maxima = false;
     }
   } else {
-    outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, false, poisoned, lane_pos, R, ext0, ext1, out);
+    outlier_phase<MODE, ASYM, E>(d, g, raw, limit, thr, false, poisoned, lane_pos, R, rowmag, ext0, ext1, out);
   }
   out.total = 0u;
 #pragma unroll
@@ -844,7 +890,10 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     widen_row(raw[j], y);
     if (out.row_cnt[j] != 0u) {  // uniform: the inlier view is zero where the mask says so
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) y[e] = ((out.mask[j] >> e) & 1u) ? 0.0f : y[e];
+      for (int e = 0; e < kOct; ++e) {
+        const uint32_t keep = (uint32_t)(((int32_t)(~out.mask[j] << (31 - e))) >> 31);  // all ones unless bit e is set
+        y[e] = __uint_as_float(__float_as_uint(y[e]) & keep);
+      }
     }
     uint32_t c[kOct];
 #pragma unroll

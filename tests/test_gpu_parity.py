@@ -182,6 +182,20 @@ def test_many_tiles_chained_scan():
     assert 0 < oc2.n_out < 200
 
 
+def test_dense_outliers_overflow_the_staging_area_mid_run():
+    """More tiles than the device holds wavefronts (runs of several tiles) and about 5 % outliers:
+    runs fill their staging area part-way and finish with the second, select-only pass."""
+    n = 2048 * 9001
+    rng = np.random.default_rng(4242)
+    v = rng.normal(0.0, 1.0, size=n).astype(np.float32)
+    x = torch.from_numpy(v).to(torch.bfloat16)
+    for mode, thresh, gq, gs, asym in (("abs", 1.96, 64, 0, 0), ("std", 1.96, 2048, 2048, 1)):
+        md = dict(bits=8, quant_group=gq, asym=asym, outlier_mode=mode, stat_group=gs, thresh=thresh, topk=0)
+        log(f"[parity] dense outliers mode={mode} n={n}")
+        oc, *_ = run_parity(x, md)
+        assert oc.n_out > n // 25
+
+
 def test_deterministic_and_workspace_reuse():
     """One workspace, many calls of different sizes and methods: every blob equals the oracle's,
     and repeated calls give identical bytes."""
