@@ -23,7 +23,7 @@ namespace adacc {
 #ifndef ADACC_COMPRESS_MIN_WAVES
 #define ADACC_COMPRESS_MIN_WAVES 1
 #endif
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
 __global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
                                                                                       uint64_t* state2, uint32_t tag,
                                                                                       uint32_t spin_limit) {
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_k
     __shared__ WaveStage stage[kWavesPerWg];
     const ScanCtx sc{state1, state2, tag, spin_limit};
     const uint32_t u = blockIdx.x * kWavesPerWg + wave;
-    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E, ROWWISE>(d, u, sc, &stage[wave]);
+    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, u, sc, &stage[wave]);
   }
 }
 
@@ -92,6 +92,19 @@ __device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint
   }
 }
 
+// TOPK over the whole tile: the specialised encoder
+template <bool EIGHT_ROWS>
+__device__ __forceinline__ void compress_dispatch_topk_whole(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
+                                                             WaveStage* stage) {
+  constexpr int kRows = EIGHT_ROWS ? 8 : 4;
+  switch (d.variant & 6u) {
+    case 0: compress_run<kModeTopk, 4, false, kRows, false, true>(d, unit, sc, stage); break;
+    case 2: compress_run<kModeTopk, 4, true, kRows, false, true>(d, unit, sc, stage); break;
+    case 4: compress_run<kModeTopk, 8, false, kRows, false, true>(d, unit, sc, stage); break;
+    default: compress_run<kModeTopk, 8, true, kRows, false, true>(d, unit, sc, stage); break;
+  }
+}
+
 template <int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t unit) {
   const uint32_t t0 = unit * d.tiles_per_unit;
@@ -144,7 +157,10 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDe
       break;
     case kModeAbs: compress_dispatch_mode<kModeAbs, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
     case kModeStd: compress_dispatch_mode<kModeStd, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
-    default: compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
+    default:
+      if (d.lgs == (EIGHT_ROWS ? 12u : 11u)) compress_dispatch_topk_whole<EIGHT_ROWS>(d, unit, sc, &stage[wave]);
+      else compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, unit, sc, &stage[wave]);
+      break;
   }
 }
 
@@ -409,22 +425,27 @@ static int grid_for(uint32_t n_tiles, const void* kernel, uint32_t rounds, uint3
 typedef void (*CompressFn)(TensorDesc, uint64_t*, uint64_t*, uint32_t, uint32_t);
 typedef void (*DecompressFn)(TensorDesc, uint32_t);
 
+// `whole` (TOPK only): the statistics group is the whole tile; that case has a kernel of its own
 template <int MODE, int BITS, bool ASYM>
-static CompressFn compress_fn_e(bool e8, bool rowwise) {
+static CompressFn compress_fn_e(bool e8, bool rowwise, bool whole) {
   if (rowwise) return compress_kernel<MODE, BITS, ASYM, 4, true>;
+  if constexpr (MODE == kModeTopk) {
+    if (whole) return e8 ? compress_kernel<MODE, BITS, ASYM, 8, false, true> : compress_kernel<MODE, BITS, ASYM, 4, false, true>;
+  }
   return e8 ? compress_kernel<MODE, BITS, ASYM, 8, false> : compress_kernel<MODE, BITS, ASYM, 4, false>;
 }
 template <int MODE>
-static CompressFn compress_fn_m(uint32_t bits, uint32_t asym, bool e8, bool rowwise) {
-  if (bits == 4) return asym ? compress_fn_e<MODE, 4, true>(e8, rowwise) : compress_fn_e<MODE, 4, false>(e8, rowwise);
-  return asym ? compress_fn_e<MODE, 8, true>(e8, rowwise) : compress_fn_e<MODE, 8, false>(e8, rowwise);
+static CompressFn compress_fn_m(uint32_t bits, uint32_t asym, bool e8, bool rowwise, bool whole) {
+  if (bits == 4)
+    return asym ? compress_fn_e<MODE, 4, true>(e8, rowwise, whole) : compress_fn_e<MODE, 4, false>(e8, rowwise, whole);
+  return asym ? compress_fn_e<MODE, 8, true>(e8, rowwise, whole) : compress_fn_e<MODE, 8, false>(e8, rowwise, whole);
 }
-static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise) {
+static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise, bool whole) {
   switch (m->outlier_mode) {
-    case ADACC_OUTLIER_NONE: return compress_fn_m<kModeNone>(m->bits, m->asym, e8, rowwise);
-    case ADACC_OUTLIER_ABS: return compress_fn_m<kModeAbs>(m->bits, m->asym, e8, rowwise);
-    case ADACC_OUTLIER_STD: return compress_fn_m<kModeStd>(m->bits, m->asym, e8, rowwise);
-    default: return compress_fn_m<kModeTopk>(m->bits, m->asym, e8, false);
+    case ADACC_OUTLIER_NONE: return compress_fn_m<kModeNone>(m->bits, m->asym, e8, rowwise, false);
+    case ADACC_OUTLIER_ABS: return compress_fn_m<kModeAbs>(m->bits, m->asym, e8, rowwise, false);
+    case ADACC_OUTLIER_STD: return compress_fn_m<kModeStd>(m->bits, m->asym, e8, rowwise, false);
+    default: return compress_fn_m<kModeTopk>(m->bits, m->asym, e8, false, whole);
   }
 }
 template <int BITS, bool ASYM>
@@ -567,7 +588,8 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   int cus = 0;
   rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
   if (rc != ADACC_OK) return rc;
-  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise);
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise,
+                              method->outlier_mode == ADACC_OUTLIER_TOPK && method->stat_group == p.tile_elems);
   uint32_t tpu = 1u;
   if (p.outliers) {
     uint32_t capacity = 0;

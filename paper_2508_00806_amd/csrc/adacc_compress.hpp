@@ -577,11 +577,10 @@ __device__ __forceinline__ void row_magnitudes(const uint32_t (&raw)[E][4], uint
 
 // thr[j] <- the k-th largest lane maximum of row j's group, as the bits of a binary32 value.
 // Returns (uniform) false when the tile holds an Inf or NaN.
-template <int E>
+template <int E, bool WHOLE>
 __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint32_t (&rowmag)[E], uint32_t (&thr)[E]) {
-  const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
   const uint32_t lane = (uint32_t)lane_id();
-  if (R == E) {  // the usual case, one group per tile, in straight-line code
+  if constexpr (WHOLE) {  // one group per tile, the usual case, in straight-line code
     uint32_t m = rowmag[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) m = m > rowmag[j] ? m : rowmag[j];
@@ -596,6 +595,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
     for (int j = 0; j < E; ++j) thr[j] = (win >> 6) << 16;
     return finite;
   }
+  const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
   uint32_t m[E];
 #pragma unroll
   for (int j = 0; j < E; ++j) m[j] = rowmag[j];
@@ -745,7 +745,9 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
   }
 }
 
-template <int MODE, int BITS, bool ASYM, int E, bool STORE>
+// WHOLE: the statistics group is the tile (known at compile time, so that nothing about rows per
+// group is decided at run time: each such decision costs scalar instructions and registers).
+template <int MODE, int BITS, bool ASYM, int E, bool STORE, bool WHOLE>
 __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const TileGeo<E>& g,
                                                     const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
   constexpr int Q = 1 << (BITS - 1);
@@ -785,8 +787,13 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     poisoned = __builtin_amdgcn_ballot_w64(nan_seen) != 0ull;
   } else if constexpr (MODE == kModeTopk) {
     const uint32_t lane = (uint32_t)lane_id();
-    R = (d.lgs > 9) ? (1 << (d.lgs - 9)) : 1;
-    lane_pos = (d.lgs > 9) ? (lane << 3) : ((lane & ((1u << (d.lgs - 3)) - 1u)) << 3);
+    if constexpr (WHOLE) {
+      R = E;
+      lane_pos = lane << 3;
+    } else {
+      R = (d.lgs > 9) ? (1 << (d.lgs - 9)) : 1;
+      lane_pos = (d.lgs > 9) ? (lane << 3) : ((lane & ((1u << (d.lgs - 3)) - 1u)) << 3);
+    }
   }
 
   // ---- a3 + a5: outlier test row by row; extremes of the inlier view per lane
@@ -795,13 +802,13 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     // First the selection by lane maxima where it applies; if it does not stand, once more by rounds.
     // One copy of the code in a loop (rather than two in a row) keeps the registers of the rare second
     // pass from adding to those of the first.
-    bool try_maxima = d.lgs >= 9u && d.topk <= 8u;
+    bool try_maxima = (WHOLE || d.lgs >= 9u) && d.topk <= 8u;
 #pragma nounroll
     while (true) {
       bool by_magnitude = false;
       if (try_maxima) {
         if constexpr (ASYM) row_magnitudes<E>(raw, rowmag);
-        by_magnitude = topk_lane_maxima<E>(d, rowmag, thr);
+        by_magnitude = topk_lane_maxima<E, WHOLE>(d, rowmag, thr);
       }
       if (!by_magnitude) {
         // nothing on this rare path may be prepared outside the loop over tiles (32 position codes
@@ -817,7 +824,7 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
 #pragma unroll
       for (int j = 0; j < E; ++j) {
         in_group += out.row_cnt[j];
-        if ((j & (R - 1)) == R - 1) { exact = exact && (in_group == d.topk); in_group = 0u; }
+        if (WHOLE ? (j == E - 1) : ((j & (R - 1)) == R - 1)) { exact = exact && (in_group == d.topk); in_group = 0u; }
       }
       if (exact) break;
       try_maxima = false;
@@ -904,11 +911,13 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
 
 // ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide.
 // STORE = false: only the outliers are found (nothing is quantised or stored).
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool STORE = true>
+// WHOLE (general encoder, TOPK): the statistics group is the whole tile.
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false, bool STORE = true>
 __device__ __forceinline__ void encode_tile(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
                                             TileOutliers<E>& out) {
+  static_assert(!WHOLE || (MODE == kModeTopk && !ROWWISE), "only the general TOPK encoder is specialised");
   if constexpr (ROWWISE) encode_tile_rowwise<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
-  else encode_tile_general<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
+  else encode_tile_general<MODE, BITS, ASYM, E, STORE, WHOLE>(d, g, raw, out);
 }
 
 // ---- a4: append a tile's outliers, in ascending index order, to `idx_out` / `val_out` starting
@@ -966,7 +975,7 @@ struct WaveStage {
 // (load, select, nothing else) and writes their outliers straight to the stream.  Dense
 // outliers therefore cost a second read of the input, never a chain of runs waiting for each
 // other.
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE>
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
 __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit, const ScanCtx& sc, WaveStage* stage) {
   static_assert(MODE != kModeNone, "runs exist for the scan only");
   const int lane = lane_id();
@@ -1002,7 +1011,7 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
     const TileGeo<E> g = tile_geo<E>(d, t);
     blank_tail<E>(g, raw);
     TileOutliers<E> out;
-    encode_tile<MODE, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
     if ((uint32_t)lane == t - t0) tile_off = run_total;
 
     if (out.total != 0u) {
@@ -1051,7 +1060,7 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
       const TileGeo<E> g = tile_geo<E>(d, t);
       blank_tail<E>(g, raw);
       TileOutliers<E> out;
-      encode_tile<MODE, BITS, ASYM, E, ROWWISE, false>(d, g, raw, out);
+      encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE, false>(d, g, raw, out);
       const uint32_t before = (uint32_t)__builtin_amdgcn_readlane((int)tile_off, (int)(t - t0));
       if (out.total != 0u) emit_outliers<E>(raw, out, t, d.idx, d.val, excl + before, d.cap);
     }
