@@ -156,9 +156,10 @@ __device__ __forceinline__ void groups_reduce_any_order(T (&s)[E], uint32_t lg, 
 // lane 31 into rows 2 and 3), and lane 63 holds the result
 __device__ __forceinline__ uint32_t wave_max_u32_scalar(uint32_t v) {
   v = lanes_reduce<16>(v, OpUMax());
-  int t = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  // rows that receive nothing read 0, the identity of the maximum, so each step is one instruction
+  int t = __builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
   v = OpUMax()(v, (uint32_t)t);
-  t = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xC, 0xF, false);      // row_bcast:31
+  t = __builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);      // row_bcast:31
   v = OpUMax()(v, (uint32_t)t);
   return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
@@ -684,6 +685,9 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
                                               TileOutliers<E>& out) {
   out.sparse = 0u;
   forget_derived<E>(raw);  // nothing formed from the octets so far is worth its registers
+  // uniform, as an integer so that it stays in a scalar register: rows may be skipped on the strength
+  // of their largest magnitude (not when keys decide, nor when Inf / NaN are about)
+  const uint32_t can_skip = ((MODE != kModeTopk || by_magnitude) && !poisoned) ? 1u : 0u;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     if constexpr (!ASYM) {
@@ -692,11 +696,11 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
       // neither the widened values nor the 8 tests are needed.
       const uint32_t top = rowmag[j] << 16;  // bits of the largest |x|
       bool maybe;
-      if constexpr (MODE == kModeTopk) maybe = top >= (by_magnitude ? thr[j] : 0u);
+      if constexpr (MODE == kModeTopk) maybe = top >= thr[j];
       else if constexpr (MODE == kModeAbs) maybe = top > __float_as_uint(d.param);  // tau >= 0; Inf / NaN are above every tau
       else if constexpr (MODE == kModeStd) maybe = __uint_as_float(top) * __uint_as_float(top) > limit[j];
       else maybe = top >= 0x7F800000u;
-      if (__builtin_amdgcn_ballot_w64(maybe) == 0ull && !poisoned) {
+      if ((__builtin_amdgcn_ballot_w64(maybe) == 0ull) & (can_skip != 0u)) {
         out.mask[j] = 0u; out.lane_excl[j] = 0u; out.row_cnt[j] = 0u;
         out.sparse |= 1u << j;
         ext0[j] = __uint_as_float(top);
@@ -708,7 +712,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
     widen_row(raw[j], x);
     uint64_t b[kOct];
     if constexpr (MODE == kModeTopk) {
-      if (by_magnitude) {
+      if (__builtin_expect(by_magnitude, 1)) {
         // rows past the end of the tensor are all selected here, which the caller's count check rejects
         const float t = __uint_as_float(thr[j]);
 #pragma unroll
