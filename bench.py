@@ -37,10 +37,10 @@ WORKLOAD_TEXT = {
 # WRITE_SIZE runs, scaled by the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); copied
 # from profiles/hbm_traffic_pmc.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "c2": {"compress": 173135052, "decompress": 173083443},
-    "c3": {"compress": 826322227, "decompress": 826724659},
-    "c4": {"compress": 1631776051, "decompress": 1664996966},
-    "c5": {"compress": 23081425408, "decompress": 23155858534},
+    "c2": {"compress": 173049139, "decompress": 173067878},
+    "c3": {"compress": 826388787, "decompress": 826758758},
+    "c4": {"compress": 1631255347, "decompress": 1664966656},
+    "c5": {"compress": 23085555814, "decompress": 23156205977},
 }
 
 
