@@ -164,10 +164,16 @@ __device__ __forceinline__ uint32_t wave_max_u32_scalar(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// sum over the whole wavefront, returned in a scalar register (same scheme as the maximum: this
+// sits on the path every run takes between learning the earlier totals and writing its outliers)
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) v += __shfl_xor(v, m);
-  return v;
+  struct OpUAdd { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; } };
+  v = lanes_reduce<16>(v, OpUAdd());
+  int t = __builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  v += (uint32_t)t;
+  t = __builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);      // row_bcast:31
+  v += (uint32_t)t;
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 // number of set bits of a wavefront mask in the lanes below this one
