@@ -114,8 +114,13 @@ __device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t
 
 // One launch (per register class) for a table of tensors: runs are numbered across the table; a
 // wavefront finds its tensor by binary search and dispatches on that tensor's method.
+// The kernel for tiles of 8 rows is held to 3 wavefronts per SIMD: the variants that matter
+// (TOPK over the whole tile) fit, the rarely used ones spill a few registers.
+#ifndef ADACC_BATCH8_MIN_WAVES
+#define ADACC_BATCH8_MIN_WAVES 3
+#endif
 template <bool EIGHT_ROWS>
-__global__ __launch_bounds__(kThreads) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
+__global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
                                                                   uint32_t total_units, uint64_t* state1,
                                                                   uint64_t* state2, uint32_t tag,
                                                                   uint32_t spin_limit) {
