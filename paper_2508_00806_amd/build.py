@@ -6,13 +6,22 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libadacc.so")
-SOURCES = [os.path.join(HERE, "csrc", "adacc.hip")]
-HEADERS = [os.path.join(HERE, "csrc", f) for f in ("adacc_common.hpp", "adacc_compress.hpp", "adacc_decompress.hpp")]
+CSRC = os.path.join(HERE, "csrc")
+# one translation unit per group of kernel instantiations, so that the library builds in parallel
+SOURCES = [os.path.join(CSRC, f) for f in (
+    "adacc.hip",              # host code, C ABI, utility kernels
+    "adacc_k_none.hip", "adacc_k_abs.hip", "adacc_k_std.hip", "adacc_k_topk.hip",  # compress, per outlier mode
+    "adacc_k_decompress.hip",
+    "adacc_k_batch4.hip", "adacc_k_batch8.hip",
+)]
+HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_compress.hpp", "adacc_decompress.hpp",
+                                           "adacc_kernels.hpp", "adacc_fn.hpp")]
 HEADERS.append(os.path.join(ROOT, "include", "adacc.h"))
+OBJDIR = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",            # the order and rounding of every float operation is part of the format
     "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -20,9 +29,23 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra=()) -> str:
-    cmd = [HIPCC, *FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-           "-o", LIB, *SOURCES]
+def build(verbose: bool = False, extra=(), jobs: int = 8) -> str:
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJDIR, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    tag = os.path.splitext(os.path.basename(LIB))[0]
+
+    def compile_one(src):
+        obj = os.path.join(OBJDIR, tag + "_" + os.path.splitext(os.path.basename(src))[0] + ".o")
+        cmd = [HIPCC, *FLAGS, *extra, *inc, "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(SOURCES)))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -10,201 +10,11 @@
 
 #include "adacc.h"
 #include "adacc_common.hpp"
-#include "adacc_compress.hpp"
-#include "adacc_decompress.hpp"
+#include "adacc_fn.hpp"
 
 namespace adacc {
 
 // ===================================================================== kernels
-
-// ---- single tensor, compress.  With outliers: run = 4 * workgroup + wavefront, and the grid is
-// exactly ceil(n_units / 4) workgroups, because the chained scan relies on runs being started
-// in index order.  NONE: tiles are independent, grid-stride loop over tiles.
-#ifndef ADACC_COMPRESS_MIN_WAVES
-#define ADACC_COMPRESS_MIN_WAVES 1
-#endif
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
-__global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
-                                                                                      uint64_t* state2, uint32_t tag,
-                                                                                      uint32_t spin_limit) {
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  if constexpr (MODE == kModeNone) {
-    for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-      compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
-  } else {
-    __shared__ WaveStage stage[kWavesPerWg];
-    const ScanCtx sc{state1, state2, tag, spin_limit};
-    const uint32_t u = blockIdx.x * kWavesPerWg + wave;
-    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, u, sc, &stage[wave]);
-  }
-}
-
-template <int BITS, bool ASYM, int E, bool F32>
-__global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint32_t has_outliers) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<E, F32>()];
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<E, F32>();
-  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-    decompress_tile<BITS, ASYM, E, F32>(d, t, has_outliers != 0u, slice);
-}
-
-// ---- batch: a launch-wide tile numbering over all tensors of the table
-template <bool BY_UNIT>
-__device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_t n, uint32_t g) {
-  uint32_t lo = 0u, hi = n;  // first_tile / first_unit ascend; find the last entry that starts at or before g
-  while (hi - lo > 1u) {
-    const uint32_t mid = (lo + hi) >> 1;
-    const uint32_t first = BY_UNIT ? table[mid].first_unit : table[mid].first_tile;
-    if (first <= g) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-// Variants with tiles of 8 rows need about twice the registers of those with 4; a kernel that
-// held both would run everything at the occupancy of the heaviest.  So the batch comes as two
-// kernels over the same table, and a wavefront whose tensor belongs to the other one leaves.
-template <int MODE, bool EIGHT_ROWS>
-__device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
-                                                       WaveStage* stage) {
-  if constexpr (!EIGHT_ROWS) {
-    if (d.rowwise) {  // groups inside a row
-      switch (d.variant & 6u) {
-        case 0: compress_run<MODE, 4, false, 4, true>(d, unit, sc, stage); break;
-        case 2: compress_run<MODE, 4, true, 4, true>(d, unit, sc, stage); break;
-        case 4: compress_run<MODE, 8, false, 4, true>(d, unit, sc, stage); break;
-        default: compress_run<MODE, 8, true, 4, true>(d, unit, sc, stage); break;
-      }
-      return;
-    }
-    switch (d.variant & 6u) {
-      case 0: compress_run<MODE, 4, false, 4, false>(d, unit, sc, stage); break;
-      case 2: compress_run<MODE, 4, true, 4, false>(d, unit, sc, stage); break;
-      case 4: compress_run<MODE, 8, false, 4, false>(d, unit, sc, stage); break;
-      default: compress_run<MODE, 8, true, 4, false>(d, unit, sc, stage); break;
-    }
-  } else {
-    switch (d.variant & 6u) {
-      case 0: compress_run<MODE, 4, false, 8, false>(d, unit, sc, stage); break;
-      case 2: compress_run<MODE, 4, true, 8, false>(d, unit, sc, stage); break;
-      case 4: compress_run<MODE, 8, false, 8, false>(d, unit, sc, stage); break;
-      default: compress_run<MODE, 8, true, 8, false>(d, unit, sc, stage); break;
-    }
-  }
-}
-
-// TOPK over the whole tile: the specialised encoder
-template <bool EIGHT_ROWS>
-__device__ __forceinline__ void compress_dispatch_topk_whole(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
-                                                             WaveStage* stage) {
-  constexpr int kRows = EIGHT_ROWS ? 8 : 4;
-  switch (d.variant & 6u) {
-    case 0: compress_run<kModeTopk, 4, false, kRows, false, true>(d, unit, sc, stage); break;
-    case 2: compress_run<kModeTopk, 4, true, kRows, false, true>(d, unit, sc, stage); break;
-    case 4: compress_run<kModeTopk, 8, false, kRows, false, true>(d, unit, sc, stage); break;
-    default: compress_run<kModeTopk, 8, true, kRows, false, true>(d, unit, sc, stage); break;
-  }
-}
-
-template <int BITS, bool ASYM, int E, bool ROWWISE>
-__device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t unit) {
-  const uint32_t t0 = unit * d.tiles_per_unit;
-  const uint32_t t1 = (t0 + d.tiles_per_unit < d.n_tiles) ? t0 + d.tiles_per_unit : d.n_tiles;
-  for (uint32_t t = t0; t < t1; ++t) compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
-}
-
-// One launch (per register class) for a table of tensors: runs are numbered across the table; a
-// wavefront finds its tensor by binary search and dispatches on that tensor's method.
-// The kernel for tiles of 8 rows is held to 3 wavefronts per SIMD: the variants that matter
-// (TOPK over the whole tile) fit, the rarely used ones spill a few registers.
-#ifndef ADACC_BATCH8_MIN_WAVES
-#define ADACC_BATCH8_MIN_WAVES 3
-#endif
-template <bool EIGHT_ROWS>
-__global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                  uint32_t total_units, uint64_t* state1,
-                                                                  uint64_t* state2, uint32_t tag,
-                                                                  uint32_t spin_limit) {
-  __shared__ WaveStage stage[kWavesPerWg];
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  const ScanCtx sc{state1, state2, tag, spin_limit};
-  const uint32_t g = blockIdx.x * kWavesPerWg + wave;
-  if (g >= total_units) return;
-  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<true>(table, n, g));
-  const TensorDesc d = table[ti];
-  if (((d.variant & 1u) != 0u) != EIGHT_ROWS) return;
-  const uint32_t unit = g - d.first_unit;
-  switch (d.variant >> 3) {
-    case kModeNone:
-      if constexpr (!EIGHT_ROWS) {
-        if (d.rowwise) {
-          switch (d.variant & 6u) {
-            case 0: compress_plain_run<4, false, 4, true>(d, unit); break;
-            case 2: compress_plain_run<4, true, 4, true>(d, unit); break;
-            case 4: compress_plain_run<8, false, 4, true>(d, unit); break;
-            default: compress_plain_run<8, true, 4, true>(d, unit); break;
-          }
-          break;
-        }
-        switch (d.variant & 6u) {
-          case 0: compress_plain_run<4, false, 4, false>(d, unit); break;
-          case 2: compress_plain_run<4, true, 4, false>(d, unit); break;
-          case 4: compress_plain_run<8, false, 4, false>(d, unit); break;
-          default: compress_plain_run<8, true, 4, false>(d, unit); break;
-        }
-      } else {
-        switch (d.variant & 6u) {
-          case 0: compress_plain_run<4, false, 8, false>(d, unit); break;
-          case 2: compress_plain_run<4, true, 8, false>(d, unit); break;
-          case 4: compress_plain_run<8, false, 8, false>(d, unit); break;
-          default: compress_plain_run<8, true, 8, false>(d, unit); break;
-        }
-      }
-      break;
-    case kModeAbs: compress_dispatch_mode<kModeAbs, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
-    case kModeStd: compress_dispatch_mode<kModeStd, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
-    default:
-      if (d.lgs == (EIGHT_ROWS ? 12u : 11u)) compress_dispatch_topk_whole<EIGHT_ROWS>(d, unit, sc, &stage[wave]);
-      else compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, unit, sc, &stage[wave]);
-      break;
-  }
-}
-
-// Like the batch compression, in two kernels: tiles of 8 rows need twice the staging area in LDS,
-// which would limit the wavefronts per CU for every tensor of the table.
-template <bool F32, bool EIGHT_ROWS>
-__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                    uint32_t total_tiles) {
-  constexpr int kRows = EIGHT_ROWS ? 8 : 4;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<kRows, F32>()];
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<kRows, F32>();
-  // A wavefront's tiles ascend, so the tensor of a tile is the one of the previous tile or a later
-  // one: one binary search at the start, then a walk, and the descriptor is read again only when
-  // the tensor changes.
-  uint32_t g = blockIdx.x * kWavesPerWg + wave;
-  if (g >= total_tiles) return;
-  uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<false>(table, n, g));
-  TensorDesc d = table[ti];
-  uint32_t next_first = (ti + 1u < n) ? table[ti + 1u].first_tile : 0xFFFFFFFFu;
-  for (; g < total_tiles; g += gridDim.x * kWavesPerWg) {
-    if (g >= next_first) {
-      do {
-        ++ti;
-        next_first = (ti + 1u < n) ? table[ti + 1u].first_tile : 0xFFFFFFFFu;
-      } while (g >= next_first);
-      d = table[ti];
-    }
-    if (((d.variant & 1u) != 0u) != EIGHT_ROWS) continue;  // the other kernel's tensor
-    const uint32_t tile = g - d.first_tile;
-    const bool ho = (d.variant >> 3) != kModeNone;
-    switch (d.variant & 6u) {
-      case 0: decompress_tile<4, false, kRows, F32>(d, tile, ho, slice); break;
-      case 2: decompress_tile<4, true, kRows, F32>(d, tile, ho, slice); break;
-      case 4: decompress_tile<8, false, kRows, F32>(d, tile, ho, slice); break;
-      default: decompress_tile<8, true, kRows, F32>(d, tile, ho, slice); break;
-    }
-  }
-}
 
 // ---- utilities
 // The table of a batch reaches the device as kernel arguments, a slice per launch: the runtime
@@ -427,40 +237,18 @@ static int grid_for(uint32_t n_tiles, const void* kernel, uint32_t rounds, uint3
   return ADACC_OK;
 }
 
-typedef void (*CompressFn)(TensorDesc, uint64_t*, uint64_t*, uint32_t, uint32_t);
-typedef void (*DecompressFn)(TensorDesc, uint32_t);
+BatchCompressFn compress_batch_fn4();
+BatchCompressFn compress_batch_fn8();
+BatchCompressFn compress_batch_fn(bool eight_rows) { return eight_rows ? compress_batch_fn8() : compress_batch_fn4(); }
 
-// `whole` (TOPK only): the statistics group is the whole tile; that case has a kernel of its own
-template <int MODE, int BITS, bool ASYM>
-static CompressFn compress_fn_e(bool e8, bool rowwise, bool whole) {
-  if (rowwise) return compress_kernel<MODE, BITS, ASYM, 4, true>;
-  if constexpr (MODE == kModeTopk) {
-    if (whole) return e8 ? compress_kernel<MODE, BITS, ASYM, 8, false, true> : compress_kernel<MODE, BITS, ASYM, 4, false, true>;
-  }
-  return e8 ? compress_kernel<MODE, BITS, ASYM, 8, false> : compress_kernel<MODE, BITS, ASYM, 4, false>;
-}
-template <int MODE>
-static CompressFn compress_fn_m(uint32_t bits, uint32_t asym, bool e8, bool rowwise, bool whole) {
-  if (bits == 4)
-    return asym ? compress_fn_e<MODE, 4, true>(e8, rowwise, whole) : compress_fn_e<MODE, 4, false>(e8, rowwise, whole);
-  return asym ? compress_fn_e<MODE, 8, true>(e8, rowwise, whole) : compress_fn_e<MODE, 8, false>(e8, rowwise, whole);
-}
+// `whole` (TOPK only): the statistics group is the whole tile; that case has kernels of its own
 static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise, bool whole) {
   switch (m->outlier_mode) {
-    case ADACC_OUTLIER_NONE: return compress_fn_m<kModeNone>(m->bits, m->asym, e8, rowwise, false);
-    case ADACC_OUTLIER_ABS: return compress_fn_m<kModeAbs>(m->bits, m->asym, e8, rowwise, false);
-    case ADACC_OUTLIER_STD: return compress_fn_m<kModeStd>(m->bits, m->asym, e8, rowwise, false);
-    default: return compress_fn_m<kModeTopk>(m->bits, m->asym, e8, false, whole);
+    case ADACC_OUTLIER_NONE: return compress_fn_none(m->bits, m->asym, e8, rowwise);
+    case ADACC_OUTLIER_ABS: return compress_fn_abs(m->bits, m->asym, e8, rowwise);
+    case ADACC_OUTLIER_STD: return compress_fn_std(m->bits, m->asym, e8, rowwise);
+    default: return compress_fn_topk(m->bits, m->asym, e8, whole);
   }
-}
-template <int BITS, bool ASYM>
-static DecompressFn decompress_fn_e(bool e8, bool f32) {
-  if (e8) return f32 ? decompress_kernel<BITS, ASYM, 8, true> : decompress_kernel<BITS, ASYM, 8, false>;
-  return f32 ? decompress_kernel<BITS, ASYM, 4, true> : decompress_kernel<BITS, ASYM, 4, false>;
-}
-static DecompressFn decompress_fn(const adacc_method* m, bool e8, bool f32) {
-  if (m->bits == 4) return m->asym ? decompress_fn_e<4, true>(e8, f32) : decompress_fn_e<4, false>(e8, f32);
-  return m->asym ? decompress_fn_e<8, true>(e8, f32) : decompress_fn_e<8, false>(e8, f32);
 }
 
 static int clear_device(void* mem, uint64_t bytes, hipStream_t s);
@@ -634,7 +422,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, 0, &d);
-  DecompressFn fn = decompress_fn(method, p.tile_elems == 4096, dst_dtype == ADACC_DST_F32);
+  DecompressFn fn = decompress_fn(method->bits, method->asym, p.tile_elems == 4096, dst_dtype == ADACC_DST_F32);
   uint32_t grid = 0;
   rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
   if (rc != ADACC_OK) return rc;
@@ -718,8 +506,7 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   for (const TensorDesc& t : table) ((t.variant & 1u) ? any_eight : any_four) = true;
   // run length from the kernel that most tensors use (the other one simply takes more rounds)
   uint32_t capacity = 0;
-  rc = wave_capacity(any_four ? reinterpret_cast<const void*>(compress_batch_kernel<false>)
-                              : reinterpret_cast<const void*>(compress_batch_kernel<true>), cus, &capacity);
+  rc = wave_capacity(reinterpret_cast<const void*>(compress_batch_fn(!any_four)), cus, &capacity);
   if (rc != ADACC_OK) return rc;
   table.clear();
   rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true,
@@ -737,10 +524,10 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   uint64_t* st1 = reinterpret_cast<uint64_t*>(mem);
   uint64_t* st2 = reinterpret_cast<uint64_t*>(mem + state1_bytes(total));
   if (any_four)
-    hipLaunchKernelGGL(compress_batch_kernel<false>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
+    hipLaunchKernelGGL(compress_batch_fn(false), dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
                        total_units, st1, st2, tag, spin_limit());
   if (any_eight)
-    hipLaunchKernelGGL(compress_batch_kernel<true>, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
+    hipLaunchKernelGGL(compress_batch_fn(true), dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
                        total_units, st1, st2, tag, spin_limit());
   return launch_check("compress_batch_kernel");
 }
@@ -766,10 +553,9 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   if (rc != ADACC_OK) return rc;
   bool any_four = false, any_eight = false;
   for (const TensorDesc& t : table) ((t.variant & 1u) ? any_eight : any_four) = true;
-  typedef void (*BatchFn)(const TensorDesc*, uint32_t, uint32_t);
   const bool f32 = dst_dtype == ADACC_DST_F32;
-  const BatchFn fn4 = f32 ? decompress_batch_kernel<true, false> : decompress_batch_kernel<false, false>;
-  const BatchFn fn8 = f32 ? decompress_batch_kernel<true, true> : decompress_batch_kernel<false, true>;
+  const BatchDecompressFn fn4 = decompress_batch_fn(f32, false);
+  const BatchDecompressFn fn8 = decompress_batch_fn(f32, true);
   uint32_t grid4 = 0, grid8 = 0;
   if (any_four) rc = grid_for(total, reinterpret_cast<const void*>(fn4), 2u, &grid4);
   if (rc == ADACC_OK && any_eight) rc = grid_for(total, reinterpret_cast<const void*>(fn8), 2u, &grid8);

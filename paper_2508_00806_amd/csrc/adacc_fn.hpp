@@ -1,0 +1,23 @@
+// Host-side handles of the kernel instantiations: each getter lives in the translation unit
+// that instantiates the kernels it returns.
+#pragma once
+
+#include "adacc_common.hpp"
+
+namespace adacc {
+
+typedef void (*CompressFn)(TensorDesc, uint64_t*, uint64_t*, uint32_t, uint32_t);
+typedef void (*DecompressFn)(TensorDesc, uint32_t);
+typedef void (*BatchCompressFn)(const TensorDesc*, uint32_t, uint32_t, uint64_t*, uint64_t*, uint32_t, uint32_t);
+typedef void (*BatchDecompressFn)(const TensorDesc*, uint32_t, uint32_t);
+
+// e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
+CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
+CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
+CompressFn compress_fn_std(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
+CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);
+DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool e8, bool f32);
+BatchCompressFn compress_batch_fn(bool eight_rows);
+BatchDecompressFn decompress_batch_fn(bool f32, bool eight_rows);
+
+}  // namespace adacc

@@ -1,0 +1,17 @@
+// Instantiations of the single-tensor compression kernels, outlier mode abs.
+#include "adacc_kernels.hpp"
+
+namespace adacc {
+
+template <int BITS, bool ASYM>
+static CompressFn pick(bool e8, bool rowwise) {
+  if (rowwise) return compress_kernel<kModeAbs, BITS, ASYM, 4, true>;
+  return e8 ? compress_kernel<kModeAbs, BITS, ASYM, 8, false> : compress_kernel<kModeAbs, BITS, ASYM, 4, false>;
+}
+
+CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise) {
+  if (bits == 4) return asym ? pick<4, true>(e8, rowwise) : pick<4, false>(e8, rowwise);
+  return asym ? pick<8, true>(e8, rowwise) : pick<8, false>(e8, rowwise);
+}
+
+}  // namespace adacc
