@@ -180,6 +180,8 @@ static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
   return (uint32_t)((tiles_in_launch + units - 1) / units);
 }
 
+static uint32_t decompress_pieces(uint64_t numel) { return (uint32_t)((numel + 2047ull) / 2048ull); }
+
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
                       void* blob, void* dst, int dst_dtype, uint32_t first_tile, uint32_t tpu, uint32_t first_unit,
                       uint32_t first_block, TensorDesc* d) {
@@ -197,6 +199,10 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
   d->numel = numel;
   d->n_tiles = p.n_tiles;
   d->first_tile = first_tile;
+  if (dst) {  // decompression counts pieces of 2048 elements
+    d->n_tiles = decompress_pieces(numel);
+    d->ptr_shift = p.tile_elems == 4096 ? 1u : 0u;
+  }
   d->tiles_per_unit = tpu;
   d->n_units = (p.n_tiles + tpu - 1) / tpu;
   d->first_unit = first_unit;
@@ -422,9 +428,9 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, 0, &d);
-  DecompressFn fn = decompress_fn(method->bits, method->asym, p.tile_elems == 4096, dst_dtype == ADACC_DST_F32);
+  DecompressFn fn = decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
   uint32_t grid = 0;
-  rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
+  rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
   if (rc != ADACC_OK) return rc;
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, p.outliers ? 1u : 0u);
   return launch_check("decompress_kernel");
@@ -474,7 +480,7 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
     fill_desc(&methods[i], numels[i], plans[i], L, compress ? srcs[i] : nullptr, blobs[i], compress ? nullptr : dsts[i],
               dst_dtype, first, tpu, first_unit, first_block, &d);
     table->push_back(d);
-    first += plans[i].n_tiles;
+    first += compress ? plans[i].n_tiles : d.n_tiles;
     first_unit += d.n_units;
     first_block += (d.n_units + kWave - 1) / kWave;
   }
@@ -551,22 +557,18 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
                    false, 1u, &table, nullptr);
   if (rc != ADACC_OK) return rc;
-  bool any_four = false, any_eight = false;
-  for (const TensorDesc& t : table) ((t.variant & 1u) ? any_eight : any_four) = true;
-  const bool f32 = dst_dtype == ADACC_DST_F32;
-  const BatchDecompressFn fn4 = decompress_batch_fn(f32, false);
-  const BatchDecompressFn fn8 = decompress_batch_fn(f32, true);
-  uint32_t grid4 = 0, grid8 = 0;
-  if (any_four) rc = grid_for(total, reinterpret_cast<const void*>(fn4), 2u, &grid4);
-  if (rc == ADACC_OK && any_eight) rc = grid_for(total, reinterpret_cast<const void*>(fn8), 2u, &grid8);
+  uint32_t pieces = 0;
+  for (const TensorDesc& t : table) pieces += t.n_tiles;
+  const BatchDecompressFn fn = decompress_batch_fn(dst_dtype == ADACC_DST_F32);
+  uint32_t grid = 0;
+  rc = grid_for(pieces, reinterpret_cast<const void*>(fn), 2u, &grid);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
   rc = upload_table(table, reinterpret_cast<TensorDesc*>(mem + bp.table_off), s);
   if (rc != ADACC_OK) return rc;
   const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
-  if (any_four) hipLaunchKernelGGL(fn4, dim3(grid4), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
-  if (any_eight) hipLaunchKernelGGL(fn8, dim3(grid8), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), total);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), pieces);
   return launch_check("decompress_batch_kernel");
 }
 

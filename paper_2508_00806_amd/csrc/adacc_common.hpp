@@ -52,6 +52,7 @@ struct TensorDesc {
   uint32_t rowwise;     // compress: 1 = every group lies inside a row (row-at-a-time encoder)
   uint32_t variant;     // index into the instantiation table
   uint32_t dst_f32;     // decompress: 1 = binary32 output
+  uint32_t ptr_shift;   // decompress: works on pieces of 2048 elements; piece u belongs to tile u >> ptr_shift
 };
 
 // Scan workspace: one 64-bit state word per run of tiles and one per block of 64 runs, high half

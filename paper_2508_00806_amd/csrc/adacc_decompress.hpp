@@ -17,9 +17,14 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 template <int E, bool F32>
 constexpr int decompress_lds_per_wave() { return E * kRow * (F32 ? 4 : 2); }
 
+// Decompression always works on pieces of E = 4 rows (2048 elements), whatever the tile of the
+// blob: a piece of a 4096-element tile looks through the outliers of the whole tile and takes
+// those that fall inside it.  (Pieces of 8 rows would need twice the staging area in LDS and
+// leave room for 5 instead of 8 workgroups per CU.)
 template <int BITS, bool ASYM, int E, bool F32>
-__device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t tile, bool has_outliers,
+__device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t tile /* piece */, bool has_outliers,
                                                 unsigned char* lds /* this wavefront's slice */) {
+  static_assert(E == 4, "pieces of 2048 elements");
   const int lane = (int)__lane_id();
   const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
   const uint64_t lane_base = tile_base + (uint64_t)lane * kOct;
@@ -27,8 +32,8 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
   // this tile's slice of the outlier stream
   uint32_t p0 = 0u, p1 = 0u;
   if (has_outliers) {
-    p0 = d.tile_ptr[tile];
-    p1 = d.tile_ptr[tile + 1];
+    p0 = d.tile_ptr[tile >> d.ptr_shift];
+    p1 = d.tile_ptr[(tile >> d.ptr_shift) + 1];
     p0 = p0 < d.cap ? p0 : d.cap;
     p1 = p1 < d.cap ? p1 : d.cap;
     if (p1 < p0) p1 = p0;

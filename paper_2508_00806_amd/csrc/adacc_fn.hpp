@@ -16,8 +16,8 @@ CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise)
 CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
 CompressFn compress_fn_std(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
 CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);
-DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool e8, bool f32);
+DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);
 BatchCompressFn compress_batch_fn(bool eight_rows);
-BatchDecompressFn decompress_batch_fn(bool f32, bool eight_rows);
+BatchDecompressFn decompress_batch_fn(bool f32);
 
 }  // namespace adacc

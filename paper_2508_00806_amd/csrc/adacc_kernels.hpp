@@ -32,13 +32,14 @@ __global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_k
   }
 }
 
-template <int BITS, bool ASYM, int E, bool F32>
+// d.n_tiles counts pieces of 2048 elements here
+template <int BITS, bool ASYM, bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint32_t has_outliers) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<E, F32>()];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<4, F32>()];
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<E, F32>();
+  unsigned char* slice = lds + wave * decompress_lds_per_wave<4, F32>();
   for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-    decompress_tile<BITS, ASYM, E, F32>(d, t, has_outliers != 0u, slice);
+    decompress_tile<BITS, ASYM, 4, F32>(d, t, has_outliers != 0u, slice);
 }
 
 // ---- batch: a launch-wide tile numbering over all tensors of the table
@@ -162,16 +163,14 @@ __global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) 
   }
 }
 
-// Like the batch compression, in two kernels: tiles of 8 rows need twice the staging area in LDS,
-// which would limit the wavefronts per CU for every tensor of the table.
-template <bool F32, bool EIGHT_ROWS>
+// Batch decompression: a launch-wide numbering of the 2048-element pieces of all tensors.
+template <bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, uint32_t n,
                                                                     uint32_t total_tiles) {
-  constexpr int kRows = EIGHT_ROWS ? 8 : 4;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<kRows, F32>()];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<4, F32>()];
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<kRows, F32>();
-  // A wavefront's tiles ascend, so the tensor of a tile is the one of the previous tile or a later
+  unsigned char* slice = lds + wave * decompress_lds_per_wave<4, F32>();
+  // A wavefront's pieces ascend, so the tensor of a piece is the one of the previous piece or a later
   // one: one binary search at the start, then a walk, and the descriptor is read again only when
   // the tensor changes.
   uint32_t g = blockIdx.x * kWavesPerWg + wave;
@@ -187,14 +186,13 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
       } while (g >= next_first);
       d = table[ti];
     }
-    if (((d.variant & 1u) != 0u) != EIGHT_ROWS) continue;  // the other kernel's tensor
     const uint32_t tile = g - d.first_tile;
     const bool ho = (d.variant >> 3) != kModeNone;
     switch (d.variant & 6u) {
-      case 0: decompress_tile<4, false, kRows, F32>(d, tile, ho, slice); break;
-      case 2: decompress_tile<4, true, kRows, F32>(d, tile, ho, slice); break;
-      case 4: decompress_tile<8, false, kRows, F32>(d, tile, ho, slice); break;
-      default: decompress_tile<8, true, kRows, F32>(d, tile, ho, slice); break;
+      case 0: decompress_tile<4, false, 4, F32>(d, tile, ho, slice); break;
+      case 2: decompress_tile<4, true, 4, F32>(d, tile, ho, slice); break;
+      case 4: decompress_tile<8, false, 4, F32>(d, tile, ho, slice); break;
+      default: decompress_tile<8, true, 4, F32>(d, tile, ho, slice); break;
     }
   }
 }
