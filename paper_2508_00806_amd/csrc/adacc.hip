@@ -180,6 +180,13 @@ static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
   return (uint32_t)((tiles_in_launch + units - 1) / units);
 }
 
+// TOPK whose statistics group is the tile has kernels of its own (for tiles of 8 rows: provided no
+// quantisation group is longer than 4 rows)
+static bool topk_whole_tile(const adacc_method* m, const Plan& p) {
+  return m->outlier_mode == ADACC_OUTLIER_TOPK && m->stat_group == p.tile_elems &&
+         (p.tile_elems == 2048 || m->quant_group <= 2048);
+}
+
 static uint32_t decompress_pieces(uint64_t numel) { return (uint32_t)((numel + 2047ull) / 2048ull); }
 
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
@@ -388,7 +395,7 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
   if (rc != ADACC_OK) return rc;
   CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise,
-                              method->outlier_mode == ADACC_OUTLIER_TOPK && method->stat_group == p.tile_elems);
+                              topk_whole_tile(method, p));
   uint32_t tpu = 1u;
   if (p.outliers) {
     uint32_t capacity = 0;

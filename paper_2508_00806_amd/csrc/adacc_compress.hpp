@@ -688,7 +688,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
                                               const float (&limit)[E], const uint32_t (&thr)[E], bool by_magnitude,
                                               bool poisoned, uint32_t lane_pos, int R,
                                               const uint32_t (&rowmag)[E], float (&ext0)[E], float (&ext1)[E],
-                                              TileOutliers<E>& out) {
+                                              TileOutliers<E>& out, int row0 = 0) {
   out.sparse = 0u;
   forget_derived<E>(raw);  // nothing formed from the octets so far is worth its registers
   // uniform, as an integer so that it stays in a scalar register: rows may be skipped on the strength
@@ -725,7 +725,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
         for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(fabsf(x[e]) >= t);
       } else {
         const bool valid = g.lane_off + (uint32_t)(j * kRow) < g.rem;  // blanked octets would be ranked too
-        const uint32_t row_pos = ((uint32_t)(j & (R - 1)) << 9) | lane_pos;
+        const uint32_t row_pos = ((uint32_t)((row0 + j) & (R - 1)) << 9) | lane_pos;
 #pragma unroll
         for (int e = 0; e < kOct; ++e) {
           const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
@@ -755,12 +755,86 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
   }
 }
 
+// ---- a6 .. a8 for a tile (or a piece of one) whose outliers are known: scales from the per-lane
+// extremes of the inlier view, then quantise, pack, store.
+template <int BITS, bool ASYM, int E>
+__device__ __forceinline__ void finish_tile(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
+                                            const float (&ext0)[E], const float (&ext1)[E],
+                                            const TileOutliers<E>& out) {
+  constexpr int Q = 1 << (BITS - 1);
+  // ---- a6: per-group scale (and offset).  Cross-lane max / min run on integer images of the floats.
+  // Every lane of a group would compute the same scale; with at least 4 lanes per group and 4 rows,
+  // lane l of every quad takes row l instead, so that one division serves the whole tile, and the
+  // results go back to the rows by a broadcast inside the quad.
+  float inv[E], off[E], scl[E];
+  const bool transposed = (E == 4) && d.lgq >= 5u;
+  const bool row1 = __builtin_amdgcn_inverse_ballot_w64(0x2222222222222222ull);
+  const bool row2 = __builtin_amdgcn_inverse_ballot_w64(0x4444444444444444ull);
+  const bool row3 = __builtin_amdgcn_inverse_ballot_w64(0x8888888888888888ull);
+  if constexpr (!ASYM) {
+    uint32_t a[E];  // max |y| as bit patterns: for non-negative floats the integer order is the float order
+#pragma unroll
+    for (int j = 0; j < E; ++j) a[j] = __float_as_uint(ext0[j]);
+    groups_reduce_any_order<E>(a, d.lgq, OpUMax());
+    if (transposed) {
+      uint32_t am = row1 ? a[1 % E] : a[0];
+      am = row2 ? a[2 % E] : am;
+      am = row3 ? a[3 % E] : am;
+      float s, i, o;
+      group_scale<false>(d, am, 0, 0, s, i, o);
+      scl[0] = dpp_move<0x00>(s); scl[1 % E] = dpp_move<0x55>(s); scl[2 % E] = dpp_move<0xAA>(s); scl[3 % E] = dpp_move<0xFF>(s);
+      inv[0] = dpp_move<0x00>(i); inv[1 % E] = dpp_move<0x55>(i); inv[2 % E] = dpp_move<0xAA>(i); inv[3 % E] = dpp_move<0xFF>(i);
+#pragma unroll
+      for (int j = 0; j < E; ++j) off[j] = 0.0f;
+    } else {
+#pragma unroll
+      for (int j = 0; j < E; ++j) group_scale<false>(d, a[j], 0, 0, scl[j], inv[j], off[j]);
+    }
+  } else {
+    int32_t hi[E], lo[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) { hi[j] = float_key(ext0[j]); lo[j] = float_key(ext1[j]); }
+    groups_reduce_any_order<E>(hi, d.lgq, OpIMax());
+    groups_reduce_any_order<E>(lo, d.lgq, OpIMin());
+    if (transposed) {
+      int32_t h = row1 ? hi[1 % E] : hi[0], l = row1 ? lo[1 % E] : lo[0];
+      h = row2 ? hi[2 % E] : h; l = row2 ? lo[2 % E] : l;
+      h = row3 ? hi[3 % E] : h; l = row3 ? lo[3 % E] : l;
+      float s, i, o;
+      group_scale<true>(d, 0u, h, l, s, i, o);
+      scl[0] = dpp_move<0x00>(s); scl[1 % E] = dpp_move<0x55>(s); scl[2 % E] = dpp_move<0xAA>(s); scl[3 % E] = dpp_move<0xFF>(s);
+      inv[0] = dpp_move<0x00>(i); inv[1 % E] = dpp_move<0x55>(i); inv[2 % E] = dpp_move<0xAA>(i); inv[3 % E] = dpp_move<0xFF>(i);
+      off[0] = dpp_move<0x00>(o); off[1 % E] = dpp_move<0x55>(o); off[2 % E] = dpp_move<0xAA>(o); off[3 % E] = dpp_move<0xFF>(o);
+    } else {
+#pragma unroll
+      for (int j = 0; j < E; ++j) group_scale<true>(d, 0u, hi[j], lo[j], scl[j], inv[j], off[j]);
+    }
+  }
+
+  // ---- a7 + a8: quantise, pack, store codes and scales
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    float y[kOct];
+    widen_row(raw[j], y);
+    if (out.row_cnt[j] != 0u) {  // uniform: the inlier view is zero where the mask says so
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        const uint32_t keep = (uint32_t)(((int32_t)(~out.mask[j] << (31 - e))) >> 31);  // all ones unless bit e is set
+        y[e] = __uint_as_float(__float_as_uint(y[e]) & keep);
+      }
+    }
+    uint32_t c[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off[j] : y[e], inv[j]);
+    store_row<BITS, ASYM, E>(d, g, j, c, scl[j], off[j]);
+  }
+}
+
 // WHOLE: the statistics group is the tile (known at compile time, so that nothing about rows per
 // group is decided at run time: each such decision costs scalar instructions and registers).
 template <int MODE, int BITS, bool ASYM, int E, bool STORE, bool WHOLE>
 __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const TileGeo<E>& g,
                                                     const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
-  constexpr int Q = 1 << (BITS - 1);
   // ---- a2: statistics of the statistics groups
   float limit[E];   // STD: k^2 * var of the row's group
   uint32_t thr[E];  // TOPK: selection threshold of the row's group
@@ -849,84 +923,113 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
   }
 
-  if constexpr (!STORE) return;  // the caller only wants the outliers
+  if constexpr (STORE) finish_tile<BITS, ASYM, E>(d, g, raw, ext0, ext1, out);
+}
 
-  // ---- a6: per-group scale (and offset).  Cross-lane max / min run on integer images of the floats.
-  // Every lane of a group would compute the same scale; with at least 4 lanes per group and 4 rows,
-  // lane l of every quad takes row l instead, so that one division serves the whole tile, and the
-  // results go back to the rows by a broadcast inside the quad.
-  float inv[E], off[E], scl[E];
-  const bool transposed = (E == 4) && d.lgq >= 5u;
-  const bool row1 = __builtin_amdgcn_inverse_ballot_w64(0x2222222222222222ull);
-  const bool row2 = __builtin_amdgcn_inverse_ballot_w64(0x4444444444444444ull);
-  const bool row3 = __builtin_amdgcn_inverse_ballot_w64(0x8888888888888888ull);
-  if constexpr (!ASYM) {
-    uint32_t a[E];  // max |y| as bit patterns: for non-negative floats the integer order is the float order
+// Rounds over a tile that is one statistics group: the k-th largest key, uniform.  Returns whether
+// it belongs to an Inf / NaN (then there may be more than k outliers).
+template <int E>
+__device__ __forceinline__ bool topk_select_rounds_whole(const TensorDesc& d, const uint32_t (&raw)[E][4], uint32_t& kth_out,
+                                                         uint32_t lane_pos) {
+  uint32_t kth = 0xFFFFFFFFu;
+  for (uint32_t r = 0; r < d.topk; ++r) {
+    forget_derived<E>(raw);  // the keys are formed again in every round
+    uint32_t m = 0u;
 #pragma unroll
-    for (int j = 0; j < E; ++j) a[j] = __float_as_uint(ext0[j]);
-    groups_reduce_any_order<E>(a, d.lgq, OpUMax());
-    if (transposed) {
-      uint32_t am = row1 ? a[1 % E] : a[0];
-      am = row2 ? a[2 % E] : am;
-      am = row3 ? a[3 % E] : am;
-      float s, i, o;
-      group_scale<false>(d, am, 0, 0, s, i, o);
-      scl[0] = dpp_move<0x00>(s); scl[1 % E] = dpp_move<0x55>(s); scl[2 % E] = dpp_move<0xAA>(s); scl[3 % E] = dpp_move<0xFF>(s);
-      inv[0] = dpp_move<0x00>(i); inv[1 % E] = dpp_move<0x55>(i); inv[2 % E] = dpp_move<0xAA>(i); inv[3 % E] = dpp_move<0xFF>(i);
-#pragma unroll
-      for (int j = 0; j < E; ++j) off[j] = 0.0f;
-    } else {
-#pragma unroll
-      for (int j = 0; j < E; ++j) group_scale<false>(d, a[j], 0, 0, scl[j], inv[j], off[j]);
-    }
-  } else {
-    int32_t hi[E], lo[E];
-#pragma unroll
-    for (int j = 0; j < E; ++j) { hi[j] = float_key(ext0[j]); lo[j] = float_key(ext1[j]); }
-    groups_reduce_any_order<E>(hi, d.lgq, OpIMax());
-    groups_reduce_any_order<E>(lo, d.lgq, OpIMin());
-    if (transposed) {
-      int32_t h = row1 ? hi[1 % E] : hi[0], l = row1 ? lo[1 % E] : lo[0];
-      h = row2 ? hi[2 % E] : h; l = row2 ? lo[2 % E] : l;
-      h = row3 ? hi[3 % E] : h; l = row3 ? lo[3 % E] : l;
-      float s, i, o;
-      group_scale<true>(d, 0u, h, l, s, i, o);
-      scl[0] = dpp_move<0x00>(s); scl[1 % E] = dpp_move<0x55>(s); scl[2 % E] = dpp_move<0xAA>(s); scl[3 % E] = dpp_move<0xFF>(s);
-      inv[0] = dpp_move<0x00>(i); inv[1 % E] = dpp_move<0x55>(i); inv[2 % E] = dpp_move<0xAA>(i); inv[3 % E] = dpp_move<0xFF>(i);
-      off[0] = dpp_move<0x00>(o); off[1 % E] = dpp_move<0x55>(o); off[2 % E] = dpp_move<0xAA>(o); off[3 % E] = dpp_move<0xFF>(o);
-    } else {
-#pragma unroll
-      for (int j = 0; j < E; ++j) group_scale<true>(d, 0u, hi[j], lo[j], scl[j], inv[j], off[j]);
-    }
-  }
-
-  // ---- a7 + a8: quantise, pack, store codes and scales
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    float y[kOct];
-    widen_row(raw[j], y);
-    if (out.row_cnt[j] != 0u) {  // uniform: the inlier view is zero where the mask says so
+    for (int j = 0; j < E; ++j) {
+      const uint32_t row_pos = ((uint32_t)j << 9) | lane_pos;
 #pragma unroll
       for (int e = 0; e < kOct; ++e) {
-        const uint32_t keep = (uint32_t)(((int32_t)(~out.mask[j] << (31 - e))) >> 31);  // all ones unless bit e is set
-        y[e] = __uint_as_float(__float_as_uint(y[e]) & keep);
+        const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
+        const uint32_t cand = (key < kth) ? key : 0u;
+        m = (cand > m) ? cand : m;
       }
     }
-    uint32_t c[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off[j] : y[e], inv[j]);
-    store_row<BITS, ASYM, E>(d, g, j, c, scl[j], off[j]);
+    kth = wave_max_u32_scalar(m);
   }
+  kth_out = kth;
+  return (kth >> 16) >= 0x7F80u;
+}
+
+// TOPK over a tile of 8 rows that is one statistics group, quantisation groups inside 4 rows
+// (such tiles are always complete: the group size divides the tensor).  The selection looks at
+// all 8 rows; everything else runs on two pieces of 4 rows with the code for 4-row tiles, whose
+// per-row arrays are half as long: 4 instead of 3 wavefronts per SIMD, and no code of its own.
+template <int BITS, bool ASYM, bool STORE>
+__device__ __forceinline__ void encode_tile_whole8(const TensorDesc& d, const TileGeo<8>& g, const uint32_t (&raw)[8][4],
+                                                   TileOutliers<8>& out) {
+  constexpr int H = 4;
+  const uint32_t(&ra)[H][4] = reinterpret_cast<const uint32_t(&)[H][4]>(raw[0]);
+  const uint32_t(&rb)[H][4] = reinterpret_cast<const uint32_t(&)[H][4]>(raw[H]);
+  TileGeo<H> ga, gb;
+  ga.base = g.base; ga.lane_off = g.lane_off; ga.rem = (uint32_t)(H * kRow); ga.full = true;
+  gb.base = g.base + (uint64_t)(H * kRow); gb.lane_off = g.lane_off; gb.rem = (uint32_t)(H * kRow); gb.full = true;
+
+  uint32_t rowmag[8];
+  row_magnitudes<8>(raw, rowmag);
+  const uint32_t(&ma)[H] = reinterpret_cast<const uint32_t(&)[H]>(rowmag[0]);
+  const uint32_t(&mb)[H] = reinterpret_cast<const uint32_t(&)[H]>(rowmag[H]);
+  uint32_t lane_pos = (uint32_t)lane_id() << 3;
+  float limit[H];
+#pragma unroll
+  for (int j = 0; j < H; ++j) limit[j] = 0.0f;
+  TileOutliers<H> oa, ob;
+  float e0a[H], e1a[H], e0b[H], e1b[H];
+  bool poisoned = false;
+  bool try_maxima = d.topk <= 8u;
+#pragma nounroll
+  while (true) {
+    bool by_magnitude = false;
+    uint32_t t = 0u;  // uniform: magnitude threshold (bits of a binary32) or k-th largest key
+    if (try_maxima) {
+      uint32_t thr8[8];
+      by_magnitude = topk_lane_maxima<8, true>(d, rowmag, thr8);
+      t = thr8[0];
+    }
+    if (!by_magnitude) {
+      asm volatile("" : "+v"(lane_pos));  // nothing of this rare path is prepared outside the loop over tiles
+      poisoned = topk_select_rounds_whole<8>(d, raw, t, lane_pos);
+    }
+    uint32_t thr[H];
+#pragma unroll
+    for (int j = 0; j < H; ++j) thr[j] = t;
+    outlier_phase<kModeTopk, ASYM, H>(d, ga, ra, limit, thr, by_magnitude, poisoned, lane_pos, 8, ma, e0a, e1a, oa, 0);
+    outlier_phase<kModeTopk, ASYM, H>(d, gb, rb, limit, thr, by_magnitude, poisoned, lane_pos, 8, mb, e0b, e1b, ob, H);
+    oa.total = 0u; ob.total = 0u;
+#pragma unroll
+    for (int j = 0; j < H; ++j) {
+      oa.row_off[j] = oa.total; oa.total += oa.row_cnt[j];
+      ob.row_off[j] = ob.total; ob.total += ob.row_cnt[j];
+    }
+    if (!by_magnitude) break;
+    if (oa.total + ob.total == d.topk) break;  // exactly k at or above the threshold: they are the k largest
+    try_maxima = false;
+  }
+  if constexpr (STORE) {
+    finish_tile<BITS, ASYM, H>(d, ga, ra, e0a, e1a, oa);
+    finish_tile<BITS, ASYM, H>(d, gb, rb, e0b, e1b, ob);
+  }
+#pragma unroll
+  for (int j = 0; j < H; ++j) {
+    out.mask[j] = oa.mask[j]; out.mask[H + j] = ob.mask[j];
+    out.lane_excl[j] = oa.lane_excl[j]; out.lane_excl[H + j] = ob.lane_excl[j];
+    out.row_cnt[j] = oa.row_cnt[j]; out.row_cnt[H + j] = ob.row_cnt[j];
+    out.row_off[j] = oa.row_off[j]; out.row_off[H + j] = oa.total + ob.row_off[j];
+  }
+  out.total = oa.total + ob.total;
+  out.sparse = oa.sparse | (ob.sparse << H);
 }
 
 // ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide.
 // STORE = false: only the outliers are found (nothing is quantised or stored).
-// WHOLE (general encoder, TOPK): the statistics group is the whole tile.
+// WHOLE (general encoder, TOPK): the statistics group is the whole tile (with 8 rows: and no
+// quantisation group is longer than 4 rows).
 template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false, bool STORE = true>
 __device__ __forceinline__ void encode_tile(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
                                             TileOutliers<E>& out) {
   static_assert(!WHOLE || (MODE == kModeTopk && !ROWWISE), "only the general TOPK encoder is specialised");
   if constexpr (ROWWISE) encode_tile_rowwise<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
+  else if constexpr (WHOLE && E == 8) encode_tile_whole8<BITS, ASYM, STORE>(d, g, raw, out);
   else encode_tile_general<MODE, BITS, ASYM, E, STORE, WHOLE>(d, g, raw, out);
 }
 

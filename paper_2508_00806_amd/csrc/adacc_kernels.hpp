@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) 
     case kModeAbs: compress_dispatch_mode<kModeAbs, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
     case kModeStd: compress_dispatch_mode<kModeStd, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
     default:
-      if (d.lgs == (EIGHT_ROWS ? 12u : 11u)) compress_dispatch_topk_whole<EIGHT_ROWS>(d, unit, sc, &stage[wave]);
+      if (d.lgs == (EIGHT_ROWS ? 12u : 11u) && d.lgq <= 11u) compress_dispatch_topk_whole<EIGHT_ROWS>(d, unit, sc, &stage[wave]);
       else compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, unit, sc, &stage[wave]);
       break;
   }
