@@ -13,11 +13,15 @@ namespace adacc {
 // ---- single tensor, compress.  With outliers: run = 4 * workgroup + wavefront, and the grid is
 // exactly ceil(n_units / 4) workgroups, because the chained scan relies on runs being started
 // in index order.  NONE: tiles are independent, grid-stride loop over tiles.
+// the symmetric whole-tile TOPK kernels for 8-row tiles fit 4 wavefronts per SIMD when asked to
+#ifndef ADACC_WHOLE8_MIN_WAVES
+#define ADACC_WHOLE8_MIN_WAVES 4
+#endif
 #ifndef ADACC_COMPRESS_MIN_WAVES
 #define ADACC_COMPRESS_MIN_WAVES 1
 #endif
 template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
-__global__ __launch_bounds__(kThreads, ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
+__global__ __launch_bounds__(kThreads, (E == 8 && WHOLE && !ASYM) ? ADACC_WHOLE8_MIN_WAVES : ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
                                                                                       uint64_t* state2, uint32_t tag,
                                                                                       uint32_t spin_limit) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
