@@ -279,12 +279,13 @@ def test_batch_matches_single_calls_and_oracle():
         methods.append(m); srcs.append(x.contiguous().view(-1).cuda()); blobs.append(blob); layouts.append(L); ocs.append(oc)
     numels = [s.numel() for s in srcs]
     ws = adacc.alloc_workspace(adacc.batch_workspace_bytes(methods, numels))
-    for rep in range(2):
+    prepared = adacc.prepare_compress_batch(methods, srcs, blobs)  # the argument arrays, marshalled once
+    for rep in range(3):
         log(f"[parity] batch compress rep={rep} tensors={len(methods)}")
         for b in blobs:
             if b is not None:
                 b.zero_()
-        adacc.compress_batch(methods, srcs, blobs, ws)
+        adacc.compress_batch(methods, srcs, blobs, ws, prepared=prepared if rep else None)
         torch.cuda.synchronize()
         for (tname, hidden, md, x), m, blob, L, oc in zip(table, methods, blobs, layouts, ocs):
             if md is None:
@@ -294,7 +295,7 @@ def test_batch_matches_single_calls_and_oracle():
     for dtype in (torch.bfloat16, torch.float32):
         dsts = [None if b is None else torch.empty(s.numel(), dtype=dtype, device="cuda") for s, b in zip(srcs, blobs)]
         log(f"[parity] batch decompress {dtype}")
-        adacc.decompress_batch(methods, blobs, dsts, ws)
+        adacc.decompress_batch(methods, blobs, dsts, ws, prepared=adacc.prepare_decompress_batch(methods, blobs, dsts))
         torch.cuda.synchronize()
         for d, oc in zip(dsts, ocs):
             if d is None:
