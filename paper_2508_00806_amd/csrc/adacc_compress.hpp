@@ -277,14 +277,21 @@ struct TileGeo {
   uint32_t lane_off;  // lane * 8
   bool full;          // uniform: rem == E*512
 };
-template <int E>
+// COMPLETE: the caller knows that every tile of the tensor is complete (the tile is a statistics
+// group, and group sizes divide the tensor), so nothing about short tiles is computed or tested.
+template <int E, bool COMPLETE = false>
 __device__ __forceinline__ TileGeo<E> tile_geo(const TensorDesc& d, uint32_t tile) {
   TileGeo<E> g;
   g.base = (uint64_t)tile * (uint64_t)(E * kRow);
-  const uint64_t left = d.numel - g.base;
-  g.rem = left < (uint64_t)(E * kRow) ? (uint32_t)left : (uint32_t)(E * kRow);
   g.lane_off = (uint32_t)lane_id() * kOct;
-  g.full = g.rem == (uint32_t)(E * kRow);
+  if constexpr (COMPLETE) {
+    g.rem = (uint32_t)(E * kRow);
+    g.full = true;
+  } else {
+    const uint64_t left = d.numel - g.base;
+    g.rem = left < (uint64_t)(E * kRow) ? (uint32_t)left : (uint32_t)(E * kRow);
+    g.full = g.rem == (uint32_t)(E * kRow);
+  }
   return g;
 }
 
@@ -292,15 +299,15 @@ __device__ __forceinline__ TileGeo<E> tile_geo(const TensorDesc& d, uint32_t til
 // the end of the tensor re-read its last octet and are blanked afterwards): a load under a
 // branch would make the number of loads in flight unknown to the compiler's wait-count
 // bookkeeping, which then waits for the prefetched tile together with the current one.
-template <int E>
+template <int E, bool COMPLETE = false>
 __device__ __forceinline__ void load_tile(const TensorDesc& d, uint32_t tile, uint32_t (&raw)[E][4]) {
-  const TileGeo<E> g = tile_geo<E>(d, tile);
+  const TileGeo<E> g = tile_geo<E, COMPLETE>(d, tile);
   const uint16_t* sp = d.src + g.base;
   const uint32_t last = g.rem - kOct;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     uint32_t off = g.lane_off + (uint32_t)(j * kRow);
-    off = off < last ? off : last;
+    if constexpr (!COMPLETE) off = off < last ? off : last;
     const uint4 v = *reinterpret_cast<const uint4*>(sp + off);
     raw[j][0] = v.x; raw[j][1] = v.y; raw[j][2] = v.z; raw[j][3] = v.w;
   }
@@ -1110,7 +1117,7 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   constexpr bool kPrefetch = (E == 4);
   uint32_t raw[E][4];
   if constexpr (kPrefetch) {
-    load_tile<E>(d, t0, raw);
+    load_tile<E, WHOLE>(d, t0, raw);
     // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
     // complete on every path, and the only wait left is the one for the prefetched tile at the end of
     // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
@@ -1118,10 +1125,10 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   }
   for (uint32_t t = t0; t < t1; ++t) {
     uint32_t nxt[kPrefetch ? E : 1][4];
-    if constexpr (kPrefetch) load_tile<E>(d, (t + 1 < t1) ? t + 1 : t, nxt);  // the run's last tile fetches itself again
-    else load_tile<E>(d, t, raw);
+    if constexpr (kPrefetch) load_tile<E, WHOLE>(d, (t + 1 < t1) ? t + 1 : t, nxt);  // the run's last tile fetches itself again
+    else load_tile<E, WHOLE>(d, t, raw);
 
-    const TileGeo<E> g = tile_geo<E>(d, t);
+    const TileGeo<E> g = tile_geo<E, WHOLE>(d, t);
     blank_tail<E>(g, raw);
     TileOutliers<E> out;
     encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
@@ -1169,8 +1176,8 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
     if ((uint32_t)lane < t1 - t0) d.tile_ptr[t0 + (uint32_t)lane] = excl + tile_off;
     // second pass over the tiles whose outliers were only counted
     for (uint32_t t = collected; t < t1; ++t) {
-      load_tile<E>(d, t, raw);
-      const TileGeo<E> g = tile_geo<E>(d, t);
+      load_tile<E, WHOLE>(d, t, raw);
+      const TileGeo<E> g = tile_geo<E, WHOLE>(d, t);
       blank_tail<E>(g, raw);
       TileOutliers<E> out;
       encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE, false>(d, g, raw, out);
