@@ -1115,38 +1115,59 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   // Tiles of 4 rows: the next tile is in flight while this one is encoded.  Tiles of 8 rows are
   // loaded when their turn comes: a second tile in registers would halve the wavefronts per SIMD.
   constexpr bool kPrefetch = (E == 4);
-  uint32_t raw[E][4];
-  if constexpr (kPrefetch) {
-    load_tile<E, WHOLE>(d, t0, raw);
-    // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
-    // complete on every path, and the only wait left is the one for the prefetched tile at the end of
-    // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-  }
-  for (uint32_t t = t0; t < t1; ++t) {
-    uint32_t nxt[kPrefetch ? E : 1][4];
-    if constexpr (kPrefetch) load_tile<E, WHOLE>(d, (t + 1 < t1) ? t + 1 : t, nxt);  // the run's last tile fetches itself again
-    else load_tile<E, WHOLE>(d, t, raw);
-
-    const TileGeo<E> g = tile_geo<E, WHOLE>(d, t);
-    blank_tail<E>(g, raw);
-    TileOutliers<E> out;
-    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
+  // what a finished tile adds to the run: its offset, and its outliers to the staging area while they fit
+  auto account = [&](uint32_t t, const TileOutliers<E>& out, const uint32_t (&tile_raw)[E][4]) {
     if ((uint32_t)lane == t - t0) tile_off = run_total;
-
     if (out.total != 0u) {
       if (collected == t1 && staged + out.total > (uint32_t)kStageCap) collected = t;  // no room from here on
       if (collected == t1) {
-        emit_outliers<E>(raw, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
+        emit_outliers<E>(tile_raw, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
         staged += out.total;
       }
       run_total += out.total;
     }
+  };
+
+  // Only the last tile of a tensor can be short.  The loop takes the complete tiles of the run with an
+  // encoder that carries no arithmetic, masks or branches for short ones; a short last tile follows on
+  // its own.
+  const bool short_last = !WHOLE && t1 == d.n_tiles && (d.numel & (uint64_t)(E * kRow - 1)) != 0u;
+  const uint32_t t1c = short_last ? t1 - 1u : t1;
+  uint32_t raw[E][4];
+  if constexpr (kPrefetch) {
+    if (t0 < t1c) {
+      load_tile<E, true>(d, t0, raw);
+      // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
+      // complete on every path, and the only wait left is the one for the prefetched tile at the end of
+      // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
+  }
+  for (uint32_t t = t0; t < t1c; ++t) {
+    uint32_t nxt[kPrefetch ? E : 1][4];
+    if constexpr (kPrefetch) load_tile<E, true>(d, (t + 1 < t1c) ? t + 1 : t, nxt);  // the last one fetches itself again
+    else load_tile<E, true>(d, t, raw);
+
+    const TileGeo<E> g = tile_geo<E, true>(d, t);
+    TileOutliers<E> out;
+    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
+    account(t, out, raw);
     if constexpr (kPrefetch) {
 #pragma unroll
       for (int j = 0; j < E; ++j) {
         raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
       }
+    }
+  }
+  if constexpr (!WHOLE) {
+    if (short_last) {
+      const uint32_t t = t1c;
+      load_tile<E, false>(d, t, raw);
+      const TileGeo<E> g = tile_geo<E, false>(d, t);
+      blank_tail<E>(g, raw);
+      TileOutliers<E> out;
+      encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
+      account(t, out, raw);
     }
   }
 
@@ -1203,11 +1224,17 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
 template <int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_tile_plain(const TensorDesc& d, uint32_t tile) {
   uint32_t raw[E][4];
-  load_tile<E>(d, tile, raw);
-  const TileGeo<E> g = tile_geo<E>(d, tile);
-  blank_tail<E>(g, raw);
   TileOutliers<E> out;
-  encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+  if (tile + 1u < d.n_tiles) {  // only the last tile can be short: the copy for the others knows nothing of it
+    load_tile<E, true>(d, tile, raw);
+    const TileGeo<E> g = tile_geo<E, true>(d, tile);
+    encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+  } else {
+    load_tile<E, false>(d, tile, raw);
+    const TileGeo<E> g = tile_geo<E, false>(d, tile);
+    blank_tail<E>(g, raw);
+    encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+  }
   if (tile == 0 && lane_id() == 0) {
     d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;
   }
