@@ -59,6 +59,16 @@ def lib():
         L.oracle_logical_bytes.restype = ctypes.c_uint64
         L.oracle_pairwise_sum.argtypes = [vp, sz]
         L.oracle_pairwise_sum.restype = ctypes.c_float
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.oracle_channel_scores.argtypes = [vp, sz, sz, vp]
+        L.oracle_channel_scores.restype = None
+        L.oracle_channel_select.argtypes = [vp, sz, ctypes.c_float, vp, vp]
+        L.oracle_channel_select.restype = None
+        L.oracle_channel_compress.argtypes = [ctypes.POINTER(_CMethod), vp, sz, sz, ctypes.c_float, vp, vp, vp,
+                                              vp, vp, vp, sz, ctypes.POINTER(sz)]
+        L.oracle_channel_compress.restype = ctypes.c_int
+        L.oracle_channel_decompress.argtypes = [ctypes.POINTER(_CMethod), vp, vp, vp, vp, vp, sz, sz, sz, vp, vp]
+        L.oracle_channel_decompress.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -141,3 +151,79 @@ def logical_bytes(m: Method, n: int, n_out: int) -> int:
 def pairwise_sum(v) -> np.float32:
     v = np.ascontiguousarray(v, dtype=np.float32)
     return np.float32(lib().oracle_pairwise_sum(_p(v), v.size))
+
+
+# ---- outlier channels (Section 3.2, Eq. 1) ----
+
+@dataclass
+class ChannelCompressed:
+    method: Method
+    tokens: int
+    hidden: int
+    codes: np.ndarray      # int8 [tokens*hidden]
+    packed: np.ndarray     # uint8
+    scale: np.ndarray      # float32 [n/Gq]
+    zp: np.ndarray         # float32 [n/Gq] (asym) or empty
+    ch_idx: np.ndarray     # int32 [min(n_ch, cap)]
+    ch_val: np.ndarray     # uint16 [tokens, n_ch] (empty if n_ch > cap)
+    n_ch: int
+
+
+def channel_scores(x_bits, tokens: int, hidden: int) -> np.ndarray:
+    x = _as_u16(x_bits)
+    assert x.size == tokens * hidden
+    S = np.zeros(hidden, dtype=np.float64)
+    lib().oracle_channel_scores(_p(x), tokens, hidden, _p(S))
+    return S
+
+
+def channel_select(S, z_thresh: float):
+    """Returns (is_out uint8[hidden], mu, sigma)."""
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    out = np.zeros(S.size, dtype=np.uint8)
+    stats = np.zeros(2, dtype=np.float64)
+    lib().oracle_channel_select(_p(S), S.size, float(z_thresh), _p(out), _p(stats))
+    return out, float(stats[0]), float(stats[1])
+
+
+def channel_compress(m: Method, x_bits, tokens: int, hidden: int, z_thresh: float = 3.0, cap=None) -> ChannelCompressed:
+    x = _as_u16(x_bits)
+    n = tokens * hidden
+    assert x.size == n
+    cap = hidden if cap is None else int(cap)
+    groups = n // m.quant_group if m.quant_group else 0
+    codes = np.zeros(n, dtype=np.int8)
+    packed = np.zeros((n * m.bits + 7) // 8, dtype=np.uint8)
+    scale = np.zeros(groups, dtype=np.float32)
+    zp = np.zeros(groups if m.asym else 0, dtype=np.float32)
+    ci = np.zeros(max(cap, 1), dtype=np.int32)
+    cv = np.zeros(max(tokens * cap, 1), dtype=np.uint16)
+    n_ch = ctypes.c_size_t(0)
+    cm = m.c()
+    rc = lib().oracle_channel_compress(ctypes.byref(cm), _p(x), tokens, hidden, float(z_thresh), _p(codes),
+                                       _p(packed), _p(scale), _p(zp) if m.asym else None, _p(ci), _p(cv), cap,
+                                       ctypes.byref(n_ch))
+    if rc != 0:
+        raise ValueError("oracle: malformed method")
+    k = n_ch.value
+    if k <= cap:
+        vals = cv[:tokens * k].copy().reshape(tokens, k)
+    else:
+        vals = np.zeros((tokens, 0), dtype=np.uint16)
+    return ChannelCompressed(m, tokens, hidden, codes, packed, scale, zp, ci[:min(k, cap)].copy(), vals, k)
+
+
+def channel_decompress(c: ChannelCompressed):
+    """Returns (xhat_f32, xhat_bf16_bits)."""
+    n = c.tokens * c.hidden
+    f = np.zeros(n, dtype=np.float32)
+    b = np.zeros(n, dtype=np.uint16)
+    cm = c.method.c()
+    ci = np.ascontiguousarray(c.ch_idx)
+    cv = np.ascontiguousarray(c.ch_val).reshape(-1)
+    rc = lib().oracle_channel_decompress(ctypes.byref(cm), _p(c.packed), _p(c.scale),
+                                         _p(c.zp) if c.method.asym else None, _p(ci), _p(cv), ci.size, c.tokens,
+                                         c.hidden, _p(f), _p(b))
+    if rc != 0:
+        raise ValueError("oracle: channel decompress failed")
+    return f, b

@@ -197,30 +197,10 @@ static void quant_asym(const oracle_method *m, const float *y, size_t g, int8_t 
   for (size_t i = 0; i < g; ++i) codes[i] = clip_code(round_product(y[i] - o, inv), q);
 }
 
-/* ---------- steps 1-4 ---------- */
-
-int oracle_compress(const oracle_method *m, const uint16_t *x, size_t n, int8_t *codes, uint8_t *packed,
-                    float *scale, float *zp, int32_t *out_idx, uint16_t *out_val, size_t cap,
-                    size_t *n_out) {
-  if (!method_ok(m, n)) return -1;
-  if (m->asym && !zp) return -1;
-  uint8_t *out = (uint8_t *)malloc(n ? n : 1);
+/* Steps 3 and 4 for a given outlier mask, then the packing of the codes. */
+static void quantise_rest(const oracle_method *m, const uint16_t *x, const uint8_t *out, size_t n,
+                          int8_t *codes, uint8_t *packed, float *scale, float *zp) {
   float *y = (float *)malloc((n ? n : 1) * sizeof(float));
-
-  /* 1. which elements are outliers */
-  oracle_select_outliers(m, x, n, out);
-
-  /* 2. keep them, in ascending index order, exactly as they are */
-  size_t cnt = 0;
-  for (size_t i = 0; i < n; ++i) {
-    if (!out[i]) continue;
-    if (cnt < cap) {
-      out_idx[cnt] = (int32_t)i;
-      out_val[cnt] = x[i];
-    }
-    ++cnt;
-  }
-  if (n_out) *n_out = cnt;
 
   /* 3. zero them in the activation; a value that is not finite, or a negative
    *    zero, also counts as zero from here on */
@@ -251,8 +231,35 @@ int oracle_compress(const oracle_method *m, const uint16_t *x, size_t n, int8_t 
       }
     }
   }
-  free(out);
   free(y);
+}
+
+/* ---------- steps 1-4 ---------- */
+
+int oracle_compress(const oracle_method *m, const uint16_t *x, size_t n, int8_t *codes, uint8_t *packed,
+                    float *scale, float *zp, int32_t *out_idx, uint16_t *out_val, size_t cap,
+                    size_t *n_out) {
+  if (!method_ok(m, n)) return -1;
+  if (m->asym && !zp) return -1;
+  uint8_t *out = (uint8_t *)malloc(n ? n : 1);
+
+  /* 1. which elements are outliers */
+  oracle_select_outliers(m, x, n, out);
+
+  /* 2. keep them, in ascending index order, exactly as they are */
+  size_t cnt = 0;
+  for (size_t i = 0; i < n; ++i) {
+    if (!out[i]) continue;
+    if (cnt < cap) {
+      out_idx[cnt] = (int32_t)i;
+      out_val[cnt] = x[i];
+    }
+    ++cnt;
+  }
+  if (n_out) *n_out = cnt;
+
+  quantise_rest(m, x, out, n, codes, packed, scale, zp);
+  free(out);
   return 0;
 }
 
@@ -264,11 +271,9 @@ static int unpack_code(const oracle_method *m, const uint8_t *packed, size_t i) 
   return (nib >= 8) ? nib - 16 : nib;
 }
 
-int oracle_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, const float *zp,
-                      const int32_t *out_idx, const uint16_t *out_val, size_t n_out, size_t n,
-                      float *xhat_f32, uint16_t *xhat_bf16) {
-  if (!method_ok(m, n)) return -1;
-  if (m->asym && !zp) return -1;
+/* X^ = code * S (+ O) for every element */
+static void dequantise_all(const oracle_method *m, const uint8_t *packed, const float *scale, const float *zp,
+                           size_t n, float *xhat_f32, uint16_t *xhat_bf16) {
   const size_t gq = m->quant_group;
   for (size_t i = 0; i < n; ++i) {
     float c = (float)unpack_code(m, packed, i);
@@ -277,6 +282,14 @@ int oracle_decompress(const oracle_method *m, const uint8_t *packed, const float
     if (xhat_f32) xhat_f32[i] = v;
     if (xhat_bf16) xhat_bf16[i] = f32_to_bf16_rne(v);
   }
+}
+
+int oracle_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, const float *zp,
+                      const int32_t *out_idx, const uint16_t *out_val, size_t n_out, size_t n,
+                      float *xhat_f32, uint16_t *xhat_bf16) {
+  if (!method_ok(m, n)) return -1;
+  if (m->asym && !zp) return -1;
+  dequantise_all(m, packed, scale, zp, n, xhat_f32, xhat_bf16);
   for (size_t j = 0; j < n_out; ++j) {
     size_t i = (size_t)out_idx[j];
     if (i >= n) return -1;
@@ -289,4 +302,138 @@ int oracle_decompress(const oracle_method *m, const uint8_t *packed, const float
 uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out) {
   uint64_t groups = n / m->quant_group;
   return (uint64_t)n * m->bits / 8 + 4ull * groups * (m->asym ? 2 : 1) + 6ull * n_out;
+}
+
+/* ====================================================================================
+ * Outlier CHANNELS (Section 3.2, Eq. 1): the paper's own selection rule.
+ *
+ * The activation is a matrix of `tokens` rows and `hidden` channels, row-major.  For channel h,
+ * S_h is the sum over the tokens of |x|; mu and sigma are mean and standard deviation of S_h over
+ * the channels; Z_h = (S_h - mu) / sigma; channels with Z_h above the threshold (3 in the paper)
+ * are kept whole and uncompressed, with their indices, are zeroed in the activation, and the rest
+ * is quantised as before.
+ *
+ * Readings (the printed Eq. 1 has a slipped subscript; the text after it defines the terms):
+ *   - sigma is the population standard deviation (divide by the number of channels);
+ *   - the threshold is compared against Z itself, formed by one binary64 division;
+ *   - a channel whose sum is not finite is always an outlier and takes no part in mu and sigma;
+ *   - if sigma is zero or not a number (all channels alike, or none left), nothing else is selected.
+ * The selection is an integer decision taken by floating-point sums, so the order of the sums is
+ * part of the definition:
+ *   - tokens are taken in chunks of 64 consecutive rows; within a chunk |x| is added up in
+ *     binary32, one token after the other, starting from +0;
+ *   - S_h is the binary64 sum of the chunk sums, one chunk after the other;
+ *   - sums over the channels use 256 binary64 accumulators, channel h going to accumulator
+ *     h mod 256 in ascending order of h, which are then folded by halves (a[j] += a[j + s],
+ *     s = 128, 64, ..., 1);
+ *   - the sum of squared deviations is accumulated with fused multiply-adds.
+ * ==================================================================================== */
+
+enum { CHUNK_TOKENS = 64, CHANNEL_ACCS = 256 };
+
+/* S_h for every channel. */
+void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S) {
+  for (size_t h = 0; h < hidden; ++h) {
+    double s = 0.0;
+    for (size_t t0 = 0; t0 < tokens; t0 += CHUNK_TOKENS) {
+      float part = 0.0f;
+      for (size_t t = t0; t < tokens && t < t0 + CHUNK_TOKENS; ++t) part = part + fabsf(bf16_to_f32(x[t * hidden + h]));
+      s = s + (double)part;
+    }
+    S[h] = s;
+  }
+}
+
+static double fold_accumulators(double *a) {
+  for (size_t s = CHANNEL_ACCS / 2; s >= 1; s /= 2)
+    for (size_t j = 0; j < s; ++j) a[j] = a[j] + a[j + s];
+  return a[0];
+}
+
+/* Eq. 1.  is_out[h] = 1 for an outlier channel.  stats (may be NULL) receives mu, sigma. */
+void oracle_channel_select(const double *S, size_t hidden, float z_thresh, uint8_t *is_out, double *stats) {
+  double a[CHANNEL_ACCS];
+  size_t finite = 0;
+  for (size_t j = 0; j < CHANNEL_ACCS; ++j) a[j] = 0.0;
+  for (size_t h = 0; h < hidden; ++h)
+    if (isfinite(S[h])) {
+      a[h % CHANNEL_ACCS] = a[h % CHANNEL_ACCS] + S[h];
+      ++finite;
+    }
+  const double mu = fold_accumulators(a) / (double)finite;
+  for (size_t j = 0; j < CHANNEL_ACCS; ++j) a[j] = 0.0;
+  for (size_t h = 0; h < hidden; ++h)
+    if (isfinite(S[h])) {
+      const double d = S[h] - mu;
+      a[h % CHANNEL_ACCS] = fma(d, d, a[h % CHANNEL_ACCS]);
+    }
+  const double sigma = sqrt(fold_accumulators(a) / (double)finite);
+  for (size_t h = 0; h < hidden; ++h) {
+    const double z = (S[h] - mu) / sigma;
+    is_out[h] = !isfinite(S[h]) || z > (double)z_thresh; /* a NaN z selects nothing */
+  }
+  if (stats) {
+    stats[0] = mu;
+    stats[1] = sigma;
+  }
+}
+
+static int channel_method_ok(const oracle_method *m, size_t tokens, size_t hidden) {
+  if (hidden == 0 || m->outlier_mode != ORACLE_OUT_NONE) return 0;
+  return method_ok(m, tokens * hidden);
+}
+
+/* Compression with outlier channels.  Outputs as oracle_compress, except for the outliers:
+ *   ch_idx [cap]            the outlier channels, ascending (at most cap are written)
+ *   ch_val [tokens * n_ch]  their values, token by token: ch_val[t * n_ch + r] is channel ch_idx[r]
+ *                           of token t, the original bf16 bit pattern
+ *   n_ch                    the number of outlier channels
+ * If n_ch exceeds cap only ch_idx and n_ch are produced. */
+int oracle_channel_compress(const oracle_method *m, const uint16_t *x, size_t tokens, size_t hidden,
+                            float z_thresh, int8_t *codes, uint8_t *packed, float *scale, float *zp,
+                            int32_t *ch_idx, uint16_t *ch_val, size_t cap, size_t *n_ch) {
+  if (!channel_method_ok(m, tokens, hidden)) return -1;
+  if (m->asym && !zp) return -1;
+  const size_t n = tokens * hidden;
+  double *S = (double *)malloc(hidden * sizeof(double));
+  uint8_t *is_out = (uint8_t *)malloc(hidden);
+  oracle_channel_scores(x, tokens, hidden, S);
+  oracle_channel_select(S, hidden, z_thresh, is_out, NULL);
+  size_t cnt = 0;
+  for (size_t h = 0; h < hidden; ++h)
+    if (is_out[h]) {
+      if (cnt < cap) ch_idx[cnt] = (int32_t)h;
+      ++cnt;
+    }
+  if (n_ch) *n_ch = cnt;
+  if (cnt <= cap) {
+    /* the outlier channels are kept as they are ... */
+    for (size_t t = 0; t < tokens; ++t)
+      for (size_t r = 0; r < cnt; ++r) ch_val[t * cnt + r] = x[t * hidden + (size_t)ch_idx[r]];
+    /* ... and count as zero when the rest is quantised */
+    uint8_t *out = (uint8_t *)malloc(n ? n : 1);
+    for (size_t i = 0; i < n; ++i) out[i] = is_out[i % hidden];
+    quantise_rest(m, x, out, n, codes, packed, scale, zp);
+    free(out);
+  }
+  free(S);
+  free(is_out);
+  return 0;
+}
+
+/* Dequantise, then put the outlier channels back. */
+int oracle_channel_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, const float *zp,
+                              const int32_t *ch_idx, const uint16_t *ch_val, size_t n_ch, size_t tokens,
+                              size_t hidden, float *xhat_f32, uint16_t *xhat_bf16) {
+  if (!channel_method_ok(m, tokens, hidden)) return -1;
+  if (m->asym && !zp) return -1;
+  dequantise_all(m, packed, scale, zp, tokens * hidden, xhat_f32, xhat_bf16);
+  for (size_t t = 0; t < tokens; ++t)
+    for (size_t r = 0; r < n_ch; ++r) {
+      const size_t h = (size_t)ch_idx[r];
+      if (h >= hidden) return -1;
+      if (xhat_f32) xhat_f32[t * hidden + h] = bf16_to_f32(ch_val[t * n_ch + r]);
+      if (xhat_bf16) xhat_bf16[t * hidden + h] = ch_val[t * n_ch + r];
+    }
+  return 0;
 }

@@ -71,6 +71,30 @@ uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out);
 /* Canonical pairwise sum (exposed so tests can pin it on its own). */
 float oracle_pairwise_sum(const float *v, size_t n);
 
+/* ---- outlier channels (Section 3.2, Eq. 1) ----
+ * x is a row-major matrix of `tokens` rows and `hidden` channels.  The order of every sum is part
+ * of the definition and is written out in adacc_oracle.c. */
+
+/* S_h = sum over the tokens of |x|, for every channel. */
+void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S);
+
+/* Eq. 1: is_out[h] = 1 where Z_h = (S_h - mu) / sigma exceeds z_thresh (or S_h is not finite).
+ * stats (may be NULL) receives mu and sigma. */
+void oracle_channel_select(const double *S, size_t hidden, float z_thresh, uint8_t *is_out, double *stats);
+
+/* Compression with whole outlier channels; m->outlier_mode must be ORACLE_OUT_NONE.
+ *   ch_idx [cap]            the outlier channels, ascending (at most cap are written)
+ *   ch_val [tokens * n_ch]  ch_val[t * n_ch + r] = channel ch_idx[r] of token t (bf16 bits)
+ * codes, packed, scale, zp as oracle_compress, with the outlier channels counted as zero.
+ * If *n_ch exceeds cap only ch_idx and *n_ch are produced. */
+int oracle_channel_compress(const oracle_method *m, const uint16_t *x, size_t tokens, size_t hidden,
+                            float z_thresh, int8_t *codes, uint8_t *packed, float *scale, float *zp,
+                            int32_t *ch_idx, uint16_t *ch_val, size_t cap, size_t *n_ch);
+
+int oracle_channel_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, const float *zp,
+                              const int32_t *ch_idx, const uint16_t *ch_val, size_t n_ch, size_t tokens,
+                              size_t hidden, float *xhat_f32, uint16_t *xhat_bf16);
+
 #ifdef __cplusplus
 }
 #endif

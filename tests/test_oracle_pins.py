@@ -452,3 +452,119 @@ def test_malformed_methods_are_rejected():
               Method(bits=8, quant_group=64, outlier_mode=OUT_TOPK, stat_group=64, topk=0)):
         with pytest.raises(ValueError):
             oracle.compress(m, x)
+
+
+# ----------------------------------------------------------------- outlier channels (Section 3.2, Eq. 1)
+def _planted(tokens, hidden, channels, seed, gain=50.0):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(tokens, hidden, generator=g)
+    x[:, channels] *= gain
+    return bf16_bits(x.numpy()).reshape(tokens, hidden)
+
+
+def test_channel_scores_are_exact_integer_sums_on_small_integers():
+    """Small integers add up without rounding in any order and precision: S_h must be the integer
+    column sum of |x| - over the tokens (axis 0), not the channels - also with a ragged last chunk."""
+    rng = np.random.default_rng(11)
+    for tokens, hidden in ((1, 8), (64, 8), (65, 24), (200, 24), (333, 7)):
+        xi = rng.integers(-8, 9, size=(tokens, hidden))
+        S = oracle.channel_scores(bf16_bits(xi.astype(np.float32)), tokens, hidden)
+        assert np.array_equal(S, np.abs(xi).sum(axis=0).astype(np.float64))
+
+
+def test_channel_scores_agree_with_the_exactly_rounded_sum():
+    """Against math.fsum (exact sum, rounded once): the defined order of additions may only cost the
+    rounding of 64-term binary32 partial sums."""
+    tokens, hidden = 1000, 40
+    xb = _planted(tokens, hidden, [3], seed=12)
+    S = oracle.channel_scores(xb, tokens, hidden)
+    xf = np.abs(bits_to_f32(xb.reshape(-1)).reshape(tokens, hidden)).astype(np.float64)
+    for h in range(hidden):
+        exact = math.fsum(xf[:, h])
+        assert abs(S[h] - exact) <= 64 * 2.0 ** -24 * exact
+
+
+def test_channel_selection_is_the_z_score_rule():
+    """Against numpy's mean / population std: Z = (S - mu) / sigma > threshold."""
+    rng = np.random.default_rng(13)
+    for hidden, thr in ((11, 3.0), (256, 3.0), (1000, 2.0), (4096, 3.0), (777, 1.0)):
+        S = rng.gamma(50.0, 1.0, size=hidden)
+        S[rng.integers(0, hidden, size=max(1, hidden // 100))] *= 3.0
+        z = (S - S.mean()) / S.std()
+        assert np.all(np.abs(z - thr) > 1e-9)  # no decision rests on the last bits
+        got, mu, sigma = oracle.channel_select(S, thr)
+        assert np.array_equal(got.astype(bool), z > thr)
+        assert math.isclose(mu, S.mean(), rel_tol=1e-12) and math.isclose(sigma, S.std(), rel_tol=1e-12)
+
+
+def test_one_deviating_channel_scores_sqrt_of_hidden_minus_one():
+    """Closed form: if all channels but one are alike, that one has Z = sqrt(hidden - 1).  So with the
+    paper's threshold of 3 it is selected for hidden = 11 (Z = 3.16) and not for hidden = 9 (2.83),
+    and no tensor with at most 9 channels can have an outlier channel at all."""
+    for hidden, want in ((9, 0), (11, 1), (64, 1)):
+        S = np.full(hidden, 7.0)
+        S[hidden // 2] = 9.5
+        got, _, _ = oracle.channel_select(S, 3.0)
+        assert got.sum() == want and (want == 0 or got[hidden // 2] == 1)
+    rng = np.random.default_rng(14)
+    for _ in range(200):
+        hidden = int(rng.integers(1, 10))
+        got, _, _ = oracle.channel_select(rng.lognormal(0.0, 3.0, size=hidden), 3.0)
+        assert got.sum() == 0
+
+
+def test_channel_selection_degenerate_cases():
+    got, mu, sigma = oracle.channel_select(np.full(32, 5.0), 3.0)  # sigma = 0: nothing stands out
+    assert got.sum() == 0 and mu == 5.0 and sigma == 0.0
+    S = np.full(32, 5.0)
+    S[4] = np.inf  # a channel that cannot be summed is kept whole and stays out of the statistics
+    got, mu, sigma = oracle.channel_select(S, 3.0)
+    assert list(np.nonzero(got)[0]) == [4] and mu == 5.0 and sigma == 0.0
+    S[7] = 1e6
+    got, mu, sigma = oracle.channel_select(S, 3.0)
+    assert list(np.nonzero(got)[0]) == [4, 7]
+
+
+@pytest.mark.parametrize("bits,asym", [(4, 0), (8, 0), (4, 1), (8, 1)])
+def test_channel_compression_keeps_channels_whole_and_quantises_the_rest(bits, asym):
+    """Structure of Section 3.2: the outlier channels and their indices are kept uncompressed, they
+    are zero in what gets quantised (so the rest equals plain group quantisation, pinned above, of
+    the tensor with those channels cleared), and decompression puts them back bit for bit."""
+    tokens, hidden, planted = 130, 64, [5, 40]
+    xb = _planted(tokens, hidden, planted, seed=15)
+    m = Method(bits=bits, quant_group=32, asym=asym)
+    c = oracle.channel_compress(m, xb, tokens, hidden, 3.0)
+    assert c.n_ch == 2 and list(c.ch_idx) == planted
+    assert np.array_equal(c.ch_val, xb[:, planted])
+    cleared = xb.copy()
+    cleared[:, planted] = 0
+    plain = oracle.compress(m, cleared)
+    assert np.array_equal(c.packed, plain.packed) and np.array_equal(c.codes, plain.codes)
+    assert np.array_equal(c.scale.view(np.uint32), plain.scale.view(np.uint32))
+    assert np.array_equal(c.zp.view(np.uint32), plain.zp.view(np.uint32))
+    f, b = oracle.channel_decompress(c)
+    pf, pb = oracle.decompress(plain)
+    f, b, pf, pb = (a.reshape(tokens, hidden) for a in (f, b, pf, pb))
+    rest = np.setdiff1d(np.arange(hidden), planted)
+    assert np.array_equal(b[:, planted], xb[:, planted])
+    assert np.array_equal(f[:, planted], bits_to_f32(xb[:, planted].reshape(-1)).reshape(tokens, 2))
+    assert np.array_equal(b[:, rest], pb[:, rest]) and np.array_equal(f[:, rest].view(np.uint32), pf[:, rest].view(np.uint32))
+
+
+def test_channel_compression_reports_more_channels_than_fit():
+    tokens, hidden = 70, 64
+    xb = _planted(tokens, hidden, [5, 40], seed=16)
+    c = oracle.channel_compress(Method(bits=8, quant_group=32), xb, tokens, hidden, 3.0, cap=1)
+    assert c.n_ch == 2 and list(c.ch_idx) == [5]
+
+
+def test_no_outlier_channel_means_plain_quantisation():
+    tokens, hidden = 64, 128
+    rng = np.random.default_rng(17)  # every channel has the same magnitudes in another order: all S_h alike
+    mags = np.stack([rng.permutation(np.arange(1, tokens + 1)) for _ in range(hidden)], axis=1)
+    xb = bf16_bits((mags * rng.choice([-0.25, 0.25], size=(tokens, hidden))).astype(np.float32))
+    m = Method(bits=4, quant_group=64)
+    c = oracle.channel_compress(m, xb, tokens, hidden, 3.0)
+    plain = oracle.compress(m, xb)
+    assert c.n_ch == 0 and np.array_equal(c.packed, plain.packed)
+    assert np.array_equal(c.scale.view(np.uint32), plain.scale.view(np.uint32))
