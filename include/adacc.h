@@ -12,8 +12,9 @@
  * The paper quantises FP16 to INT4 and picks whole outlier channels; this
  * library takes bf16, b in {4, 8}, and picks single elements by one of three
  * rules (absolute threshold, multiple of the group's standard deviation, k
- * largest magnitudes).  All arithmetic is binary32 in a fixed order, so a
- * compressed tensor is a pure function of the input bits.
+ * largest magnitudes); the paper's own rule, whole channels by Z-score (Eq. 1),
+ * is served by the adacc_channel_* calls.  All arithmetic has a fixed precision
+ * and order, so a compressed tensor is a pure function of the input bits.
  *
  * Conventions
  *   - Every pointer named src/dst/blob/workspace is DEVICE memory owned by the
@@ -160,6 +161,63 @@ int adacc_decompress_batch(uint32_t n, const adacc_method *methods, const void *
  * the only call that synchronises.  (The outlier count is what the policy
  * evolution of Section 3.4 tracks.) */
 int adacc_read_status(const void *blob, const adacc_layout *layout, void *hip_stream, uint32_t status_out[4]);
+
+/* ---- outlier channels: the selection rule of Section 3.2, Eq. 1 ----
+ * The tensor is a row-major matrix of `tokens` rows and `hidden` channels.  S_h is the sum of |x|
+ * over the tokens of channel h, mu and sigma are mean and (population) standard deviation of S_h
+ * over the channels, Z_h = (S_h - mu) / sigma.  Channels with Z_h > z_thresh (3 in the paper), and
+ * channels whose sum is not finite (they take no part in mu and sigma), are kept whole and
+ * uncompressed together with their indices, count as zero in the activation, and everything else
+ * is group-quantised in memory order exactly as with ADACC_OUTLIER_NONE (Eq. 2 / Eq. 3).
+ * The order of the sums is fixed (binary32 over chunks of 64 tokens, binary64 over the chunks in
+ * order, 256 interleaved binary64 accumulators folded by halves over the channels), so the blob is
+ * a pure function of the input bits.
+ * Limits: hidden a multiple of 8 in [8, 65536]; tokens * hidden < 2^32; quant_group a power of two
+ * in [8, 2048] dividing tokens * hidden; 1 <= max_channels <= hidden. */
+typedef struct adacc_channel_method {
+  uint32_t bits;         /* 4 or 8                                                    */
+  uint32_t quant_group;  /* Gq                                                        */
+  uint32_t asym;         /* 0: Eq. 2, 1: Eq. 3                                        */
+  uint32_t scale_rule;   /* ADACC_SCALE_*                                             */
+  float z_thresh;        /* threshold on Z (finite)                                   */
+  uint32_t max_channels; /* outlier channels the blob has room for                    */
+} adacc_channel_method;
+
+/* Blob sections (each on a 256-byte boundary):
+ *   codes, scales, zp   as in adacc_layout
+ *   ch_mask  hidden/8 bytes: bit (h & 7) of byte h >> 3 is set for an outlier channel
+ *   ch_base  hidden/8 uint32: number of outlier channels below channel 8 * (h >> 3)
+ *   ch_idx   max_channels int32: the outlier channels, ascending
+ *   ch_val   room for tokens * max_channels bf16; used as [tokens][n_ch]: ch_val[t * n_ch + r] is
+ *            channel ch_idx[r] of token t, bit for bit
+ *   status   4 uint32: [0] n_ch, the number of outlier channels found, [1] 1 if n_ch exceeds
+ *            max_channels (then only ch_mask, ch_base, the first max_channels entries of ch_idx
+ *            and status are produced and the blob cannot be decompressed), [2], [3] 0. */
+typedef struct adacc_channel_layout {
+  uint64_t codes_off, scales_off, zp_off, ch_mask_off, ch_base_off, ch_idx_off, ch_val_off, status_off;
+  uint64_t total_bytes;
+} adacc_channel_layout;
+
+/* Host only, pure.  Errors: ENULL, EINVAL. */
+int adacc_channel_layout_of(const adacc_channel_method *method, uint64_t tokens, uint32_t hidden,
+                            adacc_channel_layout *out);
+/* Device bytes adacc_channel_compress needs as scratch space (chunk sums and S_h); 0 if the
+ * sizes are not valid.  Any 256-byte aligned device buffer of that size; no initialisation, may be
+ * shared by calls that follow each other on one stream. */
+uint64_t adacc_channel_workspace_bytes(uint64_t tokens, uint32_t hidden);
+/* Enqueues the four kernels: chunk sums, channel sums, Eq. 1 selection, quantisation of the rest
+ * with extraction of the outlier channels.  src: tokens*hidden bf16, 16-byte aligned, not modified.
+ * tokens == 0: ADACC_OK, nothing is touched.  Errors: ENULL, EINVAL, ESIZE, EALIGN, EHIP. */
+int adacc_channel_compress(const adacc_channel_method *method, const void *src, uint64_t tokens, uint32_t hidden,
+                           void *blob, uint64_t blob_bytes, void *workspace, uint64_t workspace_bytes,
+                           void *hip_stream);
+/* Dequantisation followed by the write-back of the outlier channels (Fig. 3(c) decompression
+ * workflow).  dst as in adacc_decompress.  A blob whose status[1] is set leaves dst untouched. */
+int adacc_channel_decompress(const adacc_channel_method *method, const void *blob, uint64_t blob_bytes,
+                             uint64_t tokens, uint32_t hidden, void *dst, int dst_dtype, void *hip_stream);
+/* As adacc_read_status, for a blob of this kind. */
+int adacc_channel_read_status(const void *blob, const adacc_channel_layout *layout, void *hip_stream,
+                              uint32_t status_out[4]);
 
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst: the practical HBM
  * ceiling the compression kernels are measured against, and the calibration

@@ -22,7 +22,8 @@ DST_BF16, DST_F32 = 0, 1
 EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "adacc_compress",
            "adacc_decompress", "adacc_batch_workspace_bytes", "adacc_compress_batch",
            "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
-           "adacc_version")
+           "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
+           "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status")
 
 
 class CMethod(ctypes.Structure):
@@ -42,6 +43,31 @@ class CLayout(ctypes.Structure):
 class CWorkspace(ctypes.Structure):
     _fields_ = [("device_mem", ctypes.c_void_p), ("bytes", ctypes.c_uint64), ("epoch", ctypes.c_uint32),
                 ("reserved", ctypes.c_uint32)]
+
+
+class CChannelMethod(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_uint32), ("quant_group", ctypes.c_uint32), ("asym", ctypes.c_uint32),
+                ("scale_rule", ctypes.c_uint32), ("z_thresh", ctypes.c_float), ("max_channels", ctypes.c_uint32)]
+
+
+class CChannelLayout(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_uint64) for k in ("codes_off", "scales_off", "zp_off", "ch_mask_off", "ch_base_off",
+                                                "ch_idx_off", "ch_val_off", "status_off", "total_bytes")]
+
+
+@dataclass
+class ChannelMethod:
+    """Outlier channels by Z-score (adacc_channel_method)."""
+    bits: int = 4
+    quant_group: int = 128
+    asym: int = 0
+    scale_rule: int = SCALE_PAPER
+    z_thresh: float = 3.0
+    max_channels: int = 64
+
+    def c(self) -> CChannelMethod:
+        return CChannelMethod(self.bits, self.quant_group, self.asym, self.scale_rule, float(self.z_thresh),
+                              self.max_channels)
 
 
 @dataclass
@@ -108,6 +134,17 @@ def lib():
         L.adacc_hbm_copy.restype = ci
         L.adacc_strerror.argtypes = [ci]
         L.adacc_strerror.restype = ctypes.c_char_p
+        pcm, pcl = ctypes.POINTER(CChannelMethod), ctypes.POINTER(CChannelLayout)
+        L.adacc_channel_layout_of.argtypes = [pcm, u64, u32, pcl]
+        L.adacc_channel_layout_of.restype = ci
+        L.adacc_channel_workspace_bytes.argtypes = [u64, u32]
+        L.adacc_channel_workspace_bytes.restype = u64
+        L.adacc_channel_compress.argtypes = [pcm, vp, u64, u32, vp, u64, vp, u64, vp]
+        L.adacc_channel_compress.restype = ci
+        L.adacc_channel_decompress.argtypes = [pcm, vp, u64, u64, u32, vp, ci, vp]
+        L.adacc_channel_decompress.restype = ci
+        L.adacc_channel_read_status.argtypes = [vp, pcl, vp, ctypes.POINTER(u32 * 4)]
+        L.adacc_channel_read_status.restype = ci
         L.adacc_version.argtypes = []
         L.adacc_version.restype = ctypes.c_char_p
         _lib = L
@@ -261,6 +298,78 @@ def read_status(blob, layout: CLayout, stream=None):
 def hbm_copy(dst, src, nbytes=None, stream=None):
     nbytes = _nbytes(src) if nbytes is None else nbytes
     _check(lib().adacc_hbm_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "adacc_hbm_copy")
+
+
+# ---------------------------------------------------------------- outlier channels (Section 3.2, Eq. 1)
+def channel_layout_of(method: ChannelMethod, tokens: int, hidden: int) -> CChannelLayout:
+    L = CChannelLayout()
+    cm = method.c()
+    _check(lib().adacc_channel_layout_of(ctypes.byref(cm), tokens, hidden, ctypes.byref(L)),
+           "adacc_channel_layout_of")
+    return L
+
+
+def channel_workspace_bytes(tokens: int, hidden: int) -> int:
+    return int(lib().adacc_channel_workspace_bytes(tokens, hidden))
+
+
+def channel_compress(method: ChannelMethod, src, tokens: int, hidden: int, blob, workspace, stream=None):
+    cm = method.c()
+    _check(lib().adacc_channel_compress(ctypes.byref(cm), _ptr(src), tokens, hidden, _ptr(blob), _nbytes(blob),
+                                        _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "adacc_channel_compress")
+
+
+def channel_decompress(method: ChannelMethod, blob, tokens: int, hidden: int, dst, stream=None):
+    import torch
+    if dst.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("dst must be bfloat16 or float32")
+    dtype = DST_F32 if dst.dtype == torch.float32 else DST_BF16
+    cm = method.c()
+    _check(lib().adacc_channel_decompress(ctypes.byref(cm), _ptr(blob), _nbytes(blob), tokens, hidden, _ptr(dst),
+                                          dtype, _stream(stream)), "adacc_channel_decompress")
+
+
+def channel_read_status(blob, layout: CChannelLayout, stream=None):
+    """(n_channels, overflow, 0, 0) - waits for the stream."""
+    out = (ctypes.c_uint32 * 4)()
+    _check(lib().adacc_channel_read_status(_ptr(blob), ctypes.byref(layout), _stream(stream), ctypes.byref(out)),
+           "adacc_channel_read_status")
+    return tuple(int(v) for v in out)
+
+
+def alloc_channel_blob(method: ChannelMethod, tokens: int, hidden: int, device="cuda"):
+    import torch
+    L = channel_layout_of(method, tokens, hidden)
+    return torch.empty(int(L.total_bytes), dtype=torch.uint8, device=device), L
+
+
+def alloc_channel_workspace(tokens: int, hidden: int, device="cuda"):
+    import torch
+    return torch.empty(max(channel_workspace_bytes(tokens, hidden), 256), dtype=torch.uint8, device=device)
+
+
+def channel_blob_sections(blob, layout: CChannelLayout, method: ChannelMethod, tokens: int, hidden: int):
+    """Typed views of the sections of a channel blob (no copies)."""
+    import torch
+    numel = tokens * hidden
+    groups = numel // method.quant_group
+
+    def view(off, nbytes, dtype):
+        return blob[off:off + nbytes].view(dtype)
+
+    sec = {
+        "codes": view(layout.codes_off, numel * method.bits // 8, torch.uint8),
+        "scales": view(layout.scales_off, 4 * groups, torch.float32),
+        "ch_mask": view(layout.ch_mask_off, hidden // 8, torch.uint8),
+        "ch_base": view(layout.ch_base_off, 4 * (hidden // 8), torch.int32),
+        "ch_idx": view(layout.ch_idx_off, 4 * method.max_channels, torch.int32),
+        "ch_val": view(layout.ch_val_off, 2 * tokens * method.max_channels, torch.int16),
+        "status": view(layout.status_off, 16, torch.int32),
+    }
+    if method.asym:
+        sec["zp"] = view(layout.zp_off, 4 * groups, torch.float32)
+    return sec
 
 
 # ---------------------------------------------------------------- buffer helpers (allocation = plumbing)

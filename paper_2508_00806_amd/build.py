@@ -13,9 +13,10 @@ SOURCES = [os.path.join(CSRC, f) for f in (
     "adacc_k_none.hip", "adacc_k_abs.hip", "adacc_k_std.hip", "adacc_k_topk.hip",  # compress, per outlier mode
     "adacc_k_decompress.hip",
     "adacc_k_batch4.hip", "adacc_k_batch8.hip",
+    "adacc_k_channel.hip",    # outlier channels by Z-score
 )]
 HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_compress.hpp", "adacc_decompress.hpp",
-                                           "adacc_kernels.hpp", "adacc_fn.hpp")]
+                                           "adacc_kernels.hpp", "adacc_fn.hpp", "adacc_channel.hpp")]
 HEADERS.append(os.path.join(ROOT, "include", "adacc.h"))
 OBJDIR = os.path.join(HERE, "_build")
 

@@ -323,6 +323,67 @@ static BatchPlan batch_plan(uint32_t total_tiles, uint32_t n_active) {
   return b;
 }
 
+// ---- outlier channels (Section 3.2, Eq. 1)
+struct ChannelPlan {
+  adacc_method quant;  // the quantisation of the rest: the same method without outliers
+  Plan plan;
+  adacc_layout quant_layout;
+  uint64_t numel;
+  uint32_t n_chunks;
+};
+
+static int make_channel_plan(const adacc_channel_method* m, uint64_t tokens, uint32_t hidden, ChannelPlan* cp) {
+  std::memset(cp, 0, sizeof *cp);
+  if (hidden < 8 || hidden > 65536 || hidden % 8 != 0) return ADACC_EINVAL;
+  if (tokens > 0xFFFFFFFFull / hidden) return ADACC_EINVAL;  // tokens * hidden < 2^32
+  if (m->quant_group > 2048) return ADACC_EINVAL;
+  if (m->max_channels < 1 || m->max_channels > hidden) return ADACC_EINVAL;
+  if (!std::isfinite(m->z_thresh)) return ADACC_EINVAL;
+  cp->quant.kind = ADACC_KIND_QUANT;
+  cp->quant.bits = m->bits;
+  cp->quant.quant_group = m->quant_group;
+  cp->quant.asym = m->asym;
+  cp->quant.scale_rule = m->scale_rule;
+  cp->quant.outlier_mode = ADACC_OUTLIER_NONE;
+  cp->numel = tokens * hidden;
+  const int rc = make_plan(&cp->quant, cp->numel, &cp->plan);
+  if (rc != ADACC_OK) return rc;
+  fill_layout(&cp->quant, cp->numel, cp->plan, &cp->quant_layout);
+  cp->n_chunks = (uint32_t)((tokens + kChunkTokens - 1) / kChunkTokens);
+  return ADACC_OK;
+}
+
+static void fill_channel_layout(const adacc_channel_method* m, uint64_t tokens, uint32_t hidden, const ChannelPlan& cp,
+                                adacc_channel_layout* L) {
+  std::memset(L, 0, sizeof *L);
+  L->codes_off = cp.quant_layout.codes_off;
+  L->scales_off = cp.quant_layout.scales_off;
+  L->zp_off = cp.quant_layout.zp_off;
+  uint64_t off = cp.quant_layout.status_off;  // the sections of this mode start where the plain blob's status would be
+  L->ch_mask_off = off;  off = align256(off + hidden / 8);
+  L->ch_base_off = off;  off = align256(off + 4ull * (hidden / 8));
+  L->ch_idx_off = off;   off = align256(off + 4ull * m->max_channels);
+  L->ch_val_off = off;   off = align256(off + 2ull * tokens * m->max_channels);
+  L->status_off = off;   off = align256(off + 16);
+  L->total_bytes = off;
+}
+
+static uint64_t channel_partial_bytes(uint32_t n_chunks, uint32_t hidden) { return align256(4ull * n_chunks * hidden); }
+
+static void fill_channel_desc(const adacc_channel_method* m, uint64_t tokens, uint32_t hidden,
+                              const adacc_channel_layout& L, void* blob, ChannelDesc* c) {
+  unsigned char* b = static_cast<unsigned char*>(blob);
+  c->mask = b + L.ch_mask_off;
+  c->base = reinterpret_cast<uint32_t*>(b + L.ch_base_off);
+  c->ch_idx = reinterpret_cast<int32_t*>(b + L.ch_idx_off);
+  c->ch_val = reinterpret_cast<uint16_t*>(b + L.ch_val_off);
+  c->status = reinterpret_cast<uint32_t*>(b + L.status_off);
+  c->hidden = hidden;
+  c->tokens = (uint32_t)tokens;
+  c->max_channels = m->max_channels;
+  c->z_thresh = m->z_thresh;
+}
+
 }  // namespace adacc
 
 using namespace adacc;
@@ -582,6 +643,103 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
 int adacc_read_status(const void* blob, const adacc_layout* layout, void* hip_stream, uint32_t status_out[4]) {
   if (!blob || !layout || !status_out) return ADACC_ENULL;
   if (layout->total_bytes == 0) { status_out[0] = status_out[1] = status_out[2] = status_out[3] = 0; return ADACC_OK; }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipMemcpyAsync(status_out, static_cast<const unsigned char*>(blob) + layout->status_off, 16,
+                                hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(status)");
+  e = hipStreamSynchronize(s);
+  return e == hipSuccess ? ADACC_OK : hip_fail(e, "hipStreamSynchronize");
+}
+
+int adacc_channel_layout_of(const adacc_channel_method* method, uint64_t tokens, uint32_t hidden,
+                            adacc_channel_layout* out) {
+  if (!method || !out) return ADACC_ENULL;
+  ChannelPlan cp;
+  const int rc = make_channel_plan(method, tokens, hidden, &cp);
+  if (rc != ADACC_OK) return rc;
+  fill_channel_layout(method, tokens, hidden, cp, out);
+  return ADACC_OK;
+}
+
+uint64_t adacc_channel_workspace_bytes(uint64_t tokens, uint32_t hidden) {
+  if (hidden < 8 || hidden > 65536 || hidden % 8 != 0 || tokens > 0xFFFFFFFFull / hidden) return 0;
+  const uint32_t n_chunks = (uint32_t)((tokens + kChunkTokens - 1) / kChunkTokens);
+  return channel_partial_bytes(n_chunks, hidden) + align256(8ull * hidden);
+}
+
+int adacc_channel_compress(const adacc_channel_method* method, const void* src, uint64_t tokens, uint32_t hidden,
+                           void* blob, uint64_t blob_bytes, void* workspace, uint64_t workspace_bytes,
+                           void* hip_stream) {
+  if (!method) return ADACC_ENULL;
+  ChannelPlan cp;
+  int rc = make_channel_plan(method, tokens, hidden, &cp);
+  if (rc != ADACC_OK) return rc;
+  if (tokens == 0) return ADACC_OK;
+  if (!src || !blob || !workspace) return ADACC_ENULL;
+  adacc_channel_layout L;
+  fill_channel_layout(method, tokens, hidden, cp, &L);
+  if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
+  if (workspace_bytes < adacc_channel_workspace_bytes(tokens, hidden)) return ADACC_ESIZE;
+  if (misaligned(src, 16) || misaligned(blob, 256) || misaligned(workspace, 256)) return ADACC_EALIGN;
+  TensorDesc d;
+  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, src, blob, nullptr, 0, 0, 1u, 0, 0, &d);
+  ChannelDesc c;
+  fill_channel_desc(method, tokens, hidden, L, blob, &c);
+  float* partial = static_cast<float*>(workspace);
+  double* S = reinterpret_cast<double*>(static_cast<unsigned char*>(workspace) + channel_partial_bytes(cp.n_chunks, hidden));
+  ChannelFn fn = channel_compress_fn(method->bits, method->asym, cp.plan.rowwise);
+  uint32_t grid = 0;
+  rc = grid_for(cp.plan.n_tiles, reinterpret_cast<const void*>(fn), 2u, &grid);
+  if (rc != ADACC_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  const uint32_t n_items = cp.n_chunks * (hidden / 8);  // one lane: 8 channels of one chunk
+  hipLaunchKernelGGL(channel_partial_fn(), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+                     static_cast<const uint16_t*>(src), (uint32_t)tokens, hidden, partial, n_items);
+  rc = launch_check("channel_partial_kernel");
+  if (rc != ADACC_OK) return rc;
+  const uint32_t per_wg = channel_score_channels();
+  hipLaunchKernelGGL(channel_score_fn(), dim3((hidden + per_wg - 1) / per_wg), dim3(kThreads), 0, s,
+                     static_cast<const float*>(partial), cp.n_chunks, hidden, S);
+  rc = launch_check("channel_score_kernel");
+  if (rc != ADACC_OK) return rc;
+  hipLaunchKernelGGL(channel_select_fn(), dim3(1), dim3(256), 0, s, static_cast<const double*>(S), c);
+  rc = launch_check("channel_select_kernel");
+  if (rc != ADACC_OK) return rc;
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, c);
+  return launch_check("channel_compress_kernel");
+}
+
+int adacc_channel_decompress(const adacc_channel_method* method, const void* blob, uint64_t blob_bytes,
+                             uint64_t tokens, uint32_t hidden, void* dst, int dst_dtype, void* hip_stream) {
+  if (!method) return ADACC_ENULL;
+  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  ChannelPlan cp;
+  int rc = make_channel_plan(method, tokens, hidden, &cp);
+  if (rc != ADACC_OK) return rc;
+  if (tokens == 0) return ADACC_OK;
+  if (!blob || !dst) return ADACC_ENULL;
+  adacc_channel_layout L;
+  fill_channel_layout(method, tokens, hidden, cp, &L);
+  if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
+  if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
+  TensorDesc d;
+  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0,
+            0, &d);
+  ChannelDesc c;
+  fill_channel_desc(method, tokens, hidden, L, const_cast<void*>(blob), &c);
+  ChannelFn fn = channel_decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
+  uint32_t grid = 0;
+  rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
+  if (rc != ADACC_OK) return rc;
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, c);
+  return launch_check("channel_decompress_kernel");
+}
+
+int adacc_channel_read_status(const void* blob, const adacc_channel_layout* layout, void* hip_stream,
+                              uint32_t status_out[4]) {
+  if (!blob || !layout || !status_out) return ADACC_ENULL;
+  if (layout->total_bytes == 0) return ADACC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipMemcpyAsync(status_out, static_cast<const unsigned char*>(blob) + layout->status_off, 16,
                                 hipMemcpyDeviceToHost, s);

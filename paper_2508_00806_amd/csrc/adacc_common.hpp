@@ -55,6 +55,20 @@ struct TensorDesc {
   uint32_t ptr_shift;   // decompress: works on pieces of 2048 elements; piece u belongs to tile u >> ptr_shift
 };
 
+// Outlier channels (Section 3.2, Eq. 1): what those kernels need beside the TensorDesc of the quantised part.
+constexpr uint32_t kChunkTokens = 64;  // tokens per binary32 partial sum of the channel statistics
+struct ChannelDesc {
+  uint8_t* mask;        // hidden/8 bytes: bit (h & 7) of byte h >> 3 is set for an outlier channel
+  uint32_t* base;       // hidden/8 words: number of outlier channels below channel 8 * (h >> 3)
+  int32_t* ch_idx;      // the outlier channels, ascending
+  uint16_t* ch_val;     // [tokens][n_ch] bf16 bit patterns
+  uint32_t* status;     // [0] n_ch, [1] 1 if n_ch > max_channels
+  uint32_t hidden;
+  uint32_t tokens;
+  uint32_t max_channels;
+  float z_thresh;
+};
+
 // Scan workspace: one 64-bit state word per run of tiles and one per block of 64 runs, high half
 // = (epoch << 2) | flag, low half = value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
 // words written by earlier launches carry another epoch and read as empty, so the buffer is

@@ -20,4 +20,16 @@ DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);
 BatchCompressFn compress_batch_fn(bool eight_rows);
 BatchDecompressFn decompress_batch_fn(bool f32);
 
+// outlier channels (Section 3.2, Eq. 1)
+typedef void (*ChannelPartialFn)(const uint16_t*, uint32_t, uint32_t, float*, uint32_t);
+typedef void (*ChannelScoreFn)(const float*, uint32_t, uint32_t, double*);
+typedef void (*ChannelSelectFn)(const double*, ChannelDesc);
+typedef void (*ChannelFn)(TensorDesc, ChannelDesc);
+ChannelPartialFn channel_partial_fn();
+ChannelScoreFn channel_score_fn();
+ChannelSelectFn channel_select_fn();
+uint32_t channel_score_channels();  // channels per workgroup of the score kernel
+ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);
+ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);
+
 }  // namespace adacc

@@ -177,3 +177,58 @@ def test_strerror_and_version(L):
     assert adacc.strerror(0) == "ok"
     assert "align" in adacc.strerror(adacc.EALIGN)
     assert re.match(r"^\d+\.\d+$", adacc.version())
+
+
+# ----------------------------------------------------------------- outlier channels
+def test_channel_layout_closed_form_and_limits(L):
+    assert ctypes.sizeof(adacc.CChannelMethod) == 24 and ctypes.sizeof(adacc.CChannelLayout) == 72
+    m = adacc.ChannelMethod(bits=4, quant_group=128, asym=1, max_channels=10)
+    tokens, hidden = 100, 2048
+    n = tokens * hidden
+    lay = adacc.channel_layout_of(m, tokens, hidden)
+    a = lambda v: (v + 255) // 256 * 256
+    assert lay.codes_off == 0 and lay.scales_off == a(n // 2)
+    assert lay.zp_off == lay.scales_off + a(4 * n // 128)
+    assert lay.ch_mask_off == lay.zp_off + a(4 * n // 128)
+    assert lay.ch_base_off == lay.ch_mask_off + a(hidden // 8)
+    assert lay.ch_idx_off == lay.ch_base_off + a(4 * hidden // 8)
+    assert lay.ch_val_off == lay.ch_idx_off + a(40)
+    assert lay.status_off == lay.ch_val_off + a(2 * tokens * 10)
+    assert lay.total_bytes == lay.status_off + 256
+    # chunk sums (one binary32 per chunk of 64 tokens and channel) + one binary64 per channel
+    assert adacc.channel_workspace_bytes(tokens, hidden) == a(4 * 2 * hidden) + a(8 * hidden)
+    for bad in (dict(hidden=2044), dict(hidden=0), dict(hidden=65544), dict(tokens=1 << 21),
+                dict(m=adacc.ChannelMethod(bits=4, quant_group=4096)), dict(m=adacc.ChannelMethod(bits=5)),
+                dict(m=adacc.ChannelMethod(max_channels=0)), dict(m=adacc.ChannelMethod(max_channels=4096)),
+                dict(m=adacc.ChannelMethod(z_thresh=float("inf")))):
+        args = dict(m=m, tokens=tokens, hidden=hidden)
+        args.update(bad)
+        with pytest.raises(adacc.AdaccError):
+            adacc.channel_layout_of(args["m"], args["tokens"], args["hidden"])
+    assert adacc.channel_workspace_bytes(100, 2044) == 0
+
+
+def test_channel_calls_validate_before_any_device_work(L):
+    m = adacc.ChannelMethod(bits=8, quant_group=64, max_channels=4)
+    cm = m.c()
+    tokens, hidden = 64, 256
+    lay = adacc.channel_layout_of(m, tokens, hidden)
+    wsb = adacc.channel_workspace_bytes(tokens, hidden)
+    src, blob, ws = 0x10000, 0x20000, 0x30000
+    f = L.adacc_channel_compress
+    r = ctypes.byref(cm)
+    assert f(None, src, tokens, hidden, blob, lay.total_bytes, ws, wsb, None) == adacc.ENULL
+    assert f(r, None, tokens, hidden, blob, lay.total_bytes, ws, wsb, None) == adacc.ENULL
+    assert f(r, src, tokens, hidden, None, lay.total_bytes, ws, wsb, None) == adacc.ENULL
+    assert f(r, src, tokens, hidden, blob, lay.total_bytes, None, wsb, None) == adacc.ENULL
+    assert f(r, src, tokens, hidden, blob, lay.total_bytes - 1, ws, wsb, None) == adacc.ESIZE
+    assert f(r, src, tokens, hidden, blob, lay.total_bytes, ws, wsb - 1, None) == adacc.ESIZE
+    assert f(r, src + 2, tokens, hidden, blob, lay.total_bytes, ws, wsb, None) == adacc.EALIGN
+    assert f(r, src, tokens, hidden, blob, lay.total_bytes, ws + 16, wsb, None) == adacc.EALIGN
+    assert f(r, src, tokens, 250, blob, lay.total_bytes, ws, wsb, None) == adacc.EINVAL
+    assert f(r, None, 0, hidden, None, 0, None, 0, None) == adacc.OK
+    g = L.adacc_channel_decompress
+    assert g(r, blob, lay.total_bytes, tokens, hidden, None, 0, None) == adacc.ENULL
+    assert g(r, blob, lay.total_bytes, tokens, hidden, 0x40000, 2, None) == adacc.EINVAL
+    assert g(r, blob, lay.total_bytes - 1, tokens, hidden, 0x40000, 0, None) == adacc.ESIZE
+    assert g(r, blob, lay.total_bytes, tokens, hidden, 0x40002, 0, None) == adacc.EALIGN
