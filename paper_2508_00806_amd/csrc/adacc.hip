@@ -368,6 +368,8 @@ static void fill_channel_layout(const adacc_channel_method* m, uint64_t tokens, 
   L->total_bytes = off;
 }
 
+static uint32_t channel_mask_lds(uint32_t hidden) { return (3u * (hidden / 8) + 15u) & ~15u; }  // LDS copy of mask and ranks
+
 static uint64_t channel_partial_bytes(uint32_t n_chunks, uint32_t hidden) { return align256(4ull * n_chunks * hidden); }
 
 static void fill_channel_desc(const adacc_channel_method* m, uint64_t tokens, uint32_t hidden,
@@ -382,6 +384,7 @@ static void fill_channel_desc(const adacc_channel_method* m, uint64_t tokens, ui
   c->tokens = (uint32_t)tokens;
   c->max_channels = m->max_channels;
   c->z_thresh = m->z_thresh;
+  c->inv_hidden = std::nextafter(std::nextafter(1.0f / (float)hidden, 0.0f), 0.0f);
 }
 
 }  // namespace adacc
@@ -706,7 +709,7 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
   hipLaunchKernelGGL(channel_select_fn(), dim3(1), dim3(256), 0, s, static_cast<const double*>(S), c);
   rc = launch_check("channel_select_kernel");
   if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, c);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), channel_mask_lds(hidden), s, d, c);
   return launch_check("channel_compress_kernel");
 }
 
@@ -732,7 +735,8 @@ int adacc_channel_decompress(const adacc_channel_method* method, const void* blo
   uint32_t grid = 0;
   rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
   if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, c);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), channel_mask_lds(hidden), static_cast<hipStream_t>(hip_stream), d,
+                     c);
   return launch_check("channel_decompress_kernel");
 }
 

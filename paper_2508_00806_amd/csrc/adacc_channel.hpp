@@ -135,9 +135,17 @@ __global__ __launch_bounds__(kSelectThreads) void channel_select_kernel(const do
 
   double acc = 0.0;
   uint32_t n = 0;
-  for (uint32_t h = j; h < hidden; h += kSelectThreads) {
-    const double s = S[h];
-    if (finite_f64(s)) { acc = __dadd_rn(acc, s); ++n; }
+  // four loads in flight per thread; a position past the end reads as +Inf and is skipped like
+  // any other sum that is not finite
+  constexpr uint32_t kAhead = 4;
+  const double skip = __longlong_as_double(0x7FF0000000000000ll);
+  for (uint32_t h = j; h < hidden; h += kAhead * kSelectThreads) {
+    double v[kAhead];
+#pragma unroll
+    for (uint32_t i = 0; i < kAhead; ++i) v[i] = h + i * kSelectThreads < hidden ? S[h + i * kSelectThreads] : skip;
+#pragma unroll
+    for (uint32_t i = 0; i < kAhead; ++i)
+      if (finite_f64(v[i])) { acc = __dadd_rn(acc, v[i]); ++n; }
   }
   const double total = fold_accumulators(acc, a);
   cnt[j] = n;
@@ -150,12 +158,16 @@ __global__ __launch_bounds__(kSelectThreads) void channel_select_kernel(const do
   const double mu = __ddiv_rn(total, finite);
 
   acc = 0.0;
-  for (uint32_t h = j; h < hidden; h += kSelectThreads) {
-    const double s = S[h];
-    if (finite_f64(s)) {
-      const double d = __dsub_rn(s, mu);
-      acc = __fma_rn(d, d, acc);
-    }
+  for (uint32_t h = j; h < hidden; h += kAhead * kSelectThreads) {
+    double v[kAhead];
+#pragma unroll
+    for (uint32_t i = 0; i < kAhead; ++i) v[i] = h + i * kSelectThreads < hidden ? S[h + i * kSelectThreads] : skip;
+#pragma unroll
+    for (uint32_t i = 0; i < kAhead; ++i)
+      if (finite_f64(v[i])) {
+        const double d = __dsub_rn(v[i], mu);
+        acc = __fma_rn(d, d, acc);
+      }
   }
   const double sigma = __dsqrt_rn(__ddiv_rn(fold_accumulators(acc, a), finite));
   const double zt = (double)c.z_thresh;
@@ -226,11 +238,38 @@ __device__ __forceinline__ ChannelGeo channel_geo(uint32_t tile, uint32_t hidden
   return g;
 }
 
+// off = q * hidden + col for off < hidden + 2048 <= 2^24 / 8: the quotient through a binary32 reciprocal
+// that the host rounded down, so the estimate is the true quotient or one less.
+__device__ __forceinline__ void split_offset(uint32_t off, uint32_t hidden, float inv_hidden, uint32_t& q,
+                                             uint32_t& col) {
+  q = (uint32_t)((float)off * inv_hidden);
+  col = off - __umul24(q, hidden);
+  if (col >= hidden) { col -= hidden; ++q; }
+}
+
+// The channel mask is consulted for every octet, the rank table for every octet with an outlier:
+// each workgroup keeps copies in LDS (ranks as 16 bits: they stay below 65536).
+struct ChannelLds {
+  const uint16_t* base;
+  const uint8_t* mask;
+};
+__device__ __forceinline__ ChannelLds stage_channels(const ChannelDesc& c, uint8_t* lds) {
+  const uint32_t n = c.hidden / 8u;
+  uint16_t* base = reinterpret_cast<uint16_t*>(lds);
+  uint8_t* mask = lds + 2u * n;
+  for (uint32_t i = threadIdx.x; i < n; i += kThreads) {
+    mask[i] = c.mask[i];
+    base[i] = (uint16_t)c.base[i];
+  }
+  __syncthreads();
+  return ChannelLds{base, mask};
+}
+
 // ---- step 4: the outlier channels of one tile are stored and zeroed, then the tile is encoded
 // like one of a tensor without outliers.
 template <int BITS, bool ASYM, bool ROWWISE, bool COMPLETE>
 __device__ __forceinline__ void channel_compress_tile(const TensorDesc& d, const ChannelDesc& c, uint32_t n_ch,
-                                                      uint32_t tile) {
+                                                      const ChannelLds& lds, uint32_t tile) {
   constexpr int E = 4;
   uint32_t raw[E][4];
   load_tile<E, COMPLETE>(d, tile, raw);
@@ -242,21 +281,25 @@ __device__ __forceinline__ void channel_compress_tile(const TensorDesc& d, const
     for (int j = 0; j < E; ++j) {
       const uint32_t in_tile = g.lane_off + (uint32_t)(j * kRow);
       if (!COMPLETE && in_tile >= g.rem) continue;
-      const uint32_t off = cg.col0 + in_tile;
-      const uint32_t q = off / c.hidden;
-      const uint32_t col = off - q * c.hidden;
-      uint32_t m = c.mask[col >> 3];
+      uint32_t q, col;
+      split_offset(cg.col0 + in_tile, c.hidden, c.inv_hidden, q, col);
+      const uint32_t m = lds.mask[col >> 3];
       if (m != 0u) {
-        uint16_t* dst = c.ch_val + (size_t)(cg.row0 + q) * n_ch + c.base[col >> 3];
-        // clear the outlier elements: two bits of the mask per word
+        uint16_t* dst = c.ch_val + (size_t)(cg.row0 + q) * n_ch + lds.base[col >> 3];
+        // the values go out first (one round per outlier channel of the octet: mostly one) ...
+        uint32_t todo = m, r = 0u;
+        while (todo != 0u) {
+          const uint32_t e = (uint32_t)__builtin_ctz(todo);
+          todo &= todo - 1u;
+          dst[r++] = (uint16_t)octet_half(raw[j], e);
+        }
+        // ... then they are cleared: two bits of the mask per word, each spread over its half
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          const uint32_t two = (m >> (2 * k)) & 3u;
-          const uint32_t keep = ((two & 1u) ? 0u : 0x0000FFFFu) | ((two & 2u) ? 0u : 0xFFFF0000u);
-          // the value goes out before it is cleared
-          if (two & 1u) dst[__popc(m & ((1u << (2 * k)) - 1u))] = (uint16_t)(raw[j][k] & 0xFFFFu);
-          if (two & 2u) dst[__popc(m & ((1u << (2 * k + 1)) - 1u))] = (uint16_t)(raw[j][k] >> 16);
-          raw[j][k] &= keep;
+          const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)m, 2 * k, 1);      // 0 or all ones
+          const uint32_t hi = (uint32_t)__builtin_amdgcn_sbfe((int)m, 2 * k + 1, 1);
+          const uint32_t clear = (lo & 0x0000FFFFu) | (hi & 0xFFFF0000u);
+          raw[j][k] &= ~clear;
         }
       }
     }
@@ -268,61 +311,99 @@ __device__ __forceinline__ void channel_compress_tile(const TensorDesc& d, const
 template <int BITS, bool ASYM, bool ROWWISE>
 __global__ __launch_bounds__(kThreads) void channel_compress_kernel(TensorDesc d, ChannelDesc c) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes[];
   if (c.status[1] != 0u) return;  // more outlier channels than the blob holds: nothing else is produced
   const uint32_t n_ch = __builtin_amdgcn_readfirstlane(c.status[0]);
+  ChannelLds lds{nullptr, nullptr};
+  if (n_ch != 0u) lds = stage_channels(c, lds_bytes);
   for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg) {
-    if (t + 1u < d.n_tiles) channel_compress_tile<BITS, ASYM, ROWWISE, true>(d, c, n_ch, t);
-    else channel_compress_tile<BITS, ASYM, ROWWISE, false>(d, c, n_ch, t);
+    if (t + 1u < d.n_tiles) channel_compress_tile<BITS, ASYM, ROWWISE, true>(d, c, n_ch, lds, t);
+    else channel_compress_tile<BITS, ASYM, ROWWISE, false>(d, c, n_ch, lds, t);
   }
 }
 
 // ---- decompression: dequantise a piece of 2048 elements, put the outlier channels back, store.
+// Every load of the piece is issued before its first store: codes, scales, and for every octet
+// with an outlier channel the value of its first one (a second outlier channel in the same octet
+// is rare and fetched when it is needed).
 template <int BITS, bool ASYM, bool F32>
 __device__ __forceinline__ void channel_decompress_tile(const TensorDesc& d, const ChannelDesc& c, uint32_t n_ch,
-                                                        uint32_t tile) {
+                                                        const ChannelLds& lds, uint32_t tile) {
   constexpr int E = 4;
   const uint32_t lane_off = (uint32_t)lane_id() * kOct;
   const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
   const ChannelGeo cg = channel_geo(tile, c.hidden);
+  const uint64_t left = d.numel - tile_base;  // > 0, a multiple of 8
+  const uint32_t rem = left < (uint64_t)(E * kRow) ? (uint32_t)left : (uint32_t)(E * kRow);
+
+  uint32_t cw[E][2];
+  float sc[E], zp[E];
+  uint32_t m[E], first[E], pre[E];
+  const uint16_t* src[E];
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-    const uint64_t e0 = tile_base + in_tile;
-    if (e0 >= d.numel) continue;
-    int code[kOct];
+    const bool live = in_tile < rem;
+    const uint64_t e0 = tile_base + (live ? in_tile : 0u);  // octets past the end re-read the first one
     if constexpr (BITS == 8) {
       const uint2 w = *reinterpret_cast<const uint2*>(d.codes + e0);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        code[e] = (int)(int8_t)((w.x >> (8 * e)) & 0xFFu);
-        code[4 + e] = (int)(int8_t)((w.y >> (8 * e)) & 0xFFu);
-      }
+      cw[j][0] = w.x; cw[j][1] = w.y;
     } else {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) code[e] = ((int)(w << (28 - 4 * e))) >> 28;
+      cw[j][0] = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
+      cw[j][1] = 0u;
     }
     const uint64_t grp = e0 >> d.lgq;
-    const float s = d.scales[grp];
-    float o = 0.0f;
-    if constexpr (ASYM) o = d.zp[grp];
+    sc[j] = d.scales[grp];
+    zp[j] = 0.0f;
+    if constexpr (ASYM) zp[j] = d.zp[grp];
+    m[j] = 0u; first[j] = 0u; pre[j] = 0u; src[j] = c.ch_val;
+    if (n_ch != 0u && live) {
+      uint32_t q, col;
+      split_offset(cg.col0 + in_tile, c.hidden, c.inv_hidden, q, col);
+      m[j] = lds.mask[col >> 3];
+      if (m[j] != 0u) {
+        first[j] = lds.base[col >> 3];
+        if (first[j] >= n_ch) m[j] = 0u;  // a damaged blob must not be read past its end
+        else {
+          src[j] = c.ch_val + (size_t)(cg.row0 + q) * n_ch + first[j];
+          pre[j] = src[j][0];
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
+    if (in_tile >= rem) continue;
+    const uint64_t e0 = tile_base + in_tile;
+    int code[kOct];
+    if constexpr (BITS == 8) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        code[e] = (int)(int8_t)((cw[j][0] >> (8 * e)) & 0xFFu);
+        code[4 + e] = (int)(int8_t)((cw[j][1] >> (8 * e)) & 0xFFu);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) code[e] = ((int)(cw[j][0] << (28 - 4 * e))) >> 28;
+    }
     float v[kOct];
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)code[e], s, o) : (float)code[e] * s;
+    for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)code[e], sc[j], zp[j]) : (float)code[e] * sc[j];
 
-    if (n_ch != 0u) {
-      const uint32_t off = cg.col0 + in_tile;
-      const uint32_t q = off / c.hidden;
-      const uint32_t col = off - q * c.hidden;
-      const uint32_t m = c.mask[col >> 3];
-      if (m != 0u) {
-        const uint32_t first = c.base[col >> 3];
-        const uint16_t* src = c.ch_val + (size_t)(cg.row0 + q) * n_ch + first;
+    if (m[j] != 0u) {
+      const uint32_t lowest = m[j] & (0u - m[j]);
+      const float first_val = __uint_as_float(pre[j] << 16);
 #pragma unroll
-        for (int e = 0; e < kOct; ++e)
-          if (m & (1u << e)) {
-            const uint32_t r = (uint32_t)__popc(m & ((1u << e) - 1u));
-            if (first < n_ch && r < n_ch - first) v[e] = __uint_as_float((uint32_t)src[r] << 16);  // a damaged blob must not be read past its end
+      for (int e = 0; e < kOct; ++e) v[e] = lowest == (1u << e) ? first_val : v[e];
+      const uint32_t rest = m[j] ^ lowest;
+      if (rest != 0u) {
+#pragma unroll
+        for (int e = 1; e < kOct; ++e)
+          if (rest & (1u << e)) {
+            const uint32_t r = (uint32_t)__popc(m[j] & ((1u << e) - 1u));
+            if (r < n_ch - first[j]) v[e] = __uint_as_float((uint32_t)src[j][r] << 16);
           }
       }
     }
@@ -348,8 +429,11 @@ __global__ __launch_bounds__(kThreads) void channel_decompress_kernel(TensorDesc
   if (c.status[1] != 0u) return;  // not a usable blob
   uint32_t n_ch = __builtin_amdgcn_readfirstlane(c.status[0]);
   if (n_ch > c.max_channels) n_ch = c.max_channels;  // a damaged blob must not make the reads leave it
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes[];
+  ChannelLds lds{nullptr, nullptr};
+  if (n_ch != 0u) lds = stage_channels(c, lds_bytes);
   for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-    channel_decompress_tile<BITS, ASYM, F32>(d, c, n_ch, t);
+    channel_decompress_tile<BITS, ASYM, F32>(d, c, n_ch, lds, t);
 }
 
 }  // namespace adacc

@@ -67,6 +67,7 @@ struct ChannelDesc {
   uint32_t tokens;
   uint32_t max_channels;
   float z_thresh;
+  float inv_hidden;     // 1 / hidden rounded towards zero twice: never above the true reciprocal
 };
 
 // Scan workspace: one 64-bit state word per run of tiles and one per block of 64 runs, high half
