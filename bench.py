@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--only-channel", action="store_true",
+                    help="run only the outlier-channel (Z-score) measurement and print its JSON")
     return ap.parse_args()
 
 
@@ -211,6 +213,70 @@ def cpu_baseline(name, seconds):
             "sample": f"{sample}; compress+decompress repeated {reps}x in {el:.1f} s"}
 
 
+def run_channel_mode(steps=50, warmup=5, cpu_rows=2048):
+    """The paper's own selection rule (Section 3.2, Eq. 1) on the C2-shaped activation: outlier
+    channels by Z-score > 3 kept whole, the rest int4 in groups of 128.  Compression reads the
+    tensor twice (channel sums, then extraction + quantisation): algorithmic bytes 4N + outputs;
+    decompression 2N + inputs.  Three rotating buffer sets, as for the main workload."""
+    import torch
+    import workloads
+    import oracle
+    import paper_2508_00806_amd as adacc
+    from helpers import bits_of
+    x = workloads.make("c2", "cuda")
+    tokens, hidden = x.shape
+    n = tokens * hidden
+    m = adacc.ChannelMethod(bits=4, quant_group=128, z_thresh=3.0, max_channels=64)
+    sets = 4
+    xs = [x if i == 0 else x.clone() for i in range(sets)]
+    L = adacc.channel_layout_of(m, tokens, hidden)
+    blobs = [adacc.alloc_channel_blob(m, tokens, hidden)[0] for _ in range(sets)]
+    dsts = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(sets)]
+    ws = adacc.alloc_channel_workspace(tokens, hidden)
+    for i in range(sets):
+        adacc.channel_compress(m, xs[i], tokens, hidden, blobs[i], ws)
+    for i in range(warmup):
+        adacc.channel_compress(m, xs[i % sets], tokens, hidden, blobs[i % sets], ws)
+        adacc.channel_decompress(m, blobs[(i + 2) % sets], tokens, hidden, dsts[(i + 2) % sets])
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        ev[i][0].record()
+        adacc.channel_compress(m, xs[i % sets], tokens, hidden, blobs[i % sets], ws)
+        ev[i][1].record()
+        adacc.channel_decompress(m, blobs[(i + 2) % sets], tokens, hidden, dsts[(i + 2) % sets])
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    c_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    d_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    st = adacc.channel_read_status(blobs[0], L)
+    if st[1]:
+        raise RuntimeError(f"more outlier channels than the blob holds: {st}")
+    outputs = n // 2 + 4 * (n // 128) + 2 * tokens * st[0] + 4 * st[0]
+    alg_c, alg_d = 4 * n + outputs, 2 * n + outputs
+    # the oracle on the first rows of the same tensor, single thread
+    xb = bits_of(x[:cpu_rows].cpu())
+    om = oracle.Method(bits=4, quant_group=128)
+    t0 = time.perf_counter()
+    oc = oracle.channel_compress(om, xb, cpu_rows, hidden, 3.0, cap=64)
+    oracle.channel_decompress(oc)
+    el = time.perf_counter() - t0
+    del xs, blobs, dsts
+    torch.cuda.empty_cache()
+    return {
+        "workload": f"outlier channels by Z-score>3 on the c2 tensor [{tokens},{hidden}] bf16, int4 group-128",
+        "n_outlier_channels": st[0],
+        "compress": {"ms": c_ms, "kernels": 4, "algorithmic_bytes": alg_c, "hbm_GBps": alg_c / (c_ms * 1e-3) / 1e9,
+                     "frac_of_peak": alg_c / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "activation_GBps": 2.0 * n / (c_ms * 1e-3) / 1e9},
+        "decompress": {"ms": d_ms, "kernels": 1, "algorithmic_bytes": alg_d, "hbm_GBps": alg_d / (d_ms * 1e-3) / 1e9,
+                       "frac_of_peak": alg_d / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                       "activation_GBps": 2.0 * n / (d_ms * 1e-3) / 1e9},
+        "cpu_oracle": {"value": 4.0 * cpu_rows * hidden / el / 1e9, "unit": "GB/s", "cores": 1,
+                       "sample": f"first {cpu_rows} rows, compress+decompress once in {el:.2f} s"},
+    }
+
+
 def run_workload(name, steps, warmup, sets):
     import torch
     w = Workload(name, sets)
@@ -252,6 +318,9 @@ def main():
     adacc.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
 
+    if a.only_channel:
+        print(json.dumps({"channel_zscore": run_channel_mode()}))
+        return
     main_res = run_workload(a.workload, a.steps, a.warmup, a.sets)
     ceiling = copy_ceiling()
     extras = []
@@ -261,6 +330,7 @@ def main():
                 continue
             k = 10 if name == "c5" else 50
             extras.append(run_workload(name, k, 5, a.sets))
+    channel = None if a.no_extras else run_channel_mode()
     cpu = None if a.no_cpu else cpu_baseline(a.workload, a.cpu_seconds)
 
     dom = "compress" if main_res["compress"]["ms"] >= main_res["decompress"]["ms"] else "decompress"
@@ -297,6 +367,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "other_workloads": extras,
+        "channel_zscore": channel,
     }
     print(json.dumps(out))
 

@@ -77,29 +77,36 @@ __global__ __launch_bounds__(kThreads) void channel_score_kernel(const float* __
   const uint32_t row = threadIdx.x / (kScoreChannels / 4);    // 0..31
   constexpr uint32_t kRowsPerPass = kThreads / (kScoreChannels / 4);
   const bool col_ok = h0 + quad * 4u < hidden;                // hidden is a multiple of 8
-  double s = 0.0;
-  for (uint32_t c0 = 0; c0 < n_chunks; c0 += kScoreChunks) {
+  constexpr uint32_t kPasses = kScoreChunks / kRowsPerPass;
+  float4 v[kPasses];
+  auto fetch = [&](uint32_t c0) {
     const uint32_t rows = n_chunks - c0 < (uint32_t)kScoreChunks ? n_chunks - c0 : (uint32_t)kScoreChunks;
-    float4 v[kScoreChunks / kRowsPerPass];
 #pragma unroll
-    for (uint32_t i = 0; i < kScoreChunks / kRowsPerPass; ++i) {
+    for (uint32_t i = 0; i < kPasses; ++i) {
       const uint32_t r = row + i * kRowsPerPass;
       v[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
       if (col_ok && r < rows)
         v[i] = *reinterpret_cast<const float4*>(partial + (size_t)(c0 + r) * hidden + h0 + quad * 4u);
     }
+  };
+  double s = 0.0;
+  fetch(0u);
+  for (uint32_t c0 = 0; c0 < n_chunks; c0 += kScoreChunks) {
+    const uint32_t rows = n_chunks - c0 < (uint32_t)kScoreChunks ? n_chunks - c0 : (uint32_t)kScoreChunks;
 #pragma unroll
-    for (uint32_t i = 0; i < kScoreChunks / kRowsPerPass; ++i)
+    for (uint32_t i = 0; i < kPasses; ++i)
       *reinterpret_cast<float4*>(&stage[row + i * kRowsPerPass][quad * 4u]) = v[i];
     __syncthreads();
+    if (c0 + kScoreChunks < n_chunks) fetch(c0 + kScoreChunks);  // in flight while this block is added up
     if (threadIdx.x < (uint32_t)kScoreChannels) {
+      constexpr uint32_t kBatch = 32;  // LDS reads in flight ahead of the chain of additions
       uint32_t r = 0;
-      for (; r + 8 <= rows; r += 8) {
-        float w[8];
+      for (; r + kBatch <= rows; r += kBatch) {
+        float w[kBatch];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = stage[r + i][threadIdx.x];
+        for (uint32_t i = 0; i < kBatch; ++i) w[i] = stage[r + i][threadIdx.x];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s = __dadd_rn(s, (double)w[i]);
+        for (uint32_t i = 0; i < kBatch; ++i) s = __dadd_rn(s, (double)w[i]);
       }
       for (; r < rows; ++r) s = __dadd_rn(s, (double)stage[r][threadIdx.x]);
     }

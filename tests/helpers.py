@@ -122,3 +122,46 @@ def run_parity(x_cpu_bf16, md, cap=None, rule=0, decompress=True):
         assert_f32_matches(d32.cpu().numpy(), of32)
         assert_bf16_matches(bits_of(dbf), obf)
     return oc, blob, L, m
+
+
+def run_channel_parity(x, bits, gq, asym, z=3.0, cap=None, rule=0):
+    """x: bf16 [tokens, hidden] on the CPU."""
+    tokens, hidden = x.shape
+    xb = bits_of(x)
+    om = oracle.Method(bits=bits, quant_group=gq, asym=asym, scale_rule=rule)
+    is_out, _, _ = oracle.channel_select(oracle.channel_scores(xb, tokens, hidden), z)
+    n_ch = int(is_out.sum())
+    cap = max(n_ch, 1) if cap is None else cap
+    oc = oracle.channel_compress(om, xb, tokens, hidden, z, cap=cap)
+    assert oc.n_ch == n_ch
+    m = adacc.ChannelMethod(bits=bits, quant_group=gq, asym=asym, scale_rule=rule, z_thresh=z, max_channels=cap)
+    blob, L = adacc.alloc_channel_blob(m, tokens, hidden)
+    blob.fill_(0xA5)
+    ws = adacc.alloc_channel_workspace(tokens, hidden)
+    adacc.channel_compress(m, x.contiguous().cuda(), tokens, hidden, blob, ws)
+    st = adacc.channel_read_status(blob, L)
+    assert st == (n_ch, 1 if n_ch > cap else 0, 0, 0), st
+    sec = {k: v.cpu().numpy() for k, v in adacc.channel_blob_sections(blob, L, m, tokens, hidden).items()}
+    assert np.array_equal(np.unpackbits(sec["ch_mask"], bitorder="little"), is_out), "channel mask differs"
+    per_byte = is_out.reshape(-1, 8).sum(axis=1)
+    assert np.array_equal(sec["ch_base"], np.concatenate([[0], np.cumsum(per_byte)[:-1]])), "channel ranks differ"
+    k = min(n_ch, cap)
+    assert np.array_equal(sec["ch_idx"][:k], np.nonzero(is_out)[0][:k]), "channel list differs"
+    dbf = torch.full((tokens * hidden,), 7.0, dtype=torch.bfloat16, device="cuda")
+    d32 = torch.full((tokens * hidden,), 7.0, dtype=torch.float32, device="cuda")
+    adacc.channel_decompress(m, blob, tokens, hidden, dbf)
+    adacc.channel_decompress(m, blob, tokens, hidden, d32)
+    torch.cuda.synchronize()
+    if n_ch > cap:  # not a usable blob: nothing else is produced, decompression leaves dst alone
+        assert bool((dbf == 7.0).all()) and bool((d32 == 7.0).all())
+        return oc, st
+    assert np.array_equal(sec["ch_val"].view(np.uint16)[:tokens * n_ch].reshape(tokens, n_ch), oc.ch_val), \
+        "channel values differ"
+    assert np.array_equal(sec["codes"], oc.packed), "packed codes differ"
+    assert np.array_equal(sec["scales"].view(np.uint32), oc.scale.view(np.uint32)), "scales differ"
+    if asym:
+        assert np.array_equal(sec["zp"].view(np.uint32), oc.zp.view(np.uint32)), "offsets differ"
+    of32, obf = oracle.channel_decompress(oc)
+    assert_f32_matches(d32.cpu().numpy(), of32)
+    assert_bf16_matches(bits_of(dbf), obf)
+    return oc, st
