@@ -69,6 +69,10 @@ def lib():
         L.oracle_channel_compress.restype = ctypes.c_int
         L.oracle_channel_decompress.argtypes = [ctypes.POINTER(_CMethod), vp, vp, vp, vp, vp, sz, sz, sz, vp, vp]
         L.oracle_channel_decompress.restype = ctypes.c_int
+        L.oracle_mask_pack.argtypes = [vp, sz, vp]
+        L.oracle_mask_pack.restype = None
+        L.oracle_mask_unpack.argtypes = [vp, sz, vp]
+        L.oracle_mask_unpack.restype = None
         _lib = L
     return _lib
 
@@ -227,3 +231,20 @@ def channel_decompress(c: ChannelCompressed):
     if rc != 0:
         raise ValueError("oracle: channel decompress failed")
     return f, b
+
+
+# ---- dropout mask: byte format <-> bit format (Section 3.2) ----
+
+def mask_pack(mask) -> np.ndarray:
+    m = np.ascontiguousarray(mask).view(np.uint8).reshape(-1)
+    bits = np.zeros((m.size + 7) // 8, dtype=np.uint8)
+    lib().oracle_mask_pack(_p(m), m.size, _p(bits))
+    return bits
+
+
+def mask_unpack(bits, n: int) -> np.ndarray:
+    b = np.ascontiguousarray(bits, dtype=np.uint8).reshape(-1)
+    assert b.size >= (n + 7) // 8
+    m = np.zeros(n, dtype=np.uint8)
+    lib().oracle_mask_unpack(_p(b), n, _p(m))
+    return m

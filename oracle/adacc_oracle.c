@@ -437,3 +437,19 @@ int oracle_channel_decompress(const oracle_method *m, const uint8_t *packed, con
     }
   return 0;
 }
+
+/* ====================================================================================
+ * Dropout mask (Section 3.2, list of layer-specific schemes): the mask of an attention layer is
+ * kept in bit format instead of byte format, without loss.  Element i of the mask (a byte, zero =
+ * dropped, anything else = kept) becomes bit (i mod 8) of byte i / 8; unused bits of the last
+ * byte are zero.  Unpacking yields bytes 0 and 1.
+ * ==================================================================================== */
+void oracle_mask_pack(const uint8_t *mask, size_t n, uint8_t *bits) {
+  for (size_t j = 0; j < (n + 7) / 8; ++j) bits[j] = 0;
+  for (size_t i = 0; i < n; ++i)
+    if (mask[i] != 0) bits[i / 8] = (uint8_t)(bits[i / 8] | (1u << (i % 8)));
+}
+
+void oracle_mask_unpack(const uint8_t *bits, size_t n, uint8_t *mask) {
+  for (size_t i = 0; i < n; ++i) mask[i] = (uint8_t)((bits[i / 8] >> (i % 8)) & 1u);
+}

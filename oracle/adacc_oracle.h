@@ -95,6 +95,12 @@ int oracle_channel_decompress(const oracle_method *m, const uint8_t *packed, con
                               const int32_t *ch_idx, const uint16_t *ch_val, size_t n_ch, size_t tokens,
                               size_t hidden, float *xhat_f32, uint16_t *xhat_bf16);
 
+/* ---- dropout mask: byte format <-> bit format (Section 3.2), lossless ----
+ * mask: n bytes, zero = dropped, non-zero = kept.  bits: ceil(n/8) bytes, element i in bit i%8 of
+ * byte i/8, unused bits zero.  Unpacking writes bytes 0 and 1. */
+void oracle_mask_pack(const uint8_t *mask, size_t n, uint8_t *bits);
+void oracle_mask_unpack(const uint8_t *bits, size_t n, uint8_t *mask);
+
 #ifdef __cplusplus
 }
 #endif

@@ -568,3 +568,21 @@ def test_no_outlier_channel_means_plain_quantisation():
     plain = oracle.compress(m, xb)
     assert c.n_ch == 0 and np.array_equal(c.packed, plain.packed)
     assert np.array_equal(c.scale.view(np.uint32), plain.scale.view(np.uint32))
+
+
+# ----------------------------------------------------------------- dropout mask, byte -> bit (Section 3.2)
+def test_mask_bit_format_is_an_eighth_and_lossless():
+    """The paper's two statements about the scheme: bit format instead of byte format (an eighth of
+    the bytes, rounded up) and no loss.  The bit order is pinned with numpy's packbits (a library
+    routine) and one hand-written byte."""
+    rng = np.random.default_rng(31)
+    for n in (0, 1, 7, 8, 9, 31, 32, 33, 1000, 4099):
+        mask = (rng.random(n) < 0.9).astype(np.uint8)  # keep probability 0.9, as a dropout of 0.1
+        bits = oracle.mask_pack(mask)
+        assert bits.size == (n + 7) // 8
+        assert np.array_equal(bits, np.packbits(mask, bitorder="little"))
+        assert np.array_equal(oracle.mask_unpack(bits, n), mask)
+        assert np.array_equal(oracle.mask_unpack(bits, n), np.unpackbits(bits, bitorder="little")[:n])
+    assert list(oracle.mask_pack(np.array([1, 0, 0, 1, 0, 0, 0, 0, 1], dtype=np.uint8))) == [0b00001001, 0b1]
+    # any non-zero byte counts as kept and comes back as 1
+    assert list(oracle.mask_unpack(oracle.mask_pack(np.array([255, 0, 2], dtype=np.uint8)), 3)) == [1, 0, 1]
