@@ -219,6 +219,17 @@ int adacc_channel_decompress(const adacc_channel_method *method, const void *blo
 int adacc_channel_read_status(const void *blob, const adacc_channel_layout *layout, void *hip_stream,
                               uint32_t status_out[4]);
 
+/* ---- dropout mask of attention layers: byte format <-> bit format, lossless (Section 3.2,
+ * list of layer-specific schemes) ----
+ * mask: n bytes, zero = dropped, anything else = kept (a torch.bool tensor is such an array).
+ * bits: adacc_mask_packed_bytes(n) = ceil(n/8) bytes; element i is bit i % 8 of byte i / 8; the
+ * unused bits of the last byte are written as zero.  Unpacking writes bytes 0 and 1.
+ * Both pointers are device memory, 16-byte aligned.  n == 0: ADACC_OK, nothing is touched.
+ * Errors: ENULL, EALIGN, EHIP. */
+uint64_t adacc_mask_packed_bytes(uint64_t n);
+int adacc_mask_pack(const void *mask, uint64_t n, void *bits, void *hip_stream);
+int adacc_mask_unpack(const void *bits, uint64_t n, void *mask, void *hip_stream);
+
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst: the practical HBM
  * ceiling the compression kernels are measured against, and the calibration
  * kernel for hardware byte counters. */

@@ -23,7 +23,8 @@ EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "
            "adacc_decompress", "adacc_batch_workspace_bytes", "adacc_compress_batch",
            "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
            "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
-           "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status")
+           "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status",
+           "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack")
 
 
 class CMethod(ctypes.Structure):
@@ -145,6 +146,12 @@ def lib():
         L.adacc_channel_decompress.restype = ci
         L.adacc_channel_read_status.argtypes = [vp, pcl, vp, ctypes.POINTER(u32 * 4)]
         L.adacc_channel_read_status.restype = ci
+        L.adacc_mask_packed_bytes.argtypes = [u64]
+        L.adacc_mask_packed_bytes.restype = u64
+        L.adacc_mask_pack.argtypes = [vp, u64, vp, vp]
+        L.adacc_mask_pack.restype = ci
+        L.adacc_mask_unpack.argtypes = [vp, u64, vp, vp]
+        L.adacc_mask_unpack.restype = ci
         L.adacc_version.argtypes = []
         L.adacc_version.restype = ctypes.c_char_p
         _lib = L
@@ -370,6 +377,26 @@ def channel_blob_sections(blob, layout: CChannelLayout, method: ChannelMethod, t
     if method.asym:
         sec["zp"] = view(layout.zp_off, 4 * groups, torch.float32)
     return sec
+
+
+# ---------------------------------------------------------------- dropout mask, byte <-> bit (Section 3.2)
+def mask_packed_bytes(n: int) -> int:
+    return int(lib().adacc_mask_packed_bytes(n))
+
+
+def mask_pack(mask, bits, n=None, stream=None):
+    """mask: bool / uint8 tensor of n elements; bits: uint8 tensor of at least mask_packed_bytes(n)."""
+    n = mask.numel() if n is None else n
+    if _nbytes(bits) < mask_packed_bytes(n) or _nbytes(mask) < n:
+        raise AdaccError(ESIZE, "adacc_mask_pack")
+    _check(lib().adacc_mask_pack(_ptr(mask), n, _ptr(bits), _stream(stream)), "adacc_mask_pack")
+
+
+def mask_unpack(bits, mask, n=None, stream=None):
+    n = mask.numel() if n is None else n
+    if _nbytes(bits) < mask_packed_bytes(n) or _nbytes(mask) < n:
+        raise AdaccError(ESIZE, "adacc_mask_unpack")
+    _check(lib().adacc_mask_unpack(_ptr(bits), n, _ptr(mask), _stream(stream)), "adacc_mask_unpack")
 
 
 # ---------------------------------------------------------------- buffer helpers (allocation = plumbing)

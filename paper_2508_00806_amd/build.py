@@ -14,6 +14,7 @@ SOURCES = [os.path.join(CSRC, f) for f in (
     "adacc_k_decompress.hip",
     "adacc_k_batch4.hip", "adacc_k_batch8.hip",
     "adacc_k_channel.hip",    # outlier channels by Z-score
+    "adacc_k_mask.hip",       # dropout mask, byte <-> bit
 )]
 HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_compress.hpp", "adacc_decompress.hpp",
                                            "adacc_kernels.hpp", "adacc_fn.hpp", "adacc_channel.hpp")]

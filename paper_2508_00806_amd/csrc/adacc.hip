@@ -752,6 +752,33 @@ int adacc_channel_read_status(const void* blob, const adacc_channel_layout* layo
   return e == hipSuccess ? ADACC_OK : hip_fail(e, "hipStreamSynchronize");
 }
 
+uint64_t adacc_mask_packed_bytes(uint64_t n) { return (n + 7u) / 8u; }
+
+static int mask_launch(MaskFn fn, const void* in, uint64_t n, void* out, void* hip_stream, const char* what) {
+  if (n == 0) return ADACC_OK;
+  if (!in || !out) return ADACC_ENULL;
+  if (misaligned(in, 16) || misaligned(out, 16)) return ADACC_EALIGN;
+  int cus = 0;
+  const int rc = device_cus(&cus);
+  if (rc != ADACC_OK) return rc;
+  const uint64_t words = n / 32u;  // one lane turns over one 32-bit word of bits, four per round
+  uint64_t grid = (words + 4ull * kThreads - 1) / (4ull * kThreads);
+  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_MASK_WGS_PER_CU", 8);
+  if (grid > cap) grid = cap;
+  if (grid == 0) grid = 1;
+  hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const uint8_t*>(in), n, static_cast<uint8_t*>(out));
+  return launch_check(what);
+}
+
+int adacc_mask_pack(const void* mask, uint64_t n, void* bits, void* hip_stream) {
+  return mask_launch(mask_pack_fn(), mask, n, bits, hip_stream, "mask_pack_kernel");
+}
+
+int adacc_mask_unpack(const void* bits, uint64_t n, void* mask, void* hip_stream) {
+  return mask_launch(mask_unpack_fn(), bits, n, mask, hip_stream, "mask_unpack_kernel");
+}
+
 int adacc_hbm_copy(void* dst, const void* src, uint64_t bytes, void* hip_stream) {
   if (!dst || !src) return ADACC_ENULL;
   if (bytes % 16 != 0) return ADACC_EINVAL;

@@ -32,4 +32,9 @@ uint32_t channel_score_channels();  // channels per workgroup of the score kerne
 ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);
 ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);
 
+// dropout mask, byte format <-> bit format (Section 3.2)
+typedef void (*MaskFn)(const uint8_t*, uint64_t, uint8_t*);
+MaskFn mask_pack_fn();
+MaskFn mask_unpack_fn();
+
 }  // namespace adacc

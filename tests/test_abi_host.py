@@ -232,3 +232,14 @@ def test_channel_calls_validate_before_any_device_work(L):
     assert g(r, blob, lay.total_bytes, tokens, hidden, 0x40000, 2, None) == adacc.EINVAL
     assert g(r, blob, lay.total_bytes - 1, tokens, hidden, 0x40000, 0, None) == adacc.ESIZE
     assert g(r, blob, lay.total_bytes, tokens, hidden, 0x40002, 0, None) == adacc.EALIGN
+
+
+# ----------------------------------------------------------------- dropout mask
+def test_mask_calls_validate_before_any_device_work(L):
+    assert [L.adacc_mask_packed_bytes(n) for n in (0, 1, 8, 9, 4096)] == [0, 1, 1, 2, 512]
+    for f in (L.adacc_mask_pack, L.adacc_mask_unpack):
+        assert f(None, 0, None, None) == adacc.OK
+        assert f(None, 64, 0x20000, None) == adacc.ENULL
+        assert f(0x10000, 64, None, None) == adacc.ENULL
+        assert f(0x10008, 64, 0x20000, None) == adacc.EALIGN
+        assert f(0x10000, 64, 0x20004, None) == adacc.EALIGN
