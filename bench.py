@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--only-mask", action="store_true",
+                    help="run only the dropout-mask (byte <-> bit) measurement and print its JSON")
     ap.add_argument("--only-channel", action="store_true",
                     help="run only the outlier-channel (Z-score) measurement and print its JSON")
     return ap.parse_args()
@@ -277,6 +279,53 @@ def run_channel_mode(steps=50, warmup=5, cpu_rows=2048):
     }
 
 
+def run_mask(steps=30, warmup=3):
+    """Dropout mask of the attention layer of C4 ([4,32,2048,2048] bytes, keep probability 0.9):
+    byte format -> bit format and back (Section 3.2).  Algorithmic bytes per direction: n + n/8."""
+    import torch
+    import numpy as np
+    import oracle
+    import paper_2508_00806_amd as adacc
+    n = 4 * 32 * 2048 * 2048
+    sets = 3
+    g = torch.Generator(device="cuda").manual_seed(77)
+    masks = [(torch.rand(n, device="cuda", generator=g) < 0.9).to(torch.uint8) for _ in range(sets)]
+    bits = [torch.empty(adacc.mask_packed_bytes(n), dtype=torch.uint8, device="cuda") for _ in range(sets)]
+    backs = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(sets)]
+    for i in range(sets + warmup):
+        adacc.mask_pack(masks[i % sets], bits[i % sets])
+        adacc.mask_unpack(bits[i % sets], backs[i % sets])
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        ev[i][0].record()
+        adacc.mask_pack(masks[i % sets], bits[i % sets])
+        ev[i][1].record()
+        adacc.mask_unpack(bits[(i + 1) % sets], backs[(i + 1) % sets])
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    p_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    u_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    if not torch.equal(backs[0], masks[0]):
+        raise RuntimeError("mask round trip is not lossless")
+    alg = n + n // 8
+    sample = masks[0][:1 << 24].cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.mask_unpack(oracle.mask_pack(sample), sample.size)
+    el = time.perf_counter() - t0
+    del masks, bits, backs
+    torch.cuda.empty_cache()
+    return {
+        "workload": "dropout mask [4,32,2048,2048] bytes <-> bits, keep probability 0.9",
+        "pack": {"ms": p_ms, "algorithmic_bytes": alg, "hbm_GBps": alg / (p_ms * 1e-3) / 1e9,
+                 "frac_of_peak": alg / (p_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "unpack": {"ms": u_ms, "algorithmic_bytes": alg, "hbm_GBps": alg / (u_ms * 1e-3) / 1e9,
+                   "frac_of_peak": alg / (u_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "cpu_oracle": {"value": 2.0 * sample.size / el / 1e9, "unit": "GB/s of mask bytes", "cores": 1,
+                       "sample": f"first {sample.size} elements, pack+unpack once in {el:.2f} s"},
+    }
+
+
 def run_workload(name, steps, warmup, sets):
     import torch
     w = Workload(name, sets)
@@ -318,6 +367,9 @@ def main():
     adacc.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
 
+    if a.only_mask:
+        print(json.dumps({"dropout_mask": run_mask()}))
+        return
     if a.only_channel:
         print(json.dumps({"channel_zscore": run_channel_mode()}))
         return
@@ -331,6 +383,7 @@ def main():
             k = 10 if name == "c5" else 50
             extras.append(run_workload(name, k, 5, a.sets))
     channel = None if a.no_extras else run_channel_mode()
+    mask = None if a.no_extras else run_mask()
     cpu = None if a.no_cpu else cpu_baseline(a.workload, a.cpu_seconds)
 
     dom = "compress" if main_res["compress"]["ms"] >= main_res["decompress"]["ms"] else "decompress"
@@ -368,6 +421,7 @@ def main():
         "cpu_baseline": cpu,
         "other_workloads": extras,
         "channel_zscore": channel,
+        "dropout_mask": mask,
     }
     print(json.dumps(out))
 

@@ -761,9 +761,9 @@ static int mask_launch(MaskFn fn, const void* in, uint64_t n, void* out, void* h
   int cus = 0;
   const int rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
-  const uint64_t words = n / 32u;  // one lane turns over one 32-bit word of bits, four per round
-  uint64_t grid = (words + 4ull * kThreads - 1) / (4ull * kThreads);
-  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_MASK_WGS_PER_CU", 8);
+  const uint64_t pieces = n / 16u;  // one lane turns over 16 elements at a time, eight times per round
+  uint64_t grid = (pieces + 8ull * kThreads - 1) / (8ull * kThreads);
+  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_MASK_WGS_PER_CU", 32);
   if (grid > cap) grid = cap;
   if (grid == 0) grid = 1;
   hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
