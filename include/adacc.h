@@ -230,6 +230,15 @@ uint64_t adacc_mask_packed_bytes(uint64_t n);
 int adacc_mask_pack(const void *mask, uint64_t n, void *bits, void *hip_stream);
 int adacc_mask_unpack(const void *bits, uint64_t n, void *mask, void *hip_stream);
 
+/* ---- what the policy maker consumes (Section 3.3: CRate_i in the memory constraint; Section 3.4:
+ * the rate is re-evaluated while training, as the number of outliers moves) ----
+ * Host only, pure.  Bytes of the blob that carry information for a tensor compressed with `method`
+ * that produced n_outliers outliers: codes + scales (+ offsets) + 6 bytes per outlier + the tile
+ * offsets (4 bytes per tile and one more; none for ADACC_OUTLIER_NONE); padding between sections is
+ * not counted.  CRate_i = this / (2 * numel).  NOOP: 2 * numel (the tensor is retained as it is).
+ * Returns 0 for a malformed method. */
+uint64_t adacc_compressed_bytes(const adacc_method *method, uint64_t numel, uint64_t n_outliers);
+
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst: the practical HBM
  * ceiling the compression kernels are measured against, and the calibration
  * kernel for hardware byte counters. */

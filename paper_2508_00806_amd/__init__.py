@@ -24,7 +24,7 @@ EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "
            "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
            "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
            "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status",
-           "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack")
+           "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack", "adacc_compressed_bytes")
 
 
 class CMethod(ctypes.Structure):
@@ -152,6 +152,8 @@ def lib():
         L.adacc_mask_pack.restype = ci
         L.adacc_mask_unpack.argtypes = [vp, u64, vp, vp]
         L.adacc_mask_unpack.restype = ci
+        L.adacc_compressed_bytes.argtypes = [pm, u64, u64]
+        L.adacc_compressed_bytes.restype = u64
         L.adacc_version.argtypes = []
         L.adacc_version.restype = ctypes.c_char_p
         _lib = L
@@ -202,6 +204,12 @@ def layout_of(method: Method, numel: int) -> CLayout:
 def workspace_bytes(method: Method, numel: int) -> int:
     cm = method.c()
     return int(lib().adacc_workspace_bytes(ctypes.byref(cm), numel))
+
+
+def compressed_bytes(method: Method, numel: int, n_outliers: int) -> int:
+    """Information-carrying bytes of a blob; CRate_i of Section 3.3 = this / (2 * numel)."""
+    cm = method.c()
+    return int(lib().adacc_compressed_bytes(ctypes.byref(cm), numel, n_outliers))
 
 
 def batch_workspace_bytes(methods, numels) -> int:

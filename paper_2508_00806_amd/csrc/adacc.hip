@@ -779,6 +779,17 @@ int adacc_mask_unpack(const void* bits, uint64_t n, void* mask, void* hip_stream
   return mask_launch(mask_unpack_fn(), bits, n, mask, hip_stream, "mask_unpack_kernel");
 }
 
+uint64_t adacc_compressed_bytes(const adacc_method* method, uint64_t numel, uint64_t n_outliers) {
+  if (!method) return 0;
+  Plan p;
+  if (make_plan(method, numel, &p) != ADACC_OK) return 0;
+  if (p.noop) return 2ull * numel;
+  const uint64_t groups = numel / method->quant_group;
+  uint64_t bytes = numel * method->bits / 8 + 4ull * groups * (method->asym ? 2u : 1u);
+  if (p.outliers) bytes += 6ull * n_outliers + 4ull * ((uint64_t)p.n_tiles + 1u);
+  return bytes;
+}
+
 int adacc_hbm_copy(void* dst, const void* src, uint64_t bytes, void* hip_stream) {
   if (!dst || !src) return ADACC_ENULL;
   if (bytes % 16 != 0) return ADACC_EINVAL;

@@ -1,0 +1,134 @@
+"""Saved-activation compression for a real forward / backward pass, and the per-tensor figures
+the policy maker consumes.
+
+Adacc compresses the activations an operator saves for its backward pass and decompresses them
+when the backward pass needs them (Fig. 3(c)); which tensors, and how, is the per-tensor policy
+R_{i,t} of Section 3.3, whose inputs are the compression rate CRate_i and the times Tc_i / Tdc_i
+(Section 3.3, and re-evaluated during training, Section 3.4).  `SavedActivationCompression` is a
+`torch.autograd.graph.saved_tensors_hooks` context that does exactly that with libadacc, and keeps
+those three figures per saved tensor.
+
+Plumbing only: the hooks allocate buffers and call the library; every step of compression and
+decompression runs in the HIP kernels.  A tensor the policy does not cover is saved as it is.
+"""
+import torch
+
+from . import (ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
+               alloc_channel_workspace, alloc_workspace, channel_compress, channel_decompress,
+               channel_read_status, channel_workspace_bytes, compress, compressed_bytes, decompress, read_status, workspace_bytes)
+
+
+class _Saved:
+    """What the autograd graph holds instead of the activation."""
+    __slots__ = ("method", "blob", "layout", "shape", "numel", "record")
+
+    def __init__(self, method, blob, layout, shape, numel, record):
+        self.method, self.blob, self.layout, self.shape, self.numel, self.record = method, blob, layout, shape, numel, record
+
+
+class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
+    """`with SavedActivationCompression(policy): loss = model(x)` then `loss.backward()`.
+
+    policy(tensor) returns an adacc `Method` (element outliers), a `ChannelMethod` (outlier channels
+    by Z-score; the tensor is taken as [numel / last_dim, last_dim]) or None (retain).  Only contiguous
+    bf16 CUDA tensors are offered to the policy.  timing=True brackets every library call with events
+    so that `report()` can give Tc_i and Tdc_i (it costs a synchronisation in `report()` only).
+    """
+
+    def __init__(self, policy, timing=True):
+        self.policy = policy
+        self.timing = timing
+        self.records = []
+        self._ws = None      # scan workspace, grown on demand, reused by every tensor (one stream)
+        self._cws = None     # workspace of the channel statistics
+        super().__init__(self._pack, self._unpack)
+
+    # ---- hooks
+    def _eligible(self, t):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+                and t.numel() > 0):
+            return False
+        return not (t.is_leaf and t.requires_grad)  # parameters are not activations
+
+    def _pack(self, t):
+        if not self._eligible(t):
+            return t
+        m = self.policy(t)
+        if m is None or (isinstance(m, Method) and m.kind == KIND_NOOP):
+            return t
+        numel = t.numel()
+        rec = {"shape": tuple(t.shape), "numel": numel, "method": m, "events": {}}
+        ev = self._events(rec, "compress")
+        if isinstance(m, ChannelMethod):
+            hidden = t.shape[-1]
+            tokens = numel // hidden
+            blob, layout = alloc_channel_blob(m, tokens, hidden, device=t.device)
+            if self._cws is None or self._cws.numel() < channel_workspace_bytes(tokens, hidden):
+                self._cws = alloc_channel_workspace(tokens, hidden, device=t.device)
+            channel_compress(m, t, tokens, hidden, blob, self._cws)
+        else:
+            blob, layout = alloc_blob(m, numel, device=t.device)
+            ws = None
+            if m.outlier_mode != OUTLIER_NONE:
+                want = workspace_bytes(m, numel)
+                if self._ws is None or self._ws.c.bytes < want:
+                    self._ws = alloc_workspace(want, device=t.device)
+                ws = self._ws
+            compress(m, t, blob, ws)
+        if ev:
+            ev[1].record()
+        self.records.append(rec)
+        saved = _Saved(m, blob, layout, t.shape, numel, rec)
+        rec["_saved"] = saved
+        return saved
+
+    def _unpack(self, s):
+        if not isinstance(s, _Saved):
+            return s
+        out = torch.empty(s.shape, dtype=torch.bfloat16, device=s.blob.device)
+        ev = self._events(s.record, "decompress")
+        if isinstance(s.method, ChannelMethod):
+            hidden = s.shape[-1]
+            channel_decompress(s.method, s.blob, s.numel // hidden, hidden, out)
+        else:
+            decompress(s.method, s.blob, out)
+        if ev:
+            ev[1].record()
+        return out
+
+    def _events(self, rec, key):
+        if not self.timing:
+            return None
+        ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        ev[0].record()
+        rec["events"][key] = ev
+        return ev
+
+    # ---- the figures of Section 3.3 / 3.4, one entry per compressed tensor, in the order they were saved
+    def report(self):
+        """[{shape, numel, n_outliers, overflow, original_bytes, compressed_bytes, crate, tc_ms, tdc_ms}].
+        crate = compressed / original bytes, the factor CRate_i multiplies M_i with in the memory
+        constraint of Section 3.3.  Waits for the GPU."""
+        torch.cuda.synchronize()
+        rows = []
+        for rec in self.records:
+            s = rec["_saved"]
+            m = rec["method"]
+            if isinstance(m, ChannelMethod):
+                hidden = rec["shape"][-1]
+                tokens = rec["numel"] // hidden
+                st = channel_read_status(s.blob, s.layout)
+                plain = Method(bits=m.bits, quant_group=m.quant_group, asym=m.asym, scale_rule=m.scale_rule)
+                comp = compressed_bytes(plain, rec["numel"], 0) + st[0] * (2 * tokens + 4)
+            else:
+                st = read_status(s.blob, s.layout)
+                comp = compressed_bytes(m, rec["numel"], st[0])
+            row = {"shape": rec["shape"], "numel": rec["numel"], "n_outliers": st[0], "overflow": bool(st[1]),
+                   "original_bytes": 2 * rec["numel"], "compressed_bytes": comp,
+                   "crate": comp / (2.0 * rec["numel"]), "tc_ms": None, "tdc_ms": None}
+            for key, name in (("compress", "tc_ms"), ("decompress", "tdc_ms")):
+                ev = rec["events"].get(key)
+                if ev:
+                    row[name] = ev[0].elapsed_time(ev[1])
+            rows.append(row)
+        return rows

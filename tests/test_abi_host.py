@@ -243,3 +243,28 @@ def test_mask_calls_validate_before_any_device_work(L):
         assert f(0x10000, 64, None, None) == adacc.ENULL
         assert f(0x10008, 64, 0x20000, None) == adacc.EALIGN
         assert f(0x10000, 64, 0x20004, None) == adacc.EALIGN
+
+
+# ----------------------------------------------------------------- compression rate for the policy maker
+def test_compressed_bytes_against_the_oracle_and_the_closed_form(L):
+    """The oracle's logical size (pinned to the sizes the paper implies) plus the tile offsets the
+    blob also stores; int4 in groups of 128 without outliers is 0.25 + 1/64 of the bf16 bytes."""
+    import oracle
+    from helpers import oracle_method
+    import workloads
+    for name in ("c1", "c2", "c3", "c4"):
+        md = workloads.METHODS[name]
+        n = 2048 * 12
+        m = Method(bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"],
+                   outlier_mode={"none": 0, "abs": 1, "std": 2, "topk": 3}[md["outlier_mode"]],
+                   stat_group=md["stat_group"], thresh=md["thresh"], topk=md["topk"], max_outliers=100)
+        lay = adacc.layout_of(m, n)
+        for n_out in (0, 7, 100):
+            want = oracle.logical_bytes(oracle_method(md), n, n_out) + 4 * (lay.n_tiles + 1)
+            assert adacc.compressed_bytes(m, n, n_out) == want
+    plain = Method(bits=4, quant_group=128)
+    n = 1 << 20
+    assert adacc.compressed_bytes(plain, n, 0) == n // 2 + 4 * n // 128
+    assert adacc.compressed_bytes(plain, n, 0) / (2 * n) == 0.25 + 1 / 64
+    assert adacc.compressed_bytes(adacc.NOOP, n, 0) == 2 * n
+    assert adacc.compressed_bytes(Method(bits=5), n, 0) == 0
