@@ -69,6 +69,10 @@ def lib():
         L.oracle_channel_compress.restype = ctypes.c_int
         L.oracle_channel_decompress.argtypes = [ctypes.POINTER(_CMethod), vp, vp, vp, vp, vp, sz, sz, sz, vp, vp]
         L.oracle_channel_decompress.restype = ctypes.c_int
+        L.oracle_channelwise_compress.argtypes = [ctypes.POINTER(_CMethod), vp, sz, sz, vp, vp, vp]
+        L.oracle_channelwise_compress.restype = ctypes.c_int
+        L.oracle_channelwise_decompress.argtypes = [ctypes.POINTER(_CMethod), vp, vp, sz, sz, vp, vp]
+        L.oracle_channelwise_decompress.restype = ctypes.c_int
         L.oracle_mask_pack.argtypes = [vp, sz, vp]
         L.oracle_mask_pack.restype = None
         L.oracle_mask_unpack.argtypes = [vp, sz, vp]
@@ -248,3 +252,32 @@ def mask_unpack(bits, n: int) -> np.ndarray:
     m = np.zeros(n, dtype=np.uint8)
     lib().oracle_mask_unpack(_p(b), n, _p(m))
     return m
+
+
+# ---- channel-wise symmetric quantisation (Section 3.2: Query, Key, Value) ----
+
+def channelwise_compress(bits: int, x_bits, tokens: int, hidden: int, scale_rule: int = RULE_PAPER):
+    """Returns (codes int8 [tokens*hidden], packed uint8, scale float32 [hidden])."""
+    x = _as_u16(x_bits)
+    n = tokens * hidden
+    assert x.size == n
+    codes = np.zeros(n, dtype=np.int8)
+    packed = np.zeros((n * bits + 7) // 8, dtype=np.uint8)
+    scale = np.zeros(hidden, dtype=np.float32)
+    cm = Method(bits=bits, quant_group=1, scale_rule=scale_rule).c()
+    if lib().oracle_channelwise_compress(ctypes.byref(cm), _p(x), tokens, hidden, _p(codes), _p(packed), _p(scale)) != 0:
+        raise ValueError("oracle: malformed method")
+    return codes, packed, scale
+
+
+def channelwise_decompress(bits: int, packed, scale, tokens: int, hidden: int):
+    """Returns (xhat_f32, xhat_bf16_bits)."""
+    n = tokens * hidden
+    f = np.zeros(n, dtype=np.float32)
+    b = np.zeros(n, dtype=np.uint16)
+    cm = Method(bits=bits, quant_group=1).c()
+    pk = np.ascontiguousarray(packed, dtype=np.uint8)
+    sc = np.ascontiguousarray(scale, dtype=np.float32)
+    if lib().oracle_channelwise_decompress(ctypes.byref(cm), _p(pk), _p(sc), tokens, hidden, _p(f), _p(b)) != 0:
+        raise ValueError("oracle: channel-wise decompress failed")
+    return f, b

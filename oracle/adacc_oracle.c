@@ -453,3 +453,54 @@ void oracle_mask_pack(const uint8_t *mask, size_t n, uint8_t *bits) {
 void oracle_mask_unpack(const uint8_t *bits, size_t n, uint8_t *mask) {
   for (size_t i = 0; i < n; ++i) mask[i] = (uint8_t)((bits[i / 8] >> (i % 8)) & 1u);
 }
+
+/* ====================================================================================
+ * Channel-wise symmetric quantisation (Section 3.2, list of layer-specific schemes: the scheme for
+ * the Query, Key and Value matrices).  The tensor is a row-major matrix of `tokens` rows and
+ * `hidden` channels; every channel (column) is one quantisation group of Eq. 2: S_h = max over the
+ * tokens of |x| / D, code = clip(round(x / S_h)).  The codes stay in the tensor's own memory order
+ * (no transposition, "no extra memory alignment is needed").  No outliers are separated; as in
+ * the other schemes a value that is not finite, or a negative zero, counts as zero.
+ * ==================================================================================== */
+int oracle_channelwise_compress(const oracle_method *m, const uint16_t *x, size_t tokens, size_t hidden,
+                                int8_t *codes, uint8_t *packed, float *scale) {
+  if ((m->bits != 4 && m->bits != 8) || m->asym || m->outlier_mode != ORACLE_OUT_NONE || hidden == 0) return -1;
+  const size_t n = tokens * hidden;
+  float *col = (float *)malloc((tokens ? tokens : 1) * sizeof(float));
+  int8_t *ccol = (int8_t *)malloc(tokens ? tokens : 1);
+  for (size_t h = 0; h < hidden; ++h) {
+    for (size_t t = 0; t < tokens; ++t) {
+      float f = bf16_to_f32(x[t * hidden + h]);
+      if (is_nonfinite_bf16(x[t * hidden + h]) || f == 0.0f) f = 0.0f;
+      col[t] = f;
+    }
+    quant_sym(m, col, tokens, ccol, scale + h); /* Eq. 2 with the channel as the group */
+    for (size_t t = 0; t < tokens; ++t) codes[t * hidden + h] = ccol[t];
+  }
+  if (packed) {
+    if (m->bits == 8) {
+      for (size_t i = 0; i < n; ++i) packed[i] = (uint8_t)codes[i];
+    } else {
+      for (size_t j = 0; j < (n + 1) / 2; ++j) {
+        int lo = codes[2 * j] & 0xF;
+        int hi = (2 * j + 1 < n) ? (codes[2 * j + 1] & 0xF) : 0;
+        packed[j] = (uint8_t)(lo | (hi << 4));
+      }
+    }
+  }
+  free(col);
+  free(ccol);
+  return 0;
+}
+
+/* X^ = code * S_h */
+int oracle_channelwise_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, size_t tokens,
+                                  size_t hidden, float *xhat_f32, uint16_t *xhat_bf16) {
+  if ((m->bits != 4 && m->bits != 8) || m->asym || hidden == 0) return -1;
+  for (size_t i = 0; i < tokens * hidden; ++i) {
+    float v = (float)unpack_code(m, packed, i) * scale[i % hidden];
+    if (xhat_f32) xhat_f32[i] = v;
+    if (xhat_bf16) xhat_bf16[i] = f32_to_bf16_rne(v);
+  }
+  return 0;
+}

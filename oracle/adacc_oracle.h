@@ -95,6 +95,15 @@ int oracle_channel_decompress(const oracle_method *m, const uint8_t *packed, con
                               const int32_t *ch_idx, const uint16_t *ch_val, size_t n_ch, size_t tokens,
                               size_t hidden, float *xhat_f32, uint16_t *xhat_bf16);
 
+/* ---- channel-wise symmetric quantisation (Section 3.2: the scheme for Query, Key and Value) ----
+ * x: row-major [tokens][hidden]; one scale per channel, S_h = max_t |x| / D (Eq. 2 with the channel as
+ * the group); codes in the tensor's own order.  m: bits, scale_rule; asym must be 0, outlier_mode NONE;
+ * quant_group is ignored.  scale [hidden]. */
+int oracle_channelwise_compress(const oracle_method *m, const uint16_t *x, size_t tokens, size_t hidden,
+                                int8_t *codes, uint8_t *packed, float *scale);
+int oracle_channelwise_decompress(const oracle_method *m, const uint8_t *packed, const float *scale, size_t tokens,
+                                  size_t hidden, float *xhat_f32, uint16_t *xhat_bf16);
+
 /* ---- dropout mask: byte format <-> bit format (Section 3.2), lossless ----
  * mask: n bytes, zero = dropped, non-zero = kept.  bits: ceil(n/8) bytes, element i in bit i%8 of
  * byte i/8, unused bits zero.  Unpacking writes bytes 0 and 1. */

@@ -586,3 +586,52 @@ def test_mask_bit_format_is_an_eighth_and_lossless():
     assert list(oracle.mask_pack(np.array([1, 0, 0, 1, 0, 0, 0, 0, 1], dtype=np.uint8))) == [0b00001001, 0b1]
     # any non-zero byte counts as kept and comes back as 1
     assert list(oracle.mask_unpack(oracle.mask_pack(np.array([255, 0, 2], dtype=np.uint8)), 3)) == [1, 0, 1]
+
+
+# ----------------------------------------------------------------- channel-wise symmetric quantisation (Section 3.2, Q/K/V)
+def test_channelwise_toy_vector_as_a_column():
+    """The vector printed with Eq. 2 placed in one channel of a [5, 3] matrix: that channel gets the
+    hand-worked scale and codes of the golden file whatever its neighbours hold."""
+    g = read_golden("eq2_symmetric_toy.txt")
+    col = np.array([float(v) for v in g["input"]], dtype=np.float32)
+    x = np.stack([col * 100.0, col, np.zeros(5, dtype=np.float32)], axis=1)  # [tokens=5, hidden=3]
+    codes, packed, scale = oracle.channelwise_compress(4, bf16_bits(x), 5, 3)
+    codes = codes.reshape(5, 3)
+    assert float(scale[1]) == float(g["scale"][0]) and codes[:, 1].tolist() == [int(v) for v in g["codes"]]
+    assert float(scale[0]) == 25.0 and codes[:, 0].tolist() == codes[:, 1].tolist()
+    assert float(scale[2]) == 0.0 and codes[:, 2].tolist() == [0] * 5
+    f, _ = oracle.channelwise_decompress(4, packed, scale, 5, 3)
+    assert f.reshape(5, 3)[:, 1].tolist() == [float(v) for v in g["dequant"]]
+
+
+@pytest.mark.parametrize("bits,rule", [(4, RULE_PAPER), (8, RULE_PAPER), (8, RULE_FULLRANGE)])
+def test_channelwise_is_group_quantisation_of_the_transposed_tensor(bits, rule):
+    """One scale per channel over all tokens = plain group quantisation (pinned above) of the
+    transposed matrix with one group per row; the transposition is numpy's."""
+    tokens, hidden = 96, 40
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((tokens, hidden)).astype(np.float32) * rng.lognormal(0, 1.5, size=hidden).astype(np.float32)
+    xb = bf16_bits(x).reshape(tokens, hidden)
+    xb[3, 5] = 0x7F80   # +Inf: counts as zero
+    xb[4, 5] = 0x8000   # -0
+    xb[:, 7] = 0        # an empty channel
+    codes, packed, scale = oracle.channelwise_compress(bits, xb, tokens, hidden, rule)
+    t = oracle.compress(Method(bits=bits, quant_group=tokens, scale_rule=rule), np.ascontiguousarray(xb.T))
+    assert np.array_equal(codes.reshape(tokens, hidden), t.codes.reshape(hidden, tokens).T)
+    assert np.array_equal(scale.view(np.uint32), t.scale.view(np.uint32))
+    # packing follows the tensor's own order
+    if bits == 8:
+        assert np.array_equal(packed.view(np.int8), codes)
+    else:
+        assert np.array_equal(packed & 0xF, codes[0::2].astype(np.uint8) & 0xF)
+        assert np.array_equal(packed >> 4, codes[1::2].astype(np.uint8) & 0xF)
+    f, b = oracle.channelwise_decompress(bits, packed, scale, tokens, hidden)
+    tf, tb = oracle.decompress(t)
+    assert np.array_equal(f.reshape(tokens, hidden).view(np.uint32), tf.reshape(hidden, tokens).T.view(np.uint32))
+    assert np.array_equal(b.reshape(tokens, hidden), tb.reshape(hidden, tokens).T)
+    # the error bound of Eq. 2 per channel: half a step, a whole step for the capped maximum
+    xf = bits_to_f32(xb.reshape(-1)).reshape(tokens, hidden)
+    xf[~np.isfinite(xf)] = 0.0
+    err = np.abs(f.reshape(tokens, hidden).astype(np.float64) - xf)
+    # (plus the binary32 rounding of S, D/max and code * S: well below a thousandth of a step)
+    assert np.all(err <= scale.astype(np.float64)[None, :] * ((1.0 if rule == RULE_PAPER else 0.5) + 1e-3) + 1e-30)
