@@ -219,6 +219,29 @@ int adacc_channel_decompress(const adacc_channel_method *method, const void *blo
 int adacc_channel_read_status(const void *blob, const adacc_channel_layout *layout, void *hip_stream,
                               uint32_t status_out[4]);
 
+/* ---- channel-wise symmetric quantisation: the scheme for the Query, Key and Value matrices
+ * (Section 3.2, list of layer-specific schemes) ----
+ * The tensor is a row-major matrix of `tokens` rows and `hidden` channels; every channel is one
+ * group of Eq. 2: S_h = max over the tokens of |x| / D, code = clip(round(x / S_h)), with D as
+ * scale_rule says.  The codes keep the tensor's own order (nothing is transposed); no outliers are
+ * separated; a value that is not finite counts as zero.  bits: 4 or 8.
+ * Blob: codes (tokens*hidden*bits/8 bytes, packed as in adacc_layout) and scales (hidden binary32),
+ * each on a 256-byte boundary.  Workspace: any 256-byte aligned device buffer of
+ * adacc_channelwise_workspace_bytes (chunk maxima and reciprocals), no initialisation.
+ * Limits: hidden a multiple of 8 in [8, 65536]; tokens * hidden < 2^32.
+ * tokens == 0: ADACC_OK, nothing is touched.  Errors: ENULL, EINVAL, ESIZE, EALIGN, EHIP. */
+typedef struct adacc_channelwise_layout {
+  uint64_t codes_off, scales_off, total_bytes;
+} adacc_channelwise_layout;
+int adacc_channelwise_layout_of(uint32_t bits, uint64_t tokens, uint32_t hidden, adacc_channelwise_layout *out);
+uint64_t adacc_channelwise_workspace_bytes(uint64_t tokens, uint32_t hidden);
+int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, const void *src, uint64_t tokens,
+                               uint32_t hidden, void *blob, uint64_t blob_bytes, void *workspace,
+                               uint64_t workspace_bytes, void *hip_stream);
+/* X^ = code * S_h; dst and dst_dtype as in adacc_decompress. */
+int adacc_channelwise_decompress(uint32_t bits, const void *blob, uint64_t blob_bytes, uint64_t tokens,
+                                 uint32_t hidden, void *dst, int dst_dtype, void *hip_stream);
+
 /* ---- dropout mask of attention layers: byte format <-> bit format, lossless (Section 3.2,
  * list of layer-specific schemes) ----
  * mask: n bytes, zero = dropped, anything else = kept (a torch.bool tensor is such an array).

@@ -24,7 +24,9 @@ EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "
            "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
            "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
            "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status",
-           "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack", "adacc_compressed_bytes")
+           "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack", "adacc_compressed_bytes",
+           "adacc_channelwise_layout_of", "adacc_channelwise_workspace_bytes", "adacc_channelwise_compress",
+           "adacc_channelwise_decompress")
 
 
 class CMethod(ctypes.Structure):
@@ -54,6 +56,10 @@ class CChannelMethod(ctypes.Structure):
 class CChannelLayout(ctypes.Structure):
     _fields_ = [(k, ctypes.c_uint64) for k in ("codes_off", "scales_off", "zp_off", "ch_mask_off", "ch_base_off",
                                                 "ch_idx_off", "ch_val_off", "status_off", "total_bytes")]
+
+
+class CChannelwiseLayout(ctypes.Structure):
+    _fields_ = [("codes_off", ctypes.c_uint64), ("scales_off", ctypes.c_uint64), ("total_bytes", ctypes.c_uint64)]
 
 
 @dataclass
@@ -154,6 +160,14 @@ def lib():
         L.adacc_mask_unpack.restype = ci
         L.adacc_compressed_bytes.argtypes = [pm, u64, u64]
         L.adacc_compressed_bytes.restype = u64
+        L.adacc_channelwise_layout_of.argtypes = [u32, u64, u32, ctypes.POINTER(CChannelwiseLayout)]
+        L.adacc_channelwise_layout_of.restype = ci
+        L.adacc_channelwise_workspace_bytes.argtypes = [u64, u32]
+        L.adacc_channelwise_workspace_bytes.restype = u64
+        L.adacc_channelwise_compress.argtypes = [u32, u32, vp, u64, u32, vp, u64, vp, u64, vp]
+        L.adacc_channelwise_compress.restype = ci
+        L.adacc_channelwise_decompress.argtypes = [u32, vp, u64, u64, u32, vp, ci, vp]
+        L.adacc_channelwise_decompress.restype = ci
         L.adacc_version.argtypes = []
         L.adacc_version.restype = ctypes.c_char_p
         _lib = L
@@ -385,6 +399,41 @@ def channel_blob_sections(blob, layout: CChannelLayout, method: ChannelMethod, t
     if method.asym:
         sec["zp"] = view(layout.zp_off, 4 * groups, torch.float32)
     return sec
+
+
+# ---------------------------------------------------------------- channel-wise symmetric quantisation (Q / K / V)
+def channelwise_layout_of(bits: int, tokens: int, hidden: int) -> CChannelwiseLayout:
+    L = CChannelwiseLayout()
+    _check(lib().adacc_channelwise_layout_of(bits, tokens, hidden, ctypes.byref(L)), "adacc_channelwise_layout_of")
+    return L
+
+
+def channelwise_workspace_bytes(tokens: int, hidden: int) -> int:
+    return int(lib().adacc_channelwise_workspace_bytes(tokens, hidden))
+
+
+def channelwise_compress(bits: int, src, tokens: int, hidden: int, blob, workspace, scale_rule=SCALE_PAPER, stream=None):
+    _check(lib().adacc_channelwise_compress(bits, scale_rule, _ptr(src), tokens, hidden, _ptr(blob), _nbytes(blob),
+                                            _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "adacc_channelwise_compress")
+
+
+def channelwise_decompress(bits: int, blob, tokens: int, hidden: int, dst, stream=None):
+    import torch
+    if dst.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("dst must be bfloat16 or float32")
+    dtype = DST_F32 if dst.dtype == torch.float32 else DST_BF16
+    _check(lib().adacc_channelwise_decompress(bits, _ptr(blob), _nbytes(blob), tokens, hidden, _ptr(dst), dtype,
+                                              _stream(stream)), "adacc_channelwise_decompress")
+
+
+def alloc_channelwise(bits: int, tokens: int, hidden: int, device="cuda"):
+    """(blob, layout, workspace) for one tensor."""
+    import torch
+    L = channelwise_layout_of(bits, tokens, hidden)
+    blob = torch.empty(int(L.total_bytes), dtype=torch.uint8, device=device)
+    ws = torch.empty(max(channelwise_workspace_bytes(tokens, hidden), 256), dtype=torch.uint8, device=device)
+    return blob, L, ws
 
 
 # ---------------------------------------------------------------- dropout mask, byte <-> bit (Section 3.2)

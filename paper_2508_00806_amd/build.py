@@ -15,6 +15,7 @@ SOURCES = [os.path.join(CSRC, f) for f in (
     "adacc_k_batch4.hip", "adacc_k_batch8.hip",
     "adacc_k_channel.hip",    # outlier channels by Z-score
     "adacc_k_mask.hip",       # dropout mask, byte <-> bit
+    "adacc_k_channelwise.hip",  # channel-wise symmetric quantisation (Q / K / V)
 )]
 HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_compress.hpp", "adacc_decompress.hpp",
                                            "adacc_kernels.hpp", "adacc_fn.hpp", "adacc_channel.hpp")]

@@ -752,6 +752,107 @@ int adacc_channel_read_status(const void* blob, const adacc_channel_layout* layo
   return e == hipSuccess ? ADACC_OK : hip_fail(e, "hipStreamSynchronize");
 }
 
+// ---- channel-wise symmetric quantisation (Section 3.2, Query / Key / Value)
+static bool channelwise_sizes_ok(uint32_t bits, uint64_t tokens, uint32_t hidden) {
+  if (bits != 4 && bits != 8) return false;
+  if (hidden < 8 || hidden > 65536 || hidden % 8 != 0) return false;
+  return tokens <= 0xFFFFFFFFull / hidden;
+}
+
+static void channelwise_layout(uint32_t bits, uint64_t tokens, uint32_t hidden, adacc_channelwise_layout* L) {
+  L->codes_off = 0;
+  L->scales_off = align256(tokens * hidden * bits / 8);
+  L->total_bytes = L->scales_off + align256(4ull * hidden);
+}
+
+static uint64_t channelwise_partial_bytes(uint64_t tokens, uint32_t hidden) {
+  return align256(2ull * ((tokens + kChunkTokens - 1) / kChunkTokens) * hidden);
+}
+
+int adacc_channelwise_layout_of(uint32_t bits, uint64_t tokens, uint32_t hidden, adacc_channelwise_layout* out) {
+  if (!out) return ADACC_ENULL;
+  if (!channelwise_sizes_ok(bits, tokens, hidden)) return ADACC_EINVAL;
+  channelwise_layout(bits, tokens, hidden, out);
+  return ADACC_OK;
+}
+
+uint64_t adacc_channelwise_workspace_bytes(uint64_t tokens, uint32_t hidden) {
+  if (!channelwise_sizes_ok(8, tokens, hidden)) return 0;
+  return channelwise_partial_bytes(tokens, hidden) + align256(4ull * hidden);
+}
+
+static void channelwise_desc(uint32_t bits, uint32_t scale_rule, uint64_t tokens, uint32_t hidden,
+                             const adacc_channelwise_layout& L, void* blob, ChannelwiseDesc* c) {
+  std::memset(c, 0, sizeof *c);
+  unsigned char* b = static_cast<unsigned char*>(blob);
+  c->codes = b + L.codes_off;
+  c->scales = reinterpret_cast<float*>(b + L.scales_off);
+  c->numel = tokens * hidden;
+  c->tokens = (uint32_t)tokens;
+  c->hidden = hidden;
+  c->n_chunks = (uint32_t)((tokens + kChunkTokens - 1) / kChunkTokens);
+  const float q = (float)(1u << (bits - 1));
+  c->divisor = scale_rule == ADACC_SCALE_PAPER ? q : q - 1.0f;
+  c->inv_divisor = scale_rule == ADACC_SCALE_PAPER ? 1.0f / q : 0.0f;  // exact for a power of two
+  c->inv_hidden = std::nextafter(std::nextafter(1.0f / (float)hidden, 0.0f), 0.0f);
+}
+
+int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, const void* src, uint64_t tokens, uint32_t hidden,
+                               void* blob, uint64_t blob_bytes, void* workspace, uint64_t workspace_bytes,
+                               void* hip_stream) {
+  if (!channelwise_sizes_ok(bits, tokens, hidden) || scale_rule > 1) return ADACC_EINVAL;
+  if (tokens == 0) return ADACC_OK;
+  if (!src || !blob || !workspace) return ADACC_ENULL;
+  adacc_channelwise_layout L;
+  channelwise_layout(bits, tokens, hidden, &L);
+  if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
+  if (workspace_bytes < adacc_channelwise_workspace_bytes(tokens, hidden)) return ADACC_ESIZE;
+  if (misaligned(src, 16) || misaligned(blob, 256) || misaligned(workspace, 256)) return ADACC_EALIGN;
+  ChannelwiseDesc c;
+  channelwise_desc(bits, scale_rule, tokens, hidden, L, blob, &c);
+  c.src = static_cast<const uint16_t*>(src);
+  c.partial = static_cast<uint16_t*>(workspace);
+  c.inv = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + channelwise_partial_bytes(tokens, hidden));
+  ChannelwiseFn quant = channelwise_quantise_fn(bits);
+  const uint32_t n_tiles = (uint32_t)((c.numel + 2047ull) / 2048ull);
+  uint32_t grid = 0;
+  int rc = grid_for(n_tiles, reinterpret_cast<const void*>(quant), 2u, &grid);
+  if (rc != ADACC_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint32_t n_items = c.n_chunks * (hidden / 8);
+  hipLaunchKernelGGL(channelwise_partial_fn(), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s, c, n_items);
+  rc = launch_check("channelwise_partial_kernel");
+  if (rc != ADACC_OK) return rc;
+  const uint32_t per_wg = channelwise_fold_octets();
+  hipLaunchKernelGGL(channelwise_fold_fn(), dim3((hidden / 8 + per_wg - 1) / per_wg), dim3(kThreads), 0, s, c);
+  rc = launch_check("channelwise_fold_kernel");
+  if (rc != ADACC_OK) return rc;
+  hipLaunchKernelGGL(quant, dim3(grid), dim3(kThreads), 0, s, c);
+  return launch_check("channelwise_quantise_kernel");
+}
+
+int adacc_channelwise_decompress(uint32_t bits, const void* blob, uint64_t blob_bytes, uint64_t tokens, uint32_t hidden,
+                                 void* dst, int dst_dtype, void* hip_stream) {
+  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  if (!channelwise_sizes_ok(bits, tokens, hidden)) return ADACC_EINVAL;
+  if (tokens == 0) return ADACC_OK;
+  if (!blob || !dst) return ADACC_ENULL;
+  adacc_channelwise_layout L;
+  channelwise_layout(bits, tokens, hidden, &L);
+  if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
+  if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
+  ChannelwiseDesc c;
+  channelwise_desc(bits, 0, tokens, hidden, L, const_cast<void*>(blob), &c);
+  c.dst = dst;
+  ChannelwiseFn fn = channelwise_dequantise_fn(bits, dst_dtype == ADACC_DST_F32);
+  const uint32_t n_tiles = (uint32_t)((c.numel + 2047ull) / 2048ull);
+  uint32_t grid = 0;
+  const int rc = grid_for(n_tiles, reinterpret_cast<const void*>(fn), 1u, &grid);
+  if (rc != ADACC_OK) return rc;
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), c);
+  return launch_check("channelwise_dequantise_kernel");
+}
+
 uint64_t adacc_mask_packed_bytes(uint64_t n) { return (n + 7u) / 8u; }
 
 static int mask_launch(MaskFn fn, const void* in, uint64_t n, void* out, void* hip_stream, const char* what) {

@@ -70,6 +70,20 @@ struct ChannelDesc {
   float inv_hidden;     // 1 / hidden rounded towards zero twice: never above the true reciprocal
 };
 
+// Channel-wise symmetric quantisation (Section 3.2, the Query / Key / Value scheme): one scale per channel.
+struct ChannelwiseDesc {
+  const uint16_t* src;  // compress: bf16 input [tokens][hidden]
+  void* dst;            // decompress: output
+  uint8_t* codes;
+  float* scales;        // [hidden], S_h of Eq. 2
+  float* inv;           // workspace [hidden]: D / max_h
+  uint16_t* partial;    // workspace [n_chunks][hidden]: chunk maxima of the finite magnitudes
+  uint64_t numel;
+  uint32_t tokens, hidden, n_chunks;
+  float divisor, inv_divisor;  // D of Eq. 2 and, when D is a power of two, 1/D (else 0)
+  float inv_hidden;     // 1 / hidden rounded towards zero twice
+};
+
 // Scan workspace: one 64-bit state word per run of tiles and one per block of 64 runs, high half
 // = (epoch << 2) | flag, low half = value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
 // words written by earlier launches carry another epoch and read as empty, so the buffer is

@@ -32,6 +32,15 @@ uint32_t channel_score_channels();  // channels per workgroup of the score kerne
 ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);
 ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);
 
+// channel-wise symmetric quantisation (Section 3.2, Query / Key / Value)
+typedef void (*ChannelwiseItemsFn)(ChannelwiseDesc, uint32_t);
+typedef void (*ChannelwiseFn)(ChannelwiseDesc);
+ChannelwiseItemsFn channelwise_partial_fn();
+ChannelwiseFn channelwise_fold_fn();
+uint32_t channelwise_fold_octets();  // octets of channels per workgroup of the fold kernel
+ChannelwiseFn channelwise_quantise_fn(uint32_t bits);
+ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32);
+
 // dropout mask, byte format <-> bit format (Section 3.2)
 typedef void (*MaskFn)(const uint8_t*, uint64_t, uint8_t*);
 MaskFn mask_pack_fn();

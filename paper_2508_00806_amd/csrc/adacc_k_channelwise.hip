@@ -1,0 +1,242 @@
+// Channel-wise symmetric quantisation (Section 3.2, list of layer-specific schemes: the scheme for the
+// Query, Key and Value matrices).  The tensor is a row-major matrix [tokens][hidden]; every channel
+// (column) is one group of Eq. 2: S_h = max over the tokens of |x| / D, code = clip(round(x / S_h)).
+// Codes stay in the tensor's own order: nothing is transposed.
+//
+// Three kernels: maxima of |x| over chunks of 64 tokens, their fold into S_h and D / max, and the
+// quantisation proper.  A maximum does not depend on the order it is taken in, so unlike the sums of
+// the outlier-channel statistics nothing here has an order to keep.
+#include "adacc_common.hpp"
+#include "adacc_compress.hpp"
+#include "adacc_decompress.hpp"
+#include "adacc_fn.hpp"
+
+namespace adacc {
+
+// magnitudes (15 low bits) of two bf16 values; one that is not finite counts as zero
+__device__ __forceinline__ uint32_t finite_magnitudes2(uint32_t w) {
+  const uint32_t mag = w & 0x7FFF7FFFu;
+  const uint32_t nf = ((mag + 0x00800080u) >> 15) & 0x00010001u;  // magnitude >= 0x7F80: bit 15 after the add
+  return mag & ~(nf * 0xFFFFu);
+}
+
+// ---- step 1: partial[chunk][hidden] = max of the finite magnitudes over the chunk's tokens.
+// Same decomposition as the chunk sums of the outlier-channel statistics: a lane owns 8 adjacent
+// channels of one chunk, 16 loads of 16 bytes in flight, rows fully coalesced.
+__global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(ChannelwiseDesc c, uint32_t n_items) {
+  const uint32_t octs = c.hidden / kOct;
+  for (uint32_t item = blockIdx.x * kThreads + threadIdx.x; item < n_items; item += gridDim.x * kThreads) {
+    const uint32_t chunk = item / octs;
+    const uint32_t oct = item - chunk * octs;
+    const uint32_t t0 = chunk * kChunkTokens;
+    const uint32_t rows = c.tokens - t0 < kChunkTokens ? c.tokens - t0 : kChunkTokens;
+    const uint16_t* p = c.src + (size_t)t0 * c.hidden + (size_t)oct * kOct;
+    uint32_t acc[4] = {0u, 0u, 0u, 0u};
+    constexpr uint32_t kBatch = 16;
+    uint32_t r = 0;
+    for (; r + kBatch <= rows; r += kBatch) {
+      uint4 v[kBatch];
+#pragma unroll
+      for (uint32_t i = 0; i < kBatch; ++i) v[i] = *reinterpret_cast<const uint4*>(p + (size_t)(r + i) * c.hidden);
+#pragma unroll
+      for (uint32_t i = 0; i < kBatch; ++i) {
+        acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v[i].x));
+        acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v[i].y));
+        acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v[i].z));
+        acc[3] = pk_max_u16(acc[3], finite_magnitudes2(v[i].w));
+      }
+    }
+    for (; r < rows; ++r) {
+      const uint4 v = *reinterpret_cast<const uint4*>(p + (size_t)r * c.hidden);
+      acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v.x));
+      acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v.y));
+      acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v.z));
+      acc[3] = pk_max_u16(acc[3], finite_magnitudes2(v.w));
+    }
+    *reinterpret_cast<uint4*>(c.partial + (size_t)chunk * c.hidden + (size_t)oct * kOct) =
+        make_uint4(acc[0], acc[1], acc[2], acc[3]);
+  }
+}
+
+// ---- step 2: fold the chunk maxima; Eq. 2: S_h = max / D, and the reciprocal D / max the codes are
+// formed with.  A workgroup takes 16 octets of channels; 16 of its threads share the chunks of an octet.
+constexpr int kFoldOcts = 16;
+constexpr int kFoldParts = kThreads / kFoldOcts;
+__global__ __launch_bounds__(kThreads) void channelwise_fold_kernel(ChannelwiseDesc c) {
+  __shared__ uint4 part[kFoldParts][kFoldOcts];
+  const uint32_t o = threadIdx.x % kFoldOcts;
+  const uint32_t k = threadIdx.x / kFoldOcts;
+  const uint32_t oct = blockIdx.x * kFoldOcts + o;
+  const bool live = oct < c.hidden / kOct;
+  uint32_t acc[4] = {0u, 0u, 0u, 0u};
+  if (live) {
+    for (uint32_t ch0 = k; ch0 < c.n_chunks; ch0 += kFoldParts * 8u) {
+      uint4 v[8];
+#pragma unroll
+      for (uint32_t i = 0; i < 8u; ++i) {
+        const uint32_t ch = ch0 + i * kFoldParts;
+        v[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (ch < c.n_chunks) v[i] = *reinterpret_cast<const uint4*>(c.partial + (size_t)ch * c.hidden + (size_t)oct * kOct);
+      }
+#pragma unroll
+      for (uint32_t i = 0; i < 8u; ++i) {
+        acc[0] = pk_max_u16(acc[0], v[i].x); acc[1] = pk_max_u16(acc[1], v[i].y);
+        acc[2] = pk_max_u16(acc[2], v[i].z); acc[3] = pk_max_u16(acc[3], v[i].w);
+      }
+    }
+  }
+  part[k][o] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
+  __syncthreads();
+  if (k == 0 && live) {
+#pragma unroll
+    for (int i = 1; i < kFoldParts; ++i) {
+      const uint4 v = part[i][o];
+      acc[0] = pk_max_u16(acc[0], v.x); acc[1] = pk_max_u16(acc[1], v.y);
+      acc[2] = pk_max_u16(acc[2], v.z); acc[3] = pk_max_u16(acc[3], v.w);
+    }
+    float scl[kOct], inv[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      const float am = (e & 1) ? widen_hi(acc[e >> 1]) : widen_lo(acc[e >> 1]);  // the magnitude is the value's absolute
+      scl[e] = c.inv_divisor != 0.0f ? am * c.inv_divisor : am / c.divisor;
+      inv[e] = (am != 0.0f) ? fminf(c.divisor / am, kFltMax) : 0.0f;
+    }
+    float4* sp = reinterpret_cast<float4*>(c.scales + (size_t)oct * kOct);
+    float4* ip = reinterpret_cast<float4*>(c.inv + (size_t)oct * kOct);
+    sp[0] = make_float4(scl[0], scl[1], scl[2], scl[3]); sp[1] = make_float4(scl[4], scl[5], scl[6], scl[7]);
+    ip[0] = make_float4(inv[0], inv[1], inv[2], inv[3]); ip[1] = make_float4(inv[4], inv[5], inv[6], inv[7]);
+  }
+}
+
+// channel of an element offset: off = q * hidden + col, through a reciprocal the host rounded down
+__device__ __forceinline__ uint32_t column_of(uint32_t off, uint32_t hidden, float inv_hidden) {
+  const uint32_t q = (uint32_t)((float)off * inv_hidden);
+  uint32_t col = off - __umul24(q, hidden);
+  if (col >= hidden) col -= hidden;
+  return col;
+}
+
+// ---- step 3: code = clip(round(x * (D / max_h))), packed, in the tensor's own order.  Tiles of 2048
+// elements, one per wavefront at a time; a lane's 8 elements are 8 adjacent channels of one token.
+template <int BITS>
+__global__ __launch_bounds__(kThreads) void channelwise_quantise_kernel(ChannelwiseDesc c) {
+  constexpr int E = 4;
+  constexpr int Q = 1 << (BITS - 1);
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane_off = (uint32_t)lane_id() * kOct;
+  const uint32_t n_tiles = (uint32_t)((c.numel + (E * kRow - 1)) / (E * kRow));
+  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < n_tiles; t += gridDim.x * kWavesPerWg) {
+    const uint32_t base = t * (uint32_t)(E * kRow);  // numel < 2^32
+    const uint32_t left = (uint32_t)(c.numel - base);
+    const uint32_t rem = left < (uint32_t)(E * kRow) ? left : (uint32_t)(E * kRow);
+    const uint32_t col0 = base % c.hidden;
+    uint4 raw[E];
+    float4 inv[E][2];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {  // every load of the tile before its first store
+      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
+      const uint32_t off = in_tile < rem ? in_tile : 0u;  // octets past the end re-read the first one
+      raw[j] = *reinterpret_cast<const uint4*>(c.src + (size_t)base + off);
+      const uint32_t col = column_of(col0 + off, c.hidden, c.inv_hidden);
+      inv[j][0] = *reinterpret_cast<const float4*>(c.inv + col);
+      inv[j][1] = *reinterpret_cast<const float4*>(c.inv + col + 4);
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
+      if (in_tile >= rem) continue;
+      const uint32_t w[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+      const float iv[kOct] = {inv[j][0].x, inv[j][0].y, inv[j][0].z, inv[j][0].w,
+                              inv[j][1].x, inv[j][1].y, inv[j][1].z, inv[j][1].w};
+      uint32_t code[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        float x = ADACC_ELEM_F32(w, e);
+        if (is_nonfinite(x)) x = 0.0f;  // counts as zero
+        code[e] = code_bits<Q>(x, iv[e]);
+      }
+      const size_t e0 = (size_t)base + in_tile;
+      if constexpr (BITS == 8) {
+        uint2 o;
+        o.x = pack_bytes4(code[0], code[1], code[2], code[3]);
+        o.y = pack_bytes4(code[4], code[5], code[6], code[7]);
+        *reinterpret_cast<uint2*>(c.codes + e0) = o;
+      } else {
+        *reinterpret_cast<uint32_t*>(c.codes + (e0 >> 1)) = pack_nibbles8(code);
+      }
+    }
+  }
+}
+
+// ---- decompression: X^ = code * S_h
+template <int BITS, bool F32>
+__global__ __launch_bounds__(kThreads) void channelwise_dequantise_kernel(ChannelwiseDesc c) {
+  constexpr int E = 4;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t lane_off = (uint32_t)lane_id() * kOct;
+  const uint32_t n_tiles = (uint32_t)((c.numel + (E * kRow - 1)) / (E * kRow));
+  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < n_tiles; t += gridDim.x * kWavesPerWg) {
+    const uint32_t base = t * (uint32_t)(E * kRow);
+    const uint32_t left = (uint32_t)(c.numel - base);
+    const uint32_t rem = left < (uint32_t)(E * kRow) ? left : (uint32_t)(E * kRow);
+    const uint32_t col0 = base % c.hidden;
+    uint32_t cw[E][2];
+    float4 sc[E][2];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
+      const uint32_t off = in_tile < rem ? in_tile : 0u;
+      const size_t e0 = (size_t)base + off;
+      if constexpr (BITS == 8) {
+        const uint2 w = *reinterpret_cast<const uint2*>(c.codes + e0);
+        cw[j][0] = w.x; cw[j][1] = w.y;
+      } else {
+        cw[j][0] = *reinterpret_cast<const uint32_t*>(c.codes + (e0 >> 1));
+        cw[j][1] = 0u;
+      }
+      const uint32_t col = column_of(col0 + off, c.hidden, c.inv_hidden);
+      sc[j][0] = *reinterpret_cast<const float4*>(c.scales + col);
+      sc[j][1] = *reinterpret_cast<const float4*>(c.scales + col + 4);
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
+      if (in_tile >= rem) continue;
+      const size_t e0 = (size_t)base + in_tile;
+      const float s[kOct] = {sc[j][0].x, sc[j][0].y, sc[j][0].z, sc[j][0].w, sc[j][1].x, sc[j][1].y, sc[j][1].z, sc[j][1].w};
+      float v[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        int code;
+        if constexpr (BITS == 8) code = (int)(int8_t)((cw[j][e >> 2] >> (8 * (e & 3))) & 0xFFu);
+        else code = ((int)(cw[j][0] << (28 - 4 * e))) >> 28;
+        v[e] = (float)code * s[e];
+      }
+      if constexpr (F32) {
+        float4* p = reinterpret_cast<float4*>(reinterpret_cast<float*>(c.dst) + e0);
+        p[0] = make_float4(v[0], v[1], v[2], v[3]);
+        p[1] = make_float4(v[4], v[5], v[6], v[7]);
+      } else {
+        uint4 w;
+        w.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
+        w.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
+        w.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
+        w.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(c.dst) + e0) = w;
+      }
+    }
+  }
+}
+
+ChannelwiseItemsFn channelwise_partial_fn() { return channelwise_partial_kernel; }
+ChannelwiseFn channelwise_fold_fn() { return channelwise_fold_kernel; }
+uint32_t channelwise_fold_octets() { return (uint32_t)kFoldOcts; }
+ChannelwiseFn channelwise_quantise_fn(uint32_t bits) {
+  return bits == 4 ? channelwise_quantise_kernel<4> : channelwise_quantise_kernel<8>;
+}
+ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32) {
+  if (bits == 4) return f32 ? channelwise_dequantise_kernel<4, true> : channelwise_dequantise_kernel<4, false>;
+  return f32 ? channelwise_dequantise_kernel<8, true> : channelwise_dequantise_kernel<8, false>;
+}
+
+}  // namespace adacc

@@ -268,3 +268,29 @@ def test_compressed_bytes_against_the_oracle_and_the_closed_form(L):
     assert adacc.compressed_bytes(plain, n, 0) / (2 * n) == 0.25 + 1 / 64
     assert adacc.compressed_bytes(adacc.NOOP, n, 0) == 2 * n
     assert adacc.compressed_bytes(Method(bits=5), n, 0) == 0
+
+
+# ----------------------------------------------------------------- channel-wise symmetric quantisation
+def test_channelwise_layout_and_validation(L):
+    assert ctypes.sizeof(adacc.CChannelwiseLayout) == 24
+    a = lambda v: (v + 255) // 256 * 256
+    lay = adacc.channelwise_layout_of(4, 100, 2048)
+    assert (lay.codes_off, lay.scales_off, lay.total_bytes) == (0, a(100 * 2048 // 2), a(100 * 2048 // 2) + a(4 * 2048))
+    assert adacc.channelwise_workspace_bytes(100, 2048) == a(2 * 2 * 2048) + a(4 * 2048)
+    for bits, tokens, hidden in ((5, 10, 64), (8, 10, 60), (8, 10, 0), (8, 1 << 27, 64), (8, 10, 65544)):
+        with pytest.raises(adacc.AdaccError):
+            adacc.channelwise_layout_of(bits, tokens, hidden)
+    f = L.adacc_channelwise_compress
+    src, blob, ws = 0x10000, 0x20000, 0x30000
+    tb, wb = lay.total_bytes, adacc.channelwise_workspace_bytes(100, 2048)
+    assert f(4, 0, None, 100, 2048, blob, tb, ws, wb, None) == adacc.ENULL
+    assert f(4, 0, src, 100, 2048, blob, tb - 1, ws, wb, None) == adacc.ESIZE
+    assert f(4, 0, src, 100, 2048, blob, tb, ws, wb - 1, None) == adacc.ESIZE
+    assert f(4, 0, src + 8, 100, 2048, blob, tb, ws, wb, None) == adacc.EALIGN
+    assert f(4, 2, src, 100, 2048, blob, tb, ws, wb, None) == adacc.EINVAL
+    assert f(4, 0, None, 0, 2048, None, 0, None, 0, None) == adacc.OK
+    g = L.adacc_channelwise_decompress
+    assert g(4, blob, tb, 100, 2048, None, 0, None) == adacc.ENULL
+    assert g(4, blob, tb, 100, 2048, 0x40000, 3, None) == adacc.EINVAL
+    assert g(4, blob, tb - 1, 100, 2048, 0x40000, 0, None) == adacc.ESIZE
+    assert g(4, blob, tb, 100, 2048, 0x40004, 0, None) == adacc.EALIGN
