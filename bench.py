@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--only-channelwise", action="store_true",
+                    help="run only the channel-wise (Q/K/V) quantisation measurement and print its JSON")
     ap.add_argument("--only-mask", action="store_true",
                     help="run only the dropout-mask (byte <-> bit) measurement and print its JSON")
     ap.add_argument("--only-channel", action="store_true",
@@ -279,6 +281,65 @@ def run_channel_mode(steps=50, warmup=5, cpu_rows=2048):
     }
 
 
+def run_channelwise(steps=50, warmup=5, cpu_rows=2048):
+    """Channel-wise symmetric int4 quantisation (Section 3.2, the Query / Key / Value scheme) of the
+    C2-shaped tensor.  Compression reads the tensor twice (channel maxima, then quantisation):
+    algorithmic bytes 4N + N/2 + 4*hidden; decompression 2N + N/2 + 4*hidden."""
+    import torch
+    import workloads
+    import oracle
+    import paper_2508_00806_amd as adacc
+    from helpers import bits_of
+    x = workloads.make("c2", "cuda")
+    tokens, hidden = x.shape
+    n = tokens * hidden
+    sets = 4
+    xs = [x if i == 0 else x.clone() for i in range(sets)]
+    bufs = [adacc.alloc_channelwise(4, tokens, hidden) for _ in range(sets)]
+    dsts = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(sets)]
+    ws = bufs[0][2]
+
+    def comp(i):
+        adacc.channelwise_compress(4, xs[i % sets], tokens, hidden, bufs[i % sets][0], ws)
+
+    def dec(i):
+        adacc.channelwise_decompress(4, bufs[i % sets][0], tokens, hidden, dsts[i % sets])
+    for i in range(sets + warmup):
+        comp(i)
+        dec(i)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        ev[i][0].record()
+        comp(i)
+        ev[i][1].record()
+        dec(i + 2)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    c_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    d_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    outputs = n // 2 + 4 * hidden
+    alg_c, alg_d = 4 * n + outputs, 2 * n + outputs
+    xb = bits_of(x[:cpu_rows].cpu())
+    t0 = time.perf_counter()
+    _, packed, scale = oracle.channelwise_compress(4, xb, cpu_rows, hidden)
+    oracle.channelwise_decompress(4, packed, scale, cpu_rows, hidden)
+    el = time.perf_counter() - t0
+    del xs, bufs, dsts
+    torch.cuda.empty_cache()
+    return {
+        "workload": f"channel-wise symmetric int4 (Q/K/V scheme) on the c2 tensor [{tokens},{hidden}] bf16",
+        "compress": {"ms": c_ms, "kernels": 3, "algorithmic_bytes": alg_c, "hbm_GBps": alg_c / (c_ms * 1e-3) / 1e9,
+                     "frac_of_peak": alg_c / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "activation_GBps": 2.0 * n / (c_ms * 1e-3) / 1e9},
+        "decompress": {"ms": d_ms, "kernels": 1, "algorithmic_bytes": alg_d, "hbm_GBps": alg_d / (d_ms * 1e-3) / 1e9,
+                       "frac_of_peak": alg_d / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                       "activation_GBps": 2.0 * n / (d_ms * 1e-3) / 1e9},
+        "cpu_oracle": {"value": 4.0 * cpu_rows * hidden / el / 1e9, "unit": "GB/s", "cores": 1,
+                       "sample": f"first {cpu_rows} rows, compress+decompress once in {el:.2f} s"},
+    }
+
+
 def run_mask(steps=30, warmup=3):
     """Dropout mask of the attention layer of C4 ([4,32,2048,2048] bytes, keep probability 0.9):
     byte format -> bit format and back (Section 3.2).  Algorithmic bytes per direction: n + n/8."""
@@ -367,6 +428,9 @@ def main():
     adacc.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
 
+    if a.only_channelwise:
+        print(json.dumps({"channelwise_qkv": run_channelwise()}))
+        return
     if a.only_mask:
         print(json.dumps({"dropout_mask": run_mask()}))
         return
@@ -384,6 +448,7 @@ def main():
             extras.append(run_workload(name, k, 5, a.sets))
     channel = None if a.no_extras else run_channel_mode()
     mask = None if a.no_extras else run_mask()
+    channelwise = None if a.no_extras else run_channelwise()
     cpu = None if a.no_cpu else cpu_baseline(a.workload, a.cpu_seconds)
 
     dom = "compress" if main_res["compress"]["ms"] >= main_res["decompress"]["ms"] else "decompress"
@@ -422,6 +487,7 @@ def main():
         "other_workloads": extras,
         "channel_zscore": channel,
         "dropout_mask": mask,
+        "channelwise_qkv": channelwise,
     }
     print(json.dumps(out))
 
