@@ -15,7 +15,7 @@ import torch
 
 from . import (ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
                alloc_channel_workspace, alloc_workspace, channel_compress, channel_decompress,
-               channel_read_status, channel_workspace_bytes, compress, compressed_bytes, decompress, read_status, workspace_bytes)
+               channel_workspace_bytes, compress, compressed_bytes, decompress, workspace_bytes)
 
 
 class _Saved:
@@ -77,10 +77,11 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
             compress(m, t, blob, ws)
         if ev:
             ev[1].record()
+        # the record keeps a copy of the 16 status bytes, not the blob: the compressed activation is
+        # freed as soon as autograd drops it
+        rec["status"] = blob[layout.status_off:layout.status_off + 16].clone()
         self.records.append(rec)
-        saved = _Saved(m, blob, layout, t.shape, numel, rec)
-        rec["_saved"] = saved
-        return saved
+        return _Saved(m, blob, layout, t.shape, numel, rec)
 
     def _unpack(self, s):
         if not isinstance(s, _Saved):
@@ -112,16 +113,14 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
         torch.cuda.synchronize()
         rows = []
         for rec in self.records:
-            s = rec["_saved"]
             m = rec["method"]
+            st = rec["status"].view(torch.int32).cpu().tolist()
             if isinstance(m, ChannelMethod):
                 hidden = rec["shape"][-1]
                 tokens = rec["numel"] // hidden
-                st = channel_read_status(s.blob, s.layout)
                 plain = Method(bits=m.bits, quant_group=m.quant_group, asym=m.asym, scale_rule=m.scale_rule)
                 comp = compressed_bytes(plain, rec["numel"], 0) + st[0] * (2 * tokens + 4)
             else:
-                st = read_status(s.blob, s.layout)
                 comp = compressed_bytes(m, rec["numel"], st[0])
             row = {"shape": rec["shape"], "numel": rec["numel"], "n_outliers": st[0], "overflow": bool(st[1]),
                    "original_bytes": 2 * rec["numel"], "compressed_bytes": comp,
