@@ -523,6 +523,9 @@ def test_channel_selection_degenerate_cases():
     S[7] = 1e6
     got, mu, sigma = oracle.channel_select(S, 3.0)
     assert list(np.nonzero(got)[0]) == [4, 7]
+    S[9] = np.nan  # a NaN sum (a NaN in the channel) has no Z at all and is kept whole all the same
+    got, mu, sigma = oracle.channel_select(S, 3.0)
+    assert list(np.nonzero(got)[0]) == [4, 7, 9] and np.isfinite(mu) and np.isfinite(sigma)
 
 
 @pytest.mark.parametrize("bits,asym", [(4, 0), (8, 0), (4, 1), (8, 1)])
