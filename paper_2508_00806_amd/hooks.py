@@ -8,6 +8,9 @@ R_{i,t} of Section 3.3, whose inputs are the compression rate CRate_i and the ti
 `torch.autograd.graph.saved_tensors_hooks` context that does exactly that with libadacc, and keeps
 those three figures per saved tensor.
 
+Dropout masks (`torch.bool` tensors saved for the backward pass) are kept in bit format, the
+fourth of the layer-specific schemes of Section 3.2, when `pack_masks` is set.
+
 Plumbing only: the hooks allocate buffers and call the library; every step of compression and
 decompression runs in the HIP kernels.  A tensor the policy does not cover is saved as it is.
 """
@@ -15,7 +18,8 @@ import torch
 
 from . import (ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
                alloc_channel_workspace, alloc_workspace, channel_compress, channel_decompress,
-               channel_workspace_bytes, compress, compressed_bytes, decompress, workspace_bytes)
+               channel_workspace_bytes, compress, compressed_bytes, decompress, mask_pack, mask_packed_bytes, mask_unpack,
+               workspace_bytes)
 
 
 class _Saved:
@@ -24,6 +28,14 @@ class _Saved:
 
     def __init__(self, method, blob, layout, shape, numel, record):
         self.method, self.blob, self.layout, self.shape, self.numel, self.record = method, blob, layout, shape, numel, record
+
+
+class _SavedMask:
+    """A boolean mask in bit format."""
+    __slots__ = ("bits", "shape", "numel", "record")
+
+    def __init__(self, bits, shape, numel, record):
+        self.bits, self.shape, self.numel, self.record = bits, shape, numel, record
 
 
 class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
@@ -35,9 +47,10 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
     so that `report()` can give Tc_i and Tdc_i (it costs a synchronisation in `report()` only).
     """
 
-    def __init__(self, policy, timing=True):
+    def __init__(self, policy, timing=True, pack_masks=True):
         self.policy = policy
         self.timing = timing
+        self.pack_masks = pack_masks
         self.records = []
         self._ws = None      # scan workspace, grown on demand, reused by every tensor (one stream)
         self._cws = None     # workspace of the channel statistics
@@ -50,7 +63,21 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
             return False
         return not (t.is_leaf and t.requires_grad)  # parameters are not activations
 
+    def _pack_mask(self, t):
+        numel = t.numel()
+        rec = {"shape": tuple(t.shape), "numel": numel, "method": "mask", "events": {}}
+        ev = self._events(rec, "compress")
+        bits = torch.empty(mask_packed_bytes(numel), dtype=torch.uint8, device=t.device)
+        mask_pack(t, bits, numel)
+        if ev:
+            ev[1].record()
+        self.records.append(rec)
+        return _SavedMask(bits, t.shape, numel, rec)
+
     def _pack(self, t):
+        if (self.pack_masks and isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bool
+                and t.is_contiguous() and t.numel() > 0 and t.data_ptr() % 16 == 0):
+            return self._pack_mask(t)
         if not self._eligible(t):
             return t
         m = self.policy(t)
@@ -84,6 +111,13 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
         return _Saved(m, blob, layout, t.shape, numel, rec)
 
     def _unpack(self, s):
+        if isinstance(s, _SavedMask):
+            out = torch.empty(s.shape, dtype=torch.bool, device=s.bits.device)
+            ev = self._events(s.record, "decompress")
+            mask_unpack(s.bits, out, s.numel)
+            if ev:
+                ev[1].record()
+            return out
         if not isinstance(s, _Saved):
             return s
         out = torch.empty(s.shape, dtype=torch.bfloat16, device=s.blob.device)
@@ -114,6 +148,16 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
         rows = []
         for rec in self.records:
             m = rec["method"]
+            if m == "mask":  # byte format -> bit format
+                row = {"shape": rec["shape"], "numel": rec["numel"], "n_outliers": 0, "overflow": False,
+                       "original_bytes": rec["numel"], "compressed_bytes": mask_packed_bytes(rec["numel"]),
+                       "crate": mask_packed_bytes(rec["numel"]) / float(rec["numel"]), "tc_ms": None, "tdc_ms": None}
+                for key, name in (("compress", "tc_ms"), ("decompress", "tdc_ms")):
+                    ev = rec["events"].get(key)
+                    if ev:
+                        row[name] = ev[0].elapsed_time(ev[1])
+                rows.append(row)
+                continue
             st = rec["status"].view(torch.int32).cpu().tolist()
             if isinstance(m, ChannelMethod):
                 hidden = rec["shape"][-1]

@@ -115,3 +115,29 @@ def _grads(model, x, ctx):
             loss = model(x).float().pow(2).mean()
     loss.backward()
     return [p.grad.detach().clone() for p in model.parameters()]
+
+
+def test_dropout_mask_is_saved_in_bit_format_without_loss():
+    """Section 3.2: the dropout mask goes from byte format to bit format; the gradient is exactly the
+    one of the unhooked graph, because nothing is lost."""
+    print("[hooks] dropout mask", flush=True)
+    x = torch.randn(64, 4096, device="cuda", dtype=torch.bfloat16).requires_grad_(True)
+    torch.manual_seed(11)
+    y = torch.nn.functional.dropout(x, 0.1, training=True)
+    y.float().sum().backward()
+    ref = x.grad.clone()
+    x.grad = None
+    ctx = SavedActivationCompression(lambda t: None)
+    torch.manual_seed(11)
+    with ctx:
+        y = torch.nn.functional.dropout(x, 0.1, training=True)
+    y.float().sum().backward()
+    assert torch.equal(x.grad, ref)
+    rep = ctx.report()
+    masks = [r for r in rep if r["original_bytes"] == r["numel"]]
+    assert len(masks) == 1 and masks[0]["shape"] == (64, 4096) and masks[0]["crate"] == 0.125
+    # the hook's own round trip, against the oracle
+    keep = torch.rand(1000, 37, device="cuda") < 0.9
+    saved = ctx._pack(keep)
+    assert np.array_equal(saved.bits.cpu().numpy(), oracle.mask_pack(keep.cpu().numpy()))
+    assert torch.equal(ctx._unpack(saved), keep)
