@@ -308,7 +308,7 @@ __device__ __forceinline__ void load_tile(const TensorDesc& d, uint32_t tile, ui
   for (int j = 0; j < E; ++j) {
     uint32_t off = g.lane_off + (uint32_t)(j * kRow);
     if constexpr (!COMPLETE) off = off < last ? off : last;
-    const uint4 v = *reinterpret_cast<const uint4*>(sp + off);
+    const uint4 v = ADACC_LOAD16(sp + off);
     raw[j][0] = v.x; raw[j][1] = v.y; raw[j][2] = v.z; raw[j][3] = v.w;
   }
 }
@@ -362,15 +362,15 @@ __device__ __forceinline__ void store_row(const TensorDesc& d, const TileGeo<E>&
     w4 = pack_nibbles8(c);
   }
   if (g.full) {
-    if constexpr (BITS == 8) *reinterpret_cast<uint2*>(cp + eo) = w8;
-    else *reinterpret_cast<uint32_t*>(cp + (eo >> 1)) = w4;
+    if constexpr (BITS == 8) ADACC_STORE8(cp + eo, w8);
+    else ADACC_STORE4(cp + (eo >> 1), w4);
     sp[gl] = scl;
     if constexpr (ASYM) (d.zp + (g.base >> d.lgq))[gl] = off;
   } else {
     const bool valid = eo < g.rem;
     unsigned char* scrap = reinterpret_cast<unsigned char*>(d.status) + 64;
-    if constexpr (BITS == 8) *reinterpret_cast<uint2*>(valid ? cp + eo : scrap) = w8;
-    else *reinterpret_cast<uint32_t*>(valid ? cp + (eo >> 1) : scrap) = w4;
+    if constexpr (BITS == 8) ADACC_STORE8(valid ? cp + eo : scrap, w8);
+    else ADACC_STORE4(valid ? cp + (eo >> 1) : scrap, w4);
     *(valid ? sp + gl : reinterpret_cast<float*>(scrap + 16)) = scl;
     if constexpr (ASYM) *(valid ? d.zp + (g.base >> d.lgq) + gl : reinterpret_cast<float*>(scrap + 32)) = off;
   }

@@ -73,8 +73,9 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
         float4* p = reinterpret_cast<float4*>(lds + ((size_t)j * kRow + (size_t)lane * kOct) * 4);
         p[0] = a; p[1] = b;
       } else {
-        float4* p = reinterpret_cast<float4*>(reinterpret_cast<float*>(d.dst) + e0);
-        p[0] = a; p[1] = b;
+        float* p = reinterpret_cast<float*>(d.dst) + e0;
+        ADACC_STORE16(p, make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w)));
+        ADACC_STORE16(p + 4, make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w)));
       }
     } else {
       uint4 w;
@@ -85,7 +86,7 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
       if (patch)
         *reinterpret_cast<uint4*>(lds + ((size_t)j * kRow + (size_t)lane * kOct) * 2) = w;
       else
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(d.dst) + e0) = w;
+        ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
     }
   }
 
@@ -113,11 +114,13 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
       if (e0 >= d.numel) continue;
       if constexpr (F32) {
         const float4* p = reinterpret_cast<const float4*>(lds + ((size_t)j * kRow + (size_t)lane * kOct) * 4);
-        float4* q = reinterpret_cast<float4*>(reinterpret_cast<float*>(d.dst) + e0);
-        q[0] = p[0]; q[1] = p[1];
+        float* q = reinterpret_cast<float*>(d.dst) + e0;
+        const float4 a = p[0], b = p[1];
+        ADACC_STORE16(q, make_uint4(__float_as_uint(a.x), __float_as_uint(a.y), __float_as_uint(a.z), __float_as_uint(a.w)));
+        ADACC_STORE16(q + 4, make_uint4(__float_as_uint(b.x), __float_as_uint(b.y), __float_as_uint(b.z), __float_as_uint(b.w)));
       } else {
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(d.dst) + e0) =
-            *reinterpret_cast<const uint4*>(lds + ((size_t)j * kRow + (size_t)lane * kOct) * 2);
+        ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0,
+                      *reinterpret_cast<const uint4*>(lds + ((size_t)j * kRow + (size_t)lane * kOct) * 2));
       }
     }
     __builtin_amdgcn_wave_barrier();  // the slice is reused by this wavefront's next tile

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void mask_pack_kernel(const uint8_t* __re
 #pragma unroll
     for (int i = 0; i < kMaskAhead; ++i) {
       const uint64_t p = p0 + (uint64_t)i * stride;
-      v[i] = reinterpret_cast<const uint4*>(mask)[p < n_pieces ? p : p0];  // a piece past the end re-reads the first one
+      v[i] = load_stream16(reinterpret_cast<const uint4*>(mask) + (p < n_pieces ? p : p0));  // a piece past the end re-reads the first one
     }
 #pragma unroll
     for (int i = 0; i < kMaskAhead; ++i) {
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void mask_unpack_kernel(const uint8_t* __
       w.y = nibble_to_bytes((v[i] >> 4) & 0xFu);
       w.z = nibble_to_bytes((v[i] >> 8) & 0xFu);
       w.w = nibble_to_bytes((v[i] >> 12) & 0xFu);
-      reinterpret_cast<uint4*>(mask)[p] = w;
+      store_stream16(reinterpret_cast<uint4*>(mask) + p, w);
     }
   }
   if (me == 0) {
