@@ -170,7 +170,8 @@ def time_steps(w, steps, warmup):
 
 
 def copy_ceiling():
-    """GB/s (read + written bytes) of the library's plain copy kernel on 1 GiB."""
+    """GB/s (read + written bytes) of the library's copy kernel on 1 GiB, with the streaming accesses
+    the tensor streams use when ADACC_COPY_STREAM=1 is set by the caller (see main)."""
     import torch
     import paper_2508_00806_amd as adacc
     n = 1 << 30
@@ -439,6 +440,9 @@ def main():
         return
     main_res = run_workload(a.workload, a.steps, a.warmup, a.sets)
     ceiling = copy_ceiling()
+    os.environ["ADACC_COPY_STREAM"] = "1"
+    ceiling_stream = copy_ceiling()
+    os.environ.pop("ADACC_COPY_STREAM")
     extras = []
     if not a.no_extras:
         for name in sorted(WORKLOAD_TEXT):
@@ -463,6 +467,7 @@ def main():
         "algorithmic_bytes_per_launch": main_res["algorithmic_bytes_per_direction"],
         "ms_per_launch": main_res[dom]["ms"],
         "copy_kernel_GBps": ceiling,
+        "copy_kernel_streaming_GBps": ceiling_stream,
     }
     out = {
         "metric": "compress+decompress GB/s of bf16 activations; fraction of MI355X HBM peak",

@@ -43,6 +43,13 @@ __global__ __launch_bounds__(kThreads) void hbm_copy_kernel(uint4* __restrict__ 
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
+// the same with streaming (non-temporal) accesses, as the tensor streams of the library use them
+__global__ __launch_bounds__(kThreads) void hbm_copy_stream_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                                   uint64_t n16) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+    store_stream16(dst + i, load_stream16(src + i));
+}
 
 // ===================================================================== host side
 
@@ -903,8 +910,14 @@ int adacc_hbm_copy(void* dst, const void* src, uint64_t bytes, void* hip_stream)
   uint64_t grid = (n16 + kThreads - 1) / kThreads;
   const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_COPY_WGS_PER_CU", 16);
   if (grid > cap) grid = cap;
-  hipLaunchKernelGGL(hbm_copy_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+  // ADACC_COPY_STREAM=1: with the streaming accesses of the library's tensor streams (default: plain
+  // loads and stores, which is also what the byte counters were calibrated with)
+  if (env_int("ADACC_COPY_STREAM", 0) != 0)
+    hipLaunchKernelGGL(hbm_copy_stream_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+  else
+    hipLaunchKernelGGL(hbm_copy_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
   return launch_check("hbm_copy_kernel");
 }
 

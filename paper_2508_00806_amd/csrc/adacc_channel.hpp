@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_
     for (; r + kBatch <= rows; r += kBatch) {
       uint4 v[kBatch];
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) v[i] = *reinterpret_cast<const uint4*>(p + (size_t)(r + i) * hidden);
+      for (uint32_t i = 0; i < kBatch; ++i) v[i] = ADACC_LOAD16_KEEP(p + (size_t)(r + i) * hidden);
 #pragma unroll
       for (uint32_t i = 0; i < kBatch; ++i) {
         const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_
       }
     }
     for (; r < rows; ++r) {
-      const uint4 v = *reinterpret_cast<const uint4*>(p + (size_t)r * hidden);
+      const uint4 v = ADACC_LOAD16_KEEP(p + (size_t)r * hidden);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -416,16 +416,16 @@ __device__ __forceinline__ void channel_decompress_tile(const TensorDesc& d, con
     }
 
     if constexpr (F32) {
-      float4* p = reinterpret_cast<float4*>(reinterpret_cast<float*>(d.dst) + e0);
-      p[0] = make_float4(v[0], v[1], v[2], v[3]);
-      p[1] = make_float4(v[4], v[5], v[6], v[7]);
+      float* p = reinterpret_cast<float*>(d.dst) + e0;
+      ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+      ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     } else {
       uint4 w;  // the bf16 image of a widened bf16 value is that value
       w.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
       w.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
       w.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
       w.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
-      *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(d.dst) + e0) = w;
+      ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
     }
   }
 }

@@ -43,7 +43,8 @@ __device__ __forceinline__ void store_stream4(void* p, uint32_t v) {
 }
 
 // The tensor streams of the compression / decompression kernels go through these (ADACC_NO_STREAM_HINT
-// builds the plain accesses, for comparison).
+// builds the plain accesses, for comparison).  The codes a decompression reads stay plain loads: on a
+// blob that was written shortly before they are served by the caches, and the hint made that slower.
 #ifndef ADACC_NO_STREAM_HINT
 #define ADACC_LOAD16(p) load_stream16(p)
 #define ADACC_STORE16(p, v) store_stream16((p), (v))
@@ -54,6 +55,14 @@ __device__ __forceinline__ void store_stream4(void* p, uint32_t v) {
 #define ADACC_STORE16(p, v) (*reinterpret_cast<uint4*>(p) = (v))
 #define ADACC_STORE8(p, v) (*reinterpret_cast<uint2*>(p) = (v))
 #define ADACC_STORE4(p, v) (*reinterpret_cast<uint32_t*>(p) = (v))
+#endif
+
+// The statistics pass of the two-pass schemes reads what the second pass reads again: by default it
+// leaves the lines to the caches (ADACC_STATS_STREAM makes it a streaming read too).
+#ifdef ADACC_STATS_STREAM
+#define ADACC_LOAD16_KEEP(p) load_stream16(p)
+#else
+#define ADACC_LOAD16_KEEP(p) (*reinterpret_cast<const uint4*>(p))
 #endif
 
 enum : uint32_t { kModeNone = 0, kModeAbs = 1, kModeStd = 2, kModeTopk = 3 };

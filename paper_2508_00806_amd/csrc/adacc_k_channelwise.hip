@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(Channelwi
     for (; r + kBatch <= rows; r += kBatch) {
       uint4 v[kBatch];
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) v[i] = *reinterpret_cast<const uint4*>(p + (size_t)(r + i) * c.hidden);
+      for (uint32_t i = 0; i < kBatch; ++i) v[i] = ADACC_LOAD16_KEEP(p + (size_t)(r + i) * c.hidden);
 #pragma unroll
       for (uint32_t i = 0; i < kBatch; ++i) {
         acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v[i].x));
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(Channelwi
       }
     }
     for (; r < rows; ++r) {
-      const uint4 v = *reinterpret_cast<const uint4*>(p + (size_t)r * c.hidden);
+      const uint4 v = ADACC_LOAD16_KEEP(p + (size_t)r * c.hidden);
       acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v.x));
       acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v.y));
       acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v.z));
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_quantise_kernel(Channelw
     for (int j = 0; j < E; ++j) {  // every load of the tile before its first store
       const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
       const uint32_t off = in_tile < rem ? in_tile : 0u;  // octets past the end re-read the first one
-      raw[j] = *reinterpret_cast<const uint4*>(c.src + (size_t)base + off);
+      raw[j] = ADACC_LOAD16(c.src + (size_t)base + off);
       const uint32_t col = column_of(col0 + off, c.hidden, c.inv_hidden);
       inv[j][0] = *reinterpret_cast<const float4*>(c.inv + col);
       inv[j][1] = *reinterpret_cast<const float4*>(c.inv + col + 4);
@@ -160,9 +160,9 @@ __global__ __launch_bounds__(kThreads) void channelwise_quantise_kernel(Channelw
         uint2 o;
         o.x = pack_bytes4(code[0], code[1], code[2], code[3]);
         o.y = pack_bytes4(code[4], code[5], code[6], code[7]);
-        *reinterpret_cast<uint2*>(c.codes + e0) = o;
+        ADACC_STORE8(c.codes + e0, o);
       } else {
-        *reinterpret_cast<uint32_t*>(c.codes + (e0 >> 1)) = pack_nibbles8(code);
+        ADACC_STORE4(c.codes + (e0 >> 1), pack_nibbles8(code));
       }
     }
   }
@@ -213,16 +213,16 @@ __global__ __launch_bounds__(kThreads) void channelwise_dequantise_kernel(Channe
         v[e] = (float)code * s[e];
       }
       if constexpr (F32) {
-        float4* p = reinterpret_cast<float4*>(reinterpret_cast<float*>(c.dst) + e0);
-        p[0] = make_float4(v[0], v[1], v[2], v[3]);
-        p[1] = make_float4(v[4], v[5], v[6], v[7]);
+        float* p = reinterpret_cast<float*>(c.dst) + e0;
+        ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+        ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
       } else {
         uint4 w;
         w.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
         w.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
         w.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
         w.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(c.dst) + e0) = w;
+        ADACC_STORE16(reinterpret_cast<uint16_t*>(c.dst) + e0, w);
       }
     }
   }
