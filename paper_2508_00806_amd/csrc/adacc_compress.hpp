@@ -1145,7 +1145,10 @@ __device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit,
   }
   for (uint32_t t = t0; t < t1c; ++t) {
     uint32_t nxt[kPrefetch ? E : 1][4];
-    if constexpr (kPrefetch) load_tile<E, true>(d, (t + 1 < t1c) ? t + 1 : t, nxt);  // the last one fetches itself again
+    // the last iteration has nothing to fetch ahead: its (unconditional) loads go to the tensor's first
+    // tile, which every run's last iteration reads and which therefore stays in the cache (fetching the
+    // current tile again would be a second trip to memory, because streaming loads are not retained)
+    if constexpr (kPrefetch) load_tile<E, true>(d, (t + 1 < t1c) ? t + 1 : 0u, nxt);
     else load_tile<E, true>(d, t, raw);
 
     const TileGeo<E> g = tile_geo<E, true>(d, t);
