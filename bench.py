@@ -37,10 +37,10 @@ WORKLOAD_TEXT = {
 # WRITE_SIZE runs, scaled by the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); copied
 # from profiles/hbm_traffic_pmc.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "c2": {"compress": 173049139, "decompress": 173083033},
-    "c3": {"compress": 826388787, "decompress": 826899558},
-    "c4": {"compress": 1631255347, "decompress": 1665042944},
-    "c5": {"compress": 23079417651, "decompress": 23256978944},
+    "c2": {"compress": 172590694, "decompress": 173093888},
+    "c3": {"compress": 824747725, "decompress": 826356326},
+    "c4": {"compress": 1624621056, "decompress": 1653333606},
+    "c5": {"compress": 23071883571, "decompress": 23161357107},
 }
 
 
