@@ -264,7 +264,8 @@ uint64_t adacc_compressed_bytes(const adacc_method *method, uint64_t numel, uint
 
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst: the practical HBM
  * ceiling the compression kernels are measured against, and the calibration
- * kernel for hardware byte counters. */
+ * kernel for hardware byte counters.  With ADACC_COPY_STREAM=1 in the environment it uses the
+ * non-temporal loads and stores that the tensor streams of the library use. */
 int adacc_hbm_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream);
 
 /* Text for an error code; for ADACC_EHIP, the last HIP error string seen by this thread. */
