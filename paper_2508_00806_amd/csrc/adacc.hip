@@ -180,7 +180,8 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
 // longer than the limit), which also keeps the look-back short: its reach grows with the
 // number of runs in flight, not with the number of tiles.
 static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
-  const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64) > 64 ? 64 : (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 64);
+  // longest run (the staging of tile offsets in a lane allows 64; measured best on large tensors: 16 to 32)
+  const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 32) > 64 ? 64 : (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 32);
   if (tiles_in_launch <= capacity) return 1u;
   const uint64_t rounds = (tiles_in_launch + (uint64_t)capacity * tmax - 1) / ((uint64_t)capacity * tmax);
   const uint64_t units = (uint64_t)capacity * rounds;
