@@ -37,10 +37,10 @@ WORKLOAD_TEXT = {
 # WRITE_SIZE runs, scaled by the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); copied
 # from profiles/hbm_traffic_pmc.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "c2": {"compress": 172618445, "decompress": 173093888},
-    "c3": {"compress": 824715571, "decompress": 826356326},
-    "c4": {"compress": 1622748877, "decompress": 1653333606},
-    "c5": {"compress": 23084046336, "decompress": 23161357107},
+    "c2": {"compress": 172618445, "decompress": 173085286},
+    "c3": {"compress": 824715571, "decompress": 826351923},
+    "c4": {"compress": 1622748877, "decompress": 1652543386},
+    "c5": {"compress": 23084046336, "decompress": 23150024499},
 }
 
 
