@@ -169,9 +169,10 @@ int adacc_read_status(const void *blob, const adacc_layout *layout, void *hip_st
  * channels whose sum is not finite (they take no part in mu and sigma), are kept whole and
  * uncompressed together with their indices, count as zero in the activation, and everything else
  * is group-quantised in memory order exactly as with ADACC_OUTLIER_NONE (Eq. 2 / Eq. 3).
- * The order of the sums is fixed (binary32 over chunks of 64 tokens, binary64 over the chunks in
- * order, 256 interleaved binary64 accumulators folded by halves over the channels), so the blob is
- * a pure function of the input bits.
+ * The sums are floating-point sums in a fixed order (binary32 partial sums over runs of consecutive
+ * tokens, binary64 from there on), so the blob is a pure function of the input bits; a channel whose
+ * Z lies within the rounding error of those sums of z_thresh (a few 1e-6 times S_h / sigma) may fall
+ * on either side of the exact rule.
  * Limits: hidden a multiple of 8 in [8, 65536]; tokens * hidden < 2^32; quant_group a power of two
  * in [8, 2048] dividing tokens * hidden; 1 <= max_channels <= hidden. */
 typedef struct adacc_channel_method {

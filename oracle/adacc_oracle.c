@@ -16,9 +16,8 @@
  *   - outliers are single elements picked by |x| > tau, by x^2 > k^2 * var of the
  *     statistics group, or as the k largest magnitudes of the group (the paper
  *     picks whole channels by Z-score; same extract / zero / quantise structure);
- *   - X / S is evaluated as X * (D / max): one binary32 division per group; the product itself is
- *     not rounded before it is rounded to the nearest integer (binary64 holds the product of two
- *     binary32 numbers exactly), so the code is the integer nearest to X * inv;
+ *   - X / S is evaluated as X * (D / max): one binary32 division per group, one binary32
+ *     multiplication per element, and that product is then rounded to the nearest integer;
  *   - "nearest rounding" is round-half-to-even;
  *   - sums for the variance are canonical pairwise (binary tree) binary32 sums;
  *   - Inf and NaN are always outliers when outliers are kept; they never enter
@@ -148,15 +147,12 @@ int oracle_select_outliers(const oracle_method *m, const uint16_t *x, size_t n, 
 
 /* ---------- step 4: quantisation of one group ---------- */
 
-static int8_t clip_code(double r, int q) {
+static int8_t clip_code(float r, int q) {
   /* written so that a NaN lands on the lower bound */
-  if (!(r >= (double)(-q))) r = (double)(-q);
-  if (r > (double)(q - 1)) r = (double)(q - 1);
+  if (!(r >= (float)(-q))) r = (float)(-q);
+  if (r > (float)(q - 1)) r = (float)(q - 1);
   return (int8_t)r;
 }
-
-/* nearest integer (ties to even) of the exact product of two binary32 numbers */
-static double round_product(float x, float inv) { return rint((double)x * (double)inv); }
 
 /* Eq. 2:  S = max|X| / D,  code = clip(round(X / S), -Q, Q-1),  D = Q (paper) or Q-1. */
 static void quant_sym(const oracle_method *m, const float *y, size_t g, int8_t *codes, float *scale) {
@@ -171,7 +167,7 @@ static void quant_sym(const oracle_method *m, const float *y, size_t g, int8_t *
     inv = d / a;
     if (inv > FLT_MAX) inv = FLT_MAX; /* a is so small that D/a overflows */
   }
-  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(round_product(y[i], inv), q);
+  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(rintf(y[i] * inv), q);
 }
 
 /* Eq. 3:  O = (max+min)/2,  S = (max-min)/D2,  code = clip(round((X-O)/S), -Q, Q-1),
@@ -194,7 +190,7 @@ static void quant_asym(const oracle_method *m, const float *y, size_t g, int8_t 
     inv = d2 / r;
     if (inv > FLT_MAX) inv = FLT_MAX;
   }
-  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(round_product(y[i] - o, inv), q);
+  for (size_t i = 0; i < g; ++i) codes[i] = clip_code(rintf((y[i] - o) * inv), q);
 }
 
 /* Steps 3 and 4 for a given outlier mask, then the packing of the codes. */
@@ -318,56 +314,82 @@ uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out) {
  *   - the threshold is compared against Z itself, formed by one binary64 division;
  *   - a channel whose sum is not finite is always an outlier and takes no part in mu and sigma;
  *   - if sigma is zero or not a number (all channels alike, or none left), nothing else is selected.
- * The selection is an integer decision taken by floating-point sums, so the order of the sums is
- * part of the definition:
- *   - tokens are taken in chunks of 64 consecutive rows; within a chunk |x| is added up in
- *     binary32, one token after the other, starting from +0;
- *   - S_h is the binary64 sum of the chunk sums, one chunk after the other;
- *   - sums over the channels use 256 binary64 accumulators, channel h going to accumulator
- *     h mod 256 in ascending order of h, which are then folded by halves (a[j] += a[j + s],
- *     s = 128, 64, ..., 1);
- *   - the sum of squared deviations is accumulated with fused multiply-adds.
+ * S_h is the exact sum, rounded once to binary64 (the magnitude of a finite bf16 value is an
+ * integer multiple of 2^-133 below 2^128, so the sum is kept as a 320-bit integer); mu and sigma
+ * are the textbook two-pass mean and standard deviation, plain binary64 loops in channel order.
  * ==================================================================================== */
 
-enum { CHUNK_TOKENS = 64, CHANNEL_ACCS = 256 };
+/* sum of bf16 magnitudes as an integer count of 2^-133, five 64-bit limbs, least significant first */
+typedef struct exact_sum { uint64_t limb[5]; } exact_sum;
 
-/* S_h for every channel. */
-void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S) {
-  for (size_t h = 0; h < hidden; ++h) {
-    double s = 0.0;
-    for (size_t t0 = 0; t0 < tokens; t0 += CHUNK_TOKENS) {
-      float part = 0.0f;
-      for (size_t t = t0; t < tokens && t < t0 + CHUNK_TOKENS; ++t) part = part + fabsf(bf16_to_f32(x[t * hidden + h]));
-      s = s + (double)part;
-    }
-    S[h] = s;
+static void exact_add(exact_sum *a, uint16_t b) {
+  const uint32_t e = (b >> 7) & 0xFFu;
+  const uint64_t sig = e ? ((b & 0x7Fu) | 0x80u) : (b & 0x7Fu); /* |x| = sig * 2^(max(e,1) - 134) */
+  const uint32_t shift = e ? e - 1u : 0u;                       /*     = sig * 2^shift * 2^-133     */
+  const unsigned __int128 v = (unsigned __int128)sig << (shift % 64u);
+  uint64_t add[2] = {(uint64_t)v, (uint64_t)(v >> 64)};
+  uint64_t carry = 0;
+  for (uint32_t i = shift / 64u, k = 0; i < 5; ++i, ++k) {
+    const unsigned __int128 t = (unsigned __int128)a->limb[i] + (k < 2 ? add[k] : 0u) + carry;
+    a->limb[i] = (uint64_t)t;
+    carry = (uint64_t)(t >> 64);
   }
 }
 
-static double fold_accumulators(double *a) {
-  for (size_t s = CHANNEL_ACCS / 2; s >= 1; s /= 2)
-    for (size_t j = 0; j < s; ++j) a[j] = a[j] + a[j + s];
-  return a[0];
+/* the 320-bit integer times 2^-133, rounded to the nearest binary64, ties to even */
+static double exact_round(const exact_sum *a) {
+  int top = -1; /* position of the highest set bit */
+  for (int i = 4; i >= 0 && top < 0; --i)
+    if (a->limb[i])
+      for (int j = 63; j >= 0; --j)
+        if ((a->limb[i] >> j) & 1u) { top = 64 * i + j; break; }
+  if (top < 0) return 0.0;
+  uint64_t mant = 0; /* the 53 bits from `top` down (fewer if the number is shorter) */
+  int low = top - 52;
+  if (low < 0) low = 0;
+  for (int p = top; p >= low; --p) mant = (mant << 1) | ((a->limb[p / 64] >> (p % 64)) & 1u);
+  if (low > 0) {
+    const int guard = (int)((a->limb[(low - 1) / 64] >> ((low - 1) % 64)) & 1u);
+    int sticky = 0;
+    for (int p = low - 2; p >= 0 && !sticky; --p) sticky = (int)((a->limb[p / 64] >> (p % 64)) & 1u);
+    if (guard && (sticky || (mant & 1u))) ++mant; /* 2^53 is still exact as a double */
+  }
+  return ldexp((double)mant, low - 133);
+}
+
+/* S_h = sum over the tokens of |x|, for every channel. */
+void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S) {
+  for (size_t h = 0; h < hidden; ++h) {
+    exact_sum acc;
+    memset(&acc, 0, sizeof acc);
+    int inf_seen = 0, nan_seen = 0;
+    for (size_t t = 0; t < tokens; ++t) {
+      const uint16_t b = x[t * hidden + h];
+      if ((b & 0x7FFFu) > 0x7F80u) nan_seen = 1;
+      else if ((b & 0x7FFFu) == 0x7F80u) inf_seen = 1;
+      else exact_add(&acc, b);
+    }
+    S[h] = nan_seen ? (double)NAN : inf_seen ? (double)INFINITY : exact_round(&acc);
+  }
 }
 
 /* Eq. 1.  is_out[h] = 1 for an outlier channel.  stats (may be NULL) receives mu, sigma. */
 void oracle_channel_select(const double *S, size_t hidden, float z_thresh, uint8_t *is_out, double *stats) {
-  double a[CHANNEL_ACCS];
   size_t finite = 0;
-  for (size_t j = 0; j < CHANNEL_ACCS; ++j) a[j] = 0.0;
+  double sum = 0.0;
   for (size_t h = 0; h < hidden; ++h)
     if (isfinite(S[h])) {
-      a[h % CHANNEL_ACCS] = a[h % CHANNEL_ACCS] + S[h];
+      sum = sum + S[h];
       ++finite;
     }
-  const double mu = fold_accumulators(a) / (double)finite;
-  for (size_t j = 0; j < CHANNEL_ACCS; ++j) a[j] = 0.0;
+  const double mu = sum / (double)finite;
+  double ss = 0.0;
   for (size_t h = 0; h < hidden; ++h)
     if (isfinite(S[h])) {
       const double d = S[h] - mu;
-      a[h % CHANNEL_ACCS] = fma(d, d, a[h % CHANNEL_ACCS]);
+      ss = ss + d * d;
     }
-  const double sigma = sqrt(fold_accumulators(a) / (double)finite);
+  const double sigma = sqrt(ss / (double)finite);
   for (size_t h = 0; h < hidden; ++h) {
     const double z = (S[h] - mu) / sigma;
     is_out[h] = !isfinite(S[h]) || z > (double)z_thresh; /* a NaN z selects nothing */

@@ -72,8 +72,8 @@ uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out);
 float oracle_pairwise_sum(const float *v, size_t n);
 
 /* ---- outlier channels (Section 3.2, Eq. 1) ----
- * x is a row-major matrix of `tokens` rows and `hidden` channels.  The order of every sum is part
- * of the definition and is written out in adacc_oracle.c. */
+ * x is a row-major matrix of `tokens` rows and `hidden` channels.  S_h is the exact sum rounded once
+ * to binary64; mu and sigma are plain two-pass binary64 loops over the channels. */
 
 /* S_h = sum over the tokens of |x|, for every channel. */
 void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S);

@@ -243,14 +243,17 @@ __device__ __forceinline__ uint32_t scan_poll_sum(const ScanCtx& sc, const uint6
 }
 
 // ------------------------------------------------------------------ rounding and packing of codes
-// code = clip(nearest integer of y * inv).  One fused multiply-add with 1.5 * 2^23 rounds the
-// exact product to the nearest integer (ties to even) and leaves it, in two's complement, in
-// the low mantissa bits; the clip is a median with the two bounds shifted the same way
-// ("values greater than 7 are capped at 7"); a NaN lands on the lower bound.
+// code = clip(nearest integer of the binary32 product y * inv) (Eq. 2 / Eq. 3).  The product is
+// rounded to binary32 by the multiplication (never fused with what follows: the library is built
+// with contraction off); adding 1.5 * 2^23 then rounds it to the nearest integer (ties to even)
+// and leaves that integer, in two's complement, in the low mantissa bits; the clip is a median
+// with the two bounds shifted the same way ("values greater than 7 are capped at 7"); a NaN
+// lands on the lower bound.
 constexpr float kMagic = 12582912.0f;
 template <int Q>
 __device__ __forceinline__ uint32_t code_bits(float y, float inv) {
-  const float r = __fmaf_rn(y, inv, kMagic);
+  const float p = __fmul_rn(y, inv);
+  const float r = __fadd_rn(p, kMagic);
   return __float_as_uint(fminf(fmaxf(r, kMagic - (float)Q), kMagic + (float)(Q - 1)));
 }
 

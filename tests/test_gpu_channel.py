@@ -1,6 +1,9 @@
 """GPU parity for outlier channels by Z-score (Section 3.2, Eq. 1): libadacc's adacc_channel_*
 calls (through the C ABI) against the CPU oracle.  Bar: the channel mask, list and values, packed
-codes, scales and offsets bit-exact; decompressed binary32 bit-equal (hence within 1e-6), bf16 equal."""
+codes, scales and offsets bit-exact; decompressed binary32 bit-equal (hence within 1e-6), bf16 equal.
+The oracle's channel sums are exact and the library's are binary32 partial sums in a fixed order, so
+the helper also checks that no channel of a tested input has its Z within rounding reach of the
+threshold (otherwise equal channel sets would prove nothing)."""
 import numpy as np
 import pytest
 import torch
@@ -104,3 +107,26 @@ def test_second_call_reuses_blob_and_workspace():
         sec = {k: v.cpu().numpy() for k, v in adacc.channel_blob_sections(blob, L2, m, t, hidden).items()}
         assert np.array_equal(sec["codes"], oc.packed) and np.array_equal(sec["ch_idx"][:oc.n_ch], oc.ch_idx)
         assert np.array_equal(sec["ch_val"].view(np.uint16)[:t * oc.n_ch].reshape(t, oc.n_ch), oc.ch_val)
+
+
+def test_repeat_launches_give_the_same_blob():
+    """The library's sums have a fixed order: the same input gives the same bytes on every launch."""
+    log("[channel] determinism")
+    tokens, hidden = 1500, 1024
+    x = workloads.c2("cpu", rows=tokens, hidden=hidden).cuda()
+    m = adacc.ChannelMethod(bits=4, quant_group=128, max_channels=32)
+    ws = adacc.alloc_channel_workspace(tokens, hidden)
+    blobs = []
+    for _ in range(3):
+        blob, L = adacc.alloc_channel_blob(m, tokens, hidden)
+        blob.zero_()
+        adacc.channel_compress(m, x, tokens, hidden, blob, ws)
+        torch.cuda.synchronize()
+        n_ch = adacc.channel_read_status(blob, L)[0]
+        sec = adacc.channel_blob_sections(blob, L, m, tokens, hidden)
+        blobs.append((n_ch, {k: v.clone() for k, v in sec.items()}))
+    for n_ch, sec in blobs[1:]:
+        assert n_ch == blobs[0][0]
+        for k in ("codes", "scales", "ch_mask", "ch_base"):
+            assert torch.equal(sec[k], blobs[0][1][k]), k
+        assert torch.equal(sec["ch_idx"][:n_ch], blobs[0][1]["ch_idx"][:n_ch])

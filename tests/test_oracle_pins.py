@@ -285,7 +285,7 @@ def test_sym_codes_are_nearest_in_exact_arithmetic(bits, rule):
                 # only an exact or near tie may go to the other neighbour (bf16 inputs make exact
                 # ties common, and D / max carries one rounding when D is not a power of two)
                 assert abs(abs(target - math.floor(target)) - Fraction(1, 2)) <= abs(r) * Fraction(1, 2 ** 22)
-    assert exact_match >= 0.99 * x.size
+    assert exact_match >= 0.999 * x.size
 
 
 @pytest.mark.parametrize("bits", [4, 8])
@@ -463,25 +463,40 @@ def _planted(tokens, hidden, channels, seed, gain=50.0):
 
 
 def test_channel_scores_are_exact_integer_sums_on_small_integers():
-    """Small integers add up without rounding in any order and precision: S_h must be the integer
-    column sum of |x| - over the tokens (axis 0), not the channels - also with a ragged last chunk."""
+    """Small integers: S_h must be the integer column sum of |x| - over the tokens (axis 0), not the
+    channels - for square and non-square shapes.  A channel holding an Inf sums to +Inf, one holding
+    a NaN to NaN."""
     rng = np.random.default_rng(11)
     for tokens, hidden in ((1, 8), (64, 8), (65, 24), (200, 24), (333, 7)):
         xi = rng.integers(-8, 9, size=(tokens, hidden))
         S = oracle.channel_scores(bf16_bits(xi.astype(np.float32)), tokens, hidden)
         assert np.array_equal(S, np.abs(xi).sum(axis=0).astype(np.float64))
+    xb = bf16_bits(np.ones((5, 4), dtype=np.float32)).reshape(5, 4)
+    xb[2, 1], xb[3, 2], xb[4, 2] = 0xFF80, 0x7FC0, 0x7F80  # -Inf;  NaN and +Inf in one channel
+    S = oracle.channel_scores(xb, 5, 4)
+    assert S[0] == 5.0 and S[1] == np.inf and np.isnan(S[2]) and S[3] == 5.0
 
 
-def test_channel_scores_agree_with_the_exactly_rounded_sum():
-    """Against math.fsum (exact sum, rounded once): the defined order of additions may only cost the
-    rounding of 64-term binary32 partial sums."""
+def test_channel_scores_are_the_exactly_rounded_sums():
+    """Against math.fsum (exact sum of binary64 values, rounded once): equal to the last bit, on
+    ordinary activations and on columns whose magnitudes span the whole bf16 range (where adding
+    one value after the other in binary64 loses the small terms)."""
     tokens, hidden = 1000, 40
     xb = _planted(tokens, hidden, [3], seed=12)
+    rng = np.random.default_rng(120)
+    wide = rng.integers(0, 0x7F80, size=(tokens, 8)).astype(np.uint16)          # any finite magnitude
+    wide |= (rng.integers(0, 2, size=wide.shape).astype(np.uint16) << 15)       # any sign
+    wide[:, 1] &= 0x807F                                                        # subnormals only
+    wide[0, 2], wide[1:, 2] = 0x7F7F, rng.integers(0, 0x0100, size=tokens - 1)  # one huge, many tiny
+    xb = np.concatenate([xb, wide], axis=1)
+    hidden += 8
     S = oracle.channel_scores(xb, tokens, hidden)
     xf = np.abs(bits_to_f32(xb.reshape(-1)).reshape(tokens, hidden)).astype(np.float64)
+    lossy = 0
     for h in range(hidden):
-        exact = math.fsum(xf[:, h])
-        assert abs(S[h] - exact) <= 64 * 2.0 ** -24 * exact
+        assert S[h] == math.fsum(xf[:, h])
+        lossy += float(np.cumsum(xf[:, h])[-1]) != S[h]
+    assert lossy > 0  # the test data does tell an exact sum from a running binary64 sum
 
 
 def test_channel_selection_is_the_z_score_rule():
