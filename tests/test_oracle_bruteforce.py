@@ -1,0 +1,121 @@
+"""The C oracle against tests/bruteforce.py, field by field, on tiny tensors, for every outlier mode x
+bit width x symmetric / asymmetric x scale rule (Section 3.2, Eq. 2, Eq. 3, Fig. 3(c)).  The brute
+force is exact rational arithmetic with explicit binary32 rounding, one element at a time; a mistake
+in the oracle's composition (scale taken before the outliers are zeroed, a code other than that of
+zero at an outlier, the wrong nibble for the tail of an odd-length tensor, a dropped offset on the
+way back) fails here."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import bruteforce as bf
+import oracle
+from oracle import Method
+
+MODES = {"none": bf.NONE, "abs": bf.ABS, "std": bf.STD, "topk": bf.TOPK}
+
+
+def to_bf16_bits(a):
+    u = np.asarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def tensors(seed, n):
+    """A few tiny inputs: heavy-tailed values, small integers (ties everywhere), one-sided values,
+    zeros of both signs and subnormals."""
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal(n) * np.where(rng.random(n) < 0.1, 30.0, 1.0)
+    b = rng.integers(-9, 10, size=n).astype(np.float64) * 0.5
+    c = np.abs(rng.standard_normal(n)) + 0.125
+    d = to_bf16_bits(rng.standard_normal(n) * 1e-3)
+    d[::5] = 0x8000
+    d[1::7] = 0x0000
+    d[2::9] = rng.integers(1, 0x80, size=d[2::9].size)  # subnormal bf16
+    return [to_bf16_bits(a), to_bf16_bits(b), to_bf16_bits(c), d]
+
+
+def check(bits, nbits, gq, asym, rule, mode, gs=0, thresh=0.0, topk=0):
+    n = bits.size
+    m = Method(bits=nbits, quant_group=gq, asym=asym, scale_rule=rule, outlier_mode=MODES[mode], stat_group=gs,
+               thresh=thresh, topk=topk)
+    oc = oracle.compress(m, bits)
+    t32 = Fraction(float(np.float32(thresh)))
+    want = bf.compress([int(b) for b in bits], nbits=nbits, quant_group=gq, asym=asym, rule=rule, mode=MODES[mode],
+                       stat_group=gs, thresh=t32, topk=topk)
+    assert list(oc.out_idx) == want["out_idx"], "outlier indices"
+    assert [int(v) for v in oc.out_val] == want["out_val"], "outlier values"
+    assert oc.n_out == len(want["out_idx"])
+    assert [int(c) for c in oc.codes] == want["codes"], "codes"
+    assert [int(p) for p in oc.packed] == want["packed"], "packed codes"
+    assert [Fraction(float(s)) for s in oc.scale] == want["scale"], "scales"
+    if asym:
+        assert [Fraction(float(z)) for z in oc.zp] == want["zp"], "offsets"
+    f, b = oracle.decompress(oc)
+    xs, bs = bf.decompress(want, n=n, nbits=nbits, quant_group=gq, asym=asym)
+    for i in range(n):
+        if xs[i] is None:  # a non-finite outlier: the stored pattern comes back
+            assert int(b[i]) == bs[i] and not np.isfinite(f[i])
+        else:
+            assert Fraction(float(f[i])) == xs[i], f"binary32 reconstruction of element {i}"
+            assert int(b[i]) == bs[i], f"bf16 reconstruction of element {i}"
+    return oc
+
+
+@pytest.mark.parametrize("mode", ["none", "abs", "std", "topk"])
+@pytest.mark.parametrize("nbits", [4, 8])
+@pytest.mark.parametrize("asym", [0, 1])
+@pytest.mark.parametrize("rule", [bf.PAPER, bf.FULLRANGE])
+def test_whole_chain_on_tiny_tensors(mode, nbits, asym, rule):
+    n_out = 0
+    for k, bits in enumerate(tensors(7 + nbits + asym, 32)):
+        kw = dict(abs=dict(thresh=1.75), std=dict(gs=16, thresh=1.5), topk=dict(gs=16, topk=3), none={})[mode]
+        oc = check(bits, nbits, 8, asym, rule, mode, **kw)  # 4 groups of 8
+        n_out += oc.n_out
+    assert (n_out > 0) == (mode != "none")
+
+
+@pytest.mark.parametrize("nbits", [4, 8])
+@pytest.mark.parametrize("asym", [0, 1])
+def test_groups_that_are_no_power_of_two_and_an_odd_tail(nbits, asym):
+    """15 elements in groups of 5, statistics over all 15: the last byte of the int4 codes holds one
+    element; the pairwise sum is padded with a zero."""
+    for bits in tensors(21, 15):
+        check(bits, nbits, 5, asym, bf.PAPER, "std", gs=15, thresh=1.25)
+        check(bits, nbits, 5, asym, bf.FULLRANGE, "topk", gs=15, topk=2)
+        check(bits, nbits, 3, asym, bf.PAPER, "abs", thresh=0.5)
+
+
+@pytest.mark.parametrize("mode", ["abs", "std", "topk"])
+def test_values_that_are_not_finite(mode):
+    bits = tensors(33, 32)[0]
+    bits[3], bits[4], bits[20] = 0x7F80, 0xFFC1, 0xFF80  # +Inf, a NaN, -Inf
+    kw = dict(abs=dict(thresh=2.0), std=dict(gs=16, thresh=1.5), topk=dict(gs=16, topk=1))[mode]
+    for asym in (0, 1):
+        oc = check(bits, 4, 8, asym, bf.PAPER, mode, **kw)
+        assert {3, 4, 20} <= set(int(i) for i in oc.out_idx)
+    # more values that are not finite than the group's k: all of them are kept, and nothing else
+    bits[5], bits[6] = 0x7F80, 0x7FFF
+    oc = check(bits, 8, 8, 0, bf.PAPER, "topk", gs=16, topk=2)
+    assert [int(i) for i in oc.out_idx if i < 16] == [3, 4, 5, 6]
+
+
+def test_rounding_helpers_of_the_brute_force_against_numpy():
+    """The brute force's own binary32 / bf16 rounding, checked against the hardware's."""
+    rng = np.random.default_rng(5)
+    for _ in range(2000):
+        a, b = (float(np.float32(v)) for v in rng.standard_normal(2) * 10.0 ** rng.integers(-15, 15))
+        assert bf.f32(Fraction(a) * Fraction(b)) == Fraction(float(np.float32(a) * np.float32(b)))
+        assert bf.f32(Fraction(a) + Fraction(b)) == Fraction(float(np.float32(a) + np.float32(b)))
+        assert bf.f32(Fraction(a) / Fraction(b)) == Fraction(float(np.float32(a) / np.float32(b)))
+    import torch
+    pats = np.arange(0x10000, dtype=np.uint32)
+    pats = pats[(pats & 0x7F80) != 0x7F80].astype(np.uint16)
+    vals = torch.from_numpy(pats.view(np.int16).copy()).view(torch.bfloat16).to(torch.float32).numpy()
+    for p, v in zip(pats[::37], vals[::37]):
+        assert bf.bf16_value(int(p)) == Fraction(float(v))
+    x = torch.from_numpy((rng.standard_normal(3000) * 10.0 ** rng.integers(-38, 38, size=3000)).astype(np.float32))
+    want = x.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for v, w in zip(x.numpy(), want):
+        if np.isfinite(v) and (int(w) & 0x7F80) != 0x7F80:
+            assert bf.bf16_bits_of(Fraction(float(v))) == int(w)
