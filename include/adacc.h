@@ -43,6 +43,7 @@ extern "C" {
 #define ADACC_ESIZE (-3)  /* blob or workspace smaller than the layout requires       */
 #define ADACC_EALIGN (-4) /* a device pointer is not 16-byte aligned                  */
 #define ADACC_EHIP (-5)   /* a HIP runtime call failed (no device, launch failure)    */
+#define ADACC_ELIMIT (-6) /* size beyond the stated limit of the entry point          */
 
 /* ---- method descriptor ---- */
 #define ADACC_KIND_NOOP 0  /* tensor is retained as it is: nothing is read or written */
@@ -131,6 +132,18 @@ int adacc_workspace_init(adacc_workspace *ws, void *device_mem, uint64_t bytes, 
  * Errors: ENULL, EINVAL, ESIZE, EALIGN, EHIP. */
 int adacc_compress(const adacc_method *method, const void *src, uint64_t numel, void *blob,
                    uint64_t blob_bytes, adacc_workspace *ws, void *hip_stream);
+
+/* adacc_compress for callers that cannot allocate device memory at all (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same blob, but the
+ * words that order the outlier stream live in a device array inside the library (about 2 MiB per
+ * GPU the library runs on, held until the process ends) instead of a caller's workspace.  The call
+ * allocates and frees nothing.  Limit: numel <= ADACC_NOALLOC_MAX_NUMEL, else ADACC_ELIMIT.
+ * All calls on one GPU share that array: they may follow each other on one stream, or be ordered
+ * otherwise, but two that overlap on the GPU race.  The first call on a device also enqueues the
+ * clearing of the array on hip_stream.  Other errors as adacc_compress. */
+#define ADACC_NOALLOC_MAX_NUMEL (1ull << 29)
+int adacc_compress_noalloc(const adacc_method *method, const void *src, uint64_t numel, void *blob,
+                           uint64_t blob_bytes, void *hip_stream);
 
 /* adacc_decompress: Section 3.2 dequantisation (X^ = code*S, resp. code*S+O) followed by
  * the write-back of the outliers (Fig. 3(c) decompression workflow).

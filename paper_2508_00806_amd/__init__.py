@@ -13,13 +13,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadacc.so")
 
 # ---- constants of include/adacc.h
-OK, EINVAL, ENULL, ESIZE, EALIGN, EHIP = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ENULL, ESIZE, EALIGN, EHIP, ELIMIT = 0, -1, -2, -3, -4, -5, -6
 KIND_NOOP, KIND_QUANT = 0, 1
 OUTLIER_NONE, OUTLIER_ABS, OUTLIER_STD, OUTLIER_TOPK = 0, 1, 2, 3
 SCALE_PAPER, SCALE_FULLRANGE = 0, 1
 DST_BF16, DST_F32 = 0, 1
 
-EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "adacc_compress",
+EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "adacc_compress", "adacc_compress_noalloc",
            "adacc_decompress", "adacc_batch_workspace_bytes", "adacc_compress_batch",
            "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
            "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
@@ -126,6 +126,8 @@ def lib():
         L.adacc_workspace_init.restype = ci
         L.adacc_compress.argtypes = [pm, vp, u64, vp, u64, pw, vp]
         L.adacc_compress.restype = ci
+        L.adacc_compress_noalloc.argtypes = [pm, vp, u64, vp, u64, vp]
+        L.adacc_compress_noalloc.restype = ci
         L.adacc_decompress.argtypes = [pm, vp, u64, u64, vp, ci, vp]
         L.adacc_decompress.restype = ci
         pvp, pu64 = ctypes.POINTER(vp), ctypes.POINTER(u64)
@@ -257,6 +259,17 @@ def compress(method: Method, src, blob, workspace=None, numel=None, stream=None)
     cm = method.c()
     _check(lib().adacc_compress(ctypes.byref(cm), _ptr(src), numel, _ptr(blob), _nbytes(blob), _ws(workspace),
                                 _stream(stream)), "adacc_compress")
+
+
+NOALLOC_MAX_NUMEL = 1 << 29
+
+
+def compress_noalloc(method: Method, src, blob, numel=None, stream=None):
+    """adacc_compress_noalloc: no workspace argument, nothing is allocated by the call."""
+    numel = src.numel() if numel is None else numel
+    cm = method.c()
+    _check(lib().adacc_compress_noalloc(ctypes.byref(cm), _ptr(src), numel, _ptr(blob), _nbytes(blob),
+                                        _stream(stream)), "adacc_compress_noalloc")
 
 
 def decompress(method: Method, blob, dst, numel=None, stream=None):

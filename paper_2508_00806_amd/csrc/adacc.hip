@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "adacc.h"
@@ -422,6 +423,7 @@ const char* adacc_strerror(int code) {
     case ADACC_ESIZE: return "blob or workspace too small";
     case ADACC_EALIGN: return "device pointer not aligned";
     case ADACC_EHIP: return g_hip_err;
+    case ADACC_ELIMIT: return "size beyond the limit of this entry point";
     default: return "unknown error code";
   }
 }
@@ -455,8 +457,8 @@ int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, 
   return ADACC_OK;
 }
 
-int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
-                   adacc_workspace* ws, void* hip_stream) {
+static int compress_one(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
+                        adacc_workspace* ws, void* hip_stream) {
   if (!method) return ADACC_ENULL;
   Plan p;
   int rc = make_plan(method, numel, &p);
@@ -499,6 +501,48 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   uint64_t* state2 = p.outliers ? state1 + state1_bytes(p.n_tiles) / 8 : nullptr;
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, state1, state2, tag, spin_limit());
   return launch_check("compress_kernel");
+}
+
+int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
+                   adacc_workspace* ws, void* hip_stream) {
+  return compress_one(method, src, numel, blob, blob_bytes, ws, hip_stream);
+}
+
+// ---- the same for callers that cannot allocate: the scan state lives in a device array of the library
+constexpr uint64_t kNoallocScratchBytes = 2162688;  // state words of ADACC_NOALLOC_MAX_NUMEL elements in tiles of 2048
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
+int adacc_compress_noalloc(const adacc_method* method, const void* src, uint64_t numel, void* blob,
+                           uint64_t blob_bytes, void* hip_stream) {
+  if (!method) return ADACC_ENULL;
+  if (numel > ADACC_NOALLOC_MAX_NUMEL) return ADACC_ELIMIT;
+  Plan p;
+  int rc = make_plan(method, numel, &p);
+  if (rc != ADACC_OK) return rc;
+  if (p.noop || numel == 0 || !p.outliers) return compress_one(method, src, numel, blob, blob_bytes, nullptr, hip_stream);
+  if (state1_bytes(p.n_tiles) + state2_bytes(p.n_tiles, 1) > kNoallocScratchBytes) return ADACC_ELIMIT;
+  // Every device has its own copy of the array at its own address: looked up once per device, with
+  // that device current, and kept together with the launch counter of its state words.
+  static adacc_workspace per_device[64];
+  static std::mutex lock;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) return ADACC_EINVAL;
+  std::lock_guard<std::mutex> hold(lock);  // calls that share the array are serialised on the host; on the GPU they must not overlap
+  adacc_workspace* ws = &per_device[dev];
+  if (!ws->device_mem) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    // state words must start empty: cleared by a kernel on the caller's stream, before the first use
+    rc = clear_device(ptr, kNoallocScratchBytes, static_cast<hipStream_t>(hip_stream));
+    if (rc != ADACC_OK) return rc;
+    ws->device_mem = ptr;
+    ws->bytes = kNoallocScratchBytes;
+    ws->epoch = 0;
+  }
+  return compress_one(method, src, numel, blob, blob_bytes, ws, hip_stream);
 }
 
 int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob_bytes, uint64_t numel, void* dst,
