@@ -83,8 +83,7 @@ typedef struct adacc_method {
  *   idx,val  max_outliers int32 flat indices, ascending, and the bf16 bit patterns at
  *            those indices (structure of arrays).  Entries past the count are unspecified.
  *   status   4 uint32: [0] number of outliers found, [1] 1 if it exceeds max_outliers
- *            (the stream then holds the first max_outliers; the blob is not usable),
- *            [2] 1 if the kernel gave up waiting on another tile (blob not usable), [3] 0.
+ *            (the stream then holds the first max_outliers; the blob is not usable), [2], [3] 0.
  *            The rest of the 256-byte status block is scrap space of the kernels.
  */
 typedef struct adacc_layout {
@@ -99,13 +98,14 @@ typedef struct adacc_layout {
 int adacc_layout_of(const adacc_method *method, uint64_t numel, adacc_layout *out);
 
 /* ---- workspace ----
- * Compression with outliers orders the outlier stream across tiles in a single pass: the
- * wavefronts publish how many outliers their runs of tiles hold and sum the counts of the
- * runs before their own.  These words (at most 8 bytes per tile, plus 8 per 64 tiles) live in
- * a caller-owned device buffer described by an adacc_workspace.  The struct is HOST memory owned by the caller;
- * the library keeps its launch counter ("epoch") in it: state words written by earlier
- * launches carry an older epoch and read as empty, so the buffer is cleared only by
- * adacc_workspace_init and when the 30-bit epoch wraps, never per call.
+ * Compression with outliers takes every tile on its own (no tile waits for another) and settles the
+ * order of the outlier stream afterwards, in a second, small kernel.  Between the two, the number
+ * of outliers of every tile (4 bytes per tile) and, for ADACC_OUTLIER_ABS / _STD, the outliers
+ * themselves (a slot of 192 bytes per tile) wait in a caller-owned device buffer described by an
+ * adacc_workspace.  The struct is HOST memory owned by the caller; the library keeps a launch
+ * counter ("epoch") in it: a flag word written by an earlier launch carries an older epoch and
+ * reads as not set, so the buffer is cleared only by adacc_workspace_init and when the 30-bit
+ * epoch wraps, never per call.
  * Rules: initialise once with adacc_workspace_init; afterwards any number of calls may
  * reuse it, one at a time in stream order (calls that may overlap on the GPU, or host
  * threads that call concurrently, must use different workspaces). */
@@ -135,13 +135,15 @@ int adacc_compress(const adacc_method *method, const void *src, uint64_t numel, 
 
 /* adacc_compress for callers that cannot allocate device memory at all (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same blob, but the
- * words that order the outlier stream live in a device array inside the library (about 2 MiB per
- * GPU the library runs on, held until the process ends) instead of a caller's workspace.  The call
- * allocates and frees nothing.  Limit: numel <= ADACC_NOALLOC_MAX_NUMEL, else ADACC_ELIMIT.
- * All calls on one GPU share that array: they may follow each other on one stream, or be ordered
- * otherwise, but two that overlap on the GPU race.  The first call on a device also enqueues the
- * clearing of the array on hip_stream.  Other errors as adacc_compress. */
-#define ADACC_NOALLOC_MAX_NUMEL (1ull << 29)
+ * workspace is a device array inside the library (16 MiB per GPU the library runs on, held until
+ * the process ends) instead of a caller's buffer.  The call allocates and frees nothing.
+ * Limit: adacc_workspace_bytes(method, numel) <= 16 MiB, which holds for every method up to
+ * ADACC_NOALLOC_MAX_NUMEL elements (and for ADACC_OUTLIER_TOPK / _NONE at any legal size); beyond
+ * that the call returns ADACC_ELIMIT.  All calls on one GPU share that array: they may follow each
+ * other on one stream, or be ordered otherwise, but two that overlap on the GPU race.  The first
+ * call on a device also enqueues the clearing of the array on hip_stream.  Other errors as
+ * adacc_compress. */
+#define ADACC_NOALLOC_MAX_NUMEL (1ull << 27)
 int adacc_compress_noalloc(const adacc_method *method, const void *src, uint64_t numel, void *blob,
                            uint64_t blob_bytes, void *hip_stream);
 
@@ -156,11 +158,12 @@ int adacc_decompress(const adacc_method *method, const void *blob, uint64_t blob
                      void *dst, int dst_dtype, void *hip_stream);
 
 /* ---- batch: one call for a table of tensors (the per-tensor policy of Section 3.3,
- * R_{i,t}: compress or retain); the whole table is served by one kernel launch, or by two when
- * it mixes methods whose groups reach 4096 elements with smaller ones ----
+ * R_{i,t}: compress or retain); the tiles of the whole table are served by one kernel launch, or by
+ * two when it mixes methods whose groups reach 4096 elements with smaller ones, followed by one
+ * launch that places the outliers of all tensors ----
  * methods[i], srcs[i], numels[i], blobs[i], blob_bytes[i] describe tensor i; NOOP entries
- * are skipped.  The workspace holds the scan state of all tensors plus a device copy of the
- * table (adacc_batch_workspace_bytes device bytes); same init/reuse rules as above.
+ * are skipped.  The workspace holds what the single-tensor workspaces would hold plus a device copy
+ * of the table (adacc_batch_workspace_bytes device bytes); same init/reuse rules as above.
  * adacc_decompress_batch restores every non-NOOP tensor i into dsts[i]. */
 uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method *methods, const uint64_t *numels);
 int adacc_compress_batch(uint32_t n, const adacc_method *methods, const void *const *srcs,
@@ -276,10 +279,18 @@ int adacc_mask_unpack(const void *bits, uint64_t n, void *mask, void *hip_stream
  * Returns 0 for a malformed method. */
 uint64_t adacc_compressed_bytes(const adacc_method *method, uint64_t numel, uint64_t n_outliers);
 
-/* Plain streaming copy of `bytes` (multiple of 16) from src to dst: the practical HBM
- * ceiling the compression kernels are measured against, and the calibration
- * kernel for hardware byte counters.  With ADACC_COPY_STREAM=1 in the environment it uses the
- * non-temporal loads and stores that the tensor streams of the library use. */
+/* Streams of `bytes` (a multiple of 16) per operand in the access shape of the library's tensor
+ * kernels (4 KiB pieces per wavefront, full grid, non-temporal accesses): the practical HBM
+ * ceiling for a given mix of reads and writes, and the calibration kernels for hardware byte
+ * counters.  READ reads src_a; WRITE writes dst; COPY is dst = src_a; READ2_WRITE is
+ * dst = src_a ^ src_b (two bytes read per byte written, the mix of a decompression).  Operands a
+ * mix does not use may be NULL.  adacc_hbm_copy is the COPY mix.
+ * Errors: EINVAL, ENULL, EALIGN, EHIP. */
+#define ADACC_STREAM_READ 0
+#define ADACC_STREAM_WRITE 1
+#define ADACC_STREAM_COPY 2
+#define ADACC_STREAM_READ2_WRITE 3
+int adacc_hbm_stream(int mix, void *dst, const void *src_a, const void *src_b, uint64_t bytes, void *hip_stream);
 int adacc_hbm_copy(void *dst, const void *src, uint64_t bytes, void *hip_stream);
 
 /* Text for an error code; for ADACC_EHIP, the last HIP error string seen by this thread. */

@@ -21,7 +21,7 @@ DST_BF16, DST_F32 = 0, 1
 
 EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "adacc_compress", "adacc_compress_noalloc",
            "adacc_decompress", "adacc_batch_workspace_bytes", "adacc_compress_batch",
-           "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_strerror",
+           "adacc_decompress_batch", "adacc_read_status", "adacc_hbm_copy", "adacc_hbm_stream", "adacc_strerror",
            "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
            "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status",
            "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack", "adacc_compressed_bytes",
@@ -141,6 +141,8 @@ def lib():
         L.adacc_read_status.restype = ci
         L.adacc_hbm_copy.argtypes = [vp, vp, u64, vp]
         L.adacc_hbm_copy.restype = ci
+        L.adacc_hbm_stream.argtypes = [ci, vp, vp, vp, u64, vp]
+        L.adacc_hbm_stream.restype = ci
         L.adacc_strerror.argtypes = [ci]
         L.adacc_strerror.restype = ctypes.c_char_p
         pcm, pcl = ctypes.POINTER(CChannelMethod), ctypes.POINTER(CChannelLayout)
@@ -261,7 +263,7 @@ def compress(method: Method, src, blob, workspace=None, numel=None, stream=None)
                                 _stream(stream)), "adacc_compress")
 
 
-NOALLOC_MAX_NUMEL = 1 << 29
+NOALLOC_MAX_NUMEL = 1 << 27
 
 
 def compress_noalloc(method: Method, src, blob, numel=None, stream=None):
@@ -340,6 +342,14 @@ def read_status(blob, layout: CLayout, stream=None):
 def hbm_copy(dst, src, nbytes=None, stream=None):
     nbytes = _nbytes(src) if nbytes is None else nbytes
     _check(lib().adacc_hbm_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "adacc_hbm_copy")
+
+
+STREAM_READ, STREAM_WRITE, STREAM_COPY, STREAM_READ2_WRITE = 0, 1, 2, 3
+
+
+def hbm_stream(mix: int, dst, src_a, src_b, nbytes: int, stream=None):
+    p = lambda t: None if t is None else _ptr(t)
+    _check(lib().adacc_hbm_stream(mix, p(dst), p(src_a), p(src_b), nbytes, _stream(stream)), "adacc_hbm_stream")
 
 
 # ---------------------------------------------------------------- outlier channels (Section 3.2, Eq. 1)

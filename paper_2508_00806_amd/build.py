@@ -13,6 +13,7 @@ SOURCES = [os.path.join(CSRC, f) for f in (
     "adacc_k_none.hip", "adacc_k_abs.hip", "adacc_k_std.hip", "adacc_k_topk.hip",  # compress, per outlier mode
     "adacc_k_decompress.hip",
     "adacc_k_batch4.hip", "adacc_k_batch8.hip",
+    "adacc_k_place.hip",      # placement of the outliers in the stream
     "adacc_k_channel.hip",    # outlier channels by Z-score
     "adacc_k_mask.hip",       # dropout mask, byte <-> bit
     "adacc_k_channelwise.hip",  # channel-wise symmetric quantisation (Q / K / V)

@@ -21,7 +21,7 @@ namespace adacc {
 // The table of a batch reaches the device as kernel arguments, a slice per launch: the runtime
 // copies kernel arguments when the launch is enqueued, so the host buffer may go away at once
 // and the host never waits for the stream (a copy from pageable memory would).
-constexpr uint32_t kDescsPerUpload = 24;
+constexpr uint32_t kDescsPerUpload = 3968 / sizeof(TensorDesc);
 struct DescSlice { TensorDesc d[kDescsPerUpload]; };
 static_assert(sizeof(DescSlice) <= 3968, "kernel arguments are limited to 4 KiB");
 static_assert(sizeof(TensorDesc) % 4 == 0, "copied as 32-bit words");
@@ -39,17 +39,43 @@ __global__ __launch_bounds__(kThreads) void workspace_clear_kernel(uint4* p, uin
     p[i] = make_uint4(0, 0, 0, 0);
 }
 
-__global__ __launch_bounds__(kThreads) void hbm_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
-                                                            uint64_t n16) {
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+// small arrays of 32-bit words (the first-tile / first-block arrays of a batch) travel the same way
+constexpr uint32_t kWordsPerUpload = 960;
+struct WordSlice { uint32_t w[kWordsPerUpload]; };
+__global__ __launch_bounds__(kThreads) void words_upload_kernel(WordSlice slice, uint32_t* dst, uint32_t count) {
+  for (uint32_t i = threadIdx.x; i < count; i += kThreads) dst[i] = slice.w[i];
 }
-// the same with streaming (non-temporal) accesses, as the tensor streams of the library use them
-__global__ __launch_bounds__(kThreads) void hbm_copy_stream_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
-                                                                   uint64_t n16) {
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-    store_stream16(dst + i, load_stream16(src + i));
+
+// Streams of known size in the shape the tensor kernels use (one piece of 4 KiB per wavefront per
+// operand, full grid in the hardware's order, non-temporal accesses): what a kernel that only moves
+// bytes reaches on this part for a given mix of reads and writes.
+//   MIX 0: read a          1: write dst          2: dst = a (copy)          3: dst = a ^ b (two reads, one write)
+template <int MIX>
+__global__ __launch_bounds__(kThreads) void hbm_stream_kernel(uint4* __restrict__ dst, const uint4* __restrict__ a,
+                                                              const uint4* __restrict__ b, uint64_t n16,
+                                                              uint32_t* sink) {
+  const uint64_t piece = ((uint64_t)blockIdx.x * kWavesPerWg + threadIdx.x / kWave) * 256u + (threadIdx.x % kWave);
+  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+  uint4 v[4], w[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint64_t i = piece + (uint64_t)j * 64u;
+    const uint64_t ic = i < n16 ? i : n16 - 1u;
+    if constexpr (MIX != 1) v[j] = load_stream16(a + ic);
+    if constexpr (MIX == 3) w[j] = load_stream16(b + ic);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint64_t i = piece + (uint64_t)j * 64u;
+    if constexpr (MIX == 0) { acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w; }
+    if constexpr (MIX == 1) { if (i < n16) store_stream16(dst + i, make_uint4((uint32_t)i, 1u, 2u, 3u)); }
+    if constexpr (MIX == 2) { if (i < n16) store_stream16(dst + i, v[j]); }
+    if constexpr (MIX == 3) { if (i < n16) store_stream16(dst + i, make_uint4(v[j].x ^ w[j].x, v[j].y ^ w[j].y, v[j].z ^ w[j].z, v[j].w ^ w[j].w)); }
+  }
+  if constexpr (MIX == 0) {
+    // keeps the loads alive; practically never true, so nothing is written
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && sink) *sink = acc.x;
+  }
 }
 
 // ===================================================================== host side
@@ -66,6 +92,18 @@ static int env_int(const char* name, int dflt) {
   if (!s || !*s) return dflt;
   const long v = std::strtol(s, nullptr, 10);
   return v > 0 ? (int)v : dflt;
+}
+
+// Run-time knobs for measurements, read from the environment once per process.
+struct Knobs {
+  int grid_rounds;      // ADACC_GRID_ROUNDS: limit grids of independent tiles to this many rounds of resident workgroups
+  int wgs_per_cu;       // ADACC_WGS_PER_CU: overrides the occupancy query behind that limit
+  int mask_wgs_per_cu;  // ADACC_MASK_WGS_PER_CU: grid of the mask kernels
+};
+static const Knobs& knobs() {
+  static const Knobs k = {env_int("ADACC_GRID_ROUNDS", 0), env_int("ADACC_WGS_PER_CU", 0),
+                          env_int("ADACC_MASK_WGS_PER_CU", 128)};
+  return k;
 }
 
 static int device_cus(int* cus) {
@@ -169,24 +207,9 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
   int wgs = 0;
   const int rc = resident_wgs(kernel, &wgs);
   if (rc != ADACC_OK) return rc;
-  const int forced = env_int("ADACC_WGS_PER_CU", 0);
-  if (forced > 0) wgs = forced;
+  if (knobs().wgs_per_cu > 0) wgs = knobs().wgs_per_cu;
   *waves = (uint32_t)(cus * wgs * kWavesPerWg);
   return ADACC_OK;
-}
-
-// Tiles per run.  All runs take about the same time, so the launch proceeds in rounds of as many
-// runs as the device holds wavefronts; a last round that is only partly filled is wasted time.
-// The tiles are therefore cut into a whole number of full rounds (one, unless a run would get
-// longer than the limit), which also keeps the look-back short: its reach grows with the
-// number of runs in flight, not with the number of tiles.
-static uint32_t tiles_per_unit(uint64_t tiles_in_launch, uint32_t capacity) {
-  // longest run (the staging of tile offsets in a lane allows 64; measured best on large tensors: 16 to 32)
-  const uint64_t tmax = (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 32) > 64 ? 64 : (uint64_t)env_int("ADACC_MAX_TILES_PER_UNIT", 32);
-  if (tiles_in_launch <= capacity) return 1u;
-  const uint64_t rounds = (tiles_in_launch + (uint64_t)capacity * tmax - 1) / ((uint64_t)capacity * tmax);
-  const uint64_t units = (uint64_t)capacity * rounds;
-  return (uint32_t)((tiles_in_launch + units - 1) / units);
 }
 
 // TOPK whose statistics group is the tile has kernels of its own (for tiles of 8 rows: provided no
@@ -198,9 +221,28 @@ static bool topk_whole_tile(const adacc_method* m, const Plan& p) {
 
 static uint32_t decompress_pieces(uint64_t numel) { return (uint32_t)((numel + 2047ull) / 2048ull); }
 
+// Workspace of one tensor that keeps outliers: [cnt: one word per tile][flag][slot_idx][slot_val],
+// the slots for ABS / STD only.  Offsets relative to the tensor's region.
+struct WsPlan { uint64_t cnt_off, flag_off, slot_idx_off, slot_val_off, bytes; };
+static WsPlan ws_plan(const adacc_method* m, const Plan& p) {
+  WsPlan w;
+  std::memset(&w, 0, sizeof w);
+  if (p.noop || !p.outliers) return w;
+  uint64_t off = 0;
+  w.cnt_off = off;  off = align256(off + 4ull * p.n_tiles);
+  w.flag_off = off; off += 256;
+  if (m->outlier_mode != ADACC_OUTLIER_TOPK) {
+    w.slot_idx_off = off; off = align256(off + 4ull * kSlot * p.n_tiles);
+    w.slot_val_off = off; off = align256(off + 2ull * kSlot * p.n_tiles);
+  }
+  w.bytes = off;
+  return w;
+}
+static uint32_t place_blocks(const Plan& p) { return p.outliers ? (p.n_tiles + kPlaceTiles - 1) / kPlaceTiles : 0u; }
+
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
-                      void* blob, void* dst, int dst_dtype, uint32_t first_tile, uint32_t tpu, uint32_t first_unit,
-                      uint32_t first_block, TensorDesc* d) {
+                      void* blob, void* dst, int dst_dtype, uint32_t first_tile, uint32_t first_block, void* ws_region,
+                      TensorDesc* d) {
   std::memset(d, 0, sizeof *d);
   unsigned char* b = static_cast<unsigned char*>(blob);
   d->src = static_cast<const uint16_t*>(src);
@@ -212,17 +254,23 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
   d->idx = reinterpret_cast<int32_t*>(b + L.idx_off);
   d->val = reinterpret_cast<uint16_t*>(b + L.val_off);
   d->status = reinterpret_cast<uint32_t*>(b + L.status_off);
+  if (ws_region && p.outliers) {
+    const WsPlan w = ws_plan(m, p);
+    unsigned char* r = static_cast<unsigned char*>(ws_region);
+    d->cnt = reinterpret_cast<uint32_t*>(r + w.cnt_off);
+    d->flag = reinterpret_cast<uint32_t*>(r + w.flag_off);
+    d->slot_idx = reinterpret_cast<int32_t*>(r + w.slot_idx_off);
+    d->slot_val = reinterpret_cast<uint16_t*>(r + w.slot_val_off);
+  }
   d->numel = numel;
   d->n_tiles = p.n_tiles;
   d->first_tile = first_tile;
+  d->first_block = first_block;
+  d->lgt = p.tile_elems == 4096 ? 12u : 11u;
   if (dst) {  // decompression counts pieces of 2048 elements
     d->n_tiles = decompress_pieces(numel);
     d->ptr_shift = p.tile_elems == 4096 ? 1u : 0u;
   }
-  d->tiles_per_unit = tpu;
-  d->n_units = (p.n_tiles + tpu - 1) / tpu;
-  d->first_unit = first_unit;
-  d->first_block = first_block;
   d->lgq = p.lgq;
   d->lgs = p.lgs;
   d->cap = m->max_outliers;
@@ -240,8 +288,6 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
 
 static bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
-static uint32_t spin_limit() { return (uint32_t)env_int("ADACC_SPIN_LIMIT", 1 << 22); }
-
 // Grid for kernels whose tiles are independent (grid-stride loop).  By default one workgroup per
 // four tiles, i.e. every wavefront takes one tile: with streaming accesses the hardware's own
 // order of workgroups, which walks through memory front to back, beat every grid of resident
@@ -253,7 +299,7 @@ static uint32_t spin_limit() { return (uint32_t)env_int("ADACC_SPIN_LIMIT", 1 <<
 static int grid_for(uint32_t n_tiles, const void* kernel, uint32_t* grid, int resident_rounds = 0) {
   const uint64_t want = ((uint64_t)n_tiles + kWavesPerWg - 1) / kWavesPerWg;
   uint64_t cap = want;
-  const int rounds = env_int("ADACC_GRID_ROUNDS", resident_rounds);
+  const int rounds = knobs().grid_rounds > 0 ? knobs().grid_rounds : resident_rounds;
   if (rounds > 0) {
     int cus = 0;
     int rc = device_cus(&cus);
@@ -285,14 +331,14 @@ static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise, bool
 static int clear_device(void* mem, uint64_t bytes, hipStream_t s);
 
 // Next epoch of a workspace; clears the buffer first when the counter is about to wrap.
-static int next_tag(adacc_workspace* ws, hipStream_t s, uint32_t* tag) {
+static int next_epoch(adacc_workspace* ws, hipStream_t s, uint32_t* epoch) {
   if (ws->epoch >= kEpochMax) {
     const int rc = clear_device(ws->device_mem, ws->bytes, s);
     if (rc != ADACC_OK) return rc;
     ws->epoch = 0;
   }
   ws->epoch += 1;
-  *tag = ws->epoch << 2;
+  *epoch = ws->epoch;
   return ADACC_OK;
 }
 
@@ -314,6 +360,18 @@ static int upload_table(const std::vector<TensorDesc>& table, TensorDesc* dst, h
   return ADACC_OK;
 }
 
+static int upload_words(const std::vector<uint32_t>& words, uint32_t* dst, hipStream_t s) {
+  for (size_t i = 0; i < words.size(); i += kWordsPerUpload) {
+    WordSlice slice;
+    const uint32_t count = (uint32_t)std::min<size_t>(kWordsPerUpload, words.size() - i);
+    std::memcpy(slice.w, words.data() + i, count * sizeof(uint32_t));
+    hipLaunchKernelGGL(words_upload_kernel, dim3(1), dim3(kThreads), 0, s, slice, dst + i, count);
+    const int rc = launch_check("words_upload_kernel");
+    if (rc != ADACC_OK) return rc;
+  }
+  return ADACC_OK;
+}
+
 static int clear_device(void* mem, uint64_t bytes, hipStream_t s) {
   const uint64_t n16 = bytes / 16;
   uint32_t grid = (uint32_t)((n16 + kThreads - 1) / kThreads);
@@ -323,21 +381,17 @@ static int clear_device(void* mem, uint64_t bytes, hipStream_t s) {
   return launch_check("workspace_clear_kernel");
 }
 
-// scan state of a launch over `tiles` tiles: [state1: one word per run, at most one per tile]
-// [state2: one word per block of 64 runs]; every tensor of a batch starts a new block
-static uint64_t state1_bytes(uint64_t tiles) { return align256(8ull * tiles); }
-static uint64_t state2_bytes(uint64_t tiles, uint64_t tensors) { return align256(8ull * (tiles / kWave + tensors + 1)); }
-
-// batch workspace: [state1][state2][table n*sizeof(TensorDesc)]
+// batch workspace: [table: n descriptors][first_tile: n+1 words][first_block: n+1 words][the tensors' regions]
 struct BatchPlan {
-  uint32_t total_tiles;
-  uint64_t table_off, bytes;
+  uint64_t first_tile_off, first_block_off, regions_off, bytes;
 };
-static BatchPlan batch_plan(uint32_t total_tiles, uint32_t n_active) {
+static BatchPlan batch_plan(uint32_t n_active, uint64_t region_bytes) {
   BatchPlan b;
-  b.total_tiles = total_tiles;
-  b.table_off = state1_bytes(total_tiles) + state2_bytes(total_tiles, n_active);
-  b.bytes = align256(b.table_off + (uint64_t)(n_active ? n_active : 1) * sizeof(TensorDesc));
+  const uint64_t n = n_active ? n_active : 1;
+  b.first_tile_off = align256(n * sizeof(TensorDesc));
+  b.first_block_off = b.first_tile_off + align256(4ull * (n + 1));
+  b.regions_off = b.first_block_off + align256(4ull * (n + 1));
+  b.bytes = b.regions_off + region_bytes;
   return b;
 }
 
@@ -440,8 +494,8 @@ int adacc_layout_of(const adacc_method* method, uint64_t numel, adacc_layout* ou
 uint64_t adacc_workspace_bytes(const adacc_method* method, uint64_t numel) {
   if (!method) return 0;
   Plan p;
-  if (make_plan(method, numel, &p) != ADACC_OK || p.noop || !p.outliers) return 0;
-  return state1_bytes(p.n_tiles) + state2_bytes(p.n_tiles, 1);
+  if (make_plan(method, numel, &p) != ADACC_OK) return 0;
+  return ws_plan(method, p).bytes;
 }
 
 int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, void* hip_stream) {
@@ -471,36 +525,28 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
   if (misaligned(src, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   if (p.outliers) {
     if (!ws || !ws->device_mem) return ADACC_ENULL;
-    if (ws->bytes < state1_bytes(p.n_tiles) + state2_bytes(p.n_tiles, 1)) return ADACC_ESIZE;
+    if (ws->bytes < ws_plan(method, p).bytes) return ADACC_ESIZE;
     if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   }
   int cus = 0;
   rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
   if (rc != ADACC_OK) return rc;
-  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise,
-                              topk_whole_tile(method, p));
-  uint32_t tpu = 1u;
-  if (p.outliers) {
-    uint32_t capacity = 0;
-    rc = wave_capacity(reinterpret_cast<const void*>(fn), cus, &capacity);
-    if (rc != ADACC_OK) return rc;
-    tpu = tiles_per_unit(p.n_tiles, capacity);
-  }
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise, topk_whole_tile(method, p));
   TensorDesc d;
-  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, tpu, 0, 0, &d);
+  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, 0, p.outliers ? ws->device_mem : nullptr, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  uint32_t grid = 0, tag = 0;
-  if (p.outliers) {
-    grid = (d.n_units + kWavesPerWg - 1) / kWavesPerWg;  // runs start in index order: no grid-stride loop
-    rc = next_tag(ws, s, &tag);
-  } else {
-    rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), &grid);
-  }
+  uint32_t grid = 0, epoch = 0;
+  rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), &grid);
   if (rc != ADACC_OK) return rc;
-  uint64_t* state1 = p.outliers ? static_cast<uint64_t*>(ws->device_mem) : nullptr;
-  uint64_t* state2 = p.outliers ? state1 + state1_bytes(p.n_tiles) / 8 : nullptr;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, state1, state2, tag, spin_limit());
-  return launch_check("compress_kernel");
+  if (p.outliers) {
+    rc = next_epoch(ws, s, &epoch);
+    if (rc != ADACC_OK) return rc;
+  }
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, epoch);
+  rc = launch_check("compress_kernel");
+  if (rc != ADACC_OK || !p.outliers) return rc;
+  hipLaunchKernelGGL(place_fn(), dim3(place_blocks(p)), dim3(kPlaceThreads), 0, s, d, epoch);
+  return launch_check("place_kernel");
 }
 
 int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
@@ -508,21 +554,20 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
   return compress_one(method, src, numel, blob, blob_bytes, ws, hip_stream);
 }
 
-// ---- the same for callers that cannot allocate: the scan state lives in a device array of the library
-constexpr uint64_t kNoallocScratchBytes = 2162688;  // state words of ADACC_NOALLOC_MAX_NUMEL elements in tiles of 2048
+// ---- the same for callers that cannot allocate: the workspace is a device array of the library
+constexpr uint64_t kNoallocScratchBytes = 16ull << 20;
 static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
 
 int adacc_compress_noalloc(const adacc_method* method, const void* src, uint64_t numel, void* blob,
                            uint64_t blob_bytes, void* hip_stream) {
   if (!method) return ADACC_ENULL;
-  if (numel > ADACC_NOALLOC_MAX_NUMEL) return ADACC_ELIMIT;
   Plan p;
   int rc = make_plan(method, numel, &p);
   if (rc != ADACC_OK) return rc;
   if (p.noop || numel == 0 || !p.outliers) return compress_one(method, src, numel, blob, blob_bytes, nullptr, hip_stream);
-  if (state1_bytes(p.n_tiles) + state2_bytes(p.n_tiles, 1) > kNoallocScratchBytes) return ADACC_ELIMIT;
+  if (ws_plan(method, p).bytes > kNoallocScratchBytes) return ADACC_ELIMIT;
   // Every device has its own copy of the array at its own address: looked up once per device, with
-  // that device current, and kept together with the launch counter of its state words.
+  // that device current, and kept together with the launch counter of the words in it.
   static adacc_workspace per_device[64];
   static std::mutex lock;
   int dev = 0;
@@ -535,7 +580,8 @@ int adacc_compress_noalloc(const adacc_method* method, const void* src, uint64_t
     void* ptr = nullptr;
     e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
     if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
-    // state words must start empty: cleared by a kernel on the caller's stream, before the first use
+    // the flag word of a tensor must not hold a value that a later launch counter takes: cleared by a
+    // kernel on the caller's stream before the first use
     rc = clear_device(ptr, kNoallocScratchBytes, static_cast<hipStream_t>(hip_stream));
     if (rc != ADACC_OK) return rc;
     ws->device_mem = ptr;
@@ -559,7 +605,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0, 0, &d);
+  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 0, nullptr, &d);
   DecompressFn fn = decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
   uint32_t grid = 0;
   rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid);
@@ -569,20 +615,22 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
 }
 
 static int batch_prepare(uint32_t n, const adacc_method* methods, const uint64_t* numels, std::vector<Plan>* plans,
-                         uint32_t* total_tiles, uint32_t* n_active) {
+                         uint32_t* total_tiles, uint32_t* n_active, uint64_t* region_bytes) {
   plans->resize(n);
-  uint64_t tiles = 0;
+  uint64_t tiles = 0, regions = 0;
   uint32_t act = 0;
   for (uint32_t i = 0; i < n; ++i) {
     const int rc = make_plan(&methods[i], numels[i], &(*plans)[i]);
     if (rc != ADACC_OK) return rc;
     if ((*plans)[i].noop || numels[i] == 0) { (*plans)[i].noop = true; continue; }
     tiles += (*plans)[i].n_tiles;
+    regions += ws_plan(&methods[i], (*plans)[i]).bytes;
     ++act;
   }
   if (tiles >= (1ull << 32)) return ADACC_EINVAL;
   *total_tiles = (uint32_t)tiles;
   *n_active = act;
+  *region_bytes = regions;
   return ADACC_OK;
 }
 
@@ -590,15 +638,22 @@ uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method* methods, co
   if (n && (!methods || !numels)) return 0;
   std::vector<Plan> plans;
   uint32_t total = 0, act = 0;
-  if (batch_prepare(n, methods, numels, &plans, &total, &act) != ADACC_OK) return 0;
-  return batch_plan(total, act).bytes;
+  uint64_t regions = 0;
+  if (batch_prepare(n, methods, numels, &plans, &total, &act, &regions) != ADACC_OK) return 0;
+  return batch_plan(act, regions).bytes;
 }
 
+// Descriptors of the active tensors of a batch, with the launch-wide numbering of their tiles (pieces
+// for decompression) and of their placement blocks.
+struct BatchTable {
+  std::vector<TensorDesc> descs;
+  std::vector<uint32_t> first_tile, first_block;  // one entry per descriptor plus the totals
+};
 static int batch_table(uint32_t n, const adacc_method* methods, const std::vector<Plan>& plans, const uint64_t* numels,
                        const void* const* srcs, void* const* blobs, const uint64_t* blob_bytes, void* const* dsts,
-                       int dst_dtype, bool compress, uint32_t tpu, std::vector<TensorDesc>* table,
-                       uint32_t* total_units) {
-  uint32_t first = 0, first_unit = 0, first_block = 0;
+                       int dst_dtype, bool compress, unsigned char* regions, BatchTable* t) {
+  uint32_t first = 0, first_block = 0;
+  uint64_t region_off = 0;
   for (uint32_t i = 0; i < n; ++i) {
     if (plans[i].noop) continue;
     if (!blobs[i]) return ADACC_ENULL;
@@ -610,13 +665,18 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
     if (compress ? misaligned(srcs[i], 16) : misaligned(dsts[i], 16)) return ADACC_EALIGN;
     TensorDesc d;
     fill_desc(&methods[i], numels[i], plans[i], L, compress ? srcs[i] : nullptr, blobs[i], compress ? nullptr : dsts[i],
-              dst_dtype, first, tpu, first_unit, first_block, &d);
-    table->push_back(d);
-    first += compress ? plans[i].n_tiles : d.n_tiles;
-    first_unit += d.n_units;
-    first_block += (d.n_units + kWave - 1) / kWave;
+              dst_dtype, first, first_block, compress ? regions + region_off : nullptr, &d);
+    t->descs.push_back(d);
+    t->first_tile.push_back(first);
+    t->first_block.push_back(first_block);
+    first += d.n_tiles;
+    if (compress) {
+      first_block += place_blocks(plans[i]);
+      region_off += ws_plan(&methods[i], plans[i]).bytes;
+    }
   }
-  if (total_units) *total_units = first_unit;
+  t->first_tile.push_back(first);
+  t->first_block.push_back(first_block);
   return ADACC_OK;
 }
 
@@ -626,48 +686,43 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   if (!methods || !srcs || !numels || !blobs || !blob_bytes) return ADACC_ENULL;
   std::vector<Plan> plans;
   uint32_t total = 0, act = 0;
-  int rc = batch_prepare(n, methods, numels, &plans, &total, &act);
+  uint64_t region_bytes = 0;
+  int rc = batch_prepare(n, methods, numels, &plans, &total, &act, &region_bytes);
   if (rc != ADACC_OK) return rc;
   if (act == 0) return ADACC_OK;
   if (!ws || !ws->device_mem) return ADACC_ENULL;
-  const BatchPlan bp = batch_plan(total, act);
+  const BatchPlan bp = batch_plan(act, region_bytes);
   if (ws->bytes < bp.bytes) return ADACC_ESIZE;
   if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
-  std::vector<TensorDesc> table;
-  uint32_t total_units = 0;
-  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, 1u, &table, &total_units);
+  unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
+  BatchTable t;
+  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, mem + bp.regions_off, &t);
   if (rc != ADACC_OK) return rc;  // every argument is checked before the device is touched
   int cus = 0;
   rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
   bool any_four = false, any_eight = false;
-  for (const TensorDesc& t : table) ((t.variant & 1u) ? any_eight : any_four) = true;
-  // run length from the kernel that most tensors use (the other one simply takes more rounds)
-  uint32_t capacity = 0;
-  rc = wave_capacity(reinterpret_cast<const void*>(compress_batch_fn(!any_four)), cus, &capacity);
-  if (rc != ADACC_OK) return rc;
-  table.clear();
-  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true,
-                   tiles_per_unit(total, capacity), &table, &total_units);
-  if (rc != ADACC_OK) return rc;
+  for (const TensorDesc& d : t.descs) ((d.variant & 1u) ? any_eight : any_four) = true;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  uint32_t tag = 0;
-  rc = next_tag(ws, s, &tag);
+  uint32_t epoch = 0;
+  rc = next_epoch(ws, s, &epoch);
   if (rc != ADACC_OK) return rc;
-  unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
-  rc = upload_table(table, reinterpret_cast<TensorDesc*>(mem + bp.table_off), s);
+  TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
+  uint32_t* ft = reinterpret_cast<uint32_t*>(mem + bp.first_tile_off);
+  uint32_t* fb = reinterpret_cast<uint32_t*>(mem + bp.first_block_off);
+  rc = upload_table(t.descs, dt, s);
+  if (rc == ADACC_OK) rc = upload_words(t.first_tile, ft, s);
+  if (rc == ADACC_OK) rc = upload_words(t.first_block, fb, s);
   if (rc != ADACC_OK) return rc;
-  const uint32_t grid = (total_units + kWavesPerWg - 1) / kWavesPerWg;
-  const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
-  uint64_t* st1 = reinterpret_cast<uint64_t*>(mem);
-  uint64_t* st2 = reinterpret_cast<uint64_t*>(mem + state1_bytes(total));
-  if (any_four)
-    hipLaunchKernelGGL(compress_batch_fn(false), dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
-                       total_units, st1, st2, tag, spin_limit());
-  if (any_eight)
-    hipLaunchKernelGGL(compress_batch_fn(true), dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(),
-                       total_units, st1, st2, tag, spin_limit());
-  return launch_check("compress_batch_kernel");
+  const uint32_t grid = (total + kWavesPerWg - 1) / kWavesPerWg;
+  const uint32_t nt = (uint32_t)t.descs.size();
+  if (any_four) hipLaunchKernelGGL(compress_batch_fn(false), dim3(grid), dim3(kThreads), 0, s, dt, ft, nt, total, epoch);
+  if (any_eight) hipLaunchKernelGGL(compress_batch_fn(true), dim3(grid), dim3(kThreads), 0, s, dt, ft, nt, total, epoch);
+  rc = launch_check("compress_batch_kernel");
+  const uint32_t blocks = t.first_block.back();
+  if (rc != ADACC_OK || blocks == 0) return rc;
+  hipLaunchKernelGGL(place_batch_fn(), dim3(blocks), dim3(kPlaceThreads), 0, s, dt, fb, nt, epoch);
+  return launch_check("place_batch_kernel");
 }
 
 int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* const* blobs, const uint64_t* blob_bytes,
@@ -678,29 +733,31 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
   std::vector<Plan> plans;
   uint32_t total = 0, act = 0;
-  int rc = batch_prepare(n, methods, numels, &plans, &total, &act);
+  uint64_t region_bytes = 0;
+  int rc = batch_prepare(n, methods, numels, &plans, &total, &act, &region_bytes);
   if (rc != ADACC_OK) return rc;
   if (act == 0) return ADACC_OK;
   if (!ws || !ws->device_mem) return ADACC_ENULL;
-  const BatchPlan bp = batch_plan(total, act);
+  const BatchPlan bp = batch_plan(act, region_bytes);
   if (ws->bytes < bp.bytes) return ADACC_ESIZE;
   if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
-  std::vector<TensorDesc> table;
+  BatchTable t;
   rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
-                   false, 1u, &table, nullptr);
+                   false, nullptr, &t);
   if (rc != ADACC_OK) return rc;
-  uint32_t pieces = 0;
-  for (const TensorDesc& t : table) pieces += t.n_tiles;
+  const uint32_t pieces = t.first_tile.back();
   const BatchDecompressFn fn = decompress_batch_fn(dst_dtype == ADACC_DST_F32);
   uint32_t grid = 0;
   rc = grid_for(pieces, reinterpret_cast<const void*>(fn), &grid);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
-  rc = upload_table(table, reinterpret_cast<TensorDesc*>(mem + bp.table_off), s);
+  TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
+  uint32_t* ft = reinterpret_cast<uint32_t*>(mem + bp.first_tile_off);
+  rc = upload_table(t.descs, dt, s);
+  if (rc == ADACC_OK) rc = upload_words(t.first_tile, ft, s);
   if (rc != ADACC_OK) return rc;
-  const TensorDesc* dt = reinterpret_cast<const TensorDesc*>(mem + bp.table_off);
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, dt, (uint32_t)table.size(), pieces);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, dt, ft, (uint32_t)t.descs.size(), pieces);
   return launch_check("decompress_batch_kernel");
 }
 
@@ -746,7 +803,7 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
   if (workspace_bytes < adacc_channel_workspace_bytes(tokens, hidden)) return ADACC_ESIZE;
   if (misaligned(src, 16) || misaligned(blob, 256) || misaligned(workspace, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, src, blob, nullptr, 0, 0, 1u, 0, 0, &d);
+  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, src, blob, nullptr, 0, 0, 0, nullptr, &d);
   ChannelDesc c;
   fill_channel_desc(method, tokens, hidden, L, blob, &c);
   float* partial = static_cast<float*>(workspace);
@@ -788,8 +845,8 @@ int adacc_channel_decompress(const adacc_channel_method* method, const void* blo
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 1u, 0,
-            0, &d);
+  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 0,
+            nullptr, &d);
   ChannelDesc c;
   fill_channel_desc(method, tokens, hidden, L, const_cast<void*>(blob), &c);
   ChannelFn fn = channel_decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
@@ -925,7 +982,7 @@ static int mask_launch(MaskFn fn, const void* in, uint64_t n, void* out, void* h
   if (rc != ADACC_OK) return rc;
   const uint64_t pieces = n / 16u;  // one lane turns over 16 elements at a time, eight times per round
   uint64_t grid = (pieces + 8ull * kThreads - 1) / (8ull * kThreads);
-  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_MASK_WGS_PER_CU", 128);
+  const uint64_t cap = (uint64_t)cus * (uint64_t)knobs().mask_wgs_per_cu;
   if (grid > cap) grid = cap;
   if (grid == 0) grid = 1;
   hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
@@ -952,27 +1009,31 @@ uint64_t adacc_compressed_bytes(const adacc_method* method, uint64_t numel, uint
   return bytes;
 }
 
-int adacc_hbm_copy(void* dst, const void* src, uint64_t bytes, void* hip_stream) {
-  if (!dst || !src) return ADACC_ENULL;
+int adacc_hbm_stream(int mix, void* dst, const void* src_a, const void* src_b, uint64_t bytes, void* hip_stream) {
+  if (mix < ADACC_STREAM_READ || mix > ADACC_STREAM_READ2_WRITE) return ADACC_EINVAL;
+  const bool wr = mix != ADACC_STREAM_READ, rd = mix != ADACC_STREAM_WRITE, rd2 = mix == ADACC_STREAM_READ2_WRITE;
+  if ((wr && !dst) || (rd && !src_a) || (rd2 && !src_b)) return ADACC_ENULL;
   if (bytes % 16 != 0) return ADACC_EINVAL;
-  if (misaligned(dst, 16) || misaligned(src, 16)) return ADACC_EALIGN;
+  if ((wr && misaligned(dst, 16)) || (rd && misaligned(src_a, 16)) || (rd2 && misaligned(src_b, 16))) return ADACC_EALIGN;
   if (bytes == 0) return ADACC_OK;
-  int cus = 0;
-  const int rc = device_cus(&cus);
-  if (rc != ADACC_OK) return rc;
   const uint64_t n16 = bytes / 16;
-  uint64_t grid = (n16 + kThreads - 1) / kThreads;
-  const uint64_t cap = (uint64_t)cus * (uint64_t)env_int("ADACC_COPY_WGS_PER_CU", 16);
-  if (grid > cap) grid = cap;
-  // ADACC_COPY_STREAM=1: with the streaming accesses of the library's tensor streams (default: plain
-  // loads and stores, which is also what the byte counters were calibrated with)
-  if (env_int("ADACC_COPY_STREAM", 0) != 0)
-    hipLaunchKernelGGL(hbm_copy_stream_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
-  else
-    hipLaunchKernelGGL(hbm_copy_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
-  return launch_check("hbm_copy_kernel");
+  const uint64_t grid = (n16 + 1023u) / 1024u;  // a workgroup moves 4 x 4 KiB per operand
+  if (grid >= (1ull << 31)) return ADACC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  uint4* d = static_cast<uint4*>(dst);
+  const uint4* a = static_cast<const uint4*>(src_a);
+  const uint4* b = static_cast<const uint4*>(src_b);
+  switch (mix) {
+    case ADACC_STREAM_READ: hipLaunchKernelGGL(hbm_stream_kernel<0>, dim3((uint32_t)grid), dim3(kThreads), 0, s, d, a, b, n16, static_cast<uint32_t*>(dst)); break;
+    case ADACC_STREAM_WRITE: hipLaunchKernelGGL(hbm_stream_kernel<1>, dim3((uint32_t)grid), dim3(kThreads), 0, s, d, a, b, n16, nullptr); break;
+    case ADACC_STREAM_COPY: hipLaunchKernelGGL(hbm_stream_kernel<2>, dim3((uint32_t)grid), dim3(kThreads), 0, s, d, a, b, n16, nullptr); break;
+    default: hipLaunchKernelGGL(hbm_stream_kernel<3>, dim3((uint32_t)grid), dim3(kThreads), 0, s, d, a, b, n16, nullptr); break;
+  }
+  return launch_check("hbm_stream_kernel");
+}
+
+int adacc_hbm_copy(void* dst, const void* src, uint64_t bytes, void* hip_stream) {
+  return adacc_hbm_stream(ADACC_STREAM_COPY, dst, src, nullptr, bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -79,13 +79,15 @@ struct TensorDesc {
   int32_t* idx;
   uint16_t* val;
   uint32_t* status;
+  uint32_t* cnt;            // compress, workspace: outliers found in every tile
+  int32_t* slot_idx;        // compress, workspace (ABS / STD): kSlot entries per tile, the tile's outliers
+  uint16_t* slot_val;       //   until the placement kernel has moved them to the stream
+  uint32_t* flag;           // compress, workspace (TOPK): set to the epoch by a tile whose count is not the regular one
   uint64_t numel;
   uint32_t n_tiles;
-  uint32_t first_tile;      // launch-wide id of this tensor's tile 0 (batch decompress)
-  uint32_t tiles_per_unit;  // compress: tiles one wavefront handles one after the other ("run")
-  uint32_t n_units;         // ceil(n_tiles / tiles_per_unit)
-  uint32_t first_unit;      // launch-wide id of this tensor's run 0 (compress)
-  uint32_t first_block;     // launch-wide id of this tensor's first block of 64 runs (compress)
+  uint32_t first_tile;      // launch-wide id of this tensor's tile 0 (batch)
+  uint32_t first_block;     // launch-wide id of this tensor's first block of kPlaceTiles tiles (batch placement)
+  uint32_t lgt;             // log2(elements per tile): 11 or 12
   uint32_t lgq;         // log2(quant group)
   uint32_t lgs;         // log2(stat group) (STD / TOPK)
   uint32_t cap;         // capacity of idx / val
@@ -128,11 +130,14 @@ struct ChannelwiseDesc {
   float inv_hidden;     // 1 / hidden rounded towards zero twice
 };
 
-// Scan workspace: one 64-bit state word per run of tiles and one per block of 64 runs, high half
-// = (epoch << 2) | flag, low half = value.  The epoch is a per-workspace launch counter kept on the host (adacc_workspace);
-// words written by earlier launches carry another epoch and read as empty, so the buffer is
-// cleared only once, when it is set up, and again when the 30-bit epoch wraps.
-enum : uint32_t { kFlagEmpty = 0, kFlagAggregate = 1, kFlagPrefix = 2, kFlagAbort = 3 };
+// Outliers of a tile that travel through the tile's slot in the workspace (ABS / STD); a tile with
+// more is selected a second time by the placement kernel.
+constexpr int kSlot = 32;
+// The placement kernels: a workgroup of kPlaceThreads threads takes kPlaceTiles consecutive tiles.
+constexpr int kPlaceThreads = 256;
+constexpr int kPlaceTiles = 512;
+// The workspace's launch counter ("epoch", kept on the host in adacc_workspace) marks what a launch
+// wrote: a word that holds an older epoch reads as not set, so nothing has to be cleared per call.
 constexpr uint32_t kEpochMax = 0x3FFFFFFFu;
 
 // variant index: ((mode*2 + (bits==8)) * 2 + asym) * 2 + (E==8)

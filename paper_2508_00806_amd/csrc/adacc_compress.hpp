@@ -164,82 +164,9 @@ __device__ __forceinline__ uint32_t wave_max_u32_scalar(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// sum over the whole wavefront, returned in a scalar register (same scheme as the maximum: this
-// sits on the path every run takes between learning the earlier totals and writing its outliers)
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
-  struct OpUAdd { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; } };
-  v = lanes_reduce<16>(v, OpUAdd());
-  int t = __builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
-  v += (uint32_t)t;
-  t = __builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);      // row_bcast:31
-  v += (uint32_t)t;
-  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-
 // number of set bits of a wavefront mask in the lanes below this one
 __device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-}
-
-// ------------------------------------------------------------------ offsets of the runs in the outlier stream
-// The scan unit is a "run": the consecutive tiles that one wavefront compresses one after the
-// other.  All runs of a launch end at about the same time, so a chain in which every run waits
-// for its predecessor's prefix would add one memory round trip per link to the end of the
-// kernel.  Instead the totals are summed in two levels, without any chain:
-//   state1[u]  total of run u                          (published by run u when it is done)
-//   state2[b]  total of block b = runs [64b, 64b+64)   (published by the block's last run,
-//              which waits for the 63 others of its block)
-// and the offset of run u is the sum of state2 over the blocks before its own plus the sum of
-// state1 over the runs before it in its own block: two polls, each one load per lane.
-// Runs are numbered in launch order (workgroup index, wavefront index) and a run only ever
-// waits for lower-numbered ones, which the hardware has dispatched earlier.  The poll bound is
-// a second line of defence: when it trips, the run publishes "abort", which every run that
-// polls it inherits, so the kernel always drains and reports the failure in the status words.
-struct ScanCtx {
-  uint64_t* state1;
-  uint64_t* state2;
-  uint32_t tag;         // epoch << 2
-  uint32_t spin_limit;  // polls before a wavefront gives up
-};
-
-__device__ __forceinline__ uint64_t ld_state(const uint64_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_state(uint64_t* p, uint32_t hi, uint32_t lo) {
-  __hip_atomic_store(p, ((uint64_t)hi << 32) | lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void scan_publish(uint64_t* state, uint32_t i, uint32_t tag_flag, uint32_t value) {
-  if (lane_id() == 0) st_state(&state[i], tag_flag, value);
-}
-
-// Waits until the words state[lo..hi) of this launch are all published and returns the sum of
-// their values (0 for an empty range).
-__device__ __forceinline__ uint32_t scan_poll_sum(const ScanCtx& sc, const uint64_t* state, uint32_t lo, uint32_t hi,
-                                                  bool& aborted) {
-  const uint32_t lane = (uint32_t)lane_id();
-  uint32_t sum = 0u;
-  for (uint32_t i0 = lo; i0 < hi && !aborted; i0 += kWave) {  // uniform
-    const uint32_t i = i0 + lane;
-    const bool in = i < hi;
-    uint32_t flag = kFlagAggregate, value = 0u, polls = 0u;
-    while (true) {
-      if (in) {
-        const uint64_t w = ld_state(&state[i]);
-        const uint32_t h = (uint32_t)(w >> 32);
-        flag = ((h & ~3u) == sc.tag) ? (h & 3u) : (uint32_t)kFlagEmpty;
-        value = (uint32_t)w;
-      }
-      if (__builtin_amdgcn_ballot_w64(flag == kFlagEmpty) == 0ull) break;
-      if (++polls > sc.spin_limit) { aborted = true; break; }
-#ifndef ADACC_POLL_SLEEP
-#define ADACC_POLL_SLEEP 4
-#endif
-      __builtin_amdgcn_s_sleep(ADACC_POLL_SLEEP);  // a short pause between polls (units of 64 clocks)
-    }
-    if (__builtin_amdgcn_ballot_w64(flag == kFlagAbort) != 0ull) aborted = true;
-    sum += value;
-  }
-  return aborted ? 0u : wave_sum_u32(sum);
 }
 
 // ------------------------------------------------------------------ rounding and packing of codes
@@ -1081,148 +1008,182 @@ __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const
   });
 }
 
-// ------------------------------------------------------------------ one run of tiles (outlier modes)
-constexpr int kStageCap = 256;  // outliers a wavefront can hold back in LDS while its offset is unknown
-struct WaveStage {
-  int32_t idx[kStageCap];
-  uint16_t val[kStageCap];
+// ------------------------------------------------------------------ one tile with outliers (ABS / STD / TOPK)
+// Tiles are independent: a wavefront compresses one tile and never waits for another.  What the
+// ordered outlier stream needs from all tiles together - the offset of every tile - is settled
+// afterwards by place_block (below), from the per-tile counts written here.
+//
+// ABS / STD: the tile's outliers (ascending) go to the tile's own slot of kSlot entries in the
+// workspace; the placement kernel moves them to their final position.  A tile with more than
+// kSlot outliers leaves the rest out; the placement kernel then selects that tile's outliers from
+// the source once more.
+// TOPK: every statistics group has exactly topk outliers unless it holds more than topk values that
+// are not finite, so the offsets are known in advance: group g starts at topk * g.  The outliers
+// are written to their final position at once, and a tile that finds another count raises the
+// tensor's flag (the current epoch of the workspace); only then does the placement kernel do
+// anything, and it then does everything again from the source.
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
+__device__ __forceinline__ void compress_tile_outliers(const TensorDesc& d, uint32_t tile, uint32_t epoch) {
+  static_assert(MODE != kModeNone, "tiles without outliers have compress_tile_plain");
+  uint32_t raw[E][4];
+  TileOutliers<E> out;
+  const bool last = tile + 1u == d.n_tiles;
+  if (WHOLE || !last) {  // only the last tile can be short: the copy for the others knows nothing of it
+    load_tile<E, true>(d, tile, raw);
+    const TileGeo<E> g = tile_geo<E, true>(d, tile);
+    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
+  } else {
+    load_tile<E, false>(d, tile, raw);
+    const TileGeo<E> g = tile_geo<E, false>(d, tile);
+    blank_tail<E>(g, raw);
+    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
+  }
+  const bool lane0 = lane_id() == 0;
+  if constexpr (MODE == kModeTopk) {
+    const uint32_t per_tile = d.topk << (d.lgt - d.lgs);           // outliers of a complete, regular tile
+    const uint32_t pos0 = per_tile * tile;
+    uint32_t expected = per_tile;
+    if (last) expected = d.topk * (uint32_t)((d.numel - (uint64_t)tile * (uint64_t)(E * kRow)) >> d.lgs);
+    if (lane0) {
+      d.tile_ptr[tile] = pos0;
+      d.cnt[tile] = out.total;
+      if (out.total != expected) *d.flag = epoch;
+      if (last) {
+        const uint32_t n_out = pos0 + expected;
+        d.tile_ptr[d.n_tiles] = n_out;
+        d.status[0] = n_out; d.status[1] = n_out > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
+      }
+    }
+    const uint32_t end = pos0 + expected;
+    if (out.total != 0u) emit_outliers<E>(raw, out, tile, d.idx, d.val, pos0, end < d.cap ? end : d.cap);
+  } else {
+    if (lane0) d.cnt[tile] = out.total;
+    if (out.total != 0u) {
+      const uint64_t slot = (uint64_t)tile * (uint64_t)kSlot;
+      emit_outliers<E>(raw, out, tile, d.slot_idx + slot, d.slot_val + slot, 0u, (uint32_t)kSlot);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ placement of the outliers (a4)
+// One workgroup of kPlaceThreads threads takes a block of kPlaceTiles consecutive tiles: it adds up
+// the counts of all tiles before its block (every workgroup does that sum itself, straight from the
+// counts: a few hundred kilobytes from the L2 at most, and nobody waits for anybody), scans the
+// counts of its own tiles, writes their offsets, and moves the outliers of its tiles from the slots
+// to their final positions, output position by output position (coalesced stores; the tile of a
+// position is found by bisection over the block's offsets in LDS).  Tiles that hold more outliers
+// than a slot takes (or all tiles, `reselect_all`) are selected again from the source, one
+// wavefront per tile, and written straight to the stream.
+struct PlaceShared {
+  uint32_t excl[kPlaceTiles + 1];  // offsets of the block's tiles relative to the block, and the block total
+  uint32_t part[kPlaceThreads / kWave];
 };
 
-// One wavefront compresses the tiles [unit*T, unit*T + T) of a tensor one after the other.  The
-// outliers of the run are collected in LDS; when the run is done its total is published, the
-// offset of the run in the stream is resolved, and the staged outliers are copied out in one
-// coalesced sweep.  No run waits for anything before it has published its own total.
-//
-// A run whose outliers do not fit the staging area keeps encoding and counting but stops
-// collecting; once its offset is known it goes over its uncollected tiles a second time
-// (load, select, nothing else) and writes their outliers straight to the stream.  Dense
-// outliers therefore cost a second read of the input, never a chain of runs waiting for each
-// other.
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
-__device__ __forceinline__ void compress_run(const TensorDesc& d, uint32_t unit, const ScanCtx& sc, WaveStage* stage) {
-  static_assert(MODE != kModeNone, "runs exist for the scan only");
-  const int lane = lane_id();
-  const uint32_t T = d.tiles_per_unit;
-  const uint32_t t0 = unit * T;
-  const uint32_t t1 = (t0 + T < d.n_tiles) ? t0 + T : d.n_tiles;
-  const uint32_t gunit = d.first_unit + unit;                // index into state1
-  const uint32_t block = unit / kWave;                       // block of 64 runs, local to the tensor
-  const uint32_t gblock0 = d.first_block;                    // index of the tensor's block 0 in state2
-  const uint32_t gunit_block0 = d.first_unit + block * kWave;  // first run of this run's block in state1
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  struct OpUAdd { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; } };
+  v = lanes_reduce<16>(v, OpUAdd());
+  int t = __builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  v += (uint32_t)t;
+  t = __builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);      // row_bcast:31
+  v += (uint32_t)t;
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
 
-  uint32_t run_total = 0u;   // outliers of the run so far
-  uint32_t staged = 0u;      // of which are waiting in LDS
-  uint32_t collected = t1;   // first tile whose outliers were not collected (t1: none)
-  uint32_t tile_off = 0u;    // lane k: outliers of the run before its k-th tile
-
-  // Tiles of 4 rows: the next tile is in flight while this one is encoded.  Tiles of 8 rows are
-  // loaded when their turn comes: a second tile in registers would halve the wavefronts per SIMD.
-  constexpr bool kPrefetch = (E == 4);
-  // what a finished tile adds to the run: its offset, and its outliers to the staging area while they fit
-  auto account = [&](uint32_t t, const TileOutliers<E>& out, const uint32_t (&tile_raw)[E][4]) {
-    if ((uint32_t)lane == t - t0) tile_off = run_total;
-    if (out.total != 0u) {
-      if (collected == t1 && staged + out.total > (uint32_t)kStageCap) collected = t;  // no room from here on
-      if (collected == t1) {
-        emit_outliers<E>(tile_raw, out, t, stage->idx, stage->val, staged, (uint32_t)kStageCap);
-        staged += out.total;
-      }
-      run_total += out.total;
-    }
-  };
-
-  // Only the last tile of a tensor can be short.  The loop takes the complete tiles of the run with an
-  // encoder that carries no arithmetic, masks or branches for short ones; a short last tile follows on
-  // its own.
-  const bool short_last = !WHOLE && t1 == d.n_tiles && (d.numel & (uint64_t)(E * kRow - 1)) != 0u;
-  const uint32_t t1c = short_last ? t1 - 1u : t1;
-  uint32_t raw[E][4];
-  if constexpr (kPrefetch) {
-    if (t0 < t1c) {
-      load_tile<E, true>(d, t0, raw);
-      // Let the first tile arrive before the loop is entered.  Inside the loop the current tile is then
-      // complete on every path, and the only wait left is the one for the prefetched tile at the end of
-      // an iteration, which the compiler can count exactly (vmcnt(0), other counters untouched).
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-    }
-  }
-  for (uint32_t t = t0; t < t1c; ++t) {
-    uint32_t nxt[kPrefetch ? E : 1][4];
-    // the last iteration has nothing to fetch ahead: its (unconditional) loads go to the tensor's first
-    // tile, which every run's last iteration reads and which therefore stays in the cache (fetching the
-    // current tile again would be a second trip to memory, because streaming loads are not retained)
-    if constexpr (kPrefetch) load_tile<E, true>(d, (t + 1 < t1c) ? t + 1 : 0u, nxt);
-    else load_tile<E, true>(d, t, raw);
-
-    const TileGeo<E> g = tile_geo<E, true>(d, t);
-    TileOutliers<E> out;
-    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
-    account(t, out, raw);
-    if constexpr (kPrefetch) {
+// sum over the workgroup (kPlaceThreads threads), returned to every thread
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, PlaceShared& sh) {
+  const uint32_t w = wave_sum_u32(v);
+  const uint32_t wave = threadIdx.x / kWave;
+  __syncthreads();  // earlier readers of part[] are done
+  if (lane_id() == 0) sh.part[wave] = w;
+  __syncthreads();
+  uint32_t s = 0u;
 #pragma unroll
-      for (int j = 0; j < E; ++j) {
-        raw[j][0] = nxt[j][0]; raw[j][1] = nxt[j][1]; raw[j][2] = nxt[j][2]; raw[j][3] = nxt[j][3];
+  for (int i = 0; i < kPlaceThreads / kWave; ++i) s += sh.part[i];
+  return s;
+}
+
+// select the outliers of one tile again and write them to the stream from position `pos`
+template <int MODE, int E, bool ROWWISE, bool WHOLE>
+__device__ __forceinline__ void reselect_tile(const TensorDesc& d, uint32_t tile, uint32_t pos) {
+  uint32_t raw[E][4];
+  TileOutliers<E> out;
+  load_tile<E, false>(d, tile, raw);
+  const TileGeo<E> g = tile_geo<E, false>(d, tile);
+  blank_tail<E>(g, raw);
+  encode_tile<MODE, 8, false, E, ROWWISE, WHOLE, false>(d, g, raw, out);
+  if (out.total != 0u) emit_outliers<E>(raw, out, tile, d.idx, d.val, pos, d.cap);
+}
+
+template <int MODE, int E, bool ROWWISE, bool WHOLE>
+__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool reselect_all, PlaceShared& sh) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t first = block * (uint32_t)kPlaceTiles;
+  // counts of all tiles before this block (first is a multiple of 4: whole 16-byte loads)
+  uint32_t before = 0u;
+  const uint4* c4 = reinterpret_cast<const uint4*>(d.cnt);
+  for (uint32_t i = tid; i < first / 4u; i += (uint32_t)kPlaceThreads) {
+    const uint4 v = c4[i];
+    before += (v.x + v.y) + (v.z + v.w);
+  }
+  before = block_sum_u32(before, sh);
+  // this thread's two tiles
+  const uint32_t t0 = first + 2u * tid;
+  const uint32_t c0 = t0 < d.n_tiles ? d.cnt[t0] : 0u;
+  const uint32_t c1 = t0 + 1u < d.n_tiles ? d.cnt[t0 + 1u] : 0u;
+  // exclusive scan over the workgroup: inside the wavefront by shuffles, across wavefronts through LDS
+  const uint32_t mine = c0 + c1;
+  uint32_t incl = mine;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)incl, off);
+    if (lane_id() >= off) incl += up;
+  }
+  const uint32_t wave = tid / kWave;
+  __syncthreads();
+  if (lane_id() == kWave - 1) sh.part[wave] = incl;
+  __syncthreads();
+  uint32_t wave_before = 0u, total = 0u;
+#pragma unroll
+  for (int i = 0; i < kPlaceThreads / kWave; ++i) {
+    wave_before += (uint32_t)i < wave ? sh.part[i] : 0u;
+    total += sh.part[i];
+  }
+  const uint32_t e0 = wave_before + incl - mine;  // relative to the block
+  sh.excl[2u * tid] = e0;
+  sh.excl[2u * tid + 1u] = e0 + c0;
+  if (tid == 0) sh.excl[kPlaceTiles] = total;
+  if (t0 < d.n_tiles) d.tile_ptr[t0] = before + e0;
+  if (t0 + 1u < d.n_tiles) d.tile_ptr[t0 + 1u] = before + e0 + c0;
+  const uint32_t n_here = d.n_tiles - first < (uint32_t)kPlaceTiles ? d.n_tiles - first : (uint32_t)kPlaceTiles;
+  if (first + n_here == d.n_tiles && tid == 0) {  // the block that holds the last tile also closes the blob
+    const uint32_t n_out = before + total;
+    d.tile_ptr[d.n_tiles] = n_out;
+    d.status[0] = n_out; d.status[1] = n_out > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
+  }
+  __syncthreads();
+  // from the slots to the stream
+  if (!reselect_all) {
+    for (uint32_t p = tid; p < total; p += (uint32_t)kPlaceThreads) {
+      uint32_t lo = 0u, hi = n_here;  // last tile j with excl[j] <= p (tiles without outliers share their successor's offset)
+      while (hi - lo > 1u) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (sh.excl[mid] <= p) lo = mid; else hi = mid;
+      }
+      const uint32_t n_tile = sh.excl[lo + 1u] - sh.excl[lo];
+      const uint32_t dst = before + p;
+      if (n_tile <= (uint32_t)kSlot && dst < d.cap) {
+        const uint64_t src = (uint64_t)(first + lo) * (uint64_t)kSlot + (p - sh.excl[lo]);
+        d.idx[dst] = d.slot_idx[src];
+        d.val[dst] = d.slot_val[src];
       }
     }
   }
-  if constexpr (!WHOLE) {
-    if (short_last) {
-      const uint32_t t = t1c;
-      load_tile<E, false>(d, t, raw);
-      const TileGeo<E> g = tile_geo<E, false>(d, t);
-      blank_tail<E>(g, raw);
-      TileOutliers<E> out;
-      encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
-      account(t, out, raw);
-    }
-  }
-
-  // The run is complete: make its total visible, then find its offset in the stream.  The last
-  // run of a block closes the block as soon as it knows the totals of the block's other runs,
-  // BEFORE it looks at earlier blocks: no block's total depends on another block's, so the
-  // longest chain of waits is two (a run's total -> its block's total -> every later run).
-  bool aborted = false;
-  scan_publish(sc.state1, gunit, sc.tag | kFlagAggregate, run_total);
-  const bool closes_block = (unit % kWave) == kWave - 1;
-  const uint32_t in_block = scan_poll_sum(sc, sc.state1, gunit_block0, gunit, aborted);
-  if (closes_block)
-    scan_publish(sc.state2, gblock0 + block, sc.tag | (aborted ? kFlagAbort : kFlagAggregate), in_block + run_total);
-  uint32_t excl = in_block;  // outliers of the tensor before this run
-  if (!aborted) excl += scan_poll_sum(sc, sc.state2, gblock0, gblock0 + block, aborted);
-  if (aborted) {
-    scan_publish(sc.state1, gunit, sc.tag | kFlagAbort, 0u);
-    if (closes_block) scan_publish(sc.state2, gblock0 + block, sc.tag | kFlagAbort, 0u);
-  }
-
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  if (!aborted) {
-    for (uint32_t i = (uint32_t)lane; i < staged; i += kWave) {
-      const uint32_t p = excl + i;
-      if (p < d.cap) { d.idx[p] = stage->idx[i]; d.val[p] = stage->val[i]; }
-    }
-    if ((uint32_t)lane < t1 - t0) d.tile_ptr[t0 + (uint32_t)lane] = excl + tile_off;
-    // second pass over the tiles whose outliers were only counted
-    for (uint32_t t = collected; t < t1; ++t) {
-      load_tile<E, WHOLE>(d, t, raw);
-      const TileGeo<E> g = tile_geo<E, WHOLE>(d, t);
-      blank_tail<E>(g, raw);
-      TileOutliers<E> out;
-      encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE, false>(d, g, raw, out);
-      const uint32_t before = (uint32_t)__builtin_amdgcn_readlane((int)tile_off, (int)(t - t0));
-      if (out.total != 0u) emit_outliers<E>(raw, out, t, d.idx, d.val, excl + before, d.cap);
-    }
-  }
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the staging area is reused by the next run
-  if (lane == 0) {
-    if (t1 == d.n_tiles) {
-      const uint32_t n_out = excl + run_total;
-      d.tile_ptr[d.n_tiles] = n_out;
-      d.status[0] = n_out;
-      d.status[1] = (n_out > d.cap) ? 1u : 0u;
-      d.status[3] = 0u;
-      if (!aborted) d.status[2] = 0u;
-    }
-    if (aborted) d.status[2] = 1u;
+  // tiles whose outliers are not (all) in a slot: once more from the source, a wavefront per tile
+  const uint32_t w = __builtin_amdgcn_readfirstlane(tid / kWave);
+  for (uint32_t j = w; j < n_here; j += (uint32_t)(kPlaceThreads / kWave)) {
+    const uint32_t n_tile = sh.excl[j + 1u] - sh.excl[j];
+    if (n_tile > (reselect_all ? 0u : (uint32_t)kSlot))
+      reselect_tile<MODE, E, ROWWISE, WHOLE>(d, first + j, before + sh.excl[j]);
   }
 }
 

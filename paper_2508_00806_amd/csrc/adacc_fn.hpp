@@ -6,10 +6,12 @@
 
 namespace adacc {
 
-typedef void (*CompressFn)(TensorDesc, uint64_t*, uint64_t*, uint32_t, uint32_t);
+typedef void (*CompressFn)(TensorDesc, uint32_t);
 typedef void (*DecompressFn)(TensorDesc, uint32_t);
-typedef void (*BatchCompressFn)(const TensorDesc*, uint32_t, uint32_t, uint64_t*, uint64_t*, uint32_t, uint32_t);
-typedef void (*BatchDecompressFn)(const TensorDesc*, uint32_t, uint32_t);
+typedef void (*BatchCompressFn)(const TensorDesc*, const uint32_t*, uint32_t, uint32_t, uint32_t);
+typedef void (*BatchDecompressFn)(const TensorDesc*, const uint32_t*, uint32_t, uint32_t);
+typedef void (*PlaceFn)(TensorDesc, uint32_t);
+typedef void (*PlaceBatchFn)(const TensorDesc*, const uint32_t*, uint32_t, uint32_t);
 
 // e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
 CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
@@ -19,6 +21,8 @@ CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);
 DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);
 BatchCompressFn compress_batch_fn(bool eight_rows);
 BatchDecompressFn decompress_batch_fn(bool f32);
+PlaceFn place_fn();
+PlaceBatchFn place_batch_fn();
 
 // outlier channels (Section 3.2, Eq. 1)
 typedef void (*ChannelPartialFn)(const uint16_t*, uint32_t, uint32_t, float*, uint32_t);

@@ -10,9 +10,8 @@
 
 namespace adacc {
 
-// ---- single tensor, compress.  With outliers: run = 4 * workgroup + wavefront, and the grid is
-// exactly ceil(n_units / 4) workgroups, because the chained scan relies on runs being started
-// in index order.  NONE: tiles are independent, grid-stride loop over tiles.
+// ---- single tensor, compress: tiles are independent, one tile per wavefront, workgroups in the
+// hardware's own order (which walks through memory front to back).
 // the symmetric whole-tile TOPK kernels for 8-row tiles fit 4 wavefronts per SIMD when asked to
 #ifndef ADACC_WHOLE8_MIN_WAVES
 #define ADACC_WHOLE8_MIN_WAVES 4
@@ -21,20 +20,16 @@ namespace adacc {
 #define ADACC_COMPRESS_MIN_WAVES 1
 #endif
 template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
-__global__ __launch_bounds__(kThreads, (E == 8 && WHOLE && !ASYM) ? ADACC_WHOLE8_MIN_WAVES : ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint64_t* state1,
-                                                                                      uint64_t* state2, uint32_t tag,
-                                                                                      uint32_t spin_limit) {
+__global__ __launch_bounds__(kThreads, (E == 8 && WHOLE && !ASYM) ? ADACC_WHOLE8_MIN_WAVES : ADACC_COMPRESS_MIN_WAVES) void compress_kernel(TensorDesc d, uint32_t epoch) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  if constexpr (MODE == kModeNone) {
-    for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-      compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
-  } else {
-    __shared__ WaveStage stage[kWavesPerWg];
-    const ScanCtx sc{state1, state2, tag, spin_limit};
-    const uint32_t u = blockIdx.x * kWavesPerWg + wave;
-    if (u < d.n_units) compress_run<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, u, sc, &stage[wave]);
+  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg) {
+    if constexpr (MODE == kModeNone) compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
+    else compress_tile_outliers<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, t, epoch);
   }
 }
+
+// TOPK whose statistics group is the whole tile has an encoder of its own
+__device__ __forceinline__ bool topk_whole(const TensorDesc& d) { return d.lgs == d.lgt && d.lgq <= 11u; }
 
 // d.n_tiles counts pieces of 2048 elements here
 template <int BITS, bool ASYM, bool F32>
@@ -47,130 +42,117 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint
 }
 
 // ---- batch: a launch-wide tile numbering over all tensors of the table
-template <bool BY_UNIT>
-__device__ __forceinline__ uint32_t find_tensor(const TensorDesc* table, uint32_t n, uint32_t g) {
-  uint32_t lo = 0u, hi = n;  // first_tile / first_unit ascend; find the last entry that starts at or before g
-  while (hi - lo > 1u) {
-    const uint32_t mid = (lo + hi) >> 1;
-    const uint32_t first = BY_UNIT ? table[mid].first_unit : table[mid].first_tile;
-    if (first <= g) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
 // Variants with tiles of 8 rows need about twice the registers of those with 4; a kernel that
 // held both would run everything at the occupancy of the heaviest.  So the batch comes as two
 // kernels over the same table, and a wavefront whose tensor belongs to the other one leaves.
 template <int MODE, bool EIGHT_ROWS>
-__device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
-                                                       WaveStage* stage) {
+__device__ __forceinline__ void compress_dispatch_mode(const TensorDesc& d, uint32_t tile, uint32_t epoch) {
   if constexpr (!EIGHT_ROWS) {
     if (d.rowwise) {  // groups inside a row
       switch (d.variant & 6u) {
-        case 0: compress_run<MODE, 4, false, 4, true>(d, unit, sc, stage); break;
-        case 2: compress_run<MODE, 4, true, 4, true>(d, unit, sc, stage); break;
-        case 4: compress_run<MODE, 8, false, 4, true>(d, unit, sc, stage); break;
-        default: compress_run<MODE, 8, true, 4, true>(d, unit, sc, stage); break;
+        case 0: compress_tile_outliers<MODE, 4, false, 4, true>(d, tile, epoch); break;
+        case 2: compress_tile_outliers<MODE, 4, true, 4, true>(d, tile, epoch); break;
+        case 4: compress_tile_outliers<MODE, 8, false, 4, true>(d, tile, epoch); break;
+        default: compress_tile_outliers<MODE, 8, true, 4, true>(d, tile, epoch); break;
       }
       return;
     }
     switch (d.variant & 6u) {
-      case 0: compress_run<MODE, 4, false, 4, false>(d, unit, sc, stage); break;
-      case 2: compress_run<MODE, 4, true, 4, false>(d, unit, sc, stage); break;
-      case 4: compress_run<MODE, 8, false, 4, false>(d, unit, sc, stage); break;
-      default: compress_run<MODE, 8, true, 4, false>(d, unit, sc, stage); break;
+      case 0: compress_tile_outliers<MODE, 4, false, 4, false>(d, tile, epoch); break;
+      case 2: compress_tile_outliers<MODE, 4, true, 4, false>(d, tile, epoch); break;
+      case 4: compress_tile_outliers<MODE, 8, false, 4, false>(d, tile, epoch); break;
+      default: compress_tile_outliers<MODE, 8, true, 4, false>(d, tile, epoch); break;
     }
   } else {
     switch (d.variant & 6u) {
-      case 0: compress_run<MODE, 4, false, 8, false>(d, unit, sc, stage); break;
-      case 2: compress_run<MODE, 4, true, 8, false>(d, unit, sc, stage); break;
-      case 4: compress_run<MODE, 8, false, 8, false>(d, unit, sc, stage); break;
-      default: compress_run<MODE, 8, true, 8, false>(d, unit, sc, stage); break;
+      case 0: compress_tile_outliers<MODE, 4, false, 8, false>(d, tile, epoch); break;
+      case 2: compress_tile_outliers<MODE, 4, true, 8, false>(d, tile, epoch); break;
+      case 4: compress_tile_outliers<MODE, 8, false, 8, false>(d, tile, epoch); break;
+      default: compress_tile_outliers<MODE, 8, true, 8, false>(d, tile, epoch); break;
     }
   }
 }
 
 // TOPK over the whole tile: the specialised encoder
 template <bool EIGHT_ROWS>
-__device__ __forceinline__ void compress_dispatch_topk_whole(const TensorDesc& d, uint32_t unit, const ScanCtx& sc,
-                                                             WaveStage* stage) {
+__device__ __forceinline__ void compress_dispatch_topk_whole(const TensorDesc& d, uint32_t tile, uint32_t epoch) {
   constexpr int kRows = EIGHT_ROWS ? 8 : 4;
   switch (d.variant & 6u) {
-    case 0: compress_run<kModeTopk, 4, false, kRows, false, true>(d, unit, sc, stage); break;
-    case 2: compress_run<kModeTopk, 4, true, kRows, false, true>(d, unit, sc, stage); break;
-    case 4: compress_run<kModeTopk, 8, false, kRows, false, true>(d, unit, sc, stage); break;
-    default: compress_run<kModeTopk, 8, true, kRows, false, true>(d, unit, sc, stage); break;
+    case 0: compress_tile_outliers<kModeTopk, 4, false, kRows, false, true>(d, tile, epoch); break;
+    case 2: compress_tile_outliers<kModeTopk, 4, true, kRows, false, true>(d, tile, epoch); break;
+    case 4: compress_tile_outliers<kModeTopk, 8, false, kRows, false, true>(d, tile, epoch); break;
+    default: compress_tile_outliers<kModeTopk, 8, true, kRows, false, true>(d, tile, epoch); break;
   }
 }
 
-template <int BITS, bool ASYM, int E, bool ROWWISE>
-__device__ __forceinline__ void compress_plain_run(const TensorDesc& d, uint32_t unit) {
-  const uint32_t t0 = unit * d.tiles_per_unit;
-  const uint32_t t1 = (t0 + d.tiles_per_unit < d.n_tiles) ? t0 + d.tiles_per_unit : d.n_tiles;
-  for (uint32_t t = t0; t < t1; ++t) compress_tile_plain<BITS, ASYM, E, ROWWISE>(d, t);
+// first[i] = launch-wide id of the first tile (or block) of table entry i, first[n] = the total:
+// the entry that holds id g, by bisection over that compact array (scalar loads from a few cache lines)
+__device__ __forceinline__ uint32_t find_entry(const uint32_t* first, uint32_t n, uint32_t g) {
+  uint32_t lo = 0u, hi = n;
+  while (hi - lo > 1u) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (first[mid] <= g) lo = mid; else hi = mid;
+  }
+  return lo;
 }
 
-// One launch (per register class) for a table of tensors: runs are numbered across the table; a
-// wavefront finds its tensor by binary search and dispatches on that tensor's method.
+// One launch (per register class) for a table of tensors: tiles are numbered across the table; a
+// wavefront finds the tensor of its tile and dispatches on that tensor's method.
 // The kernel for tiles of 8 rows is held to 3 wavefronts per SIMD: the variants that matter
 // (TOPK over the whole tile) fit, the rarely used ones spill a few registers.
 #ifndef ADACC_BATCH8_MIN_WAVES
 #define ADACC_BATCH8_MIN_WAVES 3
 #endif
 template <bool EIGHT_ROWS>
-__global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) void compress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                  uint32_t total_units, uint64_t* state1,
-                                                                  uint64_t* state2, uint32_t tag,
-                                                                  uint32_t spin_limit) {
-  __shared__ WaveStage stage[kWavesPerWg];
+__global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) void compress_batch_kernel(const TensorDesc* table, const uint32_t* first_tile, uint32_t n,
+                                                                  uint32_t total_tiles, uint32_t epoch) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  const ScanCtx sc{state1, state2, tag, spin_limit};
   const uint32_t g = blockIdx.x * kWavesPerWg + wave;
-  if (g >= total_units) return;
-  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<true>(table, n, g));
+  if (g >= total_tiles) return;
+  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_entry(first_tile, n, g));
   const TensorDesc d = table[ti];
   if (((d.variant & 1u) != 0u) != EIGHT_ROWS) return;
-  const uint32_t unit = g - d.first_unit;
+  const uint32_t tile = g - d.first_tile;
   switch (d.variant >> 3) {
     case kModeNone:
       if constexpr (!EIGHT_ROWS) {
         if (d.rowwise) {
           switch (d.variant & 6u) {
-            case 0: compress_plain_run<4, false, 4, true>(d, unit); break;
-            case 2: compress_plain_run<4, true, 4, true>(d, unit); break;
-            case 4: compress_plain_run<8, false, 4, true>(d, unit); break;
-            default: compress_plain_run<8, true, 4, true>(d, unit); break;
+            case 0: compress_tile_plain<4, false, 4, true>(d, tile); break;
+            case 2: compress_tile_plain<4, true, 4, true>(d, tile); break;
+            case 4: compress_tile_plain<8, false, 4, true>(d, tile); break;
+            default: compress_tile_plain<8, true, 4, true>(d, tile); break;
           }
           break;
         }
         switch (d.variant & 6u) {
-          case 0: compress_plain_run<4, false, 4, false>(d, unit); break;
-          case 2: compress_plain_run<4, true, 4, false>(d, unit); break;
-          case 4: compress_plain_run<8, false, 4, false>(d, unit); break;
-          default: compress_plain_run<8, true, 4, false>(d, unit); break;
+          case 0: compress_tile_plain<4, false, 4, false>(d, tile); break;
+          case 2: compress_tile_plain<4, true, 4, false>(d, tile); break;
+          case 4: compress_tile_plain<8, false, 4, false>(d, tile); break;
+          default: compress_tile_plain<8, true, 4, false>(d, tile); break;
         }
       } else {
         switch (d.variant & 6u) {
-          case 0: compress_plain_run<4, false, 8, false>(d, unit); break;
-          case 2: compress_plain_run<4, true, 8, false>(d, unit); break;
-          case 4: compress_plain_run<8, false, 8, false>(d, unit); break;
-          default: compress_plain_run<8, true, 8, false>(d, unit); break;
+          case 0: compress_tile_plain<4, false, 8, false>(d, tile); break;
+          case 2: compress_tile_plain<4, true, 8, false>(d, tile); break;
+          case 4: compress_tile_plain<8, false, 8, false>(d, tile); break;
+          default: compress_tile_plain<8, true, 8, false>(d, tile); break;
         }
       }
       break;
-    case kModeAbs: compress_dispatch_mode<kModeAbs, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
-    case kModeStd: compress_dispatch_mode<kModeStd, EIGHT_ROWS>(d, unit, sc, &stage[wave]); break;
+    case kModeAbs: compress_dispatch_mode<kModeAbs, EIGHT_ROWS>(d, tile, epoch); break;
+    case kModeStd: compress_dispatch_mode<kModeStd, EIGHT_ROWS>(d, tile, epoch); break;
     default:
-      if (d.lgs == (EIGHT_ROWS ? 12u : 11u) && d.lgq <= 11u) compress_dispatch_topk_whole<EIGHT_ROWS>(d, unit, sc, &stage[wave]);
-      else compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, unit, sc, &stage[wave]);
+      if (topk_whole(d)) compress_dispatch_topk_whole<EIGHT_ROWS>(d, tile, epoch);
+      else compress_dispatch_mode<kModeTopk, EIGHT_ROWS>(d, tile, epoch);
       break;
   }
 }
 
 // Batch decompression: a launch-wide numbering of the 2048-element pieces of all tensors.
 template <bool F32>
-__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, uint32_t n,
-                                                                    uint32_t total_tiles) {
+__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, const uint32_t* first_tile,
+                                                                    uint32_t n, uint32_t total_tiles) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<4, F32>()];
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
   unsigned char* slice = lds + wave * decompress_lds_per_wave<4, F32>();
@@ -179,14 +161,14 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
   // the tensor changes.
   uint32_t g = blockIdx.x * kWavesPerWg + wave;
   if (g >= total_tiles) return;
-  uint32_t ti = __builtin_amdgcn_readfirstlane(find_tensor<false>(table, n, g));
+  uint32_t ti = __builtin_amdgcn_readfirstlane(find_entry(first_tile, n, g));
   TensorDesc d = table[ti];
-  uint32_t next_first = (ti + 1u < n) ? table[ti + 1u].first_tile : 0xFFFFFFFFu;
+  uint32_t next_first = first_tile[ti + 1u];  // first_tile[n] = total_tiles
   for (; g < total_tiles; g += gridDim.x * kWavesPerWg) {
     if (g >= next_first) {
       do {
         ++ti;
-        next_first = (ti + 1u < n) ? table[ti + 1u].first_tile : 0xFFFFFFFFu;
+        next_first = first_tile[ti + 1u];
       } while (g >= next_first);
       d = table[ti];
     }

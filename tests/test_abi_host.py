@@ -63,7 +63,9 @@ def test_layout_closed_form(L):
     # no-op: nothing
     lay0 = adacc.layout_of(adacc.NOOP, 12345)
     assert lay0.total_bytes == 0 and lay0.n_tiles == 0
-    assert adacc.workspace_bytes(m, n) == a(8 * 37) + a(8 * 2)
+    # workspace: one count per tile and a flag word; threshold modes add a slot of 32 (index, value) pairs per tile
+    assert adacc.workspace_bytes(m, n) == a(4 * 37) + 256
+    assert adacc.workspace_bytes(m2, 4096 * 3) == a(4 * 3) + 256 + a(4 * 32 * 3) + a(2 * 32 * 3)
     assert adacc.workspace_bytes(m3, 64 * 33) == 0
 
 
@@ -149,9 +151,8 @@ def test_batch_validation(L):
           adacc.NOOP, Method(bits=8, quant_group=128)]
     numels = [4096 * 5, 999, 128 * 100]
     need = adacc.batch_workspace_bytes(ms, numels)
-    tiles = 5 + (128 * 100 + 2047) // 2048
     a = lambda v: (v + 255) // 256 * 256
-    assert need >= a(8 * tiles) + a(8 * 3) + 2 * 128
+    assert need >= adacc.workspace_bytes(ms[0], numels[0]) + 2 * 128 + 2 * a(4 * 3)
     n = 3
     cms = (adacc.CMethod * n)(*[m.c() for m in ms])
     cn = (ctypes.c_uint64 * n)(*numels)
@@ -294,3 +295,20 @@ def test_channelwise_layout_and_validation(L):
     assert g(4, blob, tb, 100, 2048, 0x40000, 3, None) == adacc.EINVAL
     assert g(4, blob, tb - 1, 100, 2048, 0x40000, 0, None) == adacc.ESIZE
     assert g(4, blob, tb, 100, 2048, 0x40004, 0, None) == adacc.EALIGN
+
+
+def test_noalloc_limit_is_checked_on_the_host(L):
+    """adacc_compress_noalloc refuses what its 16 MiB device array cannot serve, before it looks at any
+    pointer (all pointers are NULL here: whatever the outcome, nothing can be launched)."""
+    f = L.adacc_compress_noalloc
+    m_abs = Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=64)
+    m_topk = Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=2048, topk=2, max_outliers=1 << 20)
+    for m, numel, want in ((m_abs, adacc.NOALLOC_MAX_NUMEL, None), (m_abs, 2 * adacc.NOALLOC_MAX_NUMEL, adacc.ELIMIT),
+                           (m_topk, 8 * adacc.NOALLOC_MAX_NUMEL, None)):
+        assert (adacc.workspace_bytes(m, numel) > (16 << 20)) == (want == adacc.ELIMIT)
+        cm = m.c()
+        rc = f(ctypes.byref(cm), None, numel, None, 0, None)
+        if want is not None:
+            assert rc == want and "limit" in adacc.strerror(rc)
+        else:
+            assert rc in (adacc.ENULL, adacc.EHIP)  # past the limit check: stopped by the NULL pointers (or by the missing device)

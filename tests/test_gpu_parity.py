@@ -166,15 +166,15 @@ def test_empty_and_single_group():
         run_parity(from_bits(random_bits(gq, gq, heavy=False, edge=False)), md)
 
 
-def test_many_tiles_chained_scan():
-    """Enough tiles that the look-back crosses several 64-tile windows and every CU is busy."""
+def test_many_tiles_across_placement_blocks():
+    """Enough tiles for ten placement blocks and a ragged last one, every CU busy."""
     n = 2048 * 5000 + 1024
     b = random_bits(123, n)
     md = dict(bits=8, quant_group=128, asym=0, outlier_mode="std", stat_group=1024, thresh=5.0, topk=0)
     log(f"[parity] many tiles n={n}")
     oc, *_ = run_parity(from_bits(b), md)
     assert oc.n_out > 10000
-    # sparse outliers: most tiles are empty, so the walk back over aggregates is long
+    # sparse outliers: most tiles, and whole placement blocks, are empty
     b2 = bits_of(torch.from_numpy(np.random.default_rng(3).standard_normal(n).astype(np.float32)).to(torch.bfloat16))
     md2 = dict(bits=4, quant_group=64, asym=0, outlier_mode="abs", stat_group=0, thresh=4.6, topk=0)
     oc2, *_ = run_parity(from_bits(b2), md2)
@@ -182,9 +182,9 @@ def test_many_tiles_chained_scan():
     assert 0 < oc2.n_out < 200
 
 
-def test_dense_outliers_overflow_the_staging_area_mid_run():
-    """More tiles than the device holds wavefronts (runs of several tiles) and about 5 % outliers:
-    runs fill their staging area part-way and finish with the second, select-only pass."""
+def test_dense_outliers_overflow_the_slots():
+    """About 5 % outliers: a tile holds around a hundred, more than its slot takes, so the placement
+    kernel selects the outliers of (nearly) every tile a second time from the source."""
     n = 2048 * 9001
     rng = np.random.default_rng(4242)
     v = rng.normal(0.0, 1.0, size=n).astype(np.float32)
@@ -196,14 +196,41 @@ def test_dense_outliers_overflow_the_staging_area_mid_run():
         assert oc.n_out > n // 25
 
 
+@pytest.mark.parametrize("gs,k,gq,bits", [(2048, 2, 128, 4), (4096, 4, 128, 4), (64, 1, 64, 8), (4096, 3, 4096, 8)])
+def test_topk_groups_with_more_values_that_are_not_finite_than_k(gs, k, gq, bits):
+    """TOPK places its outliers at offsets known in advance (k per group).  A group that holds more
+    than k values that are not finite breaks that: every later offset shifts, and the placement
+    kernel redoes the stream from the source.  Three placement blocks, irregular groups in the
+    first tile, in the middle and in the last tile, then a regular tensor through the same workspace."""
+    tile = max(2048, gs)
+    n = tile * 1300
+    b = random_bits(900 + gs + k, n, heavy=True, edge=False)
+    for g0 in (0, (n // gs // 2) * gs, n - gs):
+        b[g0 + 1:g0 + gs:max(1, gs // (k + 3))] = 0x7F80  # k + 3 or more infinities in this group
+        b[g0 + 5] = 0xFFC0
+    md = dict(bits=bits, quant_group=gq, asym=0, outlier_mode="topk", stat_group=gs, thresh=0.0, topk=k)
+    log(f"[parity] irregular topk gs={gs} k={k} n={n}")
+    oc, blob, L, m = run_parity(from_bits(b), md)
+    assert oc.n_out > k * (n // gs)
+    ws = adacc.alloc_workspace(adacc.workspace_bytes(m, n))
+    regular = random_bits(901 + gs, n, heavy=True, edge=False)  # finite values only
+    for bb in (b, regular, b):  # the flag of the first call must not reach the second
+        occ = oracle.compress(oracle_method(md), bb)
+        occ._full_idx = occ.out_idx.astype(np.int64)
+        mm = adacc_method(md, max(occ.n_out, 1))
+        blob2, L2, _ = gpu_compress(from_bits(bb, "cuda"), mm, ws=ws)
+        torch.cuda.synchronize()
+        compare_blob_with_oracle(blob2, L2, mm, n, occ)
+
+
 def test_deterministic_and_workspace_reuse():
     """One workspace, many calls of different sizes and methods: every blob equals the oracle's,
     and repeated calls give identical bytes."""
-    ws = adacc.alloc_workspace(8 * 4096)
     cases = [(2048 * 700 + 64, dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=2.5, topk=0)),
              (4096 * 9, dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=4096, thresh=0.0, topk=4)),
              (2048 * 3, dict(bits=8, quant_group=2048, asym=1, outlier_mode="abs", stat_group=0, thresh=2.0, topk=0)),
              (2048 * 1500, dict(bits=4, quant_group=32, asym=1, outlier_mode="abs", stat_group=0, thresh=3.0, topk=0))]
+    ws = adacc.alloc_workspace(max(adacc.workspace_bytes(adacc_method(md, 1), n) for n, md in cases))
     for rep in range(3):
         for i, (n, md) in enumerate(cases):
             b = random_bits(50 + i, n)
