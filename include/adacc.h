@@ -101,7 +101,7 @@ int adacc_layout_of(const adacc_method *method, uint64_t numel, adacc_layout *ou
  * Compression with outliers takes every tile on its own (no tile waits for another) and settles the
  * order of the outlier stream afterwards, in a second, small kernel.  Between the two, the number
  * of outliers of every tile (4 bytes per tile) and, for ADACC_OUTLIER_ABS / _STD, the outliers
- * themselves (a slot of 192 bytes per tile) wait in a caller-owned device buffer described by an
+ * themselves (a slot of 256 bytes per tile) wait in a caller-owned device buffer described by an
  * adacc_workspace.  The struct is HOST memory owned by the caller; the library keeps a launch
  * counter ("epoch") in it: a flag word written by an earlier launch carries an older epoch and
  * reads as not set, so the buffer is cleared only by adacc_workspace_init and when the 30-bit
@@ -135,9 +135,9 @@ int adacc_compress(const adacc_method *method, const void *src, uint64_t numel, 
 
 /* adacc_compress for callers that cannot allocate device memory at all (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same blob, but the
- * workspace is a device array inside the library (16 MiB per GPU the library runs on, held until
+ * workspace is a device array inside the library (24 MiB per GPU the library runs on, held until
  * the process ends) instead of a caller's buffer.  The call allocates and frees nothing.
- * Limit: adacc_workspace_bytes(method, numel) <= 16 MiB, which holds for every method up to
+ * Limit: adacc_workspace_bytes(method, numel) <= 24 MiB, which holds for every method up to
  * ADACC_NOALLOC_MAX_NUMEL elements (and for ADACC_OUTLIER_TOPK / _NONE at any legal size); beyond
  * that the call returns ADACC_ELIMIT.  All calls on one GPU share that array: they may follow each
  * other on one stream, or be ordered otherwise, but two that overlap on the GPU race.  The first

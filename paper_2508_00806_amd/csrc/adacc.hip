@@ -221,9 +221,10 @@ static bool topk_whole_tile(const adacc_method* m, const Plan& p) {
 
 static uint32_t decompress_pieces(uint64_t numel) { return (uint32_t)((numel + 2047ull) / 2048ull); }
 
-// Workspace of one tensor that keeps outliers: [cnt: one word per tile][flag][slot_idx][slot_val],
-// the slots for ABS / STD only.  Offsets relative to the tensor's region.
-struct WsPlan { uint64_t cnt_off, flag_off, slot_idx_off, slot_val_off, bytes; };
+// Workspace of one tensor that keeps outliers: [cnt: one word per tile][flag][block_sum][slots],
+// block sums and slots for ABS / STD only.  Offsets relative to the tensor's region.
+struct WsPlan { uint64_t cnt_off, flag_off, block_sum_off, slot_off, bytes; };
+static uint32_t place_blocks(const Plan& p) { return p.outliers ? (p.n_tiles + kPlaceTiles - 1) / kPlaceTiles : 0u; }
 static WsPlan ws_plan(const adacc_method* m, const Plan& p) {
   WsPlan w;
   std::memset(&w, 0, sizeof w);
@@ -232,17 +233,19 @@ static WsPlan ws_plan(const adacc_method* m, const Plan& p) {
   w.cnt_off = off;  off = align256(off + 4ull * p.n_tiles);
   w.flag_off = off; off += 256;
   if (m->outlier_mode != ADACC_OUTLIER_TOPK) {
-    w.slot_idx_off = off; off = align256(off + 4ull * kSlot * p.n_tiles);
-    w.slot_val_off = off; off = align256(off + 2ull * kSlot * p.n_tiles);
+    w.block_sum_off = off; off = align256(off + 4ull * place_blocks(p));
+    w.slot_off = off; off = align256(off + 8ull * kSlot * p.n_tiles);
   }
   w.bytes = off;
   return w;
 }
-static uint32_t place_blocks(const Plan& p) { return p.outliers ? (p.n_tiles + kPlaceTiles - 1) / kPlaceTiles : 0u; }
+// does the placement of this tensor start from per-block sums (a kernel of its own computes them)?
+static bool needs_block_sums(const adacc_method* m, const Plan& p) {
+  return p.outliers && m->outlier_mode != ADACC_OUTLIER_TOPK && place_blocks(p) > kPlaceDirectBlocks;
+}
 
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
-                      void* blob, void* dst, int dst_dtype, uint32_t first_tile, uint32_t first_block, void* ws_region,
-                      TensorDesc* d) {
+                      void* blob, void* dst, int dst_dtype, void* ws_region, TensorDesc* d) {
   std::memset(d, 0, sizeof *d);
   unsigned char* b = static_cast<unsigned char*>(blob);
   d->src = static_cast<const uint16_t*>(src);
@@ -259,13 +262,12 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
     unsigned char* r = static_cast<unsigned char*>(ws_region);
     d->cnt = reinterpret_cast<uint32_t*>(r + w.cnt_off);
     d->flag = reinterpret_cast<uint32_t*>(r + w.flag_off);
-    d->slot_idx = reinterpret_cast<int32_t*>(r + w.slot_idx_off);
-    d->slot_val = reinterpret_cast<uint16_t*>(r + w.slot_val_off);
+    d->block_sum = reinterpret_cast<uint32_t*>(r + w.block_sum_off);
+    d->slot = reinterpret_cast<uint2*>(r + w.slot_off);
   }
   d->numel = numel;
   d->n_tiles = p.n_tiles;
-  d->first_tile = first_tile;
-  d->first_block = first_block;
+  d->n_blocks = place_blocks(p);
   d->lgt = p.tile_elems == 4096 ? 12u : 11u;
   if (dst) {  // decompression counts pieces of 2048 elements
     d->n_tiles = decompress_pieces(numel);
@@ -381,18 +383,44 @@ static int clear_device(void* mem, uint64_t bytes, hipStream_t s) {
   return launch_check("workspace_clear_kernel");
 }
 
-// batch workspace: [table: n descriptors][first_tile: n+1 words][first_block: n+1 words][the tensors' regions]
+// batch workspace: [table: n descriptors][member lists of the launches: 4 n words][the tensors' regions]
 struct BatchPlan {
-  uint64_t first_tile_off, first_block_off, regions_off, bytes;
+  uint64_t members_off, regions_off, bytes;
 };
 static BatchPlan batch_plan(uint32_t n_active, uint64_t region_bytes) {
   BatchPlan b;
   const uint64_t n = n_active ? n_active : 1;
-  b.first_tile_off = align256(n * sizeof(TensorDesc));
-  b.first_block_off = b.first_tile_off + align256(4ull * (n + 1));
-  b.regions_off = b.first_block_off + align256(4ull * (n + 1));
+  b.members_off = align256(n * sizeof(TensorDesc));
+  b.regions_off = b.members_off + align256(4ull * 4ull * n);
   b.bytes = b.regions_off + region_bytes;
   return b;
+}
+
+// A launch over a group of table entries: grid.y = the group's entries, grid.x covers the largest.
+struct GroupLaunch {
+  uint32_t first_member, n_members, max_units;
+  int kind;  // what the caller makes of it (register class, kernel)
+};
+// Groups the entries for which units[i] > 0 by kind[i] and by size (unit counts within a factor of
+// two of each other, at most 65535 entries per launch) and appends their member lists to `members`.
+static void group_launches(const std::vector<uint32_t>& units, const std::vector<int>& kind,
+                           std::vector<uint32_t>* members, std::vector<GroupLaunch>* launches) {
+  for (int k = 0; k < 4; ++k) {
+    for (uint32_t bucket = 0; bucket <= 32; ++bucket) {
+      GroupLaunch g = {(uint32_t)members->size(), 0u, 0u, k};
+      for (uint32_t i = 0; i < units.size(); ++i) {
+        if (units[i] == 0 || kind[i] != k || ilog2(units[i]) != bucket) continue;
+        if (g.n_members == 65535u) {
+          launches->push_back(g);
+          g = GroupLaunch{(uint32_t)members->size(), 0u, 0u, k};
+        }
+        members->push_back(i);
+        g.n_members += 1;
+        g.max_units = std::max(g.max_units, units[i]);
+      }
+      if (g.n_members) launches->push_back(g);
+    }
+  }
 }
 
 // ---- outlier channels (Section 3.2, Eq. 1)
@@ -533,7 +561,7 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
   if (rc != ADACC_OK) return rc;
   CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise, topk_whole_tile(method, p));
   TensorDesc d;
-  fill_desc(method, numel, p, L, src, blob, nullptr, 0, 0, 0, p.outliers ? ws->device_mem : nullptr, &d);
+  fill_desc(method, numel, p, L, src, blob, nullptr, 0, p.outliers ? ws->device_mem : nullptr, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t grid = 0, epoch = 0;
   rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), &grid);
@@ -545,7 +573,12 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, epoch);
   rc = launch_check("compress_kernel");
   if (rc != ADACC_OK || !p.outliers) return rc;
-  hipLaunchKernelGGL(place_fn(), dim3(place_blocks(p)), dim3(kPlaceThreads), 0, s, d, epoch);
+  if (needs_block_sums(method, p)) {
+    hipLaunchKernelGGL(place_sum_fn(), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
+    rc = launch_check("place_sum_kernel");
+    if (rc != ADACC_OK) return rc;
+  }
+  hipLaunchKernelGGL(place_fn(), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
   return launch_check("place_kernel");
 }
 
@@ -555,7 +588,7 @@ int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, 
 }
 
 // ---- the same for callers that cannot allocate: the workspace is a device array of the library
-constexpr uint64_t kNoallocScratchBytes = 16ull << 20;
+constexpr uint64_t kNoallocScratchBytes = 24ull << 20;
 static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
 
 int adacc_compress_noalloc(const adacc_method* method, const void* src, uint64_t numel, void* blob,
@@ -605,7 +638,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 0, nullptr, &d);
+  fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, nullptr, &d);
   DecompressFn fn = decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
   uint32_t grid = 0;
   rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid);
@@ -643,16 +676,11 @@ uint64_t adacc_batch_workspace_bytes(uint32_t n, const adacc_method* methods, co
   return batch_plan(act, regions).bytes;
 }
 
-// Descriptors of the active tensors of a batch, with the launch-wide numbering of their tiles (pieces
-// for decompression) and of their placement blocks.
-struct BatchTable {
-  std::vector<TensorDesc> descs;
-  std::vector<uint32_t> first_tile, first_block;  // one entry per descriptor plus the totals
-};
+// Descriptors of the active tensors of a batch.
 static int batch_table(uint32_t n, const adacc_method* methods, const std::vector<Plan>& plans, const uint64_t* numels,
                        const void* const* srcs, void* const* blobs, const uint64_t* blob_bytes, void* const* dsts,
-                       int dst_dtype, bool compress, unsigned char* regions, BatchTable* t) {
-  uint32_t first = 0, first_block = 0;
+                       int dst_dtype, bool compress, unsigned char* regions, std::vector<TensorDesc>* descs,
+                       std::vector<uint32_t>* origin) {
   uint64_t region_off = 0;
   for (uint32_t i = 0; i < n; ++i) {
     if (plans[i].noop) continue;
@@ -665,18 +693,11 @@ static int batch_table(uint32_t n, const adacc_method* methods, const std::vecto
     if (compress ? misaligned(srcs[i], 16) : misaligned(dsts[i], 16)) return ADACC_EALIGN;
     TensorDesc d;
     fill_desc(&methods[i], numels[i], plans[i], L, compress ? srcs[i] : nullptr, blobs[i], compress ? nullptr : dsts[i],
-              dst_dtype, first, first_block, compress ? regions + region_off : nullptr, &d);
-    t->descs.push_back(d);
-    t->first_tile.push_back(first);
-    t->first_block.push_back(first_block);
-    first += d.n_tiles;
-    if (compress) {
-      first_block += place_blocks(plans[i]);
-      region_off += ws_plan(&methods[i], plans[i]).bytes;
-    }
+              dst_dtype, compress ? regions + region_off : nullptr, &d);
+    descs->push_back(d);
+    origin->push_back(i);
+    if (compress) region_off += ws_plan(&methods[i], plans[i]).bytes;
   }
-  t->first_tile.push_back(first);
-  t->first_block.push_back(first_block);
   return ADACC_OK;
 }
 
@@ -695,33 +716,48 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   if (ws->bytes < bp.bytes) return ADACC_ESIZE;
   if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
-  BatchTable t;
-  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, mem + bp.regions_off, &t);
+  std::vector<TensorDesc> descs;
+  std::vector<uint32_t> origin;
+  rc = batch_table(n, methods, plans, numels, srcs, blobs, blob_bytes, nullptr, 0, true, mem + bp.regions_off, &descs,
+                   &origin);
   if (rc != ADACC_OK) return rc;  // every argument is checked before the device is touched
   int cus = 0;
   rc = device_cus(&cus);
   if (rc != ADACC_OK) return rc;
-  bool any_four = false, any_eight = false;
-  for (const TensorDesc& d : t.descs) ((d.variant & 1u) ? any_eight : any_four) = true;
+  // the launches: tiles (by register class), block sums, placement
+  const uint32_t nt = (uint32_t)descs.size();
+  std::vector<uint32_t> units(nt), members;
+  std::vector<int> kind(nt);
+  std::vector<GroupLaunch> tiles, sums, places;
+  for (uint32_t i = 0; i < nt; ++i) { units[i] = descs[i].n_tiles; kind[i] = (int)(descs[i].variant & 1u); }
+  group_launches(units, kind, &members, &tiles);
+  for (uint32_t i = 0; i < nt; ++i) {
+    units[i] = needs_block_sums(&methods[origin[i]], plans[origin[i]]) ? descs[i].n_blocks : 0u;
+    kind[i] = 0;
+  }
+  group_launches(units, kind, &members, &sums);
+  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].n_blocks;
+  group_launches(units, kind, &members, &places);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t epoch = 0;
   rc = next_epoch(ws, s, &epoch);
   if (rc != ADACC_OK) return rc;
   TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
-  uint32_t* ft = reinterpret_cast<uint32_t*>(mem + bp.first_tile_off);
-  uint32_t* fb = reinterpret_cast<uint32_t*>(mem + bp.first_block_off);
-  rc = upload_table(t.descs, dt, s);
-  if (rc == ADACC_OK) rc = upload_words(t.first_tile, ft, s);
-  if (rc == ADACC_OK) rc = upload_words(t.first_block, fb, s);
+  uint32_t* dm = reinterpret_cast<uint32_t*>(mem + bp.members_off);
+  rc = upload_table(descs, dt, s);
+  if (rc == ADACC_OK) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
-  const uint32_t grid = (total + kWavesPerWg - 1) / kWavesPerWg;
-  const uint32_t nt = (uint32_t)t.descs.size();
-  if (any_four) hipLaunchKernelGGL(compress_batch_fn(false), dim3(grid), dim3(kThreads), 0, s, dt, ft, nt, total, epoch);
-  if (any_eight) hipLaunchKernelGGL(compress_batch_fn(true), dim3(grid), dim3(kThreads), 0, s, dt, ft, nt, total, epoch);
+  for (const GroupLaunch& g : tiles)
+    hipLaunchKernelGGL(compress_batch_fn(g.kind != 0), dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members),
+                       dim3(kThreads), 0, s, dt, dm + g.first_member, epoch);
   rc = launch_check("compress_batch_kernel");
-  const uint32_t blocks = t.first_block.back();
-  if (rc != ADACC_OK || blocks == 0) return rc;
-  hipLaunchKernelGGL(place_batch_fn(), dim3(blocks), dim3(kPlaceThreads), 0, s, dt, fb, nt, epoch);
+  if (rc != ADACC_OK) return rc;
+  for (const GroupLaunch& g : sums)
+    hipLaunchKernelGGL(place_sum_batch_fn(), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
+                       dm + g.first_member);
+  for (const GroupLaunch& g : places)
+    hipLaunchKernelGGL(place_batch_fn(), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
+                       dm + g.first_member, epoch);
   return launch_check("place_batch_kernel");
 }
 
@@ -741,23 +777,31 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   const BatchPlan bp = batch_plan(act, region_bytes);
   if (ws->bytes < bp.bytes) return ADACC_ESIZE;
   if (misaligned(ws->device_mem, 256)) return ADACC_EALIGN;
-  BatchTable t;
+  std::vector<TensorDesc> descs;
+  std::vector<uint32_t> origin;
   rc = batch_table(n, methods, plans, numels, nullptr, const_cast<void* const*>(blobs), blob_bytes, dsts, dst_dtype,
-                   false, nullptr, &t);
+                   false, nullptr, &descs, &origin);
   if (rc != ADACC_OK) return rc;
-  const uint32_t pieces = t.first_tile.back();
+  int cus = 0;
+  rc = device_cus(&cus);
+  if (rc != ADACC_OK) return rc;
+  const uint32_t nt = (uint32_t)descs.size();
+  std::vector<uint32_t> units(nt), members;
+  std::vector<int> kind(nt, 0);
+  std::vector<GroupLaunch> launches;
+  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].n_tiles;  // pieces of 2048 elements
+  group_launches(units, kind, &members, &launches);
   const BatchDecompressFn fn = decompress_batch_fn(dst_dtype == ADACC_DST_F32);
-  uint32_t grid = 0;
-  rc = grid_for(pieces, reinterpret_cast<const void*>(fn), &grid);
-  if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
   TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
-  uint32_t* ft = reinterpret_cast<uint32_t*>(mem + bp.first_tile_off);
-  rc = upload_table(t.descs, dt, s);
-  if (rc == ADACC_OK) rc = upload_words(t.first_tile, ft, s);
+  uint32_t* dm = reinterpret_cast<uint32_t*>(mem + bp.members_off);
+  rc = upload_table(descs, dt, s);
+  if (rc == ADACC_OK) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, dt, ft, (uint32_t)t.descs.size(), pieces);
+  for (const GroupLaunch& g : launches)
+    hipLaunchKernelGGL(fn, dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members), dim3(kThreads), 0, s, dt,
+                       dm + g.first_member);
   return launch_check("decompress_batch_kernel");
 }
 
@@ -803,7 +847,7 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
   if (workspace_bytes < adacc_channel_workspace_bytes(tokens, hidden)) return ADACC_ESIZE;
   if (misaligned(src, 16) || misaligned(blob, 256) || misaligned(workspace, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, src, blob, nullptr, 0, 0, 0, nullptr, &d);
+  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, src, blob, nullptr, 0, nullptr, &d);
   ChannelDesc c;
   fill_channel_desc(method, tokens, hidden, L, blob, &c);
   float* partial = static_cast<float*>(workspace);
@@ -845,8 +889,8 @@ int adacc_channel_decompress(const adacc_channel_method* method, const void* blo
   if (blob_bytes < L.total_bytes) return ADACC_ESIZE;
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
-  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, nullptr, const_cast<void*>(blob), dst, dst_dtype, 0, 0,
-            nullptr, &d);
+  fill_desc(&cp.quant, cp.numel, cp.plan, cp.quant_layout, nullptr, const_cast<void*>(blob), dst, dst_dtype, nullptr,
+            &d);
   ChannelDesc c;
   fill_channel_desc(method, tokens, hidden, L, const_cast<void*>(blob), &c);
   ChannelFn fn = channel_decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);

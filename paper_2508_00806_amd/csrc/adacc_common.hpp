@@ -80,13 +80,13 @@ struct TensorDesc {
   uint16_t* val;
   uint32_t* status;
   uint32_t* cnt;            // compress, workspace: outliers found in every tile
-  int32_t* slot_idx;        // compress, workspace (ABS / STD): kSlot entries per tile, the tile's outliers
-  uint16_t* slot_val;       //   until the placement kernel has moved them to the stream
+  uint32_t* block_sum;      // compress, workspace (ABS / STD): outliers in every block of kPlaceTiles tiles
+  uint2* slot;              // compress, workspace (ABS / STD): kSlot records (index, value) per tile, the tile's
+                            //   outliers until the placement kernel has moved them to the stream
   uint32_t* flag;           // compress, workspace (TOPK): set to the epoch by a tile whose count is not the regular one
   uint64_t numel;
   uint32_t n_tiles;
-  uint32_t first_tile;      // launch-wide id of this tensor's tile 0 (batch)
-  uint32_t first_block;     // launch-wide id of this tensor's first block of kPlaceTiles tiles (batch placement)
+  uint32_t n_blocks;        // compress: blocks of kPlaceTiles tiles (placement kernels)
   uint32_t lgt;             // log2(elements per tile): 11 or 12
   uint32_t lgq;         // log2(quant group)
   uint32_t lgs;         // log2(stat group) (STD / TOPK)
@@ -133,9 +133,11 @@ struct ChannelwiseDesc {
 // Outliers of a tile that travel through the tile's slot in the workspace (ABS / STD); a tile with
 // more is selected a second time by the placement kernel.
 constexpr int kSlot = 32;
-// The placement kernels: a workgroup of kPlaceThreads threads takes kPlaceTiles consecutive tiles.
+// The placement kernels: a workgroup of kPlaceThreads threads takes kPlaceTiles consecutive tiles, one per thread.
 constexpr int kPlaceThreads = 256;
-constexpr int kPlaceTiles = 512;
+constexpr int kPlaceTiles = 256;
+// Tensors of at most this many blocks do without the kernel that adds up the blocks' counts.
+constexpr uint32_t kPlaceDirectBlocks = 8;
 // The workspace's launch counter ("epoch", kept on the host in adacc_workspace) marks what a launch
 // wrote: a word that holds an older epoch reads as not set, so nothing has to be cleared per call.
 constexpr uint32_t kEpochMax = 0x3FFFFFFFu;

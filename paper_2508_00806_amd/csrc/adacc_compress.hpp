@@ -974,9 +974,26 @@ __device__ __forceinline__ void encode_tile(const TensorDesc& d, const TileGeo<E
 // at position pos0 (entries at or past `limit` are dropped).  The destination is either the
 // stream in global memory or the wavefront's staging area in LDS.  Only rows that have
 // outliers are visited.
-template <int E, class IdxPtr, class ValPtr>
+// where emit_outliers puts entry `pos`: the stream of the blob (two arrays) ...
+struct StreamSink {
+  int32_t* idx;
+  uint16_t* val;
+  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t index, uint32_t bits) const {
+    idx[pos] = (int32_t)index;
+    val[pos] = (uint16_t)bits;
+  }
+};
+// ... or a tile's slot in the workspace (one 8-byte record per entry: index, value)
+struct SlotSink {
+  uint2* rec;
+  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t index, uint32_t bits) const {
+    rec[pos] = make_uint2(index, bits);
+  }
+};
+
+template <int E, class Sink>
 __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const TileOutliers<E>& out, uint32_t tile,
-                                              IdxPtr idx_out, ValPtr val_out, uint32_t pos0, uint32_t limit) {
+                                              const Sink& sink, uint32_t pos0, uint32_t limit) {
   const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
   static_for<E>([&](auto J) {
     constexpr int j = decltype(J)::value;
@@ -989,17 +1006,13 @@ __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const
           const uint32_t e = (uint32_t)__builtin_ctz(bits);
           const uint64_t lo = ((uint64_t)raw[j][1] << 32) | raw[j][0], hi = ((uint64_t)raw[j][3] << 32) | raw[j][2];
           const uint64_t half = (e & 4u) ? hi : lo;
-          idx_out[pos] = (int32_t)(i0 + e);
-          val_out[pos] = (uint16_t)(half >> ((e & 3u) * 16u));
+          sink(pos, i0 + e, (uint32_t)(half >> ((e & 3u) * 16u)) & 0xFFFFu);
         }
       } else {
         static_for<kOct>([&](auto Ec) {
           constexpr int e = decltype(Ec)::value;
           if ((bits >> e) & 1u) {
-            if (pos < limit) {
-              idx_out[pos] = (int32_t)(i0 + (uint32_t)e);
-              val_out[pos] = (uint16_t)((e & 1) ? (raw[j][e >> 1] >> 16) : (raw[j][e >> 1] & 0xFFFFu));
-            }
+            if (pos < limit) sink(pos, i0 + (uint32_t)e, (e & 1) ? (raw[j][e >> 1] >> 16) : (raw[j][e >> 1] & 0xFFFFu));
             ++pos;
           }
         });
@@ -1013,7 +1026,7 @@ __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const
 // ordered outlier stream needs from all tiles together - the offset of every tile - is settled
 // afterwards by place_block (below), from the per-tile counts written here.
 //
-// ABS / STD: the tile's outliers (ascending) go to the tile's own slot of kSlot entries in the
+// ABS / STD: the tile's outliers (ascending) go to the tile's own slot of kSlot records in the
 // workspace; the placement kernel moves them to their final position.  A tile with more than
 // kSlot outliers leaves the rest out; the placement kernel then selects that tile's outliers from
 // the source once more.
@@ -1055,25 +1068,26 @@ __device__ __forceinline__ void compress_tile_outliers(const TensorDesc& d, uint
       }
     }
     const uint32_t end = pos0 + expected;
-    if (out.total != 0u) emit_outliers<E>(raw, out, tile, d.idx, d.val, pos0, end < d.cap ? end : d.cap);
+    if (out.total != 0u) emit_outliers<E>(raw, out, tile, StreamSink{d.idx, d.val}, pos0, end < d.cap ? end : d.cap);
   } else {
     if (lane0) d.cnt[tile] = out.total;
     if (out.total != 0u) {
-      const uint64_t slot = (uint64_t)tile * (uint64_t)kSlot;
-      emit_outliers<E>(raw, out, tile, d.slot_idx + slot, d.slot_val + slot, 0u, (uint32_t)kSlot);
+      emit_outliers<E>(raw, out, tile, SlotSink{d.slot + (uint64_t)tile * (uint64_t)kSlot}, 0u, (uint32_t)kSlot);
     }
   }
 }
 
 // ------------------------------------------------------------------ placement of the outliers (a4)
-// One workgroup of kPlaceThreads threads takes a block of kPlaceTiles consecutive tiles: it adds up
-// the counts of all tiles before its block (every workgroup does that sum itself, straight from the
-// counts: a few hundred kilobytes from the L2 at most, and nobody waits for anybody), scans the
-// counts of its own tiles, writes their offsets, and moves the outliers of its tiles from the slots
-// to their final positions, output position by output position (coalesced stores; the tile of a
-// position is found by bisection over the block's offsets in LDS).  Tiles that hold more outliers
-// than a slot takes (or all tiles, `reselect_all`) are selected again from the source, one
-// wavefront per tile, and written straight to the stream.
+// One workgroup of kPlaceThreads threads takes a block of kPlaceTiles consecutive tiles, one per
+// thread.  It needs the number of outliers in all tiles before its block: for ABS / STD a kernel in
+// between (place_sum_block) has added up the counts of every block, and the workgroup adds those
+// sums; for short tensors, and for TOPK (where this kernel has work only if some group was
+// irregular), it adds the counts themselves.  Nobody waits for anybody.  Then it scans the counts of
+// its own tiles, writes their offsets, and moves the outliers of its tiles from the slots to their
+// final positions, output position by output position (coalesced stores; the tile of a position is
+// found by bisection over the block's offsets in LDS).  Tiles that hold more outliers than a slot
+// takes (or all tiles, `reselect_all`) are selected again from the source, one wavefront per tile,
+// and written straight to the stream.
 struct PlaceShared {
   uint32_t excl[kPlaceTiles + 1];  // offsets of the block's tiles relative to the block, and the block total
   uint32_t part[kPlaceThreads / kWave];
@@ -1090,16 +1104,43 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 }
 
 // sum over the workgroup (kPlaceThreads threads), returned to every thread
-__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, PlaceShared& sh) {
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t (&part)[kPlaceThreads / kWave]) {
   const uint32_t w = wave_sum_u32(v);
   const uint32_t wave = threadIdx.x / kWave;
   __syncthreads();  // earlier readers of part[] are done
-  if (lane_id() == 0) sh.part[wave] = w;
+  if (lane_id() == 0) part[wave] = w;
   __syncthreads();
   uint32_t s = 0u;
 #pragma unroll
-  for (int i = 0; i < kPlaceThreads / kWave; ++i) s += sh.part[i];
+  for (int i = 0; i < kPlaceThreads / kWave; ++i) s += part[i];
   return s;
+}
+
+// sum of n 32-bit words (16-byte aligned) over the workgroup; four loads of 16 bytes per thread are
+// in flight at a time
+__device__ __forceinline__ uint32_t sum_words(const uint32_t* words, uint32_t n, uint32_t (&part)[kPlaceThreads / kWave]) {
+  const uint4* w4 = reinterpret_cast<const uint4*>(words);
+  const uint32_t n4 = n / 4u;
+  uint32_t acc = 0u;
+  for (uint32_t i0 = 0u; i0 < n4; i0 += 4u * (uint32_t)kPlaceThreads) {
+    uint4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t i = i0 + (uint32_t)k * (uint32_t)kPlaceThreads + threadIdx.x;
+      v[k] = i < n4 ? w4[i] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc += (v[k].x + v[k].y) + (v[k].z + v[k].w);
+  }
+  if (threadIdx.x < (n & 3u)) acc += words[4u * n4 + threadIdx.x];
+  return block_sum_u32(acc, part);
+}
+
+// block_sum[block] = outliers in the block's tiles
+__device__ __forceinline__ void place_sum_block(const TensorDesc& d, uint32_t block, uint32_t (&part)[kPlaceThreads / kWave]) {
+  const uint32_t t = block * (uint32_t)kPlaceTiles + threadIdx.x;
+  const uint32_t s = block_sum_u32(t < d.n_tiles ? d.cnt[t] : 0u, part);
+  if (threadIdx.x == 0) d.block_sum[block] = s;
 }
 
 // select the outliers of one tile again and write them to the stream from position `pos`
@@ -1111,28 +1152,22 @@ __device__ __forceinline__ void reselect_tile(const TensorDesc& d, uint32_t tile
   const TileGeo<E> g = tile_geo<E, false>(d, tile);
   blank_tail<E>(g, raw);
   encode_tile<MODE, 8, false, E, ROWWISE, WHOLE, false>(d, g, raw, out);
-  if (out.total != 0u) emit_outliers<E>(raw, out, tile, d.idx, d.val, pos, d.cap);
+  if (out.total != 0u) emit_outliers<E>(raw, out, tile, StreamSink{d.idx, d.val}, pos, d.cap);
 }
 
+// `from_sums`: the counts of the blocks are in d.block_sum (else the counts of the tiles are added up)
 template <int MODE, int E, bool ROWWISE, bool WHOLE>
-__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool reselect_all, PlaceShared& sh) {
+__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool from_sums, bool reselect_all,
+                                            PlaceShared& sh) {
   const uint32_t tid = threadIdx.x;
   const uint32_t first = block * (uint32_t)kPlaceTiles;
-  // counts of all tiles before this block (first is a multiple of 4: whole 16-byte loads)
-  uint32_t before = 0u;
-  const uint4* c4 = reinterpret_cast<const uint4*>(d.cnt);
-  for (uint32_t i = tid; i < first / 4u; i += (uint32_t)kPlaceThreads) {
-    const uint4 v = c4[i];
-    before += (v.x + v.y) + (v.z + v.w);
-  }
-  before = block_sum_u32(before, sh);
-  // this thread's two tiles
-  const uint32_t t0 = first + 2u * tid;
-  const uint32_t c0 = t0 < d.n_tiles ? d.cnt[t0] : 0u;
-  const uint32_t c1 = t0 + 1u < d.n_tiles ? d.cnt[t0 + 1u] : 0u;
+  // outliers of all tiles before this block
+  const uint32_t base = from_sums ? sum_words(d.block_sum, block, sh.part) : sum_words(d.cnt, first, sh.part);
+  // this thread's tile
+  const uint32_t t = first + tid;
+  const uint32_t c = t < d.n_tiles ? d.cnt[t] : 0u;
   // exclusive scan over the workgroup: inside the wavefront by shuffles, across wavefronts through LDS
-  const uint32_t mine = c0 + c1;
-  uint32_t incl = mine;
+  uint32_t incl = c;
 #pragma unroll
   for (int off = 1; off < kWave; off <<= 1) {
     const uint32_t up = (uint32_t)__shfl_up((int)incl, off);
@@ -1148,33 +1183,42 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
     wave_before += (uint32_t)i < wave ? sh.part[i] : 0u;
     total += sh.part[i];
   }
-  const uint32_t e0 = wave_before + incl - mine;  // relative to the block
-  sh.excl[2u * tid] = e0;
-  sh.excl[2u * tid + 1u] = e0 + c0;
+  const uint32_t e0 = wave_before + incl - c;  // relative to the block
+  sh.excl[tid] = e0;
   if (tid == 0) sh.excl[kPlaceTiles] = total;
-  if (t0 < d.n_tiles) d.tile_ptr[t0] = before + e0;
-  if (t0 + 1u < d.n_tiles) d.tile_ptr[t0 + 1u] = before + e0 + c0;
+  if (t < d.n_tiles) d.tile_ptr[t] = base + e0;
   const uint32_t n_here = d.n_tiles - first < (uint32_t)kPlaceTiles ? d.n_tiles - first : (uint32_t)kPlaceTiles;
   if (first + n_here == d.n_tiles && tid == 0) {  // the block that holds the last tile also closes the blob
-    const uint32_t n_out = before + total;
+    const uint32_t n_out = base + total;
     d.tile_ptr[d.n_tiles] = n_out;
     d.status[0] = n_out; d.status[1] = n_out > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
   }
   __syncthreads();
-  // from the slots to the stream
+  // from the slots to the stream: four positions per thread at a time, so that their loads overlap
   if (!reselect_all) {
-    for (uint32_t p = tid; p < total; p += (uint32_t)kPlaceThreads) {
-      uint32_t lo = 0u, hi = n_here;  // last tile j with excl[j] <= p (tiles without outliers share their successor's offset)
-      while (hi - lo > 1u) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (sh.excl[mid] <= p) lo = mid; else hi = mid;
+    for (uint32_t p0 = 0u; p0 < total; p0 += 4u * (uint32_t)kPlaceThreads) {
+      uint64_t src[4];
+      uint32_t dst[4];
+      bool ok[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t p = p0 + (uint32_t)k * (uint32_t)kPlaceThreads + tid;
+        uint32_t lo = 0u, hi = n_here;  // last tile j with excl[j] <= p (tiles without outliers share their successor's offset)
+        while (hi - lo > 1u) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (sh.excl[mid] <= p) lo = mid; else hi = mid;
+        }
+        const uint32_t n_tile = sh.excl[lo + 1u] - sh.excl[lo];
+        dst[k] = base + p;
+        ok[k] = p < total && n_tile <= (uint32_t)kSlot && dst[k] < d.cap;
+        src[k] = ok[k] ? (uint64_t)(first + lo) * (uint64_t)kSlot + (p - sh.excl[lo]) : 0ull;
       }
-      const uint32_t n_tile = sh.excl[lo + 1u] - sh.excl[lo];
-      const uint32_t dst = before + p;
-      if (n_tile <= (uint32_t)kSlot && dst < d.cap) {
-        const uint64_t src = (uint64_t)(first + lo) * (uint64_t)kSlot + (p - sh.excl[lo]);
-        d.idx[dst] = d.slot_idx[src];
-        d.val[dst] = d.slot_val[src];
+      uint2 rec[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) rec[k] = d.slot[src[k]];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (ok[k]) { d.idx[dst[k]] = (int32_t)rec[k].x; d.val[dst[k]] = (uint16_t)rec[k].y; }
       }
     }
   }
@@ -1183,7 +1227,7 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
   for (uint32_t j = w; j < n_here; j += (uint32_t)(kPlaceThreads / kWave)) {
     const uint32_t n_tile = sh.excl[j + 1u] - sh.excl[j];
     if (n_tile > (reselect_all ? 0u : (uint32_t)kSlot))
-      reselect_tile<MODE, E, ROWWISE, WHOLE>(d, first + j, before + sh.excl[j]);
+      reselect_tile<MODE, E, ROWWISE, WHOLE>(d, first + j, base + sh.excl[j]);
   }
 }
 

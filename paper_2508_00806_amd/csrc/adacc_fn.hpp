@@ -8,10 +8,12 @@ namespace adacc {
 
 typedef void (*CompressFn)(TensorDesc, uint32_t);
 typedef void (*DecompressFn)(TensorDesc, uint32_t);
-typedef void (*BatchCompressFn)(const TensorDesc*, const uint32_t*, uint32_t, uint32_t, uint32_t);
-typedef void (*BatchDecompressFn)(const TensorDesc*, const uint32_t*, uint32_t, uint32_t);
+typedef void (*BatchCompressFn)(const TensorDesc*, const uint32_t*, uint32_t);
+typedef void (*BatchDecompressFn)(const TensorDesc*, const uint32_t*);
+typedef void (*PlaceSumFn)(TensorDesc);
 typedef void (*PlaceFn)(TensorDesc, uint32_t);
-typedef void (*PlaceBatchFn)(const TensorDesc*, const uint32_t*, uint32_t, uint32_t);
+typedef void (*PlaceSumBatchFn)(const TensorDesc*, const uint32_t*);
+typedef void (*PlaceBatchFn)(const TensorDesc*, const uint32_t*, uint32_t);
 
 // e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
 CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
@@ -21,7 +23,9 @@ CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);
 DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);
 BatchCompressFn compress_batch_fn(bool eight_rows);
 BatchDecompressFn decompress_batch_fn(bool f32);
+PlaceSumFn place_sum_fn();
 PlaceFn place_fn();
+PlaceSumBatchFn place_sum_batch_fn();
 PlaceBatchFn place_batch_fn();
 
 // outlier channels (Section 3.2, Eq. 1)

@@ -7,30 +7,37 @@ namespace adacc {
 
 __device__ __forceinline__ void place_dispatch(const TensorDesc& d, uint32_t block, uint32_t epoch, PlaceShared& sh) {
   const bool e8 = (d.variant & 1u) != 0u;
+  const bool from_sums = d.n_blocks > kPlaceDirectBlocks;
   switch (d.variant >> 3) {
     case kModeAbs:
-      if (d.rowwise) place_block<kModeAbs, 4, true, false>(d, block, false, sh);
-      else if (e8) place_block<kModeAbs, 8, false, false>(d, block, false, sh);
-      else place_block<kModeAbs, 4, false, false>(d, block, false, sh);
+      if (d.rowwise) place_block<kModeAbs, 4, true, false>(d, block, from_sums, false, sh);
+      else if (e8) place_block<kModeAbs, 8, false, false>(d, block, from_sums, false, sh);
+      else place_block<kModeAbs, 4, false, false>(d, block, from_sums, false, sh);
       break;
     case kModeStd:
-      if (d.rowwise) place_block<kModeStd, 4, true, false>(d, block, false, sh);
-      else if (e8) place_block<kModeStd, 8, false, false>(d, block, false, sh);
-      else place_block<kModeStd, 4, false, false>(d, block, false, sh);
+      if (d.rowwise) place_block<kModeStd, 4, true, false>(d, block, from_sums, false, sh);
+      else if (e8) place_block<kModeStd, 8, false, false>(d, block, from_sums, false, sh);
+      else place_block<kModeStd, 4, false, false>(d, block, from_sums, false, sh);
       break;
     case kModeTopk:
       // regular counts everywhere (the usual case): the compression kernel has placed everything already
       if (__hip_atomic_load(d.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) return;
       if (topk_whole(d)) {
-        if (e8) place_block<kModeTopk, 8, false, true>(d, block, true, sh);
-        else place_block<kModeTopk, 4, false, true>(d, block, true, sh);
+        if (e8) place_block<kModeTopk, 8, false, true>(d, block, false, true, sh);
+        else place_block<kModeTopk, 4, false, true>(d, block, false, true, sh);
       } else {
-        if (e8) place_block<kModeTopk, 8, false, false>(d, block, true, sh);
-        else place_block<kModeTopk, 4, false, false>(d, block, true, sh);
+        if (e8) place_block<kModeTopk, 8, false, false>(d, block, false, true, sh);
+        else place_block<kModeTopk, 4, false, false>(d, block, false, true, sh);
       }
       break;
     default: break;
   }
+}
+
+// single tensor: blockIdx.x is the block of tiles
+__global__ __launch_bounds__(kPlaceThreads) void place_sum_kernel(TensorDesc d) {
+  __shared__ uint32_t part[kPlaceThreads / kWave];
+  place_sum_block(d, blockIdx.x, part);
 }
 
 __global__ __launch_bounds__(kPlaceThreads) void place_kernel(TensorDesc d, uint32_t epoch) {
@@ -38,18 +45,23 @@ __global__ __launch_bounds__(kPlaceThreads) void place_kernel(TensorDesc d, uint
   place_dispatch(d, blockIdx.x, epoch, sh);
 }
 
-// Placement for a table of tensors: blocks of kPlaceTiles tiles are numbered across the tensors that
-// keep outliers (first_block[]); tensors without outliers have no blocks.
-__global__ __launch_bounds__(kPlaceThreads) void place_batch_kernel(const TensorDesc* table, const uint32_t* first_block,
-                                                                    uint32_t n, uint32_t epoch) {
-  __shared__ PlaceShared sh;
-  // entries without blocks share their successor's first block; the bisection returns the last entry
-  // that starts at or before this block, which is the one that owns it
-  const TensorDesc d = table[find_entry(first_block, n, blockIdx.x)];
-  place_dispatch(d, blockIdx.x - d.first_block, epoch, sh);
+// a group of tensors of a table: blockIdx.y picks the tensor, blockIdx.x its block of tiles
+__global__ __launch_bounds__(kPlaceThreads) void place_sum_batch_kernel(const TensorDesc* table, const uint32_t* members) {
+  __shared__ uint32_t part[kPlaceThreads / kWave];
+  const TensorDesc d = table[members[blockIdx.y]];
+  if (blockIdx.x < d.n_blocks) place_sum_block(d, blockIdx.x, part);
 }
 
+__global__ __launch_bounds__(kPlaceThreads) void place_batch_kernel(const TensorDesc* table, const uint32_t* members,
+                                                                    uint32_t epoch) {
+  __shared__ PlaceShared sh;
+  const TensorDesc d = table[members[blockIdx.y]];
+  if (blockIdx.x < d.n_blocks) place_dispatch(d, blockIdx.x, epoch, sh);
+}
+
+PlaceSumFn place_sum_fn() { return place_sum_kernel; }
 PlaceFn place_fn() { return place_kernel; }
+PlaceSumBatchFn place_sum_batch_fn() { return place_sum_batch_kernel; }
 PlaceBatchFn place_batch_fn() { return place_batch_kernel; }
 
 }  // namespace adacc

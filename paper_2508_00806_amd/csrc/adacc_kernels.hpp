@@ -34,14 +34,12 @@ __device__ __forceinline__ bool topk_whole(const TensorDesc& d) { return d.lgs =
 // d.n_tiles counts pieces of 2048 elements here
 template <int BITS, bool ASYM, bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint32_t has_outliers) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<4, F32>()];
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<4, F32>();
   for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-    decompress_tile<BITS, ASYM, 4, F32>(d, t, has_outliers != 0u, slice);
+    decompress_tile<BITS, ASYM, 4, F32>(d, t, has_outliers != 0u);
 }
 
-// ---- batch: a launch-wide tile numbering over all tensors of the table
+// ---- batch
 // Variants with tiles of 8 rows need about twice the registers of those with 4; a kernel that
 // held both would run everything at the occupancy of the heaviest.  So the batch comes as two
 // kernels over the same table, and a wavefront whose tensor belongs to the other one leaves.
@@ -85,34 +83,25 @@ __device__ __forceinline__ void compress_dispatch_topk_whole(const TensorDesc& d
   }
 }
 
-// first[i] = launch-wide id of the first tile (or block) of table entry i, first[n] = the total:
-// the entry that holds id g, by bisection over that compact array (scalar loads from a few cache lines)
-__device__ __forceinline__ uint32_t find_entry(const uint32_t* first, uint32_t n, uint32_t g) {
-  uint32_t lo = 0u, hi = n;
-  while (hi - lo > 1u) {
-    const uint32_t mid = (lo + hi) >> 1;
-    if (first[mid] <= g) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-// One launch (per register class) for a table of tensors: tiles are numbered across the table; a
-// wavefront finds the tensor of its tile and dispatches on that tensor's method.
+// One launch for a group of tensors of a table: blockIdx.y picks the tensor (members[] holds the
+// group's table entries), blockIdx.x its tiles, four per workgroup; workgroups past the end of a
+// shorter tensor leave at once.  The host groups the tensors by register class (tiles of 4 or of 8
+// rows: variants with 8 rows need about twice the registers, and a kernel that held both would run
+// everything at the occupancy of the heaviest) and by size (tile counts within a factor of two), so
+// few workgroups are empty; within a launch the hardware goes through the tensors one after the
+// other, front to back.
 // The kernel for tiles of 8 rows is held to 3 wavefronts per SIMD: the variants that matter
 // (TOPK over the whole tile) fit, the rarely used ones spill a few registers.
 #ifndef ADACC_BATCH8_MIN_WAVES
 #define ADACC_BATCH8_MIN_WAVES 3
 #endif
 template <bool EIGHT_ROWS>
-__global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) void compress_batch_kernel(const TensorDesc* table, const uint32_t* first_tile, uint32_t n,
-                                                                  uint32_t total_tiles, uint32_t epoch) {
+__global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) void compress_batch_kernel(const TensorDesc* table, const uint32_t* members,
+                                                                  uint32_t epoch) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  const uint32_t g = blockIdx.x * kWavesPerWg + wave;
-  if (g >= total_tiles) return;
-  const uint32_t ti = __builtin_amdgcn_readfirstlane(find_entry(first_tile, n, g));
-  const TensorDesc d = table[ti];
-  if (((d.variant & 1u) != 0u) != EIGHT_ROWS) return;
-  const uint32_t tile = g - d.first_tile;
+  const TensorDesc d = table[members[blockIdx.y]];
+  const uint32_t tile = blockIdx.x * kWavesPerWg + wave;
+  if (tile >= d.n_tiles) return;
   switch (d.variant >> 3) {
     case kModeNone:
       if constexpr (!EIGHT_ROWS) {
@@ -149,37 +138,19 @@ __global__ __launch_bounds__(kThreads, EIGHT_ROWS ? ADACC_BATCH8_MIN_WAVES : 1) 
   }
 }
 
-// Batch decompression: a launch-wide numbering of the 2048-element pieces of all tensors.
+// Batch decompression: the same grouping, over the 2048-element pieces of the tensors.
 template <bool F32>
-__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, const uint32_t* first_tile,
-                                                                    uint32_t n, uint32_t total_tiles) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWavesPerWg * decompress_lds_per_wave<4, F32>()];
+__global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, const uint32_t* members) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  unsigned char* slice = lds + wave * decompress_lds_per_wave<4, F32>();
-  // A wavefront's pieces ascend, so the tensor of a piece is the one of the previous piece or a later
-  // one: one binary search at the start, then a walk, and the descriptor is read again only when
-  // the tensor changes.
-  uint32_t g = blockIdx.x * kWavesPerWg + wave;
-  if (g >= total_tiles) return;
-  uint32_t ti = __builtin_amdgcn_readfirstlane(find_entry(first_tile, n, g));
-  TensorDesc d = table[ti];
-  uint32_t next_first = first_tile[ti + 1u];  // first_tile[n] = total_tiles
-  for (; g < total_tiles; g += gridDim.x * kWavesPerWg) {
-    if (g >= next_first) {
-      do {
-        ++ti;
-        next_first = first_tile[ti + 1u];
-      } while (g >= next_first);
-      d = table[ti];
-    }
-    const uint32_t tile = g - d.first_tile;
-    const bool ho = (d.variant >> 3) != kModeNone;
-    switch (d.variant & 6u) {
-      case 0: decompress_tile<4, false, 4, F32>(d, tile, ho, slice); break;
-      case 2: decompress_tile<4, true, 4, F32>(d, tile, ho, slice); break;
-      case 4: decompress_tile<8, false, 4, F32>(d, tile, ho, slice); break;
-      default: decompress_tile<8, true, 4, F32>(d, tile, ho, slice); break;
-    }
+  const TensorDesc d = table[members[blockIdx.y]];
+  const uint32_t piece = blockIdx.x * kWavesPerWg + wave;
+  if (piece >= d.n_tiles) return;
+  const bool ho = (d.variant >> 3) != kModeNone;
+  switch (d.variant & 6u) {
+    case 0: decompress_tile<4, false, 4, F32>(d, piece, ho); break;
+    case 2: decompress_tile<4, true, 4, F32>(d, piece, ho); break;
+    case 4: decompress_tile<8, false, 4, F32>(d, piece, ho); break;
+    default: decompress_tile<8, true, 4, F32>(d, piece, ho); break;
   }
 }
 
