@@ -212,11 +212,14 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
   return ADACC_OK;
 }
 
-// TOPK whose statistics group is the tile has kernels of its own (for tiles of 8 rows: provided no
-// quantisation group is longer than 4 rows)
+// TOPK whose statistics group is the tile, with every quantisation group inside a 512-element row, has kernels of its own
 static bool topk_whole_tile(const adacc_method* m, const Plan& p) {
-  return m->outlier_mode == ADACC_OUTLIER_TOPK && m->stat_group == p.tile_elems &&
-         (p.tile_elems == 2048 || m->quant_group <= 2048);
+  return m->outlier_mode == ADACC_OUTLIER_TOPK && m->stat_group == p.tile_elems && m->quant_group <= 512;
+}
+static int batch_kind(const adacc_method* m, const Plan& p) {
+  const bool whole = topk_whole_tile(m, p);
+  if (p.tile_elems == 4096) return whole ? kBatchTopk8 : kBatchAny8;
+  return p.rowwise ? kBatchRows4 : (whole ? kBatchTopk4 : kBatchAny4);
 }
 
 static uint32_t decompress_pieces(uint64_t numel) { return (uint32_t)((numel + 2047ull) / 2048ull); }
@@ -282,6 +285,7 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
   {
     int ex = 0;
     d->inv_divisor = (std::frexp(p.divisor, &ex) == 0.5f) ? 1.0f / p.divisor : 0.0f;  // exact for a power of two
+    d->pow2_divisor = d->inv_divisor != 0.0f ? 1u : 0u;
   }
   d->variant = p.variant;
   d->rowwise = p.rowwise ? 1u : 0u;
@@ -316,9 +320,9 @@ static int grid_for(uint32_t n_tiles, const void* kernel, uint32_t* grid, int re
   return ADACC_OK;
 }
 
-BatchCompressFn compress_batch_fn4();
-BatchCompressFn compress_batch_fn8();
-BatchCompressFn compress_batch_fn(bool eight_rows) { return eight_rows ? compress_batch_fn8() : compress_batch_fn4(); }
+BatchCompressFn compress_batch_fn4(int kind);
+BatchCompressFn compress_batch_fn8(int kind);
+BatchCompressFn compress_batch_fn(int kind) { return kind >= kBatchAny8 ? compress_batch_fn8(kind) : compress_batch_fn4(kind); }
 
 // `whole` (TOPK only): the statistics group is the whole tile; that case has kernels of its own
 static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise, bool whole) {
@@ -405,7 +409,7 @@ struct GroupLaunch {
 // two of each other, at most 65535 entries per launch) and appends their member lists to `members`.
 static void group_launches(const std::vector<uint32_t>& units, const std::vector<int>& kind,
                            std::vector<uint32_t>* members, std::vector<GroupLaunch>* launches) {
-  for (int k = 0; k < 4; ++k) {
+  for (int k = 0; k < kBatchKinds; ++k) {
     for (uint32_t bucket = 0; bucket <= 32; ++bucket) {
       GroupLaunch g = {(uint32_t)members->size(), 0u, 0u, k};
       for (uint32_t i = 0; i < units.size(); ++i) {
@@ -563,9 +567,8 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
   TensorDesc d;
   fill_desc(method, numel, p, L, src, blob, nullptr, 0, p.outliers ? ws->device_mem : nullptr, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  uint32_t grid = 0, epoch = 0;
-  rc = grid_for(p.n_tiles, reinterpret_cast<const void*>(fn), &grid);
-  if (rc != ADACC_OK) return rc;
+  const uint32_t grid = (p.n_tiles + kWavesPerWg - 1) / kWavesPerWg;  // one tile per wavefront
+  uint32_t epoch = 0;
   if (p.outliers) {
     rc = next_epoch(ws, s, &epoch);
     if (rc != ADACC_OK) return rc;
@@ -729,7 +732,7 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   std::vector<uint32_t> units(nt), members;
   std::vector<int> kind(nt);
   std::vector<GroupLaunch> tiles, sums, places;
-  for (uint32_t i = 0; i < nt; ++i) { units[i] = descs[i].n_tiles; kind[i] = (int)(descs[i].variant & 1u); }
+  for (uint32_t i = 0; i < nt; ++i) { units[i] = descs[i].n_tiles; kind[i] = batch_kind(&methods[origin[i]], plans[origin[i]]); }
   group_launches(units, kind, &members, &tiles);
   for (uint32_t i = 0; i < nt; ++i) {
     units[i] = needs_block_sums(&methods[origin[i]], plans[origin[i]]) ? descs[i].n_blocks : 0u;
@@ -748,7 +751,7 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   if (rc == ADACC_OK) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : tiles)
-    hipLaunchKernelGGL(compress_batch_fn(g.kind != 0), dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members),
+    hipLaunchKernelGGL(compress_batch_fn(g.kind), dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members),
                        dim3(kThreads), 0, s, dt, dm + g.first_member, epoch);
   rc = launch_check("compress_batch_kernel");
   if (rc != ADACC_OK) return rc;

@@ -311,8 +311,7 @@ __device__ __forceinline__ void channel_compress_tile(const TensorDesc& d, const
       }
     }
   }
-  TileOutliers<E> out;
-  encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+  encode_tile<kModeNone, BITS, ASYM, E, ROWWISE, false, true>(d, g, raw, tile, NullSink{}, 0u, 0u);
 }
 
 template <int BITS, bool ASYM, bool ROWWISE>
@@ -421,10 +420,10 @@ __device__ __forceinline__ void channel_decompress_tile(const TensorDesc& d, con
       ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     } else {
       uint4 w;  // the bf16 image of a widened bf16 value is that value
-      w.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
-      w.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
-      w.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
-      w.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
+      w.x = bf16_pair(v[0], v[1]);
+      w.y = bf16_pair(v[2], v[3]);
+      w.z = bf16_pair(v[4], v[5]);
+      w.w = bf16_pair(v[6], v[7]);
       ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
     }
   }

@@ -95,6 +95,7 @@ struct TensorDesc {
   float param;          // ABS: tau.  STD: k*k
   float divisor;        // D of Eq. 2 resp. Eq. 3 (2^(b-1), 2^b, or one less)
   float inv_divisor;    // 1/D when D is a power of two (the paper's rule), else 0
+  uint32_t pow2_divisor;  // 1 when D is a power of two
   uint32_t rowwise;     // compress: 1 = every group lies inside a row (row-at-a-time encoder)
   uint32_t variant;     // index into the instantiation table
   uint32_t dst_f32;     // decompress: 1 = binary32 output
@@ -141,6 +142,9 @@ constexpr uint32_t kPlaceDirectBlocks = 8;
 // The workspace's launch counter ("epoch", kept on the host in adacc_workspace) marks what a launch
 // wrote: a word that holds an older epoch reads as not set, so nothing has to be cleared per call.
 constexpr uint32_t kEpochMax = 0x3FFFFFFFu;
+
+// the batch compression kernels, by the weight of the variants they hold (adacc_kernels.hpp)
+enum : int { kBatchRows4 = 0, kBatchAny4 = 1, kBatchTopk4 = 2, kBatchAny8 = 3, kBatchTopk8 = 4, kBatchKinds = 5 };
 
 // variant index: ((mode*2 + (bits==8)) * 2 + asym) * 2 + (E==8)
 __host__ __device__ inline uint32_t variant_index(uint32_t mode, uint32_t bits, uint32_t asym, uint32_t e8) {

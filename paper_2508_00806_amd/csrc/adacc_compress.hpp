@@ -279,8 +279,13 @@ __device__ __forceinline__ void widen_row(const uint32_t (&oct)[4], float (&x)[k
 template <int BITS, bool ASYM, int E>
 __device__ __forceinline__ void store_row(const TensorDesc& d, const TileGeo<E>& g, int j, const uint32_t (&c)[kOct],
                                           float scl, float off) {
-  const uint32_t eo = g.lane_off + (uint32_t)(j * kRow);  // element offset in the tile
-  unsigned char* cp = d.codes + g.base * BITS / 8;         // uniform
+  // The lane's offset is formed here, per row, from a copy the compiler knows nothing about: else it
+  // prepares the offsets (and the group numbers) of all rows ahead of the first row, for every
+  // group size the caller can be asked for, and keeps them in registers.
+  uint32_t lane_off = g.lane_off;
+  asm volatile("" : "+v"(lane_off));
+  const uint32_t eo = lane_off + (uint32_t)(j * kRow);  // element offset in the tile
+  unsigned char* cp = d.codes + g.base * BITS / 8;       // uniform
   float* sp = d.scales + (g.base >> d.lgq);                // uniform
   const uint32_t gl = eo >> d.lgq;
   uint2 w8;
@@ -404,36 +409,192 @@ __device__ __forceinline__ bool outlier_test(float x, float param_or_limit) {
 }
 __device__ __forceinline__ bool is_nonfinite(float x) { return (__float_as_uint(x) & 0x7FFFFFFFu) >= 0x7F800000u; }
 
+// ---- a4: where the outliers of a tile go.  Entry `pos` of the stream of the blob (two arrays) ...
+struct StreamSink {
+  int32_t* idx;
+  uint16_t* val;
+  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t index, uint32_t bits) const {
+    idx[pos] = (int32_t)index;
+    val[pos] = (uint16_t)bits;
+  }
+};
+// ... or of a tile's slot in the workspace (one 8-byte record per entry: index, value) ...
+struct SlotSink {
+  uint2* rec;
+  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t index, uint32_t bits) const {
+    rec[pos] = make_uint2(index, bits);
+  }
+};
+// ... or nowhere (tiles without outliers)
+struct NullSink {
+  __device__ __forceinline__ void operator()(uint32_t, uint32_t, uint32_t) const {}
+};
+
+// The outliers of one row, in ascending index order, to positions pos_row, pos_row + 1, ... of the
+// sink (entries at or past `limit` are dropped).  mask: this lane's outliers among its 8 elements;
+// lane_excl: the row's outliers in lower lanes; sparse (uniform): no lane holds more than one;
+// i0: flat index of the lane's first element of the row.
+template <class Sink>
+__device__ __forceinline__ void emit_row(const uint32_t (&oct)[4], uint32_t mask, uint32_t lane_excl, bool sparse,
+                                         uint32_t i0, const Sink& sink, uint32_t pos_row, uint32_t limit) {
+  uint32_t pos = pos_row + lane_excl;
+  if (sparse) {
+    if (mask != 0u && pos < limit) {
+      const uint32_t e = (uint32_t)__builtin_ctz(mask);
+      const uint64_t lo = ((uint64_t)oct[1] << 32) | oct[0], hi = ((uint64_t)oct[3] << 32) | oct[2];
+      const uint64_t half = (e & 4u) ? hi : lo;
+      sink(pos, i0 + e, (uint32_t)(half >> ((e & 3u) * 16u)) & 0xFFFFu);
+    }
+  } else {
+    static_for<kOct>([&](auto Ec) {
+      constexpr int e = decltype(Ec)::value;
+      if ((mask >> e) & 1u) {
+        if (pos < limit) sink(pos, i0 + (uint32_t)e, (e & 1) ? (oct[e >> 1] >> 16) : (oct[e >> 1] & 0xFFFFu));
+        ++pos;
+      }
+    });
+  }
+}
+
+// the outliers of a whole tile whose bookkeeping was kept (general encoder); only rows that have any are visited
+template <int E, class Sink>
+__device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const TileOutliers<E>& out, uint32_t tile,
+                                              const Sink& sink, uint32_t pos0, uint32_t limit) {
+  const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
+  static_for<E>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    if (out.row_cnt[j] != 0u)  // uniform
+      emit_row(raw[j], out.mask[j], out.lane_excl[j], ((out.sparse >> j) & 1u) != 0u, lane_first + (uint32_t)(j * kRow),
+               sink, pos0 + out.row_off[j], limit);
+  });
+}
+
+// ------------------------------------------------------------------ rows without outliers
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t,
+                            __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
+}
+
+// zero the elements of an octet that `mask` names (bit e: element e)
+__device__ __forceinline__ void clear_elements(uint32_t (&oct)[4], uint32_t mask) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)mask, 2 * k, 1);  // 0 or all ones
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_sbfe((int)mask, 2 * k + 1, 1);
+    oct[k] &= ~((lo & 0x0000FFFFu) | (hi & 0xFFFF0000u));
+  }
+}
+
+// largest magnitude (15 low bits of the bf16 patterns) among the 8 elements of an octet
+__device__ __forceinline__ uint32_t octet_magnitude(const uint32_t (&oct)[4]) {
+  constexpr uint32_t kMag2 = 0x7FFF7FFFu;
+  const uint32_t m = pk_max_u16(pk_max_u16(oct[0] & kMag2, oct[1] & kMag2), pk_max_u16(oct[2] & kMag2, oct[3] & kMag2));
+  const uint32_t hi = m >> 16, lo = m & 0xFFFFu;
+  return hi > lo ? hi : lo;
+}
+
+// a6, symmetric, for a row free of outliers and of values that are not finite: S and D / max from
+// the group's largest magnitude (`am_bits`: its binary32 bits; it has at most 8 significant bits).
+// For the paper's divisor, a power of two, D / max needs no division sequence: the hardware
+// reciprocal is within one unit in the last place, and for an operand of 8 significant bits one
+// Newton step then gives the correctly rounded 1 / max (verified for every significand and every
+// such starting value); the factor D is exact.  Outside 2^-100 .. 2^100 (where the reciprocal, or
+// D / max, leaves the normal range) and for other divisors the division is carried out.
+__device__ __forceinline__ void scale_sym_clean(const TensorDesc& d, uint32_t am_bits, float& scl, float& inv) {
+  const float am = __uint_as_float(am_bits);
+  const bool mid = am_bits - 0x0D800000u <= 0x71800000u - 0x0D800000u;  // 2^-100 <= max <= 2^100
+  const bool hard = !mid && am_bits != 0u;
+  if ((d.pow2_divisor != 0u) & (__builtin_amdgcn_ballot_w64(hard) == 0ull)) {  // uniform
+    scl = am * d.inv_divisor;
+    float r = __builtin_amdgcn_rcpf(am);
+    const float e = __fmaf_rn(-am, r, 1.0f);
+    r = __fmaf_rn(r, e, r);
+    inv = am_bits != 0u ? r * d.divisor : 0.0f;
+  } else {
+    float off;
+    group_scale<false>(d, am_bits, 0, 0, scl, inv, off);
+  }
+}
+
+// a6 .. a8 for one row of a tile from which outliers and values that are not finite are gone
+// (they are zero in `oct`).  top: symmetric, the lane's largest magnitude of the row as binary32 bits.
+template <int BITS, bool ASYM, int E, int LANES>
+__device__ __forceinline__ void encode_clean_row(const TensorDesc& d, const TileGeo<E>& g, int j, const uint32_t (&oct)[4],
+                                                 uint32_t top) {
+  constexpr int Q = 1 << (BITS - 1);
+  float x[kOct];
+  widen_row(oct, x);
+  float scl, inv, off = 0.0f;
+  if constexpr (!ASYM) {
+    scale_sym_clean(d, lanes_reduce<LANES>(top, OpUMax()), scl, inv);
+  } else {
+    float ext0, ext1;
+    row_extremes<true>(x, ext0, ext1);
+    const int32_t k0 = lanes_reduce<LANES>(float_key(ext0), OpIMax());
+    const int32_t k1 = lanes_reduce<LANES>(float_key(ext1), OpIMin());
+    group_scale<true>(d, 0u, k0, k1, scl, inv, off);
+  }
+  uint32_t c[kOct];
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? x[e] - off : x[e], inv);
+  store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
+}
+
 // ------------------------------------------------------------------ tile encoder for groups inside a row
 // Used when every group (statistics and quantisation) lies inside one 512-element row and both
 // kinds have the same size: each row is taken from the raw octets to its stored codes in one
 // go, so nothing but the raw octets lives across rows.  LANES = lanes per group.
-template <int MODE, int BITS, bool ASYM, int E, int LANES, bool STORE>
-__device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
-                                            TileOutliers<E>& out) {
+template <int MODE, int BITS, bool ASYM, int E, int LANES, bool STORE, class Sink>
+__device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
+                                                uint32_t tile, const Sink& sink, uint32_t pos0, uint32_t limit) {
   constexpr int Q = 1 << (BITS - 1);
   const float inv_gs = __uint_as_float((127u - d.lgs) << 23);  // 2^-lgs, exact
-  out.total = 0u;
-  out.sparse = 0u;
+  const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
+  uint32_t total = 0u;  // uniform: outliers of the rows so far
 #pragma unroll
   for (int j = 0; j < E; ++j) {
+    __builtin_amdgcn_sched_barrier(0);  // one row after the other
     float x[kOct];
     widen_row(raw[j], x);
-    // the 8 outlier tests of the row as wavefront ballots (scalar registers)
-    uint64_t b[kOct];
+    // First a test per lane that is cheap and errs on the safe side: can this lane's octet hold an
+    // outlier (or, without outliers, a value that is not finite)?  If no lane says yes - nearly
+    // every row - the row is quantised as it is.  am_bits: the lane's largest |x| (symmetric).
+    float q[kOct];
+    float limit_sq = 0.0f;
+    uint32_t am_bits = 0u;
+    bool suspect;
     if constexpr (MODE == kModeStd) {
-      float q[kOct];
 #pragma unroll
       for (int e = 0; e < kOct; ++e) q[e] = x[e] * x[e];  // exact: two 8-bit significands
       float s1 = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
       float s2 = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
       s1 = lanes_reduce<LANES>(s1, OpAdd());
       s2 = lanes_reduce<LANES>(s2, OpAdd());
-      const float limit = std_limit(s1, s2, inv_gs, d.param);
+      limit_sq = std_limit(s1, s2, inv_gs, d.param);
+      const float qm = fmaxf(fmaxf(fmaxf(q[0], q[1]), fmaxf(q[2], q[3])), fmaxf(fmaxf(q[4], q[5]), fmaxf(q[6], q[7])));
+      // an Inf or NaN anywhere in a group makes its limit NaN
+      suspect = !(qm <= limit_sq);
+      if constexpr (!ASYM) {
+        const float am = fmaxf(fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3]))),
+                               fmaxf(fmaxf(fabsf(x[4]), fabsf(x[5])), fmaxf(fabsf(x[6]), fabsf(x[7]))));
+        am_bits = __float_as_uint(am);
+      }
+    } else {
+      am_bits = octet_magnitude(raw[j]) << 16;  // Inf / NaN show as a value of 0x7F800000 or more
+      if constexpr (MODE == kModeAbs) suspect = am_bits > __float_as_uint(d.param);  // tau >= 0, finite
+      else suspect = am_bits >= 0x7F800000u;
+    }
+    if (__builtin_amdgcn_ballot_w64(suspect) == 0ull) {  // uniform
+      if constexpr (STORE) encode_clean_row<BITS, ASYM, E, LANES>(d, g, j, raw[j], am_bits);
+      continue;
+    }
+    // the 8 outlier tests of the row as wavefront ballots (scalar registers)
+    uint64_t b[kOct];
+    if constexpr (MODE == kModeStd) {
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(q[e] > limit);
-      // an Inf or NaN anywhere in a group makes its limit NaN; only then is the per-element test needed
-      if (__builtin_amdgcn_ballot_w64(limit != limit) != 0ull) {
+      for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(q[e] > limit_sq);
+      if (__builtin_amdgcn_ballot_w64(limit_sq != limit_sq) != 0ull) {  // then every element is tested for Inf / NaN
 #pragma unroll
         for (int e = 0; e < kOct; ++e) b[e] |= __builtin_amdgcn_ballot_w64(is_nonfinite(x[e]));
       }
@@ -441,19 +602,13 @@ __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E
 #pragma unroll
       for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(outlier_test<MODE>(x[e], d.param));
     }
+    uint32_t mask, lane_excl, row_cnt;
     bool any, sparse;
-    row_bookkeeping(b, out.mask[j], out.lane_excl[j], out.row_cnt[j], any, sparse);
-    out.sparse |= sparse ? (1u << j) : 0u;
-    out.row_off[j] = out.total;
-    if constexpr (MODE != kModeNone) out.total += out.row_cnt[j];
+    row_bookkeeping(b, mask, lane_excl, row_cnt, any, sparse);
     if constexpr (STORE) {
       float y[kOct];
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) y[e] = x[e];
-      if (any) {  // uniform: the inlier view differs from the row only where the ballots say so
-#pragma unroll
-        for (int e = 0; e < kOct; ++e) y[e] = __builtin_amdgcn_inverse_ballot_w64(b[e]) ? 0.0f : x[e];
-      }
+      for (int e = 0; e < kOct; ++e) y[e] = __builtin_amdgcn_inverse_ballot_w64(b[e]) ? 0.0f : x[e];
       float ext0, ext1;
       row_extremes<ASYM>(y, ext0, ext1);
       float scl, inv, off;
@@ -470,20 +625,28 @@ __device__ __forceinline__ void encode_rows(const TensorDesc& d, const TileGeo<E
       for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off : y[e], inv);
       store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
     }
+    if constexpr (MODE != kModeNone) {
+      if (any) {  // uniform: the row's outliers leave at once, nothing about them is kept
+        emit_row(raw[j], mask, lane_excl, sparse, lane_first + (uint32_t)(j * kRow), sink, pos0 + total, limit);
+        total += row_cnt;
+      }
+    }
   }
+  return total;
 }
 
-template <int MODE, int BITS, bool ASYM, int E, bool STORE>
-__device__ __forceinline__ void encode_tile_rowwise(const TensorDesc& d, const TileGeo<E>& g,
-                                                    const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
+template <int MODE, int BITS, bool ASYM, int E, bool STORE, class Sink>
+__device__ __forceinline__ uint32_t encode_tile_rowwise(const TensorDesc& d, const TileGeo<E>& g,
+                                                        const uint32_t (&raw)[E][4], uint32_t tile, const Sink& sink,
+                                                        uint32_t pos0, uint32_t limit) {
   switch (d.lgq) {  // one switch per tile selects straight-line code for the group size
-    case 3: encode_rows<MODE, BITS, ASYM, E, 1, STORE>(d, g, raw, out); break;
-    case 4: encode_rows<MODE, BITS, ASYM, E, 2, STORE>(d, g, raw, out); break;
-    case 5: encode_rows<MODE, BITS, ASYM, E, 4, STORE>(d, g, raw, out); break;
-    case 6: encode_rows<MODE, BITS, ASYM, E, 8, STORE>(d, g, raw, out); break;
-    case 7: encode_rows<MODE, BITS, ASYM, E, 16, STORE>(d, g, raw, out); break;
-    case 8: encode_rows<MODE, BITS, ASYM, E, 32, STORE>(d, g, raw, out); break;
-    default: encode_rows<MODE, BITS, ASYM, E, 64, STORE>(d, g, raw, out); break;
+    case 3: return encode_rows<MODE, BITS, ASYM, E, 1, STORE>(d, g, raw, tile, sink, pos0, limit);
+    case 4: return encode_rows<MODE, BITS, ASYM, E, 2, STORE>(d, g, raw, tile, sink, pos0, limit);
+    case 5: return encode_rows<MODE, BITS, ASYM, E, 4, STORE>(d, g, raw, tile, sink, pos0, limit);
+    case 6: return encode_rows<MODE, BITS, ASYM, E, 8, STORE>(d, g, raw, tile, sink, pos0, limit);
+    case 7: return encode_rows<MODE, BITS, ASYM, E, 16, STORE>(d, g, raw, tile, sink, pos0, limit);
+    case 8: return encode_rows<MODE, BITS, ASYM, E, 32, STORE>(d, g, raw, tile, sink, pos0, limit);
+    default: return encode_rows<MODE, BITS, ASYM, E, 64, STORE>(d, g, raw, tile, sink, pos0, limit);
   }
 }
 
@@ -499,12 +662,6 @@ __device__ __forceinline__ void encode_tile_rowwise(const TensorDesc& d, const T
 //
 // By rounds (any group, any k): k max-reductions over keys (magnitude above, inverted position
 // below, so ties go to the lower index), each restricted to the keys below the previous winner.
-typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t,
-                            __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a), __builtin_bit_cast(u16x2_t, b)));
-}
-
 // largest magnitude (15 low bits of the bf16 patterns) among the lane's 8 elements of every row:
 // two 16-bit lanes at a time.  An Inf or NaN shows as a value >= 0x7F80.
 template <int E>
@@ -588,6 +745,7 @@ __device__ __forceinline__ bool topk_select_rounds(const TensorDesc& d, const ui
   for (int j = 0; j < E; ++j) kth[j] = 0xFFFFFFFFu;
   for (uint32_t r = 0; r < d.topk; ++r) {
     forget_derived<E>(raw);  // the keys are formed again in every round: holding them would cost 8 registers per row
+    asm volatile("" : "+v"(lane_pos));  // and so are the position codes
     uint32_t best[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) {
@@ -767,9 +925,7 @@ __device__ __forceinline__ void finish_tile(const TensorDesc& d, const TileGeo<E
   }
 }
 
-// WHOLE: the statistics group is the tile (known at compile time, so that nothing about rows per
-// group is decided at run time: each such decision costs scalar instructions and registers).
-template <int MODE, int BITS, bool ASYM, int E, bool STORE, bool WHOLE>
+template <int MODE, int BITS, bool ASYM, int E, bool STORE>
 __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const TileGeo<E>& g,
                                                     const uint32_t (&raw)[E][4], TileOutliers<E>& out) {
   // ---- a2: statistics of the statistics groups
@@ -808,13 +964,8 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     poisoned = __builtin_amdgcn_ballot_w64(nan_seen) != 0ull;
   } else if constexpr (MODE == kModeTopk) {
     const uint32_t lane = (uint32_t)lane_id();
-    if constexpr (WHOLE) {
-      R = E;
-      lane_pos = lane << 3;
-    } else {
-      R = (d.lgs > 9) ? (1 << (d.lgs - 9)) : 1;
-      lane_pos = (d.lgs > 9) ? (lane << 3) : ((lane & ((1u << (d.lgs - 3)) - 1u)) << 3);
-    }
+    R = (d.lgs > 9) ? (1 << (d.lgs - 9)) : 1;
+    lane_pos = (d.lgs > 9) ? (lane << 3) : ((lane & ((1u << (d.lgs - 3)) - 1u)) << 3);
   }
 
   // ---- a3 + a5: outlier test row by row; extremes of the inlier view per lane
@@ -823,13 +974,13 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
     // First the selection by lane maxima where it applies; if it does not stand, once more by rounds.
     // One copy of the code in a loop (rather than two in a row) keeps the registers of the rare second
     // pass from adding to those of the first.
-    bool try_maxima = (WHOLE || d.lgs >= 9u) && d.topk <= 8u;
+    bool try_maxima = d.lgs >= 9u && d.topk <= 8u;
 #pragma nounroll
     while (true) {
       bool by_magnitude = false;
       if (try_maxima) {
         if constexpr (ASYM) row_magnitudes<E>(raw, rowmag);
-        by_magnitude = topk_lane_maxima<E, WHOLE>(d, rowmag, thr);
+        by_magnitude = topk_lane_maxima<E, false>(d, rowmag, thr);
       }
       if (!by_magnitude) {
         // nothing on this rare path may be prepared outside the loop over tiles (32 position codes
@@ -845,7 +996,7 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
 #pragma unroll
       for (int j = 0; j < E; ++j) {
         in_group += out.row_cnt[j];
-        if (WHOLE ? (j == E - 1) : ((j & (R - 1)) == R - 1)) { exact = exact && (in_group == d.topk); in_group = 0u; }
+        if ((j & (R - 1)) == R - 1) { exact = exact && (in_group == d.topk); in_group = 0u; }
       }
       if (exact) break;
       try_maxima = false;
@@ -870,7 +1021,8 @@ __device__ __forceinline__ bool topk_select_rounds_whole(const TensorDesc& d, co
                                                          uint32_t lane_pos) {
   uint32_t kth = 0xFFFFFFFFu;
   for (uint32_t r = 0; r < d.topk; ++r) {
-    forget_derived<E>(raw);  // the keys are formed again in every round
+    forget_derived<E>(raw);  // the keys are formed again in every round ...
+    asm volatile("" : "+v"(lane_pos));  // ... and so are the position codes: 8 per row would sit in registers otherwise
     uint32_t m = 0u;
 #pragma unroll
     for (int j = 0; j < E; ++j) {
@@ -888,137 +1040,153 @@ __device__ __forceinline__ bool topk_select_rounds_whole(const TensorDesc& d, co
   return (kth >> 16) >= 0x7F80u;
 }
 
-// TOPK over a tile of 8 rows that is one statistics group, quantisation groups inside 4 rows
-// (such tiles are always complete: the group size divides the tensor).  The selection looks at
-// all 8 rows; everything else runs on two pieces of 4 rows with the code for 4-row tiles, whose
-// per-row arrays are half as long: 4 instead of 3 wavefronts per SIMD, and no code of its own.
-template <int BITS, bool ASYM, bool STORE>
-__device__ __forceinline__ void encode_tile_whole8(const TensorDesc& d, const TileGeo<8>& g, const uint32_t (&raw)[8][4],
-                                                   TileOutliers<8>& out) {
-  constexpr int H = 4;
-  const uint32_t(&ra)[H][4] = reinterpret_cast<const uint32_t(&)[H][4]>(raw[0]);
-  const uint32_t(&rb)[H][4] = reinterpret_cast<const uint32_t(&)[H][4]>(raw[H]);
-  TileGeo<H> ga, gb;
-  ga.base = g.base; ga.lane_off = g.lane_off; ga.rem = (uint32_t)(H * kRow); ga.full = true;
-  gb.base = g.base + (uint64_t)(H * kRow); gb.lane_off = g.lane_off; gb.rem = (uint32_t)(H * kRow); gb.full = true;
+// ------------------------------------------------------------------ TOPK over a whole tile, quantisation groups inside a row
+// The tile is one statistics group (so it is complete: group sizes divide the tensor) and every
+// quantisation group lies inside a 512-element row.  The paper's order, literally: the outliers
+// are found, handed to the sink, and set to zero in the registers that hold the tile; what is left
+// is quantised row by row with no thought of outliers.  Nothing but the raw octets and the lane's
+// largest magnitude per row lives across rows.  LANES = lanes per quantisation group.
 
-  uint32_t rowmag[8];
-  row_magnitudes<8>(raw, rowmag);
-  const uint32_t(&ma)[H] = reinterpret_cast<const uint32_t(&)[H]>(rowmag[0]);
-  const uint32_t(&mb)[H] = reinterpret_cast<const uint32_t(&)[H]>(rowmag[H]);
-  uint32_t lane_pos = (uint32_t)lane_id() << 3;
-  float limit[H];
-#pragma unroll
-  for (int j = 0; j < H; ++j) limit[j] = 0.0f;
-  TileOutliers<H> oa, ob;
-  float e0a[H], e1a[H], e0b[H], e1b[H];
-  bool poisoned = false;
-  bool try_maxima = d.topk <= 8u;
-#pragma nounroll
-  while (true) {
-    bool by_magnitude = false;
-    uint32_t t = 0u;  // uniform: magnitude threshold (bits of a binary32) or k-th largest key
-    if (try_maxima) {
-      uint32_t thr8[8];
-      by_magnitude = topk_lane_maxima<8, true>(d, rowmag, thr8);
-      t = thr8[0];
-    }
-    if (!by_magnitude) {
-      asm volatile("" : "+v"(lane_pos));  // nothing of this rare path is prepared outside the loop over tiles
-      poisoned = topk_select_rounds_whole<8>(d, raw, t, lane_pos);
-    }
-    uint32_t thr[H];
-#pragma unroll
-    for (int j = 0; j < H; ++j) thr[j] = t;
-    outlier_phase<kModeTopk, ASYM, H>(d, ga, ra, limit, thr, by_magnitude, poisoned, lane_pos, 8, ma, e0a, e1a, oa, 0);
-    outlier_phase<kModeTopk, ASYM, H>(d, gb, rb, limit, thr, by_magnitude, poisoned, lane_pos, 8, mb, e0b, e1b, ob, H);
-    oa.total = 0u; ob.total = 0u;
-#pragma unroll
-    for (int j = 0; j < H; ++j) {
-      oa.row_off[j] = oa.total; oa.total += oa.row_cnt[j];
-      ob.row_off[j] = ob.total; ob.total += ob.row_cnt[j];
-    }
-    if (!by_magnitude) break;
-    if (oa.total + ob.total == d.topk) break;  // exactly k at or above the threshold: they are the k largest
-    try_maxima = false;
-  }
-  if constexpr (STORE) {
-    finish_tile<BITS, ASYM, H>(d, ga, ra, e0a, e1a, oa);
-    finish_tile<BITS, ASYM, H>(d, gb, rb, e0b, e1b, ob);
-  }
-#pragma unroll
-  for (int j = 0; j < H; ++j) {
-    out.mask[j] = oa.mask[j]; out.mask[H + j] = ob.mask[j];
-    out.lane_excl[j] = oa.lane_excl[j]; out.lane_excl[H + j] = ob.lane_excl[j];
-    out.row_cnt[j] = oa.row_cnt[j]; out.row_cnt[H + j] = ob.row_cnt[j];
-    out.row_off[j] = oa.row_off[j]; out.row_off[H + j] = oa.total + ob.row_off[j];
-  }
-  out.total = oa.total + ob.total;
-  out.sparse = oa.sparse | (ob.sparse << H);
-}
-
-// ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide.
-// STORE = false: only the outliers are found (nothing is quantised or stored).
-// WHOLE (general encoder, TOPK): the statistics group is the whole tile (with 8 rows: and no
-// quantisation group is longer than 4 rows).
-template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false, bool STORE = true>
-__device__ __forceinline__ void encode_tile(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
-                                            TileOutliers<E>& out) {
-  static_assert(!WHOLE || (MODE == kModeTopk && !ROWWISE), "only the general TOPK encoder is specialised");
-  if constexpr (ROWWISE) encode_tile_rowwise<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
-  else if constexpr (WHOLE && E == 8) encode_tile_whole8<BITS, ASYM, STORE>(d, g, raw, out);
-  else encode_tile_general<MODE, BITS, ASYM, E, STORE, WHOLE>(d, g, raw, out);
-}
-
-// ---- a4: append a tile's outliers, in ascending index order, to `idx_out` / `val_out` starting
-// at position pos0 (entries at or past `limit` are dropped).  The destination is either the
-// stream in global memory or the wavefront's staging area in LDS.  Only rows that have
-// outliers are visited.
-// where emit_outliers puts entry `pos`: the stream of the blob (two arrays) ...
-struct StreamSink {
-  int32_t* idx;
-  uint16_t* val;
-  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t index, uint32_t bits) const {
-    idx[pos] = (int32_t)index;
-    val[pos] = (uint16_t)bits;
-  }
-};
-// ... or a tile's slot in the workspace (one 8-byte record per entry: index, value)
-struct SlotSink {
-  uint2* rec;
-  __device__ __forceinline__ void operator()(uint32_t pos, uint32_t index, uint32_t bits) const {
-    rec[pos] = make_uint2(index, bits);
-  }
-};
-
+// Extraction by keys (any tile): the k largest keys (magnitude above, inverted position below), and
+// every value that is not finite when those are more than k.  Returns the number of outliers.
 template <int E, class Sink>
-__device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const TileOutliers<E>& out, uint32_t tile,
-                                              const Sink& sink, uint32_t pos0, uint32_t limit) {
+__device__ __forceinline__ uint32_t topk_extract_by_keys(const TensorDesc& d, uint32_t (&raw)[E][4], uint32_t tile,
+                                                        const Sink& sink, uint32_t pos0, uint32_t limit) {
+  uint32_t lane_pos = (uint32_t)lane_id() << 3;
+  uint32_t kth;
+  const bool poisoned = topk_select_rounds_whole<E>(d, raw, kth, lane_pos);
   const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
-  static_for<E>([&](auto J) {
-    constexpr int j = decltype(J)::value;
-    if (out.row_cnt[j] != 0u) {  // uniform
-      const uint32_t bits = out.mask[j];
-      uint32_t pos = pos0 + out.row_off[j] + out.lane_excl[j];
-      const uint32_t i0 = lane_first + (uint32_t)(j * kRow);
-      if ((out.sparse >> j) & 1u) {  // uniform: at most one outlier per lane
-        if (bits != 0u && pos < limit) {
-          const uint32_t e = (uint32_t)__builtin_ctz(bits);
-          const uint64_t lo = ((uint64_t)raw[j][1] << 32) | raw[j][0], hi = ((uint64_t)raw[j][3] << 32) | raw[j][2];
-          const uint64_t half = (e & 4u) ? hi : lo;
-          sink(pos, i0 + e, (uint32_t)(half >> ((e & 3u) * 16u)) & 0xFFFFu);
-        }
-      } else {
-        static_for<kOct>([&](auto Ec) {
-          constexpr int e = decltype(Ec)::value;
-          if ((bits >> e) & 1u) {
-            if (pos < limit) sink(pos, i0 + (uint32_t)e, (e & 1) ? (raw[j][e >> 1] >> 16) : (raw[j][e >> 1] & 0xFFFFu));
-            ++pos;
-          }
-        });
-      }
+  uint32_t total = 0u;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    __builtin_amdgcn_sched_barrier(0);  // row after row, and the position codes of a row formed when its turn comes
+    asm volatile("" : "+v"(lane_pos));
+    const uint32_t row_pos = ((uint32_t)j << 9) | lane_pos;
+    uint64_t b[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      const uint32_t mag = ADACC_ELEM_MAG(raw[j], e);
+      const uint32_t key = (mag << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
+      b[e] = __builtin_amdgcn_ballot_w64(key >= kth || (poisoned && mag >= 0x7F80u));
     }
-  });
+    uint32_t mask, lane_excl, row_cnt;
+    bool any, sparse;
+    row_bookkeeping(b, mask, lane_excl, row_cnt, any, sparse);
+    if (any) {
+      emit_row(raw[j], mask, lane_excl, sparse, lane_first + (uint32_t)(j * kRow), sink, pos0 + total, limit);
+      total += row_cnt;
+      clear_elements(raw[j], mask);
+    }
+  }
+  return total;
+}
+
+// The extraction: finds the k largest, hands them to the sink, clears them in `raw`.  rowmag: the
+// lane's largest magnitude per row of what is left.  Returns the number of outliers (uniform).
+template <int E, bool STORE, class Sink>
+__device__ __forceinline__ uint32_t topk_extract(const TensorDesc& d, uint32_t (&raw)[E][4], uint32_t (&rowmag)[E],
+                                                 uint32_t tile, const Sink& sink, uint32_t pos0, uint32_t limit) {
+  row_magnitudes<E>(raw, rowmag);
+  const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
+  uint32_t total = 0u;  // uniform: outliers found
+  bool done = false;    // uniform
+  if (d.topk <= 8u) {
+    uint32_t thr[E];
+    if (topk_lane_maxima<E, true>(d, rowmag, thr)) {  // false if the tile holds an Inf or a NaN
+      // Selection |x| >= t, t the k-th largest of the lanes' maxima: it is the answer if exactly k
+      // elements pass.  Only rows in which some lane's largest magnitude reaches t can hold any.
+      // The outliers leave and are cleared as they are found; if in the end they were not k (two of
+      // the largest in one lane, a tie at the k-th place: a tile in a hundred) the tile is read
+      // again and done by keys.
+      const uint32_t t = thr[0];
+      const float tf = __uint_as_float(t);
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        if (__builtin_amdgcn_ballot_w64((rowmag[j] << 16) >= t) == 0ull) continue;  // uniform
+        float x[kOct];
+        widen_row(raw[j], x);
+        uint64_t b[kOct];
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(fabsf(x[e]) >= tf);
+        uint32_t mask, lane_excl, row_cnt;
+        bool any, sparse;
+        row_bookkeeping(b, mask, lane_excl, row_cnt, any, sparse);
+        emit_row(raw[j], mask, lane_excl, sparse, lane_first + (uint32_t)(j * kRow), sink, pos0 + total, limit);
+        total += row_cnt;
+        clear_elements(raw[j], mask);
+        rowmag[j] = octet_magnitude(raw[j]);
+      }
+      done = total == d.topk;
+    }
+  }
+  if (!done) {
+    if (total != 0u) {
+      // some outliers have left and are cleared already: start over from the source, once the
+      // stores of the first attempt are complete (the second attempt writes the same entries)
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      load_tile<E, true>(d, tile, raw);
+    }
+    total = topk_extract_by_keys<E>(d, raw, tile, sink, pos0, limit);
+    if constexpr (STORE) row_magnitudes<E>(raw, rowmag);
+  }
+  return total;
+}
+
+template <int BITS, bool ASYM, int E, int LANES>
+__device__ __forceinline__ void encode_clean_rows(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
+                                                  const uint32_t (&rowmag)[E]) {
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    // one row after the other: the compiler shall not start on the next rows to hide this row's
+    // latencies (other wavefronts do that), it would pay for it with the registers of a wavefront
+    __builtin_amdgcn_sched_barrier(0);
+    encode_clean_row<BITS, ASYM, E, LANES>(d, g, j, raw[j], rowmag[j] << 16);
+  }
+}
+
+template <int BITS, bool ASYM, int E, bool STORE, class Sink>
+__device__ __forceinline__ uint32_t encode_tile_topk_whole(const TensorDesc& d, const TileGeo<E>& g,
+                                                           uint32_t (&raw)[E][4], uint32_t tile, const Sink& sink,
+                                                           uint32_t pos0, uint32_t limit) {
+  uint32_t rowmag[E];
+  const uint32_t total = topk_extract<E, STORE>(d, raw, rowmag, tile, sink, pos0, limit);
+  if constexpr (STORE) {
+    switch (d.lgq) {  // one switch per tile selects straight-line code for the group size
+      case 3: encode_clean_rows<BITS, ASYM, E, 1>(d, g, raw, rowmag); break;
+      case 4: encode_clean_rows<BITS, ASYM, E, 2>(d, g, raw, rowmag); break;
+      case 5: encode_clean_rows<BITS, ASYM, E, 4>(d, g, raw, rowmag); break;
+      case 6: encode_clean_rows<BITS, ASYM, E, 8>(d, g, raw, rowmag); break;
+      case 7: encode_clean_rows<BITS, ASYM, E, 16>(d, g, raw, rowmag); break;
+      case 8: encode_clean_rows<BITS, ASYM, E, 32>(d, g, raw, rowmag); break;
+      default: encode_clean_rows<BITS, ASYM, E, 64>(d, g, raw, rowmag); break;
+    }
+  }
+  return total;
+}
+
+// ------------------------------------------------------------------ one tile, whatever the encoder
+// Encodes the tile (a2 .. a8) and hands its outliers, in ascending index order, to `sink` from
+// position pos0 on (entries at or past `limit` are dropped).  Returns the number of outliers of the
+// tile (uniform).
+// ROWWISE: all groups lie inside a row and statistics and quantisation groups coincide.
+// WHOLE (TOPK): the statistics group is the whole tile and every quantisation group lies inside a row.
+// STORE = false: only the outliers are found (nothing is quantised or stored).
+template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE, bool STORE, class Sink>
+__device__ __forceinline__ uint32_t encode_tile(const TensorDesc& d, const TileGeo<E>& g, uint32_t (&raw)[E][4],
+                                                uint32_t tile, const Sink& sink, uint32_t pos0, uint32_t limit) {
+  static_assert(!WHOLE || (MODE == kModeTopk && !ROWWISE), "WHOLE is a TOPK encoder");
+  if constexpr (ROWWISE) {
+    return encode_tile_rowwise<MODE, BITS, ASYM, E, STORE>(d, g, raw, tile, sink, pos0, limit);
+  } else if constexpr (WHOLE) {
+    return encode_tile_topk_whole<BITS, ASYM, E, STORE>(d, g, raw, tile, sink, pos0, limit);
+  } else {
+    TileOutliers<E> out;
+    encode_tile_general<MODE, BITS, ASYM, E, STORE>(d, g, raw, out);
+    if constexpr (MODE != kModeNone) {
+      if (out.total != 0u) emit_outliers<E>(raw, out, tile, sink, pos0, limit);
+    }
+    return out.total;
+  }
 }
 
 // ------------------------------------------------------------------ one tile with outliers (ABS / STD / TOPK)
@@ -1038,42 +1206,49 @@ __device__ __forceinline__ void emit_outliers(const uint32_t (&raw)[E][4], const
 template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
 __device__ __forceinline__ void compress_tile_outliers(const TensorDesc& d, uint32_t tile, uint32_t epoch) {
   static_assert(MODE != kModeNone, "tiles without outliers have compress_tile_plain");
-  uint32_t raw[E][4];
-  TileOutliers<E> out;
   const bool last = tile + 1u == d.n_tiles;
-  if (WHOLE || !last) {  // only the last tile can be short: the copy for the others knows nothing of it
-    load_tile<E, true>(d, tile, raw);
-    const TileGeo<E> g = tile_geo<E, true>(d, tile);
-    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
-  } else {
-    load_tile<E, false>(d, tile, raw);
-    const TileGeo<E> g = tile_geo<E, false>(d, tile);
-    blank_tail<E>(g, raw);
-    encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE>(d, g, raw, out);
-  }
   const bool lane0 = lane_id() == 0;
+  uint32_t raw[E][4];
   if constexpr (MODE == kModeTopk) {
-    const uint32_t per_tile = d.topk << (d.lgt - d.lgs);           // outliers of a complete, regular tile
+    const uint32_t per_tile = d.topk << (d.lgt - d.lgs);  // outliers of a complete, regular tile
     const uint32_t pos0 = per_tile * tile;
     uint32_t expected = per_tile;
     if (last) expected = d.topk * (uint32_t)((d.numel - (uint64_t)tile * (uint64_t)(E * kRow)) >> d.lgs);
+    const uint32_t end = pos0 + expected;
+    const StreamSink sink{d.idx, d.val};
+    const uint32_t limit = end < d.cap ? end : d.cap;
+    uint32_t total;
+    if (WHOLE || !last) {  // only the last tile can be short: the copy for the others knows nothing of it
+      load_tile<E, true>(d, tile, raw);
+      total = encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE, true>(d, tile_geo<E, true>(d, tile), raw, tile, sink, pos0, limit);
+    } else {
+      load_tile<E, false>(d, tile, raw);
+      const TileGeo<E> g = tile_geo<E, false>(d, tile);
+      blank_tail<E>(g, raw);
+      total = encode_tile<MODE, BITS, ASYM, E, ROWWISE, WHOLE, true>(d, g, raw, tile, sink, pos0, limit);
+    }
     if (lane0) {
       d.tile_ptr[tile] = pos0;
-      d.cnt[tile] = out.total;
-      if (out.total != expected) *d.flag = epoch;
+      d.cnt[tile] = total;
+      if (total != expected) *d.flag = epoch;
       if (last) {
-        const uint32_t n_out = pos0 + expected;
-        d.tile_ptr[d.n_tiles] = n_out;
-        d.status[0] = n_out; d.status[1] = n_out > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
+        d.tile_ptr[d.n_tiles] = end;
+        d.status[0] = end; d.status[1] = end > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
       }
     }
-    const uint32_t end = pos0 + expected;
-    if (out.total != 0u) emit_outliers<E>(raw, out, tile, StreamSink{d.idx, d.val}, pos0, end < d.cap ? end : d.cap);
   } else {
-    if (lane0) d.cnt[tile] = out.total;
-    if (out.total != 0u) {
-      emit_outliers<E>(raw, out, tile, SlotSink{d.slot + (uint64_t)tile * (uint64_t)kSlot}, 0u, (uint32_t)kSlot);
+    const SlotSink sink{d.slot + (uint64_t)tile * (uint64_t)kSlot};
+    uint32_t total;
+    if (!last) {
+      load_tile<E, true>(d, tile, raw);
+      total = encode_tile<MODE, BITS, ASYM, E, ROWWISE, false, true>(d, tile_geo<E, true>(d, tile), raw, tile, sink, 0u, (uint32_t)kSlot);
+    } else {
+      load_tile<E, false>(d, tile, raw);
+      const TileGeo<E> g = tile_geo<E, false>(d, tile);
+      blank_tail<E>(g, raw);
+      total = encode_tile<MODE, BITS, ASYM, E, ROWWISE, false, true>(d, g, raw, tile, sink, 0u, (uint32_t)kSlot);
     }
+    if (lane0) d.cnt[tile] = total;
   }
 }
 
@@ -1143,16 +1318,17 @@ __device__ __forceinline__ void place_sum_block(const TensorDesc& d, uint32_t bl
   if (threadIdx.x == 0) d.block_sum[block] = s;
 }
 
-// select the outliers of one tile again and write them to the stream from position `pos`
+// select the outliers of one tile again and write them to the stream, into the tile's own `count`
+// entries from position `pos` (an attempt of the selection that has to be given up must not reach
+// into a neighbour's entries)
 template <int MODE, int E, bool ROWWISE, bool WHOLE>
-__device__ __forceinline__ void reselect_tile(const TensorDesc& d, uint32_t tile, uint32_t pos) {
+__device__ __forceinline__ void reselect_tile(const TensorDesc& d, uint32_t tile, uint32_t pos, uint32_t count) {
   uint32_t raw[E][4];
-  TileOutliers<E> out;
   load_tile<E, false>(d, tile, raw);
   const TileGeo<E> g = tile_geo<E, false>(d, tile);
   blank_tail<E>(g, raw);
-  encode_tile<MODE, 8, false, E, ROWWISE, WHOLE, false>(d, g, raw, out);
-  if (out.total != 0u) emit_outliers<E>(raw, out, tile, StreamSink{d.idx, d.val}, pos, d.cap);
+  const uint32_t end = pos + count;
+  encode_tile<MODE, 8, false, E, ROWWISE, WHOLE, false>(d, g, raw, tile, StreamSink{d.idx, d.val}, pos, end < d.cap ? end : d.cap);
 }
 
 // `from_sums`: the counts of the blocks are in d.block_sum (else the counts of the tiles are added up)
@@ -1227,7 +1403,7 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
   for (uint32_t j = w; j < n_here; j += (uint32_t)(kPlaceThreads / kWave)) {
     const uint32_t n_tile = sh.excl[j + 1u] - sh.excl[j];
     if (n_tile > (reselect_all ? 0u : (uint32_t)kSlot))
-      reselect_tile<MODE, E, ROWWISE, WHOLE>(d, first + j, base + sh.excl[j]);
+      reselect_tile<MODE, E, ROWWISE, WHOLE>(d, first + j, base + sh.excl[j], n_tile);
   }
 }
 
@@ -1235,16 +1411,14 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
 template <int BITS, bool ASYM, int E, bool ROWWISE>
 __device__ __forceinline__ void compress_tile_plain(const TensorDesc& d, uint32_t tile) {
   uint32_t raw[E][4];
-  TileOutliers<E> out;
   if (tile + 1u < d.n_tiles) {  // only the last tile can be short: the copy for the others knows nothing of it
     load_tile<E, true>(d, tile, raw);
-    const TileGeo<E> g = tile_geo<E, true>(d, tile);
-    encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+    encode_tile<kModeNone, BITS, ASYM, E, ROWWISE, false, true>(d, tile_geo<E, true>(d, tile), raw, tile, NullSink{}, 0u, 0u);
   } else {
     load_tile<E, false>(d, tile, raw);
     const TileGeo<E> g = tile_geo<E, false>(d, tile);
     blank_tail<E>(g, raw);
-    encode_tile<kModeNone, BITS, ASYM, E, ROWWISE>(d, g, raw, out);
+    encode_tile<kModeNone, BITS, ASYM, E, ROWWISE, false, true>(d, g, raw, tile, NullSink{}, 0u, 0u);
   }
   if (tile == 0 && lane_id() == 0) {
     d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;

@@ -6,11 +6,13 @@
 
 namespace adacc {
 
-// binary32 -> bf16, round to nearest even (dequantised values are always finite)
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
+// two binary32 values -> two bf16 in one word (first value in the low half), round to nearest even:
+// the conversion instruction of gfx950
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Decompression always works on pieces of E = 4 rows (2048 elements), whatever the tile of the
@@ -23,14 +25,81 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 // stores come from the same wavefront and the second is issued only after the first is complete,
 // so the outliers are what stays.  (Staging the piece in LDS to patch it there cost a round trip
 // through LDS for every piece of a TOPK tensor, a third of the kernel's time.)
+// One row (512 elements, 8 per lane) of a piece: codes and scale (offset) of the lane's octet.
+template <int BITS>
+struct RowCodes {
+  uint32_t w[BITS == 8 ? 2 : 1];
+  float s, o;
+};
+
+template <int BITS, bool ASYM>
+__device__ __forceinline__ void load_row_codes(const TensorDesc& d, uint64_t e0, RowCodes<BITS>& r) {
+  if constexpr (BITS == 8) {
+    const uint2 w = *reinterpret_cast<const uint2*>(d.codes + e0);
+    r.w[0] = w.x; r.w[1] = w.y;
+  } else {
+    r.w[0] = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
+  }
+  const uint64_t g = e0 >> d.lgq;
+  r.s = d.scales[g];
+  r.o = 0.0f;
+  if constexpr (ASYM) r.o = d.zp[g];
+}
+
+// a9 for one row: unpack, dequantise, store
+template <int BITS, bool ASYM, bool F32>
+__device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e0, const RowCodes<BITS>& r) {
+  int c[kOct];
+  if constexpr (BITS == 8) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      c[e] = (int)(int8_t)((r.w[0] >> (8 * e)) & 0xFFu);
+      c[4 + e] = (int)(int8_t)((r.w[1] >> (8 * e)) & 0xFFu);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) c[e] = ((int)(r.w[0] << (28 - 4 * e))) >> 28;  // sign-extended nibble
+  }
+  float v[kOct];
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)c[e], r.s, r.o) : (float)c[e] * r.s;
+  if constexpr (F32) {
+    float* p = reinterpret_cast<float*>(d.dst) + e0;
+    ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+    ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
+  } else {
+    uint4 w;
+    w.x = bf16_pair(v[0], v[1]);
+    w.y = bf16_pair(v[2], v[3]);
+    w.z = bf16_pair(v[4], v[5]);
+    w.w = bf16_pair(v[6], v[7]);
+    ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
+  }
+}
+
 template <int BITS, bool ASYM, int E, bool F32>
 __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t tile /* piece */, bool has_outliers) {
   static_assert(E == 4, "pieces of 2048 elements");
   const int lane = (int)__lane_id();
   const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
   const uint64_t lane_base = tile_base + (uint64_t)lane * kOct;
+  const bool complete = tile_base + (uint64_t)(E * kRow) <= d.numel;  // uniform; only a tensor's last piece can be short
 
-  // this tile's slice of the outlier stream; its first 64 entries are fetched before anything else
+  // All loads of the piece are issued before anything waits for one of them: a complete piece
+  // (every piece but possibly the last) has no branch between them.
+  RowCodes<BITS> rc[E];
+  if (complete) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) load_row_codes<BITS, ASYM>(d, lane_base + (uint64_t)j * kRow, rc[j]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint64_t e0 = lane_base + (uint64_t)j * kRow;
+      if (e0 < d.numel) load_row_codes<BITS, ASYM>(d, e0, rc[j]);
+    }
+  }
+
+  // this tile's slice of the outlier stream and its first 64 entries
   uint32_t p0 = 0u, p1 = 0u;
   if (has_outliers) {
     p0 = d.tile_ptr[tile >> d.ptr_shift];
@@ -47,49 +116,21 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
   }
 
   // ---- a9: unpack, dequantise, store
+  if (complete) {
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const uint64_t e0 = lane_base + (uint64_t)j * kRow;
-    if (e0 >= d.numel) continue;
-    int c[kOct];
-    if constexpr (BITS == 8) {
-      const uint2 w = *reinterpret_cast<const uint2*>(d.codes + e0);
+    for (int j = 0; j < E; ++j) store_row_values<BITS, ASYM, F32>(d, lane_base + (uint64_t)j * kRow, rc[j]);
+  } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        c[e] = (int)(int8_t)((w.x >> (8 * e)) & 0xFFu);
-        c[4 + e] = (int)(int8_t)((w.y >> (8 * e)) & 0xFFu);
-      }
-    } else {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) c[e] = ((int)(w << (28 - 4 * e))) >> 28;  // sign-extended nibble
-    }
-    const uint64_t g = e0 >> d.lgq;
-    const float s = d.scales[g];
-    float o = 0.0f;
-    if constexpr (ASYM) o = d.zp[g];
-    float v[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)c[e], s, o) : (float)c[e] * s;
-
-    if constexpr (F32) {
-      float* p = reinterpret_cast<float*>(d.dst) + e0;
-      ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
-      ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
-    } else {
-      uint4 w;
-      w.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
-      w.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
-      w.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
-      w.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
-      ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
+    for (int j = 0; j < E; ++j) {
+      const uint64_t e0 = lane_base + (uint64_t)j * kRow;
+      if (e0 < d.numel) store_row_values<BITS, ASYM, F32>(d, e0, rc[j]);
     }
   }
 
   // ---- a10: the outliers overwrite their positions
   if (patch) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the stores above are complete
-    const uint64_t piece_end = tile_base + (uint64_t)(E * kRow) < d.numel ? tile_base + (uint64_t)(E * kRow) : d.numel;
+    const uint64_t piece_end = complete ? tile_base + (uint64_t)(E * kRow) : d.numel;
     for (uint32_t cpos = p0 + (uint32_t)lane; cpos < p1; cpos += kWave) {
       if (cpos >= p0 + (uint32_t)kWave) {  // past the entries fetched at the start
         o_idx = (uint32_t)d.idx[cpos];

@@ -21,7 +21,7 @@ CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
 CompressFn compress_fn_std(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
 CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);
 DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);
-BatchCompressFn compress_batch_fn(bool eight_rows);
+BatchCompressFn compress_batch_fn(int kind);  // kind: kBatch* of adacc_kernels.hpp
 BatchDecompressFn decompress_batch_fn(bool f32);
 PlaceSumFn place_sum_fn();
 PlaceFn place_fn();

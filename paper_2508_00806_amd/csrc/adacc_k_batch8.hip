@@ -1,8 +1,10 @@
-// Instantiation of the batch compression kernel for tiles of 8 rows.
+// Instantiations of the batch compression kernels for tiles of 8 rows.
 #include "adacc_kernels.hpp"
 
 namespace adacc {
 
-BatchCompressFn compress_batch_fn8() { return compress_batch_kernel<true>; }
+BatchCompressFn compress_batch_fn8(int kind) {
+  return kind == kBatchTopk8 ? compress_batch_kernel<kBatchTopk8> : compress_batch_kernel<kBatchAny8>;
+}
 
 }  // namespace adacc
