@@ -6,8 +6,14 @@ A step = one compression and one decompression of the workload (every row of the
 table: load, statistics, outlier mask, ordered compaction, scale, quantise, pack, and on the
 way back unpack, dequantise, outlier patch, store).  Inputs are generated once and are
 resident in HBM before the timed region.  Several buffer sets are rotated and a step
-decompresses a blob that was compressed two steps earlier, so that neither kernel reads
-its input from the 256 MB Infinity Cache.
+decompresses a blob that was compressed in another step, so that neither call reads its input
+from the 256 MB Infinity Cache.
+
+The headline workload is C5, the largest configuration that fits one GPU: the saved tensors of
+32 LLaMA-7B-shaped layers (20 GiB of bf16), compressed by one batched call and restored by one
+batched call.  The other configurations, the layer-specific schemes (outlier channels, dropout
+mask, channel-wise Q/K/V) and the stream ceilings of the part follow as short runs in the same
+JSON line, each with a roofline block of its own.
 
 Prints ONE JSON line.  value = bytes of bf16 activations compressed plus bytes restored,
 per second (GB/s, 1e9), whole job.
@@ -15,13 +21,13 @@ per second (GB/s, 1e9), whole job.
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for p in (ROOT, os.path.join(ROOT, "tests")):
-    if p not in sys.path:
-        sys.path.insert(0, p)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 
@@ -31,36 +37,50 @@ WORKLOAD_TEXT = {
     "c3": "c3: MLP GELU output [8x2048,16384] bf16, int8 group-64, outliers at 8*group_std",
     "c4": "c4: attention softmax [4,32,2048,2048] bf16, asymmetric int8 per row, outliers > 0.05",
     "c5": "c5: LLaMA-7B-shaped layer set, 32 layers x 5 tensors at batch 2 x seq 4096, batched launch",
+    # second readings of two configurations (same tensors, another method)
+    "c2b": "c2 read as top-1 of every 128-group: [16x2048,2048] bf16, int4 group-128, top-1 per 128",
+    "c4b": "c4 with symmetric codes: [4,32,2048,2048] bf16, symmetric int8 per row, outliers > 0.05",
 }
-
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); copied
-# from profiles/hbm_traffic_pmc.txt.
-MEASURED_TRAFFIC_BYTES = {
-    "c2": {"compress": 172618445, "decompress": 173085286},
-    "c3": {"compress": 824715571, "decompress": 826351923},
-    "c4": {"compress": 1622748877, "decompress": 1652543386},
-    "c5": {"compress": 23084046336, "decompress": 23150024499},
+SECOND_READINGS = {
+    "c2b": ("c2", dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=128, thresh=0.0, topk=1)),
+    "c4b": ("c4", dict(bits=8, quant_group=2048, asym=0, outlier_mode="abs", stat_group=0, thresh=0.05, topk=0)),
 }
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough to exceed 1 GiB)")
-    ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads and schemes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-seconds", type=float, default=16.0, help="about this much CPU time for the oracle")
     ap.add_argument("--only-channelwise", action="store_true",
                     help="run only the channel-wise (Q/K/V) quantisation measurement and print its JSON")
     ap.add_argument("--only-mask", action="store_true",
                     help="run only the dropout-mask (byte <-> bit) measurement and print its JSON")
     ap.add_argument("--only-channel", action="store_true",
                     help="run only the outlier-channel (Z-score) measurement and print its JSON")
+    ap.add_argument("--only-streams", action="store_true",
+                    help="run only the read / write / copy / 2R:1W stream probes and print their JSON")
     return ap.parse_args()
+
+
+def measured_traffic():
+    """HBM bytes per call from profiles/hbm_traffic_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+    this file, scaled by the copy kernel).  Lines of the form `traffic <workload> <compress|decompress> <bytes>`."""
+    out = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")) as f:
+            for line in f:
+                m = re.match(r"^traffic\s+(\S+)\s+(compress|decompress)\s+(\d+)\s*$", line)
+                if m:
+                    out[(m.group(1), m.group(2))] = int(m.group(3))
+    except OSError:
+        pass
+    return out
 
 
 class Workload:
@@ -70,18 +90,17 @@ class Workload:
         import torch
         import workloads
         import paper_2508_00806_amd as adacc
-        from helpers import adacc_method
         self.name = name
         self.adacc = adacc
         if name == "c5":
-            specs = [(f"L{layer}.{tname}", hidden, md, x) for layer, tname, x, md in workloads.c5("cuda")
-                     for hidden in [x.shape[-1]]]
+            specs = [(f"L{layer}.{tname}", x.shape[-1], md, x) for layer, tname, x, md in workloads.c5("cuda")]
         else:
-            x = workloads.make(name, "cuda")
-            specs = [(name, x.shape[-1], workloads.METHODS[name], x)]
+            base, md = SECOND_READINGS.get(name, (name, None))
+            x = workloads.make(base, "cuda")
+            specs = [(name, x.shape[-1], md or workloads.METHODS[base], x)]
         self.mds = [s[2] for s in specs]
         self.numels = [s[3].numel() for s in specs]
-        self.methods = [adacc_method(md, workloads.outlier_capacity(md, n, h))
+        self.methods = [adacc.method_from_dict(md, workloads.outlier_capacity(md, n, h))
                         for (_, h, md, _), n in zip(specs, self.numels)]
         self.layouts = [adacc.layout_of(m, n) for m, n in zip(self.methods, self.numels)]
         self.batched = len(specs) > 1
@@ -134,17 +153,21 @@ class Workload:
                    for md, n, k, L in zip(self.mds, self.numels, self.n_out, self.layouts))
 
     def check_status(self):
-        for md, b, L in zip(self.mds, self.blob[0], self.layouts):
-            if md is None:
-                continue
-            st = self.adacc.read_status(b, L)
-            if st[1] or st[2]:
-                raise RuntimeError(f"compression reported overflow/abort: {st}")
+        """Every blob of every buffer set: no overflow of the outlier stream, and the same count in all sets."""
+        for s in range(self.sets):
+            for i, (md, b, L) in enumerate(zip(self.mds, self.blob[s], self.layouts)):
+                if md is None:
+                    continue
+                st = self.adacc.read_status(b, L)
+                if st[1] or st[2]:
+                    raise RuntimeError(f"{self.name}: set {s} tensor {i}: compression reported overflow: {st}")
+                if s and st[0] != self.adacc.read_status(self.blob[0][i], L)[0]:
+                    raise RuntimeError(f"{self.name}: set {s} tensor {i}: outlier count differs between buffer sets")
 
 
 def time_steps(w, steps, warmup):
-    """Returns (ms per step, ms per compress launch, ms per decompress launch), all measured with
-    events on the stream the kernels run on, inside the same timed region."""
+    """Returns (ms per step, ms per compress call, ms per decompress call, wall ms per step).  Events are
+    recorded on the stream the library launches on (torch's current stream), inside the timed region."""
     import torch
     half = w.sets // 2
     for s in range(w.sets):       # every blob exists before a decompress reads it
@@ -169,70 +192,175 @@ def time_steps(w, steps, warmup):
     return total_ms / steps, c_ms, d_ms, wall_ms / steps
 
 
-def copy_ceiling():
-    """GB/s (read + written bytes) of the library's copy kernel on 1 GiB, with the streaming accesses
-    the tensor streams use when ADACC_COPY_STREAM=1 is set by the caller (see main)."""
+def direction_block(alg, ms, act_bytes, traffic):
+    gbps = alg / (ms * 1e-3) / 1e9
+    return {"ms": ms, "activation_GBps": act_bytes / (ms * 1e-3) / 1e9, "hbm_GBps": gbps,
+            "frac_of_peak": gbps / HBM_PEAK_GBPS, "algorithmic_bytes": alg, "traffic": traffic}
+
+
+def roofline_block(res):
+    """The slower of the two calls of a workload against the HBM peak."""
+    dom = "compress" if res["compress"]["ms"] >= res["decompress"]["ms"] else "decompress"
+    r = res[dom]
+    return {"bound": "hbm", "kernel": f"{res['workload']} {dom} call", "achieved": r["hbm_GBps"], "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": r["frac_of_peak"], "traffic": r["traffic"],
+            "algorithmic_bytes_per_launch": r["algorithmic_bytes"], "ms_per_launch": r["ms"]}
+
+
+def run_workload(name, steps, warmup, sets, cold=True):
+    import torch
+    w = Workload(name, sets if cold else 1)
+    if not cold:
+        w.sets = 1
+    ms, c_ms, d_ms, wall_ms = time_steps(w, steps, warmup)
+    w.check_status()
+    alg = w.algorithmic_bytes()
+    traffic = measured_traffic()
+    res = {
+        "workload": name,
+        "description": WORKLOAD_TEXT[name],
+        "ms_per_step": ms,
+        "wall_ms_per_step": wall_ms,
+        "activation_GBps": 2.0 * w.act_bytes / (ms * 1e-3) / 1e9,
+        "compress": direction_block(alg, c_ms, w.act_bytes, traffic.get((name, "compress"))),
+        "decompress": direction_block(alg, d_ms, w.act_bytes, traffic.get((name, "decompress"))),
+        "roundtrip_hbm_frac_of_peak": 2.0 * alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "activation_bytes": w.act_bytes,
+        "n_outliers": int(sum(w.n_out)),
+        "tensors": len(w.methods),
+        "buffer_sets": w.sets,
+        "cache_state": "cold: rotating buffer sets, inputs come from HBM" if cold else "warm: one buffer set, 8 MB stays in the caches",
+    }
+    res["roofline"] = roofline_block(res)
+    del w
+    torch.cuda.empty_cache()
+    return res
+
+
+def stream_ceilings():
+    """What a kernel that only moves bytes reaches on this part, in the access shape of the library's
+    tensor kernels, for four mixes of reads and writes at 1 GiB per operand (GB/s of bytes moved)."""
     import torch
     import paper_2508_00806_amd as adacc
     n = 1 << 30
-    a = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
-    b = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(2)]
-    for i in range(3):
-        adacc.hbm_copy(b[i % 2], a)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 20
-    e0.record()
-    for i in range(reps):
-        adacc.hbm_copy(b[i % 2], a)
-    e1.record()
-    torch.cuda.synchronize()
-    return 2.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    a = [torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(2)]
+    b = [torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(2)]
+    d = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    out = {}
+    for key, mix, moved in (("read", adacc.STREAM_READ, 1), ("write", adacc.STREAM_WRITE, 1),
+                            ("copy_1r1w", adacc.STREAM_COPY, 2), ("2r1w", adacc.STREAM_READ2_WRITE, 3)):
+        for i in range(3):
+            adacc.hbm_stream(mix, d[i % 2], a[i % 2], b[i % 2], n)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record()
+        for i in range(reps):
+            adacc.hbm_stream(mix, d[i % 2], a[i % 2], b[i % 2], n)
+        e1.record()
+        torch.cuda.synchronize()
+        gbps = moved * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        out[key] = {"GBps": gbps, "frac_of_peak": gbps / HBM_PEAK_GBPS}
+    del a, b, d
+    torch.cuda.empty_cache()
+    return out
+
+
+def bits_of(t):
+    """bf16 torch tensor (any device) -> numpy uint16 bit patterns, for the oracle."""
+    import numpy as np
+    import torch
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
+
+
+def host_description():
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    usable = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    return {"cpu_model": model, "os_cpu_count": os.cpu_count(), "usable_cores": usable}
 
 
 def cpu_baseline(name, seconds):
-    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    """The oracle as it stands on a bounded sample of the same workload: on one thread, and on all host
+    cores (row blocks of the sample handed to a pool of threads; the oracle's C code runs outside the
+    interpreter lock, and every group lies inside a row, so the blocks are independent)."""
+    from concurrent.futures import ThreadPoolExecutor
+    import numpy as np
     import workloads
     import oracle
-    from helpers import bits_of, oracle_method
+    host = host_description()
+    cores = max(1, min(int(os.environ.get("OMP_NUM_THREADS", host["usable_cores"])), host["usable_cores"]))
     if name == "c5":
-        tname, hidden, md = workloads.C5_LAYER[0]
-        x = workloads.c5_tensor(tname, "cpu", rows=2048)
-        sample = f"first 2048 rows of tensor {tname} of layer 0"
+        rows = 2048
+        parts = [(workloads.c5_tensor(t, "cpu", rows=rows), md) for t, _h, md in workloads.C5_LAYER if md is not None]
+        sample = f"first {rows} rows of each of the 4 compressed tensors of layer 0"
     else:
-        rows = {"c1": 4096, "c2": 4096, "c3": 512, "c4": 4096}[name]
-        x = workloads.make(name, "cpu", rows=rows)
-        md = workloads.METHODS[name]
+        base, md2 = SECOND_READINGS.get(name, (name, None))
+        rows = {"c1": 4096, "c2": 4096, "c3": 512, "c4": 4096}[base]
+        x = workloads.make(base, "cpu", rows=rows)
+        parts = [(x, md2 or workloads.METHODS[base])]
         sample = f"{rows} rows ({x.numel()} elements) of the workload, same generator"
-    b = bits_of(x)
-    om = oracle_method(md)
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        c = oracle.compress(om, b)
+    work = []  # (method, bits of a block of whole rows)
+    total = 0
+    for x, md in parts:
+        b = bits_of(x).reshape(x.shape[0], -1)
+        total += b.size
+        om = oracle.method_from_dict(md)
+        step = max(1, b.shape[0] // (4 * cores))
+        step += (-step) % max(1, -(-md["stat_group"] // b.shape[1]))  # whole statistics groups per block
+        for r0 in range(0, b.shape[0], step):
+            work.append((om, np.ascontiguousarray(b[r0:r0 + step]).reshape(-1)))
+
+    def one(item):
+        c = oracle.compress(item[0], item[1])
         oracle.decompress(c)
-        reps += 1
-        el = time.perf_counter() - t0
-        if el >= seconds or reps >= 200:
-            break
-    gbps = 4.0 * b.size * reps / el / 1e9
-    return {"value": gbps, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{sample}; compress+decompress repeated {reps}x in {el:.1f} s"}
+
+    def timed(threads):
+        reps, t0 = 0, time.perf_counter()
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            while True:
+                list(pool.map(one, work))
+                reps += 1
+                el = time.perf_counter() - t0
+                if el >= seconds / 2 or reps >= 50:
+                    break
+        return 4.0 * total * reps / el / 1e9, reps, el
+
+    v1, r1, e1 = timed(1)
+    vn, rn, en = timed(cores)
+    return {"value": vn, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{sample}; compress+decompress of the sample {rn}x in {en:.1f} s on {cores} threads",
+            "single_thread": {"value": v1, "unit": "GB/s", "cores": 1,
+                              "sample": f"the same sample {r1}x in {e1:.1f} s on one thread"},
+            "host": host}
 
 
-def run_channel_mode(steps=50, warmup=5, cpu_rows=2048):
-    """The paper's own selection rule (Section 3.2, Eq. 1) on the C2-shaped activation: outlier
-    channels by Z-score > 3 kept whole, the rest int4 in groups of 128.  Compression reads the
-    tensor twice (channel sums, then extraction + quantisation): algorithmic bytes 4N + outputs;
-    decompression 2N + inputs.  Three rotating buffer sets, as for the main workload."""
+def two_pass_block(alg, ms, n, kernels):
+    gbps = alg / (ms * 1e-3) / 1e9
+    return {"ms": ms, "kernels": kernels, "algorithmic_bytes": alg, "hbm_GBps": gbps,
+            "frac_of_peak": gbps / HBM_PEAK_GBPS, "activation_GBps": 2.0 * n / (ms * 1e-3) / 1e9}
+
+
+def run_channel_mode(steps=30, warmup=4, cpu_rows=1024):
+    """The paper's own selection rule (Section 3.2, Eq. 1) on a [16384,16384] activation (512 MiB, so that
+    the second read of the tensor comes from HBM, not from the Infinity Cache): outlier channels by
+    Z-score > 3 kept whole, the rest int4 in groups of 128.  Compression reads the tensor twice (channel
+    sums, then extraction + quantisation): algorithmic bytes 4N + outputs; decompression 2N + inputs."""
     import torch
     import workloads
     import oracle
     import paper_2508_00806_amd as adacc
-    from helpers import bits_of
-    x = workloads.make("c2", "cuda")
-    tokens, hidden = x.shape
+    tokens, hidden = 16384, 16384
+    x = workloads.c2("cuda", rows=tokens, hidden=hidden)
     n = tokens * hidden
-    m = adacc.ChannelMethod(bits=4, quant_group=128, z_thresh=3.0, max_channels=64)
-    sets = 4
+    m = adacc.ChannelMethod(bits=4, quant_group=128, z_thresh=3.0, max_channels=256)
+    sets = 3
     xs = [x if i == 0 else x.clone() for i in range(sets)]
     L = adacc.channel_layout_of(m, tokens, hidden)
     blobs = [adacc.alloc_channel_blob(m, tokens, hidden)[0] for _ in range(sets)]
@@ -242,14 +370,14 @@ def run_channel_mode(steps=50, warmup=5, cpu_rows=2048):
         adacc.channel_compress(m, xs[i], tokens, hidden, blobs[i], ws)
     for i in range(warmup):
         adacc.channel_compress(m, xs[i % sets], tokens, hidden, blobs[i % sets], ws)
-        adacc.channel_decompress(m, blobs[(i + 2) % sets], tokens, hidden, dsts[(i + 2) % sets])
+        adacc.channel_decompress(m, blobs[(i + 1) % sets], tokens, hidden, dsts[(i + 1) % sets])
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     torch.cuda.synchronize()
     for i in range(steps):
         ev[i][0].record()
         adacc.channel_compress(m, xs[i % sets], tokens, hidden, blobs[i % sets], ws)
         ev[i][1].record()
-        adacc.channel_decompress(m, blobs[(i + 2) % sets], tokens, hidden, dsts[(i + 2) % sets])
+        adacc.channel_decompress(m, blobs[(i + 1) % sets], tokens, hidden, dsts[(i + 1) % sets])
         ev[i][2].record()
     torch.cuda.synchronize()
     c_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
@@ -263,38 +391,37 @@ def run_channel_mode(steps=50, warmup=5, cpu_rows=2048):
     xb = bits_of(x[:cpu_rows].cpu())
     om = oracle.Method(bits=4, quant_group=128)
     t0 = time.perf_counter()
-    oc = oracle.channel_compress(om, xb, cpu_rows, hidden, 3.0, cap=64)
+    oc = oracle.channel_compress(om, xb, cpu_rows, hidden, 3.0, cap=256)
     oracle.channel_decompress(oc)
     el = time.perf_counter() - t0
-    del xs, blobs, dsts
+    del xs, blobs, dsts, x
     torch.cuda.empty_cache()
-    return {
-        "workload": f"outlier channels by Z-score>3 on the c2 tensor [{tokens},{hidden}] bf16, int4 group-128",
+    res = {
+        "workload": f"outlier channels by Z-score>3 on a [{tokens},{hidden}] bf16 activation (0.5 % heavy-tailed channels), int4 group-128",
         "n_outlier_channels": st[0],
-        "compress": {"ms": c_ms, "kernels": 4, "algorithmic_bytes": alg_c, "hbm_GBps": alg_c / (c_ms * 1e-3) / 1e9,
-                     "frac_of_peak": alg_c / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "activation_GBps": 2.0 * n / (c_ms * 1e-3) / 1e9},
-        "decompress": {"ms": d_ms, "kernels": 1, "algorithmic_bytes": alg_d, "hbm_GBps": alg_d / (d_ms * 1e-3) / 1e9,
-                       "frac_of_peak": alg_d / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                       "activation_GBps": 2.0 * n / (d_ms * 1e-3) / 1e9},
+        "compress": two_pass_block(alg_c, c_ms, n, 4),
+        "decompress": two_pass_block(alg_d, d_ms, n, 1),
         "cpu_oracle": {"value": 4.0 * cpu_rows * hidden / el / 1e9, "unit": "GB/s", "cores": 1,
                        "sample": f"first {cpu_rows} rows, compress+decompress once in {el:.2f} s"},
     }
+    res["roofline"] = {"bound": "hbm", "kernel": "channel compress call (4 kernels)", "achieved": res["compress"]["hbm_GBps"],
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["compress"]["frac_of_peak"], "traffic": None}
+    return res
 
 
-def run_channelwise(steps=50, warmup=5, cpu_rows=2048):
-    """Channel-wise symmetric int4 quantisation (Section 3.2, the Query / Key / Value scheme) of the
-    C2-shaped tensor.  Compression reads the tensor twice (channel maxima, then quantisation):
-    algorithmic bytes 4N + N/2 + 4*hidden; decompression 2N + N/2 + 4*hidden."""
+def run_channelwise(steps=30, warmup=4, cpu_rows=1024):
+    """Channel-wise symmetric int4 quantisation (Section 3.2, the Query / Key / Value scheme) of a
+    [16384,16384] tensor (512 MiB: the second read comes from HBM).  Compression reads the tensor twice
+    (channel maxima, then quantisation): algorithmic bytes 4N + N/2 + 4*hidden; decompression 2N + N/2 +
+    4*hidden."""
     import torch
     import workloads
     import oracle
     import paper_2508_00806_amd as adacc
-    from helpers import bits_of
-    x = workloads.make("c2", "cuda")
-    tokens, hidden = x.shape
+    tokens, hidden = 16384, 16384
+    x = workloads.c2("cuda", rows=tokens, hidden=hidden)
     n = tokens * hidden
-    sets = 4
+    sets = 3
     xs = [x if i == 0 else x.clone() for i in range(sets)]
     bufs = [adacc.alloc_channelwise(4, tokens, hidden) for _ in range(sets)]
     dsts = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(sets)]
@@ -314,7 +441,7 @@ def run_channelwise(steps=50, warmup=5, cpu_rows=2048):
         ev[i][0].record()
         comp(i)
         ev[i][1].record()
-        dec(i + 2)
+        dec(i + 1)
         ev[i][2].record()
     torch.cuda.synchronize()
     c_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
@@ -326,26 +453,24 @@ def run_channelwise(steps=50, warmup=5, cpu_rows=2048):
     _, packed, scale = oracle.channelwise_compress(4, xb, cpu_rows, hidden)
     oracle.channelwise_decompress(4, packed, scale, cpu_rows, hidden)
     el = time.perf_counter() - t0
-    del xs, bufs, dsts
+    del xs, bufs, dsts, x
     torch.cuda.empty_cache()
-    return {
-        "workload": f"channel-wise symmetric int4 (Q/K/V scheme) on the c2 tensor [{tokens},{hidden}] bf16",
-        "compress": {"ms": c_ms, "kernels": 3, "algorithmic_bytes": alg_c, "hbm_GBps": alg_c / (c_ms * 1e-3) / 1e9,
-                     "frac_of_peak": alg_c / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "activation_GBps": 2.0 * n / (c_ms * 1e-3) / 1e9},
-        "decompress": {"ms": d_ms, "kernels": 1, "algorithmic_bytes": alg_d, "hbm_GBps": alg_d / (d_ms * 1e-3) / 1e9,
-                       "frac_of_peak": alg_d / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                       "activation_GBps": 2.0 * n / (d_ms * 1e-3) / 1e9},
+    res = {
+        "workload": f"channel-wise symmetric int4 (Q/K/V scheme) on a [{tokens},{hidden}] bf16 tensor",
+        "compress": two_pass_block(alg_c, c_ms, n, 3),
+        "decompress": two_pass_block(alg_d, d_ms, n, 1),
         "cpu_oracle": {"value": 4.0 * cpu_rows * hidden / el / 1e9, "unit": "GB/s", "cores": 1,
                        "sample": f"first {cpu_rows} rows, compress+decompress once in {el:.2f} s"},
     }
+    res["roofline"] = {"bound": "hbm", "kernel": "channel-wise compress call (3 kernels)", "achieved": res["compress"]["hbm_GBps"],
+                       "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["compress"]["frac_of_peak"], "traffic": None}
+    return res
 
 
 def run_mask(steps=30, warmup=3):
     """Dropout mask of the attention layer of C4 ([4,32,2048,2048] bytes, keep probability 0.9):
     byte format -> bit format and back (Section 3.2).  Algorithmic bytes per direction: n + n/8."""
     import torch
-    import numpy as np
     import oracle
     import paper_2508_00806_amd as adacc
     n = 4 * 32 * 2048 * 2048
@@ -377,7 +502,7 @@ def run_mask(steps=30, warmup=3):
     el = time.perf_counter() - t0
     del masks, bits, backs
     torch.cuda.empty_cache()
-    return {
+    res = {
         "workload": "dropout mask [4,32,2048,2048] bytes <-> bits, keep probability 0.9",
         "pack": {"ms": p_ms, "algorithmic_bytes": alg, "hbm_GBps": alg / (p_ms * 1e-3) / 1e9,
                  "frac_of_peak": alg / (p_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
@@ -386,32 +511,9 @@ def run_mask(steps=30, warmup=3):
         "cpu_oracle": {"value": 2.0 * sample.size / el / 1e9, "unit": "GB/s of mask bytes", "cores": 1,
                        "sample": f"first {sample.size} elements, pack+unpack once in {el:.2f} s"},
     }
-
-
-def run_workload(name, steps, warmup, sets):
-    import torch
-    w = Workload(name, sets)
-    ms, c_ms, d_ms, wall_ms = time_steps(w, steps, warmup)
-    w.check_status()
-    alg = w.algorithmic_bytes()
-    res = {
-        "workload": name,
-        "ms_per_step": ms,
-        "wall_ms_per_step": wall_ms,
-        "activation_GBps": 2.0 * w.act_bytes / (ms * 1e-3) / 1e9,
-        "compress": {"ms": c_ms, "activation_GBps": w.act_bytes / (c_ms * 1e-3) / 1e9,
-                     "hbm_GBps": alg / (c_ms * 1e-3) / 1e9, "frac_of_peak": alg / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
-        "decompress": {"ms": d_ms, "activation_GBps": w.act_bytes / (d_ms * 1e-3) / 1e9,
-                       "hbm_GBps": alg / (d_ms * 1e-3) / 1e9, "frac_of_peak": alg / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS},
-        "roundtrip_hbm_frac_of_peak": 2.0 * alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "algorithmic_bytes_per_direction": alg,
-        "activation_bytes": w.act_bytes,
-        "n_outliers": int(sum(w.n_out)),
-        "tensors": len(w.methods),
-        "buffer_sets": w.sets,
-    }
-    del w
-    torch.cuda.empty_cache()
+    slow = "pack" if p_ms >= u_ms else "unpack"
+    res["roofline"] = {"bound": "hbm", "kernel": f"mask_{slow}_kernel", "achieved": res[slow]["hbm_GBps"], "peak": HBM_PEAK_GBPS,
+                       "unit": "GB/s", "frac": res[slow]["frac_of_peak"], "traffic": None}
     return res
 
 
@@ -438,37 +540,29 @@ def main():
     if a.only_channel:
         print(json.dumps({"channel_zscore": run_channel_mode()}))
         return
+    if a.only_streams:
+        print(json.dumps({"stream_ceilings": stream_ceilings()}))
+        return
     main_res = run_workload(a.workload, a.steps, a.warmup, a.sets)
-    ceiling = copy_ceiling()
-    os.environ["ADACC_COPY_STREAM"] = "1"
-    ceiling_stream = copy_ceiling()
-    os.environ.pop("ADACC_COPY_STREAM")
-    extras = []
+    extras, channel, mask, channelwise, ceilings = [], None, None, None, None
     if not a.no_extras:
+        ceilings = stream_ceilings()
         for name in sorted(WORKLOAD_TEXT):
             if name == a.workload:
                 continue
             k = 10 if name == "c5" else 50
             extras.append(run_workload(name, k, 5, a.sets))
-    channel = None if a.no_extras else run_channel_mode()
-    mask = None if a.no_extras else run_mask()
-    channelwise = None if a.no_extras else run_channelwise()
+            if name == "c1":  # 8 MB: also with everything in the caches
+                warm = run_workload(name, k, 5, 1, cold=False)
+                warm["workload"] = "c1 (warm)"
+                extras.append(warm)
+        channel = run_channel_mode()
+        mask = run_mask()
+        channelwise = run_channelwise()
     cpu = None if a.no_cpu else cpu_baseline(a.workload, a.cpu_seconds)
 
-    dom = "compress" if main_res["compress"]["ms"] >= main_res["decompress"]["ms"] else "decompress"
-    roof = {
-        "bound": "hbm",
-        "kernel": dom,
-        "achieved": main_res[dom]["hbm_GBps"],
-        "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s",
-        "frac": main_res[dom]["frac_of_peak"],
-        "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload, {}).get(dom),
-        "algorithmic_bytes_per_launch": main_res["algorithmic_bytes_per_direction"],
-        "ms_per_launch": main_res[dom]["ms"],
-        "copy_kernel_GBps": ceiling,
-        "copy_kernel_streaming_GBps": ceiling_stream,
-    }
+    roof = dict(main_res["roofline"])
+    roof["stream_ceilings"] = ceilings
     out = {
         "metric": "compress+decompress GB/s of bf16 activations; fraction of MI355X HBM peak",
         "value": main_res["activation_GBps"],
@@ -483,7 +577,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[a.workload], "buffer_sets": main_res["buffer_sets"],
-                   "tensors": main_res["tensors"], "n_outliers": main_res["n_outliers"]},
+                   "tensors": main_res["tensors"], "n_outliers": main_res["n_outliers"],
+                   "storage": "bf16 in and out; int8 / int4 codes, binary32 scales, (int32, bf16) outliers in between"},
         "hbm_frac_of_peak_roundtrip": main_res["roundtrip_hbm_frac_of_peak"],
         "compress": main_res["compress"],
         "decompress": main_res["decompress"],

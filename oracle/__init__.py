@@ -38,6 +38,16 @@ class Method:
                         self.stat_group, float(self.thresh), self.topk)
 
 
+MODE_BY_NAME = {"none": OUT_NONE, "abs": OUT_ABS, "std": OUT_STD, "topk": OUT_TOPK}
+
+
+def method_from_dict(md, scale_rule: int = RULE_PAPER) -> Method:
+    """A method written as a plain dictionary (outlier_mode by name) as the oracle's descriptor."""
+    return Method(bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"], scale_rule=scale_rule,
+                  outlier_mode=MODE_BY_NAME[md["outlier_mode"]], stat_group=md["stat_group"],
+                  thresh=md["thresh"], topk=md["topk"])
+
+
 _lib = None
 
 

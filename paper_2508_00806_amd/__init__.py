@@ -97,6 +97,18 @@ class Method:
 
 NOOP = Method(kind=KIND_NOOP, bits=0, quant_group=0)
 
+OUTLIER_MODE_BY_NAME = {"none": OUTLIER_NONE, "abs": OUTLIER_ABS, "std": OUTLIER_STD, "topk": OUTLIER_TOPK}
+
+
+def method_from_dict(md, max_outliers: int, scale_rule: int = SCALE_PAPER) -> Method:
+    """A method written as a plain dictionary (keys bits, quant_group, asym, outlier_mode by name,
+    stat_group, thresh, topk) as the library's descriptor; None = retain the tensor as it is."""
+    if md is None:
+        return NOOP
+    return Method(kind=KIND_QUANT, bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"],
+                  scale_rule=scale_rule, outlier_mode=OUTLIER_MODE_BY_NAME[md["outlier_mode"]],
+                  stat_group=md["stat_group"], thresh=md["thresh"], topk=md["topk"], max_outliers=max_outliers)
+
 
 class AdaccError(RuntimeError):
     def __init__(self, code, where):

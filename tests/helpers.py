@@ -10,17 +10,11 @@ MODE_ID = {"none": 0, "abs": 1, "std": 2, "topk": 3}
 
 
 def oracle_method(md, rule=0):
-    return oracle.Method(bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"], scale_rule=rule,
-                         outlier_mode=MODE_ID[md["outlier_mode"]], stat_group=md["stat_group"],
-                         thresh=md["thresh"], topk=md["topk"])
+    return oracle.method_from_dict(md, rule)
 
 
 def adacc_method(md, cap, rule=0):
-    if md is None:
-        return adacc.NOOP
-    return adacc.Method(kind=adacc.KIND_QUANT, bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"],
-                        scale_rule=rule, outlier_mode=MODE_ID[md["outlier_mode"]], stat_group=md["stat_group"],
-                        thresh=md["thresh"], topk=md["topk"], max_outliers=cap)
+    return adacc.method_from_dict(md, cap, rule)
 
 
 def bits_of(t):

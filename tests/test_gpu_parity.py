@@ -337,55 +337,72 @@ def test_batch_matches_single_calls_and_oracle():
 
 
 # ------------------------------------------------------------------ full-size configurations, sampled
-def sampled_full_size(name, x_dev, md, hidden, n_samples=24):
-    """Compress the full tensor on the GPU in the launch configuration the bench uses; run the
-    oracle on sampled tiles (every group lies inside one tile, so a tile can be checked alone)."""
-    numel = x_dev.numel()
-    cap = workloads.outlier_capacity(md, numel, hidden)
-    m = adacc_method(md, cap)
-    blob, L, ws = gpu_compress(x_dev.view(-1), m)
-    torch.cuda.synchronize()
+def check_compressed_tiles(name, xf, md, m, blob, L, tiles):
+    """The blob of a whole tensor against the oracle on the given tiles (every group lies inside one tile,
+    so a tile can be checked alone), plus what holds for the whole outlier stream.  Returns the status."""
+    numel = xf.numel()
     st = adacc.read_status(blob, L)
-    assert st[1] == 0 and st[2] == 0, st
+    assert st[1] == 0 and st[2] == 0, (name, st)
     sec = adacc.blob_sections(blob, L, m, numel)
     te = int(L.tile_elems)
     has_out = md["outlier_mode"] != "none"
     if has_out:
         tp = sec["tile_ptr"].cpu().numpy().view(np.uint32).astype(np.int64)
-        assert tp[0] == 0 and np.all(np.diff(tp) >= 0) and tp[-1] == st[0]
+        assert tp[0] == 0 and np.all(np.diff(tp) >= 0) and tp[-1] == st[0], name
         idx = sec["idx"][:st[0]]
-        assert bool((idx[1:] > idx[:-1]).all()), "outlier stream is not strictly ascending"
-    g = np.random.default_rng(2024)
-    tiles = sorted(set([0, L.n_tiles - 1] + g.integers(0, L.n_tiles, n_samples).tolist()))
+        assert bool((idx[1:] > idx[:-1]).all()), f"{name}: outlier stream is not strictly ascending"
     om = oracle_method(md)
-    xf = x_dev.view(-1)
+    cb, gq = md["bits"], md["quant_group"]
     for t in tiles:
         lo, hi = t * te, min(numel, (t + 1) * te)
         oc = oracle.compress(om, bits_of(xf[lo:hi]))
-        cb = md["bits"]
         got_codes = sec["codes"][lo * cb // 8: hi * cb // 8].cpu().numpy()
         assert np.array_equal(got_codes, oc.packed), (name, t)
-        gq = md["quant_group"]
         assert np.array_equal(sec["scales"][lo // gq: hi // gq].cpu().numpy().view(np.uint32), oc.scale.view(np.uint32)), (name, t)
         if md["asym"]:
             assert np.array_equal(sec["zp"][lo // gq: hi // gq].cpu().numpy().view(np.uint32), oc.zp.view(np.uint32)), (name, t)
         if has_out:
             p0, p1 = int(tp[t]), int(tp[t + 1])
             assert p1 - p0 == oc.n_out, (name, t, p1 - p0, oc.n_out)
-            assert np.array_equal(sec["idx"][p0:p1].cpu().numpy().astype(np.int64), oc.out_idx.astype(np.int64) + lo)
-            assert np.array_equal(sec["val"][p0:p1].cpu().numpy().view(np.uint16), oc.out_val)
-    # round trip: bf16 output of sampled tiles equals the oracle's; outliers exact everywhere
+            assert np.array_equal(sec["idx"][p0:p1].cpu().numpy().astype(np.int64), oc.out_idx.astype(np.int64) + lo), (name, t)
+            assert np.array_equal(sec["val"][p0:p1].cpu().numpy().view(np.uint16), oc.out_val), (name, t)
+    return st
+
+
+def check_restored_tiles(name, xf, md, m, blob, L, dst, tiles):
+    """The bf16 output on the given tiles equals the oracle's reconstruction; every outlier of the whole
+    tensor comes back exactly."""
+    numel = xf.numel()
+    te = int(L.tile_elems)
+    om = oracle_method(md)
+    for t in tiles:
+        lo, hi = t * te, min(numel, (t + 1) * te)
+        _, obf = oracle.decompress(oracle.compress(om, bits_of(xf[lo:hi])))
+        assert np.array_equal(bits_of(dst[lo:hi]), obf), (name, t)
+    n_out = adacc.read_status(blob, L)[0]
+    if md["outlier_mode"] != "none" and n_out > 0:
+        ii = adacc.blob_sections(blob, L, m, numel)["idx"][:n_out].long()
+        assert torch.equal(dst[ii].view(torch.int16), xf[ii].view(torch.int16)), name
+
+
+def sampled_tiles(g, n_tiles, n_samples):
+    return sorted(set([0, n_tiles - 1] + g.integers(0, n_tiles, n_samples).tolist()))
+
+
+def sampled_full_size(name, x_dev, md, hidden, n_samples=24):
+    """Compress the full tensor on the GPU in the launch configuration the bench uses; run the
+    oracle on sampled tiles."""
+    numel = x_dev.numel()
+    m = adacc_method(md, workloads.outlier_capacity(md, numel, hidden))
+    xf = x_dev.view(-1)
+    blob, L, ws = gpu_compress(xf, m)
+    torch.cuda.synchronize()
+    tiles = sampled_tiles(np.random.default_rng(2024), L.n_tiles, n_samples)
+    st = check_compressed_tiles(name, xf, md, m, blob, L, tiles)
     dst = torch.empty(numel, dtype=torch.bfloat16, device="cuda")
     adacc.decompress(m, blob, dst)
     torch.cuda.synchronize()
-    for t in tiles:
-        lo, hi = t * te, min(numel, (t + 1) * te)
-        oc = oracle.compress(om, bits_of(xf[lo:hi]))
-        _, obf = oracle.decompress(oc)
-        assert np.array_equal(bits_of(dst[lo:hi]), obf), (name, t)
-    if has_out and st[0] > 0:
-        ii = sec["idx"][:st[0]].long()
-        assert torch.equal(dst[ii].view(torch.int16), xf[ii].view(torch.int16))
+    check_restored_tiles(name, xf, md, m, blob, L, dst, tiles)
     return st
 
 
@@ -401,37 +418,64 @@ def test_full_size_sampled(name):
     torch.cuda.empty_cache()
 
 
-def test_full_size_c5_one_layer_batch_sampled():
-    """One LLaMA-7B-shaped layer at its real shape through the batch entry point."""
-    methods, srcs, blobs, layouts, mds = [], [], [], [], []
-    for t, (tname, hidden, md) in enumerate(workloads.C5_LAYER):
-        x = workloads.c5_tensor(tname, "cuda", seed=5000 + t).view(-1)
+def c5_batch(layers):
+    """The saved tensors of `layers` LLaMA-7B-shaped layers on the GPU with their methods, blobs and layouts,
+    seeded as the bench seeds them."""
+    names, mds, methods, srcs, blobs, layouts = [], [], [], [], [], []
+    for layer, tname, x, md in workloads.c5("cuda", layers=layers):
         n = x.numel()
-        m = adacc_method(md, workloads.outlier_capacity(md, n, hidden))
+        m = adacc_method(md, workloads.outlier_capacity(md, n, x.shape[-1]))
         blob, L = (None, None) if md is None else adacc.alloc_blob(m, n)
-        methods.append(m); srcs.append(x); blobs.append(blob); layouts.append(L); mds.append(md)
-    ws = adacc.alloc_workspace(adacc.batch_workspace_bytes(methods, [s.numel() for s in srcs]))
-    log("[parity] c5 layer batch compress")
-    adacc.compress_batch(methods, srcs, blobs, ws)
+        names.append(f"L{layer}.{tname}"); mds.append(md); methods.append(m); srcs.append(x.view(-1))
+        blobs.append(blob); layouts.append(L)
+    return names, mds, methods, srcs, blobs, layouts
+
+
+def run_c5_batch(layers, n_samples):
+    """Batched compression and decompression in the configuration the bench times (argument arrays
+    prepared once, one workspace for the whole set); the oracle on sampled tiles of every tensor; then
+    every tensor again through the single-tensor decompression, last tensor first, as a backward pass
+    would ask for them."""
+    names, mds, methods, srcs, blobs, layouts = c5_batch(layers)
+    numels = [x.numel() for x in srcs]
+    ws = adacc.alloc_workspace(adacc.batch_workspace_bytes(methods, numels))
+    dsts = [None if md is None else torch.empty(n, dtype=torch.bfloat16, device="cuda") for md, n in zip(mds, numels)]
+    cargs = adacc.prepare_compress_batch(methods, srcs, blobs)
+    dargs = adacc.prepare_decompress_batch(methods, blobs, dsts)
+    log(f"[parity] c5 x{layers} layers: batch compress of {len(srcs)} tensors")
+    adacc.compress_batch(methods, srcs, blobs, ws, prepared=cargs)
+    torch.cuda.synchronize()
+    log(f"[parity] c5 x{layers} layers: batch decompress")
+    adacc.decompress_batch(methods, blobs, dsts, ws, prepared=dargs)
     torch.cuda.synchronize()
     g = np.random.default_rng(7)
-    for x, m, blob, L, md in zip(srcs, methods, blobs, layouts, mds):
+    total_out = 0
+    for name, md, m, x, blob, L, dst in zip(names, mds, methods, srcs, blobs, layouts, dsts):
         if md is None:
             continue
-        st = adacc.read_status(blob, L)
-        assert st[1] == 0 and st[2] == 0
-        sec = adacc.blob_sections(blob, L, m, x.numel())
-        te = int(L.tile_elems)
-        om = oracle_method(md)
-        has_out = md["outlier_mode"] != "none"
-        tp = sec["tile_ptr"].cpu().numpy().view(np.uint32).astype(np.int64) if has_out else None
-        for t in sorted(set([0, L.n_tiles - 1] + g.integers(0, L.n_tiles, 8).tolist())):
-            lo, hi = t * te, min(x.numel(), (t + 1) * te)
-            oc = oracle.compress(om, bits_of(x[lo:hi]))
-            assert np.array_equal(sec["codes"][lo * md["bits"] // 8: hi * md["bits"] // 8].cpu().numpy(), oc.packed)
-            gq = md["quant_group"]
-            assert np.array_equal(sec["scales"][lo // gq: hi // gq].cpu().numpy().view(np.uint32), oc.scale.view(np.uint32))
-            if has_out:
-                p0, p1 = int(tp[t]), int(tp[t + 1])
-                assert p1 - p0 == oc.n_out
-                assert np.array_equal(sec["idx"][p0:p1].cpu().numpy().astype(np.int64), oc.out_idx.astype(np.int64) + lo)
+        tiles = sampled_tiles(g, L.n_tiles, n_samples)
+        st = check_compressed_tiles(name, x, md, m, blob, L, tiles)
+        if md["outlier_mode"] == "topk":
+            assert st[0] == md["topk"] * (x.numel() // md["stat_group"]), name
+        total_out += st[0]
+        check_restored_tiles(name, x, md, m, blob, L, dst, tiles)
+    log(f"[parity] c5 x{layers} layers: {total_out} outliers; single-tensor decompress in reverse order")
+    scratch = torch.empty(max(numels), dtype=torch.bfloat16, device="cuda")
+    for i in reversed(range(len(srcs))):
+        if mds[i] is None:
+            continue
+        out = scratch[:numels[i]]
+        adacc.decompress(methods[i], blobs[i], out)
+        assert torch.equal(out.view(torch.int16), dsts[i].view(torch.int16)), names[i]
+    del srcs, blobs, dsts, scratch, ws
+    torch.cuda.empty_cache()
+
+
+def test_full_size_c5_one_layer_batch_sampled():
+    """One LLaMA-7B-shaped layer at its real shape through the batch entry points."""
+    run_c5_batch(1, 8)
+
+
+def test_full_size_c5_all_layers_batch_sampled():
+    """The whole C5 layer set (32 layers, 160 tensors, 20 GiB of bf16) exactly as the bench launches it."""
+    run_c5_batch(workloads.C5_LAYERS, 4)
