@@ -278,6 +278,12 @@ int adacc_mask_unpack(const void *bits, uint64_t n, void *mask, void *hip_stream
  * not counted.  CRate_i = this / (2 * numel).  NOOP: 2 * numel (the tensor is retained as it is).
  * Returns 0 for a malformed method. */
 uint64_t adacc_compressed_bytes(const adacc_method *method, uint64_t numel, uint64_t n_outliers);
+/* The same figure for a [tokens, hidden] tensor compressed by outlier channels (Section 3.2, Eq. 1) that
+ * produced n_channels of them: codes + scales (+ offsets) of the whole tensor + per outlier channel its
+ * index (4 bytes) and its tokens values in bf16.  The channel bitmap and prefix table are derived from the
+ * indices and are not counted.  Returns 0 for a malformed method or shape. */
+uint64_t adacc_channel_compressed_bytes(const adacc_channel_method *method, uint64_t tokens, uint32_t hidden,
+                                        uint64_t n_channels);
 
 /* Streams of `bytes` (a multiple of 16) per operand in the access shape of the library's tensor
  * kernels (4 KiB pieces per wavefront, full grid, non-temporal accesses): the practical HBM

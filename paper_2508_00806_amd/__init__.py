@@ -25,6 +25,7 @@ EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "
            "adacc_version", "adacc_channel_layout_of", "adacc_channel_workspace_bytes",
            "adacc_channel_compress", "adacc_channel_decompress", "adacc_channel_read_status",
            "adacc_mask_packed_bytes", "adacc_mask_pack", "adacc_mask_unpack", "adacc_compressed_bytes",
+           "adacc_channel_compressed_bytes",
            "adacc_channelwise_layout_of", "adacc_channelwise_workspace_bytes", "adacc_channelwise_compress",
            "adacc_channelwise_decompress")
 
@@ -176,6 +177,8 @@ def lib():
         L.adacc_mask_unpack.restype = ci
         L.adacc_compressed_bytes.argtypes = [pm, u64, u64]
         L.adacc_compressed_bytes.restype = u64
+        L.adacc_channel_compressed_bytes.argtypes = [pcm, u64, u32, u64]
+        L.adacc_channel_compressed_bytes.restype = u64
         L.adacc_channelwise_layout_of.argtypes = [u32, u64, u32, ctypes.POINTER(CChannelwiseLayout)]
         L.adacc_channelwise_layout_of.restype = ci
         L.adacc_channelwise_workspace_bytes.argtypes = [u64, u32]
@@ -371,6 +374,12 @@ def channel_layout_of(method: ChannelMethod, tokens: int, hidden: int) -> CChann
     _check(lib().adacc_channel_layout_of(ctypes.byref(cm), tokens, hidden, ctypes.byref(L)),
            "adacc_channel_layout_of")
     return L
+
+
+def channel_compressed_bytes(method: ChannelMethod, tokens: int, hidden: int, n_channels: int) -> int:
+    """Information-carrying bytes of a channel blob that holds n_channels outlier channels."""
+    cm = method.c()
+    return int(lib().adacc_channel_compressed_bytes(ctypes.byref(cm), tokens, hidden, n_channels))
 
 
 def channel_workspace_bytes(tokens: int, hidden: int) -> int:

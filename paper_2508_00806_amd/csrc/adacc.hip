@@ -1056,6 +1056,16 @@ uint64_t adacc_compressed_bytes(const adacc_method* method, uint64_t numel, uint
   return bytes;
 }
 
+uint64_t adacc_channel_compressed_bytes(const adacc_channel_method* method, uint64_t tokens, uint32_t hidden,
+                                        uint64_t n_channels) {
+  if (!method) return 0;
+  ChannelPlan cp;
+  if (make_channel_plan(method, tokens, hidden, &cp) != ADACC_OK) return 0;
+  const uint64_t numel = tokens * hidden;
+  const uint64_t groups = numel / method->quant_group;
+  return numel * method->bits / 8 + 4ull * groups * (method->asym ? 2u : 1u) + n_channels * (2ull * tokens + 4u);
+}
+
 int adacc_hbm_stream(int mix, void* dst, const void* src_a, const void* src_b, uint64_t bytes, void* hip_stream) {
   if (mix < ADACC_STREAM_READ || mix > ADACC_STREAM_READ2_WRITE) return ADACC_EINVAL;
   const bool wr = mix != ADACC_STREAM_READ, rd = mix != ADACC_STREAM_WRITE, rd2 = mix == ADACC_STREAM_READ2_WRITE;

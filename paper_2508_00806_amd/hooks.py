@@ -16,10 +16,30 @@ decompression runs in the HIP kernels.  A tensor the policy does not cover is sa
 """
 import torch
 
-from . import (ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
-               alloc_channel_workspace, alloc_workspace, channel_compress, channel_decompress,
-               channel_workspace_bytes, compress, compressed_bytes, decompress, mask_pack, mask_packed_bytes, mask_unpack,
-               workspace_bytes)
+from . import (AdaccError, ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
+               alloc_channel_workspace, alloc_workspace, channel_compress, channel_compressed_bytes,
+               channel_decompress, channel_layout_of, channel_workspace_bytes, compress, compressed_bytes, decompress,
+               layout_of, mask_pack, mask_packed_bytes, mask_unpack, workspace_bytes)
+
+
+class CompressedActivationLost(RuntimeError):
+    """A saved activation needed more room for its outliers than its method allowed: the blob does not
+    hold the tensor, and the backward pass must not go on with it."""
+
+
+class _StatusPool:
+    """Pinned host words for the status of every compressed tensor, filled by asynchronous copies."""
+    CHUNK = 1024
+
+    def __init__(self):
+        self.chunks, self.used = [], 0
+
+    def take(self):
+        if self.used % self.CHUNK == 0 and self.used // self.CHUNK == len(self.chunks):
+            self.chunks.append(torch.zeros((self.CHUNK, 4), dtype=torch.int32, pin_memory=True))
+        slot = self.chunks[self.used // self.CHUNK][self.used % self.CHUNK]
+        self.used += 1
+        return slot
 
 
 class _Saved:
@@ -45,13 +65,27 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
     by Z-score; the tensor is taken as [numel / last_dim, last_dim]) or None (retain).  Only contiguous
     bf16 CUDA tensors are offered to the policy.  timing=True brackets every library call with events
     so that `report()` can give Tc_i and Tdc_i (it costs a synchronisation in `report()` only).
+
+    The number of outliers moves while a model trains (Section 3.4), so a method's `max_outliers` /
+    `max_channels` can turn out too small.  The status words of every blob are copied to the host as
+    soon as the blob is written (asynchronously), and looked at before the blob is used:
+    on_overflow="raise" (the default) makes the backward pass raise `CompressedActivationLost`;
+    on_overflow="retain" waits for the status right after compression and saves the tensor as it is when
+    the blob can not hold it (one synchronisation per compressed tensor in the forward pass).
+    A tensor whose address or size the library does not take (not 16-byte aligned, a size its groups do
+    not divide) is saved as it is.
     """
 
-    def __init__(self, policy, timing=True, pack_masks=True):
+    def __init__(self, policy, timing=True, pack_masks=True, on_overflow="raise"):
+        if on_overflow not in ("raise", "retain"):
+            raise ValueError("on_overflow is 'raise' or 'retain'")
         self.policy = policy
         self.timing = timing
         self.pack_masks = pack_masks
+        self.on_overflow = on_overflow
         self.records = []
+        self.retained = []   # (shape, reason) of tensors offered to the policy and saved as they are
+        self._status = _StatusPool()
         self._ws = None      # scan workspace, grown on demand, reused by every tensor (one stream)
         self._cws = None     # workspace of the channel statistics
         super().__init__(self._pack, self._unpack)
@@ -59,7 +93,7 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
     # ---- hooks
     def _eligible(self, t):
         if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
-                and t.numel() > 0):
+                and t.numel() > 0 and t.data_ptr() % 16 == 0):
             return False
         return not (t.is_leaf and t.requires_grad)  # parameters are not activations
 
@@ -84,6 +118,14 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
         if m is None or (isinstance(m, Method) and m.kind == KIND_NOOP):
             return t
         numel = t.numel()
+        try:  # a shape the method can not take is no error of the training run: the tensor is retained
+            if isinstance(m, ChannelMethod):
+                channel_layout_of(m, numel // t.shape[-1], t.shape[-1])
+            else:
+                layout_of(m, numel)
+        except AdaccError as e:
+            self.retained.append((tuple(t.shape), str(e)))
+            return t
         rec = {"shape": tuple(t.shape), "numel": numel, "method": m, "events": {}}
         ev = self._events(rec, "compress")
         if isinstance(m, ChannelMethod):
@@ -104,11 +146,25 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
             compress(m, t, blob, ws)
         if ev:
             ev[1].record()
-        # the record keeps a copy of the 16 status bytes, not the blob: the compressed activation is
+        # the record keeps a host copy of the 16 status bytes, not the blob: the compressed activation is
         # freed as soon as autograd drops it
-        rec["status"] = blob[layout.status_off:layout.status_off + 16].clone()
+        rec["status"] = self._status.take()
+        rec["status"].copy_(blob[layout.status_off:layout.status_off + 16].view(torch.int32), non_blocking=True)
+        rec["status_ready"] = torch.cuda.Event()
+        rec["status_ready"].record()
+        if self.on_overflow == "retain" and self._lost(rec):
+            rec["retained"] = True
+            self.records.append(rec)
+            return t
         self.records.append(rec)
         return _Saved(m, blob, layout, t.shape, numel, rec)
+
+    @staticmethod
+    def _lost(rec):
+        """True when the blob of this record does not hold its tensor.  Waits for the status copy only."""
+        rec["status_ready"].synchronize()
+        st = rec["status"].tolist()
+        return bool(st[1] or st[2])
 
     def _unpack(self, s):
         if isinstance(s, _SavedMask):
@@ -120,6 +176,12 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
             return out
         if not isinstance(s, _Saved):
             return s
+        if self._lost(s.record):
+            m = s.method
+            room = m.max_channels if isinstance(m, ChannelMethod) else m.max_outliers
+            raise CompressedActivationLost(
+                f"saved activation of shape {tuple(s.shape)}: {s.record['status'][0].item()} outliers found, the method "
+                f"has room for {room}; raise max_outliers / max_channels or use on_overflow='retain'")
         out = torch.empty(s.shape, dtype=torch.bfloat16, device=s.blob.device)
         ev = self._events(s.record, "decompress")
         if isinstance(s.method, ChannelMethod):
@@ -158,15 +220,15 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
                         row[name] = ev[0].elapsed_time(ev[1])
                 rows.append(row)
                 continue
-            st = rec["status"].view(torch.int32).cpu().tolist()
-            if isinstance(m, ChannelMethod):
+            st = rec["status"].tolist()
+            if rec.get("retained"):
+                comp = 2 * rec["numel"]
+            elif isinstance(m, ChannelMethod):
                 hidden = rec["shape"][-1]
-                tokens = rec["numel"] // hidden
-                plain = Method(bits=m.bits, quant_group=m.quant_group, asym=m.asym, scale_rule=m.scale_rule)
-                comp = compressed_bytes(plain, rec["numel"], 0) + st[0] * (2 * tokens + 4)
+                comp = channel_compressed_bytes(m, rec["numel"] // hidden, hidden, st[0])
             else:
                 comp = compressed_bytes(m, rec["numel"], st[0])
-            row = {"shape": rec["shape"], "numel": rec["numel"], "n_outliers": st[0], "overflow": bool(st[1]),
+            row = {"shape": rec["shape"], "numel": rec["numel"], "n_outliers": st[0], "overflow": bool(st[1] or st[2]),
                    "original_bytes": 2 * rec["numel"], "compressed_bytes": comp,
                    "crate": comp / (2.0 * rec["numel"]), "tc_ms": None, "tdc_ms": None}
             for key, name in (("compress", "tc_ms"), ("decompress", "tdc_ms")):

@@ -270,6 +270,15 @@ def test_compressed_bytes_against_the_oracle_and_the_closed_form(L):
     assert adacc.compressed_bytes(plain, n, 0) / (2 * n) == 0.25 + 1 / 64
     assert adacc.compressed_bytes(adacc.NOOP, n, 0) == 2 * n
     assert adacc.compressed_bytes(Method(bits=5), n, 0) == 0
+    # outlier channels: the quantised tensor + per kept channel its index and one bf16 per token
+    cm = adacc.ChannelMethod(bits=4, quant_group=128, max_channels=16)
+    tokens, hidden = 96, 2048
+    for n_ch in (0, 3, 16):
+        assert adacc.channel_compressed_bytes(cm, tokens, hidden, n_ch) == \
+            adacc.compressed_bytes(plain, tokens * hidden, 0) + n_ch * (2 * tokens + 4)
+    asym = adacc.ChannelMethod(bits=8, quant_group=64, asym=1, max_channels=4)
+    assert adacc.channel_compressed_bytes(asym, 10, 256, 2) == 2560 + 8 * 40 + 2 * 24
+    assert adacc.channel_compressed_bytes(adacc.ChannelMethod(bits=5), tokens, hidden, 0) == 0
 
 
 # ----------------------------------------------------------------- channel-wise symmetric quantisation

@@ -141,3 +141,76 @@ def test_dropout_mask_is_saved_in_bit_format_without_loss():
     saved = ctx._pack(keep)
     assert np.array_equal(saved.bits.cpu().numpy(), oracle.mask_pack(keep.cpu().numpy()))
     assert torch.equal(ctx._unpack(saved), keep)
+
+
+def linear_case(tokens=96, hidden=2048, out=64, seed=11):
+    torch.manual_seed(seed)
+    x = torch.randn(tokens, hidden)
+    x[:, [7, 900]] *= 40.0
+    x = x.to(torch.bfloat16).cuda()
+    w = (torch.randn(out, hidden) * 0.02).to(torch.bfloat16).cuda().requires_grad_(True)
+    g = torch.randn(tokens, out).to(torch.bfloat16).cuda()
+    return x, w, g
+
+
+@pytest.mark.parametrize("kind", ["abs", "channel"])
+def test_a_blob_that_overflowed_stops_the_backward_pass(kind):
+    """More outliers than the method has room for (Section 3.4: the number of outliers moves while
+    training): the blob does not hold the tensor, and the backward pass must say so instead of
+    handing a wrong activation to the gradient."""
+    from paper_2508_00806_amd.hooks import CompressedActivationLost
+    print(f"[hooks] overflow raises, {kind}", flush=True)
+    x, w, g = linear_case()
+    if kind == "abs":
+        m = adacc.Method(bits=8, quant_group=128, outlier_mode=adacc.OUTLIER_ABS, thresh=3.0, max_outliers=8)
+    else:
+        m = adacc.ChannelMethod(bits=4, quant_group=128, z_thresh=3.0, max_channels=1)  # two channels stand out
+    ctx = SavedActivationCompression(lambda t: m if t.shape == x.shape else None)
+    with ctx:
+        y = torch.nn.functional.linear(x, w)
+    with pytest.raises(CompressedActivationLost):
+        y.backward(g)
+    rep = ctx.report()
+    assert len(rep) == 1 and rep[0]["overflow"] and rep[0]["n_outliers"] > (8 if kind == "abs" else 1)
+
+
+@pytest.mark.parametrize("kind", ["abs", "channel"])
+def test_a_blob_that_overflowed_can_fall_back_to_the_tensor(kind):
+    print(f"[hooks] overflow retains, {kind}", flush=True)
+    x, w, g = linear_case()
+    if kind == "abs":
+        m = adacc.Method(bits=8, quant_group=128, outlier_mode=adacc.OUTLIER_ABS, thresh=3.0, max_outliers=8)
+    else:
+        m = adacc.ChannelMethod(bits=4, quant_group=128, z_thresh=3.0, max_channels=1)
+    ctx = SavedActivationCompression(lambda t: m if t.shape == x.shape else None, on_overflow="retain")
+    with ctx:
+        y = torch.nn.functional.linear(x, w)
+    y.backward(g)
+    w2 = w.detach().clone().requires_grad_(True)
+    torch.nn.functional.linear(x, w2).backward(g)
+    assert torch.equal(w.grad, w2.grad)  # the activation itself was used
+    rep = ctx.report()
+    assert len(rep) == 1 and rep[0]["overflow"] and rep[0]["crate"] == 1.0 and rep[0]["tdc_ms"] is None
+
+
+def test_tensors_the_library_does_not_take_are_saved_as_they_are():
+    """A contiguous view at an address that is not a multiple of 16 bytes, and a size the groups do not
+    divide: no error in the forward pass, the tensor is retained."""
+    print("[hooks] misaligned and indivisible tensors", flush=True)
+    m = adacc.Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=64, thresh=6.0, max_outliers=4096)
+    for tokens, hidden, offset in ((32, 256, 1), (30, 100, 0)):
+        torch.manual_seed(5)
+        buf = torch.randn(tokens * hidden + 8).to(torch.bfloat16).cuda()
+        x = buf[offset:offset + tokens * hidden].view(tokens, hidden)
+        assert x.is_contiguous() and (offset == 0 or x.data_ptr() % 16 != 0)
+        w = (torch.randn(16, hidden) * 0.1).to(torch.bfloat16).cuda().requires_grad_(True)
+        g = torch.randn(tokens, 16).to(torch.bfloat16).cuda()
+        ctx = SavedActivationCompression(lambda t: m if t.shape == x.shape else None)
+        with ctx:
+            y = torch.nn.functional.linear(x, w)
+        y.backward(g)
+        w2 = w.detach().clone().requires_grad_(True)
+        torch.nn.functional.linear(x, w2).backward(g)
+        assert torch.equal(w.grad, w2.grad)
+        assert ctx.report() == []
+        assert (len(ctx.retained) == 1) == (offset == 0)  # the indivisible size was offered and turned down
