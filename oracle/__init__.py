@@ -14,12 +14,14 @@ from .build import build as _build, LIB as _LIB
 
 OUT_NONE, OUT_ABS, OUT_STD, OUT_TOPK = 0, 1, 2, 3
 RULE_PAPER, RULE_FULLRANGE = 0, 1
+DT_BF16, DT_F16 = 0, 1
 
 
 class _CMethod(ctypes.Structure):
     _fields_ = [("bits", ctypes.c_uint32), ("quant_group", ctypes.c_uint32), ("asym", ctypes.c_uint32),
                 ("scale_rule", ctypes.c_uint32), ("outlier_mode", ctypes.c_uint32),
-                ("stat_group", ctypes.c_uint32), ("thresh", ctypes.c_float), ("topk", ctypes.c_uint32)]
+                ("stat_group", ctypes.c_uint32), ("thresh", ctypes.c_float), ("topk", ctypes.c_uint32),
+                ("dtype", ctypes.c_uint32)]
 
 
 @dataclass
@@ -32,20 +34,21 @@ class Method:
     stat_group: int = 0
     thresh: float = 0.0
     topk: int = 0
+    dtype: int = DT_BF16
 
     def c(self):
         return _CMethod(self.bits, self.quant_group, self.asym, self.scale_rule, self.outlier_mode,
-                        self.stat_group, float(self.thresh), self.topk)
+                        self.stat_group, float(self.thresh), self.topk, self.dtype)
 
 
 MODE_BY_NAME = {"none": OUT_NONE, "abs": OUT_ABS, "std": OUT_STD, "topk": OUT_TOPK}
 
 
-def method_from_dict(md, scale_rule: int = RULE_PAPER) -> Method:
+def method_from_dict(md, scale_rule: int = RULE_PAPER, dtype: int = DT_BF16) -> Method:
     """A method written as a plain dictionary (outlier_mode by name) as the oracle's descriptor."""
     return Method(bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"], scale_rule=scale_rule,
                   outlier_mode=MODE_BY_NAME[md["outlier_mode"]], stat_group=md["stat_group"],
-                  thresh=md["thresh"], topk=md["topk"])
+                  thresh=md["thresh"], topk=md["topk"], dtype=dtype)
 
 
 _lib = None
@@ -70,7 +73,11 @@ def lib():
         L.oracle_pairwise_sum.argtypes = [vp, sz]
         L.oracle_pairwise_sum.restype = ctypes.c_float
         dp = ctypes.POINTER(ctypes.c_double)
-        L.oracle_channel_scores.argtypes = [vp, sz, sz, vp]
+        L.oracle_to_f32.argtypes = [ctypes.POINTER(_CMethod), ctypes.c_uint16]
+        L.oracle_to_f32.restype = ctypes.c_float
+        L.oracle_from_f32.argtypes = [ctypes.POINTER(_CMethod), ctypes.c_float]
+        L.oracle_from_f32.restype = ctypes.c_uint16
+        L.oracle_channel_scores.argtypes = [ctypes.c_uint32, vp, sz, sz, vp]
         L.oracle_channel_scores.restype = None
         L.oracle_channel_select.argtypes = [vp, sz, ctypes.c_float, vp, vp]
         L.oracle_channel_select.restype = None
@@ -98,7 +105,7 @@ def _p(a):
 def _as_u16(x):
     x = np.ascontiguousarray(x)
     if x.dtype != np.uint16:
-        raise TypeError("oracle input is an array of bf16 bit patterns (uint16)")
+        raise TypeError("oracle input is an array of 16-bit patterns (uint16)")
     return x.reshape(-1)
 
 
@@ -129,7 +136,7 @@ def compress(m: Method, x_bits, cap=None) -> Compressed:
     x = _as_u16(x_bits)
     n = x.size
     cap = n if cap is None else int(cap)
-    groups = n // m.quant_group if m.quant_group else 0
+    groups = -(-n // m.quant_group) if m.quant_group else 0
     codes = np.zeros(n, dtype=np.int8)
     packed = np.zeros((n * m.bits + 7) // 8, dtype=np.uint8)
     scale = np.zeros(groups, dtype=np.float32)
@@ -187,12 +194,27 @@ class ChannelCompressed:
     n_ch: int
 
 
-def channel_scores(x_bits, tokens: int, hidden: int) -> np.ndarray:
+def channel_scores(x_bits, tokens: int, hidden: int, dtype: int = DT_BF16) -> np.ndarray:
     x = _as_u16(x_bits)
     assert x.size == tokens * hidden
     S = np.zeros(hidden, dtype=np.float64)
-    lib().oracle_channel_scores(_p(x), tokens, hidden, _p(S))
+    lib().oracle_channel_scores(dtype, _p(x), tokens, hidden, _p(S))
     return S
+
+
+def to_f32(x_bits, dtype: int = DT_BF16) -> np.ndarray:
+    """The oracle's own widening of 16-bit patterns, element by element."""
+    cm = Method(dtype=dtype).c()
+    f = lib().oracle_to_f32
+    return np.array([f(ctypes.byref(cm), int(b)) for b in _as_u16(x_bits)], dtype=np.float32)
+
+
+def from_f32(values, dtype: int = DT_BF16) -> np.ndarray:
+    """The oracle's own rounding of binary32 values to the 16-bit format, element by element."""
+    cm = Method(dtype=dtype).c()
+    f = lib().oracle_from_f32
+    return np.array([f(ctypes.byref(cm), float(v)) for v in np.asarray(values, dtype=np.float32).reshape(-1)],
+                    dtype=np.uint16)
 
 
 def channel_select(S, z_thresh: float):
@@ -209,7 +231,7 @@ def channel_compress(m: Method, x_bits, tokens: int, hidden: int, z_thresh: floa
     n = tokens * hidden
     assert x.size == n
     cap = hidden if cap is None else int(cap)
-    groups = n // m.quant_group if m.quant_group else 0
+    groups = -(-n // m.quant_group) if m.quant_group else 0
     codes = np.zeros(n, dtype=np.int8)
     packed = np.zeros((n * m.bits + 7) // 8, dtype=np.uint8)
     scale = np.zeros(groups, dtype=np.float32)
@@ -266,7 +288,7 @@ def mask_unpack(bits, n: int) -> np.ndarray:
 
 # ---- channel-wise symmetric quantisation (Section 3.2: Query, Key, Value) ----
 
-def channelwise_compress(bits: int, x_bits, tokens: int, hidden: int, scale_rule: int = RULE_PAPER):
+def channelwise_compress(bits: int, x_bits, tokens: int, hidden: int, scale_rule: int = RULE_PAPER, dtype: int = DT_BF16):
     """Returns (codes int8 [tokens*hidden], packed uint8, scale float32 [hidden])."""
     x = _as_u16(x_bits)
     n = tokens * hidden
@@ -274,18 +296,18 @@ def channelwise_compress(bits: int, x_bits, tokens: int, hidden: int, scale_rule
     codes = np.zeros(n, dtype=np.int8)
     packed = np.zeros((n * bits + 7) // 8, dtype=np.uint8)
     scale = np.zeros(hidden, dtype=np.float32)
-    cm = Method(bits=bits, quant_group=1, scale_rule=scale_rule).c()
+    cm = Method(bits=bits, quant_group=1, scale_rule=scale_rule, dtype=dtype).c()
     if lib().oracle_channelwise_compress(ctypes.byref(cm), _p(x), tokens, hidden, _p(codes), _p(packed), _p(scale)) != 0:
         raise ValueError("oracle: malformed method")
     return codes, packed, scale
 
 
-def channelwise_decompress(bits: int, packed, scale, tokens: int, hidden: int):
+def channelwise_decompress(bits: int, packed, scale, tokens: int, hidden: int, dtype: int = DT_BF16):
     """Returns (xhat_f32, xhat_bf16_bits)."""
     n = tokens * hidden
     f = np.zeros(n, dtype=np.float32)
     b = np.zeros(n, dtype=np.uint16)
-    cm = Method(bits=bits, quant_group=1).c()
+    cm = Method(bits=bits, quant_group=1, dtype=dtype).c()
     pk = np.ascontiguousarray(packed, dtype=np.uint8)
     sc = np.ascontiguousarray(scale, dtype=np.float32)
     if lib().oracle_channelwise_decompress(ctypes.byref(cm), _p(pk), _p(sc), tokens, hidden, _p(f), _p(b)) != 0:

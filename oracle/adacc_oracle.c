@@ -11,8 +11,12 @@
  *   5. decompression: code * S (+ O), then the outliers are put back.
  *
  * Readings taken where the paper is silent (each is listed in the design notes):
- *   - input is bf16, arithmetic is binary32, the bit width b generalises the
- *     paper's 4 (divisor 8 -> 2^(b-1), divisor 16 -> 2^b, clip [-2^(b-1), 2^(b-1)-1]);
+ *   - input is bf16 or (the paper's own format) binary16, arithmetic is binary32, the bit width b
+ *     generalises the paper's 4 (divisor 8 -> 2^(b-1), divisor 16 -> 2^b, clip [-2^(b-1), 2^(b-1)-1]);
+ *   - the tensor is one flat array cut into groups from its start; when the group length does not
+ *     divide the number of elements, the last group is the shorter one and is treated like any
+ *     other group over the elements it has (its own scale; its own mean and variance, divided by
+ *     its own count; at most as many largest values as it has elements);
  *   - outliers are single elements picked by |x| > tau, by x^2 > k^2 * var of the
  *     statistics group, or as the k largest magnitudes of the group (the paper
  *     picks whole channels by Z-score; same extract / zero / quantise structure);
@@ -32,7 +36,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-/* ---------- bf16 <-> binary32 ---------- */
+/* ---------- 16-bit formats <-> binary32 ---------- */
 
 static float bf16_to_f32(uint16_t b) {
   uint32_t u = (uint32_t)b << 16;
@@ -49,7 +53,60 @@ static uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
-static int is_nonfinite_bf16(uint16_t b) { return (b & 0x7FFFu) >= 0x7F80u; }
+/* binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits.  Every value is a binary32 value. */
+static float f16_to_f32(uint16_t b) {
+  const int e = (b >> 10) & 0x1F;
+  const int frac = b & 0x3FF;
+  float mag;
+  if (e == 0x1F)
+    mag = frac ? NAN : INFINITY;
+  else if (e == 0)
+    mag = ldexpf((float)frac, -24); /* subnormal: frac * 2^-24 */
+  else
+    mag = ldexpf((float)(frac + 1024), e - 25); /* (1 + frac/1024) * 2^(e-15) */
+  return (b & 0x8000u) ? -mag : mag;
+}
+
+/* Round to nearest, ties to even.  Values of magnitude 65520 and above (half a step past the largest
+ * finite value, 65504) become infinite. */
+static uint16_t f32_to_f16_rne(float f) {
+  const uint16_t sign = signbit(f) ? 0x8000u : 0u;
+  if (isnan(f)) return (uint16_t)(sign | 0x7E00u);
+  const double a = fabs((double)f);
+  if (a >= 65520.0) return (uint16_t)(sign | 0x7C00u);
+  int e2;
+  frexp(a, &e2);                                 /* a = frac * 2^e2 with frac in [0.5, 1): a in [2^(e2-1), 2^e2) */
+  int e = (a == 0.0) ? -14 : e2 - 1;
+  if (e < -14) e = -14;                          /* subnormal range: fixed spacing 2^-24 */
+  const double steps = rint(ldexp(a, 10 - e));   /* a in units of the spacing 2^(e-10): exact scaling, one rounding */
+  /* steps is in [0, 2048]; 2048 means the value rounded up into the next binade, 1024 .. 2047 is a
+   * normal number of exponent e, below 1024 (only when e == -14) a subnormal */
+  uint32_t bits;
+  if (steps >= 2048.0)
+    bits = (uint32_t)(e + 1 + 15) << 10;
+  else if (steps >= 1024.0)
+    bits = ((uint32_t)(e + 15) << 10) | ((uint32_t)steps - 1024u);
+  else
+    bits = (uint32_t)steps;
+  return (uint16_t)(sign | bits);
+}
+
+static float to_f32(const oracle_method *m, uint16_t b) {
+  return m->dtype == ORACLE_DT_F16 ? f16_to_f32(b) : bf16_to_f32(b);
+}
+
+static uint16_t from_f32(const oracle_method *m, float f) {
+  return m->dtype == ORACLE_DT_F16 ? f32_to_f16_rne(f) : f32_to_bf16_rne(f);
+}
+
+/* Inf or NaN: the exponent field is all ones.  In both formats the 15 low bits, read as an integer,
+ * grow with |x|, and the patterns that are not finite are the largest. */
+static int is_nonfinite(const oracle_method *m, uint16_t b) {
+  return (b & 0x7FFFu) >= (m->dtype == ORACLE_DT_F16 ? 0x7C00u : 0x7F80u);
+}
+
+float oracle_to_f32(const oracle_method *m, uint16_t b) { return to_f32(m, b); }
+uint16_t oracle_from_f32(const oracle_method *m, float f) { return from_f32(m, f); }
 
 /* ---------- canonical pairwise sum ----------
  * Pad with +0 to the next power of two, then add neighbours until one value is left:
@@ -70,10 +127,12 @@ float oracle_pairwise_sum(const float *v, size_t n) {
 
 static int method_ok(const oracle_method *m, size_t n) {
   if (m->bits != 4 && m->bits != 8) return 0;
-  if (m->quant_group == 0 || n % m->quant_group != 0) return 0;
+  (void)n; /* any length: the last group of either kind may be short */
+  if (m->dtype > ORACLE_DT_F16) return 0;
+  if (m->quant_group == 0) return 0;
   if (m->outlier_mode > ORACLE_OUT_TOPK) return 0;
   if (m->outlier_mode == ORACLE_OUT_STD || m->outlier_mode == ORACLE_OUT_TOPK) {
-    if (m->stat_group == 0 || n % m->stat_group != 0) return 0;
+    if (m->stat_group == 0) return 0;
   }
   if (m->outlier_mode == ORACLE_OUT_TOPK && (m->topk == 0 || m->topk > m->stat_group)) return 0;
   return 1;
@@ -83,7 +142,7 @@ static int method_ok(const oracle_method *m, size_t n) {
 
 /* |x| > tau, compared in binary32. */
 static void select_abs(const oracle_method *m, const uint16_t *x, size_t n, uint8_t *out) {
-  for (size_t i = 0; i < n; ++i) out[i] = fabsf(bf16_to_f32(x[i])) > m->thresh;
+  for (size_t i = 0; i < n; ++i) out[i] = fabsf(to_f32(m, x[i])) > m->thresh;
 }
 
 /* x^2 > k^2 * var, var = population variance of the statistics group about its mean.
@@ -93,38 +152,40 @@ static void select_std(const oracle_method *m, const uint16_t *x, size_t n, uint
   const float k2 = m->thresh * m->thresh;
   float *v = (float *)malloc(gs * sizeof(float));
   float *v2 = (float *)malloc(gs * sizeof(float));
-  for (size_t g = 0; g < n / gs; ++g) {
-    const uint16_t *xg = x + g * gs;
-    for (size_t i = 0; i < gs; ++i) {
-      v[i] = bf16_to_f32(xg[i]);
-      v2[i] = v[i] * v[i]; /* exact: two 8-bit significands */
+  for (size_t g0 = 0; g0 < n; g0 += gs) {
+    const size_t cnt = (n - g0 < gs) ? n - g0 : gs; /* the last group may be short */
+    const uint16_t *xg = x + g0;
+    for (size_t i = 0; i < cnt; ++i) {
+      v[i] = to_f32(m, xg[i]);
+      v2[i] = v[i] * v[i]; /* exact: two significands of at most 11 bits */
     }
-    float s1 = oracle_pairwise_sum(v, gs);
-    float s2 = oracle_pairwise_sum(v2, gs);
-    float mean = s1 / (float)gs;
-    float var = fmaf(-mean, mean, s2 / (float)gs);
+    float s1 = oracle_pairwise_sum(v, cnt);
+    float s2 = oracle_pairwise_sum(v2, cnt);
+    float mean = s1 / (float)cnt;
+    float var = fmaf(-mean, mean, s2 / (float)cnt);
     if (var < 0.0f) var = 0.0f; /* a NaN (non-finite input) stays NaN: nothing then passes the test */
     float limit = k2 * var;
-    for (size_t i = 0; i < gs; ++i) out[g * gs + i] = v2[i] > limit;
+    for (size_t i = 0; i < cnt; ++i) out[g0 + i] = v2[i] > limit;
   }
   free(v);
   free(v2);
 }
 
-/* The k largest magnitudes of each statistics group.  Magnitudes are compared as
- * the 15 low bits of the bf16 pattern (monotone in |x|); equal magnitudes are
- * ranked by position, the earlier one first. */
+/* The k largest magnitudes of each statistics group (all of a group that has no more than k).
+ * Magnitudes are compared as the 15 low bits of the pattern (monotone in |x| in both formats);
+ * equal magnitudes are ranked by position, the earlier one first. */
 static void select_topk(const oracle_method *m, const uint16_t *x, size_t n, uint8_t *out) {
   const size_t gs = m->stat_group;
-  for (size_t g = 0; g < n / gs; ++g) {
-    const uint16_t *xg = x + g * gs;
-    uint8_t *og = out + g * gs;
-    memset(og, 0, gs);
-    for (uint32_t r = 0; r < m->topk; ++r) {
-      size_t best = gs;
-      for (size_t i = 0; i < gs; ++i) {
+  for (size_t g0 = 0; g0 < n; g0 += gs) {
+    const size_t cnt = (n - g0 < gs) ? n - g0 : gs; /* the last group may be short */
+    const uint16_t *xg = x + g0;
+    uint8_t *og = out + g0;
+    memset(og, 0, cnt);
+    for (uint32_t r = 0; r < m->topk && r < cnt; ++r) {
+      size_t best = cnt;
+      for (size_t i = 0; i < cnt; ++i) {
         if (og[i]) continue;
-        if (best == gs || (xg[i] & 0x7FFFu) > (xg[best] & 0x7FFFu)) best = i;
+        if (best == cnt || (xg[i] & 0x7FFFu) > (xg[best] & 0x7FFFu)) best = i;
       }
       og[best] = 1;
     }
@@ -141,7 +202,7 @@ int oracle_select_outliers(const oracle_method *m, const uint16_t *x, size_t n, 
   }
   /* a value that cannot be quantised at all is always kept exactly */
   for (size_t i = 0; i < n; ++i)
-    if (is_nonfinite_bf16(x[i])) out[i] = 1;
+    if (is_nonfinite(m, x[i])) out[i] = 1;
   return 0;
 }
 
@@ -201,18 +262,19 @@ static void quantise_rest(const oracle_method *m, const uint16_t *x, const uint8
   /* 3. zero them in the activation; a value that is not finite, or a negative
    *    zero, also counts as zero from here on */
   for (size_t i = 0; i < n; ++i) {
-    float f = bf16_to_f32(x[i]);
-    if (out[i] || is_nonfinite_bf16(x[i]) || f == 0.0f) f = 0.0f;
+    float f = to_f32(m, x[i]);
+    if (out[i] || is_nonfinite(m, x[i]) || f == 0.0f) f = 0.0f;
     y[i] = f;
   }
 
-  /* 4. quantise every group of the flat array */
+  /* 4. quantise every group of the flat array; the last one may be short */
   const size_t gq = m->quant_group;
-  for (size_t h = 0; h < n / gq; ++h) {
+  for (size_t h = 0; h * gq < n; ++h) {
+    const size_t cnt = (n - h * gq < gq) ? n - h * gq : gq;
     if (m->asym)
-      quant_asym(m, y + h * gq, gq, codes + h * gq, scale + h, zp + h);
+      quant_asym(m, y + h * gq, cnt, codes + h * gq, scale + h, zp + h);
     else
-      quant_sym(m, y + h * gq, gq, codes + h * gq, scale + h);
+      quant_sym(m, y + h * gq, cnt, codes + h * gq, scale + h);
   }
 
   /* pack */
@@ -276,7 +338,7 @@ static void dequantise_all(const oracle_method *m, const uint8_t *packed, const 
     float s = scale[i / gq];
     float v = m->asym ? fmaf(c, s, zp[i / gq]) : c * s; /* X^ = code * S (+ O) */
     if (xhat_f32) xhat_f32[i] = v;
-    if (xhat_bf16) xhat_bf16[i] = f32_to_bf16_rne(v);
+    if (xhat_bf16) xhat_bf16[i] = from_f32(m, v);
   }
 }
 
@@ -289,15 +351,15 @@ int oracle_decompress(const oracle_method *m, const uint8_t *packed, const float
   for (size_t j = 0; j < n_out; ++j) {
     size_t i = (size_t)out_idx[j];
     if (i >= n) return -1;
-    if (xhat_f32) xhat_f32[i] = bf16_to_f32(out_val[j]);
+    if (xhat_f32) xhat_f32[i] = to_f32(m, out_val[j]);
     if (xhat_bf16) xhat_bf16[i] = out_val[j];
   }
   return 0;
 }
 
 uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out) {
-  uint64_t groups = n / m->quant_group;
-  return (uint64_t)n * m->bits / 8 + 4ull * groups * (m->asym ? 2 : 1) + 6ull * n_out;
+  uint64_t groups = (n + m->quant_group - 1) / m->quant_group;
+  return ((uint64_t)n * m->bits + 7) / 8 + 4ull * groups * (m->asym ? 2 : 1) + 6ull * n_out;
 }
 
 /* ====================================================================================
@@ -314,18 +376,27 @@ uint64_t oracle_logical_bytes(const oracle_method *m, size_t n, size_t n_out) {
  *   - the threshold is compared against Z itself, formed by one binary64 division;
  *   - a channel whose sum is not finite is always an outlier and takes no part in mu and sigma;
  *   - if sigma is zero or not a number (all channels alike, or none left), nothing else is selected.
- * S_h is the exact sum, rounded once to binary64 (the magnitude of a finite bf16 value is an
- * integer multiple of 2^-133 below 2^128, so the sum is kept as a 320-bit integer); mu and sigma
+ * S_h is the exact sum, rounded once to binary64 (the magnitude of a finite value of either 16-bit
+ * format is an integer multiple of 2^-133 below 2^128, so the sum is kept as a 320-bit integer); mu and sigma
  * are the textbook two-pass mean and standard deviation, plain binary64 loops in channel order.
  * ==================================================================================== */
 
-/* sum of bf16 magnitudes as an integer count of 2^-133, five 64-bit limbs, least significant first */
+/* sum of magnitudes as an integer count of 2^-133, five 64-bit limbs, least significant first */
 typedef struct exact_sum { uint64_t limb[5]; } exact_sum;
 
-static void exact_add(exact_sum *a, uint16_t b) {
-  const uint32_t e = (b >> 7) & 0xFFu;
-  const uint64_t sig = e ? ((b & 0x7Fu) | 0x80u) : (b & 0x7Fu); /* |x| = sig * 2^(max(e,1) - 134) */
-  const uint32_t shift = e ? e - 1u : 0u;                       /*     = sig * 2^shift * 2^-133     */
+/* adds the magnitude of the finite 16-bit pattern b */
+static void exact_add(exact_sum *a, uint32_t dtype, uint16_t b) {
+  uint64_t sig;
+  uint32_t shift; /* |x| = sig * 2^shift * 2^-133 */
+  if (dtype == ORACLE_DT_F16) {
+    const uint32_t e = (b >> 10) & 0x1Fu;
+    sig = e ? ((b & 0x3FFu) | 0x400u) : (b & 0x3FFu); /* |x| = sig * 2^(max(e,1) - 25) */
+    shift = (e ? e : 1u) + 108u;
+  } else {
+    const uint32_t e = (b >> 7) & 0xFFu;
+    sig = e ? ((b & 0x7Fu) | 0x80u) : (b & 0x7Fu); /* |x| = sig * 2^(max(e,1) - 134) */
+    shift = e ? e - 1u : 0u;
+  }
   const unsigned __int128 v = (unsigned __int128)sig << (shift % 64u);
   uint64_t add[2] = {(uint64_t)v, (uint64_t)(v >> 64)};
   uint64_t carry = 0;
@@ -358,16 +429,17 @@ static double exact_round(const exact_sum *a) {
 }
 
 /* S_h = sum over the tokens of |x|, for every channel. */
-void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S) {
+void oracle_channel_scores(uint32_t dtype, const uint16_t *x, size_t tokens, size_t hidden, double *S) {
+  const uint16_t inf = (dtype == ORACLE_DT_F16) ? 0x7C00u : 0x7F80u;
   for (size_t h = 0; h < hidden; ++h) {
     exact_sum acc;
     memset(&acc, 0, sizeof acc);
     int inf_seen = 0, nan_seen = 0;
     for (size_t t = 0; t < tokens; ++t) {
       const uint16_t b = x[t * hidden + h];
-      if ((b & 0x7FFFu) > 0x7F80u) nan_seen = 1;
-      else if ((b & 0x7FFFu) == 0x7F80u) inf_seen = 1;
-      else exact_add(&acc, b);
+      if ((b & 0x7FFFu) > inf) nan_seen = 1;
+      else if ((b & 0x7FFFu) == inf) inf_seen = 1;
+      else exact_add(&acc, dtype, b);
     }
     S[h] = nan_seen ? (double)NAN : inf_seen ? (double)INFINITY : exact_round(&acc);
   }
@@ -419,7 +491,7 @@ int oracle_channel_compress(const oracle_method *m, const uint16_t *x, size_t to
   const size_t n = tokens * hidden;
   double *S = (double *)malloc(hidden * sizeof(double));
   uint8_t *is_out = (uint8_t *)malloc(hidden);
-  oracle_channel_scores(x, tokens, hidden, S);
+  oracle_channel_scores(m->dtype, x, tokens, hidden, S);
   oracle_channel_select(S, hidden, z_thresh, is_out, NULL);
   size_t cnt = 0;
   for (size_t h = 0; h < hidden; ++h)
@@ -454,7 +526,7 @@ int oracle_channel_decompress(const oracle_method *m, const uint8_t *packed, con
     for (size_t r = 0; r < n_ch; ++r) {
       const size_t h = (size_t)ch_idx[r];
       if (h >= hidden) return -1;
-      if (xhat_f32) xhat_f32[t * hidden + h] = bf16_to_f32(ch_val[t * n_ch + r]);
+      if (xhat_f32) xhat_f32[t * hidden + h] = to_f32(m, ch_val[t * n_ch + r]);
       if (xhat_bf16) xhat_bf16[t * hidden + h] = ch_val[t * n_ch + r];
     }
   return 0;
@@ -492,8 +564,8 @@ int oracle_channelwise_compress(const oracle_method *m, const uint16_t *x, size_
   int8_t *ccol = (int8_t *)malloc(tokens ? tokens : 1);
   for (size_t h = 0; h < hidden; ++h) {
     for (size_t t = 0; t < tokens; ++t) {
-      float f = bf16_to_f32(x[t * hidden + h]);
-      if (is_nonfinite_bf16(x[t * hidden + h]) || f == 0.0f) f = 0.0f;
+      float f = to_f32(m, x[t * hidden + h]);
+      if (is_nonfinite(m, x[t * hidden + h]) || f == 0.0f) f = 0.0f;
       col[t] = f;
     }
     quant_sym(m, col, tokens, ccol, scale + h); /* Eq. 2 with the channel as the group */
@@ -522,7 +594,7 @@ int oracle_channelwise_decompress(const oracle_method *m, const uint8_t *packed,
   for (size_t i = 0; i < tokens * hidden; ++i) {
     float v = (float)unpack_code(m, packed, i) * scale[i % hidden];
     if (xhat_f32) xhat_f32[i] = v;
-    if (xhat_bf16) xhat_bf16[i] = f32_to_bf16_rne(v);
+    if (xhat_bf16) xhat_bf16[i] = from_f32(m, v);
   }
   return 0;
 }

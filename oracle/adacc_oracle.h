@@ -26,6 +26,7 @@ extern "C" {
 
 enum { ORACLE_OUT_NONE = 0, ORACLE_OUT_ABS = 1, ORACLE_OUT_STD = 2, ORACLE_OUT_TOPK = 3 };
 enum { ORACLE_RULE_PAPER = 0, ORACLE_RULE_FULLRANGE = 1 };
+enum { ORACLE_DT_BF16 = 0, ORACLE_DT_F16 = 1 }; /* the 16-bit format of the tensor: bfloat16 or IEEE binary16 */
 
 typedef struct oracle_method {
   uint32_t bits;         /* 4 or 8                                                  */
@@ -36,7 +37,14 @@ typedef struct oracle_method {
   uint32_t stat_group;   /* elements per statistics group (STD, TOPK)               */
   float    thresh;       /* ABS: tau     STD: k (multiples of the group's std)      */
   uint32_t topk;         /* TOPK: outliers kept per statistics group                */
+  uint32_t dtype;        /* ORACLE_DT_*: format of the input, of the kept outliers and of the 16-bit output */
 } oracle_method;
+
+/* The two conversions every other function uses, exported so that they can be pinned on their own:
+ * a 16-bit pattern of the method's format as binary32 (exact), and binary32 rounded to that format
+ * (to nearest, ties to even; NaN stays NaN; too large becomes infinite). */
+float oracle_to_f32(const oracle_method *m, uint16_t b);
+uint16_t oracle_from_f32(const oracle_method *m, float f);
 
 /* Step 1: which elements are outliers.  out[i] = 1 for an outlier, else 0.
  * x holds n bf16 bit patterns.  Returns 0, or -1 on a malformed method. */
@@ -76,7 +84,7 @@ float oracle_pairwise_sum(const float *v, size_t n);
  * to binary64; mu and sigma are plain two-pass binary64 loops over the channels. */
 
 /* S_h = sum over the tokens of |x|, for every channel. */
-void oracle_channel_scores(const uint16_t *x, size_t tokens, size_t hidden, double *S);
+void oracle_channel_scores(uint32_t dtype, const uint16_t *x, size_t tokens, size_t hidden, double *S);
 
 /* Eq. 1: is_out[h] = 1 where Z_h = (S_h - mu) / sigma exceeds z_thresh (or S_h is not finite).
  * stats (may be NULL) receives mu and sigma. */

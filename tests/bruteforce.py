@@ -13,6 +13,7 @@ from fractions import Fraction
 FLT_MAX = Fraction((2 ** 24 - 1) * 2 ** 104)
 NONE, ABS, STD, TOPK = 0, 1, 2, 3
 PAPER, FULLRANGE = 0, 1
+BF16, F16 = 0, 1   # the tensor's 16-bit format
 
 
 def round_half_even(q: Fraction) -> int:
@@ -68,6 +69,41 @@ def bf16_bits_of(q: Fraction) -> int:
     return sign | ((e + 127) << 7) | int((a / Fraction(2) ** e - 1) * 128)
 
 
+def f16_value(bits: int):
+    """Value of a binary16 bit pattern (5 exponent bits, bias 15, 10 fraction bits); None for Inf / NaN."""
+    e, f = (bits >> 10) & 0x1F, bits & 0x3FF
+    if e == 0x1F:
+        return None
+    mag = Fraction(f, 1024) * Fraction(2) ** -14 if e == 0 else (1 + Fraction(f, 1024)) * Fraction(2) ** (e - 15)
+    return -mag if bits >> 15 else mag
+
+
+def f16_bits_of(q: Fraction) -> int:
+    """binary32 value -> binary16 bit pattern, round to nearest even; what rounds past the largest finite
+    value (65504) is infinite."""
+    r = to_grid(q, 11, -24)
+    sign = 0x8000 if (r < 0 or (r == 0 and q < 0)) else 0
+    a = abs(r)
+    if a == 0:
+        return sign
+    if a > 65504:
+        return sign | 0x7C00
+    if a < Fraction(2) ** -14:
+        return sign | int(a / Fraction(2) ** -24)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    return sign | ((e + 15) << 10) | int((a / Fraction(2) ** e - 1) * 1024)
+
+
+def value_of(bits: int, fmt: int):
+    return f16_value(bits) if fmt == F16 else bf16_value(bits)
+
+
+def bits_of_value(q: Fraction, fmt: int) -> int:
+    return f16_bits_of(q) if fmt == F16 else bf16_bits_of(q)
+
+
 def pairwise(v):
     """Canonical pairwise binary32 sum: pad with zeros to a power of two, split in halves."""
     n = 1
@@ -83,9 +119,9 @@ def pairwise(v):
     return rec(0, n)
 
 
-def select(bits, mode, stat_group, thresh: Fraction, topk):
+def select(bits, mode, stat_group, thresh: Fraction, topk, fmt=BF16):
     n = len(bits)
-    vals = [bf16_value(b) for b in bits]
+    vals = [value_of(b, fmt) for b in bits]
     out = [False] * n
     if mode == ABS:
         out = [v is not None and abs(v) > thresh for v in vals]
@@ -96,9 +132,9 @@ def select(bits, mode, stat_group, thresh: Fraction, topk):
             if any(v is None for v in grp):
                 continue  # the statistics are not numbers: nothing passes the threshold
             s1 = pairwise(grp)
-            s2 = pairwise([v * v for v in grp])  # squares of bf16 values are exact in binary32
-            mean = f32(s1 / stat_group)
-            var = f32(f32(s2 / stat_group) - mean * mean)  # fused: one rounding
+            s2 = pairwise([v * v for v in grp])  # squares of 16-bit values are exact in binary32
+            mean = f32(s1 / len(grp))                      # a short last group has its own count
+            var = f32(f32(s2 / len(grp)) - mean * mean)    # fused: one rounding
             if var < 0:
                 var = Fraction(0)
             limit = f32(k2 * var)
@@ -106,7 +142,7 @@ def select(bits, mode, stat_group, thresh: Fraction, topk):
                 out[g0 + i] = v * v > limit
     elif mode == TOPK:
         for g0 in range(0, n, stat_group):
-            order = sorted(range(g0, g0 + stat_group), key=lambda i: (-(bits[i] & 0x7FFF), i))
+            order = sorted(range(g0, min(n, g0 + stat_group)), key=lambda i: (-(bits[i] & 0x7FFF), i))
             for i in order[:topk]:
                 out[i] = True
     if mode != NONE:
@@ -116,16 +152,17 @@ def select(bits, mode, stat_group, thresh: Fraction, topk):
     return out
 
 
-def compress(bits, *, nbits, quant_group, asym, rule, mode, stat_group=0, thresh=Fraction(0), topk=0):
-    """Returns a dict: codes, packed, scale, zp (Fractions), out_idx, out_val."""
+def compress(bits, *, nbits, quant_group, asym, rule, mode, stat_group=0, thresh=Fraction(0), topk=0, fmt=BF16):
+    """Returns a dict: codes, packed, scale, zp (Fractions), out_idx, out_val.  Groups are cut from the
+    start of the flat array; the last one of either kind may be short."""
     n = len(bits)
     q = 1 << (nbits - 1)
-    out = select(bits, mode, stat_group, thresh, topk)
+    out = select(bits, mode, stat_group, thresh, topk, fmt)
     out_idx = [i for i in range(n) if out[i]]
     out_val = [bits[i] for i in out_idx]
     y = []
     for i, b in enumerate(bits):
-        v = bf16_value(b)
+        v = value_of(b, fmt)
         y.append(Fraction(0) if (out[i] or v is None) else v)
     codes, scale, zp = [], [], []
     for g0 in range(0, n, quant_group):
@@ -157,8 +194,8 @@ def compress(bits, *, nbits, quant_group, asym, rule, mode, stat_group=0, thresh
     return dict(codes=codes, packed=packed, scale=scale, zp=zp, out_idx=out_idx, out_val=out_val)
 
 
-def decompress(c, *, n, nbits, quant_group, asym):
-    """Returns (list of Fractions or None for a non-finite outlier, list of bf16 bit patterns)."""
+def decompress(c, *, n, nbits, quant_group, asym, fmt=BF16):
+    """Returns (list of Fractions or None for a non-finite outlier, list of 16-bit patterns)."""
     xs, bs = [], []
     for i in range(n):
         if nbits == 8:
@@ -169,8 +206,8 @@ def decompress(c, *, n, nbits, quant_group, asym):
         s = c["scale"][i // quant_group]
         v = f32(code * s + c["zp"][i // quant_group]) if asym else f32(code * s)
         xs.append(v)
-        bs.append(bf16_bits_of(v))
+        bs.append(bits_of_value(v, fmt))
     for i, b in zip(c["out_idx"], c["out_val"]):
-        xs[i] = bf16_value(b)
+        xs[i] = value_of(b, fmt)
         bs[i] = b
     return xs, bs

@@ -35,14 +35,14 @@ def tensors(seed, n):
     return [to_bf16_bits(a), to_bf16_bits(b), to_bf16_bits(c), d]
 
 
-def check(bits, nbits, gq, asym, rule, mode, gs=0, thresh=0.0, topk=0):
+def check(bits, nbits, gq, asym, rule, mode, gs=0, thresh=0.0, topk=0, fmt=bf.BF16):
     n = bits.size
     m = Method(bits=nbits, quant_group=gq, asym=asym, scale_rule=rule, outlier_mode=MODES[mode], stat_group=gs,
-               thresh=thresh, topk=topk)
+               thresh=thresh, topk=topk, dtype=fmt)
     oc = oracle.compress(m, bits)
     t32 = Fraction(float(np.float32(thresh)))
     want = bf.compress([int(b) for b in bits], nbits=nbits, quant_group=gq, asym=asym, rule=rule, mode=MODES[mode],
-                       stat_group=gs, thresh=t32, topk=topk)
+                       stat_group=gs, thresh=t32, topk=topk, fmt=fmt)
     assert list(oc.out_idx) == want["out_idx"], "outlier indices"
     assert [int(v) for v in oc.out_val] == want["out_val"], "outlier values"
     assert oc.n_out == len(want["out_idx"])
@@ -52,13 +52,13 @@ def check(bits, nbits, gq, asym, rule, mode, gs=0, thresh=0.0, topk=0):
     if asym:
         assert [Fraction(float(z)) for z in oc.zp] == want["zp"], "offsets"
     f, b = oracle.decompress(oc)
-    xs, bs = bf.decompress(want, n=n, nbits=nbits, quant_group=gq, asym=asym)
+    xs, bs = bf.decompress(want, n=n, nbits=nbits, quant_group=gq, asym=asym, fmt=fmt)
     for i in range(n):
         if xs[i] is None:  # a non-finite outlier: the stored pattern comes back
             assert int(b[i]) == bs[i] and not np.isfinite(f[i])
         else:
             assert Fraction(float(f[i])) == xs[i], f"binary32 reconstruction of element {i}"
-            assert int(b[i]) == bs[i], f"bf16 reconstruction of element {i}"
+            assert int(b[i]) == bs[i], f"16-bit reconstruction of element {i}"
     return oc
 
 
@@ -119,3 +119,93 @@ def test_rounding_helpers_of_the_brute_force_against_numpy():
     for v, w in zip(x.numpy(), want):
         if np.isfinite(v) and (int(w) & 0x7F80) != 0x7F80:
             assert bf.bf16_bits_of(Fraction(float(v))) == int(w)
+
+
+# ------------------------------------------------------------------ binary16 tensors (the paper's own format)
+def to_f16_bits(a):
+    return np.asarray(a, dtype=np.float64).astype(np.float16).view(np.uint16)
+
+
+def f16_tensors(seed, n):
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal(n) * np.where(rng.random(n) < 0.1, 30.0, 1.0)
+    b = rng.integers(-9, 10, size=n).astype(np.float64) * 0.5
+    c = np.abs(rng.standard_normal(n)) * 300.0 + 0.125        # large: the reconstruction nears the end of the range
+    d = to_f16_bits(rng.standard_normal(n) * 1e-4)
+    d[::5] = 0x8000
+    d[1::7] = 0x0000
+    d[2::9] = rng.integers(1, 0x400, size=d[2::9].size)       # subnormal binary16
+    return [to_f16_bits(a), to_f16_bits(b), to_f16_bits(c), d]
+
+
+@pytest.mark.parametrize("mode", ["none", "abs", "std", "topk"])
+@pytest.mark.parametrize("nbits", [4, 8])
+@pytest.mark.parametrize("asym", [0, 1])
+def test_whole_chain_on_tiny_binary16_tensors(mode, nbits, asym):
+    n_out = 0
+    for rule in (bf.PAPER, bf.FULLRANGE):
+        for bits in f16_tensors(70 + nbits + asym, 32):
+            kw = dict(abs=dict(thresh=1.75), std=dict(gs=16, thresh=1.5), topk=dict(gs=16, topk=3), none={})[mode]
+            n_out += check(bits, nbits, 8, asym, rule, mode, fmt=bf.F16, **kw).n_out
+    assert (n_out > 0) == (mode != "none")
+
+
+def test_binary16_values_that_are_not_finite_and_the_largest_finite_ones():
+    bits = f16_tensors(3, 32)[0]
+    bits[3], bits[4], bits[20] = 0x7C00, 0xFE01, 0xFC00   # +Inf, a NaN, -Inf
+    bits[8], bits[9] = 0x7BFF, 0xFBFF                       # +-65504
+    for asym in (0, 1):
+        oc = check(bits, 4, 8, asym, bf.PAPER, "topk", gs=16, topk=1, fmt=bf.F16)
+        assert {3, 4, 20} <= set(int(i) for i in oc.out_idx)
+        check(bits, 8, 8, asym, bf.FULLRANGE, "abs", thresh=70000.0, fmt=bf.F16)  # only what is not finite is kept
+
+
+# ------------------------------------------------------------------ a last group that is short
+@pytest.mark.parametrize("fmt", [bf.BF16, bf.F16])
+@pytest.mark.parametrize("nbits", [4, 8])
+@pytest.mark.parametrize("asym", [0, 1])
+def test_short_last_groups(fmt, nbits, asym):
+    """The group length divides the tensor's length in neither case; 27 and 29 elements in quantisation
+    groups of 8 and statistics groups of 16: the last quantisation group has 3 (5) elements, the last
+    statistics group 11 (13), and with int4 the last byte holds one element."""
+    for n in (27, 29):
+        src = f16_tensors(90 + n, n) if fmt == bf.F16 else tensors(90 + n, n)
+        for bits in src:
+            check(bits, nbits, 8, asym, bf.PAPER, "none", fmt=fmt)
+            check(bits, nbits, 8, asym, bf.FULLRANGE, "abs", thresh=1.0, fmt=fmt)
+            check(bits, nbits, 8, asym, bf.PAPER, "std", gs=16, thresh=1.25, fmt=fmt)
+            check(bits, nbits, 8, asym, bf.PAPER, "topk", gs=16, topk=3, fmt=fmt)
+    # a last statistics group with fewer elements than k: all of it is kept, and no more
+    bits = (f16_tensors(5, 18) if fmt == bf.F16 else tensors(5, 18))[0]
+    oc = check(bits, nbits, 8, asym, bf.PAPER, "topk", gs=16, topk=3, fmt=fmt)
+    assert [int(i) for i in oc.out_idx if i >= 16] == [16, 17] and oc.n_out == 5
+
+
+def test_a_short_last_group_is_a_group_of_its_own():
+    """Groups do not see each other: the result for a tensor with a short last group is the result for
+    the whole groups followed by the result for the rest taken as a tensor of its own."""
+    rng = np.random.default_rng(12)
+    x = to_bf16_bits(rng.standard_normal(1000) * np.where(rng.random(1000) < 0.05, 25.0, 1.0))
+    for m in (Method(bits=4, quant_group=64, outlier_mode=2, stat_group=128, thresh=2.0),
+              Method(bits=8, quant_group=128, asym=1, outlier_mode=3, stat_group=128, topk=2)):
+        whole = oracle.compress(m, x)
+        head, tail = oracle.compress(m, x[:896]), oracle.compress(m, x[896:])   # 896 = 7 * 128
+        assert np.array_equal(whole.codes, np.concatenate([head.codes, tail.codes]))
+        assert np.array_equal(whole.scale.view(np.uint32), np.concatenate([head.scale, tail.scale]).view(np.uint32))
+        assert list(whole.out_idx) == list(head.out_idx) + [int(i) + 896 for i in tail.out_idx]
+        assert tail.scale.size == -(-104 // m.quant_group)  # 104 elements: 64 + 40, or one group of 104
+
+
+def test_rounding_helpers_of_the_brute_force_for_binary16_against_numpy():
+    pats = np.arange(0x10000, dtype=np.uint32)
+    pats = pats[(pats & 0x7C00) != 0x7C00].astype(np.uint16)
+    vals = pats.view(np.float16).astype(np.float64)
+    for p, v in zip(pats[::29], vals[::29]):
+        assert bf.f16_value(int(p)) == Fraction(float(v))
+    rng = np.random.default_rng(6)
+    x = (rng.standard_normal(4000) * 10.0 ** rng.integers(-9, 6, size=4000)).astype(np.float32)
+    x = np.concatenate([x, np.float32([65504, 65519.99, 65520, -65520, 1e9, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -25])])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    for v, w in zip(x, want):
+        assert bf.f16_bits_of(Fraction(float(v))) == int(w), float(v)

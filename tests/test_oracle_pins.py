@@ -127,6 +127,50 @@ def test_widen_and_round_match_torch():
     assert np.array_equal(b, bf16_bits(f))
 
 
+def test_binary16_widen_and_round_match_torch():
+    """The paper compresses FP16 activations (Section 3.2, "compressed from FP16 to INT4").  The oracle's
+    binary16 -> binary32 widening on every one of the 65 536 patterns, and its binary32 -> binary16
+    rounding on random values, on every tie between two neighbouring binary16 values and the binary32
+    values next to it, and at the end of the range, against torch."""
+    allbits = np.arange(65536, dtype=np.uint16)
+    got = oracle.to_f32(allbits, oracle.DT_F16)
+    want = torch.from_numpy(allbits.view(np.int16).copy()).view(torch.float16).to(torch.float32).numpy()
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan) and nan.sum() == 2 * 1023
+    assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+    # rounding: ties and their neighbours
+    fin = allbits[(allbits & 0x7C00) != 0x7C00]
+    pos = np.sort(fin[fin < 0x8000])                      # 0 .. 65504 in ascending order
+    v = want[pos].astype(np.float64)
+    mid = ((v[:-1] + v[1:]) / 2).astype(np.float32)       # exact in binary32: 12 significant bits
+    assert np.array_equal(mid.astype(np.float64), (v[:-1] + v[1:]) / 2)
+    cases = np.concatenate([mid, np.nextafter(mid, np.float32(np.inf)), np.nextafter(mid, np.float32(-np.inf)),
+                            np.float32([0.0, -0.0, 65504, 65519.996, 65520, 65536, 1e30, np.inf, 2.0 ** -24,
+                                        2.0 ** -25, np.nextafter(np.float32(2.0 ** -25), np.float32(1)), 1e-30])])
+    g = np.random.default_rng(17)
+    rnd = (g.standard_normal(20000) * 10.0 ** g.integers(-10, 6, 20000)).astype(np.float32)
+    cases = np.concatenate([cases, -cases, rnd])
+    got = oracle.from_f32(cases, oracle.DT_F16)
+    want16 = torch.from_numpy(cases).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want16)
+    assert oracle.from_f32(np.float32([np.nan]), oracle.DT_F16)[0] & 0x7FFF > 0x7C00
+    # and through the whole chain: with tau = 0 every non-zero element is kept and comes back bit for bit
+    m = Method(bits=8, quant_group=65536, outlier_mode=OUT_ABS, thresh=0.0, dtype=oracle.DT_F16)
+    f, b = oracle.decompress(oracle.compress(m, allbits))
+    nz = (allbits & 0x7FFF) != 0
+    assert np.array_equal(b[nz], allbits[nz])
+
+
+def test_binary16_channel_scores_are_the_exactly_rounded_sums():
+    import math
+    g = np.random.default_rng(23)
+    tokens, hidden = 300, 24
+    x = (g.standard_normal((tokens, hidden)) * 10.0 ** g.integers(-7, 4, (tokens, hidden))).astype(np.float16)
+    S = oracle.channel_scores(x.view(np.uint16), tokens, hidden, oracle.DT_F16)
+    for h in range(hidden):
+        assert S[h] == math.fsum(abs(float(v)) for v in x[:, h])
+
+
 # ----------------------------------------------------------------- pairwise sum
 def test_pairwise_sum_order_is_a_binary_tree():
     # hand-worked in binary32: (1e8+1)=1e8, (-1e8+1)=-1e8, sum 0.  Left-to-right would give 1.
@@ -447,7 +491,7 @@ def test_capacity_truncates_the_stream_but_not_the_count():
 
 def test_malformed_methods_are_rejected():
     x = np.zeros(128, dtype=np.uint16)
-    for m in (Method(bits=5, quant_group=64), Method(bits=8, quant_group=48),
+    for m in (Method(bits=5, quant_group=64), Method(bits=8, quant_group=0), Method(bits=8, quant_group=64, dtype=2),
               Method(bits=8, quant_group=64, outlier_mode=OUT_STD, stat_group=0, thresh=1.0),
               Method(bits=8, quant_group=64, outlier_mode=OUT_TOPK, stat_group=64, topk=0)):
         with pytest.raises(ValueError):
