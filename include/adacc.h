@@ -1,6 +1,6 @@
 /*
  * adacc.h - C ABI of libadacc: outlier-separated quantising compression of saved
- * bf16 activation tensors on AMD MI355X (gfx950), after Adacc (arXiv 2508.00806),
+ * 16-bit (bf16 or binary16) activation tensors on AMD MI355X (gfx950), after Adacc (arXiv 2508.00806),
  * Section 3.2 "Layer-specific Compression".
  *
  * What the library computes (Section 3.2, Fig. 3(c), Eq. 2 and Eq. 3):
@@ -10,7 +10,7 @@
  *                one binary32 scale S (and, asymmetric, one offset O) per group;
  *   decompress : code * S (+ O), then the outliers are written back.
  * The paper quantises FP16 to INT4 and picks whole outlier channels; this
- * library takes bf16, b in {4, 8}, and picks single elements by one of three
+ * library takes bf16 or FP16 (adacc_method.dtype), b in {4, 8}, and picks single elements by one of three
  * rules (absolute threshold, multiple of the group's standard deviation, k
  * largest magnitudes); the paper's own rule, whole channels by Z-score (Eq. 1),
  * is served by the adacc_channel_* calls.  All arithmetic has a fixed precision
@@ -54,6 +54,9 @@ extern "C" {
 #define ADACC_OUTLIER_STD 2  /* x*x > thresh^2 * var(stat group), population variance about the mean */
 #define ADACC_OUTLIER_TOPK 3 /* the topk largest |x| of every stat group, ties to the lower index */
 
+#define ADACC_DTYPE_BF16 0 /* bfloat16                                                */
+#define ADACC_DTYPE_F16 1  /* IEEE binary16, the format the paper compresses (Section 3.2) */
+
 #define ADACC_SCALE_PAPER 0     /* Eq. 2: S = max|X| / 2^(b-1);  Eq. 3: S = (max-min) / 2^b */
 #define ADACC_SCALE_FULLRANGE 1 /* S = max|X| / (2^(b-1)-1);     S = (max-min) / (2^b-1)    */
 
@@ -68,6 +71,8 @@ typedef struct adacc_method {
   float thresh;          /* ABS: tau >= 0.  STD: k >= 0 (the library forms k*k in binary32)  */
   uint32_t topk;         /* TOPK: 1..32 outliers per stat group                              */
   uint32_t max_outliers; /* capacity of the outlier stream of the blob (0 allowed for NONE)  */
+  uint32_t dtype;        /* ADACC_DTYPE_*: the 16-bit format of the tensor, of the outlier values kept in
+                            the blob and of the 16-bit output of decompression                */
 } adacc_method;
 
 /* ---- blob layout ----
@@ -80,7 +85,7 @@ typedef struct adacc_method {
  *   tile_ptr (n_tiles+1) uint32: tile t (elements [t*tile_elems, (t+1)*tile_elems))
  *            owns outliers [tile_ptr[t], tile_ptr[t+1]) of the stream; tile_ptr[n_tiles]
  *            is the total count.  Empty for ADACC_OUTLIER_NONE.
- *   idx,val  max_outliers int32 flat indices, ascending, and the bf16 bit patterns at
+ *   idx,val  max_outliers int32 flat indices, ascending, and the 16-bit patterns of the tensor at
  *            those indices (structure of arrays).  Entries past the count are unspecified.
  *   status   4 uint32: [0] number of outliers found, [1] 1 if it exceeds max_outliers
  *            (the stream then holds the first max_outliers; the blob is not usable), [2], [3] 0.
@@ -124,7 +129,7 @@ int adacc_workspace_init(adacc_workspace *ws, void *device_mem, uint64_t bytes, 
 
 /* ---- single tensor ----
  * adacc_compress: Section 3.2 / Fig. 3(c) compression workflow.
- *   src   numel bf16, 16-byte aligned, never modified (the zeroing of outliers happens in registers)
+ *   src   numel 16-bit values of method->dtype, 16-byte aligned, never modified (the zeroing of outliers happens in registers)
  *   blob  at least adacc_layout_of(...).total_bytes, 256-byte aligned
  *   ws    an initialised workspace of at least adacc_workspace_bytes(...); may be NULL for
  *         ADACC_OUTLIER_NONE
@@ -149,10 +154,12 @@ int adacc_compress_noalloc(const adacc_method *method, const void *src, uint64_t
 
 /* adacc_decompress: Section 3.2 dequantisation (X^ = code*S, resp. code*S+O) followed by
  * the write-back of the outliers (Fig. 3(c) decompression workflow).
- *   dst_dtype 0: bf16 (round-to-nearest-even of the binary32 result; outliers bit-exact)
- *             1: binary32
+ *   dst_dtype ADACC_DST_16:  the tensor's own 16-bit format, method->dtype (round-to-nearest-even of the
+ *                            binary32 result, too large becomes infinite; outliers bit-exact)
+ *             ADACC_DST_F32: binary32
  *   dst   numel elements of that type, 16-byte aligned */
-#define ADACC_DST_BF16 0
+#define ADACC_DST_16 0
+#define ADACC_DST_BF16 ADACC_DST_16 /* the same, for a bf16 tensor */
 #define ADACC_DST_F32 1
 int adacc_decompress(const adacc_method *method, const void *blob, uint64_t blob_bytes, uint64_t numel,
                      void *dst, int dst_dtype, void *hip_stream);
@@ -198,6 +205,7 @@ typedef struct adacc_channel_method {
   uint32_t scale_rule;   /* ADACC_SCALE_*                                             */
   float z_thresh;        /* threshold on Z (finite)                                   */
   uint32_t max_channels; /* outlier channels the blob has room for                    */
+  uint32_t dtype;        /* ADACC_DTYPE_*, as in adacc_method                         */
 } adacc_channel_method;
 
 /* Blob sections (each on a 256-byte boundary):
@@ -205,7 +213,7 @@ typedef struct adacc_channel_method {
  *   ch_mask  hidden/8 bytes: bit (h & 7) of byte h >> 3 is set for an outlier channel
  *   ch_base  hidden/8 uint32: number of outlier channels below channel 8 * (h >> 3)
  *   ch_idx   max_channels int32: the outlier channels, ascending
- *   ch_val   room for tokens * max_channels bf16; used as [tokens][n_ch]: ch_val[t * n_ch + r] is
+ *   ch_val   room for tokens * max_channels 16-bit values; used as [tokens][n_ch]: ch_val[t * n_ch + r] is
  *            channel ch_idx[r] of token t, bit for bit
  *   status   4 uint32: [0] n_ch, the number of outlier channels found, [1] 1 if n_ch exceeds
  *            max_channels (then only ch_mask, ch_base, the first max_channels entries of ch_idx
@@ -223,7 +231,7 @@ int adacc_channel_layout_of(const adacc_channel_method *method, uint64_t tokens,
  * shared by calls that follow each other on one stream. */
 uint64_t adacc_channel_workspace_bytes(uint64_t tokens, uint32_t hidden);
 /* Enqueues the four kernels: chunk sums, channel sums, Eq. 1 selection, quantisation of the rest
- * with extraction of the outlier channels.  src: tokens*hidden bf16, 16-byte aligned, not modified.
+ * with extraction of the outlier channels.  src: tokens*hidden 16-bit values, 16-byte aligned, not modified.
  * tokens == 0: ADACC_OK, nothing is touched.  Errors: ENULL, EINVAL, ESIZE, EALIGN, EHIP. */
 int adacc_channel_compress(const adacc_channel_method *method, const void *src, uint64_t tokens, uint32_t hidden,
                            void *blob, uint64_t blob_bytes, void *workspace, uint64_t workspace_bytes,
@@ -252,11 +260,12 @@ typedef struct adacc_channelwise_layout {
 } adacc_channelwise_layout;
 int adacc_channelwise_layout_of(uint32_t bits, uint64_t tokens, uint32_t hidden, adacc_channelwise_layout *out);
 uint64_t adacc_channelwise_workspace_bytes(uint64_t tokens, uint32_t hidden);
-int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, const void *src, uint64_t tokens,
+int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, uint32_t dtype, const void *src, uint64_t tokens,
                                uint32_t hidden, void *blob, uint64_t blob_bytes, void *workspace,
                                uint64_t workspace_bytes, void *hip_stream);
-/* X^ = code * S_h; dst and dst_dtype as in adacc_decompress. */
-int adacc_channelwise_decompress(uint32_t bits, const void *blob, uint64_t blob_bytes, uint64_t tokens,
+/* X^ = code * S_h; dst and dst_dtype as in adacc_decompress, dtype (ADACC_DTYPE_*) names the 16-bit
+ * format ADACC_DST_16 stands for. */
+int adacc_channelwise_decompress(uint32_t bits, uint32_t dtype, const void *blob, uint64_t blob_bytes, uint64_t tokens,
                                  uint32_t hidden, void *dst, int dst_dtype, void *hip_stream);
 
 /* ---- dropout mask of attention layers: byte format <-> bit format, lossless (Section 3.2,
@@ -280,7 +289,7 @@ int adacc_mask_unpack(const void *bits, uint64_t n, void *mask, void *hip_stream
 uint64_t adacc_compressed_bytes(const adacc_method *method, uint64_t numel, uint64_t n_outliers);
 /* The same figure for a [tokens, hidden] tensor compressed by outlier channels (Section 3.2, Eq. 1) that
  * produced n_channels of them: codes + scales (+ offsets) of the whole tensor + per outlier channel its
- * index (4 bytes) and its tokens values in bf16.  The channel bitmap and prefix table are derived from the
+ * index (4 bytes) and its tokens values (2 bytes each).  The channel bitmap and prefix table are derived from the
  * indices and are not counted.  Returns 0 for a malformed method or shape. */
 uint64_t adacc_channel_compressed_bytes(const adacc_channel_method *method, uint64_t tokens, uint32_t hidden,
                                         uint64_t n_channels);

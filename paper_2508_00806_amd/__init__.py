@@ -17,7 +17,9 @@ OK, EINVAL, ENULL, ESIZE, EALIGN, EHIP, ELIMIT = 0, -1, -2, -3, -4, -5, -6
 KIND_NOOP, KIND_QUANT = 0, 1
 OUTLIER_NONE, OUTLIER_ABS, OUTLIER_STD, OUTLIER_TOPK = 0, 1, 2, 3
 SCALE_PAPER, SCALE_FULLRANGE = 0, 1
-DST_BF16, DST_F32 = 0, 1
+DST_16, DST_F32 = 0, 1
+DST_BF16 = DST_16
+DTYPE_BF16, DTYPE_F16 = 0, 1
 
 EXPORTS = ("adacc_layout_of", "adacc_workspace_bytes", "adacc_workspace_init", "adacc_compress", "adacc_compress_noalloc",
            "adacc_decompress", "adacc_batch_workspace_bytes", "adacc_compress_batch",
@@ -34,7 +36,7 @@ class CMethod(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_uint32), ("bits", ctypes.c_uint32), ("quant_group", ctypes.c_uint32),
                 ("asym", ctypes.c_uint32), ("scale_rule", ctypes.c_uint32), ("outlier_mode", ctypes.c_uint32),
                 ("stat_group", ctypes.c_uint32), ("thresh", ctypes.c_float), ("topk", ctypes.c_uint32),
-                ("max_outliers", ctypes.c_uint32)]
+                ("max_outliers", ctypes.c_uint32), ("dtype", ctypes.c_uint32)]
 
 
 class CLayout(ctypes.Structure):
@@ -51,7 +53,8 @@ class CWorkspace(ctypes.Structure):
 
 class CChannelMethod(ctypes.Structure):
     _fields_ = [("bits", ctypes.c_uint32), ("quant_group", ctypes.c_uint32), ("asym", ctypes.c_uint32),
-                ("scale_rule", ctypes.c_uint32), ("z_thresh", ctypes.c_float), ("max_channels", ctypes.c_uint32)]
+                ("scale_rule", ctypes.c_uint32), ("z_thresh", ctypes.c_float), ("max_channels", ctypes.c_uint32),
+                ("dtype", ctypes.c_uint32)]
 
 
 class CChannelLayout(ctypes.Structure):
@@ -72,10 +75,11 @@ class ChannelMethod:
     scale_rule: int = SCALE_PAPER
     z_thresh: float = 3.0
     max_channels: int = 64
+    dtype: int = DTYPE_BF16
 
     def c(self) -> CChannelMethod:
         return CChannelMethod(self.bits, self.quant_group, self.asym, self.scale_rule, float(self.z_thresh),
-                              self.max_channels)
+                              self.max_channels, self.dtype)
 
 
 @dataclass
@@ -90,10 +94,11 @@ class Method:
     thresh: float = 0.0
     topk: int = 0
     max_outliers: int = 0
+    dtype: int = DTYPE_BF16
 
     def c(self) -> CMethod:
         return CMethod(self.kind, self.bits, self.quant_group, self.asym, self.scale_rule, self.outlier_mode,
-                       self.stat_group, float(self.thresh), self.topk, self.max_outliers)
+                       self.stat_group, float(self.thresh), self.topk, self.max_outliers, self.dtype)
 
 
 NOOP = Method(kind=KIND_NOOP, bits=0, quant_group=0)
@@ -101,14 +106,15 @@ NOOP = Method(kind=KIND_NOOP, bits=0, quant_group=0)
 OUTLIER_MODE_BY_NAME = {"none": OUTLIER_NONE, "abs": OUTLIER_ABS, "std": OUTLIER_STD, "topk": OUTLIER_TOPK}
 
 
-def method_from_dict(md, max_outliers: int, scale_rule: int = SCALE_PAPER) -> Method:
+def method_from_dict(md, max_outliers: int, scale_rule: int = SCALE_PAPER, dtype: int = DTYPE_BF16) -> Method:
     """A method written as a plain dictionary (keys bits, quant_group, asym, outlier_mode by name,
     stat_group, thresh, topk) as the library's descriptor; None = retain the tensor as it is."""
     if md is None:
         return NOOP
     return Method(kind=KIND_QUANT, bits=md["bits"], quant_group=md["quant_group"], asym=md["asym"],
                   scale_rule=scale_rule, outlier_mode=OUTLIER_MODE_BY_NAME[md["outlier_mode"]],
-                  stat_group=md["stat_group"], thresh=md["thresh"], topk=md["topk"], max_outliers=max_outliers)
+                  stat_group=md["stat_group"], thresh=md["thresh"], topk=md["topk"], max_outliers=max_outliers,
+                  dtype=dtype)
 
 
 class AdaccError(RuntimeError):
@@ -183,9 +189,9 @@ def lib():
         L.adacc_channelwise_layout_of.restype = ci
         L.adacc_channelwise_workspace_bytes.argtypes = [u64, u32]
         L.adacc_channelwise_workspace_bytes.restype = u64
-        L.adacc_channelwise_compress.argtypes = [u32, u32, vp, u64, u32, vp, u64, vp, u64, vp]
+        L.adacc_channelwise_compress.argtypes = [u32, u32, u32, vp, u64, u32, vp, u64, vp, u64, vp]
         L.adacc_channelwise_compress.restype = ci
-        L.adacc_channelwise_decompress.argtypes = [u32, vp, u64, u64, u32, vp, ci, vp]
+        L.adacc_channelwise_decompress.argtypes = [u32, u32, vp, u64, u64, u32, vp, ci, vp]
         L.adacc_channelwise_decompress.restype = ci
         L.adacc_version.argtypes = []
         L.adacc_version.restype = ctypes.c_char_p
@@ -204,6 +210,22 @@ def version() -> str:
 def _check(rc, where):
     if rc != OK:
         raise AdaccError(rc, where)
+
+
+def torch_dtype(dtype: int):
+    """The torch dtype of a tensor in the 16-bit format DTYPE_*."""
+    import torch
+    return torch.float16 if dtype == DTYPE_F16 else torch.bfloat16
+
+
+def _dst_dtype(dst, dtype: int) -> int:
+    """ABI code for the element type of dst: binary32, or the 16-bit format `dtype` names."""
+    import torch
+    if dst.dtype == torch.float32:
+        return DST_F32
+    if dst.dtype != torch_dtype(dtype):
+        raise TypeError(f"dst must be float32 or {torch_dtype(dtype)}, the tensor's own format")
+    return DST_16
 
 
 def _ptr(t):
@@ -292,9 +314,7 @@ def compress_noalloc(method: Method, src, blob, numel=None, stream=None):
 def decompress(method: Method, blob, dst, numel=None, stream=None):
     import torch
     numel = dst.numel() if numel is None else numel
-    dtype = DST_F32 if dst.dtype == torch.float32 else DST_BF16
-    if dst.dtype not in (torch.float32, torch.bfloat16):
-        raise TypeError("dst must be bfloat16 or float32")
+    dtype = _dst_dtype(dst, method.dtype)
     cm = method.c()
     _check(lib().adacc_decompress(ctypes.byref(cm), _ptr(blob), _nbytes(blob), numel, _ptr(dst), dtype,
                                   _stream(stream)), "adacc_decompress")
@@ -326,11 +346,11 @@ def prepare_compress_batch(methods, srcs, blobs) -> BatchArgs:
 
 def prepare_decompress_batch(methods, blobs, dsts) -> BatchArgs:
     import torch
-    kinds = {d.dtype for d in dsts if d is not None}
+    kinds = {_dst_dtype(d, m.dtype) for m, d in zip(methods, dsts) if d is not None}
     if len(kinds) > 1:
-        raise TypeError("all dsts of a batch share one dtype")
+        raise TypeError("the dsts of a batch are all float32 or all in their tensors' own formats")
     args = BatchArgs(methods, blobs, dsts, [0 if d is None else d.numel() for d in dsts], blobs)
-    args.dst_dtype = DST_F32 if kinds == {torch.float32} else DST_BF16
+    args.dst_dtype = DST_F32 if kinds == {DST_F32} else DST_16
     return args
 
 
@@ -395,9 +415,7 @@ def channel_compress(method: ChannelMethod, src, tokens: int, hidden: int, blob,
 
 def channel_decompress(method: ChannelMethod, blob, tokens: int, hidden: int, dst, stream=None):
     import torch
-    if dst.dtype not in (torch.float32, torch.bfloat16):
-        raise TypeError("dst must be bfloat16 or float32")
-    dtype = DST_F32 if dst.dtype == torch.float32 else DST_BF16
+    dtype = _dst_dtype(dst, method.dtype)
     cm = method.c()
     _check(lib().adacc_channel_decompress(ctypes.byref(cm), _ptr(blob), _nbytes(blob), tokens, hidden, _ptr(dst),
                                           dtype, _stream(stream)), "adacc_channel_decompress")
@@ -457,17 +475,20 @@ def channelwise_workspace_bytes(tokens: int, hidden: int) -> int:
 
 
 def channelwise_compress(bits: int, src, tokens: int, hidden: int, blob, workspace, scale_rule=SCALE_PAPER, stream=None):
-    _check(lib().adacc_channelwise_compress(bits, scale_rule, _ptr(src), tokens, hidden, _ptr(blob), _nbytes(blob),
+    import torch
+    dtype = DTYPE_F16 if getattr(src, "dtype", None) == torch.float16 else DTYPE_BF16
+    _check(lib().adacc_channelwise_compress(bits, scale_rule, dtype, _ptr(src), tokens, hidden, _ptr(blob), _nbytes(blob),
                                             _ptr(workspace), _nbytes(workspace), _stream(stream)),
            "adacc_channelwise_compress")
 
 
 def channelwise_decompress(bits: int, blob, tokens: int, hidden: int, dst, stream=None):
     import torch
-    if dst.dtype not in (torch.float32, torch.bfloat16):
-        raise TypeError("dst must be bfloat16 or float32")
-    dtype = DST_F32 if dst.dtype == torch.float32 else DST_BF16
-    _check(lib().adacc_channelwise_decompress(bits, _ptr(blob), _nbytes(blob), tokens, hidden, _ptr(dst), dtype,
+    if dst.dtype not in (torch.float32, torch.bfloat16, torch.float16):
+        raise TypeError("dst must be bfloat16, float16 or float32")
+    fmt = DTYPE_F16 if dst.dtype == torch.float16 else DTYPE_BF16
+    dtype = DST_F32 if dst.dtype == torch.float32 else DST_16
+    _check(lib().adacc_channelwise_decompress(bits, fmt, _ptr(blob), _nbytes(blob), tokens, hidden, _ptr(dst), dtype,
                                               _stream(stream)), "adacc_channelwise_decompress")
 
 

@@ -8,18 +8,26 @@ ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libadacc.so")
 CSRC = os.path.join(HERE, "csrc")
 # one translation unit per group of kernel instantiations, so that the library builds in parallel
-SOURCES = [os.path.join(CSRC, f) for f in (
-    "adacc.hip",              # host code, C ABI, utility kernels
+# Sources that touch the tensor's elements are compiled once per 16-bit format (bf16; binary16 with -DADACC_F16=1).
+PER_FORMAT = (
     "adacc_k_none.hip", "adacc_k_abs.hip", "adacc_k_std.hip", "adacc_k_topk.hip",  # compress, per outlier mode
     "adacc_k_decompress.hip",
     "adacc_k_batch4.hip", "adacc_k_batch8.hip",
     "adacc_k_place.hip",      # placement of the outliers in the stream
     "adacc_k_channel.hip",    # outlier channels by Z-score
-    "adacc_k_mask.hip",       # dropout mask, byte <-> bit
     "adacc_k_channelwise.hip",  # channel-wise symmetric quantisation (Q / K / V)
-)]
-HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_compress.hpp", "adacc_decompress.hpp",
-                                           "adacc_kernels.hpp", "adacc_fn.hpp", "adacc_channel.hpp")]
+)
+ONCE = (
+    "adacc.hip",              # host code, C ABI, utility kernels
+    "adacc_k_mask.hip",       # dropout mask, byte <-> bit
+)
+# (source, object suffix, extra flags); the long ones first
+SOURCES = ([(os.path.join(CSRC, f), "", ()) for f in PER_FORMAT] +
+           [(os.path.join(CSRC, f), "_f16", ("-DADACC_F16=1",)) for f in PER_FORMAT] +
+           [(os.path.join(CSRC, f), "", ()) for f in ONCE])
+HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_dtype.hpp", "adacc_compress.hpp",
+                                           "adacc_decompress.hpp", "adacc_kernels.hpp", "adacc_fn.hpp",
+                                           "adacc_channel.hpp")]
 HEADERS.append(os.path.join(ROOT, "include", "adacc.h"))
 OBJDIR = os.path.join(HERE, "_build")
 
@@ -39,9 +47,10 @@ def build(verbose: bool = False, extra=(), jobs: int = 8) -> str:
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     tag = os.path.splitext(os.path.basename(LIB))[0]
 
-    def compile_one(src):
-        obj = os.path.join(OBJDIR, tag + "_" + os.path.splitext(os.path.basename(src))[0] + ".o")
-        cmd = [HIPCC, *FLAGS, *extra, *inc, "-c", src, "-o", obj]
+    def compile_one(item):
+        src, suffix, defines = item
+        obj = os.path.join(OBJDIR, tag + "_" + os.path.splitext(os.path.basename(src))[0] + suffix + ".o")
+        cmd = [HIPCC, *FLAGS, *defines, *extra, *inc, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

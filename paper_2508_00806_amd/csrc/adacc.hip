@@ -129,6 +129,7 @@ struct Plan {  // everything derived from (method, numel)
   bool outliers;
   uint32_t tile_elems, n_tiles, lgq, lgs, variant;
   bool rowwise;  // every group lies inside a 512-element row and both kinds of group coincide
+  bool half;     // the tensor is binary16 (else bf16)
   float param, divisor;
 };
 
@@ -138,6 +139,8 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   if (m->kind != ADACC_KIND_QUANT) return ADACC_EINVAL;
   if (m->bits != 4 && m->bits != 8) return ADACC_EINVAL;
   if (m->asym > 1 || m->scale_rule > 1 || m->outlier_mode > ADACC_OUTLIER_TOPK) return ADACC_EINVAL;
+  if (m->dtype > ADACC_DTYPE_F16) return ADACC_EINVAL;
+  p->half = m->dtype == ADACC_DTYPE_F16;
   if (!is_pow2(m->quant_group) || m->quant_group < 8 || m->quant_group > 4096) return ADACC_EINVAL;
   if (numel % m->quant_group != 0) return ADACC_EINVAL;
   uint32_t gs = m->quant_group;
@@ -320,17 +323,18 @@ static int grid_for(uint32_t n_tiles, const void* kernel, uint32_t* grid, int re
   return ADACC_OK;
 }
 
-BatchCompressFn compress_batch_fn4(int kind);
-BatchCompressFn compress_batch_fn8(int kind);
-BatchCompressFn compress_batch_fn(int kind) { return kind >= kBatchAny8 ? compress_batch_fn8(kind) : compress_batch_fn4(kind); }
+static BatchCompressFn compress_batch_fn(bool half, int kind) {
+  return kind >= kBatchAny8 ? ADACC_PICK(half, compress_batch_fn8(kind)) : ADACC_PICK(half, compress_batch_fn4(kind));
+}
 
 // `whole` (TOPK only): the statistics group is the whole tile; that case has kernels of its own
 static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise, bool whole) {
+  const bool half = m->dtype == ADACC_DTYPE_F16;
   switch (m->outlier_mode) {
-    case ADACC_OUTLIER_NONE: return compress_fn_none(m->bits, m->asym, e8, rowwise);
-    case ADACC_OUTLIER_ABS: return compress_fn_abs(m->bits, m->asym, e8, rowwise);
-    case ADACC_OUTLIER_STD: return compress_fn_std(m->bits, m->asym, e8, rowwise);
-    default: return compress_fn_topk(m->bits, m->asym, e8, whole);
+    case ADACC_OUTLIER_NONE: return ADACC_PICK(half, compress_fn_none(m->bits, m->asym, e8, rowwise));
+    case ADACC_OUTLIER_ABS: return ADACC_PICK(half, compress_fn_abs(m->bits, m->asym, e8, rowwise));
+    case ADACC_OUTLIER_STD: return ADACC_PICK(half, compress_fn_std(m->bits, m->asym, e8, rowwise));
+    default: return ADACC_PICK(half, compress_fn_topk(m->bits, m->asym, e8, whole));
   }
 }
 
@@ -409,7 +413,7 @@ struct GroupLaunch {
 // two of each other, at most 65535 entries per launch) and appends their member lists to `members`.
 static void group_launches(const std::vector<uint32_t>& units, const std::vector<int>& kind,
                            std::vector<uint32_t>* members, std::vector<GroupLaunch>* launches) {
-  for (int k = 0; k < kBatchKinds; ++k) {
+  for (int k = 0; k < 2 * kBatchKinds; ++k) {  // kinds of the second half: the same for binary16 tensors
     for (uint32_t bucket = 0; bucket <= 32; ++bucket) {
       GroupLaunch g = {(uint32_t)members->size(), 0u, 0u, k};
       for (uint32_t i = 0; i < units.size(); ++i) {
@@ -449,6 +453,7 @@ static int make_channel_plan(const adacc_channel_method* m, uint64_t tokens, uin
   cp->quant.asym = m->asym;
   cp->quant.scale_rule = m->scale_rule;
   cp->quant.outlier_mode = ADACC_OUTLIER_NONE;
+  cp->quant.dtype = m->dtype;
   cp->numel = tokens * hidden;
   const int rc = make_plan(&cp->quant, cp->numel, &cp->plan);
   if (rc != ADACC_OK) return rc;
@@ -577,11 +582,11 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
   rc = launch_check("compress_kernel");
   if (rc != ADACC_OK || !p.outliers) return rc;
   if (needs_block_sums(method, p)) {
-    hipLaunchKernelGGL(place_sum_fn(), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
+    hipLaunchKernelGGL(ADACC_PICK(p.half, place_sum_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
     rc = launch_check("place_sum_kernel");
     if (rc != ADACC_OK) return rc;
   }
-  hipLaunchKernelGGL(place_fn(), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
+  hipLaunchKernelGGL(ADACC_PICK(p.half, place_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
   return launch_check("place_kernel");
 }
 
@@ -630,7 +635,7 @@ int adacc_compress_noalloc(const adacc_method* method, const void* src, uint64_t
 int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob_bytes, uint64_t numel, void* dst,
                      int dst_dtype, void* hip_stream) {
   if (!method) return ADACC_ENULL;
-  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  if (dst_dtype != ADACC_DST_16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
   Plan p;
   int rc = make_plan(method, numel, &p);
   if (rc != ADACC_OK) return rc;
@@ -642,7 +647,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, nullptr, &d);
-  DecompressFn fn = decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
+  DecompressFn fn = ADACC_PICK(p.half, decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
   uint32_t grid = 0;
   rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid);
   if (rc != ADACC_OK) return rc;
@@ -732,11 +737,14 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   std::vector<uint32_t> units(nt), members;
   std::vector<int> kind(nt);
   std::vector<GroupLaunch> tiles, sums, places;
-  for (uint32_t i = 0; i < nt; ++i) { units[i] = descs[i].n_tiles; kind[i] = batch_kind(&methods[origin[i]], plans[origin[i]]); }
+  for (uint32_t i = 0; i < nt; ++i) {
+    units[i] = descs[i].n_tiles;
+    kind[i] = batch_kind(&methods[origin[i]], plans[origin[i]]) + (plans[origin[i]].half ? kBatchKinds : 0);
+  }
   group_launches(units, kind, &members, &tiles);
   for (uint32_t i = 0; i < nt; ++i) {
     units[i] = needs_block_sums(&methods[origin[i]], plans[origin[i]]) ? descs[i].n_blocks : 0u;
-    kind[i] = 0;
+    kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
   }
   group_launches(units, kind, &members, &sums);
   for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].n_blocks;
@@ -751,15 +759,16 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   if (rc == ADACC_OK) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : tiles)
-    hipLaunchKernelGGL(compress_batch_fn(g.kind), dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members),
+    hipLaunchKernelGGL(compress_batch_fn(g.kind >= kBatchKinds, g.kind % kBatchKinds),
+                       dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members),
                        dim3(kThreads), 0, s, dt, dm + g.first_member, epoch);
   rc = launch_check("compress_batch_kernel");
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : sums)
-    hipLaunchKernelGGL(place_sum_batch_fn(), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
+    hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, place_sum_batch_fn()), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
                        dm + g.first_member);
   for (const GroupLaunch& g : places)
-    hipLaunchKernelGGL(place_batch_fn(), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
+    hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, place_batch_fn()), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
                        dm + g.first_member, epoch);
   return launch_check("place_batch_kernel");
 }
@@ -769,7 +778,7 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
                            void* hip_stream) {
   if (n == 0) return ADACC_OK;
   if (!methods || !blobs || !numels || !dsts || !blob_bytes) return ADACC_ENULL;
-  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  if (dst_dtype != ADACC_DST_16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
   std::vector<Plan> plans;
   uint32_t total = 0, act = 0;
   uint64_t region_bytes = 0;
@@ -792,9 +801,11 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   std::vector<uint32_t> units(nt), members;
   std::vector<int> kind(nt, 0);
   std::vector<GroupLaunch> launches;
-  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].n_tiles;  // pieces of 2048 elements
+  for (uint32_t i = 0; i < nt; ++i) {
+    units[i] = descs[i].n_tiles;  // pieces of 2048 elements
+    kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
+  }
   group_launches(units, kind, &members, &launches);
-  const BatchDecompressFn fn = decompress_batch_fn(dst_dtype == ADACC_DST_F32);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
   TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
@@ -803,7 +814,8 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   if (rc == ADACC_OK) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : launches)
-    hipLaunchKernelGGL(fn, dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members), dim3(kThreads), 0, s, dt,
+    hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, decompress_batch_fn(dst_dtype == ADACC_DST_F32)),
+                       dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members), dim3(kThreads), 0, s, dt,
                        dm + g.first_member);
   return launch_check("decompress_batch_kernel");
 }
@@ -855,23 +867,24 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
   fill_channel_desc(method, tokens, hidden, L, blob, &c);
   float* partial = static_cast<float*>(workspace);
   double* S = reinterpret_cast<double*>(static_cast<unsigned char*>(workspace) + channel_partial_bytes(cp.n_chunks, hidden));
-  ChannelFn fn = channel_compress_fn(method->bits, method->asym, cp.plan.rowwise);
+  const bool half = cp.plan.half;
+  ChannelFn fn = ADACC_PICK(half, channel_compress_fn(method->bits, method->asym, cp.plan.rowwise));
   uint32_t grid = 0;
   rc = grid_for(cp.plan.n_tiles, reinterpret_cast<const void*>(fn), &grid, 2);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
   const uint32_t n_items = cp.n_chunks * (hidden / 8);  // one lane: 8 channels of one chunk
-  hipLaunchKernelGGL(channel_partial_fn(), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+  hipLaunchKernelGGL(ADACC_PICK(half, channel_partial_fn()), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
                      static_cast<const uint16_t*>(src), (uint32_t)tokens, hidden, partial, n_items);
   rc = launch_check("channel_partial_kernel");
   if (rc != ADACC_OK) return rc;
-  const uint32_t per_wg = channel_score_channels();
-  hipLaunchKernelGGL(channel_score_fn(), dim3((hidden + per_wg - 1) / per_wg), dim3(kThreads), 0, s,
+  const uint32_t per_wg = ADACC_PICK(half, channel_score_channels());
+  hipLaunchKernelGGL(ADACC_PICK(half, channel_score_fn()), dim3((hidden + per_wg - 1) / per_wg), dim3(kThreads), 0, s,
                      static_cast<const float*>(partial), cp.n_chunks, hidden, S);
   rc = launch_check("channel_score_kernel");
   if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(channel_select_fn(), dim3(1), dim3(256), 0, s, static_cast<const double*>(S), c);
+  hipLaunchKernelGGL(ADACC_PICK(half, channel_select_fn()), dim3(1), dim3(256), 0, s, static_cast<const double*>(S), c);
   rc = launch_check("channel_select_kernel");
   if (rc != ADACC_OK) return rc;
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), channel_mask_lds(hidden), s, d, c);
@@ -881,7 +894,7 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
 int adacc_channel_decompress(const adacc_channel_method* method, const void* blob, uint64_t blob_bytes,
                              uint64_t tokens, uint32_t hidden, void* dst, int dst_dtype, void* hip_stream) {
   if (!method) return ADACC_ENULL;
-  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  if (dst_dtype != ADACC_DST_16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
   ChannelPlan cp;
   int rc = make_channel_plan(method, tokens, hidden, &cp);
   if (rc != ADACC_OK) return rc;
@@ -896,7 +909,7 @@ int adacc_channel_decompress(const adacc_channel_method* method, const void* blo
             &d);
   ChannelDesc c;
   fill_channel_desc(method, tokens, hidden, L, const_cast<void*>(blob), &c);
-  ChannelFn fn = channel_decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32);
+  ChannelFn fn = ADACC_PICK(cp.plan.half, channel_decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
   uint32_t grid = 0;
   rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid, 1);
   if (rc != ADACC_OK) return rc;
@@ -962,10 +975,11 @@ static void channelwise_desc(uint32_t bits, uint32_t scale_rule, uint64_t tokens
   c->inv_hidden = std::nextafter(std::nextafter(1.0f / (float)hidden, 0.0f), 0.0f);
 }
 
-int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, const void* src, uint64_t tokens, uint32_t hidden,
-                               void* blob, uint64_t blob_bytes, void* workspace, uint64_t workspace_bytes,
-                               void* hip_stream) {
-  if (!channelwise_sizes_ok(bits, tokens, hidden) || scale_rule > 1) return ADACC_EINVAL;
+int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, uint32_t dtype, const void* src, uint64_t tokens,
+                               uint32_t hidden, void* blob, uint64_t blob_bytes, void* workspace,
+                               uint64_t workspace_bytes, void* hip_stream) {
+  if (!channelwise_sizes_ok(bits, tokens, hidden) || scale_rule > 1 || dtype > ADACC_DTYPE_F16) return ADACC_EINVAL;
+  const bool half = dtype == ADACC_DTYPE_F16;
   if (tokens == 0) return ADACC_OK;
   if (!src || !blob || !workspace) return ADACC_ENULL;
   adacc_channelwise_layout L;
@@ -978,27 +992,28 @@ int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, const void* s
   c.src = static_cast<const uint16_t*>(src);
   c.partial = static_cast<uint16_t*>(workspace);
   c.inv = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + channelwise_partial_bytes(tokens, hidden));
-  ChannelwiseFn quant = channelwise_quantise_fn(bits);
+  ChannelwiseFn quant = ADACC_PICK(half, channelwise_quantise_fn(bits));
   const uint32_t n_tiles = (uint32_t)((c.numel + 2047ull) / 2048ull);
   uint32_t grid = 0;
   int rc = grid_for(n_tiles, reinterpret_cast<const void*>(quant), &grid);
   if (rc != ADACC_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t n_items = c.n_chunks * (hidden / 8);
-  hipLaunchKernelGGL(channelwise_partial_fn(), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s, c, n_items);
+  hipLaunchKernelGGL(ADACC_PICK(half, channelwise_partial_fn()), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s, c, n_items);
   rc = launch_check("channelwise_partial_kernel");
   if (rc != ADACC_OK) return rc;
-  const uint32_t per_wg = channelwise_fold_octets();
-  hipLaunchKernelGGL(channelwise_fold_fn(), dim3((hidden / 8 + per_wg - 1) / per_wg), dim3(kThreads), 0, s, c);
+  const uint32_t per_wg = ADACC_PICK(half, channelwise_fold_octets());
+  hipLaunchKernelGGL(ADACC_PICK(half, channelwise_fold_fn()), dim3((hidden / 8 + per_wg - 1) / per_wg), dim3(kThreads), 0, s, c);
   rc = launch_check("channelwise_fold_kernel");
   if (rc != ADACC_OK) return rc;
   hipLaunchKernelGGL(quant, dim3(grid), dim3(kThreads), 0, s, c);
   return launch_check("channelwise_quantise_kernel");
 }
 
-int adacc_channelwise_decompress(uint32_t bits, const void* blob, uint64_t blob_bytes, uint64_t tokens, uint32_t hidden,
-                                 void* dst, int dst_dtype, void* hip_stream) {
-  if (dst_dtype != ADACC_DST_BF16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+int adacc_channelwise_decompress(uint32_t bits, uint32_t dtype, const void* blob, uint64_t blob_bytes, uint64_t tokens,
+                                 uint32_t hidden, void* dst, int dst_dtype, void* hip_stream) {
+  if (dst_dtype != ADACC_DST_16 && dst_dtype != ADACC_DST_F32) return ADACC_EINVAL;
+  if (dtype > ADACC_DTYPE_F16) return ADACC_EINVAL;
   if (!channelwise_sizes_ok(bits, tokens, hidden)) return ADACC_EINVAL;
   if (tokens == 0) return ADACC_OK;
   if (!blob || !dst) return ADACC_ENULL;
@@ -1009,7 +1024,7 @@ int adacc_channelwise_decompress(uint32_t bits, const void* blob, uint64_t blob_
   ChannelwiseDesc c;
   channelwise_desc(bits, 0, tokens, hidden, L, const_cast<void*>(blob), &c);
   c.dst = dst;
-  ChannelwiseFn fn = channelwise_dequantise_fn(bits, dst_dtype == ADACC_DST_F32);
+  ChannelwiseFn fn = ADACC_PICK(dtype == ADACC_DTYPE_F16, channelwise_dequantise_fn(bits, dst_dtype == ADACC_DST_F32));
   const uint32_t n_tiles = (uint32_t)((c.numel + 2047ull) / 2048ull);
   uint32_t grid = 0;
   const int rc = grid_for(n_tiles, reinterpret_cast<const void*>(fn), &grid);

@@ -13,6 +13,7 @@
 #include "adacc_decompress.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 constexpr int kSelectThreads = 256;     // accumulators of the sums over channels
 
@@ -43,8 +44,8 @@ __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_
         const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          acc[2 * k] = acc[2 * k] + fabsf(__uint_as_float(w[k] << 16));
-          acc[2 * k + 1] = acc[2 * k + 1] + fabsf(__uint_as_float(w[k] & 0xFFFF0000u));
+          acc[2 * k] = acc[2 * k] + fabsf(widen_lo(w[k]));
+          acc[2 * k + 1] = acc[2 * k + 1] + fabsf(widen_hi(w[k]));
         }
       }
     }
@@ -53,8 +54,8 @@ __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        acc[2 * k] = acc[2 * k] + fabsf(__uint_as_float(w[k] << 16));
-        acc[2 * k + 1] = acc[2 * k + 1] + fabsf(__uint_as_float(w[k] & 0xFFFF0000u));
+        acc[2 * k] = acc[2 * k] + fabsf(widen_lo(w[k]));
+        acc[2 * k + 1] = acc[2 * k + 1] + fabsf(widen_hi(w[k]));
       }
     }
     float4* q = reinterpret_cast<float4*>(partial + (size_t)chunk * hidden + (size_t)oct * kOct);
@@ -398,33 +399,46 @@ __device__ __forceinline__ void channel_decompress_tile(const TensorDesc& d, con
 #pragma unroll
     for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)code[e], sc[j], zp[j]) : (float)code[e] * sc[j];
 
+    // the kept channels of this octet, as their stored 16-bit patterns (hold[e] valid where keep has bit e)
+    uint32_t keep = 0u, hold[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) hold[e] = 0u;
     if (m[j] != 0u) {
       const uint32_t lowest = m[j] & (0u - m[j]);
-      const float first_val = __uint_as_float(pre[j] << 16);
+      keep = lowest;
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) v[e] = lowest == (1u << e) ? first_val : v[e];
+      for (int e = 0; e < kOct; ++e) hold[e] = lowest == (1u << e) ? pre[j] : 0u;
       const uint32_t rest = m[j] ^ lowest;
       if (rest != 0u) {
 #pragma unroll
         for (int e = 1; e < kOct; ++e)
           if (rest & (1u << e)) {
             const uint32_t r = (uint32_t)__popc(m[j] & ((1u << e) - 1u));
-            if (r < n_ch - first[j]) v[e] = __uint_as_float((uint32_t)src[j][r] << 16);
+            if (r < n_ch - first[j]) { hold[e] = src[j][r]; keep |= 1u << e; }
           }
       }
     }
 
     if constexpr (F32) {
+      if (keep != 0u) {
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) v[e] = (keep & (1u << e)) ? widen_lo(hold[e]) : v[e];
+      }
       float* p = reinterpret_cast<float*>(d.dst) + e0;
       ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
       ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     } else {
-      uint4 w;  // the bf16 image of a widened bf16 value is that value
-      w.x = bf16_pair(v[0], v[1]);
-      w.y = bf16_pair(v[2], v[3]);
-      w.z = bf16_pair(v[4], v[5]);
-      w.w = bf16_pair(v[6], v[7]);
-      ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
+      uint32_t w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) w[k] = narrow_pair(v[2 * k], v[2 * k + 1]);
+      if (keep != 0u) {  // the kept values go in as they were stored, bit for bit (no conversion touches a NaN)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (keep & (1u << (2 * k))) w[k] = (w[k] & 0xFFFF0000u) | hold[2 * k];
+          if (keep & (2u << (2 * k))) w[k] = (w[k] & 0x0000FFFFu) | (hold[2 * k + 1] << 16);
+        }
+      }
+      ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, make_uint4(w[0], w[1], w[2], w[3]));
     }
   }
 }
@@ -442,4 +456,5 @@ __global__ __launch_bounds__(kThreads) void channel_decompress_kernel(TensorDesc
     channel_decompress_tile<BITS, ASYM, F32>(d, c, n_ch, lds, t);
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

@@ -12,14 +12,14 @@
 #include <type_traits>
 
 #include "adacc_common.hpp"
+#include "adacc_dtype.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 // ------------------------------------------------------------------ small helpers
 __device__ __forceinline__ int lane_id() { return (int)__lane_id(); }
 
-__device__ __forceinline__ float widen_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 // element e (0..7) of an octet held in 4 dwords
 #define ADACC_ELEM_F32(oct, e) (((e)&1) ? widen_hi((oct)[(e) >> 1]) : widen_lo((oct)[(e) >> 1]))
 #define ADACC_ELEM_MAG(oct, e) ((((e)&1) ? ((oct)[(e) >> 1] >> 16) : (oct)[(e) >> 1]) & 0x7FFFu)
@@ -265,7 +265,7 @@ __device__ __forceinline__ void forget_derived(const uint32_t (&raw)[E][4]) {
   }
 }
 
-// bf16 -> binary32 (exact): the 16 bits become the upper half of the word
+// 16-bit format -> binary32 (exact)
 __device__ __forceinline__ void widen_row(const uint32_t (&oct)[4], float (&x)[kOct]) {
 #pragma unroll
   for (int e = 0; e < kOct; ++e) x[e] = ADACC_ELEM_F32(oct, e);
@@ -486,7 +486,7 @@ __device__ __forceinline__ void clear_elements(uint32_t (&oct)[4], uint32_t mask
   }
 }
 
-// largest magnitude (15 low bits of the bf16 patterns) among the 8 elements of an octet
+// largest magnitude (15 low bits of the patterns) among the 8 elements of an octet
 __device__ __forceinline__ uint32_t octet_magnitude(const uint32_t (&oct)[4]) {
   constexpr uint32_t kMag2 = 0x7FFF7FFFu;
   const uint32_t m = pk_max_u16(pk_max_u16(oct[0] & kMag2, oct[1] & kMag2), pk_max_u16(oct[2] & kMag2, oct[3] & kMag2));
@@ -495,9 +495,9 @@ __device__ __forceinline__ uint32_t octet_magnitude(const uint32_t (&oct)[4]) {
 }
 
 // a6, symmetric, for a row free of outliers and of values that are not finite: S and D / max from
-// the group's largest magnitude (`am_bits`: its binary32 bits; it has at most 8 significant bits).
+// the group's largest magnitude (`am_bits`: its binary32 bits; it has at most 11 significant bits).
 // For the paper's divisor, a power of two, D / max needs no division sequence: the hardware
-// reciprocal is within one unit in the last place, and for an operand of 8 significant bits one
+// reciprocal is within one unit in the last place, and for an operand of 11 significant bits one
 // Newton step then gives the correctly rounded 1 / max (verified for every significand and every
 // such starting value); the factor D is exact.  Outside 2^-100 .. 2^100 (where the reciprocal, or
 // D / max, leaves the normal range) and for other divisors the division is carried out.
@@ -581,7 +581,7 @@ __device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileG
         am_bits = __float_as_uint(am);
       }
     } else {
-      am_bits = octet_magnitude(raw[j]) << 16;  // Inf / NaN show as a value of 0x7F800000 or more
+      am_bits = mag_bits32(octet_magnitude(raw[j]));  // Inf / NaN show as a value of 0x7F800000 or more
       if constexpr (MODE == kModeAbs) suspect = am_bits > __float_as_uint(d.param);  // tau >= 0, finite
       else suspect = am_bits >= 0x7F800000u;
     }
@@ -651,7 +651,7 @@ __device__ __forceinline__ uint32_t encode_tile_rowwise(const TensorDesc& d, con
 }
 
 // ------------------------------------------------------------------ TOPK selection
-// Magnitudes are the 15 low bits of the bf16 patterns.  Two ways to find a group's k largest:
+// Magnitudes are the 15 low bits of the patterns.  Two ways to find a group's k largest:
 //
 // By lane maxima (groups of whole rows, small k): every lane takes the largest magnitude among
 // its own elements of the group, and the k-th largest of these lane maxima, w, is found by k
@@ -662,8 +662,8 @@ __device__ __forceinline__ uint32_t encode_tile_rowwise(const TensorDesc& d, con
 //
 // By rounds (any group, any k): k max-reductions over keys (magnitude above, inverted position
 // below, so ties go to the lower index), each restricted to the keys below the previous winner.
-// largest magnitude (15 low bits of the bf16 patterns) among the lane's 8 elements of every row:
-// two 16-bit lanes at a time.  An Inf or NaN shows as a value >= 0x7F80.
+// largest magnitude (15 low bits of the patterns) among the lane's 8 elements of every row:
+// two 16-bit lanes at a time.  An Inf or NaN shows as a value >= kNonfiniteMag.
 template <int E>
 __device__ __forceinline__ void row_magnitudes(const uint32_t (&raw)[E][4], uint32_t (&rowmag)[E]) {
 #pragma unroll
@@ -685,7 +685,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
     uint32_t m = rowmag[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) m = m > rowmag[j] ? m : rowmag[j];
-    const bool finite = __builtin_amdgcn_ballot_w64(m >= 0x7F80u) == 0ull;
+    const bool finite = __builtin_amdgcn_ballot_w64(m >= kNonfiniteMag) == 0ull;
     uint32_t cur = (m << 6) | lane;  // unique per lane: equal maxima are taken one after the other
     uint32_t win = 0u;               // uniform
     for (uint32_t r = 0; r < d.topk; ++r) {
@@ -693,7 +693,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
       cur = (cur == win) ? 0u : cur;
     }
 #pragma unroll
-    for (int j = 0; j < E; ++j) thr[j] = (win >> 6) << 16;
+    for (int j = 0; j < E; ++j) thr[j] = mag_bits32(win >> 6);
     return finite;
   }
   const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
@@ -712,7 +712,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
   bool nonfinite = false;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-    if ((j & (R - 1)) == 0) nonfinite |= m[j] >= 0x7F80u;
+    if ((j & (R - 1)) == 0) nonfinite |= m[j] >= kNonfiniteMag;
     cur[j] = (m[j] << 6) | lane;
     win[j] = 0u;
   }
@@ -732,7 +732,7 @@ __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint
     }
   }
 #pragma unroll
-  for (int j = 0; j < E; ++j) thr[j] = (win[j] >> 6) << 16;
+  for (int j = 0; j < E; ++j) thr[j] = mag_bits32(win[j] >> 6);
   return __builtin_amdgcn_ballot_w64(nonfinite) == 0ull;
 }
 
@@ -765,7 +765,7 @@ __device__ __forceinline__ bool topk_select_rounds(const TensorDesc& d, const ui
   }
   bool many = false;
 #pragma unroll
-  for (int j = 0; j < E; ++j) many |= (kth[j] >> 16) >= 0x7F80u;
+  for (int j = 0; j < E; ++j) many |= (kth[j] >> 16) >= kNonfiniteMag;
   return __builtin_amdgcn_ballot_w64(many) != 0ull;
 }
 
@@ -795,7 +795,7 @@ __device__ __forceinline__ void outlier_phase(const TensorDesc& d, const TileGeo
       // Symmetric: one test of the lane's largest magnitude of the row tells whether the row can
       // hold an outlier at all; if not, that magnitude is also the lane's share of max |y|, and
       // neither the widened values nor the 8 tests are needed.
-      const uint32_t top = rowmag[j] << 16;  // bits of the largest |x|
+      const uint32_t top = mag_bits32(rowmag[j]);  // bits of the largest |x|
       bool maybe;
       if constexpr (MODE == kModeTopk) maybe = top >= thr[j];
       else if constexpr (MODE == kModeAbs) maybe = top > __float_as_uint(d.param);  // tau >= 0; Inf / NaN are above every tau
@@ -948,7 +948,7 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
       float x[kOct];
       widen_row(raw[j], x);
       s1[j] = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
-      // squares of bf16 values are exact in binary32
+      // squares of 16-bit values (at most 11 significant bits) are exact in binary32
       s2[j] = ((x[0] * x[0] + x[1] * x[1]) + (x[2] * x[2] + x[3] * x[3])) +
               ((x[4] * x[4] + x[5] * x[5]) + (x[6] * x[6] + x[7] * x[7]));
     }
@@ -1037,7 +1037,7 @@ __device__ __forceinline__ bool topk_select_rounds_whole(const TensorDesc& d, co
     kth = wave_max_u32_scalar(m);
   }
   kth_out = kth;
-  return (kth >> 16) >= 0x7F80u;
+  return (kth >> 16) >= kNonfiniteMag;
 }
 
 // ------------------------------------------------------------------ TOPK over a whole tile, quantisation groups inside a row
@@ -1067,7 +1067,7 @@ __device__ __forceinline__ uint32_t topk_extract_by_keys(const TensorDesc& d, ui
     for (int e = 0; e < kOct; ++e) {
       const uint32_t mag = ADACC_ELEM_MAG(raw[j], e);
       const uint32_t key = (mag << 16) | (0xFFFFu - (row_pos | (uint32_t)e));
-      b[e] = __builtin_amdgcn_ballot_w64(key >= kth || (poisoned && mag >= 0x7F80u));
+      b[e] = __builtin_amdgcn_ballot_w64(key >= kth || (poisoned && mag >= kNonfiniteMag));
     }
     uint32_t mask, lane_excl, row_cnt;
     bool any, sparse;
@@ -1102,7 +1102,7 @@ __device__ __forceinline__ uint32_t topk_extract(const TensorDesc& d, uint32_t (
       const float tf = __uint_as_float(t);
 #pragma unroll
       for (int j = 0; j < E; ++j) {
-        if (__builtin_amdgcn_ballot_w64((rowmag[j] << 16) >= t) == 0ull) continue;  // uniform
+        if (__builtin_amdgcn_ballot_w64(mag_bits32(rowmag[j]) >= t) == 0ull) continue;  // uniform
         float x[kOct];
         widen_row(raw[j], x);
         uint64_t b[kOct];
@@ -1140,7 +1140,7 @@ __device__ __forceinline__ void encode_clean_rows(const TensorDesc& d, const Til
     // one row after the other: the compiler shall not start on the next rows to hide this row's
     // latencies (other wavefronts do that), it would pay for it with the registers of a wavefront
     __builtin_amdgcn_sched_barrier(0);
-    encode_clean_row<BITS, ASYM, E, LANES>(d, g, j, raw[j], rowmag[j] << 16);
+    encode_clean_row<BITS, ASYM, E, LANES>(d, g, j, raw[j], mag_bits32(rowmag[j]));
   }
 }
 
@@ -1425,4 +1425,5 @@ __device__ __forceinline__ void compress_tile_plain(const TensorDesc& d, uint32_
   }
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

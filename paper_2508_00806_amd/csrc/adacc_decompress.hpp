@@ -3,17 +3,10 @@
 #pragma once
 
 #include "adacc_common.hpp"
+#include "adacc_dtype.hpp"
 
 namespace adacc {
-
-// two binary32 values -> two bf16 in one word (first value in the low half), round to nearest even:
-// the conversion instruction of gfx950
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
-  const f32x2_t v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
+namespace ADACC_DT_NS {
 
 // Decompression always works on pieces of E = 4 rows (2048 elements), whatever the tile of the
 // blob: a piece of a 4096-element tile looks through the outliers of the whole tile and takes
@@ -69,10 +62,10 @@ __device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e
     ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
   } else {
     uint4 w;
-    w.x = bf16_pair(v[0], v[1]);
-    w.y = bf16_pair(v[2], v[3]);
-    w.z = bf16_pair(v[4], v[5]);
-    w.w = bf16_pair(v[6], v[7]);
+    w.x = narrow_pair(v[0], v[1]);
+    w.y = narrow_pair(v[2], v[3]);
+    w.z = narrow_pair(v[4], v[5]);
+    w.w = narrow_pair(v[6], v[7]);
     ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
   }
 }
@@ -138,11 +131,12 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
       }
       const uint64_t i = o_idx;
       if (i >= tile_base && i < piece_end) {  // a damaged stream must not write outside the piece
-        if constexpr (F32) reinterpret_cast<uint32_t*>(d.dst)[i] = o_val << 16;
+        if constexpr (F32) reinterpret_cast<float*>(d.dst)[i] = widen_lo(o_val);
         else reinterpret_cast<uint16_t*>(d.dst)[i] = (uint16_t)o_val;
       }
     }
   }
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

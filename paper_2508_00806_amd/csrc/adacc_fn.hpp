@@ -15,39 +15,52 @@ typedef void (*PlaceFn)(TensorDesc, uint32_t);
 typedef void (*PlaceSumBatchFn)(const TensorDesc*, const uint32_t*);
 typedef void (*PlaceBatchFn)(const TensorDesc*, const uint32_t*, uint32_t);
 
-// e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
-CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
-CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
-CompressFn compress_fn_std(uint32_t bits, uint32_t asym, bool e8, bool rowwise);
-CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);
-DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);
-BatchCompressFn compress_batch_fn(int kind);  // kind: kBatch* of adacc_kernels.hpp
-BatchDecompressFn decompress_batch_fn(bool f32);
-PlaceSumFn place_sum_fn();
-PlaceFn place_fn();
-PlaceSumBatchFn place_sum_batch_fn();
-PlaceBatchFn place_batch_fn();
-
-// outlier channels (Section 3.2, Eq. 1)
+// Types of the channel and channel-wise kernels
 typedef void (*ChannelPartialFn)(const uint16_t*, uint32_t, uint32_t, float*, uint32_t);
 typedef void (*ChannelScoreFn)(const float*, uint32_t, uint32_t, double*);
 typedef void (*ChannelSelectFn)(const double*, ChannelDesc);
 typedef void (*ChannelFn)(TensorDesc, ChannelDesc);
-ChannelPartialFn channel_partial_fn();
-ChannelScoreFn channel_score_fn();
-ChannelSelectFn channel_select_fn();
-uint32_t channel_score_channels();  // channels per workgroup of the score kernel
-ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);
-ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);
-
-// channel-wise symmetric quantisation (Section 3.2, Query / Key / Value)
 typedef void (*ChannelwiseItemsFn)(ChannelwiseDesc, uint32_t);
 typedef void (*ChannelwiseFn)(ChannelwiseDesc);
-ChannelwiseItemsFn channelwise_partial_fn();
-ChannelwiseFn channelwise_fold_fn();
-uint32_t channelwise_fold_octets();  // octets of channels per workgroup of the fold kernel
-ChannelwiseFn channelwise_quantise_fn(uint32_t bits);
-ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32);
+
+// The getters of the kernels that read or write the tensor itself exist once per 16-bit format, in
+// adacc::bf16 and adacc::f16 (the same sources compiled twice).
+//   e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
+//   kind: kBatch* of adacc_common.hpp
+//   channel_score_channels: channels per workgroup of the score kernel
+//   channelwise_fold_octets: octets of channels per workgroup of the fold kernel
+#define ADACC_DTYPE_GETTERS                                                            \
+  CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);    \
+  CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
+  CompressFn compress_fn_std(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
+  CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);      \
+  DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);                  \
+  BatchCompressFn compress_batch_fn4(int kind);                                        \
+  BatchCompressFn compress_batch_fn8(int kind);                                        \
+  BatchDecompressFn decompress_batch_fn(bool f32);                                     \
+  PlaceSumFn place_sum_fn();                                                           \
+  PlaceFn place_fn();                                                                  \
+  PlaceSumBatchFn place_sum_batch_fn();                                                \
+  PlaceBatchFn place_batch_fn();                                                       \
+  ChannelPartialFn channel_partial_fn();                                               \
+  ChannelScoreFn channel_score_fn();                                                   \
+  ChannelSelectFn channel_select_fn();                                                 \
+  uint32_t channel_score_channels();                                                   \
+  ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);           \
+  ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);             \
+  ChannelwiseItemsFn channelwise_partial_fn();                                         \
+  ChannelwiseFn channelwise_fold_fn();                                                 \
+  uint32_t channelwise_fold_octets();                                                  \
+  ChannelwiseFn channelwise_quantise_fn(uint32_t bits);                                \
+  ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32);
+namespace bf16 {
+ADACC_DTYPE_GETTERS
+}
+namespace f16 {
+ADACC_DTYPE_GETTERS
+}
+// half: the tensor is binary16 (else bf16)
+#define ADACC_PICK(half, call) ((half) ? ::adacc::f16::call : ::adacc::bf16::call)
 
 // dropout mask, byte format <-> bit format (Section 3.2)
 typedef void (*MaskFn)(const uint8_t*, uint64_t, uint8_t*);

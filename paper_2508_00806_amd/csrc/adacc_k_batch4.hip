@@ -2,6 +2,7 @@
 #include "adacc_kernels.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 BatchCompressFn compress_batch_fn4(int kind) {
   if (kind == kBatchRows4) return compress_batch_kernel<kBatchRows4>;
@@ -9,4 +10,5 @@ BatchCompressFn compress_batch_fn4(int kind) {
   return compress_batch_kernel<kBatchAny4>;
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

@@ -3,6 +3,7 @@
 #include "adacc_fn.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 ChannelPartialFn channel_partial_fn() { return channel_partial_kernel; }
 ChannelScoreFn channel_score_fn() { return channel_score_kernel; }
@@ -27,4 +28,5 @@ ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32) {
   return asym ? pick_decompress<8, true>(f32) : pick_decompress<8, false>(f32);
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

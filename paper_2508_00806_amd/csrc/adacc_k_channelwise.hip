@@ -12,11 +12,13 @@
 #include "adacc_fn.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
-// magnitudes (15 low bits) of two bf16 values; one that is not finite counts as zero
+// magnitudes (15 low bits) of two 16-bit values; one that is not finite counts as zero
 __device__ __forceinline__ uint32_t finite_magnitudes2(uint32_t w) {
   const uint32_t mag = w & 0x7FFF7FFFu;
-  const uint32_t nf = ((mag + 0x00800080u) >> 15) & 0x00010001u;  // magnitude >= 0x7F80: bit 15 after the add
+  constexpr uint32_t kLift = (0x8000u - kNonfiniteMag) * 0x00010001u;
+  const uint32_t nf = ((mag + kLift) >> 15) & 0x00010001u;  // magnitude >= kNonfiniteMag: bit 15 after the add
   return mag & ~(nf * 0xFFFFu);
 }
 
@@ -218,10 +220,10 @@ __global__ __launch_bounds__(kThreads) void channelwise_dequantise_kernel(Channe
         ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
       } else {
         uint4 w;
-        w.x = bf16_pair(v[0], v[1]);
-        w.y = bf16_pair(v[2], v[3]);
-        w.z = bf16_pair(v[4], v[5]);
-        w.w = bf16_pair(v[6], v[7]);
+        w.x = narrow_pair(v[0], v[1]);
+        w.y = narrow_pair(v[2], v[3]);
+        w.z = narrow_pair(v[4], v[5]);
+        w.w = narrow_pair(v[6], v[7]);
         ADACC_STORE16(reinterpret_cast<uint16_t*>(c.dst) + e0, w);
       }
     }
@@ -239,4 +241,5 @@ ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32) {
   return f32 ? channelwise_dequantise_kernel<8, true> : channelwise_dequantise_kernel<8, false>;
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

@@ -2,6 +2,7 @@
 #include "adacc_kernels.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32) {
   if (bits == 4) {
@@ -16,4 +17,5 @@ BatchDecompressFn decompress_batch_fn(bool f32) {
   return f32 ? decompress_batch_kernel<true> : decompress_batch_kernel<false>;
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

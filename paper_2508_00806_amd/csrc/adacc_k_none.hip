@@ -2,6 +2,7 @@
 #include "adacc_kernels.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 template <int BITS, bool ASYM>
 static CompressFn pick(bool e8, bool rowwise) {
@@ -14,4 +15,5 @@ CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise)
   return asym ? pick<8, true>(e8, rowwise) : pick<8, false>(e8, rowwise);
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

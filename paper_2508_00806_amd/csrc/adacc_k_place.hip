@@ -4,6 +4,7 @@
 #include "adacc_kernels.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 __device__ __forceinline__ void place_dispatch(const TensorDesc& d, uint32_t block, uint32_t epoch, PlaceShared& sh) {
   const bool e8 = (d.variant & 1u) != 0u;
@@ -64,4 +65,5 @@ PlaceFn place_fn() { return place_kernel; }
 PlaceSumBatchFn place_sum_batch_fn() { return place_sum_batch_kernel; }
 PlaceBatchFn place_batch_fn() { return place_batch_kernel; }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

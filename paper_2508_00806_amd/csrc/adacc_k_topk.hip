@@ -2,6 +2,7 @@
 #include "adacc_kernels.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 template <int BITS, bool ASYM>
 static CompressFn pick(bool e8, bool whole) {
@@ -14,4 +15,5 @@ CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole) {
   return asym ? pick<8, true>(e8, whole) : pick<8, false>(e8, whole);
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

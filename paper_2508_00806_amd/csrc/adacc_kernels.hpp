@@ -9,6 +9,7 @@
 #include "adacc_fn.hpp"
 
 namespace adacc {
+namespace ADACC_DT_NS {
 
 // ---- single tensor, compress: tiles are independent, one tile per wavefront, workgroups in the
 // hardware's own order (which walks through memory front to back).
@@ -120,4 +121,5 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
   }
 }
 
+}  // namespace ADACC_DT_NS
 }  // namespace adacc

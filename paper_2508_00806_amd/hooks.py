@@ -14,9 +14,11 @@ fourth of the layer-specific schemes of Section 3.2, when `pack_masks` is set.
 Plumbing only: the hooks allocate buffers and call the library; every step of compression and
 decompression runs in the HIP kernels.  A tensor the policy does not cover is saved as it is.
 """
+import dataclasses
+
 import torch
 
-from . import (AdaccError, ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
+from . import (DTYPE_BF16, DTYPE_F16, AdaccError, ChannelMethod, Method, KIND_NOOP, OUTLIER_NONE, alloc_blob, alloc_channel_blob,
                alloc_channel_workspace, alloc_workspace, channel_compress, channel_compressed_bytes,
                channel_decompress, channel_layout_of, channel_workspace_bytes, compress, compressed_bytes, decompress,
                layout_of, mask_pack, mask_packed_bytes, mask_unpack, workspace_bytes)
@@ -63,7 +65,7 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
 
     policy(tensor) returns an adacc `Method` (element outliers), a `ChannelMethod` (outlier channels
     by Z-score; the tensor is taken as [numel / last_dim, last_dim]) or None (retain).  Only contiguous
-    bf16 CUDA tensors are offered to the policy.  timing=True brackets every library call with events
+    bf16 and float16 CUDA tensors are offered to the policy; the method's dtype field follows the tensor.  timing=True brackets every library call with events
     so that `report()` can give Tc_i and Tdc_i (it costs a synchronisation in `report()` only).
 
     The number of outliers moves while a model trains (Section 3.4), so a method's `max_outliers` /
@@ -92,7 +94,7 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
 
     # ---- hooks
     def _eligible(self, t):
-        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype in (torch.bfloat16, torch.float16) and t.is_contiguous()
                 and t.numel() > 0 and t.data_ptr() % 16 == 0):
             return False
         return not (t.is_leaf and t.requires_grad)  # parameters are not activations
@@ -117,6 +119,9 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
         m = self.policy(t)
         if m is None or (isinstance(m, Method) and m.kind == KIND_NOOP):
             return t
+        fmt = DTYPE_F16 if t.dtype == torch.float16 else DTYPE_BF16
+        if m.dtype != fmt:  # the policy names the method; the format is the tensor's
+            m = dataclasses.replace(m, dtype=fmt)
         numel = t.numel()
         try:  # a shape the method can not take is no error of the training run: the tensor is retained
             if isinstance(m, ChannelMethod):
@@ -182,7 +187,8 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
             raise CompressedActivationLost(
                 f"saved activation of shape {tuple(s.shape)}: {s.record['status'][0].item()} outliers found, the method "
                 f"has room for {room}; raise max_outliers / max_channels or use on_overflow='retain'")
-        out = torch.empty(s.shape, dtype=torch.bfloat16, device=s.blob.device)
+        out = torch.empty(s.shape, dtype=torch.float16 if s.method.dtype == DTYPE_F16 else torch.bfloat16,
+                          device=s.blob.device)
         ev = self._events(s.record, "decompress")
         if isinstance(s.method, ChannelMethod):
             hidden = s.shape[-1]

@@ -9,21 +9,27 @@ import paper_2508_00806_amd as adacc
 MODE_ID = {"none": 0, "abs": 1, "std": 2, "topk": 3}
 
 
-def oracle_method(md, rule=0):
-    return oracle.method_from_dict(md, rule)
+def fmt_of(t):
+    """0 (bf16) or 1 (binary16): the value both the oracle and the library use for the format of t."""
+    assert t.dtype in (torch.bfloat16, torch.float16)
+    return 1 if t.dtype == torch.float16 else 0
 
 
-def adacc_method(md, cap, rule=0):
-    return adacc.method_from_dict(md, cap, rule)
+def oracle_method(md, rule=0, fmt=0):
+    return oracle.method_from_dict(md, rule, fmt)
+
+
+def adacc_method(md, cap, rule=0, fmt=0):
+    return adacc.method_from_dict(md, cap, rule, fmt)
 
 
 def bits_of(t):
-    """bf16 torch tensor (any device) -> numpy uint16 bit patterns."""
+    """bf16 / float16 torch tensor (any device) -> numpy uint16 bit patterns."""
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
 
 
-def from_bits(b, device="cpu"):
-    return torch.from_numpy(np.ascontiguousarray(b).view(np.int16).copy()).view(torch.bfloat16).to(device)
+def from_bits(b, device="cpu", dtype=torch.bfloat16):
+    return torch.from_numpy(np.ascontiguousarray(b).view(np.int16).copy()).view(dtype).to(device)
 
 
 def gpu_compress(x_dev, m, ws=None):
@@ -82,23 +88,26 @@ def assert_f32_matches(got, want):
     assert np.array_equal(got.view(np.uint32)[ok], want.view(np.uint32)[ok]), "binary32 reconstruction not bit-equal"
 
 
-def assert_bf16_matches(got_bits, want_bits):
-    nan = (want_bits & 0x7FFF) > 0x7F80
-    assert np.array_equal((got_bits & 0x7FFF) > 0x7F80, nan)
-    assert np.array_equal(got_bits[~nan], want_bits[~nan]), "bf16 reconstruction differs"
+def assert_bf16_matches(got_bits, want_bits, fmt=0):
+    """16-bit reconstructions, bit for bit; for a NaN only the class has to agree."""
+    inf = 0x7C00 if fmt == 1 else 0x7F80
+    nan = (want_bits & 0x7FFF) > inf
+    assert np.array_equal((got_bits & 0x7FFF) > inf, nan)
+    assert np.array_equal(got_bits[~nan], want_bits[~nan]), "16-bit reconstruction differs"
 
 
 def run_parity(x_cpu_bf16, md, cap=None, rule=0, decompress=True):
     """Compress on the GPU and in the oracle, compare everything, then decompress both ways."""
     x_bits = bits_of(x_cpu_bf16)
     numel = x_bits.size
-    om = oracle_method(md, rule)
+    fmt = fmt_of(x_cpu_bf16)
+    om = oracle_method(md, rule, fmt)
     oc_full = oracle.compress(om, x_bits)
     if cap is None:
         cap = max(oc_full.n_out, 1) if md["outlier_mode"] != "none" else 0
     oc = oracle.compress(om, x_bits, cap=cap)
     oc._full_idx = oc_full.out_idx.astype(np.int64)
-    m = adacc_method(md, cap, rule)
+    m = adacc_method(md, cap, rule, fmt)
     x_dev = x_cpu_bf16.contiguous().view(-1).cuda()
     blob, L, ws = gpu_compress(x_dev, m)
     torch.cuda.synchronize()
@@ -109,21 +118,22 @@ def run_parity(x_cpu_bf16, md, cap=None, rule=0, decompress=True):
     if decompress and oc.n_out <= cap:
         of32, obf = oracle.decompress(oc)
         d32 = torch.empty(numel, dtype=torch.float32, device="cuda")
-        dbf = torch.empty(numel, dtype=torch.bfloat16, device="cuda")
+        dbf = torch.empty(numel, dtype=x_cpu_bf16.dtype, device="cuda")
         adacc.decompress(m, blob, d32)
         adacc.decompress(m, blob, dbf)
         torch.cuda.synchronize()
         assert_f32_matches(d32.cpu().numpy(), of32)
-        assert_bf16_matches(bits_of(dbf), obf)
+        assert_bf16_matches(bits_of(dbf), obf, fmt)
     return oc, blob, L, m
 
 
 def run_channel_parity(x, bits, gq, asym, z=3.0, cap=None, rule=0):
-    """x: bf16 [tokens, hidden] on the CPU."""
+    """x: bf16 or float16 [tokens, hidden] on the CPU."""
     tokens, hidden = x.shape
     xb = bits_of(x)
-    om = oracle.Method(bits=bits, quant_group=gq, asym=asym, scale_rule=rule)
-    S = oracle.channel_scores(xb, tokens, hidden)
+    fmt = fmt_of(x)
+    om = oracle.Method(bits=bits, quant_group=gq, asym=asym, scale_rule=rule, dtype=fmt)
+    S = oracle.channel_scores(xb, tokens, hidden, fmt)
     is_out, mu, sigma = oracle.channel_select(S, z)
     n_ch = int(is_out.sum())
     # The selection is an integer decided by sums.  The oracle's sums are exact; the library adds in
@@ -139,7 +149,8 @@ def run_channel_parity(x, bits, gq, asym, z=3.0, cap=None, rule=0):
     cap = max(n_ch, 1) if cap is None else cap
     oc = oracle.channel_compress(om, xb, tokens, hidden, z, cap=cap)
     assert oc.n_ch == n_ch
-    m = adacc.ChannelMethod(bits=bits, quant_group=gq, asym=asym, scale_rule=rule, z_thresh=z, max_channels=cap)
+    m = adacc.ChannelMethod(bits=bits, quant_group=gq, asym=asym, scale_rule=rule, z_thresh=z, max_channels=cap,
+                            dtype=fmt)
     blob, L = adacc.alloc_channel_blob(m, tokens, hidden)
     blob.fill_(0xA5)
     ws = adacc.alloc_channel_workspace(tokens, hidden)
@@ -152,7 +163,7 @@ def run_channel_parity(x, bits, gq, asym, z=3.0, cap=None, rule=0):
     assert np.array_equal(sec["ch_base"], np.concatenate([[0], np.cumsum(per_byte)[:-1]])), "channel ranks differ"
     k = min(n_ch, cap)
     assert np.array_equal(sec["ch_idx"][:k], np.nonzero(is_out)[0][:k]), "channel list differs"
-    dbf = torch.full((tokens * hidden,), 7.0, dtype=torch.bfloat16, device="cuda")
+    dbf = torch.full((tokens * hidden,), 7.0, dtype=x.dtype, device="cuda")
     d32 = torch.full((tokens * hidden,), 7.0, dtype=torch.float32, device="cuda")
     adacc.channel_decompress(m, blob, tokens, hidden, dbf)
     adacc.channel_decompress(m, blob, tokens, hidden, d32)
@@ -168,5 +179,5 @@ def run_channel_parity(x, bits, gq, asym, z=3.0, cap=None, rule=0):
         assert np.array_equal(sec["zp"].view(np.uint32), oc.zp.view(np.uint32)), "offsets differ"
     of32, obf = oracle.channel_decompress(oc)
     assert_f32_matches(d32.cpu().numpy(), of32)
-    assert_bf16_matches(bits_of(dbf), obf)
+    assert_bf16_matches(bits_of(dbf), obf, fmt)
     return oc, st

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_struct_sizes_match_the_header(L):
-    assert ctypes.sizeof(adacc.CMethod) == 40
+    assert ctypes.sizeof(adacc.CMethod) == 44
     assert ctypes.sizeof(adacc.CLayout) == 72
     assert ctypes.sizeof(adacc.CWorkspace) == 24
 
@@ -183,7 +183,7 @@ def test_strerror_and_version(L):
 
 # ----------------------------------------------------------------- outlier channels
 def test_channel_layout_closed_form_and_limits(L):
-    assert ctypes.sizeof(adacc.CChannelMethod) == 24 and ctypes.sizeof(adacc.CChannelLayout) == 72
+    assert ctypes.sizeof(adacc.CChannelMethod) == 28 and ctypes.sizeof(adacc.CChannelLayout) == 72
     m = adacc.ChannelMethod(bits=4, quant_group=128, asym=1, max_channels=10)
     tokens, hidden = 100, 2048
     n = tokens * hidden
@@ -294,17 +294,19 @@ def test_channelwise_layout_and_validation(L):
     f = L.adacc_channelwise_compress
     src, blob, ws = 0x10000, 0x20000, 0x30000
     tb, wb = lay.total_bytes, adacc.channelwise_workspace_bytes(100, 2048)
-    assert f(4, 0, None, 100, 2048, blob, tb, ws, wb, None) == adacc.ENULL
-    assert f(4, 0, src, 100, 2048, blob, tb - 1, ws, wb, None) == adacc.ESIZE
-    assert f(4, 0, src, 100, 2048, blob, tb, ws, wb - 1, None) == adacc.ESIZE
-    assert f(4, 0, src + 8, 100, 2048, blob, tb, ws, wb, None) == adacc.EALIGN
-    assert f(4, 2, src, 100, 2048, blob, tb, ws, wb, None) == adacc.EINVAL
-    assert f(4, 0, None, 0, 2048, None, 0, None, 0, None) == adacc.OK
+    assert f(4, 0, 0, None, 100, 2048, blob, tb, ws, wb, None) == adacc.ENULL
+    assert f(4, 0, 0, src, 100, 2048, blob, tb - 1, ws, wb, None) == adacc.ESIZE
+    assert f(4, 0, 0, src, 100, 2048, blob, tb, ws, wb - 1, None) == adacc.ESIZE
+    assert f(4, 0, 0, src + 8, 100, 2048, blob, tb, ws, wb, None) == adacc.EALIGN
+    assert f(4, 2, 1, src, 100, 2048, blob, tb, ws, wb, None) == adacc.EINVAL
+    assert f(4, 0, 0, None, 0, 2048, None, 0, None, 0, None) == adacc.OK
+    assert f(4, 0, 2, src, 100, 2048, blob, tb, ws, wb, None) == adacc.EINVAL  # no such 16-bit format
     g = L.adacc_channelwise_decompress
-    assert g(4, blob, tb, 100, 2048, None, 0, None) == adacc.ENULL
-    assert g(4, blob, tb, 100, 2048, 0x40000, 3, None) == adacc.EINVAL
-    assert g(4, blob, tb - 1, 100, 2048, 0x40000, 0, None) == adacc.ESIZE
-    assert g(4, blob, tb, 100, 2048, 0x40004, 0, None) == adacc.EALIGN
+    assert g(4, 2, blob, tb, 100, 2048, 0x40000, 0, None) == adacc.EINVAL
+    assert g(4, 0, blob, tb, 100, 2048, None, 0, None) == adacc.ENULL
+    assert g(4, 0, blob, tb, 100, 2048, 0x40000, 3, None) == adacc.EINVAL
+    assert g(4, 0, blob, tb - 1, 100, 2048, 0x40000, 0, None) == adacc.ESIZE
+    assert g(4, 0, blob, tb, 100, 2048, 0x40004, 0, None) == adacc.EALIGN
 
 
 def test_noalloc_limit_is_checked_on_the_host(L):

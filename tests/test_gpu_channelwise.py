@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2508_00806_amd as adacc
 import workloads
-from helpers import assert_bf16_matches, assert_f32_matches, bits_of, from_bits
+from helpers import assert_bf16_matches, assert_f32_matches, bits_of, fmt_of, from_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 def run(x, bits, rule=0):
     tokens, hidden = x.shape
     xb = bits_of(x)
-    codes, packed, scale = oracle.channelwise_compress(bits, xb, tokens, hidden, rule)
+    fmt = fmt_of(x)
+    codes, packed, scale = oracle.channelwise_compress(bits, xb, tokens, hidden, rule, fmt)
     blob, L, ws = adacc.alloc_channelwise(bits, tokens, hidden)
     blob.fill_(0xA5)
     adacc.channelwise_compress(bits, x.contiguous().cuda(), tokens, hidden, blob, ws, scale_rule=rule)
@@ -25,14 +26,14 @@ def run(x, bits, rule=0):
     got_scale = blob[L.scales_off:L.scales_off + 4 * hidden].view(torch.float32).cpu().numpy()
     assert np.array_equal(got_scale.view(np.uint32), scale.view(np.uint32)), "scales differ"
     assert np.array_equal(got_codes, packed), "packed codes differ"
-    of32, obf = oracle.channelwise_decompress(bits, packed, scale, tokens, hidden)
+    of32, obf = oracle.channelwise_decompress(bits, packed, scale, tokens, hidden, fmt)
     d32 = torch.empty(n, dtype=torch.float32, device="cuda")
-    dbf = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    dbf = torch.empty(n, dtype=x.dtype, device="cuda")
     adacc.channelwise_decompress(bits, blob, tokens, hidden, d32)
     adacc.channelwise_decompress(bits, blob, tokens, hidden, dbf)
     torch.cuda.synchronize()
     assert_f32_matches(d32.cpu().numpy(), of32)
-    assert_bf16_matches(bits_of(dbf), obf)
+    assert_bf16_matches(bits_of(dbf), obf, fmt)
 
 
 def matrix(tokens, hidden, seed):

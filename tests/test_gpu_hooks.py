@@ -214,3 +214,36 @@ def test_tensors_the_library_does_not_take_are_saved_as_they_are():
         assert torch.equal(w.grad, w2.grad)
         assert ctx.report() == []
         assert (len(ctx.retained) == 1) == (offset == 0)  # the indivisible size was offered and turned down
+
+
+def test_float16_activations_are_compressed_in_their_own_format():
+    """The paper's own setting: an FP16 activation saved as INT4 with its outlier channels kept."""
+    print("[hooks] float16", flush=True)
+    torch.manual_seed(21)
+    tokens, hidden, out = 96, 2048, 64
+    x = torch.randn(tokens, hidden)
+    x[:, [7, 900]] *= 40.0
+    x = x.to(torch.float16).cuda()
+    w = (torch.randn(out, hidden) * 0.02).to(torch.float16).cuda().requires_grad_(True)
+    g = torch.randn(tokens, out).to(torch.float16).cuda()
+    for m in (adacc.ChannelMethod(bits=4, quant_group=128, z_thresh=3.0, max_channels=16),
+              adacc.Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=2048, topk=2,
+                           max_outliers=2 * tokens)):
+        w.grad = None
+        ctx = SavedActivationCompression(lambda t: m if t.shape == x.shape else None)
+        with ctx:
+            y = torch.nn.functional.linear(x, w)
+        y.backward(g)
+        xb = bits_of(x)
+        if isinstance(m, adacc.ChannelMethod):
+            om = oracle.Method(bits=4, quant_group=128, dtype=oracle.DT_F16)
+            c = oracle.channel_compress(om, xb, tokens, hidden, 3.0, cap=16)
+            xhat = from_bits(oracle.channel_decompress(c)[1], dtype=torch.float16).view(tokens, hidden)
+        else:
+            om = oracle.Method(bits=4, quant_group=128, outlier_mode=oracle.OUT_TOPK, stat_group=2048, topk=2,
+                               dtype=oracle.DT_F16)
+            xhat = from_bits(oracle.decompress(oracle.compress(om, xb))[1], dtype=torch.float16).view(tokens, hidden)
+        want = g.t().float() @ xhat.cuda().float()
+        assert torch.allclose(w.grad.float(), want, rtol=2e-2, atol=2e-2 * float(want.abs().max()))
+        rep = ctx.report()
+        assert len(rep) == 1 and not rep[0]["overflow"] and rep[0]["crate"] < 0.3
