@@ -63,11 +63,14 @@ extern "C" {
 typedef struct adacc_method {
   uint32_t kind;         /* ADACC_KIND_*                                                     */
   uint32_t bits;         /* 4 or 8                                                           */
-  uint32_t quant_group;  /* Gq, elements per scale: a power of two in [8, 4096] dividing numel */
+  uint32_t quant_group;  /* Gq, elements per scale: a power of two in [8, 4096]; the groups are cut from the
+                            start of the flat tensor, the last one may be short                */
   uint32_t asym;         /* 0: symmetric (Eq. 2), 1: asymmetric (Eq. 3, adds one offset per group) */
   uint32_t scale_rule;   /* ADACC_SCALE_*                                                    */
   uint32_t outlier_mode; /* ADACC_OUTLIER_*                                                  */
-  uint32_t stat_group;   /* Gs, STD/TOPK only: power of two, multiple of Gq, <= 4096, divides numel */
+  uint32_t stat_group;   /* Gs, STD/TOPK only: power of two, multiple of Gq, <= 4096; the last group may be
+                            short: mean and variance over its own count, at most as many largest values
+                            as it has elements                                                   */
   float thresh;          /* ABS: tau >= 0.  STD: k >= 0 (the library forms k*k in binary32)  */
   uint32_t topk;         /* TOPK: 1..32 outliers per stat group                              */
   uint32_t max_outliers; /* capacity of the outlier stream of the blob (0 allowed for NONE)  */
@@ -78,10 +81,11 @@ typedef struct adacc_method {
 /* ---- blob layout ----
  * A compressed tensor ("blob") is one caller-owned device buffer cut into
  * sections, each starting on a 256-byte boundary:
- *   codes    numel*bits/8 bytes.  b=8: one two's-complement byte per element.
- *            b=4: element 2j in the low nibble of byte j, 2j+1 in the high nibble.
- *   scales   numel/Gq binary32, S of Eq. 2 / Eq. 3.
- *   zp       numel/Gq binary32, O of Eq. 3 (asym only, else empty).
+ *   codes    ceil(numel*bits/8) bytes.  b=8: one two's-complement byte per element.
+ *            b=4: element 2j in the low nibble of byte j, 2j+1 in the high nibble (zero when
+ *            numel is odd and 2j+1 is past the end).
+ *   scales   ceil(numel/Gq) binary32, S of Eq. 2 / Eq. 3.
+ *   zp       ceil(numel/Gq) binary32, O of Eq. 3 (asym only, else empty).
  *   tile_ptr (n_tiles+1) uint32: tile t (elements [t*tile_elems, (t+1)*tile_elems))
  *            owns outliers [tile_ptr[t], tile_ptr[t+1]) of the stream; tile_ptr[n_tiles]
  *            is the total count.  Empty for ADACC_OUTLIER_NONE.

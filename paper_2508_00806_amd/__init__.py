@@ -450,7 +450,7 @@ def channel_blob_sections(blob, layout: CChannelLayout, method: ChannelMethod, t
         return blob[off:off + nbytes].view(dtype)
 
     sec = {
-        "codes": view(layout.codes_off, numel * method.bits // 8, torch.uint8),
+        "codes": view(layout.codes_off, (numel * method.bits + 7) // 8, torch.uint8),
         "scales": view(layout.scales_off, 4 * groups, torch.float32),
         "ch_mask": view(layout.ch_mask_off, hidden // 8, torch.uint8),
         "ch_base": view(layout.ch_base_off, 4 * (hidden // 8), torch.int32),
@@ -538,14 +538,14 @@ def alloc_workspace(nbytes: int, device="cuda", stream=None) -> Workspace:
 def blob_sections(blob, layout: CLayout, method: Method, numel: int):
     """Typed views of the sections of a blob (no copies)."""
     import torch
-    groups = numel // method.quant_group
+    groups = -(-numel // method.quant_group)  # the last group may be short
     has_out = method.outlier_mode != OUTLIER_NONE
 
     def view(off, nbytes, dtype):
         return blob[off:off + nbytes].view(dtype)
 
     sec = {
-        "codes": view(layout.codes_off, numel * method.bits // 8, torch.uint8),
+        "codes": view(layout.codes_off, (numel * method.bits + 7) // 8, torch.uint8),
         "scales": view(layout.scales_off, 4 * groups, torch.float32),
         "status": view(layout.status_off, 16, torch.int32),
     }

@@ -127,7 +127,11 @@ static uint64_t align256(uint64_t v) { return (v + 255ull) & ~255ull; }
 struct Plan {  // everything derived from (method, numel)
   bool noop;
   bool outliers;
-  uint32_t tile_elems, n_tiles, lgq, lgs, variant;
+  uint32_t tile_elems, lgq, lgs, variant;
+  uint64_t numel_main;   // the whole groups of the larger kind: what the tile kernels take
+  uint32_t tail;         // elements after those, done by the tail kernels
+  uint32_t n_tiles;      // tiles of the main part
+  uint32_t n_tiles_all;  // tiles of the whole tensor (what the layout reports)
   bool rowwise;  // every group lies inside a 512-element row and both kinds of group coincide
   bool half;     // the tensor is binary16 (else bf16)
   float param, divisor;
@@ -142,12 +146,10 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   if (m->dtype > ADACC_DTYPE_F16) return ADACC_EINVAL;
   p->half = m->dtype == ADACC_DTYPE_F16;
   if (!is_pow2(m->quant_group) || m->quant_group < 8 || m->quant_group > 4096) return ADACC_EINVAL;
-  if (numel % m->quant_group != 0) return ADACC_EINVAL;
   uint32_t gs = m->quant_group;
   const bool stat = m->outlier_mode == ADACC_OUTLIER_STD || m->outlier_mode == ADACC_OUTLIER_TOPK;
   if (stat) {
     if (!is_pow2(m->stat_group) || m->stat_group < m->quant_group || m->stat_group > 4096) return ADACC_EINVAL;
-    if (numel % m->stat_group != 0) return ADACC_EINVAL;
     gs = m->stat_group;
   }
   if (m->outlier_mode == ADACC_OUTLIER_TOPK && (m->topk < 1 || m->topk > 32 || m->topk > gs)) return ADACC_EINVAL;
@@ -158,7 +160,10 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   if (p->outliers && numel >= (1ull << 31)) return ADACC_EINVAL;  // 32-bit signed flat indices
   if (numel >= (1ull << 42)) return ADACC_EINVAL;
   p->tile_elems = gs > 2048 ? 4096u : 2048u;
-  p->n_tiles = (uint32_t)((numel + p->tile_elems - 1) / p->tile_elems);
+  p->numel_main = numel - numel % gs;
+  p->tail = (uint32_t)(numel % gs);
+  p->n_tiles = (uint32_t)((p->numel_main + p->tile_elems - 1) / p->tile_elems);
+  p->n_tiles_all = (uint32_t)((numel + p->tile_elems - 1) / p->tile_elems);
   p->lgq = ilog2(m->quant_group);
   p->lgs = ilog2(gs);
   p->variant = variant_index(m->outlier_mode, m->bits, m->asym, p->tile_elems == 4096 ? 1u : 0u);
@@ -175,18 +180,18 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
 static void fill_layout(const adacc_method* m, uint64_t numel, const Plan& p, adacc_layout* L) {
   std::memset(L, 0, sizeof *L);
   if (p.noop) return;
-  const uint64_t groups = numel / m->quant_group;
+  const uint64_t groups = (numel + m->quant_group - 1) / m->quant_group;  // the last one may be short
   uint64_t off = 0;
-  L->codes_off = off;   off = align256(off + numel * m->bits / 8);
+  L->codes_off = off;   off = align256(off + (numel * m->bits + 7) / 8);
   L->scales_off = off;  off = align256(off + 4 * groups);
   L->zp_off = off;      off = align256(off + (m->asym ? 4 * groups : 0));
-  L->tile_ptr_off = off; off = align256(off + (p.outliers ? 4ull * ((uint64_t)p.n_tiles + 1) : 0));
+  L->tile_ptr_off = off; off = align256(off + (p.outliers ? 4ull * ((uint64_t)p.n_tiles_all + 1) : 0));
   L->idx_off = off;     off = align256(off + (p.outliers ? 4ull * m->max_outliers : 0));
   L->val_off = off;     off = align256(off + (p.outliers ? 2ull * m->max_outliers : 0));
   L->status_off = off;  off = align256(off + 16);
   L->total_bytes = off;
   L->tile_elems = p.tile_elems;
-  L->n_tiles = p.n_tiles;
+  L->n_tiles = p.n_tiles_all;
 }
 
 // Workgroups of `kernel` that one CU holds at once (cached per kernel: the query is not free).
@@ -271,12 +276,18 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
     d->block_sum = reinterpret_cast<uint32_t*>(r + w.block_sum_off);
     d->slot = reinterpret_cast<uint2*>(r + w.slot_off);
   }
-  d->numel = numel;
+  (void)numel;
+  d->numel = p.numel_main;
+  d->tail = p.tail;
   d->n_tiles = p.n_tiles;
+  d->n_tiles_all = p.n_tiles_all;
+  d->bits = m->bits;
+  d->asym = m->asym;
+  d->mode = m->outlier_mode;
   d->n_blocks = place_blocks(p);
   d->lgt = p.tile_elems == 4096 ? 12u : 11u;
   if (dst) {  // decompression counts pieces of 2048 elements
-    d->n_tiles = decompress_pieces(numel);
+    d->n_tiles = decompress_pieces(p.numel_main);
     d->ptr_shift = p.tile_elems == 4096 ? 1u : 0u;
   }
   d->lgq = p.lgq;
@@ -457,6 +468,7 @@ static int make_channel_plan(const adacc_channel_method* m, uint64_t tokens, uin
   cp->numel = tokens * hidden;
   const int rc = make_plan(&cp->quant, cp->numel, &cp->plan);
   if (rc != ADACC_OK) return rc;
+  if (cp->plan.tail != 0) return ADACC_EINVAL;  // here the groups have to divide the tensor
   fill_layout(&cp->quant, cp->numel, cp->plan, &cp->quant_layout);
   cp->n_chunks = (uint32_t)((tokens + kChunkTokens - 1) / kChunkTokens);
   return ADACC_OK;
@@ -578,16 +590,26 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
     rc = next_epoch(ws, s, &epoch);
     if (rc != ADACC_OK) return rc;
   }
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, epoch);
-  rc = launch_check("compress_kernel");
-  if (rc != ADACC_OK || !p.outliers) return rc;
-  if (needs_block_sums(method, p)) {
-    hipLaunchKernelGGL(ADACC_PICK(p.half, place_sum_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
-    rc = launch_check("place_sum_kernel");
+  if (p.n_tiles != 0) {
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, epoch);
+    rc = launch_check("compress_kernel");
     if (rc != ADACC_OK) return rc;
+    if (p.outliers) {
+      if (needs_block_sums(method, p)) {
+        hipLaunchKernelGGL(ADACC_PICK(p.half, place_sum_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
+        rc = launch_check("place_sum_kernel");
+        if (rc != ADACC_OK) return rc;
+      }
+      hipLaunchKernelGGL(ADACC_PICK(p.half, place_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
+      rc = launch_check("place_kernel");
+      if (rc != ADACC_OK) return rc;
+    }
   }
-  hipLaunchKernelGGL(ADACC_PICK(p.half, place_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
-  return launch_check("place_kernel");
+  if (p.tail != 0) {  // after the placement: the tail's outliers go behind those of the main part
+    hipLaunchKernelGGL(ADACC_PICK(p.half, compress_tail_fn()), dim3(1), dim3(kWave), 0, s, d);
+    rc = launch_check("compress_tail_kernel");
+  }
+  return rc;
 }
 
 int adacc_compress(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
@@ -648,11 +670,20 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   TensorDesc d;
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, nullptr, &d);
   DecompressFn fn = ADACC_PICK(p.half, decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
-  uint32_t grid = 0;
-  rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid);
-  if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, p.outliers ? 1u : 0u);
-  return launch_check("decompress_kernel");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (d.n_tiles != 0) {
+    uint32_t grid = 0;
+    rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid);
+    if (rc != ADACC_OK) return rc;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, d, p.outliers ? 1u : 0u);
+    rc = launch_check("decompress_kernel");
+    if (rc != ADACC_OK) return rc;
+  }
+  if (p.tail != 0) {  // writes elements the kernel above does not touch
+    hipLaunchKernelGGL(ADACC_PICK(p.half, decompress_tail_fn()), dim3(1), dim3(kWave), 0, s, d);
+    rc = launch_check("decompress_tail_kernel");
+  }
+  return rc;
 }
 
 static int batch_prepare(uint32_t n, const adacc_method* methods, const uint64_t* numels, std::vector<Plan>* plans,
@@ -736,7 +767,7 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   const uint32_t nt = (uint32_t)descs.size();
   std::vector<uint32_t> units(nt), members;
   std::vector<int> kind(nt);
-  std::vector<GroupLaunch> tiles, sums, places;
+  std::vector<GroupLaunch> tiles, sums, places, tails;
   for (uint32_t i = 0; i < nt; ++i) {
     units[i] = descs[i].n_tiles;
     kind[i] = batch_kind(&methods[origin[i]], plans[origin[i]]) + (plans[origin[i]].half ? kBatchKinds : 0);
@@ -749,6 +780,8 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   group_launches(units, kind, &members, &sums);
   for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].n_blocks;
   group_launches(units, kind, &members, &places);
+  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].tail != 0u ? 1u : 0u;
+  group_launches(units, kind, &members, &tails);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t epoch = 0;
   rc = next_epoch(ws, s, &epoch);
@@ -770,7 +803,12 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   for (const GroupLaunch& g : places)
     hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, place_batch_fn()), dim3(g.max_units, g.n_members), dim3(kPlaceThreads), 0, s, dt,
                        dm + g.first_member, epoch);
-  return launch_check("place_batch_kernel");
+  rc = launch_check("place_batch_kernel");
+  if (rc != ADACC_OK) return rc;
+  for (const GroupLaunch& g : tails)  // one workgroup per tensor that has a tail, after the placement
+    hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, compress_tail_batch_fn()), dim3(g.n_members), dim3(kWave), 0, s, dt,
+                       dm + g.first_member);
+  return launch_check("compress_tail_batch_kernel");
 }
 
 int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* const* blobs, const uint64_t* blob_bytes,
@@ -806,6 +844,9 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
     kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
   }
   group_launches(units, kind, &members, &launches);
+  std::vector<GroupLaunch> tails;
+  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].tail != 0u ? 1u : 0u;
+  group_launches(units, kind, &members, &tails);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
   TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
@@ -816,6 +857,9 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   for (const GroupLaunch& g : launches)
     hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, decompress_batch_fn(dst_dtype == ADACC_DST_F32)),
                        dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members), dim3(kThreads), 0, s, dt,
+                       dm + g.first_member);
+  for (const GroupLaunch& g : tails)
+    hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, decompress_tail_batch_fn()), dim3(g.n_members), dim3(kWave), 0, s, dt,
                        dm + g.first_member);
   return launch_check("decompress_batch_kernel");
 }
@@ -1065,9 +1109,9 @@ uint64_t adacc_compressed_bytes(const adacc_method* method, uint64_t numel, uint
   Plan p;
   if (make_plan(method, numel, &p) != ADACC_OK) return 0;
   if (p.noop) return 2ull * numel;
-  const uint64_t groups = numel / method->quant_group;
-  uint64_t bytes = numel * method->bits / 8 + 4ull * groups * (method->asym ? 2u : 1u);
-  if (p.outliers) bytes += 6ull * n_outliers + 4ull * ((uint64_t)p.n_tiles + 1u);
+  const uint64_t groups = (numel + method->quant_group - 1) / method->quant_group;
+  uint64_t bytes = (numel * method->bits + 7) / 8 + 4ull * groups * (method->asym ? 2u : 1u);
+  if (p.outliers) bytes += 6ull * n_outliers + 4ull * ((uint64_t)p.n_tiles_all + 1u);
   return bytes;
 }
 

@@ -84,8 +84,11 @@ struct TensorDesc {
   uint2* slot;              // compress, workspace (ABS / STD): kSlot records (index, value) per tile, the tile's
                             //   outliers until the placement kernel has moved them to the stream
   uint32_t* flag;           // compress, workspace (TOPK): set to the epoch by a tile whose count is not the regular one
-  uint64_t numel;
-  uint32_t n_tiles;
+  uint64_t numel;           // elements the tile kernels take: the whole groups of the larger kind
+  uint32_t tail;            // elements after those (fewer than the larger group), done by the tail kernels
+  uint32_t n_tiles;         // tiles of the first numel elements (decompress: pieces of 2048 of them)
+  uint32_t n_tiles_all;     // tiles of the whole tensor, tail included: tile_ptr has one entry more
+  uint32_t bits, asym, mode;  // the method, for kernels that do not get it as template arguments
   uint32_t n_blocks;        // compress: blocks of kPlaceTiles tiles (placement kernels)
   uint32_t lgt;             // log2(elements per tile): 11 or 12
   uint32_t lgq;         // log2(quant group)

@@ -14,6 +14,8 @@ typedef void (*PlaceSumFn)(TensorDesc);
 typedef void (*PlaceFn)(TensorDesc, uint32_t);
 typedef void (*PlaceSumBatchFn)(const TensorDesc*, const uint32_t*);
 typedef void (*PlaceBatchFn)(const TensorDesc*, const uint32_t*, uint32_t);
+typedef void (*TailFn)(TensorDesc);
+typedef void (*TailBatchFn)(const TensorDesc*, const uint32_t*);
 
 // Types of the channel and channel-wise kernels
 typedef void (*ChannelPartialFn)(const uint16_t*, uint32_t, uint32_t, float*, uint32_t);
@@ -42,6 +44,10 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   PlaceFn place_fn();                                                                  \
   PlaceSumBatchFn place_sum_batch_fn();                                                \
   PlaceBatchFn place_batch_fn();                                                       \
+  TailFn compress_tail_fn();                                                           \
+  TailBatchFn compress_tail_batch_fn();                                                \
+  TailFn decompress_tail_fn();                                                         \
+  TailBatchFn decompress_tail_batch_fn();                                              \
   ChannelPartialFn channel_partial_fn();                                               \
   ChannelScoreFn channel_score_fn();                                                   \
   ChannelSelectFn channel_select_fn();                                                 \

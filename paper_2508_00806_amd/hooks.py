@@ -74,8 +74,8 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
     on_overflow="raise" (the default) makes the backward pass raise `CompressedActivationLost`;
     on_overflow="retain" waits for the status right after compression and saves the tensor as it is when
     the blob can not hold it (one synchronisation per compressed tensor in the forward pass).
-    A tensor whose address or size the library does not take (not 16-byte aligned, a size its groups do
-    not divide) is saved as it is.
+    A tensor whose address or shape the library does not take (not 16-byte aligned; for outlier channels a
+    size the groups do not divide or a last dimension that is no multiple of 8) is saved as it is.
     """
 
     def __init__(self, policy, timing=True, pack_masks=True, on_overflow="raise"):

@@ -97,8 +97,17 @@ def test_malformed_methods(L, m):
 
 def test_numel_rules(L):
     m = Method(bits=8, quant_group=64)
+    a = lambda v: (v + 255) // 256 * 256
+    lay = adacc.layout_of(m, 100)  # the group does not divide numel: two groups, the second of 36 elements
+    assert (lay.scales_off, lay.zp_off - lay.scales_off, lay.n_tiles) == (a(100), a(4 * 2), 1)
+    m4 = Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=2048, topk=2, max_outliers=64)
+    lay = adacc.layout_of(m4, 2048 * 3 + 77)  # int4, odd length: the last byte holds one element
+    assert lay.scales_off == a((2048 * 3 + 77 + 1) // 2) and lay.n_tiles == 4
+    assert lay.idx_off - lay.tile_ptr_off == a(4 * 5)
+    assert adacc.compressed_bytes(m4, 2048 * 3 + 77, 7) == (2048 * 3 + 78) // 2 + 4 * 49 + 6 * 7 + 4 * 5
+    cm = adacc.ChannelMethod(bits=4, quant_group=128, max_channels=4)
     with pytest.raises(adacc.AdaccError):
-        adacc.layout_of(m, 100)  # group does not divide numel
+        adacc.channel_layout_of(cm, 3, 200)  # with outlier channels the group still has to divide the tensor
     mo = Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=4)
     with pytest.raises(adacc.AdaccError):
         adacc.layout_of(mo, 1 << 31)  # 32-bit indices
@@ -129,7 +138,8 @@ def test_errors_are_returned_before_any_device_work(L):
     assert f(ctypes.byref(cm), src + 2, n, blob, lay.total_bytes, w, None) == adacc.EALIGN
     assert f(ctypes.byref(cm), src, n, blob + 16, lay.total_bytes, w, None) == adacc.EALIGN
     assert f(ctypes.byref(cm), src, n, blob, lay.total_bytes, ctypes.byref(odd), None) == adacc.EALIGN
-    assert f(ctypes.byref(cm), src, n + 1, blob, lay.total_bytes, w, None) == adacc.EINVAL
+    assert f(ctypes.byref(cm), src, 1 << 31, blob, lay.total_bytes, w, None) == adacc.EINVAL  # 32-bit indices
+    assert f(ctypes.byref(cm), src, n + 1, blob, lay.total_bytes, w, None) == adacc.ESIZE   # one more group
     assert ws.epoch == 0  # a rejected call does not consume an epoch
     # nothing to do: OK without looking at the pointers
     assert f(ctypes.byref(cm), None, 0, None, 0, None, None) == adacc.OK

@@ -194,11 +194,13 @@ def test_a_blob_that_overflowed_can_fall_back_to_the_tensor(kind):
 
 
 def test_tensors_the_library_does_not_take_are_saved_as_they_are():
-    """A contiguous view at an address that is not a multiple of 16 bytes, and a size the groups do not
-    divide: no error in the forward pass, the tensor is retained."""
+    """A contiguous view at an address that is not a multiple of 16 bytes, and (outlier channels) a size
+    the groups do not divide: no error in the forward pass, the tensor is retained."""
     print("[hooks] misaligned and indivisible tensors", flush=True)
-    m = adacc.Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=64, thresh=6.0, max_outliers=4096)
-    for tokens, hidden, offset in ((32, 256, 1), (30, 100, 0)):
+    for tokens, hidden, offset, m in (
+            (32, 256, 1, adacc.Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=64, thresh=6.0,
+                                      max_outliers=4096)),
+            (30, 104, 0, adacc.ChannelMethod(bits=4, quant_group=128, max_channels=8))):
         torch.manual_seed(5)
         buf = torch.randn(tokens * hidden + 8).to(torch.bfloat16).cuda()
         x = buf[offset:offset + tokens * hidden].view(tokens, hidden)
