@@ -176,12 +176,17 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t m) {
 // and leaves that integer, in two's complement, in the low mantissa bits; the clip is a median
 // with the two bounds shifted the same way ("values greater than 7 are capped at 7"); a NaN
 // lands on the lower bound.
+// Symmetric codes need the upper bound only: |y| <= max and inv = RN(D / max) (or less, when that was cut
+// to the largest finite value) give |y * inv| <= D * (1 + 2^-24), which rounds to at most D <= Q in
+// magnitude, -Q is a code, and neither factor can be a NaN or infinite.  (Asymmetric codes keep both
+// bounds: a group of huge values can make O infinite and the product a NaN.)
 constexpr float kMagic = 12582912.0f;
-template <int Q>
+template <int Q, bool BOTH_BOUNDS = true>
 __device__ __forceinline__ uint32_t code_bits(float y, float inv) {
   const float p = __fmul_rn(y, inv);
   const float r = __fadd_rn(p, kMagic);
-  return __float_as_uint(fminf(fmaxf(r, kMagic - (float)Q), kMagic + (float)(Q - 1)));
+  if constexpr (BOTH_BOUNDS) return __float_as_uint(fminf(fmaxf(r, kMagic - (float)Q), kMagic + (float)(Q - 1)));
+  else return __float_as_uint(fminf(r, kMagic + (float)(Q - 1)));
 }
 
 __device__ __forceinline__ uint32_t pack_bytes4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
@@ -537,7 +542,7 @@ __device__ __forceinline__ void encode_clean_row(const TensorDesc& d, const Tile
   }
   uint32_t c[kOct];
 #pragma unroll
-  for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? x[e] - off : x[e], inv);
+  for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q, ASYM>(ASYM ? x[e] - off : x[e], inv);
   store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
 }
 
@@ -622,7 +627,7 @@ __device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileG
       }
       uint32_t c[kOct];
 #pragma unroll
-      for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off : y[e], inv);
+      for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q, ASYM>(ASYM ? y[e] - off : y[e], inv);
       store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
     }
     if constexpr (MODE != kModeNone) {
@@ -682,15 +687,24 @@ template <int E, bool WHOLE>
 __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint32_t (&rowmag)[E], uint32_t (&thr)[E]) {
   const uint32_t lane = (uint32_t)lane_id();
   if constexpr (WHOLE) {  // one group per tile, the usual case, in straight-line code
-    uint32_t m = rowmag[0];
+    // Every lane offers its two largest row maxima: the threshold then fails to cut off exactly k
+    // elements only when a lane holds three of the k largest, or two of them in one octet, or on a tie.
+    uint32_t m1 = rowmag[0], m2 = 0u;
 #pragma unroll
-    for (int j = 1; j < E; ++j) m = m > rowmag[j] ? m : rowmag[j];
-    const bool finite = __builtin_amdgcn_ballot_w64(m >= kNonfiniteMag) == 0ull;
-    uint32_t cur = (m << 6) | lane;  // unique per lane: equal maxima are taken one after the other
-    uint32_t win = 0u;               // uniform
+    for (int j = 1; j < E; ++j) {
+      const uint32_t lo = m1 < rowmag[j] ? m1 : rowmag[j];
+      m2 = m2 > lo ? m2 : lo;
+      m1 = m1 > rowmag[j] ? m1 : rowmag[j];
+    }
+    const bool finite = __builtin_amdgcn_ballot_w64(m1 >= kNonfiniteMag) == 0ull;
+    uint32_t cur = (m1 << 6) | lane;  // unique per lane: equal maxima are taken one after the other
+    uint32_t nxt = (m2 << 6) | lane;
+    uint32_t win = 0u;                // uniform
     for (uint32_t r = 0; r < d.topk; ++r) {
       win = wave_max_u32_scalar(cur);
-      cur = (cur == win) ? 0u : cur;
+      const bool won = cur == win;
+      cur = won ? nxt : cur;
+      nxt = won ? 0u : nxt;
     }
 #pragma unroll
     for (int j = 0; j < E; ++j) thr[j] = mag_bits32(win >> 6);
@@ -920,7 +934,7 @@ __device__ __forceinline__ void finish_tile(const TensorDesc& d, const TileGeo<E
     }
     uint32_t c[kOct];
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q>(ASYM ? y[e] - off[j] : y[e], inv[j]);
+    for (int e = 0; e < kOct; ++e) c[e] = code_bits<Q, ASYM>(ASYM ? y[e] - off[j] : y[e], inv[j]);
     store_row<BITS, ASYM, E>(d, g, j, c, scl[j], off[j]);
   }
 }
