@@ -41,7 +41,9 @@ __global__ __launch_bounds__(kPlaceThreads) void place_sum_kernel(TensorDesc d) 
   place_sum_block(d, blockIdx.x, part);
 }
 
-__global__ __launch_bounds__(kPlaceThreads) void place_kernel(TensorDesc d, uint32_t epoch) {
+// The selection code for tiles that have to be looked at again (rare) would take 173 registers and leave room
+// for two wavefronts per SIMD; the kernel is a chain of dependent memory round trips, so it is held to 128.
+__global__ __launch_bounds__(kPlaceThreads, 4) void place_kernel(TensorDesc d, uint32_t epoch) {
   __shared__ PlaceShared sh;
   place_dispatch(d, blockIdx.x, epoch, sh);
 }
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(kPlaceThreads) void place_sum_batch_kernel(const Te
   if (blockIdx.x < d.n_blocks) place_sum_block(d, blockIdx.x, part);
 }
 
-__global__ __launch_bounds__(kPlaceThreads) void place_batch_kernel(const TensorDesc* table, const uint32_t* members,
+__global__ __launch_bounds__(kPlaceThreads, 4) void place_batch_kernel(const TensorDesc* table, const uint32_t* members,
                                                                     uint32_t epoch) {
   __shared__ PlaceShared sh;
   const TensorDesc d = table[members[blockIdx.y]];
