@@ -681,35 +681,39 @@ __device__ __forceinline__ void row_magnitudes(const uint32_t (&raw)[E][4], uint
   }
 }
 
+// One group per tile, in straight-line code: t16 <- the k-th largest of the candidates the lanes offer, as
+// a 15-bit magnitude.  Returns (uniform) false when the tile holds an Inf or NaN.
+// Every lane offers its two largest row maxima: the threshold then fails to cut off exactly k
+// elements only when a lane holds three of the k largest, or two of them in one octet, or on a tie.
+template <int E>
+__device__ __forceinline__ bool topk_whole_threshold(const TensorDesc& d, const uint32_t (&rowmag)[E], uint32_t& t16) {
+  const uint32_t lane = (uint32_t)lane_id();
+  uint32_t m1 = rowmag[0], m2 = 0u;
+#pragma unroll
+  for (int j = 1; j < E; ++j) {
+    const uint32_t lo = m1 < rowmag[j] ? m1 : rowmag[j];
+    m2 = m2 > lo ? m2 : lo;
+    m1 = m1 > rowmag[j] ? m1 : rowmag[j];
+  }
+  const bool finite = __builtin_amdgcn_ballot_w64(m1 >= kNonfiniteMag) == 0ull;
+  uint32_t cur = (m1 << 6) | lane;  // unique per lane: equal maxima are taken one after the other
+  uint32_t nxt = (m2 << 6) | lane;
+  uint32_t win = 0u;                // uniform
+  for (uint32_t r = 0; r < d.topk; ++r) {
+    win = wave_max_u32_scalar(cur);
+    const bool won = cur == win;
+    cur = won ? nxt : cur;
+    nxt = won ? 0u : nxt;
+  }
+  t16 = win >> 6;
+  return finite;
+}
+
 // thr[j] <- the k-th largest lane maximum of row j's group, as the bits of a binary32 value.
 // Returns (uniform) false when the tile holds an Inf or NaN.
-template <int E, bool WHOLE>
+template <int E>
 __device__ __forceinline__ bool topk_lane_maxima(const TensorDesc& d, const uint32_t (&rowmag)[E], uint32_t (&thr)[E]) {
   const uint32_t lane = (uint32_t)lane_id();
-  if constexpr (WHOLE) {  // one group per tile, the usual case, in straight-line code
-    // Every lane offers its two largest row maxima: the threshold then fails to cut off exactly k
-    // elements only when a lane holds three of the k largest, or two of them in one octet, or on a tie.
-    uint32_t m1 = rowmag[0], m2 = 0u;
-#pragma unroll
-    for (int j = 1; j < E; ++j) {
-      const uint32_t lo = m1 < rowmag[j] ? m1 : rowmag[j];
-      m2 = m2 > lo ? m2 : lo;
-      m1 = m1 > rowmag[j] ? m1 : rowmag[j];
-    }
-    const bool finite = __builtin_amdgcn_ballot_w64(m1 >= kNonfiniteMag) == 0ull;
-    uint32_t cur = (m1 << 6) | lane;  // unique per lane: equal maxima are taken one after the other
-    uint32_t nxt = (m2 << 6) | lane;
-    uint32_t win = 0u;                // uniform
-    for (uint32_t r = 0; r < d.topk; ++r) {
-      win = wave_max_u32_scalar(cur);
-      const bool won = cur == win;
-      cur = won ? nxt : cur;
-      nxt = won ? 0u : nxt;
-    }
-#pragma unroll
-    for (int j = 0; j < E; ++j) thr[j] = mag_bits32(win >> 6);
-    return finite;
-  }
   const int R = 1 << (d.lgs - 9);  // rows per group (the caller guarantees lgs >= 9)
   uint32_t m[E];
 #pragma unroll
@@ -994,7 +998,7 @@ __device__ __forceinline__ void encode_tile_general(const TensorDesc& d, const T
       bool by_magnitude = false;
       if (try_maxima) {
         if constexpr (ASYM) row_magnitudes<E>(raw, rowmag);
-        by_magnitude = topk_lane_maxima<E, false>(d, rowmag, thr);
+        by_magnitude = topk_lane_maxima<E>(d, rowmag, thr);
       }
       if (!by_magnitude) {
         // nothing on this rare path may be prepared outside the loop over tiles (32 position codes
@@ -1095,42 +1099,70 @@ __device__ __forceinline__ uint32_t topk_extract_by_keys(const TensorDesc& d, ui
   return total;
 }
 
+// The elements of one octet (that of lane `owner`, a uniform number) whose magnitude reaches t16 leave for
+// the sink, in index order from entry `pos` on, and are cleared in the owner's registers.  The octet is
+// broadcast through scalar registers and lanes 0..7 take one element each.  Returns their number (uniform).
+template <class Sink>
+__device__ __forceinline__ uint32_t extract_octet(uint32_t (&oct)[4], uint32_t owner, uint32_t t16, uint32_t first_index,
+                                                  const Sink& sink, uint32_t pos, uint32_t limit) {
+  const uint32_t lane = (uint32_t)lane_id();
+  const uint32_t w0 = (uint32_t)__builtin_amdgcn_readlane((int)oct[0], (int)owner);
+  const uint32_t w1 = (uint32_t)__builtin_amdgcn_readlane((int)oct[1], (int)owner);
+  const uint32_t w2 = (uint32_t)__builtin_amdgcn_readlane((int)oct[2], (int)owner);
+  const uint32_t w3 = (uint32_t)__builtin_amdgcn_readlane((int)oct[3], (int)owner);
+  const uint32_t e = lane & 7u;
+  const uint32_t lo = (e & 4u) ? w2 : w0;
+  const uint32_t hi = (e & 4u) ? w3 : w1;
+  const uint32_t word = (e & 2u) ? hi : lo;
+  const uint32_t pat = (e & 1u) ? word >> 16 : word & 0xFFFFu;
+  const bool hit = lane < 8u && (pat & 0x7FFFu) >= t16;
+  const uint32_t m8 = (uint32_t)__builtin_amdgcn_ballot_w64(hit);  // bit e: element e
+  if (hit) {
+    const uint32_t p = pos + __builtin_amdgcn_mbcnt_lo(m8, 0u);
+    if (p < limit) sink(p, first_index + e, pat);
+  }
+  if (lane == owner) clear_elements(oct, m8);
+  return (uint32_t)__builtin_popcount(m8);
+}
+
 // The extraction: finds the k largest, hands them to the sink, clears them in `raw`.  rowmag: the
 // lane's largest magnitude per row of what is left.  Returns the number of outliers (uniform).
 template <int E, bool STORE, class Sink>
 __device__ __forceinline__ uint32_t topk_extract(const TensorDesc& d, uint32_t (&raw)[E][4], uint32_t (&rowmag)[E],
                                                  uint32_t tile, const Sink& sink, uint32_t pos0, uint32_t limit) {
   row_magnitudes<E>(raw, rowmag);
-  const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
+  const uint32_t tile_first = tile * (uint32_t)(E * kRow);
   uint32_t total = 0u;  // uniform: outliers found
   bool done = false;    // uniform
   if (d.topk <= 8u) {
-    uint32_t thr[E];
-    if (topk_lane_maxima<E, true>(d, rowmag, thr)) {  // false if the tile holds an Inf or a NaN
-      // Selection |x| >= t, t the k-th largest of the lanes' maxima: it is the answer if exactly k
-      // elements pass.  Only rows in which some lane's largest magnitude reaches t can hold any.
-      // The outliers leave and are cleared as they are found; if in the end they were not k (two of
-      // the largest in one lane, a tie at the k-th place: a tile in a hundred) the tile is read
-      // again and done by keys.
-      const uint32_t t = thr[0];
-      const float tf = __uint_as_float(t);
+    uint32_t t16;
+    if (topk_whole_threshold<E>(d, rowmag, t16)) {  // false if the tile holds an Inf or a NaN
+      // Selection |x| >= t: it is the answer if exactly k elements pass.  Only octets whose largest magnitude
+      // reaches t can hold any; there are at most k of them if the selection is to stand, so they are
+      // taken one at a time (a constant tile, where every octet passes, goes straight to the keys).
+      uint64_t cand[E];
+      uint32_t octets = 0u;
 #pragma unroll
       for (int j = 0; j < E; ++j) {
-        if (__builtin_amdgcn_ballot_w64(mag_bits32(rowmag[j]) >= t) == 0ull) continue;  // uniform
-        float x[kOct];
-        widen_row(raw[j], x);
-        uint64_t b[kOct];
-#pragma unroll
-        for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(fabsf(x[e]) >= tf);
-        uint32_t mask, lane_excl, row_cnt;
-        bool any, sparse;
-        row_bookkeeping(b, mask, lane_excl, row_cnt, any, sparse);
-        emit_row(raw[j], mask, lane_excl, sparse, lane_first + (uint32_t)(j * kRow), sink, pos0 + total, limit);
-        total += row_cnt;
-        clear_elements(raw[j], mask);
-        rowmag[j] = octet_magnitude(raw[j]);
+        cand[j] = __builtin_amdgcn_ballot_w64(rowmag[j] >= t16);
+        octets += (uint32_t)__builtin_popcountll(cand[j]);
       }
-      done = total == d.topk;
+      if (octets <= d.topk) {
+        // The outliers leave and are cleared as they are found; if in the end they were not k (two of
+        // the largest in one octet, a tie at the k-th place) the tile is read again and done by keys.
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          uint64_t todo = cand[j];
+          if (todo == 0ull) continue;  // uniform
+          do {
+            const uint32_t owner = (uint32_t)__builtin_ctzll(todo);
+            todo &= todo - 1ull;
+            total += extract_octet(raw[j], owner, t16, tile_first + (uint32_t)(j * kRow) + owner * kOct, sink, pos0 + total, limit);
+          } while (todo != 0ull);
+          rowmag[j] = octet_magnitude(raw[j]);
+        }
+        done = total == d.topk;
+      }
     }
   }
   if (!done) {

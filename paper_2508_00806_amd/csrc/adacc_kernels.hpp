@@ -19,7 +19,7 @@ namespace ADACC_DT_NS {
 template <int E, bool ROWWISE, bool WHOLE>
 constexpr int compress_min_waves() {
   if (ROWWISE) return 6;
-  if (WHOLE) return E == 8 ? 5 : 8;
+  if (WHOLE) return E == 8 ? 7 : 8;
   return E == 8 ? 2 : 4;
 }
 template <int MODE, int BITS, bool ASYM, int E, bool ROWWISE, bool WHOLE = false>
@@ -79,7 +79,7 @@ __device__ __forceinline__ void compress_dispatch(const TensorDesc& d, uint32_t 
 
 template <int KIND>
 constexpr int batch_min_waves() {
-  return KIND == kBatchRows4 ? 6 : KIND == kBatchTopk4 ? 8 : KIND == kBatchTopk8 ? 5 : KIND == kBatchAny4 ? 4 : 2;
+  return KIND == kBatchRows4 ? 6 : KIND == kBatchTopk4 ? 8 : KIND == kBatchTopk8 ? 7 : KIND == kBatchAny4 ? 4 : 2;
 }
 
 template <int KIND>
