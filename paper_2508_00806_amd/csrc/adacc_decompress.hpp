@@ -12,8 +12,9 @@ namespace ADACC_DT_NS {
 // blob: a piece of a 4096-element tile looks through the outliers of the whole tile and takes
 // those that fall inside it.
 //
-// The outliers are written over the dequantised values in memory: the piece is stored first, the
-// wavefront waits until those stores have reached the L2 (its store counter at zero), and then
+// A piece whose tile has up to 6 outliers takes them into the output words in registers before they are
+// stored.  With more, the outliers are written over the dequantised values in memory: the piece is stored
+// first, the wavefront waits until those stores have reached the L2 (its store counter at zero), and then
 // stores the outliers of the piece, 2 (or 4) bytes each, to their positions.  Both rounds of
 // stores come from the same wavefront and the second is issued only after the first is complete,
 // so the outliers are what stays.  (Staging the piece in LDS to patch it there cost a round trip
@@ -39,9 +40,41 @@ __device__ __forceinline__ void load_row_codes(const TensorDesc& d, uint64_t e0,
   if constexpr (ASYM) r.o = d.zp[g];
 }
 
-// a9 for one row: unpack, dequantise, store
-template <int BITS, bool ASYM, bool F32>
-__device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e0, const RowCodes<BITS>& r) {
+// The outliers of a piece that has only a few of them, applied to the output words of row `row` before they
+// are stored.  Lane i holds entry i of the tile's slice of the stream (o_idx, o_val); `n` entries, uniform.
+// Every entry is looked at through scalar registers: row, lane and element of its index are uniform, so the
+// row test is a scalar branch and the update one select per output word.  WORDS = 4 (two 16-bit values per
+// word) or 8 (binary32).
+constexpr uint32_t kRegisterPatchMax = 6;
+template <int WORDS>
+__device__ __forceinline__ void patch_row_words(uint32_t (&w)[WORDS], uint32_t row, uint64_t tile_base, uint32_t o_idx,
+                                                uint32_t o_val, uint32_t n) {
+  const uint32_t lane = (uint32_t)__lane_id();
+  const uint32_t base = (uint32_t)tile_base;  // a tensor that keeps outliers has fewer than 2^31 elements
+  for (uint32_t i = 0; i < n; ++i) {
+    const uint32_t rel = (uint32_t)__builtin_amdgcn_readlane((int)o_idx, (int)i) - base;
+    if ((rel >> 9) != row) continue;  // uniform; also what lies outside the piece (a 4096-element tile's other half)
+    const uint32_t pat = (uint32_t)__builtin_amdgcn_readlane((int)o_val, (int)i);
+    const bool mine = lane == ((rel >> 3) & 63u);
+    const uint32_t e = rel & 7u;
+    if constexpr (WORDS == 8) {
+      const uint32_t bits = __float_as_uint(widen_lo(pat));
+#pragma unroll
+      for (int k = 0; k < 8; ++k) w[k] = (mine && e == (uint32_t)k) ? bits : w[k];
+    } else {
+      const uint32_t keep = (e & 1u) ? 0x0000FFFFu : 0xFFFF0000u;
+      const uint32_t put = (e & 1u) ? pat << 16 : pat;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) w[k] = (mine && (e >> 1) == (uint32_t)k) ? ((w[k] & keep) | put) : w[k];
+    }
+  }
+}
+
+// a9 for one row: unpack, dequantise, [patch a few outliers in,] store
+template <int BITS, bool ASYM, bool F32, bool PATCH = false>
+__device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e0, const RowCodes<BITS>& r, uint32_t row = 0u,
+                                                 uint64_t tile_base = 0u, uint32_t o_idx = 0u, uint32_t o_val = 0u,
+                                                 uint32_t n_patch = 0u) {
   int c[kOct];
   if constexpr (BITS == 8) {
 #pragma unroll
@@ -57,16 +90,19 @@ __device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e
 #pragma unroll
   for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)c[e], r.s, r.o) : (float)c[e] * r.s;
   if constexpr (F32) {
+    uint32_t w[8];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) w[e] = __float_as_uint(v[e]);
+    if constexpr (PATCH) patch_row_words<8>(w, row, tile_base, o_idx, o_val, n_patch);
     float* p = reinterpret_cast<float*>(d.dst) + e0;
-    ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
-    ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
+    ADACC_STORE16(p, make_uint4(w[0], w[1], w[2], w[3]));
+    ADACC_STORE16(p + 4, make_uint4(w[4], w[5], w[6], w[7]));
   } else {
-    uint4 w;
-    w.x = narrow_pair(v[0], v[1]);
-    w.y = narrow_pair(v[2], v[3]);
-    w.z = narrow_pair(v[4], v[5]);
-    w.w = narrow_pair(v[6], v[7]);
-    ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, w);
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = narrow_pair(v[2 * k], v[2 * k + 1]);
+    if constexpr (PATCH) patch_row_words<4>(w, row, tile_base, o_idx, o_val, n_patch);
+    ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, make_uint4(w[0], w[1], w[2], w[3]));
   }
 }
 
@@ -108,7 +144,14 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
     o_val = d.val[p0 + (uint32_t)lane];
   }
 
-  // ---- a9: unpack, dequantise, store
+  // ---- a9: unpack, dequantise, store.  A complete piece with only a few outliers (TOPK tensors: every piece)
+  // takes them in on the way, in registers: nothing is written twice and nothing waits for a store.
+  if (complete && patch && p1 - p0 <= kRegisterPatchMax) {
+#pragma unroll
+    for (int j = 0; j < E; ++j)
+      store_row_values<BITS, ASYM, F32, true>(d, lane_base + (uint64_t)j * kRow, rc[j], (uint32_t)j, tile_base, o_idx, o_val, p1 - p0);
+    return;
+  }
   if (complete) {
 #pragma unroll
     for (int j = 0; j < E; ++j) store_row_values<BITS, ASYM, F32>(d, lane_base + (uint64_t)j * kRow, rc[j]);
