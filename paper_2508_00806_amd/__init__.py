@@ -276,7 +276,7 @@ def batch_workspace_bytes(methods, numels) -> int:
 
 # ---------------------------------------------------------------- device calls
 class Workspace:
-    """A scan workspace: the adacc_workspace struct plus the torch buffer it points to."""
+    """A workspace of compression with outliers: the adacc_workspace struct plus the torch buffer it points to."""
 
     def __init__(self, buffer, stream=None):
         self.buffer = buffer  # keeps the device memory alive
@@ -367,7 +367,7 @@ def decompress_batch(methods, blobs, dsts, workspace, stream=None, prepared: Bat
 
 
 def read_status(blob, layout: CLayout, stream=None):
-    """(n_outliers, overflow, aborted, 0) - waits for the stream."""
+    """(n_outliers, overflow, 0, 0) - waits for the stream."""
     out = (ctypes.c_uint32 * 4)()
     _check(lib().adacc_read_status(_ptr(blob), ctypes.byref(layout), _stream(stream), ctypes.byref(out)),
            "adacc_read_status")
@@ -529,7 +529,7 @@ def alloc_blob(method: Method, numel: int, device="cuda"):
 
 
 def alloc_workspace(nbytes: int, device="cuda", stream=None) -> Workspace:
-    """A cleared scan workspace of at least nbytes."""
+    """A cleared workspace of at least nbytes."""
     import torch
     buf = torch.empty(max((int(nbytes) + 255) // 256 * 256, 512), dtype=torch.uint8, device=device)
     return Workspace(buf, stream)

@@ -919,7 +919,7 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
   const uint32_t n_items = cp.n_chunks * (hidden / 8);  // one lane: 8 channels of one chunk
-  hipLaunchKernelGGL(ADACC_PICK(half, channel_partial_fn()), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+  hipLaunchKernelGGL(ADACC_PICK(half, channel_partial_fn(2ull * cp.numel > kStatsKeepBytes)), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
                      static_cast<const uint16_t*>(src), (uint32_t)tokens, hidden, partial, n_items);
   rc = launch_check("channel_partial_kernel");
   if (rc != ADACC_OK) return rc;
@@ -1003,6 +1003,12 @@ uint64_t adacc_channelwise_workspace_bytes(uint64_t tokens, uint32_t hidden) {
   return channelwise_partial_bytes(tokens, hidden) + align256(4ull * hidden);
 }
 
+// one wavefront per strip of 512 channels and `rows` tokens, four wavefronts per workgroup
+static uint32_t channelwise_strip_grid(uint64_t tokens, uint32_t hidden, uint32_t rows) {
+  const uint64_t units = ((tokens + rows - 1) / rows) * ((hidden + 511u) / 512u);
+  return (uint32_t)((units + kWavesPerWg - 1) / kWavesPerWg);  // tokens * hidden < 2^32: far below 2^31
+}
+
 static void channelwise_desc(uint32_t bits, uint32_t scale_rule, uint64_t tokens, uint32_t hidden,
                              const adacc_channelwise_layout& L, void* blob, ChannelwiseDesc* c) {
   std::memset(c, 0, sizeof *c);
@@ -1016,7 +1022,6 @@ static void channelwise_desc(uint32_t bits, uint32_t scale_rule, uint64_t tokens
   const float q = (float)(1u << (bits - 1));
   c->divisor = scale_rule == ADACC_SCALE_PAPER ? q : q - 1.0f;
   c->inv_divisor = scale_rule == ADACC_SCALE_PAPER ? 1.0f / q : 0.0f;  // exact for a power of two
-  c->inv_hidden = std::nextafter(std::nextafter(1.0f / (float)hidden, 0.0f), 0.0f);
 }
 
 int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, uint32_t dtype, const void* src, uint64_t tokens,
@@ -1037,13 +1042,11 @@ int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, uint32_t dtyp
   c.partial = static_cast<uint16_t*>(workspace);
   c.inv = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + channelwise_partial_bytes(tokens, hidden));
   ChannelwiseFn quant = ADACC_PICK(half, channelwise_quantise_fn(bits));
-  const uint32_t n_tiles = (uint32_t)((c.numel + 2047ull) / 2048ull);
-  uint32_t grid = 0;
-  int rc = grid_for(n_tiles, reinterpret_cast<const void*>(quant), &grid);
-  if (rc != ADACC_OK) return rc;
+  const uint32_t grid = channelwise_strip_grid(tokens, hidden, ADACC_PICK(half, channelwise_strip_rows()));
+  int rc = ADACC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t n_items = c.n_chunks * (hidden / 8);
-  hipLaunchKernelGGL(ADACC_PICK(half, channelwise_partial_fn()), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s, c, n_items);
+  hipLaunchKernelGGL(ADACC_PICK(half, channelwise_partial_fn(2ull * c.numel > kStatsKeepBytes)), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s, c, n_items);
   rc = launch_check("channelwise_partial_kernel");
   if (rc != ADACC_OK) return rc;
   const uint32_t per_wg = ADACC_PICK(half, channelwise_fold_octets());
@@ -1069,10 +1072,7 @@ int adacc_channelwise_decompress(uint32_t bits, uint32_t dtype, const void* blob
   channelwise_desc(bits, 0, tokens, hidden, L, const_cast<void*>(blob), &c);
   c.dst = dst;
   ChannelwiseFn fn = ADACC_PICK(dtype == ADACC_DTYPE_F16, channelwise_dequantise_fn(bits, dst_dtype == ADACC_DST_F32));
-  const uint32_t n_tiles = (uint32_t)((c.numel + 2047ull) / 2048ull);
-  uint32_t grid = 0;
-  const int rc = grid_for(n_tiles, reinterpret_cast<const void*>(fn), &grid);
-  if (rc != ADACC_OK) return rc;
+  const uint32_t grid = channelwise_strip_grid(tokens, hidden, ADACC_PICK(dtype == ADACC_DTYPE_F16, channelwise_strip_rows()));
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), c);
   return launch_check("channelwise_dequantise_kernel");
 }

@@ -20,6 +20,7 @@ constexpr int kSelectThreads = 256;     // accumulators of the sums over channel
 // ---- step 1: binary32 sums of |x| over chunks of 64 tokens.  One lane owns 8 adjacent channels
 // (one 16-byte load per token), consecutive lanes consecutive octets: fully coalesced rows.
 // partial[chunk][hidden].
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_t* __restrict__ x, uint32_t tokens,
                                                                    uint32_t hidden, float* __restrict__ partial,
                                                                    uint32_t n_items) {
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_
     for (; r + kBatch <= rows; r += kBatch) {
       uint4 v[kBatch];
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) v[i] = ADACC_LOAD16_KEEP(p + (size_t)(r + i) * hidden);
+      for (uint32_t i = 0; i < kBatch; ++i) v[i] = load_stats16<STREAM>(p + (size_t)(r + i) * hidden);
 #pragma unroll
       for (uint32_t i = 0; i < kBatch; ++i) {
         const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_
       }
     }
     for (; r < rows; ++r) {
-      const uint4 v = ADACC_LOAD16_KEEP(p + (size_t)r * hidden);
+      const uint4 v = load_stats16<STREAM>(p + (size_t)r * hidden);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int k = 0; k < 4; ++k) {

@@ -57,13 +57,15 @@ __device__ __forceinline__ void store_stream4(void* p, uint32_t v) {
 #define ADACC_STORE4(p, v) (*reinterpret_cast<uint32_t*>(p) = (v))
 #endif
 
-// The statistics pass of the two-pass schemes reads what the second pass reads again: by default it
-// leaves the lines to the caches (ADACC_STATS_STREAM makes it a streaming read too).
-#ifdef ADACC_STATS_STREAM
-#define ADACC_LOAD16_KEEP(p) load_stream16(p)
-#else
-#define ADACC_LOAD16_KEEP(p) (*reinterpret_cast<const uint4*>(p))
-#endif
+// The statistics pass of the two-pass schemes reads what the second pass reads again: for a tensor that the
+// Infinity Cache can hold a good part of, it leaves the lines to the caches (plain loads); for a larger one
+// nothing would survive until the second pass, and it streams like every other pass (STREAM).
+constexpr uint64_t kStatsKeepBytes = 128ull << 20;
+template <bool STREAM>
+__device__ __forceinline__ uint4 load_stats16(const void* p) {
+  if constexpr (STREAM) return load_stream16(p);
+  else return *reinterpret_cast<const uint4*>(p);
+}
 
 enum : uint32_t { kModeNone = 0, kModeAbs = 1, kModeStd = 2, kModeTopk = 3 };
 
@@ -131,7 +133,6 @@ struct ChannelwiseDesc {
   uint64_t numel;
   uint32_t tokens, hidden, n_chunks;
   float divisor, inv_divisor;  // D of Eq. 2 and, when D is a power of two, 1/D (else 0)
-  float inv_hidden;     // 1 / hidden rounded towards zero twice
 };
 
 // Outliers of a tile that travel through the tile's slot in the workspace (ABS / STD); a tile with

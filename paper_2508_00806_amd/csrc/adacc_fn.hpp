@@ -29,8 +29,10 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
 // adacc::bf16 and adacc::f16 (the same sources compiled twice).
 //   e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
 //   kind: kBatch* of adacc_common.hpp
+//   stream: the statistics pass reads with the streaming hint (tensors beyond kStatsKeepBytes)
 //   channel_score_channels: channels per workgroup of the score kernel
 //   channelwise_fold_octets: octets of channels per workgroup of the fold kernel
+//   channelwise_strip_rows: tokens a wavefront of the (de)quantisation kernels takes
 #define ADACC_DTYPE_GETTERS                                                            \
   CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);    \
   CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
@@ -48,15 +50,16 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   TailBatchFn compress_tail_batch_fn();                                                \
   TailFn decompress_tail_fn();                                                         \
   TailBatchFn decompress_tail_batch_fn();                                              \
-  ChannelPartialFn channel_partial_fn();                                               \
+  ChannelPartialFn channel_partial_fn(bool stream);                                    \
   ChannelScoreFn channel_score_fn();                                                   \
   ChannelSelectFn channel_select_fn();                                                 \
   uint32_t channel_score_channels();                                                   \
   ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);           \
   ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);             \
-  ChannelwiseItemsFn channelwise_partial_fn();                                         \
+  ChannelwiseItemsFn channelwise_partial_fn(bool stream);                              \
   ChannelwiseFn channelwise_fold_fn();                                                 \
   uint32_t channelwise_fold_octets();                                                  \
+  uint32_t channelwise_strip_rows();                                                   \
   ChannelwiseFn channelwise_quantise_fn(uint32_t bits);                                \
   ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32);
 namespace bf16 {

@@ -5,7 +5,7 @@
 namespace adacc {
 namespace ADACC_DT_NS {
 
-ChannelPartialFn channel_partial_fn() { return channel_partial_kernel; }
+ChannelPartialFn channel_partial_fn(bool stream) { return stream ? channel_partial_kernel<true> : channel_partial_kernel<false>; }
 ChannelScoreFn channel_score_fn() { return channel_score_kernel; }
 ChannelSelectFn channel_select_fn() { return channel_select_kernel; }
 uint32_t channel_score_channels() { return (uint32_t)kScoreChannels; }

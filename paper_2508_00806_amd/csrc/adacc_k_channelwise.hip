@@ -25,6 +25,7 @@ __device__ __forceinline__ uint32_t finite_magnitudes2(uint32_t w) {
 // ---- step 1: partial[chunk][hidden] = max of the finite magnitudes over the chunk's tokens.
 // Same decomposition as the chunk sums of the outlier-channel statistics: a lane owns 8 adjacent
 // channels of one chunk, 16 loads of 16 bytes in flight, rows fully coalesced.
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(ChannelwiseDesc c, uint32_t n_items) {
   const uint32_t octs = c.hidden / kOct;
   for (uint32_t item = blockIdx.x * kThreads + threadIdx.x; item < n_items; item += gridDim.x * kThreads) {
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(Channelwi
     for (; r + kBatch <= rows; r += kBatch) {
       uint4 v[kBatch];
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) v[i] = ADACC_LOAD16_KEEP(p + (size_t)(r + i) * c.hidden);
+      for (uint32_t i = 0; i < kBatch; ++i) v[i] = load_stats16<STREAM>(p + (size_t)(r + i) * c.hidden);
 #pragma unroll
       for (uint32_t i = 0; i < kBatch; ++i) {
         acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v[i].x));
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(Channelwi
       }
     }
     for (; r < rows; ++r) {
-      const uint4 v = ADACC_LOAD16_KEEP(p + (size_t)r * c.hidden);
+      const uint4 v = load_stats16<STREAM>(p + (size_t)r * c.hidden);
       acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v.x));
       acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v.y));
       acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v.z));
@@ -110,46 +111,53 @@ __global__ __launch_bounds__(kThreads) void channelwise_fold_kernel(ChannelwiseD
   }
 }
 
-// channel of an element offset: off = q * hidden + col, through a reciprocal the host rounded down
-__device__ __forceinline__ uint32_t column_of(uint32_t off, uint32_t hidden, float inv_hidden) {
-  const uint32_t q = (uint32_t)((float)off * inv_hidden);
-  uint32_t col = off - __umul24(q, hidden);
-  if (col >= hidden) col -= hidden;
-  return col;
+// ---- steps 3 and X^: a wavefront takes a strip of 512 adjacent channels (8 per lane) over kStripRows
+// consecutive tokens, so the 8 per-channel factors of a lane are loaded once and stay in registers (with
+// tiles of 2048 consecutive elements a lane had to fetch 32 bytes of factors for every 16 bytes of input).
+// Units are numbered strip by strip within a block of tokens, so the four wavefronts of a workgroup take
+// four adjacent strips and the launch walks through memory front to back.
+constexpr uint32_t kStripRows = 8;
+
+struct Strip {
+  uint32_t col;    // first channel of the lane
+  size_t first;    // element offset of the lane's octet in the strip's first token
+  uint32_t rows;   // tokens of the strip (the last block of tokens may be short)
+  bool live;
+};
+__device__ __forceinline__ Strip strip_of(const ChannelwiseDesc& c) {
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t strips = (c.hidden + (uint32_t)kRow - 1u) / (uint32_t)kRow;
+  const uint32_t unit = blockIdx.x * kWavesPerWg + wave;
+  const uint32_t block = unit / strips;
+  const uint32_t row0 = block * kStripRows;
+  Strip s;
+  s.col = (unit - block * strips) * (uint32_t)kRow + (uint32_t)lane_id() * kOct;
+  s.live = row0 < c.tokens && s.col < c.hidden;
+  s.rows = s.live ? (c.tokens - row0 < kStripRows ? c.tokens - row0 : kStripRows) : 0u;
+  s.first = (size_t)row0 * c.hidden + s.col;
+  return s;
 }
 
-// ---- step 3: code = clip(round(x * (D / max_h))), packed, in the tensor's own order.  Tiles of 2048
-// elements, one per wavefront at a time; a lane's 8 elements are 8 adjacent channels of one token.
+// ---- step 3: code = clip(round(x * (D / max_h))), packed, in the tensor's own order
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void channelwise_quantise_kernel(ChannelwiseDesc c) {
-  constexpr int E = 4;
   constexpr int Q = 1 << (BITS - 1);
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const uint32_t lane_off = (uint32_t)lane_id() * kOct;
-  const uint32_t n_tiles = (uint32_t)((c.numel + (E * kRow - 1)) / (E * kRow));
-  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < n_tiles; t += gridDim.x * kWavesPerWg) {
-    const uint32_t base = t * (uint32_t)(E * kRow);  // numel < 2^32
-    const uint32_t left = (uint32_t)(c.numel - base);
-    const uint32_t rem = left < (uint32_t)(E * kRow) ? left : (uint32_t)(E * kRow);
-    const uint32_t col0 = base % c.hidden;
-    uint4 raw[E];
-    float4 inv[E][2];
+  const Strip s = strip_of(c);
+  if (!s.live) return;
+  const float4 i0 = *reinterpret_cast<const float4*>(c.inv + s.col);
+  const float4 i1 = *reinterpret_cast<const float4*>(c.inv + s.col + 4);
+  const float iv[kOct] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+  for (uint32_t r = 0; r < s.rows; r += 4u) {
+    uint4 raw[4];
 #pragma unroll
-    for (int j = 0; j < E; ++j) {  // every load of the tile before its first store
-      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-      const uint32_t off = in_tile < rem ? in_tile : 0u;  // octets past the end re-read the first one
-      raw[j] = ADACC_LOAD16(c.src + (size_t)base + off);
-      const uint32_t col = column_of(col0 + off, c.hidden, c.inv_hidden);
-      inv[j][0] = *reinterpret_cast<const float4*>(c.inv + col);
-      inv[j][1] = *reinterpret_cast<const float4*>(c.inv + col + 4);
+    for (uint32_t i = 0; i < 4u; ++i) {  // four loads in flight; rows past the end re-read the last one
+      const uint32_t row = r + i < s.rows ? r + i : s.rows - 1u;
+      raw[i] = ADACC_LOAD16(c.src + s.first + (size_t)row * c.hidden);
     }
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-      if (in_tile >= rem) continue;
-      const uint32_t w[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
-      const float iv[kOct] = {inv[j][0].x, inv[j][0].y, inv[j][0].z, inv[j][0].w,
-                              inv[j][1].x, inv[j][1].y, inv[j][1].z, inv[j][1].w};
+    for (uint32_t i = 0; i < 4u; ++i) {
+      if (r + i >= s.rows) break;
+      const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
       uint32_t code[kOct];
 #pragma unroll
       for (int e = 0; e < kOct; ++e) {
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_quantise_kernel(Channelw
         if (is_nonfinite(x)) x = 0.0f;  // counts as zero
         code[e] = code_bits<Q>(x, iv[e]);
       }
-      const size_t e0 = (size_t)base + in_tile;
+      const size_t e0 = s.first + (size_t)(r + i) * c.hidden;
       if constexpr (BITS == 8) {
         uint2 o;
         o.x = pack_bytes4(code[0], code[1], code[2], code[3]);
@@ -173,46 +181,36 @@ __global__ __launch_bounds__(kThreads) void channelwise_quantise_kernel(Channelw
 // ---- decompression: X^ = code * S_h
 template <int BITS, bool F32>
 __global__ __launch_bounds__(kThreads) void channelwise_dequantise_kernel(ChannelwiseDesc c) {
-  constexpr int E = 4;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const uint32_t lane_off = (uint32_t)lane_id() * kOct;
-  const uint32_t n_tiles = (uint32_t)((c.numel + (E * kRow - 1)) / (E * kRow));
-  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < n_tiles; t += gridDim.x * kWavesPerWg) {
-    const uint32_t base = t * (uint32_t)(E * kRow);
-    const uint32_t left = (uint32_t)(c.numel - base);
-    const uint32_t rem = left < (uint32_t)(E * kRow) ? left : (uint32_t)(E * kRow);
-    const uint32_t col0 = base % c.hidden;
-    uint32_t cw[E][2];
-    float4 sc[E][2];
+  const Strip s = strip_of(c);
+  if (!s.live) return;
+  const float4 s0 = *reinterpret_cast<const float4*>(c.scales + s.col);
+  const float4 s1 = *reinterpret_cast<const float4*>(c.scales + s.col + 4);
+  const float sc[kOct] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+  for (uint32_t r = 0; r < s.rows; r += 4u) {
+    uint32_t cw[4][2];
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-      const uint32_t off = in_tile < rem ? in_tile : 0u;
-      const size_t e0 = (size_t)base + off;
+    for (uint32_t i = 0; i < 4u; ++i) {
+      const uint32_t row = r + i < s.rows ? r + i : s.rows - 1u;
+      const size_t e0 = s.first + (size_t)row * c.hidden;
       if constexpr (BITS == 8) {
         const uint2 w = *reinterpret_cast<const uint2*>(c.codes + e0);
-        cw[j][0] = w.x; cw[j][1] = w.y;
+        cw[i][0] = w.x; cw[i][1] = w.y;
       } else {
-        cw[j][0] = *reinterpret_cast<const uint32_t*>(c.codes + (e0 >> 1));
-        cw[j][1] = 0u;
+        cw[i][0] = *reinterpret_cast<const uint32_t*>(c.codes + (e0 >> 1));
+        cw[i][1] = 0u;
       }
-      const uint32_t col = column_of(col0 + off, c.hidden, c.inv_hidden);
-      sc[j][0] = *reinterpret_cast<const float4*>(c.scales + col);
-      sc[j][1] = *reinterpret_cast<const float4*>(c.scales + col + 4);
     }
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-      if (in_tile >= rem) continue;
-      const size_t e0 = (size_t)base + in_tile;
-      const float s[kOct] = {sc[j][0].x, sc[j][0].y, sc[j][0].z, sc[j][0].w, sc[j][1].x, sc[j][1].y, sc[j][1].z, sc[j][1].w};
+    for (uint32_t i = 0; i < 4u; ++i) {
+      if (r + i >= s.rows) break;
+      const size_t e0 = s.first + (size_t)(r + i) * c.hidden;
       float v[kOct];
 #pragma unroll
       for (int e = 0; e < kOct; ++e) {
         int code;
-        if constexpr (BITS == 8) code = (int)(int8_t)((cw[j][e >> 2] >> (8 * (e & 3))) & 0xFFu);
-        else code = ((int)(cw[j][0] << (28 - 4 * e))) >> 28;
-        v[e] = (float)code * s[e];
+        if constexpr (BITS == 8) code = (int)(int8_t)((cw[i][e >> 2] >> (8 * (e & 3))) & 0xFFu);
+        else code = ((int)(cw[i][0] << (28 - 4 * e))) >> 28;
+        v[e] = (float)code * sc[e];
       }
       if constexpr (F32) {
         float* p = reinterpret_cast<float*>(c.dst) + e0;
@@ -230,7 +228,10 @@ __global__ __launch_bounds__(kThreads) void channelwise_dequantise_kernel(Channe
   }
 }
 
-ChannelwiseItemsFn channelwise_partial_fn() { return channelwise_partial_kernel; }
+uint32_t channelwise_strip_rows() { return kStripRows; }
+ChannelwiseItemsFn channelwise_partial_fn(bool stream) {
+  return stream ? channelwise_partial_kernel<true> : channelwise_partial_kernel<false>;
+}
 ChannelwiseFn channelwise_fold_fn() { return channelwise_fold_kernel; }
 uint32_t channelwise_fold_octets() { return (uint32_t)kFoldOcts; }
 ChannelwiseFn channelwise_quantise_fn(uint32_t bits) {

@@ -88,7 +88,7 @@ class SavedActivationCompression(torch.autograd.graph.saved_tensors_hooks):
         self.records = []
         self.retained = []   # (shape, reason) of tensors offered to the policy and saved as they are
         self._status = _StatusPool()
-        self._ws = None      # scan workspace, grown on demand, reused by every tensor (one stream)
+        self._ws = None      # workspace of compression with outliers, grown on demand, reused by every tensor (one stream)
         self._cws = None     # workspace of the channel statistics
         super().__init__(self._pack, self._unpack)
 

@@ -50,7 +50,7 @@ def compare_blob_with_oracle(blob, L, m, numel, oc, check_stream=True):
     if m.asym:
         assert np.array_equal(sec["zp"].view(np.uint32), oc.zp.view(np.uint32)), "offsets differ"
     st = sec["status"].view(np.uint32)
-    assert st[2] == 0, "kernel reported an aborted scan"
+    assert st[2] == 0, "status word 2 is not zero"
     if m.outlier_mode != adacc.OUTLIER_NONE:
         assert int(st[0]) == oc.n_out, f"outlier count {int(st[0])} != {oc.n_out}"
         assert int(st[1]) == (1 if oc.n_out > m.max_outliers else 0)
