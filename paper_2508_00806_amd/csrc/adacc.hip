@@ -442,6 +442,12 @@ static void group_launches(const std::vector<uint32_t>& units, const std::vector
   }
 }
 
+// one wavefront per strip of 512 channels and `rows` tokens, four wavefronts per workgroup
+static uint32_t strip_grid(uint64_t tokens, uint32_t hidden, uint32_t rows) {
+  const uint64_t units = ((tokens + rows - 1) / rows) * ((hidden + 511u) / 512u);
+  return (uint32_t)((units + kWavesPerWg - 1) / kWavesPerWg);  // tokens * hidden < 2^32: far below 2^31
+}
+
 // ---- outlier channels (Section 3.2, Eq. 1)
 struct ChannelPlan {
   adacc_method quant;  // the quantisation of the rest: the same method without outliers
@@ -954,11 +960,8 @@ int adacc_channel_decompress(const adacc_channel_method* method, const void* blo
   ChannelDesc c;
   fill_channel_desc(method, tokens, hidden, L, const_cast<void*>(blob), &c);
   ChannelFn fn = ADACC_PICK(cp.plan.half, channel_decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
-  uint32_t grid = 0;
-  rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid, 1);
-  if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), channel_mask_lds(hidden), static_cast<hipStream_t>(hip_stream), d,
-                     c);
+  const uint32_t grid = strip_grid(tokens, hidden, ADACC_PICK(cp.plan.half, channel_strip_rows()));
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), d, c);
   return launch_check("channel_decompress_kernel");
 }
 
@@ -1003,12 +1006,6 @@ uint64_t adacc_channelwise_workspace_bytes(uint64_t tokens, uint32_t hidden) {
   return channelwise_partial_bytes(tokens, hidden) + align256(4ull * hidden);
 }
 
-// one wavefront per strip of 512 channels and `rows` tokens, four wavefronts per workgroup
-static uint32_t channelwise_strip_grid(uint64_t tokens, uint32_t hidden, uint32_t rows) {
-  const uint64_t units = ((tokens + rows - 1) / rows) * ((hidden + 511u) / 512u);
-  return (uint32_t)((units + kWavesPerWg - 1) / kWavesPerWg);  // tokens * hidden < 2^32: far below 2^31
-}
-
 static void channelwise_desc(uint32_t bits, uint32_t scale_rule, uint64_t tokens, uint32_t hidden,
                              const adacc_channelwise_layout& L, void* blob, ChannelwiseDesc* c) {
   std::memset(c, 0, sizeof *c);
@@ -1042,7 +1039,7 @@ int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, uint32_t dtyp
   c.partial = static_cast<uint16_t*>(workspace);
   c.inv = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + channelwise_partial_bytes(tokens, hidden));
   ChannelwiseFn quant = ADACC_PICK(half, channelwise_quantise_fn(bits));
-  const uint32_t grid = channelwise_strip_grid(tokens, hidden, ADACC_PICK(half, channelwise_strip_rows()));
+  const uint32_t grid = strip_grid(tokens, hidden, ADACC_PICK(half, channelwise_strip_rows()));
   int rc = ADACC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint32_t n_items = c.n_chunks * (hidden / 8);
@@ -1072,7 +1069,7 @@ int adacc_channelwise_decompress(uint32_t bits, uint32_t dtype, const void* blob
   channelwise_desc(bits, 0, tokens, hidden, L, const_cast<void*>(blob), &c);
   c.dst = dst;
   ChannelwiseFn fn = ADACC_PICK(dtype == ADACC_DTYPE_F16, channelwise_dequantise_fn(bits, dst_dtype == ADACC_DST_F32));
-  const uint32_t grid = channelwise_strip_grid(tokens, hidden, ADACC_PICK(dtype == ADACC_DTYPE_F16, channelwise_strip_rows()));
+  const uint32_t grid = strip_grid(tokens, hidden, ADACC_PICK(dtype == ADACC_DTYPE_F16, channelwise_strip_rows()));
   hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), c);
   return launch_check("channelwise_dequantise_kernel");
 }

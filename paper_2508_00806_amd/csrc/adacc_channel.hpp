@@ -330,119 +330,13 @@ __global__ __launch_bounds__(kThreads) void channel_compress_kernel(TensorDesc d
   }
 }
 
-// ---- decompression: dequantise a piece of 2048 elements, put the outlier channels back, store.
-// Every load of the piece is issued before its first store: codes, scales, and for every octet
-// with an outlier channel the value of its first one (a second outlier channel in the same octet
-// is rare and fetched when it is needed).
-template <int BITS, bool ASYM, bool F32>
-__device__ __forceinline__ void channel_decompress_tile(const TensorDesc& d, const ChannelDesc& c, uint32_t n_ch,
-                                                        const ChannelLds& lds, uint32_t tile) {
-  constexpr int E = 4;
-  const uint32_t lane_off = (uint32_t)lane_id() * kOct;
-  const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
-  const ChannelGeo cg = channel_geo(tile, c.hidden);
-  const uint64_t left = d.numel - tile_base;  // > 0, a multiple of 8
-  const uint32_t rem = left < (uint64_t)(E * kRow) ? (uint32_t)left : (uint32_t)(E * kRow);
-
-  uint32_t cw[E][2];
-  float sc[E], zp[E];
-  uint32_t m[E], first[E], pre[E];
-  const uint16_t* src[E];
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-    const bool live = in_tile < rem;
-    const uint64_t e0 = tile_base + (live ? in_tile : 0u);  // octets past the end re-read the first one
-    if constexpr (BITS == 8) {
-      const uint2 w = *reinterpret_cast<const uint2*>(d.codes + e0);
-      cw[j][0] = w.x; cw[j][1] = w.y;
-    } else {
-      cw[j][0] = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
-      cw[j][1] = 0u;
-    }
-    const uint64_t grp = e0 >> d.lgq;
-    sc[j] = d.scales[grp];
-    zp[j] = 0.0f;
-    if constexpr (ASYM) zp[j] = d.zp[grp];
-    m[j] = 0u; first[j] = 0u; pre[j] = 0u; src[j] = c.ch_val;
-    if (n_ch != 0u && live) {
-      uint32_t q, col;
-      split_offset(cg.col0 + in_tile, c.hidden, c.inv_hidden, q, col);
-      m[j] = lds.mask[col >> 3];
-      if (m[j] != 0u) {
-        first[j] = lds.base[col >> 3];
-        if (first[j] >= n_ch) m[j] = 0u;  // a damaged blob must not be read past its end
-        else {
-          src[j] = c.ch_val + (size_t)(cg.row0 + q) * n_ch + first[j];
-          pre[j] = src[j][0];
-        }
-      }
-    }
-  }
-
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const uint32_t in_tile = lane_off + (uint32_t)(j * kRow);
-    if (in_tile >= rem) continue;
-    const uint64_t e0 = tile_base + in_tile;
-    int code[kOct];
-    if constexpr (BITS == 8) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        code[e] = (int)(int8_t)((cw[j][0] >> (8 * e)) & 0xFFu);
-        code[4 + e] = (int)(int8_t)((cw[j][1] >> (8 * e)) & 0xFFu);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) code[e] = ((int)(cw[j][0] << (28 - 4 * e))) >> 28;
-    }
-    float v[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)code[e], sc[j], zp[j]) : (float)code[e] * sc[j];
-
-    // the kept channels of this octet, as their stored 16-bit patterns (hold[e] valid where keep has bit e)
-    uint32_t keep = 0u, hold[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) hold[e] = 0u;
-    if (m[j] != 0u) {
-      const uint32_t lowest = m[j] & (0u - m[j]);
-      keep = lowest;
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) hold[e] = lowest == (1u << e) ? pre[j] : 0u;
-      const uint32_t rest = m[j] ^ lowest;
-      if (rest != 0u) {
-#pragma unroll
-        for (int e = 1; e < kOct; ++e)
-          if (rest & (1u << e)) {
-            const uint32_t r = (uint32_t)__popc(m[j] & ((1u << e) - 1u));
-            if (r < n_ch - first[j]) { hold[e] = src[j][r]; keep |= 1u << e; }
-          }
-      }
-    }
-
-    if constexpr (F32) {
-      if (keep != 0u) {
-#pragma unroll
-        for (int e = 0; e < kOct; ++e) v[e] = (keep & (1u << e)) ? widen_lo(hold[e]) : v[e];
-      }
-      float* p = reinterpret_cast<float*>(d.dst) + e0;
-      ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
-      ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
-    } else {
-      uint32_t w[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) w[k] = narrow_pair(v[2 * k], v[2 * k + 1]);
-      if (keep != 0u) {  // the kept values go in as they were stored, bit for bit (no conversion touches a NaN)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if (keep & (1u << (2 * k))) w[k] = (w[k] & 0xFFFF0000u) | hold[2 * k];
-          if (keep & (2u << (2 * k))) w[k] = (w[k] & 0x0000FFFFu) | (hold[2 * k + 1] << 16);
-        }
-      }
-      ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, make_uint4(w[0], w[1], w[2], w[3]));
-    }
-  }
-}
+// ---- decompression: dequantise, put the outlier channels back, store.
+// A wavefront takes a strip of 512 adjacent channels (8 per lane) over kChannelStripRows consecutive tokens:
+// which of a lane's 8 channels are outlier channels, and where their values start in a token's record, is
+// the same for every token, so it is looked up once (no table in LDS, no division per octet).  The loads of
+// four tokens (codes, scale, offset, the first kept value of the octet) are issued before their first store;
+// a second outlier channel in the same octet is rare and fetched when it is needed.
+constexpr uint32_t kChannelStripRows = 8;
 
 template <int BITS, bool ASYM, bool F32>
 __global__ __launch_bounds__(kThreads) void channel_decompress_kernel(TensorDesc d, ChannelDesc c) {
@@ -450,11 +344,102 @@ __global__ __launch_bounds__(kThreads) void channel_decompress_kernel(TensorDesc
   if (c.status[1] != 0u) return;  // not a usable blob
   uint32_t n_ch = __builtin_amdgcn_readfirstlane(c.status[0]);
   if (n_ch > c.max_channels) n_ch = c.max_channels;  // a damaged blob must not make the reads leave it
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes[];
-  ChannelLds lds{nullptr, nullptr};
-  if (n_ch != 0u) lds = stage_channels(c, lds_bytes);
-  for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-    channel_decompress_tile<BITS, ASYM, F32>(d, c, n_ch, lds, t);
+  const uint32_t strips = (c.hidden + (uint32_t)kRow - 1u) / (uint32_t)kRow;
+  const uint32_t unit = blockIdx.x * kWavesPerWg + wave;
+  const uint32_t block = unit / strips;
+  const uint32_t row0 = block * kChannelStripRows;
+  const uint32_t col = (unit - block * strips) * (uint32_t)kRow + (uint32_t)lane_id() * kOct;
+  if (row0 >= c.tokens || col >= c.hidden) return;
+  const uint32_t rows = c.tokens - row0 < kChannelStripRows ? c.tokens - row0 : kChannelStripRows;
+
+  // the lane's 8 channels: which are outlier channels, and the rank of the first of them
+  uint32_t m = 0u, first = 0u;
+  if (n_ch != 0u) {
+    m = c.mask[col >> 3];
+    first = c.base[col >> 3];
+    if (first >= n_ch) m = 0u;  // a damaged blob must not be read past its end
+  }
+  const uint32_t lowest = m & (0u - m);
+  const uint32_t rest = m ^ lowest;
+
+  for (uint32_t r = 0; r < rows; r += 4u) {
+    uint32_t cw[4][2];
+    float sc[4], zp[4];
+    uint32_t pre[4];
+    const uint16_t* src[4];
+#pragma unroll
+    for (uint32_t i = 0; i < 4u; ++i) {  // rows past the end re-read the last one
+      const uint32_t row = row0 + (r + i < rows ? r + i : rows - 1u);
+      const uint64_t e0 = (uint64_t)row * c.hidden + col;
+      if constexpr (BITS == 8) {
+        const uint2 w = *reinterpret_cast<const uint2*>(d.codes + e0);
+        cw[i][0] = w.x; cw[i][1] = w.y;
+      } else {
+        cw[i][0] = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
+        cw[i][1] = 0u;
+      }
+      const uint64_t grp = e0 >> d.lgq;
+      sc[i] = d.scales[grp];
+      zp[i] = 0.0f;
+      if constexpr (ASYM) zp[i] = d.zp[grp];
+      src[i] = c.ch_val + (size_t)row * n_ch + first;
+      pre[i] = m != 0u ? (uint32_t)src[i][0] : 0u;
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < 4u; ++i) {
+      if (r + i >= rows) break;
+      const uint64_t e0 = (uint64_t)(row0 + r + i) * c.hidden + col;
+      int code[kOct];
+      if constexpr (BITS == 8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          code[e] = (int)(int8_t)((cw[i][0] >> (8 * e)) & 0xFFu);
+          code[4 + e] = (int)(int8_t)((cw[i][1] >> (8 * e)) & 0xFFu);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) code[e] = ((int)(cw[i][0] << (28 - 4 * e))) >> 28;
+      }
+      float v[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) v[e] = ASYM ? __fmaf_rn((float)code[e], sc[i], zp[i]) : (float)code[e] * sc[i];
+
+      // the kept channels of this octet, as their stored 16-bit patterns (hold[e] valid where keep has bit e)
+      uint32_t keep = lowest, hold[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) hold[e] = lowest == (1u << e) ? pre[i] : 0u;
+      if (rest != 0u) {
+#pragma unroll
+        for (int e = 1; e < kOct; ++e)
+          if (rest & (1u << e)) {
+            const uint32_t rank = (uint32_t)__popc(m & ((1u << e) - 1u));
+            if (rank < n_ch - first) { hold[e] = src[i][rank]; keep |= 1u << e; }
+          }
+      }
+
+      if constexpr (F32) {
+        if (keep != 0u) {
+#pragma unroll
+          for (int e = 0; e < kOct; ++e) v[e] = (keep & (1u << e)) ? widen_lo(hold[e]) : v[e];
+        }
+        float* p = reinterpret_cast<float*>(d.dst) + e0;
+        ADACC_STORE16(p, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+        ADACC_STORE16(p + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
+      } else {
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[k] = narrow_pair(v[2 * k], v[2 * k + 1]);
+        if (keep != 0u) {  // the kept values go in as they were stored, bit for bit (no conversion touches a NaN)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (keep & (1u << (2 * k))) w[k] = (w[k] & 0xFFFF0000u) | hold[2 * k];
+            if (keep & (2u << (2 * k))) w[k] = (w[k] & 0x0000FFFFu) | (hold[2 * k + 1] << 16);
+          }
+        }
+        ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, make_uint4(w[0], w[1], w[2], w[3]));
+      }
+    }
+  }
 }
 
 }  // namespace ADACC_DT_NS

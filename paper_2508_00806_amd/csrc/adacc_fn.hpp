@@ -32,7 +32,7 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
 //   stream: the statistics pass reads with the streaming hint (tensors beyond kStatsKeepBytes)
 //   channel_score_channels: channels per workgroup of the score kernel
 //   channelwise_fold_octets: octets of channels per workgroup of the fold kernel
-//   channelwise_strip_rows: tokens a wavefront of the (de)quantisation kernels takes
+//   channelwise_strip_rows, channel_strip_rows: tokens a wavefront of the strip kernels takes
 #define ADACC_DTYPE_GETTERS                                                            \
   CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);    \
   CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
@@ -54,6 +54,7 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   ChannelScoreFn channel_score_fn();                                                   \
   ChannelSelectFn channel_select_fn();                                                 \
   uint32_t channel_score_channels();                                                   \
+  uint32_t channel_strip_rows();                                                       \
   ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);           \
   ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);             \
   ChannelwiseItemsFn channelwise_partial_fn(bool stream);                              \

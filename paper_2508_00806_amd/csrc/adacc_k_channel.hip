@@ -8,6 +8,7 @@ namespace ADACC_DT_NS {
 ChannelPartialFn channel_partial_fn(bool stream) { return stream ? channel_partial_kernel<true> : channel_partial_kernel<false>; }
 ChannelScoreFn channel_score_fn() { return channel_score_kernel; }
 ChannelSelectFn channel_select_fn() { return channel_select_kernel; }
+uint32_t channel_strip_rows() { return kChannelStripRows; }
 uint32_t channel_score_channels() { return (uint32_t)kScoreChannels; }
 
 template <int BITS, bool ASYM>
