@@ -63,12 +63,14 @@ extern "C" {
 typedef struct adacc_method {
   uint32_t kind;         /* ADACC_KIND_*                                                     */
   uint32_t bits;         /* 4 or 8                                                           */
-  uint32_t quant_group;  /* Gq, elements per scale: a power of two in [8, 4096]; the groups are cut from the
-                            start of the flat tensor, the last one may be short                */
+  uint32_t quant_group;  /* Gq, elements per scale: a multiple of 8 in [8, 16384]; the groups are cut from the
+                            start of the flat tensor, the last one may be short.  Powers of two up to 4096
+                            (with a stat_group of that kind) run in the fast kernels, everything else in
+                            fallback kernels that are 5 to 60 times slower                      */
   uint32_t asym;         /* 0: symmetric (Eq. 2), 1: asymmetric (Eq. 3, adds one offset per group) */
   uint32_t scale_rule;   /* ADACC_SCALE_*                                                    */
   uint32_t outlier_mode; /* ADACC_OUTLIER_*                                                  */
-  uint32_t stat_group;   /* Gs, STD/TOPK only: power of two, multiple of Gq, <= 4096; the last group may be
+  uint32_t stat_group;   /* Gs, STD/TOPK only: a multiple of Gq, <= 16384; the last group may be
                             short: mean and variance over its own count, at most as many largest values
                             as it has elements                                                   */
   float thresh;          /* ABS: tau >= 0.  STD: k >= 0 (the library forms k*k in binary32)  */
@@ -98,7 +100,9 @@ typedef struct adacc_method {
 typedef struct adacc_layout {
   uint64_t codes_off, scales_off, zp_off, tile_ptr_off, idx_off, val_off, status_off;
   uint64_t total_bytes; /* size the blob must have                                       */
-  uint32_t tile_elems;  /* elements per tile: max(2048, Gq, Gs)                          */
+  uint32_t tile_elems;  /* elements per tile: 2048, or 4096 when Gq or Gs is 4096; for group sizes that go
+                           through the fallback kernels, the largest multiple of the larger group up to
+                           4096 (the group itself if it is larger)                        */
   uint32_t n_tiles;     /* ceil(numel / tile_elems)                                      */
 } adacc_layout;
 

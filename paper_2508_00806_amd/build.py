@@ -15,6 +15,7 @@ PER_FORMAT = (
     "adacc_k_batch4.hip", "adacc_k_batch8.hip",
     "adacc_k_place.hip",      # placement of the outliers in the stream
     "adacc_k_tail.hip",       # the end of a tensor that the group sizes do not divide
+    "adacc_k_generic.hip",    # fallback for group sizes that are no powers of two or exceed 4096
     "adacc_k_channel.hip",    # outlier channels by Z-score
     "adacc_k_channelwise.hip",  # channel-wise symmetric quantisation (Q / K / V)
 )
@@ -28,7 +29,7 @@ SOURCES = ([(os.path.join(CSRC, f), "", ()) for f in PER_FORMAT] +
            [(os.path.join(CSRC, f), "", ()) for f in ONCE])
 HEADERS = [os.path.join(CSRC, f) for f in ("adacc_common.hpp", "adacc_dtype.hpp", "adacc_compress.hpp",
                                            "adacc_decompress.hpp", "adacc_kernels.hpp", "adacc_fn.hpp",
-                                           "adacc_channel.hpp", "adacc_tail.hpp")]
+                                           "adacc_channel.hpp", "adacc_tail.hpp", "adacc_generic.hpp")]
 HEADERS.append(os.path.join(ROOT, "include", "adacc.h"))
 OBJDIR = os.path.join(HERE, "_build")
 

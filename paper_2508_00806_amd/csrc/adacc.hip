@@ -134,8 +134,11 @@ struct Plan {  // everything derived from (method, numel)
   uint32_t n_tiles_all;  // tiles of the whole tensor (what the layout reports)
   bool rowwise;  // every group lies inside a 512-element row and both kinds of group coincide
   bool half;     // the tensor is binary16 (else bf16)
+  bool generic;  // group sizes the tile kernels do not take: the fallback kernels do the whole tensor
   float param, divisor;
 };
+
+constexpr uint32_t kGenericMaxGroup = 16384;  // the longest segment of the fallback kernels
 
 static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   std::memset(p, 0, sizeof *p);
@@ -145,13 +148,16 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   if (m->asym > 1 || m->scale_rule > 1 || m->outlier_mode > ADACC_OUTLIER_TOPK) return ADACC_EINVAL;
   if (m->dtype > ADACC_DTYPE_F16) return ADACC_EINVAL;
   p->half = m->dtype == ADACC_DTYPE_F16;
-  if (!is_pow2(m->quant_group) || m->quant_group < 8 || m->quant_group > 4096) return ADACC_EINVAL;
+  if (m->quant_group < 8 || m->quant_group % 8 != 0 || m->quant_group > kGenericMaxGroup) return ADACC_EINVAL;
   uint32_t gs = m->quant_group;
   const bool stat = m->outlier_mode == ADACC_OUTLIER_STD || m->outlier_mode == ADACC_OUTLIER_TOPK;
   if (stat) {
-    if (!is_pow2(m->stat_group) || m->stat_group < m->quant_group || m->stat_group > 4096) return ADACC_EINVAL;
+    if (m->stat_group < m->quant_group || m->stat_group % m->quant_group != 0 || m->stat_group > kGenericMaxGroup)
+      return ADACC_EINVAL;
     gs = m->stat_group;
   }
+  // the tile kernels take powers of two up to 4096; everything else goes through the fallback kernels
+  p->generic = !is_pow2(m->quant_group) || !is_pow2(gs) || gs > 4096;
   if (m->outlier_mode == ADACC_OUTLIER_TOPK && (m->topk < 1 || m->topk > 32 || m->topk > gs)) return ADACC_EINVAL;
   if (m->outlier_mode == ADACC_OUTLIER_ABS || m->outlier_mode == ADACC_OUTLIER_STD) {
     if (!(m->thresh >= 0.0f) || std::isinf(m->thresh)) return ADACC_EINVAL;
@@ -159,15 +165,26 @@ static int make_plan(const adacc_method* m, uint64_t numel, Plan* p) {
   p->outliers = m->outlier_mode != ADACC_OUTLIER_NONE;
   if (p->outliers && numel >= (1ull << 31)) return ADACC_EINVAL;  // 32-bit signed flat indices
   if (numel >= (1ull << 42)) return ADACC_EINVAL;
-  p->tile_elems = gs > 2048 ? 4096u : 2048u;
-  p->numel_main = numel - numel % gs;
-  p->tail = (uint32_t)(numel % gs);
-  p->n_tiles = (uint32_t)((p->numel_main + p->tile_elems - 1) / p->tile_elems);
-  p->n_tiles_all = (uint32_t)((numel + p->tile_elems - 1) / p->tile_elems);
-  p->lgq = ilog2(m->quant_group);
-  p->lgs = ilog2(gs);
+  if (p->generic) {
+    // a segment: as many whole groups of the larger kind as fit 4096 elements (one, if it is larger);
+    // the last segment and its last groups may be short, so there is no tail
+    p->tile_elems = gs >= 4096 ? gs : gs * (4096u / gs);
+    p->numel_main = numel;
+    p->tail = 0;
+    const uint64_t segs = (numel + p->tile_elems - 1) / p->tile_elems;
+    if (segs >= (1ull << 31)) return ADACC_EINVAL;
+    p->n_tiles = p->n_tiles_all = (uint32_t)segs;
+  } else {
+    p->tile_elems = gs > 2048 ? 4096u : 2048u;
+    p->numel_main = numel - numel % gs;
+    p->tail = (uint32_t)(numel % gs);
+    p->n_tiles = (uint32_t)((p->numel_main + p->tile_elems - 1) / p->tile_elems);
+    p->n_tiles_all = (uint32_t)((numel + p->tile_elems - 1) / p->tile_elems);
+    p->lgq = ilog2(m->quant_group);
+    p->lgs = ilog2(gs);
+  }
   p->variant = variant_index(m->outlier_mode, m->bits, m->asym, p->tile_elems == 4096 ? 1u : 0u);
-  p->rowwise = m->outlier_mode != ADACC_OUTLIER_TOPK && m->quant_group <= 512 &&
+  p->rowwise = !p->generic && m->outlier_mode != ADACC_OUTLIER_TOPK && m->quant_group <= 512 &&
                (m->outlier_mode != ADACC_OUTLIER_STD || m->stat_group == m->quant_group);
   const float q = (float)(1u << (m->bits - 1));
   if (m->asym) p->divisor = m->scale_rule == ADACC_SCALE_PAPER ? 2.0f * q : 2.0f * q - 1.0f;
@@ -243,16 +260,16 @@ static WsPlan ws_plan(const adacc_method* m, const Plan& p) {
   uint64_t off = 0;
   w.cnt_off = off;  off = align256(off + 4ull * p.n_tiles);
   w.flag_off = off; off += 256;
-  if (m->outlier_mode != ADACC_OUTLIER_TOPK) {
+  if (m->outlier_mode != ADACC_OUTLIER_TOPK || p.generic) {
     w.block_sum_off = off; off = align256(off + 4ull * place_blocks(p));
-    w.slot_off = off; off = align256(off + 8ull * kSlot * p.n_tiles);
+    if (!p.generic) { w.slot_off = off; off = align256(off + 8ull * kSlot * p.n_tiles); }
   }
   w.bytes = off;
   return w;
 }
 // does the placement of this tensor start from per-block sums (a kernel of its own computes them)?
 static bool needs_block_sums(const adacc_method* m, const Plan& p) {
-  return p.outliers && m->outlier_mode != ADACC_OUTLIER_TOPK && place_blocks(p) > kPlaceDirectBlocks;
+  return p.outliers && (m->outlier_mode != ADACC_OUTLIER_TOPK || p.generic) && place_blocks(p) > kPlaceDirectBlocks;
 }
 
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
@@ -284,9 +301,13 @@ static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, cons
   d->bits = m->bits;
   d->asym = m->asym;
   d->mode = m->outlier_mode;
+  d->gq = m->quant_group;
+  d->gs = (m->outlier_mode == ADACC_OUTLIER_STD || m->outlier_mode == ADACC_OUTLIER_TOPK) ? m->stat_group : m->quant_group;
+  d->tile_elems = p.tile_elems;
+  d->generic = p.generic ? 1u : 0u;
   d->n_blocks = place_blocks(p);
   d->lgt = p.tile_elems == 4096 ? 12u : 11u;
-  if (dst) {  // decompression counts pieces of 2048 elements
+  if (dst && !p.generic) {  // decompression counts pieces of 2048 elements
     d->n_tiles = decompress_pieces(p.numel_main);
     d->ptr_shift = p.tile_elems == 4096 ? 1u : 0u;
   }
@@ -474,7 +495,7 @@ static int make_channel_plan(const adacc_channel_method* m, uint64_t tokens, uin
   cp->numel = tokens * hidden;
   const int rc = make_plan(&cp->quant, cp->numel, &cp->plan);
   if (rc != ADACC_OK) return rc;
-  if (cp->plan.tail != 0) return ADACC_EINVAL;  // here the groups have to divide the tensor
+  if (cp->plan.tail != 0 || cp->plan.generic) return ADACC_EINVAL;  // here: a power of two that divides the tensor
   fill_layout(&cp->quant, cp->numel, cp->plan, &cp->quant_layout);
   cp->n_chunks = (uint32_t)((tokens + kChunkTokens - 1) / kChunkTokens);
   return ADACC_OK;
@@ -566,6 +587,28 @@ int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, 
   return ADACC_OK;
 }
 
+// The fallback kernels for one tensor: count, offsets, then everything (one launch without outliers).
+static int launch_generic_compress(const adacc_method* method, const Plan& p, const TensorDesc& d, uint32_t epoch,
+                                   hipStream_t s) {
+  int rc = ADACC_OK;
+  const uint32_t lds = 4u * kWave + 3u * p.tile_elems;  // lane counts, 16-bit patterns, a byte per element
+  if (p.outliers) {
+    hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(true)), dim3(p.n_tiles), dim3(kWave), lds, s, d);
+    rc = launch_check("compress_generic_kernel (count)");
+    if (rc != ADACC_OK) return rc;
+    if (needs_block_sums(method, p)) {
+      hipLaunchKernelGGL(ADACC_PICK(p.half, place_sum_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
+      rc = launch_check("place_sum_kernel");
+      if (rc != ADACC_OK) return rc;
+    }
+    hipLaunchKernelGGL(ADACC_PICK(p.half, place_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
+    rc = launch_check("place_kernel");
+    if (rc != ADACC_OK) return rc;
+  }
+  hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(false)), dim3(p.n_tiles), dim3(kWave), lds, s, d);
+  return launch_check("compress_generic_kernel");
+}
+
 static int compress_one(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,
                         adacc_workspace* ws, void* hip_stream) {
   if (!method) return ADACC_ENULL;
@@ -586,10 +629,18 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
   int cus = 0;
   rc = device_cus(&cus);  // also: fail here, before any state changes, when there is no device
   if (rc != ADACC_OK) return rc;
-  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise, topk_whole_tile(method, p));
   TensorDesc d;
   fill_desc(method, numel, p, L, src, blob, nullptr, 0, p.outliers ? ws->device_mem : nullptr, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (p.generic) {
+    uint32_t epoch = 0;
+    if (p.outliers) {
+      rc = next_epoch(ws, s, &epoch);
+      if (rc != ADACC_OK) return rc;
+    }
+    return launch_generic_compress(method, p, d, epoch, s);
+  }
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise, topk_whole_tile(method, p));
   const uint32_t grid = (p.n_tiles + kWavesPerWg - 1) / kWavesPerWg;  // one tile per wavefront
   uint32_t epoch = 0;
   if (p.outliers) {
@@ -675,8 +726,12 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   if (misaligned(dst, 16) || misaligned(blob, 256)) return ADACC_EALIGN;
   TensorDesc d;
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, nullptr, &d);
-  DecompressFn fn = ADACC_PICK(p.half, decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (p.generic) {
+    hipLaunchKernelGGL(ADACC_PICK(p.half, decompress_generic_fn()), dim3(p.n_tiles), dim3(kWave), 0, s, d);
+    return launch_check("decompress_generic_kernel");
+  }
+  DecompressFn fn = ADACC_PICK(p.half, decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
   if (d.n_tiles != 0) {
     uint32_t grid = 0;
     rc = grid_for(d.n_tiles, reinterpret_cast<const void*>(fn), &grid);
@@ -774,17 +829,18 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   std::vector<uint32_t> units(nt), members;
   std::vector<int> kind(nt);
   std::vector<GroupLaunch> tiles, sums, places, tails;
+  // (tensors that go through the fallback kernels are launched one by one, after the others)
   for (uint32_t i = 0; i < nt; ++i) {
-    units[i] = descs[i].n_tiles;
+    units[i] = descs[i].generic ? 0u : descs[i].n_tiles;
     kind[i] = batch_kind(&methods[origin[i]], plans[origin[i]]) + (plans[origin[i]].half ? kBatchKinds : 0);
   }
   group_launches(units, kind, &members, &tiles);
   for (uint32_t i = 0; i < nt; ++i) {
-    units[i] = needs_block_sums(&methods[origin[i]], plans[origin[i]]) ? descs[i].n_blocks : 0u;
+    units[i] = (!descs[i].generic && needs_block_sums(&methods[origin[i]], plans[origin[i]])) ? descs[i].n_blocks : 0u;
     kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
   }
   group_launches(units, kind, &members, &sums);
-  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].n_blocks;
+  for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].generic ? 0u : descs[i].n_blocks;
   group_launches(units, kind, &members, &places);
   for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].tail != 0u ? 1u : 0u;
   group_launches(units, kind, &members, &tails);
@@ -814,7 +870,10 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   for (const GroupLaunch& g : tails)  // one workgroup per tensor that has a tail, after the placement
     hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, compress_tail_batch_fn()), dim3(g.n_members), dim3(kWave), 0, s, dt,
                        dm + g.first_member);
-  return launch_check("compress_tail_batch_kernel");
+  rc = launch_check("compress_tail_batch_kernel");
+  for (uint32_t i = 0; i < nt && rc == ADACC_OK; ++i)
+    if (descs[i].generic) rc = launch_generic_compress(&methods[origin[i]], plans[origin[i]], descs[i], epoch, s);
+  return rc;
 }
 
 int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* const* blobs, const uint64_t* blob_bytes,
@@ -846,7 +905,7 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   std::vector<int> kind(nt, 0);
   std::vector<GroupLaunch> launches;
   for (uint32_t i = 0; i < nt; ++i) {
-    units[i] = descs[i].n_tiles;  // pieces of 2048 elements
+    units[i] = descs[i].generic ? 0u : descs[i].n_tiles;  // pieces of 2048 elements
     kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
   }
   group_launches(units, kind, &members, &launches);
@@ -867,6 +926,10 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
   for (const GroupLaunch& g : tails)
     hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, decompress_tail_batch_fn()), dim3(g.n_members), dim3(kWave), 0, s, dt,
                        dm + g.first_member);
+  for (uint32_t i = 0; i < nt; ++i)
+    if (descs[i].generic)
+      hipLaunchKernelGGL(ADACC_PICK(plans[origin[i]].half, decompress_generic_fn()), dim3(descs[i].n_tiles), dim3(kWave), 0,
+                         s, descs[i]);
   return launch_check("decompress_batch_kernel");
 }
 

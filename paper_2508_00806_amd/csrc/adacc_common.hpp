@@ -91,6 +91,9 @@ struct TensorDesc {
   uint32_t n_tiles;         // tiles of the first numel elements (decompress: pieces of 2048 of them)
   uint32_t n_tiles_all;     // tiles of the whole tensor, tail included: tile_ptr has one entry more
   uint32_t bits, asym, mode;  // the method, for kernels that do not get it as template arguments
+  uint32_t gq, gs;          // group sizes as numbers (the fallback kernels take groups that are no powers of two)
+  uint32_t tile_elems;      // elements per tile of the blob
+  uint32_t generic;         // 1: the method goes through the fallback kernels
   uint32_t n_blocks;        // compress: blocks of kPlaceTiles tiles (placement kernels)
   uint32_t lgt;             // log2(elements per tile): 11 or 12
   uint32_t lgq;         // log2(quant group)

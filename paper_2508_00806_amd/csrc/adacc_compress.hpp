@@ -1377,10 +1377,12 @@ __device__ __forceinline__ void reselect_tile(const TensorDesc& d, uint32_t tile
   encode_tile<MODE, 8, false, E, ROWWISE, WHOLE, false>(d, g, raw, tile, StreamSink{d.idx, d.val}, pos, end < d.cap ? end : d.cap);
 }
 
+// The offsets of a block's tiles from the counts: tile_ptr for the block's tiles, and in the block that holds the
+// last tile the total and the overflow flag.  Leaves in sh.excl the offsets relative to the block (and the
+// block's total behind them).  Returns the number of outliers before the block; n_here: tiles of the block.
 // `from_sums`: the counts of the blocks are in d.block_sum (else the counts of the tiles are added up)
-template <int MODE, int E, bool ROWWISE, bool WHOLE>
-__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool from_sums, bool reselect_all,
-                                            PlaceShared& sh) {
+__device__ __forceinline__ uint32_t place_offsets_block(const TensorDesc& d, uint32_t block, bool from_sums, PlaceShared& sh,
+                                                        uint32_t& n_here, uint32_t& total) {
   const uint32_t tid = threadIdx.x;
   const uint32_t first = block * (uint32_t)kPlaceTiles;
   // outliers of all tiles before this block
@@ -1399,7 +1401,8 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
   __syncthreads();
   if (lane_id() == kWave - 1) sh.part[wave] = incl;
   __syncthreads();
-  uint32_t wave_before = 0u, total = 0u;
+  uint32_t wave_before = 0u;
+  total = 0u;
 #pragma unroll
   for (int i = 0; i < kPlaceThreads / kWave; ++i) {
     wave_before += (uint32_t)i < wave ? sh.part[i] : 0u;
@@ -1409,12 +1412,22 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
   sh.excl[tid] = e0;
   if (tid == 0) sh.excl[kPlaceTiles] = total;
   if (t < d.n_tiles) d.tile_ptr[t] = base + e0;
-  const uint32_t n_here = d.n_tiles - first < (uint32_t)kPlaceTiles ? d.n_tiles - first : (uint32_t)kPlaceTiles;
+  n_here = d.n_tiles - first < (uint32_t)kPlaceTiles ? d.n_tiles - first : (uint32_t)kPlaceTiles;
   if (first + n_here == d.n_tiles && tid == 0) {  // the block that holds the last tile also closes the blob
     const uint32_t n_out = base + total;
     d.tile_ptr[d.n_tiles] = n_out;
     d.status[0] = n_out; d.status[1] = n_out > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
   }
+  return base;
+}
+
+template <int MODE, int E, bool ROWWISE, bool WHOLE>
+__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool from_sums, bool reselect_all,
+                                            PlaceShared& sh) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t first = block * (uint32_t)kPlaceTiles;
+  uint32_t n_here, total;
+  const uint32_t base = place_offsets_block(d, block, from_sums, sh, n_here, total);
   __syncthreads();
   // from the slots to the stream: four positions per thread at a time, so that their loads overlap
   if (!reselect_all) {

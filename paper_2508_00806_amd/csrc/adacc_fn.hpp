@@ -50,6 +50,8 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   TailBatchFn compress_tail_batch_fn();                                                \
   TailFn decompress_tail_fn();                                                         \
   TailBatchFn decompress_tail_batch_fn();                                              \
+  TailFn compress_generic_fn(bool count_only);                                         \
+  TailFn decompress_generic_fn();                                                      \
   ChannelPartialFn channel_partial_fn(bool stream);                                    \
   ChannelScoreFn channel_score_fn();                                                   \
   ChannelSelectFn channel_select_fn();                                                 \

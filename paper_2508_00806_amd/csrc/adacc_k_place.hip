@@ -9,6 +9,11 @@ namespace ADACC_DT_NS {
 __device__ __forceinline__ void place_dispatch(const TensorDesc& d, uint32_t block, uint32_t epoch, PlaceShared& sh) {
   const bool e8 = (d.variant & 1u) != 0u;
   const bool from_sums = d.n_blocks > kPlaceDirectBlocks;
+  if (d.generic != 0u) {  // the fallback kernels only ask for the offsets: they write the outliers themselves
+    uint32_t n_here, total;
+    place_offsets_block(d, block, from_sums, sh, n_here, total);
+    return;
+  }
   switch (d.variant >> 3) {
     case kModeAbs:
       if (d.rowwise) place_block<kModeAbs, 4, true, false>(d, block, from_sums, false, sh);

@@ -72,20 +72,40 @@ def test_layout_closed_form(L):
 
 BAD = [
     Method(bits=5, quant_group=64),
-    Method(bits=8, quant_group=48),
+    Method(bits=8, quant_group=44),      # no multiple of 8
     Method(bits=8, quant_group=4),
-    Method(bits=8, quant_group=8192),
+    Method(bits=8, quant_group=16392),   # beyond the longest segment
     Method(bits=8, quant_group=64, asym=2),
     Method(bits=8, quant_group=64, scale_rule=2),
     Method(bits=8, quant_group=64, outlier_mode=4),
     Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=32, thresh=1.0),
-    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=8192, thresh=1.0),
+    Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=16448, thresh=1.0),
+    Method(bits=8, quant_group=48, outlier_mode=adacc.OUTLIER_STD, stat_group=100, thresh=1.0),  # no multiple of the quant group
     Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_STD, stat_group=64, thresh=-1.0),
     Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_ABS, thresh=float("nan")),
     Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_TOPK, stat_group=64, topk=0),
     Method(bits=8, quant_group=64, outlier_mode=adacc.OUTLIER_TOPK, stat_group=64, topk=33),
     Method(kind=7, bits=8, quant_group=64),
 ]
+
+
+def test_group_sizes_of_the_fallback_kernels(L):
+    """Quantisation groups of any multiple of 8 and statistics groups up to 16384: the tile is the largest
+    multiple of the larger group up to 4096 (the group itself beyond that); no slots in the workspace."""
+    a = lambda v: (v + 255) // 256 * 256
+    m = Method(bits=8, quant_group=48)
+    lay = adacc.layout_of(m, 10000)
+    assert lay.tile_elems == 48 * 85 and lay.n_tiles == 3 and lay.scales_off == a(10000)
+    assert lay.zp_off - lay.scales_off == a(4 * 209)  # 208 whole groups and one of 16 elements
+    row = Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=11008, topk=8, max_outliers=800)
+    lay = adacc.layout_of(row, 11008 * 100)
+    assert lay.tile_elems == 11008 and lay.n_tiles == 100
+    assert adacc.workspace_bytes(row, 11008 * 100) == a(4 * 100) + 256 + a(4 * 1)
+    big = Method(bits=8, quant_group=8192, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=10)
+    assert adacc.layout_of(big, 8192 * 5 + 1).tile_elems == 8192 and adacc.layout_of(big, 8192 * 5 + 1).n_tiles == 6
+    cm = adacc.ChannelMethod(bits=4, quant_group=48, max_channels=4)
+    with pytest.raises(adacc.AdaccError):
+        adacc.channel_layout_of(cm, 12, 96)  # the channel scheme keeps to powers of two
 
 
 @pytest.mark.parametrize("m", BAD)

@@ -1,0 +1,120 @@
+"""GPU parity for group sizes outside the fast kernels' shapes (Section 3.2 groups the flat activation;
+nothing makes the groups powers of two): quantisation groups of any multiple of 8, statistics groups of any
+multiple of those up to 16384 - a whole 11008-wide row as one STD / TOPK group.  These run in fallback
+kernels (a wavefront per segment, plain loops over LDS); the bar is the same as everywhere: every section
+of the blob and both reconstructions against the oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_00806_amd as adacc
+import workloads
+from helpers import (adacc_method, assert_bf16_matches, assert_f32_matches, bits_of, compare_blob_with_oracle, from_bits,
+                     oracle_method, run_parity)
+from test_gpu_f16 import random_f16_bits
+from test_gpu_parity import random_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+def tensor(seed, n, fmt):
+    if fmt == 1:
+        return from_bits(random_f16_bits(seed, n), dtype=torch.float16)
+    return from_bits(random_bits(seed, n))
+
+
+# (quantisation group, statistics group, elements)
+SHAPES = [(24, 24, 24 * 700 + 5), (24, 96, 96 * 200), (40, 4000, 4000 * 3 + 17), (1000, 1000, 1000 * 9 + 999),
+          (344, 11008, 11008 * 3), (11008, 11008, 11008 * 2 + 300), (8192, 8192, 8192 * 3), (128, 11008, 11008 * 5 + 64),
+          (4096, 16384, 16384 * 2 + 4097), (48, 48, 40)]
+
+
+@pytest.mark.parametrize("mode", ["none", "abs", "std", "topk"])
+def test_group_sizes_of_every_kind(mode):
+    for gq, gs, n in SHAPES:
+        for bits, asym, rule, fmt in ((4, 0, 0, 0), (8, 1, 1, 0), (4, 1, 0, 1), (8, 0, 0, 1)):
+            md = dict(bits=bits, quant_group=gq, asym=asym, outlier_mode=mode, stat_group=gs,
+                      thresh={"abs": 2.5, "std": 2.5}.get(mode, 0.0), topk=5 if mode == "topk" else 0)
+            log(f"[generic] mode={mode} gq={gq} gs={gs} n={n} bits={bits} asym={asym} rule={rule} fmt={fmt}")
+            run_parity(tensor(n % 1000 + bits + asym, n, fmt), md, rule=rule)
+
+
+def test_whole_rows_of_a_llama_mlp_activation_as_groups():
+    """An [rows, 11008] activation with the row as the statistics group, the shape the configurations'
+    per-row rules ask for on the MLP tensors: STD over the row and TOPK of the row."""
+    x = workloads.c5_tensor("mlp_up", "cpu", rows=48, seed=77)
+    for md in (dict(bits=8, quant_group=11008, asym=0, outlier_mode="std", stat_group=11008, thresh=4.0, topk=0),
+               dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=11008, thresh=0.0, topk=11)):
+        log(f"[generic] mlp_up rows as groups: {md['outlier_mode']}")
+        oc, *_ = run_parity(x, md)
+        if md["outlier_mode"] == "topk":
+            assert oc.n_out == 11 * 48
+
+
+def test_values_that_are_not_finite_and_degenerate_groups():
+    n = 1000 * 6
+    b = random_bits(3, n)
+    b[5], b[1500], b[1501], b[5999] = 0x7F80, 0xFFC1, 0xFF80, 0x7FFF
+    b[2000:3000] = 0x3F80          # a constant group
+    b[3000:4000] = 0               # an all-zero group
+    b[3007] = 0x8000
+    for mode, kw in (("none", {}), ("abs", dict(thresh=3.0)), ("std", dict(thresh=3.0)), ("topk", dict(topk=2))):
+        for asym in (0, 1):
+            md = dict(bits=8, quant_group=200, asym=asym, outlier_mode=mode, stat_group=1000, thresh=0.0, topk=0)
+            md.update(kw)
+            log(f"[generic] not finite / degenerate mode={mode} asym={asym}")
+            run_parity(from_bits(b), md)
+
+
+def test_capacity_and_many_segments():
+    """More segments than one placement block holds (block sums), and a capacity that ends inside a segment."""
+    n = 4080 * 2100 + 77
+    x = tensor(9, n, 0)
+    md = dict(bits=8, quant_group=24, asym=0, outlier_mode="abs", stat_group=0, thresh=2.0, topk=0)
+    log("[generic] many segments")
+    oc, blob, L, m = run_parity(x, md)
+    assert L.n_tiles == 2101 and oc.n_out > 10000
+    oc2, blob, L, m = run_parity(x, md, cap=oc.n_out // 2, decompress=False)
+    assert adacc.read_status(blob, L)[:2] == (oc.n_out, 1)
+
+
+def test_batch_with_both_kinds_of_kernels():
+    table = []
+    for i, (n, md) in enumerate([
+            (11008 * 7, dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=11008, thresh=0.0, topk=4)),
+            (2048 * 5, dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=2048, thresh=0.0, topk=2)),
+            (24 * 333 + 7, dict(bits=8, quant_group=24, asym=1, outlier_mode="std", stat_group=72, thresh=2.0, topk=0)),
+            (64 * 70, dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=2.0, topk=0)),
+            (1000, dict(bits=8, quant_group=40, asym=0, outlier_mode="none", stat_group=0, thresh=0.0, topk=0))]):
+        for fmt in (0, 1):
+            table.append((n, md, tensor(60 + i, n, fmt), fmt))
+    methods, srcs, blobs, layouts, ocs = [], [], [], [], []
+    for n, md, x, fmt in table:
+        oc = oracle.compress(oracle_method(md, fmt=fmt), bits_of(x))
+        oc._full_idx = oc.out_idx.astype(np.int64)
+        m = adacc_method(md, max(oc.n_out, 1), fmt=fmt)
+        blob, L = adacc.alloc_blob(m, n)
+        methods.append(m); srcs.append(x.cuda()); blobs.append(blob); layouts.append(L); ocs.append(oc)
+    ws = adacc.alloc_workspace(adacc.batch_workspace_bytes(methods, [s.numel() for s in srcs]))
+    for rep in range(2):
+        log(f"[generic] batch compress rep={rep}")
+        adacc.compress_batch(methods, srcs, blobs, ws)
+        torch.cuda.synchronize()
+        for (n, md, x, fmt), m, blob, L, oc in zip(table, methods, blobs, layouts, ocs):
+            compare_blob_with_oracle(blob, L, m, n, oc)
+    for kind in ("own", "f32"):
+        dsts = [torch.empty(s.numel(), dtype=s.dtype if kind == "own" else torch.float32, device="cuda") for s in srcs]
+        log(f"[generic] batch decompress {kind}")
+        adacc.decompress_batch(methods, blobs, dsts, ws)
+        torch.cuda.synchronize()
+        for d, oc, m in zip(dsts, ocs, methods):
+            of32, o16 = oracle.decompress(oc)
+            if kind == "f32":
+                assert_f32_matches(d.cpu().numpy(), of32)
+            else:
+                assert_bf16_matches(bits_of(d), o16, m.dtype)
