@@ -517,6 +517,46 @@ def run_mask(steps=30, warmup=3):
     return res
 
 
+def run_fallback(steps=5):
+    """Group sizes outside the fast kernels' shapes (a whole 11008-wide row as one statistics group, groups
+    that are no powers of two) on an [8192, 11008] bf16 tensor: the fallback kernels, for the record."""
+    import torch
+    import workloads
+    import paper_2508_00806_amd as adacc
+    x = workloads.c5_tensor("mlp_up", "cuda", rows=8192, seed=1).view(-1)
+    n = x.numel()
+    out = []
+    for name, md in (
+            ("TOPK-8 of every 11008-row, int4 g128", dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=11008, thresh=0.0, topk=8)),
+            ("STD 4 sigma of every 11008-row, int8 per row", dict(bits=8, quant_group=11008, asym=0, outlier_mode="std", stat_group=11008, thresh=4.0, topk=0)),
+            ("no outliers, int8 g96", dict(bits=8, quant_group=96, asym=0, outlier_mode="none", stat_group=0, thresh=0.0, topk=0))):
+        m = adacc.method_from_dict(md, max(4096, n // 64))
+        blob, L = adacc.alloc_blob(m, n)
+        ws = adacc.alloc_workspace(max(512, adacc.workspace_bytes(m, n)))
+        dst = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        adacc.compress(m, x, blob, ws)
+        adacc.decompress(m, blob, dst)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        for _ in range(steps):
+            adacc.compress(m, x, blob, ws)
+        e[1].record()
+        for _ in range(steps):
+            adacc.decompress(m, blob, dst)
+        e[2].record()
+        torch.cuda.synchronize()
+        c_ms, d_ms = e[0].elapsed_time(e[1]) / steps, e[1].elapsed_time(e[2]) / steps
+        st = adacc.read_status(blob, L)
+        if st[1]:
+            raise RuntimeError(f"fallback workload {name}: overflow {st}")
+        out.append({"workload": name, "compress_ms": c_ms, "decompress_ms": d_ms, "n_outliers": st[0],
+                    "compress_activation_GBps": 2.0 * n / (c_ms * 1e-3) / 1e9,
+                    "decompress_activation_GBps": 2.0 * n / (d_ms * 1e-3) / 1e9})
+    del x
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -544,7 +584,7 @@ def main():
         print(json.dumps({"stream_ceilings": stream_ceilings()}))
         return
     main_res = run_workload(a.workload, a.steps, a.warmup, a.sets)
-    extras, channel, mask, channelwise, ceilings = [], None, None, None, None
+    extras, channel, mask, channelwise, ceilings, fallback = [], None, None, None, None, None
     if not a.no_extras:
         ceilings = stream_ceilings()
         for name in sorted(WORKLOAD_TEXT):
@@ -559,6 +599,7 @@ def main():
         channel = run_channel_mode()
         mask = run_mask()
         channelwise = run_channelwise()
+        fallback = run_fallback()
     cpu = None if a.no_cpu else cpu_baseline(a.workload, a.cpu_seconds)
 
     roof = dict(main_res["roofline"])
@@ -588,6 +629,7 @@ def main():
         "channel_zscore": channel,
         "dropout_mask": mask,
         "channelwise_qkv": channelwise,
+        "fallback_group_sizes": fallback,
     }
     print(json.dumps(out))
 
