@@ -479,3 +479,75 @@ def test_full_size_c5_one_layer_batch_sampled():
 def test_full_size_c5_all_layers_batch_sampled():
     """The whole C5 layer set (32 layers, 160 tensors, 20 GiB of bf16) exactly as the bench launches it."""
     run_c5_batch(workloads.C5_LAYERS, 4)
+
+
+# ------------------------------------------------------------------ the largest sizes the library takes
+def check_sampled(name, xf, md, m, blob, L, dst, n_samples, seed):
+    tiles = sampled_tiles(np.random.default_rng(seed), L.n_tiles, n_samples)
+    st = check_compressed_tiles(name, xf, md, m, blob, L, tiles[:-1])  # the last tile may be short: checked by its own slice
+    check_restored_tiles(name, xf, md, m, blob, L, dst, tiles[:-1])
+    return st
+
+
+def test_offsets_beyond_32_bits():
+    """Without outliers a tensor may have more than 2^32 elements (element offsets, code offsets and
+    group numbers are 64-bit): 2^32 + 6152 bf16 values, int4 in groups of 128 - the length is no multiple of
+    the group, so the last 8 elements are a short group.  Oracle on tiles sampled over the whole range and
+    on the end of the tensor."""
+    n = (1 << 32) + 3 * 2048 + 8
+    log(f"[parity] {n} elements without outliers")
+    x = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(4242)
+    step = 1 << 28
+    for i0 in range(0, n, step):
+        x[i0:i0 + step].normal_(0.0, 1.5, generator=g)
+    md = dict(bits=4, quant_group=128, asym=0, outlier_mode="none", stat_group=0, thresh=0.0, topk=0)
+    m = adacc_method(md, 0)
+    blob, L = adacc.alloc_blob(m, n)
+    adacc.compress(m, x, blob, None)
+    dst = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    adacc.decompress(m, blob, dst)
+    torch.cuda.synchronize()
+    assert L.n_tiles == (n + 2047) // 2048
+    check_sampled("beyond 2^32", x, md, m, blob, L, dst, 24, 11)
+    # the end: the last whole tiles and the short group, against the oracle on that slice
+    lo = n - (2048 + 8)
+    oc = oracle.compress(oracle_method(md), bits_of(x[lo:]))
+    sec = adacc.blob_sections(blob, L, m, n)
+    assert np.array_equal(sec["codes"][lo // 2:].cpu().numpy(), oc.packed)
+    assert np.array_equal(sec["scales"][lo // 128:].cpu().numpy().view(np.uint32), oc.scale.view(np.uint32))
+    assert np.array_equal(bits_of(dst[lo:]), oracle.decompress(oc)[1])
+    del x, dst, blob
+    torch.cuda.empty_cache()
+
+
+def test_the_longest_tensor_that_keeps_outliers():
+    """Outlier indices are 32-bit signed: 2^31 - 2048 elements is the longest tensor in a mode that keeps
+    outliers.  STD in groups of 64 (row encoder, slots, block sums over 4096 blocks) and TOPK over 4096."""
+    n = (1 << 31) - 2048
+    x = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(777)
+    step = 1 << 28
+    for i0 in range(0, n, step):
+        x[i0:i0 + step].normal_(0.0, 1.0, generator=g)
+    x[n - 5] = 1000.0   # an outlier at the very end: its index is close to 2^31
+    dst = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    for md, cap in ((dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=3.5, topk=0), n // 256),
+                    (dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=4096, thresh=0.0, topk=2), n // 2048 + 8)):
+        log(f"[parity] {n} elements, {md['outlier_mode']}")
+        m = adacc_method(md, cap)
+        blob, L = adacc.alloc_blob(m, n)
+        ws = adacc.alloc_workspace(adacc.workspace_bytes(m, n))
+        adacc.compress(m, x, blob, ws)
+        adacc.decompress(m, blob, dst)
+        torch.cuda.synchronize()
+        st = check_sampled("longest with outliers", x, md, m, blob, L, dst, 24, 5)
+        sec = adacc.blob_sections(blob, L, m, n)
+        assert st[1] == 0 and (n - 5) in sec["idx"][st[0] - 2:st[0]].cpu().tolist()
+        assert int(bits_of(dst[n - 5:n - 4])[0]) == int(bits_of(x[n - 5:n - 4])[0])
+        if md["outlier_mode"] == "topk":
+            assert st[0] == 2 * (n // 4096) + 2  # the last tile is half a group short: a tail of 2048 elements
+        del blob, ws
+        torch.cuda.empty_cache()
+    del x, dst
+    torch.cuda.empty_cache()
