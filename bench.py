@@ -50,8 +50,8 @@ SECOND_READINGS = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough to exceed 1 GiB)")
     ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads and schemes")
@@ -105,8 +105,8 @@ class Workload:
         self.layouts = [adacc.layout_of(m, n) for m, n in zip(self.methods, self.numels)]
         self.batched = len(specs) > 1
         in_bytes = sum(2 * n for n, md in zip(self.numels, self.mds) if md is not None)
-        if sets <= 0:
-            sets = max(2, min(8, -(-(1 << 30) // max(in_bytes, 1))))
+        if sets <= 0:  # at least 1 GiB of inputs in rotation (the Infinity Cache holds 256 MB), at most 64 sets
+            sets = max(2, min(64, -(-(1 << 30) // max(in_bytes, 1))))
             sets += sets % 2
         if name == "c5":
             sets = 2  # 20 GiB per set: far beyond any cache already
@@ -187,9 +187,11 @@ def time_steps(w, steps, warmup):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     total_ms = ev[0][0].elapsed_time(ev[-1][2])
-    c_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
-    d_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
-    return total_ms / steps, c_ms, d_ms, wall_ms / steps
+    c_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    d_all = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    spread = {"compress": {"ms_median": c_all[len(c_all) // 2], "ms_min": c_all[0]},
+              "decompress": {"ms_median": d_all[len(d_all) // 2], "ms_min": d_all[0]}}
+    return total_ms / steps, sum(c_all) / steps, sum(d_all) / steps, wall_ms / steps, spread
 
 
 def direction_block(alg, ms, act_bytes, traffic):
@@ -212,7 +214,7 @@ def run_workload(name, steps, warmup, sets, cold=True):
     w = Workload(name, sets if cold else 1)
     if not cold:
         w.sets = 1
-    ms, c_ms, d_ms, wall_ms = time_steps(w, steps, warmup)
+    ms, c_ms, d_ms, wall_ms, spread = time_steps(w, steps, warmup)
     w.check_status()
     alg = w.algorithmic_bytes()
     traffic = measured_traffic()
@@ -231,6 +233,8 @@ def run_workload(name, steps, warmup, sets, cold=True):
         "buffer_sets": w.sets,
         "cache_state": "cold: rotating buffer sets, inputs come from HBM" if cold else "warm: one buffer set, 8 MB stays in the caches",
     }
+    res["compress"].update(spread["compress"])
+    res["decompress"].update(spread["decompress"])
     res["roofline"] = roofline_block(res)
     del w
     torch.cuda.empty_cache()
@@ -601,6 +605,10 @@ def main():
         channelwise = run_channelwise()
         fallback = run_fallback()
     cpu = None if a.no_cpu else cpu_baseline(a.workload, a.cpu_seconds)
+    if cpu:  # the same metric on both sides: bytes compressed plus bytes restored per second
+        cpu["gpu_over_cpu"] = {"all_cores": main_res["activation_GBps"] / cpu["value"],
+                               "single_thread": main_res["activation_GBps"] / cpu["single_thread"]["value"]}
+    props = torch.cuda.get_device_properties(0)
 
     roof = dict(main_res["roofline"])
     roof["stream_ceilings"] = ceilings
@@ -617,7 +625,9 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[a.workload], "buffer_sets": main_res["buffer_sets"],
+        "config": {"workload": WORKLOAD_TEXT[a.workload], "device": f"{props.name} ({getattr(props, 'gcnArchName', '?')}, "
+                                                                      f"{props.multi_processor_count} CUs, {props.total_memory >> 30} GiB)",
+                   "buffer_sets": main_res["buffer_sets"],
                    "tensors": main_res["tensors"], "n_outliers": main_res["n_outliers"],
                    "storage": "bf16 in and out; int8 / int4 codes, binary32 scales, (int32, bf16) outliers in between"},
         "hbm_frac_of_peak_roundtrip": main_res["roundtrip_hbm_frac_of_peak"],
