@@ -209,3 +209,23 @@ def test_rounding_helpers_of_the_brute_force_for_binary16_against_numpy():
         want = x.astype(np.float16).view(np.uint16)
     for v, w in zip(x, want):
         assert bf.f16_bits_of(Fraction(float(v))) == int(w), float(v)
+
+
+# ------------------------------------------------------------------ one element through every kind of bit pattern
+@pytest.mark.parametrize("fmt", [bf.BF16, bf.F16])
+def test_one_element_swept_over_the_16_bit_patterns(fmt):
+    """One group of eight; seven elements fixed, the eighth takes every 13th of the 65 536 bit patterns
+    (13 is odd, so both signs, every exponent, subnormals, zeros, infinities and NaNs are visited) under
+    ABS outliers with symmetric int8 and asymmetric int4 codes.  Whatever the pattern, the oracle and
+    the exact-arithmetic brute force agree field by field."""
+    base = to_bf16_bits([0.5, -0.75, 0.0, 1.25, -0.125, 0.3125, 1.0, 0.0]) if fmt == bf.BF16 else \
+        to_f16_bits([0.5, -0.75, 0.0, 1.25, -0.125, 0.3125, 1.0, 0.0])
+    kept = 0
+    for pattern in range(0, 0x10000, 13):
+        bits = base.copy()
+        bits[7] = pattern
+        oc = check(bits, 8, 8, 0, bf.FULLRANGE, "abs", thresh=3.0, fmt=fmt)
+        kept += oc.n_out
+        if pattern % 3 == 0:
+            check(bits, 4, 8, 1, bf.PAPER, "abs", thresh=3.0, fmt=fmt)
+    assert 0 < kept < 0x10000 // 13

@@ -427,6 +427,36 @@ def test_special_case_equals_textbook_per_token_int8():
     assert np.allclose(c.scale.astype(np.float64), (amax / 127.0).ravel(), rtol=2e-7)
 
 
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("rule", [RULE_PAPER, RULE_FULLRANGE])
+@pytest.mark.parametrize("dtype", [oracle.DT_BF16, oracle.DT_F16])
+def test_a_tensor_on_the_quantisation_grid_is_a_fixed_point(bits, rule, dtype):
+    """x = c / 8 with integer c over the whole code range and the range's end present in every group
+    (Eq. 2): the scale is exactly 1/8, the codes are c, the reconstruction is x bit for bit, and
+    compressing the reconstruction gives the same codes and scales again.  Both 16-bit formats hold
+    these values exactly (|c| <= 128 needs 8 significant bits)."""
+    q = 1 << (bits - 1)
+    d = q if rule == RULE_PAPER else q - 1
+    gq, groups = 32, 16
+    g = np.random.default_rng(40 + bits + rule)
+    c = g.integers(-d if rule == RULE_FULLRANGE else -q, q, size=(groups, gq))
+    c[:, 0] = -d                       # the end of the range: max |x| = d / 8, so S = 1 / 8
+    if rule == RULE_FULLRANGE:
+        c[1::2, 0] = d                 # either sign of the largest magnitude serves
+    x = oracle.from_f32((c.reshape(-1) / 8.0).astype(np.float32), dtype)
+    assert np.array_equal(oracle.to_f32(x, dtype), (c.reshape(-1) / 8.0).astype(np.float32))
+    m = Method(bits=bits, quant_group=gq, scale_rule=rule, dtype=dtype)
+    first = oracle.compress(m, x)
+    assert np.all(first.scale == np.float32(0.125))
+    assert np.array_equal(first.codes.astype(np.int64), c.reshape(-1))
+    f, b = oracle.decompress(first)
+    assert np.array_equal(b, x), "a tensor on the grid comes back bit for bit"
+    assert np.array_equal(f, oracle.to_f32(x, dtype))
+    second = oracle.compress(m, b)
+    assert np.array_equal(second.codes, first.codes) and np.array_equal(second.scale, first.scale)
+    assert np.array_equal(second.packed, first.packed)
+
+
 def test_symmetry_and_monotonicity_of_codes():
     # every positive bf16 below 4 plus the negatives, in one group with absmax 4
     pos = np.arange(0x0080, 0x4080, 37, dtype=np.uint16)
