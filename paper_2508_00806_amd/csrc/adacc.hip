@@ -981,15 +981,23 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
   float* partial = static_cast<float*>(workspace);
   double* S = reinterpret_cast<double*>(static_cast<unsigned char*>(workspace) + channel_partial_bytes(cp.n_chunks, hidden));
   const bool half = cp.plan.half;
-  ChannelFn fn = ADACC_PICK(half, channel_compress_fn(method->bits, method->asym, cp.plan.rowwise));
+  // strips of 512 channels where the matrix and the groups allow them, else tiles of 2048 consecutive elements
+  const bool by_strips = cp.plan.rowwise && hidden % 512u == 0;
+  ChannelFn fn = by_strips ? ADACC_PICK(half, channel_compress_strip_fn(method->bits, method->asym))
+                           : ADACC_PICK(half, channel_compress_fn(method->bits, method->asym, cp.plan.rowwise));
   uint32_t grid = 0;
-  rc = grid_for(cp.plan.n_tiles, reinterpret_cast<const void*>(fn), &grid, 2);
-  if (rc != ADACC_OK) return rc;
+  if (by_strips) {
+    grid = strip_grid(tokens, hidden, ADACC_PICK(half, channel_strip_rows()));
+  } else {
+    rc = grid_for(cp.plan.n_tiles, reinterpret_cast<const void*>(fn), &grid, 2);
+    if (rc != ADACC_OK) return rc;
+  }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
-  const uint32_t n_items = cp.n_chunks * (hidden / 8);  // one lane: 8 channels of one chunk
-  hipLaunchKernelGGL(ADACC_PICK(half, channel_partial_fn(2ull * cp.numel > kStatsKeepBytes)), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
-                     static_cast<const uint16_t*>(src), (uint32_t)tokens, hidden, partial, n_items);
+  const uint32_t strips = (hidden / 8 + kWave - 1) / kWave;  // a workgroup: one chunk of a strip of 512 channels
+  hipLaunchKernelGGL(ADACC_PICK(half, channel_partial_fn(2ull * cp.numel > kStatsKeepBytes)), dim3(cp.n_chunks * strips),
+                     dim3(ADACC_PICK(half, channel_partial_threads())), 0, s, static_cast<const uint16_t*>(src), (uint32_t)tokens,
+                     hidden, partial, strips);
   rc = launch_check("channel_partial_kernel");
   if (rc != ADACC_OK) return rc;
   const uint32_t per_wg = ADACC_PICK(half, channel_score_channels());
@@ -997,10 +1005,10 @@ int adacc_channel_compress(const adacc_channel_method* method, const void* src, 
                      static_cast<const float*>(partial), cp.n_chunks, hidden, S);
   rc = launch_check("channel_score_kernel");
   if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(ADACC_PICK(half, channel_select_fn()), dim3(1), dim3(256), 0, s, static_cast<const double*>(S), c);
+  hipLaunchKernelGGL(ADACC_PICK(half, channel_select_fn()), dim3(1), dim3(ADACC_PICK(half, channel_select_threads())), 0, s, static_cast<const double*>(S), c);
   rc = launch_check("channel_select_kernel");
   if (rc != ADACC_OK) return rc;
-  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), channel_mask_lds(hidden), s, d, c);
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), by_strips ? 0u : channel_mask_lds(hidden), s, d, c);
   return launch_check("channel_compress_kernel");
 }
 
@@ -1105,8 +1113,9 @@ int adacc_channelwise_compress(uint32_t bits, uint32_t scale_rule, uint32_t dtyp
   const uint32_t grid = strip_grid(tokens, hidden, ADACC_PICK(half, channelwise_strip_rows()));
   int rc = ADACC_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const uint32_t n_items = c.n_chunks * (hidden / 8);
-  hipLaunchKernelGGL(ADACC_PICK(half, channelwise_partial_fn(2ull * c.numel > kStatsKeepBytes)), dim3((n_items + kThreads - 1) / kThreads), dim3(kThreads), 0, s, c, n_items);
+  const uint32_t strips = (hidden / 8 + kWave - 1) / kWave;  // a workgroup: one chunk of a strip of 512 channels
+  hipLaunchKernelGGL(ADACC_PICK(half, channelwise_partial_fn(2ull * c.numel > kStatsKeepBytes)), dim3(c.n_chunks * strips),
+                     dim3(ADACC_PICK(half, channelwise_partial_threads())), 0, s, c, strips);
   rc = launch_check("channelwise_partial_kernel");
   if (rc != ADACC_OK) return rc;
   const uint32_t per_wg = ADACC_PICK(half, channelwise_fold_octets());

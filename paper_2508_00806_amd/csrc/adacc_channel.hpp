@@ -15,49 +15,55 @@
 namespace adacc {
 namespace ADACC_DT_NS {
 
-constexpr int kSelectThreads = 256;     // accumulators of the sums over channels
+constexpr int kSelectThreads = 1024;    // accumulators of the sums over channels
 
-// ---- step 1: binary32 sums of |x| over chunks of 64 tokens.  One lane owns 8 adjacent channels
-// (one 16-byte load per token), consecutive lanes consecutive octets: fully coalesced rows.
-// partial[chunk][hidden].
+// ---- step 1: binary32 sums of |x| over chunks of 64 tokens, partial[chunk][hidden].  A workgroup
+// takes one chunk of a strip of 512 channels: a lane owns 8 adjacent channels (one 16-byte load per
+// token, rows fully coalesced), each wavefront a run of the chunk's tokens, all its loads in flight
+// at once; the wavefronts' sums meet in LDS and are added in token order.  Short-lived workgroups in
+// the hardware's order walk through the tensor as a window, which reads faster than a grid that is
+// resident as a whole and covers the tensor all the time.
 template <bool STREAM>
-__global__ __launch_bounds__(kThreads) void channel_partial_kernel(const uint16_t* __restrict__ x, uint32_t tokens,
-                                                                   uint32_t hidden, float* __restrict__ partial,
-                                                                   uint32_t n_items) {
-  const uint32_t octs = hidden / kOct;
-  for (uint32_t item = blockIdx.x * kThreads + threadIdx.x; item < n_items; item += gridDim.x * kThreads) {
-    const uint32_t chunk = item / octs;
-    const uint32_t oct = item - chunk * octs;
-    const uint32_t t0 = chunk * kChunkTokens;
-    const uint32_t rows = tokens - t0 < kChunkTokens ? tokens - t0 : kChunkTokens;
-    const uint16_t* p = x + (size_t)t0 * hidden + (size_t)oct * kOct;
-    float acc[kOct];
+__global__ __launch_bounds__(kPartialWaves * kWave) void channel_partial_kernel(const uint16_t* __restrict__ x,
+                                                                               uint32_t tokens, uint32_t hidden,
+                                                                               float* __restrict__ partial,
+                                                                               uint32_t strips) {
+  __shared__ float meet[kPartialWaves - 1][kOct][kWave];
+  const uint32_t wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint32_t chunk = blockIdx.x / strips;
+  const uint32_t oct = (blockIdx.x - chunk * strips) * kWave + lane;
+  const bool live = oct < hidden / kOct;
+  const uint32_t t0 = chunk * kChunkTokens + wave * kPartialRows;
+  const uint32_t rows = t0 >= tokens ? 0u : (tokens - t0 < kPartialRows ? tokens - t0 : kPartialRows);
+  const uint16_t* p = x + (size_t)t0 * hidden + (size_t)oct * kOct;
+  uint4 v[kPartialRows];
 #pragma unroll
-    for (int e = 0; e < kOct; ++e) acc[e] = 0.0f;
-    constexpr uint32_t kBatch = 16;  // loads in flight per lane
-    uint32_t r = 0;
-    for (; r + kBatch <= rows; r += kBatch) {
-      uint4 v[kBatch];
+  for (uint32_t i = 0; i < kPartialRows; ++i) {
+    v[i] = make_uint4(0u, 0u, 0u, 0u);  // a token that is not there adds +0
+    if (live && i < rows) v[i] = load_stats16<STREAM>(p + (size_t)i * hidden);
+  }
+  float acc[kOct];
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) v[i] = load_stats16<STREAM>(p + (size_t)(r + i) * hidden);
+  for (int e = 0; e < kOct; ++e) acc[e] = 0.0f;
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) {
-        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+  for (uint32_t i = 0; i < kPartialRows; ++i) {
+    const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          acc[2 * k] = acc[2 * k] + fabsf(widen_lo(w[k]));
-          acc[2 * k + 1] = acc[2 * k + 1] + fabsf(widen_hi(w[k]));
-        }
-      }
+    for (int k = 0; k < 4; ++k) {
+      acc[2 * k] = acc[2 * k] + fabsf(widen_lo(w[k]));
+      acc[2 * k + 1] = acc[2 * k + 1] + fabsf(widen_hi(w[k]));
     }
-    for (; r < rows; ++r) {
-      const uint4 v = load_stats16<STREAM>(p + (size_t)r * hidden);
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  }
+  if (wave != 0) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        acc[2 * k] = acc[2 * k] + fabsf(widen_lo(w[k]));
-        acc[2 * k + 1] = acc[2 * k + 1] + fabsf(widen_hi(w[k]));
-      }
+    for (int e = 0; e < kOct; ++e) meet[wave - 1][e][lane] = acc[e];
+  }
+  __syncthreads();
+  if (wave == 0 && live) {
+#pragma unroll
+    for (uint32_t w = 0; w + 1 < kPartialWaves; ++w) {
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) acc[e] = acc[e] + meet[w][e][lane];
     }
     float4* q = reinterpret_cast<float4*>(partial + (size_t)chunk * hidden + (size_t)oct * kOct);
     q[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -121,32 +127,58 @@ __device__ __forceinline__ bool finite_f64(double v) {
   return ((uint64_t)__double_as_longlong(v) & 0x7FF0000000000000ull) != 0x7FF0000000000000ull;
 }
 
-// 256 accumulators (thread j holds the sum over the channels h = j mod 256, ascending) folded by halves
-__device__ __forceinline__ double fold_accumulators(double mine, double* a /* LDS, 256 */) {
-  const int j = (int)threadIdx.x;
+// One accumulator per thread (thread j holds the sum over the channels h = j mod 1024, ascending).  They meet
+// in a fixed order: the xor butterfly inside a wavefront (both partners add the same two numbers, so every
+// lane ends with the same bits), then the wavefronts' sums through LDS, added in wavefront order by every
+// thread.  Two barriers instead of one per level of a tree over LDS.
+constexpr int kSelectWaves = kSelectThreads / kWave;
+__device__ __forceinline__ double meet_accumulators(double mine, double* a /* LDS, one per wavefront */) {
+#pragma unroll
+  for (int o = kWave / 2; o >= 1; o >>= 1) mine = __dadd_rn(mine, __shfl_xor(mine, o, kWave));
   __syncthreads();  // the previous use of `a` is over
-  a[j] = mine;
+  if (threadIdx.x % kWave == 0) a[threadIdx.x / kWave] = mine;
   __syncthreads();
-  for (int s = kSelectThreads / 2; s >= 1; s >>= 1) {
-    if (j < s) a[j] = __dadd_rn(a[j], a[j + s]);
-    __syncthreads();
+  double total = a[0];
+#pragma unroll
+  for (int w = 1; w < kSelectWaves; ++w) total = __dadd_rn(total, a[w]);
+  return total;
+}
+// the same for counts; `below`: the sum over the threads before this one
+__device__ __forceinline__ uint32_t meet_counts(uint32_t mine, uint32_t* cnt /* LDS, one per wavefront */, uint32_t* below) {
+  const uint32_t lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  uint32_t incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const uint32_t t = __shfl_up(incl, o, kWave);
+    if (lane >= (uint32_t)o) incl += t;
   }
-  return a[0];
+  __syncthreads();  // the previous use of `cnt` is over
+  if (lane == kWave - 1) cnt[wave] = incl;
+  __syncthreads();
+  uint32_t total = 0u, before = 0u;
+#pragma unroll
+  for (int w = 0; w < kSelectWaves; ++w) {
+    if ((uint32_t)w < wave) before += cnt[w];
+    total += cnt[w];
+  }
+  *below = before + incl - mine;
+  return total;
 }
 
 // ---- step 3 (Eq. 1): mu, sigma, Z, the channel mask, the list of outlier channels.  One
-// workgroup of 256 threads; the work is a few passes over `hidden` numbers.
+// workgroup of 1024 threads; the work is a few passes over `hidden` numbers (a division per channel).
 __global__ __launch_bounds__(kSelectThreads) void channel_select_kernel(const double* __restrict__ S, ChannelDesc c) {
-  __shared__ double a[kSelectThreads];
-  __shared__ uint32_t cnt[kSelectThreads];
+  __shared__ double a[kSelectWaves];
+  __shared__ uint32_t cnt[kSelectWaves];
   const uint32_t j = threadIdx.x;
   const uint32_t hidden = c.hidden;
 
   double acc = 0.0;
   uint32_t n = 0;
-  // four loads in flight per thread; a position past the end reads as +Inf and is skipped like
-  // any other sum that is not finite
-  constexpr uint32_t kAhead = 4;
+  // sixteen loads in flight per thread (the whole of a thread's share up to 16384 channels: the kernel is a
+  // chain of round trips to memory); a position past the end reads as +Inf and is skipped like any other sum
+  // that is not finite
+  constexpr uint32_t kAhead = 16;
   const double skip = __longlong_as_double(0x7FF0000000000000ll);
   for (uint32_t h = j; h < hidden; h += kAhead * kSelectThreads) {
     double v[kAhead];
@@ -156,14 +188,9 @@ __global__ __launch_bounds__(kSelectThreads) void channel_select_kernel(const do
     for (uint32_t i = 0; i < kAhead; ++i)
       if (finite_f64(v[i])) { acc = __dadd_rn(acc, v[i]); ++n; }
   }
-  const double total = fold_accumulators(acc, a);
-  cnt[j] = n;
-  __syncthreads();
-  for (int s = kSelectThreads / 2; s >= 1; s >>= 1) {
-    if ((int)j < s) cnt[j] += cnt[j + s];
-    __syncthreads();
-  }
-  const double finite = (double)cnt[0];
+  const double total = meet_accumulators(acc, a);
+  uint32_t unused;
+  const double finite = (double)meet_counts(n, cnt, &unused);
   const double mu = __ddiv_rn(total, finite);
 
   acc = 0.0;
@@ -178,7 +205,7 @@ __global__ __launch_bounds__(kSelectThreads) void channel_select_kernel(const do
         acc = __fma_rn(d, d, acc);
       }
   }
-  const double sigma = __dsqrt_rn(__ddiv_rn(fold_accumulators(acc, a), finite));
+  const double sigma = __dsqrt_rn(__ddiv_rn(meet_accumulators(acc, a), finite));
   const double zt = (double)c.z_thresh;
 
   // every thread takes a contiguous stretch of mask bytes, so that the channels stay in order
@@ -187,30 +214,26 @@ __global__ __launch_bounds__(kSelectThreads) void channel_select_kernel(const do
   const uint32_t b0 = j * per < n_bytes ? j * per : n_bytes;
   const uint32_t b1 = b0 + per < n_bytes ? b0 + per : n_bytes;
   uint32_t mine = 0;
+  uint64_t masks = 0ull;  // the thread's mask bytes (at most 8: hidden <= 65536), first byte lowest
   for (uint32_t b = b0; b < b1; ++b) {
+    double v[8];
+#pragma unroll
+    for (uint32_t e = 0; e < 8u; ++e) v[e] = S[b * 8u + e];
     uint32_t m = 0;
+#pragma unroll
     for (uint32_t e = 0; e < 8u; ++e) {
-      const double s = S[b * 8u + e];
-      const double z = __ddiv_rn(__dsub_rn(s, mu), sigma);
-      if (!finite_f64(s) || z > zt) m |= 1u << e;  // a NaN z selects nothing
+      const double z = __ddiv_rn(__dsub_rn(v[e], mu), sigma);
+      if (!finite_f64(v[e]) || z > zt) m |= 1u << e;  // a NaN z selects nothing
     }
     c.mask[b] = (uint8_t)m;
+    masks |= (uint64_t)m << (8u * (b - b0));
     mine += (uint32_t)__popc(m);
   }
-  // exclusive scan of the per-thread counts
-  __syncthreads();
-  cnt[j] = mine;
-  __syncthreads();
-  for (int s = 1; s < kSelectThreads; s <<= 1) {
-    const uint32_t add = (int)j >= s ? cnt[j - s] : 0u;
-    __syncthreads();
-    cnt[j] += add;
-    __syncthreads();
-  }
-  uint32_t running = cnt[j] - mine;
-  const uint32_t n_ch = cnt[kSelectThreads - 1];
+  // where this thread's channels go in the list: the outlier channels of the threads before it
+  uint32_t running;
+  const uint32_t n_ch = meet_counts(mine, cnt, &running);
   for (uint32_t b = b0; b < b1; ++b) {
-    uint32_t m = c.mask[b];  // written by this thread
+    uint32_t m = (uint32_t)(masks >> (8u * (b - b0))) & 0xFFu;
     c.base[b] = running;
     while (m) {
       const uint32_t e = (uint32_t)__builtin_ctz(m);
@@ -330,14 +353,92 @@ __global__ __launch_bounds__(kThreads) void channel_compress_kernel(TensorDesc d
   }
 }
 
+// ---- step 4 for matrices whose rows are whole multiples of 512 channels, groups inside 512 channels:
+// a wavefront takes a strip of 512 adjacent channels (8 per lane) over kChannelStripRows consecutive
+// tokens.  Which of a lane's 8 channels are outlier channels, and where their values go in a token's
+// record, is the same for every token: looked up once, no table in LDS and no division per octet.  All
+// loads of the strip are issued first; its rows are then encoded four at a time like a tile's.
+constexpr uint32_t kChannelStripRows = 8;
+
+template <int BITS, bool ASYM>
+__global__ __launch_bounds__(kThreads) void channel_compress_strip_kernel(TensorDesc d, ChannelDesc c) {
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  if (c.status[1] != 0u) return;  // more outlier channels than the blob holds: nothing else is produced
+  const uint32_t n_ch = __builtin_amdgcn_readfirstlane(c.status[0]);
+  const uint32_t strips = c.hidden / (uint32_t)kRow;
+  const uint32_t unit = blockIdx.x * kWavesPerWg + wave;
+  const uint32_t block = unit / strips;
+  const uint32_t row0 = block * kChannelStripRows;
+  if (row0 >= c.tokens) return;  // uniform
+  const uint32_t col0 = (unit - block * strips) * (uint32_t)kRow;
+  const uint32_t rows = c.tokens - row0 < kChannelStripRows ? c.tokens - row0 : kChannelStripRows;
+  const uint32_t lane_off = (uint32_t)lane_id() * kOct;
+
+  uint32_t m = 0u, first = 0u;
+  if (n_ch != 0u) {
+    m = c.mask[(col0 + lane_off) >> 3];
+    first = c.base[(col0 + lane_off) >> 3];
+  }
+  constexpr uint32_t kHalf = kChannelStripRows / 2;
+  const uint64_t base = (uint64_t)row0 * c.hidden + col0;  // uniform
+  const uint16_t* sp = d.src + base;
+  uint32_t raw[2][kHalf][4];
+#pragma unroll
+  for (uint32_t i = 0; i < kChannelStripRows; ++i) {  // rows past the end re-read the last one
+    const uint32_t row = i < rows ? i : rows - 1u;
+    const uint4 v = ADACC_LOAD16(sp + (row * c.hidden + lane_off));
+    raw[i / kHalf][i % kHalf][0] = v.x; raw[i / kHalf][i % kHalf][1] = v.y;
+    raw[i / kHalf][i % kHalf][2] = v.z; raw[i / kHalf][i % kHalf][3] = v.w;
+  }
+  if (m != 0u) {  // the kept channels go out first, then they are cleared
+    uint16_t* dst = c.ch_val + (size_t)row0 * n_ch + first;
+    static_for<(int)kChannelStripRows>([&](auto Ic) {  // the data-dependent loop inside must not keep this one rolled
+      constexpr uint32_t i = (uint32_t)decltype(Ic)::value;
+      if (i < rows) {
+        uint32_t todo = m, r = 0u;
+        while (todo != 0u) {
+          const uint32_t e = (uint32_t)__builtin_ctz(todo);
+          todo &= todo - 1u;
+          dst[(size_t)i * n_ch + r++] = (uint16_t)octet_half(raw[i / kHalf][i % kHalf], e);
+        }
+      }
+      clear_elements(raw[i / kHalf][i % kHalf], m);
+    });
+  }
+  static_for<2>([&](auto Hc) {
+    constexpr uint32_t h = (uint32_t)decltype(Hc)::value;
+    if (rows >= (h + 1u) * kHalf) {  // uniform: four whole rows
+      TileGeo<(int)kHalf, true> g;
+      g.base = base + (uint64_t)(h * kHalf) * c.hidden;
+      g.rem = kHalf * (uint32_t)kRow;
+      g.lane_off = lane_off;
+      g.full = true;
+      g.stride = c.hidden;
+      encode_tile_rowwise<kModeNone, BITS, ASYM, (int)kHalf, true>(d, g, raw[h], 0u, NullSink{}, 0u, 0u);
+    } else {
+      static_for<(int)kHalf>([&](auto Ic) {  // the last tokens of the matrix, one row at a time
+        constexpr uint32_t i = (uint32_t)decltype(Ic)::value;
+        if (h * kHalf + i < rows) {
+          TileGeo<1, true> g;
+          g.base = base + (uint64_t)(h * kHalf + i) * c.hidden;
+          g.rem = (uint32_t)kRow;
+          g.lane_off = lane_off;
+          g.full = true;
+          g.stride = c.hidden;
+          const uint32_t one[1][4] = {{raw[h][i][0], raw[h][i][1], raw[h][i][2], raw[h][i][3]}};
+          encode_tile_rowwise<kModeNone, BITS, ASYM, 1, true>(d, g, one, 0u, NullSink{}, 0u, 0u);
+        }
+      });
+    }
+  });
+}
+
 // ---- decompression: dequantise, put the outlier channels back, store.
 // A wavefront takes a strip of 512 adjacent channels (8 per lane) over kChannelStripRows consecutive tokens:
 // which of a lane's 8 channels are outlier channels, and where their values start in a token's record, is
 // the same for every token, so it is looked up once (no table in LDS, no division per octet).  The loads of
 // four tokens (codes, scale, offset, the first kept value of the octet) are issued before their first store;
 // a second outlier channel in the same octet is rare and fetched when it is needed.
-constexpr uint32_t kChannelStripRows = 8;
-
 template <int BITS, bool ASYM, bool F32>
 __global__ __launch_bounds__(kThreads) void channel_decompress_kernel(TensorDesc d, ChannelDesc c) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);

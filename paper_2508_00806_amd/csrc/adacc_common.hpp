@@ -112,6 +112,8 @@ struct TensorDesc {
 
 // Outlier channels (Section 3.2, Eq. 1): what those kernels need beside the TensorDesc of the quantised part.
 constexpr uint32_t kChunkTokens = 64;  // tokens per binary32 partial sum of the channel statistics
+constexpr uint32_t kPartialWaves = 16;  // wavefronts that share a chunk in the statistics pass (one workgroup)
+constexpr uint32_t kPartialRows = kChunkTokens / kPartialWaves;  // tokens per wavefront there
 struct ChannelDesc {
   uint8_t* mask;        // hidden/8 bytes: bit (h & 7) of byte h >> 3 is set for an outlier channel
   uint32_t* base;       // hidden/8 words: number of outlier channels below channel 8 * (h >> 3)

@@ -205,12 +205,19 @@ __device__ __forceinline__ uint32_t pack_nibbles8(const uint32_t (&c)[kOct]) {
 // ------------------------------------------------------------------ tile geometry, loads and stores
 // A tile is addressed as a wavefront-uniform base (kept in scalar registers) plus a 32-bit
 // lane offset, so that address arithmetic costs no vector instructions.
-template <int E>
+// STRIP: the E rows of 512 elements are not adjacent in memory but `stride` elements apart (rows of a
+// matrix: a strip of 512 columns); such a tile is always complete, and base, stride are multiples of 512.
+template <int E, bool STRIP = false>
 struct TileGeo {
   uint64_t base;      // uniform: index of the tile's first element
   uint32_t rem;       // uniform: elements of the tensor from `base` on, at most E*512 (a multiple of 8, > 0)
   uint32_t lane_off;  // lane * 8
   bool full;          // uniform: rem == E*512
+  uint32_t stride;    // uniform, STRIP only: elements from one row to the next
+  __device__ __forceinline__ uint32_t row_offset(int j) const {
+    if constexpr (STRIP) return (uint32_t)j * stride;
+    else return (uint32_t)(j * kRow);
+  }
 };
 // COMPLETE: the caller knows that every tile of the tensor is complete (the tile is a statistics
 // group, and group sizes divide the tensor), so nothing about short tiles is computed or tested.
@@ -219,6 +226,7 @@ __device__ __forceinline__ TileGeo<E> tile_geo(const TensorDesc& d, uint32_t til
   TileGeo<E> g;
   g.base = (uint64_t)tile * (uint64_t)(E * kRow);
   g.lane_off = (uint32_t)lane_id() * kOct;
+  g.stride = (uint32_t)kRow;
   if constexpr (COMPLETE) {
     g.rem = (uint32_t)(E * kRow);
     g.full = true;
@@ -281,15 +289,15 @@ __device__ __forceinline__ void widen_row(const uint32_t (&oct)[4], float (&x)[k
 // compiler's wait-count bookkeeping, and the wait for the prefetched tile would then also wait
 // for these stores.  In a tensor's last tile, octets past the end go to a scrap area in the
 // unused part of the blob's status block; all lanes of a group store their (identical) scale.
-template <int BITS, bool ASYM, int E>
-__device__ __forceinline__ void store_row(const TensorDesc& d, const TileGeo<E>& g, int j, const uint32_t (&c)[kOct],
-                                          float scl, float off) {
+template <int BITS, bool ASYM, int E, bool STRIP>
+__device__ __forceinline__ void store_row(const TensorDesc& d, const TileGeo<E, STRIP>& g, int j,
+                                          const uint32_t (&c)[kOct], float scl, float off) {
   // The lane's offset is formed here, per row, from a copy the compiler knows nothing about: else it
   // prepares the offsets (and the group numbers) of all rows ahead of the first row, for every
   // group size the caller can be asked for, and keeps them in registers.
   uint32_t lane_off = g.lane_off;
   asm volatile("" : "+v"(lane_off));
-  const uint32_t eo = lane_off + (uint32_t)(j * kRow);  // element offset in the tile
+  const uint32_t eo = lane_off + g.row_offset(j);  // element offset from the tile's first element
   unsigned char* cp = d.codes + g.base * BITS / 8;       // uniform
   float* sp = d.scales + (g.base >> d.lgq);                // uniform
   const uint32_t gl = eo >> d.lgq;
@@ -524,9 +532,9 @@ __device__ __forceinline__ void scale_sym_clean(const TensorDesc& d, uint32_t am
 
 // a6 .. a8 for one row of a tile from which outliers and values that are not finite are gone
 // (they are zero in `oct`).  top: symmetric, the lane's largest magnitude of the row as binary32 bits.
-template <int BITS, bool ASYM, int E, int LANES>
-__device__ __forceinline__ void encode_clean_row(const TensorDesc& d, const TileGeo<E>& g, int j, const uint32_t (&oct)[4],
-                                                 uint32_t top) {
+template <int BITS, bool ASYM, int E, int LANES, bool STRIP>
+__device__ __forceinline__ void encode_clean_row(const TensorDesc& d, const TileGeo<E, STRIP>& g, int j,
+                                                 const uint32_t (&oct)[4], uint32_t top) {
   constexpr int Q = 1 << (BITS - 1);
   float x[kOct];
   widen_row(oct, x);
@@ -550,9 +558,11 @@ __device__ __forceinline__ void encode_clean_row(const TensorDesc& d, const Tile
 // Used when every group (statistics and quantisation) lies inside one 512-element row and both
 // kinds have the same size: each row is taken from the raw octets to its stored codes in one
 // go, so nothing but the raw octets lives across rows.  LANES = lanes per group.
-template <int MODE, int BITS, bool ASYM, int E, int LANES, bool STORE, class Sink>
-__device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileGeo<E>& g, const uint32_t (&raw)[E][4],
-                                                uint32_t tile, const Sink& sink, uint32_t pos0, uint32_t limit) {
+template <int MODE, int BITS, bool ASYM, int E, int LANES, bool STORE, class Sink, bool STRIP>
+__device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileGeo<E, STRIP>& g,
+                                                const uint32_t (&raw)[E][4], uint32_t tile, const Sink& sink,
+                                                uint32_t pos0, uint32_t limit) {
+  static_assert(!STRIP || MODE == kModeNone, "element indices of outliers are formed for adjacent rows only");
   constexpr int Q = 1 << (BITS - 1);
   const float inv_gs = __uint_as_float((127u - d.lgs) << 23);  // 2^-lgs, exact
   const uint32_t lane_first = tile * (uint32_t)(E * kRow) + (uint32_t)lane_id() * kOct;
@@ -640,8 +650,8 @@ __device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileG
   return total;
 }
 
-template <int MODE, int BITS, bool ASYM, int E, bool STORE, class Sink>
-__device__ __forceinline__ uint32_t encode_tile_rowwise(const TensorDesc& d, const TileGeo<E>& g,
+template <int MODE, int BITS, bool ASYM, int E, bool STORE, class Sink, bool STRIP>
+__device__ __forceinline__ uint32_t encode_tile_rowwise(const TensorDesc& d, const TileGeo<E, STRIP>& g,
                                                         const uint32_t (&raw)[E][4], uint32_t tile, const Sink& sink,
                                                         uint32_t pos0, uint32_t limit) {
   switch (d.lgq) {  // one switch per tile selects straight-line code for the group size

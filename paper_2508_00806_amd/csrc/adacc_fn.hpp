@@ -31,8 +31,12 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
 //   kind: kBatch* of adacc_common.hpp
 //   stream: the statistics pass reads with the streaming hint (tensors beyond kStatsKeepBytes)
 //   channel_score_channels: channels per workgroup of the score kernel
+//   channel_select_threads: size of the one workgroup of the select kernel
+//   channel_partial_threads, channelwise_partial_threads: size of a workgroup of the statistics pass (one chunk of
+//     64 tokens of a strip of 512 channels)
 //   channelwise_fold_octets: octets of channels per workgroup of the fold kernel
 //   channelwise_strip_rows, channel_strip_rows: tokens a wavefront of the strip kernels takes
+//   channel_compress_strip_fn: for matrices whose rows are multiples of 512 channels, groups inside 512 channels
 #define ADACC_DTYPE_GETTERS                                                            \
   CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);    \
   CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
@@ -56,13 +60,17 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   ChannelScoreFn channel_score_fn();                                                   \
   ChannelSelectFn channel_select_fn();                                                 \
   uint32_t channel_score_channels();                                                   \
+  uint32_t channel_select_threads();                                                   \
+  uint32_t channel_partial_threads();                                                  \
   uint32_t channel_strip_rows();                                                       \
   ChannelFn channel_compress_fn(uint32_t bits, uint32_t asym, bool rowwise);           \
+  ChannelFn channel_compress_strip_fn(uint32_t bits, uint32_t asym);                   \
   ChannelFn channel_decompress_fn(uint32_t bits, uint32_t asym, bool f32);             \
   ChannelwiseItemsFn channelwise_partial_fn(bool stream);                              \
   ChannelwiseFn channelwise_fold_fn();                                                 \
   uint32_t channelwise_fold_octets();                                                  \
   uint32_t channelwise_strip_rows();                                                   \
+  uint32_t channelwise_partial_threads();                                              \
   ChannelwiseFn channelwise_quantise_fn(uint32_t bits);                                \
   ChannelwiseFn channelwise_dequantise_fn(uint32_t bits, bool f32);
 namespace bf16 {

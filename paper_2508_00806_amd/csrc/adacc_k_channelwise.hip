@@ -23,38 +23,43 @@ __device__ __forceinline__ uint32_t finite_magnitudes2(uint32_t w) {
 }
 
 // ---- step 1: partial[chunk][hidden] = max of the finite magnitudes over the chunk's tokens.
-// Same decomposition as the chunk sums of the outlier-channel statistics: a lane owns 8 adjacent
-// channels of one chunk, 16 loads of 16 bytes in flight, rows fully coalesced.
+// Same decomposition as the chunk sums of the outlier-channel statistics: a workgroup takes one chunk of
+// a strip of 512 channels, a lane owns 8 adjacent channels, each wavefront a run of the chunk's tokens
+// with all its loads in flight at once; the wavefronts' maxima meet in LDS.
 template <bool STREAM>
-__global__ __launch_bounds__(kThreads) void channelwise_partial_kernel(ChannelwiseDesc c, uint32_t n_items) {
-  const uint32_t octs = c.hidden / kOct;
-  for (uint32_t item = blockIdx.x * kThreads + threadIdx.x; item < n_items; item += gridDim.x * kThreads) {
-    const uint32_t chunk = item / octs;
-    const uint32_t oct = item - chunk * octs;
-    const uint32_t t0 = chunk * kChunkTokens;
-    const uint32_t rows = c.tokens - t0 < kChunkTokens ? c.tokens - t0 : kChunkTokens;
-    const uint16_t* p = c.src + (size_t)t0 * c.hidden + (size_t)oct * kOct;
-    uint32_t acc[4] = {0u, 0u, 0u, 0u};
-    constexpr uint32_t kBatch = 16;
-    uint32_t r = 0;
-    for (; r + kBatch <= rows; r += kBatch) {
-      uint4 v[kBatch];
+__global__ __launch_bounds__(kPartialWaves * kWave) void channelwise_partial_kernel(ChannelwiseDesc c, uint32_t strips) {
+  __shared__ uint32_t meet[kPartialWaves - 1][4][kWave];
+  const uint32_t wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const uint32_t chunk = blockIdx.x / strips;
+  const uint32_t oct = (blockIdx.x - chunk * strips) * kWave + lane;
+  const bool live = oct < c.hidden / kOct;
+  const uint32_t t0 = chunk * kChunkTokens + wave * kPartialRows;
+  const uint32_t rows = t0 >= c.tokens ? 0u : (c.tokens - t0 < kPartialRows ? c.tokens - t0 : kPartialRows);
+  const uint16_t* p = c.src + (size_t)t0 * c.hidden + (size_t)oct * kOct;
+  uint4 v[kPartialRows];
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) v[i] = load_stats16<STREAM>(p + (size_t)(r + i) * c.hidden);
+  for (uint32_t i = 0; i < kPartialRows; ++i) {
+    v[i] = make_uint4(0u, 0u, 0u, 0u);  // a token that is not there: magnitude zero
+    if (live && i < rows) v[i] = load_stats16<STREAM>(p + (size_t)i * c.hidden);
+  }
+  uint32_t acc[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-      for (uint32_t i = 0; i < kBatch; ++i) {
-        acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v[i].x));
-        acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v[i].y));
-        acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v[i].z));
-        acc[3] = pk_max_u16(acc[3], finite_magnitudes2(v[i].w));
-      }
-    }
-    for (; r < rows; ++r) {
-      const uint4 v = load_stats16<STREAM>(p + (size_t)r * c.hidden);
-      acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v.x));
-      acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v.y));
-      acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v.z));
-      acc[3] = pk_max_u16(acc[3], finite_magnitudes2(v.w));
+  for (uint32_t i = 0; i < kPartialRows; ++i) {
+    acc[0] = pk_max_u16(acc[0], finite_magnitudes2(v[i].x));
+    acc[1] = pk_max_u16(acc[1], finite_magnitudes2(v[i].y));
+    acc[2] = pk_max_u16(acc[2], finite_magnitudes2(v[i].z));
+    acc[3] = pk_max_u16(acc[3], finite_magnitudes2(v[i].w));
+  }
+  if (wave != 0) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) meet[wave - 1][k][lane] = acc[k];
+  }
+  __syncthreads();
+  if (wave == 0 && live) {
+#pragma unroll
+    for (uint32_t w = 0; w + 1 < kPartialWaves; ++w) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[k] = pk_max_u16(acc[k], meet[w][k][lane]);
     }
     *reinterpret_cast<uint4*>(c.partial + (size_t)chunk * c.hidden + (size_t)oct * kOct) =
         make_uint4(acc[0], acc[1], acc[2], acc[3]);
@@ -229,6 +234,7 @@ __global__ __launch_bounds__(kThreads) void channelwise_dequantise_kernel(Channe
 }
 
 uint32_t channelwise_strip_rows() { return kStripRows; }
+uint32_t channelwise_partial_threads() { return kPartialWaves * (uint32_t)kWave; }
 ChannelwiseItemsFn channelwise_partial_fn(bool stream) {
   return stream ? channelwise_partial_kernel<true> : channelwise_partial_kernel<false>;
 }

@@ -53,6 +53,21 @@ def test_narrow_matrix_with_neighbouring_outlier_channels():
     assert list(oc.ch_idx) == [3, 4, 17, 39]
 
 
+@pytest.mark.parametrize("tokens", [203, 206, 5])
+def test_strips_with_a_short_last_block_of_tokens(tokens):
+    """Rows of 3 x 512 channels, groups inside 512 channels: the strip kernel (8 tokens per wavefront), with
+    1 .. 7 tokens left for the last block; two outlier channels in one octet, the first and the last
+    channel of a strip, and two channels kept because one of their values is not finite."""
+    log(f"[channel] strips hidden=1536 tokens={tokens}")
+    x = planted(tokens, 1536, [0, 511, 512, 700, 701, 1535], seed=24 + tokens)
+    x[tokens // 2, 100] = float("inf")
+    x[tokens - 1, 1400] = float("nan")
+    for bits, gq, asym in ((4, 128, 0), (8, 512, 1), (4, 8, 1), (8, 64, 0)):
+        oc, _ = run_channel_parity(x, bits, gq, asym)
+        assert [int(i) for i in oc.ch_idx] == [0, 100, 511, 512, 700, 701, 1400, 1535]
+    run_channel_parity(x.to(torch.float32).clamp(-6e4, 6e4).to(torch.float16), 4, 128, 0)
+
+
 def test_groups_of_a_whole_tile_and_the_other_scale_rule():
     log("[channel] hidden=4096 gq=2048")
     x = planted(70, 4096, [9, 10, 11, 12, 13, 14, 15, 16, 4000], seed=23)
