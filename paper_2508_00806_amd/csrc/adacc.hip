@@ -241,10 +241,14 @@ static int wave_capacity(const void* kernel, int cus, uint32_t* waves) {
 static bool topk_whole_tile(const adacc_method* m, const Plan& p) {
   return m->outlier_mode == ADACC_OUTLIER_TOPK && m->stat_group == p.tile_elems && m->quant_group <= 512;
 }
+// TOPK over groups that are the quantisation groups and lie inside a 512-element row: the row-at-a-time encoder
+static bool topk_in_rows(const adacc_method* m, const Plan& p) {
+  return !p.generic && m->outlier_mode == ADACC_OUTLIER_TOPK && m->stat_group == m->quant_group && m->quant_group <= 512;
+}
 static int batch_kind(const adacc_method* m, const Plan& p) {
   const bool whole = topk_whole_tile(m, p);
   if (p.tile_elems == 4096) return whole ? kBatchTopk8 : kBatchAny8;
-  return p.rowwise ? kBatchRows4 : (whole ? kBatchTopk4 : kBatchAny4);
+  return (p.rowwise || topk_in_rows(m, p)) ? kBatchRows4 : (whole ? kBatchTopk4 : kBatchAny4);
 }
 
 static uint32_t decompress_pieces(uint64_t numel) { return (uint32_t)((numel + 2047ull) / 2048ull); }
@@ -359,14 +363,15 @@ static BatchCompressFn compress_batch_fn(bool half, int kind) {
   return kind >= kBatchAny8 ? ADACC_PICK(half, compress_batch_fn8(kind)) : ADACC_PICK(half, compress_batch_fn4(kind));
 }
 
-// `whole` (TOPK only): the statistics group is the whole tile; that case has kernels of its own
+// `whole` (TOPK only): the statistics group is the whole tile; that case has kernels of its own.
+// `rowwise`: for TOPK, statistics group = quantisation group inside a row (topk_in_rows)
 static CompressFn compress_fn(const adacc_method* m, bool e8, bool rowwise, bool whole) {
   const bool half = m->dtype == ADACC_DTYPE_F16;
   switch (m->outlier_mode) {
     case ADACC_OUTLIER_NONE: return ADACC_PICK(half, compress_fn_none(m->bits, m->asym, e8, rowwise));
     case ADACC_OUTLIER_ABS: return ADACC_PICK(half, compress_fn_abs(m->bits, m->asym, e8, rowwise));
     case ADACC_OUTLIER_STD: return ADACC_PICK(half, compress_fn_std(m->bits, m->asym, e8, rowwise));
-    default: return ADACC_PICK(half, compress_fn_topk(m->bits, m->asym, e8, whole));
+    default: return ADACC_PICK(half, compress_fn_topk(m->bits, m->asym, e8, whole, rowwise));
   }
 }
 
@@ -640,7 +645,7 @@ static int compress_one(const adacc_method* method, const void* src, uint64_t nu
     }
     return launch_generic_compress(method, p, d, epoch, s);
   }
-  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise, topk_whole_tile(method, p));
+  CompressFn fn = compress_fn(method, p.tile_elems == 4096, p.rowwise || topk_in_rows(method, p), topk_whole_tile(method, p));
   const uint32_t grid = (p.n_tiles + kWavesPerWg - 1) / kWavesPerWg;  // one tile per wavefront
   uint32_t epoch = 0;
   if (p.outliers) {

@@ -554,6 +554,35 @@ __device__ __forceinline__ void encode_clean_row(const TensorDesc& d, const Tile
   store_row<BITS, ASYM, E>(d, g, j, c, scl, off);
 }
 
+// ------------------------------------------------------------------ TOPK over groups inside a row
+// The k largest of every group of LANES lanes (8 * LANES elements of one row) by (magnitude, lower index),
+// as the 8 ballots of the row: k rounds of a maximum over keys (magnitude in the high bits, the reversed
+// position in the group below it, plus one so that no live key is zero); the winner's key is unique in its
+// group, its owner sets it to zero.  Every value that is not finite is an outlier besides.
+template <int LANES>
+__device__ __forceinline__ void topk_row_ballots(const TensorDesc& d, const uint32_t (&oct)[4], uint64_t (&b)[kOct]) {
+  const uint32_t last = (uint32_t)(LANES * kOct) - 1u - ((uint32_t)lane_id() & (uint32_t)(LANES - 1)) * kOct;  // reversed position of element 0
+  uint32_t key[kOct];
+  bool nonfinite[kOct];
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) {
+    const uint32_t word = oct[e >> 1];
+    const uint32_t mag = (e & 1) ? (word >> 16) & 0x7FFFu : word & 0x7FFFu;
+    nonfinite[e] = mag >= kNonfiniteMag;
+    key[e] = ((mag << 9) | (last - (uint32_t)e)) + 1u;
+  }
+  for (uint32_t r = 0; r < d.topk; ++r) {  // uniform
+    uint32_t best = key[0];
+#pragma unroll
+    for (int e = 1; e < kOct; ++e) best = key[e] > best ? key[e] : best;
+    const uint32_t win = lanes_reduce<LANES>(best, OpUMax());
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) key[e] = key[e] == win ? 0u : key[e];
+  }
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(key[e] == 0u || nonfinite[e]);
+}
+
 // ------------------------------------------------------------------ tile encoder for groups inside a row
 // Used when every group (statistics and quantisation) lies inside one 512-element row and both
 // kinds have the same size: each row is taken from the raw octets to its stored codes in one
@@ -579,7 +608,16 @@ __device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileG
     float limit_sq = 0.0f;
     uint32_t am_bits = 0u;
     bool suspect;
-    if constexpr (MODE == kModeStd) {
+    uint64_t b[kOct];
+    if constexpr (MODE == kModeTopk) {
+      suspect = true;  // every group has outliers: its k largest
+      topk_row_ballots<LANES>(d, raw[j], b);
+      if (!g.full) {  // uniform; the tensor's last tile: groups past its end (blanked) have no outliers
+        const uint64_t valid = __builtin_amdgcn_ballot_w64(g.lane_off + g.row_offset(j) < g.rem);
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) b[e] &= valid;
+      }
+    } else if constexpr (MODE == kModeStd) {
 #pragma unroll
       for (int e = 0; e < kOct; ++e) q[e] = x[e] * x[e];  // exact: two 8-bit significands
       float s1 = ((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]));
@@ -600,13 +638,16 @@ __device__ __forceinline__ uint32_t encode_rows(const TensorDesc& d, const TileG
       if constexpr (MODE == kModeAbs) suspect = am_bits > __float_as_uint(d.param);  // tau >= 0, finite
       else suspect = am_bits >= 0x7F800000u;
     }
-    if (__builtin_amdgcn_ballot_w64(suspect) == 0ull) {  // uniform
-      if constexpr (STORE) encode_clean_row<BITS, ASYM, E, LANES>(d, g, j, raw[j], am_bits);
-      continue;
+    if constexpr (MODE != kModeTopk) {
+      if (__builtin_amdgcn_ballot_w64(suspect) == 0ull) {  // uniform
+        if constexpr (STORE) encode_clean_row<BITS, ASYM, E, LANES>(d, g, j, raw[j], am_bits);
+        continue;
+      }
     }
     // the 8 outlier tests of the row as wavefront ballots (scalar registers)
-    uint64_t b[kOct];
-    if constexpr (MODE == kModeStd) {
+    if constexpr (MODE == kModeTopk) {
+      // formed above
+    } else if constexpr (MODE == kModeStd) {
 #pragma unroll
       for (int e = 0; e < kOct; ++e) b[e] = __builtin_amdgcn_ballot_w64(q[e] > limit_sq);
       if (__builtin_amdgcn_ballot_w64(limit_sq != limit_sq) != 0ull) {  // then every element is tested for Inf / NaN

@@ -27,7 +27,8 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
 
 // The getters of the kernels that read or write the tensor itself exist once per 16-bit format, in
 // adacc::bf16 and adacc::f16 (the same sources compiled twice).
-//   e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile
+//   e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile;
+//   rows (TOPK): statistics group = quantisation group, inside a row
 //   kind: kBatch* of adacc_common.hpp
 //   stream: the statistics pass reads with the streaming hint (tensors beyond kStatsKeepBytes)
 //   channel_score_channels: channels per workgroup of the score kernel
@@ -41,7 +42,7 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   CompressFn compress_fn_none(uint32_t bits, uint32_t asym, bool e8, bool rowwise);    \
   CompressFn compress_fn_abs(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
   CompressFn compress_fn_std(uint32_t bits, uint32_t asym, bool e8, bool rowwise);     \
-  CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole);      \
+  CompressFn compress_fn_topk(uint32_t bits, uint32_t asym, bool e8, bool whole, bool rows); \
   DecompressFn decompress_fn(uint32_t bits, uint32_t asym, bool f32);                  \
   BatchCompressFn compress_batch_fn4(int kind);                                        \
   BatchCompressFn compress_batch_fn8(int kind);                                        \

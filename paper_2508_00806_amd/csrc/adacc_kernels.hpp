@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint
 // the tensors one after the other, front to back.
 // A kernel holds as many wavefronts per SIMD as its heaviest variant allows, so the variants come
 // in five kernels by weight:
-//   kBatchRows4   tiles of 4 rows, all groups inside a row (NONE / ABS / STD)       lightest
+//   kBatchRows4   tiles of 4 rows, all groups inside a row (TOPK: over the quantisation groups)   lightest
 //   kBatchAny4    tiles of 4 rows, any other grouping
 //   kBatchTopk4   tiles of 4 rows, TOPK over the whole tile, quantisation groups inside a row
 //   kBatchAny8    tiles of 8 rows, general encoder                                   heaviest
@@ -98,9 +98,7 @@ __global__ __launch_bounds__(kThreads, (batch_min_waves<KIND>())) void compress_
       case kModeNone: compress_dispatch<kModeNone, E, ROWWISE, false>(d, tile, epoch); break;
       case kModeAbs: compress_dispatch<kModeAbs, E, ROWWISE, false>(d, tile, epoch); break;
       case kModeStd: compress_dispatch<kModeStd, E, ROWWISE, false>(d, tile, epoch); break;
-      default:
-        if constexpr (!ROWWISE) compress_dispatch<kModeTopk, E, false, false>(d, tile, epoch);
-        break;
+      default: compress_dispatch<kModeTopk, E, ROWWISE, false>(d, tile, epoch); break;
     }
   }
 }

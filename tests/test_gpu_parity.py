@@ -109,36 +109,57 @@ def test_degenerate_inputs():
     run_parity(from_bits(nonfin), md)
 
 
+def topk_corner_case_bits(gs, k, rng):
+    """Seven groups: the largest values share a lane, tie at the k-th place, sit in a constant group, or
+    come with Inf / NaN, next to groups where the k largest are clear-cut."""
+    n_groups = 7
+    v = rng.normal(0.0, 1.0, size=gs * n_groups).astype(np.float32)
+    b = bits_of(torch.from_numpy(v).to(torch.bfloat16)).copy()
+    big = int(bits_of(torch.tensor([50.0], dtype=torch.bfloat16))[0])
+    g = lambda i: slice(i * gs, (i + 1) * gs)
+    # group 0: the k+1 largest next to each other (one lane holds most of them)
+    b[g(0)][8:8 + k + 1] = [big + i for i in range(k + 1)]
+    # group 1: k+2 equal maxima spread over the group, negative ones included
+    pos = np.sort(rng.choice(gs, size=k + 2, replace=False))
+    b[g(1)][pos] = big
+    b[g(1)][pos[::2]] |= 0x8000
+    # group 2: constant; group 3: all zero with one -0
+    b[g(2)] = 0x3F80
+    b[g(3)] = 0
+    b[g(3)][5] = 0x8000
+    # group 4: Inf, NaN and large values together
+    b[g(4)][[3, gs // 2, gs // 2 + 9, gs // 2 + 10]] = [0x7F80, 0xFFC1, big, big + 1]
+    # group 5: more Inf / NaN than k
+    b[g(5)][rng.choice(gs, size=k + 3, replace=False)] = 0xFF80
+    # group 6 stays plain random
+    return b
+
+
 def test_topk_selection_corner_cases():
-    """TOPK over groups of whole rows: the largest values share a lane, tie at the k-th place, sit in
-    a constant group, or come with Inf / NaN, next to groups where the k largest are clear-cut."""
+    """TOPK over groups of whole rows."""
     rng = np.random.default_rng(99)
     for gs in (512, 2048, 4096):
         for k in (1, 2, 4, 8, 9):
-            n_groups = 7
-            v = rng.normal(0.0, 1.0, size=gs * n_groups).astype(np.float32)
-            b = bits_of(torch.from_numpy(v).to(torch.bfloat16)).copy()
-            big = int(bits_of(torch.tensor([50.0], dtype=torch.bfloat16))[0])
-            g = lambda i: slice(i * gs, (i + 1) * gs)
-            # group 0: the k+1 largest next to each other (one lane holds most of them)
-            b[g(0)][8:8 + k + 1] = [big + i for i in range(k + 1)]
-            # group 1: k+2 equal maxima spread over the group, negative ones included
-            pos = np.sort(rng.choice(gs, size=k + 2, replace=False))
-            b[g(1)][pos] = big
-            b[g(1)][pos[::2]] |= 0x8000
-            # group 2: constant; group 3: all zero with one -0
-            b[g(2)] = 0x3F80
-            b[g(3)] = 0
-            b[g(3)][5] = 0x8000
-            # group 4: Inf, NaN and large values together
-            b[g(4)][[3, 200, 300, 301]] = [0x7F80, 0xFFC1, big, big + 1]
-            # group 5: more Inf / NaN than k
-            b[g(5)][rng.choice(gs, size=k + 3, replace=False)] = 0xFF80
-            # group 6 stays plain random
+            b = topk_corner_case_bits(gs, k, rng)
             for bits, gq, asym in ((4, 128, 0), (8, gs, 1)):
                 md = dict(bits=bits, quant_group=gq, asym=asym, outlier_mode="topk", stat_group=gs, thresh=0.0, topk=k)
                 log(f"[parity] topk corner cases gs={gs} k={k} bits={bits} gq={gq} asym={asym}")
                 run_parity(from_bits(b), md)
+
+
+def test_topk_selection_corner_cases_in_groups_inside_a_row():
+    """TOPK whose statistics group is the quantisation group and lies inside a 512-element row (the
+    row-at-a-time encoder): the same corner cases in groups of 32 .. 512, k up to 32."""
+    rng = np.random.default_rng(98)
+    for gs in (32, 128, 256, 512):
+        for k in (1, 2, 5, 8, 32):  # 32: the most the library takes; for groups of 32 the whole group
+            b = topk_corner_case_bits(gs, min(k, 9), rng)
+            for bits, asym in ((4, 0), (8, 1), (4, 1)):
+                md = dict(bits=bits, quant_group=gs, asym=asym, outlier_mode="topk", stat_group=gs, thresh=0.0, topk=k)
+                log(f"[parity] topk in rows gs={gs} k={k} bits={bits} asym={asym}")
+                run_parity(from_bits(b), md)
+                if k == 1:
+                    run_parity(from_bits(b).to(torch.float32).clamp(-6e4, 6e4).to(torch.float16), md)
 
 
 def test_every_element_an_outlier_and_overflow():
@@ -291,6 +312,13 @@ def test_batch_matches_single_calls_and_oracle():
     table.append(("softmax", 2048, workloads.C4_METHOD, workloads.c4("cpu", rows=2048)[:64].contiguous()))
     table.append(("small", 64, dict(bits=8, quant_group=64, asym=0, outlier_mode="std", stat_group=64, thresh=2.0, topk=0),
                   from_bits(random_bits(9, 64 * 5)).view(5, 64)))
+    # TOPK over the quantisation groups (the row-at-a-time encoder inside the batch kernel): a regular tensor,
+    # and one whose first group holds more values that are not finite than k (placed again from the source)
+    top1 = dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=128, thresh=0.0, topk=1)
+    table.append(("top1", 128, top1, from_bits(random_bits(10, 128 * 70, edge=False)).view(70, 128)))
+    irregular = random_bits(11, 128 * 50, edge=False)
+    irregular[[3, 40, 77]] = [0x7F80, 0xFF80, 0x7FC0]
+    table.append(("top1-irregular", 128, top1, from_bits(irregular).view(50, 128)))
     methods, srcs, blobs, layouts, ocs = [], [], [], [], []
     for tname, hidden, md, x in table:
         n = x.numel()
