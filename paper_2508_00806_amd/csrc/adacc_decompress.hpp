@@ -12,12 +12,14 @@ namespace ADACC_DT_NS {
 // blob: a piece of a 4096-element tile looks through the outliers of the whole tile and takes
 // those that fall inside it.
 //
-// A piece whose tile has up to 6 outliers takes them into the output words in registers before they are
-// stored.  With more, the outliers are written over the dequantised values in memory: the piece is stored
-// first, the wavefront waits until those stores have reached the L2 (its store counter at zero), and then
-// stores the outliers of the piece, 2 (or 4) bytes each, to their positions.  Both rounds of
+// A piece whose tile has up to 64 outliers, no two of them in the same octet, takes them into the output
+// words in registers before they are stored: the lanes that hold the entries of the stream drop them into a
+// mailbox of the wavefront in LDS (one word per octet of the piece, 1 KiB), every lane picks up the four
+// words of its own octets.  Otherwise the outliers are written over the dequantised values in memory: the
+// piece is stored first, the wavefront waits until those stores have reached the L2 (its store counter at
+// zero), and then stores the outliers of the piece, 2 (or 4) bytes each, to their positions.  Both rounds of
 // stores come from the same wavefront and the second is issued only after the first is complete,
-// so the outliers are what stays.  (Staging the piece in LDS to patch it there cost a round trip
+// so the outliers are what stays.  (Staging the whole piece in LDS to patch it there cost a round trip
 // through LDS for every piece of a TOPK tensor, a third of the kernel's time.)
 // One row (512 elements, 8 per lane) of a piece: codes and scale (offset) of the lane's octet.
 template <int BITS>
@@ -40,41 +42,30 @@ __device__ __forceinline__ void load_row_codes(const TensorDesc& d, uint64_t e0,
   if constexpr (ASYM) r.o = d.zp[g];
 }
 
-// The outliers of a piece that has only a few of them, applied to the output words of row `row` before they
-// are stored.  Lane i holds entry i of the tile's slice of the stream (o_idx, o_val); `n` entries, uniform.
-// Every entry is looked at through scalar registers: row, lane and element of its index are uniform, so the
-// row test is a scalar branch and the update one select per output word.  WORDS = 4 (two 16-bit values per
-// word) or 8 (binary32).
-constexpr uint32_t kRegisterPatchMax = 6;
+// What a lane finds in the mailbox for one of its octets: 0, or bit 31 set, the element (0..7) in bits 16..18
+// and the outlier's 16-bit pattern in the low half.  Applied to the output words of that row before they are
+// stored: WORDS = 4 (two 16-bit values per word) or 8 (binary32).
+constexpr uint32_t kMailFull = 0x80000000u;
 template <int WORDS>
-__device__ __forceinline__ void patch_row_words(uint32_t (&w)[WORDS], uint32_t row, uint64_t tile_base, uint32_t o_idx,
-                                                uint32_t o_val, uint32_t n) {
-  const uint32_t lane = (uint32_t)__lane_id();
-  const uint32_t base = (uint32_t)tile_base;  // a tensor that keeps outliers has fewer than 2^31 elements
-  for (uint32_t i = 0; i < n; ++i) {
-    const uint32_t rel = (uint32_t)__builtin_amdgcn_readlane((int)o_idx, (int)i) - base;
-    if ((rel >> 9) != row) continue;  // uniform; also what lies outside the piece (a 4096-element tile's other half)
-    const uint32_t pat = (uint32_t)__builtin_amdgcn_readlane((int)o_val, (int)i);
-    const bool mine = lane == ((rel >> 3) & 63u);
-    const uint32_t e = rel & 7u;
-    if constexpr (WORDS == 8) {
-      const uint32_t bits = __float_as_uint(widen_lo(pat));
+__device__ __forceinline__ void patch_row_words(uint32_t (&w)[WORDS], uint32_t mail) {
+  const bool mine = mail != 0u;
+  const uint32_t e = (mail >> 16) & 7u;
+  const uint32_t pat = mail & 0xFFFFu;
+  if constexpr (WORDS == 8) {
+    const uint32_t bits = __float_as_uint(widen_lo(pat));
 #pragma unroll
-      for (int k = 0; k < 8; ++k) w[k] = (mine && e == (uint32_t)k) ? bits : w[k];
-    } else {
-      const uint32_t keep = (e & 1u) ? 0x0000FFFFu : 0xFFFF0000u;
-      const uint32_t put = (e & 1u) ? pat << 16 : pat;
+    for (int k = 0; k < 8; ++k) w[k] = (mine && e == (uint32_t)k) ? bits : w[k];
+  } else {
+    const uint32_t keep = (e & 1u) ? 0x0000FFFFu : 0xFFFF0000u;
+    const uint32_t put = (e & 1u) ? pat << 16 : pat;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) w[k] = (mine && (e >> 1) == (uint32_t)k) ? ((w[k] & keep) | put) : w[k];
-    }
+    for (int k = 0; k < 4; ++k) w[k] = (mine && (e >> 1) == (uint32_t)k) ? ((w[k] & keep) | put) : w[k];
   }
 }
 
 // a9 for one row: unpack, dequantise, [patch a few outliers in,] store
 template <int BITS, bool ASYM, bool F32, bool PATCH = false>
-__device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e0, const RowCodes<BITS>& r, uint32_t row = 0u,
-                                                 uint64_t tile_base = 0u, uint32_t o_idx = 0u, uint32_t o_val = 0u,
-                                                 uint32_t n_patch = 0u) {
+__device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e0, const RowCodes<BITS>& r, uint32_t mail = 0u) {
   int c[kOct];
   if constexpr (BITS == 8) {
 #pragma unroll
@@ -93,7 +84,7 @@ __device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e
     uint32_t w[8];
 #pragma unroll
     for (int e = 0; e < kOct; ++e) w[e] = __float_as_uint(v[e]);
-    if constexpr (PATCH) patch_row_words<8>(w, row, tile_base, o_idx, o_val, n_patch);
+    if constexpr (PATCH) patch_row_words<8>(w, mail);
     float* p = reinterpret_cast<float*>(d.dst) + e0;
     ADACC_STORE16(p, make_uint4(w[0], w[1], w[2], w[3]));
     ADACC_STORE16(p + 4, make_uint4(w[4], w[5], w[6], w[7]));
@@ -101,13 +92,20 @@ __device__ __forceinline__ void store_row_values(const TensorDesc& d, uint64_t e
     uint32_t w[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) w[k] = narrow_pair(v[2 * k], v[2 * k + 1]);
-    if constexpr (PATCH) patch_row_words<4>(w, row, tile_base, o_idx, o_val, n_patch);
+    if constexpr (PATCH) patch_row_words<4>(w, mail);
     ADACC_STORE16(reinterpret_cast<uint16_t*>(d.dst) + e0, make_uint4(w[0], w[1], w[2], w[3]));
   }
 }
 
+// What the kernels that call decompress_tile keep in LDS: a mailbox of one word per octet of a piece for
+// every wavefront of the workgroup.
+struct DecompressShared {
+  uint32_t mailbox[kWavesPerWg][kWave][4];
+};
+
 template <int BITS, bool ASYM, int E, bool F32>
-__device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t tile /* piece */, bool has_outliers) {
+__device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t tile /* piece */, bool has_outliers,
+                                                DecompressShared& shared) {
   static_assert(E == 4, "pieces of 2048 elements");
   const int lane = (int)__lane_id();
   const uint64_t tile_base = (uint64_t)tile * (uint64_t)(E * kRow);
@@ -144,13 +142,28 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
     o_val = d.val[p0 + (uint32_t)lane];
   }
 
-  // ---- a9: unpack, dequantise, store.  A complete piece with only a few outliers (TOPK tensors: every piece)
-  // takes them in on the way, in registers: nothing is written twice and nothing waits for a store.
-  if (complete && patch && p1 - p0 <= kRegisterPatchMax) {
+  // ---- a9: unpack, dequantise, store.  A complete piece whose tile has at most 64 outliers (TOPK tensors:
+  // every piece), no two in one octet, takes them in on the way, in registers: nothing is written twice and
+  // nothing waits for a store.  The stream is ascending, so two entries of one octet are neighbours in it.
+  if (complete && patch && p1 - p0 <= (uint32_t)kWave) {
+    const uint32_t rel = o_idx - (uint32_t)tile_base;  // a tensor that keeps outliers has fewer than 2^31 elements
+    const bool valid = (uint32_t)lane < p1 - p0 && rel < (uint32_t)(E * kRow);  // also: not in a 4096-element tile's other half
+    const uint32_t oct = rel >> 3;
+    const uint32_t prev_oct = (uint32_t)__shfl_up((int)oct, 1, kWave);
+    if (__builtin_amdgcn_ballot_w64(valid && lane != 0 && oct == prev_oct) == 0ull) {  // uniform
+      uint32_t(*box)[E] = shared.mailbox[threadIdx.x / kWave];
+      *reinterpret_cast<uint4*>(box[lane]) = make_uint4(0u, 0u, 0u, 0u);
+      __builtin_amdgcn_wave_barrier();  // LDS takes a wavefront's accesses in order: nothing may be moved across
+      if (valid) box[oct & 63u][oct >> 6] = kMailFull | ((rel & 7u) << 16) | (o_val & 0xFFFFu);
+      __builtin_amdgcn_wave_barrier();
+      const uint4 mail = *reinterpret_cast<const uint4*>(box[lane]);
+      __builtin_amdgcn_wave_barrier();  // the next piece of this wavefront clears the mailbox only after this
+      const uint32_t m[E] = {mail.x, mail.y, mail.z, mail.w};
 #pragma unroll
-    for (int j = 0; j < E; ++j)
-      store_row_values<BITS, ASYM, F32, true>(d, lane_base + (uint64_t)j * kRow, rc[j], (uint32_t)j, tile_base, o_idx, o_val, p1 - p0);
-    return;
+      for (int j = 0; j < E; ++j)
+        store_row_values<BITS, ASYM, F32, true>(d, lane_base + (uint64_t)j * kRow, rc[j], m[j]);
+      return;
+    }
   }
   if (complete) {
 #pragma unroll

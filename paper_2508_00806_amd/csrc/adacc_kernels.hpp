@@ -40,8 +40,9 @@ __device__ __forceinline__ bool topk_whole(const TensorDesc& d) { return d.lgs =
 template <int BITS, bool ASYM, bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(TensorDesc d, uint32_t has_outliers) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
+  __shared__ __attribute__((aligned(16))) DecompressShared shared;
   for (uint32_t t = blockIdx.x * kWavesPerWg + wave; t < d.n_tiles; t += gridDim.x * kWavesPerWg)
-    decompress_tile<BITS, ASYM, 4, F32>(d, t, has_outliers != 0u);
+    decompress_tile<BITS, ASYM, 4, F32>(d, t, has_outliers != 0u, shared);
 }
 
 // ---- batch
@@ -111,11 +112,12 @@ __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const Tensor
   const uint32_t piece = blockIdx.x * kWavesPerWg + wave;
   if (piece >= d.n_tiles) return;
   const bool ho = (d.variant >> 3) != kModeNone;
+  __shared__ __attribute__((aligned(16))) DecompressShared shared;
   switch (d.variant & 6u) {
-    case 0: decompress_tile<4, false, 4, F32>(d, piece, ho); break;
-    case 2: decompress_tile<4, true, 4, F32>(d, piece, ho); break;
-    case 4: decompress_tile<8, false, 4, F32>(d, piece, ho); break;
-    default: decompress_tile<8, true, 4, F32>(d, piece, ho); break;
+    case 0: decompress_tile<4, false, 4, F32>(d, piece, ho, shared); break;
+    case 2: decompress_tile<4, true, 4, F32>(d, piece, ho, shared); break;
+    case 4: decompress_tile<8, false, 4, F32>(d, piece, ho, shared); break;
+    default: decompress_tile<8, true, 4, F32>(d, piece, ho, shared); break;
   }
 }
 
