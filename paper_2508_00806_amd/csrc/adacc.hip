@@ -596,9 +596,11 @@ int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, 
 static int launch_generic_compress(const adacc_method* method, const Plan& p, const TensorDesc& d, uint32_t epoch,
                                    hipStream_t s) {
   int rc = ADACC_OK;
-  const uint32_t lds = 4u * kWave + 3u * p.tile_elems;  // lane counts, 16-bit patterns, a byte per element
+  const uint32_t lds = ADACC_PICK(p.half, generic_lds_bytes(p.tile_elems));  // 16-bit patterns and a byte per element
+  const uint32_t threads = ADACC_PICK(p.half, generic_threads());
+  const bool topk = method->outlier_mode == ADACC_OUTLIER_TOPK;
   if (p.outliers) {
-    hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(true)), dim3(p.n_tiles), dim3(kWave), lds, s, d);
+    hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(true, topk)), dim3(p.n_tiles), dim3(threads), lds, s, d);
     rc = launch_check("compress_generic_kernel (count)");
     if (rc != ADACC_OK) return rc;
     if (needs_block_sums(method, p)) {
@@ -610,7 +612,7 @@ static int launch_generic_compress(const adacc_method* method, const Plan& p, co
     rc = launch_check("place_kernel");
     if (rc != ADACC_OK) return rc;
   }
-  hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(false)), dim3(p.n_tiles), dim3(kWave), lds, s, d);
+  hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(false, topk)), dim3(p.n_tiles), dim3(threads), lds, s, d);
   return launch_check("compress_generic_kernel");
 }
 
@@ -733,7 +735,7 @@ int adacc_decompress(const adacc_method* method, const void* blob, uint64_t blob
   fill_desc(method, numel, p, L, nullptr, const_cast<void*>(blob), dst, dst_dtype, nullptr, &d);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (p.generic) {
-    hipLaunchKernelGGL(ADACC_PICK(p.half, decompress_generic_fn()), dim3(p.n_tiles), dim3(kWave), 0, s, d);
+    hipLaunchKernelGGL(ADACC_PICK(p.half, decompress_generic_fn()), dim3(p.n_tiles), dim3(ADACC_PICK(p.half, generic_threads())), 0, s, d);
     return launch_check("decompress_generic_kernel");
   }
   DecompressFn fn = ADACC_PICK(p.half, decompress_fn(method->bits, method->asym, dst_dtype == ADACC_DST_F32));
@@ -933,8 +935,8 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
                        dm + g.first_member);
   for (uint32_t i = 0; i < nt; ++i)
     if (descs[i].generic)
-      hipLaunchKernelGGL(ADACC_PICK(plans[origin[i]].half, decompress_generic_fn()), dim3(descs[i].n_tiles), dim3(kWave), 0,
-                         s, descs[i]);
+      hipLaunchKernelGGL(ADACC_PICK(plans[origin[i]].half, decompress_generic_fn()), dim3(descs[i].n_tiles),
+                         dim3(ADACC_PICK(plans[origin[i]].half, generic_threads())), 0, s, descs[i]);
   return launch_check("decompress_batch_kernel");
 }
 

@@ -1,7 +1,7 @@
 """GPU parity for group sizes outside the fast kernels' shapes (Section 3.2 groups the flat activation;
 nothing makes the groups powers of two): quantisation groups of any multiple of 8, statistics groups of any
 multiple of those up to 16384 - a whole 11008-wide row as one STD / TOPK group.  These run in fallback
-kernels (a wavefront per segment, plain loops over LDS); the bar is the same as everywhere: every section
+kernels (a workgroup per segment, plain loops over LDS); the bar is the same as everywhere: every section
 of the blob and both reconstructions against the oracle, bit for bit."""
 import numpy as np
 import pytest
