@@ -338,12 +338,26 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, SegmentSha
     }
   }
   __syncthreads();
+  // the codes leave an octet at a time (8 resp. 4 bytes; the segment starts on a multiple of 8 elements), what
+  // is left of a tensor's ragged end one by one
+  const uint32_t octs = cnt / (uint32_t)kOct;
   if constexpr (Q == 128) {
     uint8_t* out = d.codes + first_elem;
-    for (uint32_t i = tid; i < cnt; i += kSegThreads) out[i] = sh.byte[i];
+    for (uint32_t o = tid; o < octs; o += kSegThreads)
+      *reinterpret_cast<uint2*>(out + o * kOct) = *reinterpret_cast<const uint2*>(sh.byte + o * kOct);
+    for (uint32_t i = octs * kOct + tid; i < cnt; i += kSegThreads) out[i] = sh.byte[i];
   } else {
     uint8_t* out = d.codes + (first_elem >> 1);
-    for (uint32_t b = tid; b < (cnt + 1u) / 2u; b += kSegThreads) {
+    for (uint32_t o = tid; o < octs; o += kSegThreads) {
+      const uint2 c = *reinterpret_cast<const uint2*>(sh.byte + o * kOct);
+      const uint32_t e = (c.x & 0x0F0F0F0Fu) | ((c.x >> 4) & 0x00F000F0u);   // bytes 0 and 2: the nibble pairs of elements 0..3
+      const uint32_t f = (c.y & 0x0F0F0F0Fu) | ((c.y >> 4) & 0x00F000F0u);
+      // pair (2j, 2j+1) -> one byte: low nibble the even element
+      const uint32_t lo = (e & 0xFFu) | ((e >> 8) & 0xFF00u);
+      const uint32_t hi = (f & 0xFFu) | ((f >> 8) & 0xFF00u);
+      *reinterpret_cast<uint32_t*>(out + o * 4u) = lo | (hi << 16);
+    }
+    for (uint32_t b = octs * 4u + tid; b < (cnt + 1u) / 2u; b += kSegThreads) {
       const uint32_t lo = sh.byte[2u * b] & 0xFu;
       const uint32_t hi = 2u * b + 1u < cnt ? (sh.byte[2u * b + 1u] & 0xFu) : 0u;  // an odd end: the high nibble is 0
       out[b] = (uint8_t)(lo | (hi << 4));
@@ -404,7 +418,40 @@ __device__ __forceinline__ void decompress_segment(const TensorDesc& d, uint32_t
   const uint64_t left = d.numel - first_elem;
   const uint32_t cnt = left < (uint64_t)d.tile_elems ? (uint32_t)left : d.tile_elems;
   const uint64_t first_group = first_elem / d.gq;
-  for (uint32_t i = tid; i < cnt; i += kSegThreads) {
+  // an octet at a time: it lies inside one quantisation group (groups are multiples of 8, the segment starts
+  // on a group), so one scale serves it; what is left of a tensor's ragged end goes one by one
+  const uint32_t octs = cnt / (uint32_t)kOct;
+  for (uint32_t o = tid; o < octs; o += kSegThreads) {
+    const uint64_t e0 = first_elem + (uint64_t)o * kOct;
+    int code[kOct];
+    if (d.bits == 8u) {
+      const uint2 w = *reinterpret_cast<const uint2*>(d.codes + e0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        code[e] = (int)(int8_t)((w.x >> (8 * e)) & 0xFFu);
+        code[4 + e] = (int)(int8_t)((w.y >> (8 * e)) & 0xFFu);
+      }
+    } else {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(d.codes + (e0 >> 1));
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) code[e] = ((int)(w << (28 - 4 * e))) >> 28;  // sign-extended nibble
+    }
+    const uint64_t grp = first_group + (o * (uint32_t)kOct) / d.gq;
+    const float s = d.scales[grp];
+    const float z = d.asym ? d.zp[grp] : 0.0f;
+    float v[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) v[e] = d.asym ? __fmaf_rn((float)code[e], s, z) : (float)code[e] * s;
+    if (d.dst_f32) {
+      float* p = reinterpret_cast<float*>(d.dst) + e0;
+      *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(d.dst) + e0) =
+          make_uint4(narrow_pair(v[0], v[1]), narrow_pair(v[2], v[3]), narrow_pair(v[4], v[5]), narrow_pair(v[6], v[7]));
+    }
+  }
+  for (uint32_t i = octs * kOct + tid; i < cnt; i += kSegThreads) {
     int code;
     if (d.bits == 8u) code = (int)(int8_t)d.codes[first_elem + i];
     else code = ((int)((uint32_t)d.codes[(first_elem + i) >> 1] << (28u - 4u * (i & 1u)))) >> 28;  // first_elem is even
