@@ -217,6 +217,45 @@ def test_dense_outliers_overflow_the_slots():
         assert oc.n_out > n // 25
 
 
+def test_decompression_with_few_many_and_crowded_outliers_per_tile():
+    """The decompression takes up to 64 outliers of a tile, no two in one octet, into the output in registers
+    and writes them over the stored piece otherwise: tiles with 1, 63, 64 and 65 outliers in octets of their
+    own, with two and with eight in one octet, and tiles of 4096 elements whose outliers lie in one half, in
+    both halves (fewer and more than 64 together)."""
+    rng = np.random.default_rng(4242)
+    small = bits_of(torch.from_numpy(rng.uniform(-0.5, 0.5, size=2048 * 8).astype(np.float32)).to(torch.bfloat16)).copy()
+    big = int(bits_of(torch.tensor([8.0], dtype=torch.bfloat16))[0])
+
+    def plant(b, tile, tile_elems, positions):
+        for j, p in enumerate(positions):
+            b[tile * tile_elems + p] = (big + j % 5) | (0x8000 if j % 3 == 0 else 0)
+
+    b = small.copy()
+    octets = rng.permutation(256)
+    plant(b, 0, 2048, [int(o) * 8 + int(rng.integers(8)) for o in octets[:1]])
+    plant(b, 1, 2048, [int(o) * 8 + int(rng.integers(8)) for o in octets[:63]])
+    plant(b, 2, 2048, [int(o) * 8 + int(rng.integers(8)) for o in octets[:64]])
+    plant(b, 3, 2048, [int(o) * 8 + int(rng.integers(8)) for o in octets[:65]])
+    plant(b, 4, 2048, [800, 803, 17])                 # two in one octet
+    plant(b, 5, 2048, list(range(1024, 1032)) + [5])  # a whole octet
+    plant(b, 7, 2048, [2047])                         # tile 6 has none
+    for bits, gq, asym in ((4, 128, 0), (8, 64, 1)):
+        md = dict(bits=bits, quant_group=gq, asym=asym, outlier_mode="abs", stat_group=0, thresh=4.0, topk=0)
+        log(f"[parity] outliers per tile bits={bits}")
+        oc, _, _, _ = run_parity(from_bits(b), md)
+        assert oc.n_out == 1 + 63 + 64 + 65 + 3 + 9 + 1
+    # tiles of 4096 elements (statistics over 4096), decompressed in halves
+    b = np.tile(small, 2)[:4096 * 4].copy()
+    plant(b, 0, 4096, [int(o) * 8 for o in octets[:20]])                                      # first half only
+    plant(b, 1, 4096, [int(o) * 8 for o in octets[:30]] + [2048 + int(o) * 8 for o in octets[:30]])  # 60: both halves in registers
+    plant(b, 2, 4096, [int(o) * 8 for o in octets[:40]] + [2048 + int(o) * 8 for o in octets[:40]])  # 80: both halves through memory
+    plant(b, 3, 4096, [4095])
+    md = dict(bits=4, quant_group=128, asym=0, outlier_mode="std", stat_group=4096, thresh=3.0, topk=0)
+    log("[parity] outliers per 4096-tile")
+    oc, _, _, _ = run_parity(from_bits(b), md)
+    assert oc.n_out == 20 + 60 + 80 + 1
+
+
 @pytest.mark.parametrize("gs,k,gq,bits", [(2048, 2, 128, 4), (4096, 4, 128, 4), (64, 1, 64, 8), (4096, 3, 4096, 8)])
 def test_topk_groups_with_more_values_that_are_not_finite_than_k(gs, k, gq, bits):
     """TOPK places its outliers at offsets known in advance (k per group).  A group that holds more
