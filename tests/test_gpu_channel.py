@@ -68,6 +68,19 @@ def test_strips_with_a_short_last_block_of_tokens(tokens):
     run_channel_parity(x.to(torch.float32).clamp(-6e4, 6e4).to(torch.float16), 4, 128, 0)
 
 
+def test_widest_and_narrowest_matrices():
+    """hidden = 65536 (the most the mode takes: 8 mask bytes per thread of the selection, 128 strips) with a
+    short block of tokens, and hidden = 8 (one octet, one live lane in the statistics pass)."""
+    log("[channel] hidden=65536 tokens=9")
+    x = planted(9, 65536, [0, 7, 8, 32767, 40000, 65535], seed=31)
+    oc, _ = run_channel_parity(x, 4, 512, 0)
+    assert [int(i) for i in oc.ch_idx] == [0, 7, 8, 32767, 40000, 65535]
+    log("[channel] hidden=8 tokens=100")
+    x = planted(100, 8, [5], seed=32, gain=400.0)
+    oc, _ = run_channel_parity(x, 8, 8, 1, z=2.0)
+    assert [int(i) for i in oc.ch_idx] == [5]
+
+
 def test_groups_of_a_whole_tile_and_the_other_scale_rule():
     log("[channel] hidden=4096 gq=2048")
     x = planted(70, 4096, [9, 10, 11, 12, 13, 14, 15, 16, 4000], seed=23)
