@@ -264,16 +264,16 @@ static WsPlan ws_plan(const adacc_method* m, const Plan& p) {
   uint64_t off = 0;
   w.cnt_off = off;  off = align256(off + 4ull * p.n_tiles);
   w.flag_off = off; off += 256;
-  if (m->outlier_mode != ADACC_OUTLIER_TOPK || p.generic) {
+  if (m->outlier_mode != ADACC_OUTLIER_TOPK) {
     w.block_sum_off = off; off = align256(off + 4ull * place_blocks(p));
-    if (!p.generic) { w.slot_off = off; off = align256(off + 8ull * kSlot * p.n_tiles); }
+    w.slot_off = off; off = align256(off + 8ull * kSlot * p.n_tiles);
   }
   w.bytes = off;
   return w;
 }
 // does the placement of this tensor start from per-block sums (a kernel of its own computes them)?
 static bool needs_block_sums(const adacc_method* m, const Plan& p) {
-  return p.outliers && (m->outlier_mode != ADACC_OUTLIER_TOPK || p.generic) && place_blocks(p) > kPlaceDirectBlocks;
+  return p.outliers && m->outlier_mode != ADACC_OUTLIER_TOPK && place_blocks(p) > kPlaceDirectBlocks;
 }
 
 static void fill_desc(const adacc_method* m, uint64_t numel, const Plan& p, const adacc_layout& L, const void* src,
@@ -596,24 +596,24 @@ int adacc_workspace_init(adacc_workspace* ws, void* device_mem, uint64_t bytes, 
 static int launch_generic_compress(const adacc_method* method, const Plan& p, const TensorDesc& d, uint32_t epoch,
                                    hipStream_t s) {
   int rc = ADACC_OK;
-  const uint32_t lds = ADACC_PICK(p.half, generic_lds_bytes(p.tile_elems));  // 16-bit patterns and a byte per element
-  const uint32_t threads = ADACC_PICK(p.half, generic_threads());
   const bool topk = method->outlier_mode == ADACC_OUTLIER_TOPK;
-  if (p.outliers) {
-    hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(true, topk)), dim3(p.n_tiles), dim3(threads), lds, s, d);
-    rc = launch_check("compress_generic_kernel (count)");
-    if (rc != ADACC_OK) return rc;
-    if (needs_block_sums(method, p)) {
-      hipLaunchKernelGGL(ADACC_PICK(p.half, place_sum_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
-      rc = launch_check("place_sum_kernel");
-      if (rc != ADACC_OK) return rc;
-    }
-    hipLaunchKernelGGL(ADACC_PICK(p.half, place_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
-    rc = launch_check("place_kernel");
+  const uint32_t lds = ADACC_PICK(p.half, generic_lds_bytes(p.tile_elems, method->quant_group, topk && d.gs < p.tile_elems));
+  const uint32_t threads = ADACC_PICK(p.half, generic_threads());
+  hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(p.tile_elems, false)), dim3(p.n_tiles), dim3(threads), lds, s, d, epoch);
+  rc = launch_check("compress_generic_kernel");
+  if (rc != ADACC_OK || !p.outliers) return rc;
+  if (needs_block_sums(method, p)) {
+    hipLaunchKernelGGL(ADACC_PICK(p.half, place_sum_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d);
+    rc = launch_check("place_sum_kernel");
     if (rc != ADACC_OK) return rc;
   }
-  hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(false, topk)), dim3(p.n_tiles), dim3(threads), lds, s, d);
-  return launch_check("compress_generic_kernel");
+  hipLaunchKernelGGL(ADACC_PICK(p.half, place_fn()), dim3(d.n_blocks), dim3(kPlaceThreads), 0, s, d, epoch);
+  rc = launch_check("place_kernel");
+  if (rc != ADACC_OK) return rc;
+  // segments whose outliers the first launch could not place (more than a slot holds; TOPK: some group with
+  // another count than k): every other workgroup of this launch leaves at once
+  hipLaunchKernelGGL(ADACC_PICK(p.half, compress_generic_fn(p.tile_elems, true)), dim3(p.n_tiles), dim3(threads), lds, s, d, epoch);
+  return launch_check("compress_generic_kernel (outliers again)");
 }
 
 static int compress_one(const adacc_method* method, const void* src, uint64_t numel, void* blob, uint64_t blob_bytes,

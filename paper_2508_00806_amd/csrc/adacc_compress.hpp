@@ -1472,16 +1472,17 @@ __device__ __forceinline__ uint32_t place_offsets_block(const TensorDesc& d, uin
   return base;
 }
 
-template <int MODE, int E, bool ROWWISE, bool WHOLE>
-__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool from_sums, bool reselect_all,
-                                            PlaceShared& sh) {
+// The offsets of a block's tiles, and the outliers of its tiles from the slots to the stream: four positions per
+// thread at a time, so that their loads overlap.  Tiles with more outliers than a slot takes are left out.
+// Returns the number of outliers before the block; n_here: tiles of the block.  `move`: false = offsets only
+__device__ __forceinline__ uint32_t place_moves_block(const TensorDesc& d, uint32_t block, bool from_sums, bool move,
+                                                      PlaceShared& sh, uint32_t& n_here) {
   const uint32_t tid = threadIdx.x;
   const uint32_t first = block * (uint32_t)kPlaceTiles;
-  uint32_t n_here, total;
+  uint32_t total;
   const uint32_t base = place_offsets_block(d, block, from_sums, sh, n_here, total);
   __syncthreads();
-  // from the slots to the stream: four positions per thread at a time, so that their loads overlap
-  if (!reselect_all) {
+  if (move) {
     for (uint32_t p0 = 0u; p0 < total; p0 += 4u * (uint32_t)kPlaceThreads) {
       uint64_t src[4];
       uint32_t dst[4];
@@ -1508,6 +1509,16 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
       }
     }
   }
+  return base;
+}
+
+template <int MODE, int E, bool ROWWISE, bool WHOLE>
+__device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block, bool from_sums, bool reselect_all,
+                                            PlaceShared& sh) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t first = block * (uint32_t)kPlaceTiles;
+  uint32_t n_here;
+  const uint32_t base = place_moves_block(d, block, from_sums, !reselect_all, sh, n_here);
   // tiles whose outliers are not (all) in a slot: once more from the source, a wavefront per tile
   const uint32_t w = __builtin_amdgcn_readfirstlane(tid / kWave);
   for (uint32_t j = w; j < n_here; j += (uint32_t)(kPlaceThreads / kWave)) {

@@ -30,7 +30,8 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
 //   e8: tiles of 8 rows; rowwise: every group inside a row; whole (TOPK): the statistics group is the tile;
 //   rows (TOPK): statistics group = quantisation group, inside a row
 //   kind: kBatch* of adacc_common.hpp
-//   generic_threads, generic_lds_bytes: workgroup size and dynamic LDS of the fallback kernels (one segment per workgroup)
+//   generic_threads, generic_lds_bytes: workgroup size and dynamic LDS of the fallback kernels (one segment per workgroup;
+//     topk_groups: TOPK over several statistics groups of a segment); compress_generic_fn(fixup): the second launch
 //   stream: the statistics pass reads with the streaming hint (tensors beyond kStatsKeepBytes)
 //   channel_score_channels: channels per workgroup of the score kernel
 //   channel_select_threads: size of the one workgroup of the select kernel
@@ -56,10 +57,10 @@ typedef void (*ChannelwiseFn)(ChannelwiseDesc);
   TailBatchFn compress_tail_batch_fn();                                                \
   TailFn decompress_tail_fn();                                                         \
   TailBatchFn decompress_tail_batch_fn();                                              \
-  TailFn compress_generic_fn(bool count_only, bool topk);                              \
+  CompressFn compress_generic_fn(uint32_t tile_elems, bool fixup);                     \
   TailFn decompress_generic_fn();                                                      \
   uint32_t generic_threads();                                                          \
-  uint32_t generic_lds_bytes(uint32_t tile_elems);                                     \
+  uint32_t generic_lds_bytes(uint32_t tile_elems, uint32_t gq, bool topk_groups);      \
   ChannelPartialFn channel_partial_fn(bool stream);                                    \
   ChannelScoreFn channel_score_fn();                                                   \
   ChannelSelectFn channel_select_fn();                                                 \

@@ -5,17 +5,23 @@
 // kernels reduce over power-of-two numbers of lanes inside one wavefront's tile and cannot take these.
 //
 // Here a workgroup of four wavefronts takes a "segment": as many whole statistics groups as fit 4096
-// elements (one group, if it is larger), held in LDS as 16-bit patterns, and works through it with plain
-// loops - by the same definitions as everywhere: canonical pairwise sums (pad to a power of two, add
-// neighbours level by level), mean and variance over the group's own count, the k largest by (magnitude,
-// lower index), D / max by one IEEE division per group, the same rounding of the codes.  A segment that is
-// one statistics group is worked on by the whole workgroup; in a segment of several groups every wavefront
-// takes groups of its own.  It is a fallback, several times slower than the tile kernels, not a hot path.
+// elements (one group, if it is larger).  Thread t holds the octets t, t + 256, t + 512, .. of the segment in
+// registers (one 16-byte load each, a wavefront's load is 1 KiB of consecutive memory); what the groups need
+// from all their octets - the pairwise sums of the STD rule, the largest magnitude or the extremes of a
+// quantisation group - goes through one word per octet in LDS and is reduced there by as many adjacent lanes
+// as the group has octets (rounded up to a power of two; a wavefront per group beyond 64 octets).  The
+// definitions are those of the fast kernels: canonical pairwise sums (pad to a power of two, add neighbours
+// level by level), mean and variance over the group's own count, the k largest by (magnitude, lower index),
+// D / max by one IEEE division per group, the same rounding of the codes.
 //
-// With outliers a compression is two launches of the same kernel around the placement kernels: the first
-// only counts the outliers of every segment (cnt[segment]), the placement kernels turn the counts into
-// offsets (tile_ptr, the total, the overflow flag), the second writes the outliers at their offsets and
-// everything else.  The segment is the blob's tile (adacc_layout.tile_elems).
+// Outliers take the ways of the tile kernels.  ABS / STD: a segment's outliers go to its slot of kSlot
+// records in the workspace and its count to cnt[]; the placement kernels turn the counts into offsets and move
+// the slots' records to the stream; a segment with more outliers than a slot holds is selected once more, by a
+// second launch of this kernel (FIXUP) in which every other workgroup leaves at once.  TOPK: the offsets are
+// known in advance (k per group), the outliers go straight to the stream, and a segment that finds another
+// count (values that are not finite) raises the tensor's flag; only then do the placement kernel and the
+// second launch anything: offsets from the counts, and every segment's outliers written again.
+// The segment is the blob's tile (adacc_layout.tile_elems).
 #pragma once
 
 #include "adacc_common.hpp"
@@ -27,388 +33,607 @@ namespace ADACC_DT_NS {
 
 constexpr uint32_t kSegThreads = (uint32_t)kThreads;
 constexpr uint32_t kSegWaves = kSegThreads / (uint32_t)kWave;
+constexpr int kSegOctsMax = 8;  // octets per thread at most: 16384 elements / 8 / 256 threads
+// (the kernels exist for 2, 4, 6 and 8 octets per thread - SL - so that short segments do not pay for the registers of long ones)
 // bytes of LDS before the segment's arrays: the words the wavefronts meet in
-constexpr uint32_t kSegHeadBytes = 4u * 16u;
+constexpr uint32_t kSegHeadWords = 48u;
+constexpr uint32_t kSegHeadBytes = 4u * kSegHeadWords;
 
-// The LDS of a workgroup, sized by the host for the method's segment length:
-// [meet: 16 words][raw: tile_elems 16-bit patterns][byte: tile_elems bytes]
+// The LDS of a workgroup, sized by the host for the method's segment length (n_oct octets, n_grp quantisation groups):
+// [head: 48 words][a: n_oct words][b: n_oct words][g0: n_grp words][g1: n_grp words]
+//   head[0..7]   the wavefronts' maxima of a TOPK round (two sets of four, used in turn)
+//   head[8..39]  outliers of every (octet slice, wavefront)
+//   head[40..47] the wavefronts' results of a group that the whole workgroup reduces (two sets of four, used in turn)
+//   a, b         one word per octet: sums / sums of squares (STD), largest magnitude or extreme keys (quantisation)
+//   g0, g1       one word per group: the STD limit of a statistics group; D / max and the offset of a quantisation group
+// TOPK over several groups of a segment keeps the segment's 16-bit patterns (16 bytes per octet, from a on) and
+// behind them a byte per element instead, before a .. g1 are used (generic_lds_bytes gives the larger size).
 struct SegmentShared {
-  uint32_t* meet;
-  uint16_t* raw;   // the patterns of the segment; an element that is kept aside or not finite is set to zero
-  uint8_t* byte;   // first: 1 = outlier; later: the element's code
+  uint32_t* head;
+  uint32_t* a;
+  uint32_t* b;
+  uint32_t* g0;
+  uint32_t* g1;
+  uint8_t* byte;  // TOPK over several groups: 1 = among the k largest
 };
-__device__ __forceinline__ SegmentShared segment_shared(unsigned char* lds, uint32_t tile_elems) {
+__device__ __forceinline__ uint32_t segment_octets(uint32_t tile_elems) { return (tile_elems + 7u) / 8u; }
+__device__ __forceinline__ SegmentShared segment_shared(unsigned char* lds, uint32_t tile_elems, uint32_t gq) {
+  const uint32_t n_oct = segment_octets(tile_elems);
+  const uint32_t n_grp = (tile_elems + gq - 1u) / gq;
   SegmentShared sh;
-  sh.meet = reinterpret_cast<uint32_t*>(lds);
-  sh.raw = reinterpret_cast<uint16_t*>(lds + kSegHeadBytes);
-  sh.byte = lds + kSegHeadBytes + 2u * tile_elems;
+  sh.head = reinterpret_cast<uint32_t*>(lds);
+  sh.a = sh.head + kSegHeadWords;
+  sh.b = sh.a + n_oct;
+  sh.g0 = sh.b + n_oct;
+  sh.g1 = sh.g0 + n_grp;
+  sh.byte = reinterpret_cast<uint8_t*>(sh.a) + 16u * n_oct;
   return sh;
 }
 
 __device__ __forceinline__ bool pattern_nonfinite(uint32_t pattern) { return (pattern & 0x7FFFu) >= kNonfiniteMag; }
 
-// Who works on a group: the whole workgroup (WG) or one wavefront.  size / id: the members and this
-// thread's number among them; sync: all members have finished their LDS accesses (a wavefront's own
-// accesses are taken in order, so for a wavefront nothing is waited for); max_u32 / tree_sum: over all
-// members, the result in every member.  tree_sum adds in the order of the balanced tree over the members.
-template <bool WG>
-struct Team {
-  uint32_t* meet;  // WG: LDS words where the wavefronts meet
-  __device__ __forceinline__ static uint32_t size() { return WG ? kSegThreads : (uint32_t)kWave; }
-  __device__ __forceinline__ static uint32_t id() { return WG ? threadIdx.x : (uint32_t)lane_id(); }
-  __device__ __forceinline__ static void sync() {
-    if constexpr (WG) __syncthreads();
-    else __builtin_amdgcn_wave_barrier();
-  }
-  __device__ __forceinline__ uint32_t max_u32(uint32_t v) const {
-    v = wave_max_u32_scalar(v);
-    if constexpr (WG) {
-      __syncthreads();  // the previous use of meet is over
-      if (lane_id() == 0) meet[threadIdx.x / kWave] = v;
-      __syncthreads();
-      v = meet[0];
-#pragma unroll
-      for (uint32_t w = 1; w < kSegWaves; ++w) v = meet[w] > v ? meet[w] : v;
-    }
-    return v;
-  }
-  __device__ __forceinline__ float tree_sum(float v) const {
-    v = lanes_reduce<kWave>(v, OpAdd());
-    if constexpr (WG) {
-      static_assert(kSegWaves == 4, "the wavefronts' sums are added as a tree of four");
-      __syncthreads();
-      if (lane_id() == 0) meet[threadIdx.x / kWave] = __float_as_uint(v);
-      __syncthreads();
-      v = (__uint_as_float(meet[0]) + __uint_as_float(meet[1])) + (__uint_as_float(meet[2]) + __uint_as_float(meet[3]));
-    }
-    return v;
-  }
+// What a thread knows of the segment and of its own octets
+struct SegmentGeo {
+  uint64_t first_elem;  // tensor index of the segment's first element (a multiple of 8)
+  uint32_t cnt;         // elements of the segment (the tensor's last one may be short)
+  uint32_t octs;        // octets that hold any of them
 };
+// octet o = tid + 256 * j is the thread's octet j
 
-// Canonical pairwise sums over the team of raw[i] and of raw[i]^2, i < cnt: the leaves are padded with zeros
-// to a power of two p, member t owns the p / size leaves from t * (p / size) on (one leaf for p <= size) and
-// adds them as a binary tree by carries (partial sums of 1, 2, 4, .. units wait in s[]), the members' sums then
-// meet as a tree: together the balanced tree over the padded array.  A member with 8 leaves or more takes
-// them an octet at a time (one 16-byte read; the tree over the 8 written out) and carries the octets' sums.
-__device__ __forceinline__ void carry_in(float (&s)[7], uint32_t i, float v) {
+// o / opg for octets o < 2048 and 1 <= opg <= 2048 without the division sequence: `r` is 1 / opg moved up by three
+// units in the last place, so that the binary32 product lies at or above the quotient where the quotient is an
+// integer, and (the excess is below o * 2^-21 / opg < 1 / opg) below the next integer everywhere else.
+__device__ __forceinline__ float group_reciprocal(uint32_t opg) {
+  return __uint_as_float(__float_as_uint(__frcp_rn((float)opg)) + 3u);
+}
+__device__ __forceinline__ uint32_t group_of(uint32_t o, float r) { return (uint32_t)((float)o * r); }
+__device__ __forceinline__ uint32_t octet_valid(const SegmentGeo& g, uint32_t o) {  // elements of octet o that exist
+  const uint32_t first = o * (uint32_t)kOct;
+  return first >= g.cnt ? 0u : (g.cnt - first < (uint32_t)kOct ? g.cnt - first : (uint32_t)kOct);
+}
+
+// reduce over LANES = 2^lg adjacent lanes, lg a run-time (uniform) value
+template <class T, class Op>
+__device__ __forceinline__ T lanes_reduce_lg(T v, uint32_t lg, Op op) {
+  switch (lg) {
+    case 0: break;
+    case 1: v = lanes_reduce<2>(v, op); break;
+    case 2: v = lanes_reduce<4>(v, op); break;
+    case 3: v = lanes_reduce<8>(v, op); break;
+    case 4: v = lanes_reduce<16>(v, op); break;
+    case 5: v = lanes_reduce<32>(v, op); break;
+    default: v = lanes_reduce<64>(v, op); break;
+  }
+  return v;
+}
+
+// Binary tree over values that arrive one by one: partial sums of 1, 2, 4, .. values wait in s[]; after 2^m
+// values the result sits in s[m].
+template <class T, class Op>
+__device__ __forceinline__ void carry_in(T (&s)[4], uint32_t i, T v, Op op) {
   bool placed = false;
 #pragma unroll
-  for (int l = 0; l < 6; ++l) {
+  for (int l = 0; l < 3; ++l) {
     if (!placed) {
-      if ((i >> l) & 1u) v = s[l] + v;  // the earlier units on the left
+      if ((i >> l) & 1u) v = op(s[l], v);  // the earlier values on the left
       else { s[l] = v; placed = true; }
     }
   }
-  if (!placed) s[6] = v;
+  if (!placed) s[3] = v;
 }
-template <bool WG>
-__device__ __forceinline__ void segment_pairwise(const Team<WG>& team, const uint16_t* raw, uint32_t cnt, float& sum,
-                                                 float& sum_sq) {
-  uint32_t p = 1u;
-  while (p < cnt) p <<= 1;
-  const uint32_t per = p > team.size() ? p / team.size() : 1u;  // a power of two, at most 64 (2048 / 64, 16384 / 256)
-  const uint32_t first = team.id() * per;
-  float s1[7], s2[7];
-#pragma unroll
-  for (int l = 0; l < 7; ++l) s1[l] = s2[l] = 0.0f;
-  uint32_t units = per;  // what the carries count: leaves, or octets of leaves
-  if (per >= (uint32_t)kOct) {
-    units = per / (uint32_t)kOct;
-    const bool aligned = (reinterpret_cast<uintptr_t>(raw) & 15u) == 0;  // uniform: the group starts on a 16-byte boundary of the LDS
-    for (uint32_t o = 0; o < units; ++o) {  // uniform
-      const uint32_t i0 = first + o * (uint32_t)kOct;
-      float v[kOct];
-      if (aligned && i0 + (uint32_t)kOct <= cnt) {
-        const uint4 w = *reinterpret_cast<const uint4*>(raw + i0);
-        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { v[2 * k] = widen_lo(ww[k]); v[2 * k + 1] = widen_hi(ww[k]); }
-      } else {
-#pragma unroll
-        for (int e = 0; e < kOct; ++e) v[e] = i0 + (uint32_t)e < cnt ? widen_lo(raw[i0 + e]) : 0.0f;
-      }
-      carry_in(s1, o, ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) v[e] = v[e] * v[e];
-      carry_in(s2, o, ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
+
+// For every group of `opg` consecutive octets (the last group of the segment may have fewer; n_oct octets in
+// all): the balanced binary tree `op` over the group's words w[], padded with `pad` to the next power of two;
+// finish(group, result) is called by one thread per group.  Groups of up to 64 octets are taken by as many
+// adjacent lanes as the padded group has octets, several groups to a wavefront; groups of up to 128 by a
+// wavefront each; longer ones by the whole workgroup in turn, every thread folding the padded group's consecutive
+// words that fall to it first, the wavefronts' results meeting in head[40..47] (two sets, used in turn).
+// Called by all threads of the workgroup.  (For sums the padding adds +0.0 to partial sums, which changes no value.)
+template <class T, class Op, class Finish>
+__device__ __forceinline__ void groups_tree(SegmentShared& sh, const uint32_t* w, uint32_t n_oct, uint32_t opg, T pad,
+                                            Op op, Finish finish) {
+  const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / (uint32_t)kWave;
+  const uint32_t n_grp = (n_oct + opg - 1u) / opg;
+  uint32_t lg = 0u;
+  while ((1u << lg) < opg) ++lg;  // uniform
+  if (lg <= 6u) {
+    const uint32_t per_wave = (uint32_t)kWave >> lg;  // groups a wavefront takes at a time
+    const uint32_t leaf = lane & ((1u << lg) - 1u);
+    for (uint32_t g0 = wave * per_wave; g0 < n_grp; g0 += kSegWaves * per_wave) {  // uniform
+      const uint32_t g = g0 + (lane >> lg);
+      const uint32_t o = g * opg + leaf;
+      T v = pad;
+      if (g < n_grp && leaf < opg && o < n_oct) v = __builtin_bit_cast(T, w[o]);
+      v = lanes_reduce_lg(v, lg, op);
+      if (g < n_grp && leaf == 0u) finish(g, v);
+    }
+  } else if (lg == 7u) {
+    for (uint32_t g = wave; g < n_grp; g += kSegWaves) {  // uniform
+      const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
+      const uint32_t* wg = w + g * opg;
+      const T v0 = 2u * lane < left ? __builtin_bit_cast(T, wg[2u * lane]) : pad;
+      const T v1 = 2u * lane + 1u < left ? __builtin_bit_cast(T, wg[2u * lane + 1u]) : pad;
+      const T v = lanes_reduce<kWave>(op(v0, v1), op);
+      if (lane == 0u) finish(g, v);
     }
   } else {
-    for (uint32_t i = 0; i < per; ++i) {  // uniform
-      const float v = first + i < cnt ? widen_lo(raw[first + i]) : 0.0f;
-      carry_in(s1, i, v);
-      carry_in(s2, i, v * v);
-    }
-  }
-  // after all units = 2^m the last carry chain has run up to level m and the sum sits in s[m]
-  float mine1 = s1[0], mine2 = s2[0];
+    static_assert(kSegWaves == 4, "the wavefronts' results are combined as a tree of four");
+    const uint32_t per = 1u << (lg - 8u);  // words per thread: 1 .. 8
+    for (uint32_t g = 0; g < n_grp; ++g) {  // uniform
+      const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
+      const uint32_t* wg = w + g * opg;
+      T s[4];
 #pragma unroll
-  for (int l = 1; l < 7; ++l) {
-    mine1 = units == (1u << l) ? s1[l] : mine1;
-    mine2 = units == (1u << l) ? s2[l] : mine2;
+      for (int l = 0; l < 4; ++l) s[l] = pad;
+      for (uint32_t i = 0; i < per; ++i) {  // uniform
+        const uint32_t o = threadIdx.x * per + i;
+        carry_in(s, i, o < left ? __builtin_bit_cast(T, wg[o]) : pad, op);
+      }
+      T v = s[0];
+#pragma unroll
+      for (int l = 1; l < 4; ++l) v = per == (1u << l) ? s[l] : v;
+      v = lanes_reduce<kWave>(v, op);
+      uint32_t* meet = sh.head + 40u + (g & 1u) * kSegWaves;
+      if (lane == 0u) meet[wave] = __builtin_bit_cast(uint32_t, v);
+      __syncthreads();
+      if (threadIdx.x == 0u)
+        finish(g, op(op(__builtin_bit_cast(T, meet[0]), __builtin_bit_cast(T, meet[1])),
+                     op(__builtin_bit_cast(T, meet[2]), __builtin_bit_cast(T, meet[3]))));
+    }
+    __syncthreads();  // the words in head[] are free for the next call
   }
-  sum = team.tree_sum(mine1);
-  sum_sq = team.tree_sum(mine2);
 }
 
-// a2 / a3 for one statistics group (ABS: the whole segment): byte[i] = 1 for the outliers among raw[0 .. cnt)
-// TOPK: the kernel is the one for TOPK methods (its keys take 64 registers, the other modes do without)
-template <bool WG, bool TOPK>
-__device__ __forceinline__ void segment_select(const TensorDesc& d, const Team<WG>& team, const uint16_t* raw,
-                                               uint8_t* byte, uint32_t cnt) {
-  const uint32_t me = team.id(), step = team.size();
-  if constexpr (!TOPK) {
-    if (d.mode == kModeAbs) {
-      for (uint32_t i = me; i < cnt; i += step)
-        byte[i] = (fabsf(widen_lo(raw[i])) > d.param || pattern_nonfinite(raw[i])) ? 1 : 0;
-    } else {  // STD
-      float s1, s2;
-      segment_pairwise<WG>(team, raw, cnt, s1, s2);
-      const float n = (float)cnt;
-      const float mean = __fdiv_rn(s1, n);
-      float var = __fmaf_rn(-mean, mean, __fdiv_rn(s2, n));
-      var = (var < 0.0f) ? 0.0f : var;  // a NaN stays a NaN: then nothing passes the test
-      const float limit = d.param * var;  // param = k * k
-      for (uint32_t i = me; i < cnt; i += step) {
-        const float v = widen_lo(raw[i]);
-        byte[i] = (v * v > limit || pattern_nonfinite(raw[i])) ? 1 : 0;
+// ---- a1: the thread's octets.  Whole octets with one 16-byte load, the tensor's ragged end one by one;
+// what does not exist reads as +0.  The loads of all slices are issued without a branch between them (an
+// octet that does not exist reads the segment's first one again and is blanked afterwards): a load under
+// a branch is waited for at the end of that branch, and the slices' memory round trips would add up.
+template <int SL>
+__device__ __forceinline__ void segment_load(const TensorDesc& d, const SegmentGeo& g, uint32_t (&raw)[SL][4]) {
+  const uint16_t* sp = d.src + g.first_elem;
+  const uint32_t whole = g.cnt / (uint32_t)kOct;  // uniform
+  if (whole != 0u) {
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      const uint32_t o = threadIdx.x + (uint32_t)j * kSegThreads;
+      const uint4 v = ADACC_LOAD16(sp + (o < whole ? o : 0u) * (uint32_t)kOct);
+      raw[j][0] = v.x; raw[j][1] = v.y; raw[j][2] = v.z; raw[j][3] = v.w;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < SL; ++j) {
+    const uint32_t o = threadIdx.x + (uint32_t)j * kSegThreads;
+    if (whole == 0u || o >= whole) raw[j][0] = raw[j][1] = raw[j][2] = raw[j][3] = 0u;
+  }
+  if ((g.cnt & 7u) != 0u) {  // uniform: the tensor's last segment
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      const uint32_t o = threadIdx.x + (uint32_t)j * kSegThreads;
+      if (o == whole) {
+#pragma unroll
+        for (int e = 0; e < kOct - 1; ++e) {
+          if ((uint32_t)e < (g.cnt & 7u)) raw[j][e >> 1] |= (uint32_t)sp[o * (uint32_t)kOct + (uint32_t)e] << (16 * (e & 1));
+        }
       }
     }
-  } else {  // TOPK: the k largest magnitudes, ties to the lower index
-    // Every member holds the keys of its own elements (at most 16384 / 256 resp. 2048 / 64 of them) in
-    // registers: magnitude above the reversed index, never zero.  A round is one maximum over everything;
-    // the winner's key is unique, its owner sets it to zero.  Zero keys are the outliers.
-    constexpr int kCap = WG ? 64 : 32;
-    uint32_t key[kCap];
-#pragma unroll
-    for (int j = 0; j < kCap; ++j) {
-      const uint32_t i = me + (uint32_t)j * step;
-      key[j] = i < cnt ? (((uint32_t)(raw[i] & 0x7FFFu) << 16) | (0xFFFFu - i)) : 0u;
-    }
-    const uint32_t rounds = d.topk < cnt ? d.topk : cnt;
-    for (uint32_t round = 0; round < rounds; ++round) {
-      uint32_t best = 0u;
-#pragma unroll
-      for (int j = 0; j < kCap; ++j) best = key[j] > best ? key[j] : best;
-      const uint32_t win = team.max_u32(best);  // not zero: fewer than cnt elements are taken so far
-#pragma unroll
-      for (int j = 0; j < kCap; ++j) key[j] = key[j] == win ? 0u : key[j];
-    }
-#pragma unroll
-    for (int j = 0; j < kCap; ++j) {
-      const uint32_t i = me + (uint32_t)j * step;
-      // a value that cannot be quantised at all is always kept exactly
-      if (i < cnt) byte[i] = (key[j] == 0u || pattern_nonfinite(raw[i])) ? 1 : 0;
-    }
   }
-  team.sync();
 }
 
-// The outliers of raw[0 .. cnt) (byte[i] == 1), in index order: their number (uniform), and, when `emit`,
-// entry pos, pos + 1, .. of the stream for them (indices first_index + i).  The whole workgroup.
-__device__ __forceinline__ uint32_t segment_outliers(const TensorDesc& d, SegmentShared& sh, uint32_t cnt, bool emit,
-                                                     uint32_t pos, uint64_t first_index) {
+// bit e: element e of the octet is not finite
+__device__ __forceinline__ uint32_t octet_nonfinite(const uint32_t (&oct)[4]) {
+  uint32_t m = 0u;
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) m |= (ADACC_ELEM_MAG(oct, e) >= kNonfiniteMag ? 1u : 0u) << e;
+  return m;
+}
+
+// TOPK works on one key per octet: the largest magnitude among the octet's elements that exist (nv of them) and
+// are not taken yet, above the reversed number of the octet (never zero while such an element is left; 0 when
+// none is).  Among equal magnitudes the lower octet wins, and inside the octet the lower element (octet_take):
+// together the lower index.
+__device__ __forceinline__ uint32_t octet_key(const uint32_t (&oct)[4], uint32_t taken, uint32_t o, uint32_t nv) {
+  uint32_t best = 0u;
+  bool any = false;
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) {
+    const uint32_t mag = ADACC_ELEM_MAG(oct, e);
+    const bool live = (uint32_t)e < nv && ((taken >> e) & 1u) == 0u;
+    best = (live && mag > best) ? mag : best;
+    any = any || live;
+  }
+  return any ? (best << 16) | (0xFFFFu - o) : 0u;
+}
+// the first element of the octet that exists, is not taken and has the magnitude of `key`
+__device__ __forceinline__ uint32_t octet_take(const uint32_t (&oct)[4], uint32_t taken, uint32_t key, uint32_t nv) {
+  uint32_t first = 0u;
+#pragma unroll
+  for (int e = kOct - 1; e >= 0; --e) {
+    const bool hit = (uint32_t)e < nv && ((taken >> e) & 1u) == 0u && ADACC_ELEM_MAG(oct, e) == (key >> 16);
+    first = hit ? (uint32_t)e : first;
+  }
+  return first;
+}
+
+// ---- a2 / a3: mask[j] bit e = element e of the thread's octet j is an outlier by the method's rule
+// omag[j]: the largest magnitude of octet j, as the 15 low bits of the pattern
+template <int SL>
+__device__ __forceinline__ void segment_select(const TensorDesc& d, const SegmentGeo& g, SegmentShared& sh,
+                                               const uint32_t (&raw)[SL][4], const uint32_t (&omag)[SL],
+                                               uint32_t (&mask)[SL]) {
   const uint32_t tid = threadIdx.x;
-  const uint32_t per = (cnt + kSegThreads - 1u) / kSegThreads;
-  const uint32_t i0 = tid * per < cnt ? tid * per : cnt;
-  const uint32_t i1 = i0 + per < cnt ? i0 + per : cnt;
-  uint32_t mine = 0u;
-  for (uint32_t i = i0; i < i1; ++i) mine += sh.byte[i];
-  // threads before this one: inside the wavefront by a scan over the lanes, the wavefronts through LDS
-  const uint32_t lane = (uint32_t)lane_id(), wave = tid / (uint32_t)kWave;
-  uint32_t incl = mine;
 #pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t t = (uint32_t)__shfl_up((int)incl, o, kWave);
-    if (lane >= (uint32_t)o) incl += t;
-  }
-  if (lane == (uint32_t)kWave - 1u) sh.meet[8u + wave] = incl;
-  __syncthreads();
-  uint32_t before = incl - mine, total = 0u;
+  for (int j = 0; j < SL; ++j) mask[j] = 0u;
+  if (d.mode == kModeAbs) {
 #pragma unroll
-  for (uint32_t w = 0; w < kSegWaves; ++w) {
-    const uint32_t c = sh.meet[8u + w];
-    before += w < wave ? c : 0u;
-    total += c;
-  }
-  if (emit) {
-    uint32_t p = pos + before;
-    for (uint32_t i = i0; i < i1; ++i) {
-      if (sh.byte[i] == 0) continue;
-      if (p < d.cap) {
-        d.idx[p] = (int32_t)(first_index + i);
-        d.val[p] = sh.raw[i];
+    for (int j = 0; j < SL; ++j) {
+      // no element passes where the octet's largest magnitude does not (an octet with a NaN is looked at)
+      if (!(widen_lo(omag[j]) <= d.param)) {
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) mask[j] |= (fabsf(ADACC_ELEM_F32(raw[j], e)) > d.param ? 1u : 0u) << e;
       }
-      ++p;
+    }
+  } else if (d.mode == kModeStd) {
+    // the three lowest levels of the pairwise sums inside the octet, the rest over the octets' words
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      const uint32_t o = tid + (uint32_t)j * kSegThreads;
+      if (o < g.octs) {
+        float v[kOct];
+        widen_row(raw[j], v);
+        sh.a[o] = __float_as_uint(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
+#pragma unroll
+        for (int e = 0; e < kOct; ++e) v[e] = v[e] * v[e];
+        sh.b[o] = __float_as_uint(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
+      }
+    }
+    __syncthreads();
+    const uint32_t opg = d.gs / (uint32_t)kOct;
+    float* mean = reinterpret_cast<float*>(sh.g1);
+    groups_tree<float>(sh, sh.a, g.octs, opg, 0.0f, OpAdd(), [&](uint32_t grp, float s1) {
+      const uint32_t left = g.cnt - grp * d.gs;
+      mean[grp] = __fdiv_rn(s1, (float)(left < d.gs ? left : d.gs));
+    });
+    // (a group's two words are written and read by the same thread)
+    groups_tree<float>(sh, sh.b, g.octs, opg, 0.0f, OpAdd(), [&](uint32_t grp, float s2) {
+      const uint32_t left = g.cnt - grp * d.gs;
+      const float m = mean[grp];
+      float var = __fmaf_rn(-m, m, __fdiv_rn(s2, (float)(left < d.gs ? left : d.gs)));
+      var = (var < 0.0f) ? 0.0f : var;  // a NaN stays a NaN: then nothing passes the test
+      sh.g0[grp] = __float_as_uint(d.param * var);  // param = k * k
+    });
+    __syncthreads();
+    const float r = group_reciprocal(opg);
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      const uint32_t o = tid + (uint32_t)j * kSegThreads;
+      if (o < g.octs) {
+        const float limit = __uint_as_float(sh.g0[group_of(o, r)]);
+        const float top = widen_lo(omag[j]);
+        if (!(top * top <= limit)) {  // the square is monotonic: no element passes where the largest magnitude does not
+#pragma unroll
+          for (int e = 0; e < kOct; ++e) {
+            const float v = ADACC_ELEM_F32(raw[j], e);
+            mask[j] |= (v * v > limit ? 1u : 0u) << e;
+          }
+        }
+      }
+    }
+    __syncthreads();  // a, b, g0, g1 are free again
+  } else if (d.mode == kModeTopk) {
+    if (d.gs >= d.tile_elems) {
+      // The segment is one group.  Every thread knows the key of each of its octets; a round is one maximum over
+      // the workgroup (the wavefronts meet in head[], two sets of words used in turn, so one barrier per round);
+      // the winner's key is unique, its owner takes the element and forms the octet's key again.
+      uint32_t okey[SL], best = 0u;
+#pragma unroll
+      for (int j = 0; j < SL; ++j) {
+        const uint32_t o = tid + (uint32_t)j * kSegThreads;
+        // whole octets (all but a tensor's ragged end): every element exists, the largest magnitude is known
+        const uint32_t nv = octet_valid(g, o);
+        okey[j] = nv == (uint32_t)kOct ? (omag[j] << 16) | (0xFFFFu - o) : octet_key(raw[j], 0u, o, nv);
+        best = okey[j] > best ? okey[j] : best;
+      }
+      const uint32_t rounds = d.topk < g.cnt ? d.topk : g.cnt;
+      for (uint32_t r = 0; r < rounds; ++r) {  // uniform
+        const uint32_t w = wave_max_u32_scalar(best);
+        uint32_t* meet = sh.head + (r & 1u) * kSegWaves;
+        if (lane_id() == 0) meet[tid / (uint32_t)kWave] = w;
+        __syncthreads();
+        uint32_t win = meet[0];
+#pragma unroll
+        for (uint32_t k = 1; k < kSegWaves; ++k) win = meet[k] > win ? meet[k] : win;
+        if (best == win) {  // one thread of the workgroup (the key of an octet with an element left is never zero)
+          best = 0u;
+#pragma unroll
+          for (int j = 0; j < SL; ++j) {
+            const uint32_t o = tid + (uint32_t)j * kSegThreads;
+            if (okey[j] == win) {
+              const uint32_t nv = octet_valid(g, o);
+              mask[j] |= 1u << octet_take(raw[j], mask[j], win, nv);
+              okey[j] = octet_key(raw[j], mask[j], o, nv);
+            }
+            best = okey[j] > best ? okey[j] : best;
+          }
+        }
+      }
+      __syncthreads();  // head[] is free again
+    } else {
+      // Several groups (of at most 2048 elements): the patterns go to LDS, a wavefront takes a group at a time
+      // with the keys of its elements in registers (32 per lane at most), k rounds of a maximum over the wavefront.
+      uint16_t* pat = reinterpret_cast<uint16_t*>(sh.a);
+#pragma unroll
+      for (int j = 0; j < SL; ++j) {
+        const uint32_t o = tid + (uint32_t)j * kSegThreads;
+        if (o < g.octs)
+          *reinterpret_cast<uint4*>(pat + o * (uint32_t)kOct) = make_uint4(raw[j][0], raw[j][1], raw[j][2], raw[j][3]);
+      }
+      __syncthreads();
+      const uint32_t lane = (uint32_t)lane_id();
+      for (uint32_t e0 = (tid / (uint32_t)kWave) * d.gs; e0 < g.cnt; e0 += kSegWaves * d.gs) {  // uniform
+        const uint32_t n = g.cnt - e0 < d.gs ? g.cnt - e0 : d.gs;
+        constexpr int kCap = 32;
+        uint32_t key[kCap];
+#pragma unroll
+        for (int k = 0; k < kCap; ++k) {
+          const uint32_t i = lane + (uint32_t)k * (uint32_t)kWave;
+          key[k] = i < n ? (((uint32_t)(pat[e0 + i] & 0x7FFFu) << 16) | (0xFFFFu - i)) : 0u;
+        }
+        const uint32_t rounds = d.topk < n ? d.topk : n;
+        for (uint32_t r = 0; r < rounds; ++r) {
+          uint32_t best = 0u;
+#pragma unroll
+          for (int k = 0; k < kCap; ++k) best = key[k] > best ? key[k] : best;
+          const uint32_t win = wave_max_u32_scalar(best);
+#pragma unroll
+          for (int k = 0; k < kCap; ++k) key[k] = key[k] == win ? 0u : key[k];
+        }
+#pragma unroll
+        for (int k = 0; k < kCap; ++k) {
+          const uint32_t i = lane + (uint32_t)k * (uint32_t)kWave;
+          if (i < n) sh.byte[e0 + i] = key[k] == 0u ? 1 : 0;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < SL; ++j) {
+        const uint32_t o = tid + (uint32_t)j * kSegThreads;
+        if (o < g.octs) {
+          const uint2 f = *reinterpret_cast<const uint2*>(sh.byte + o * (uint32_t)kOct);
+          const uint32_t nv = octet_valid(g, o);
+#pragma unroll
+          for (int e = 0; e < kOct; ++e) {
+            const uint32_t bit = ((e < 4 ? f.x : f.y) >> (8 * (e & 3))) & 1u;
+            mask[j] |= ((uint32_t)e < nv ? bit : 0u) << e;
+          }
+        }
+      }
+      __syncthreads();  // a, b and the bytes are free again
     }
   }
+}
+
+// ---- a4: the outliers of the segment (mask[]), in index order, to entries pos0, pos0 + 1, .. of the sink
+// (entries at or past `limit` are dropped).  Returns their number (uniform).
+template <int SL, class Sink>
+__device__ __forceinline__ uint32_t segment_emit(const SegmentGeo& g, SegmentShared& sh, const uint32_t (&raw)[SL][4],
+                                                 const uint32_t (&mask)[SL], const Sink& sink, uint32_t pos0,
+                                                 uint32_t limit) {
+  const uint32_t tid = threadIdx.x, wave = tid / (uint32_t)kWave;
+  uint32_t* counts = sh.head + 8u;  // [slice][wavefront]
+  // outliers of each of this wavefront's octet slices (element order is slice, wavefront, lane)
+#pragma unroll
+  for (int j = 0; j < SL; ++j) {
+    uint32_t c = 0u;
+    if (__builtin_amdgcn_ballot_w64(mask[j] != 0u) != 0ull) c = wave_sum_u32(__builtin_popcount(mask[j]));
+    if (lane_id() == 0) counts[(uint32_t)j * kSegWaves + wave] = c;
+  }
   __syncthreads();
+  uint32_t total = 0u, before[SL];
+#pragma unroll
+  for (int j = 0; j < SL; ++j) {
+#pragma unroll
+    for (uint32_t w = 0; w < kSegWaves; ++w) {
+      if (w == wave) before[j] = total;  // uniform in the wavefront
+      total += counts[(uint32_t)j * kSegWaves + w];
+    }
+  }
+  if (total != 0u) {  // uniform
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      const uint64_t any = __builtin_amdgcn_ballot_w64(mask[j] != 0u);
+      if (any == 0ull) continue;  // uniform
+      const bool sparse = __builtin_amdgcn_ballot_w64((mask[j] & (mask[j] - 1u)) != 0u) == 0ull;
+      uint32_t lane_excl;
+      if (sparse) {
+        lane_excl = lanes_below(any);
+      } else {
+        const uint32_t c = (uint32_t)__builtin_popcount(mask[j]);
+        uint32_t incl = c;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+          const uint32_t up = (uint32_t)__shfl_up((int)incl, off, kWave);
+          if (lane_id() >= off) incl += up;
+        }
+        lane_excl = incl - c;
+      }
+      const uint32_t o = tid + (uint32_t)j * kSegThreads;
+      emit_row(raw[j], mask[j], lane_excl, sparse, (uint32_t)g.first_elem + o * (uint32_t)kOct, sink, pos0 + before[j], limit);
+    }
+  }
+  __syncthreads();  // counts[] is free again
   return total;
 }
 
-// a5: from here on the outliers, and every value that is not finite, count as zero
-__device__ __forceinline__ void segment_clear(const TensorDesc& d, SegmentShared& sh, uint32_t cnt) {
-  for (uint32_t i = threadIdx.x; i < cnt; i += kSegThreads)
-    if ((d.mode != kModeNone && sh.byte[i] != 0) || pattern_nonfinite(sh.raw[i])) sh.raw[i] = 0;
-  __syncthreads();
-}
-
-// a6 .. a8 for one quantisation group raw[g0 .. g0 + n) by a team: scale (offset) and the codes into byte[]
-template <int Q, bool ASYM, bool WG>
-__device__ __forceinline__ void quantise_group(const TensorDesc& d, const Team<WG>& team, SegmentShared& sh, uint32_t g0,
-                                               uint32_t n, uint64_t group) {
-  const uint32_t me = team.id(), step = team.size();
-  float scl, inv, off;
-  if constexpr (!ASYM) {
-    uint32_t am = 0u;
-    for (uint32_t i = me; i < n; i += step) {
-      const uint32_t bits = __float_as_uint(fabsf(widen_lo(sh.raw[g0 + i])));
-      am = bits > am ? bits : am;
-    }
-    group_scale<false>(d, team.max_u32(am), 0, 0, scl, inv, off);
-  } else {
-    int32_t hi = float_key(widen_lo(sh.raw[g0])), lo = hi;
-    for (uint32_t i = me; i < n; i += step) {
-      const int32_t k = float_key(widen_lo(sh.raw[g0 + i]));
-      hi = k > hi ? k : hi;
-      lo = k < lo ? k : lo;
-    }
-    // signed keys through the unsigned maximum: flip the sign bit (and, for the minimum, the rest)
-    const int32_t k0 = (int32_t)(team.max_u32((uint32_t)hi ^ 0x80000000u) ^ 0x80000000u);
-    const int32_t k1 = (int32_t)(~team.max_u32(~((uint32_t)lo ^ 0x80000000u)) ^ 0x80000000u);
-    group_scale<true>(d, 0u, k0, k1, scl, inv, off);
-  }
-  for (uint32_t i = me; i < n; i += step) {
-    const float y = widen_lo(sh.raw[g0 + i]);
-    sh.byte[g0 + i] = (uint8_t)code_bits<Q>(ASYM ? y - off : y, inv);
-  }
-  if (me == 0u) {
-    d.scales[group] = scl;
-    if constexpr (ASYM) d.zp[group] = off;
-  }
-}
-
-// a6 .. a8 for raw[0 .. cnt), cut into groups of gq from its start (the last one may be short); first_elem:
-// the tensor index of raw[0], a multiple of gq and of 8.  Small groups are taken one per thread, larger ones
-// one per wavefront, those beyond 1024 elements (at most four to a segment) by the whole workgroup in turn.
-template <int Q, bool ASYM>
-__device__ __forceinline__ void segment_quantise(const TensorDesc& d, SegmentShared& sh, uint32_t cnt, uint64_t first_elem) {
+// ---- a6 .. a8: scales (offsets) of the quantisation groups and the codes of the thread's octets, from which
+// outliers and values that are not finite are gone
+// omag[j]: the largest magnitude of octet j as it is now
+template <int BITS, bool ASYM, int SL>
+__device__ __forceinline__ void segment_quantise(const TensorDesc& d, const SegmentGeo& g, SegmentShared& sh,
+                                                 const uint32_t (&raw)[SL][4], const uint32_t (&omag)[SL]) {
+  constexpr int Q = 1 << (BITS - 1);
   const uint32_t tid = threadIdx.x;
-  const uint32_t gq = d.gq;
-  const uint64_t first_group = first_elem / gq;
-  const uint32_t n_groups = (cnt + gq - 1u) / gq;
-  if (gq <= 64u) {
-    for (uint32_t g = tid; g < n_groups; g += kSegThreads) {
-      const uint32_t g0 = g * gq;
-      const uint32_t n = cnt - g0 < gq ? cnt - g0 : gq;
-      float scl, inv, off;
+  const uint32_t opg = d.gq / (uint32_t)kOct;
+  const uint64_t first_group = g.first_elem / d.gq;
+#pragma unroll
+  for (int j = 0; j < SL; ++j) {
+    const uint32_t o = tid + (uint32_t)j * kSegThreads;
+    if (o < g.octs) {
       if constexpr (!ASYM) {
-        uint32_t am = 0u;
-        for (uint32_t i = 0; i < n; ++i) {
-          const uint32_t bits = __float_as_uint(fabsf(widen_lo(sh.raw[g0 + i])));
-          am = bits > am ? bits : am;
-        }
-        group_scale<false>(d, am, 0, 0, scl, inv, off);
+        sh.a[o] = omag[j];  // what does not exist is zero and cannot raise the maximum
       } else {
-        int32_t hi = float_key(widen_lo(sh.raw[g0])), lo = hi;
-        for (uint32_t i = 1; i < n; ++i) {
-          const int32_t k = float_key(widen_lo(sh.raw[g0 + i]));
-          hi = k > hi ? k : hi;
-          lo = k < lo ? k : lo;
+        const uint32_t nv = octet_valid(g, o);
+        int32_t hi = float_key(widen_lo(raw[j][0])), lo = hi;  // element 0 exists
+#pragma unroll
+        for (int e = 1; e < kOct; ++e) {
+          const int32_t k = float_key(ADACC_ELEM_F32(raw[j], e));
+          hi = ((uint32_t)e < nv && k > hi) ? k : hi;
+          lo = ((uint32_t)e < nv && k < lo) ? k : lo;
         }
-        group_scale<true>(d, 0u, hi, lo, scl, inv, off);
+        sh.a[o] = (uint32_t)hi;
+        sh.b[o] = (uint32_t)lo;
       }
-      for (uint32_t i = 0; i < n; ++i) {
-        const float y = widen_lo(sh.raw[g0 + i]);
-        sh.byte[g0 + i] = (uint8_t)code_bits<Q>(ASYM ? y - off : y, inv);
-      }
-      d.scales[first_group + g] = scl;
-      if constexpr (ASYM) d.zp[first_group + g] = off;
-    }
-  } else if (gq <= 1024u) {
-    const Team<false> team{nullptr};
-    for (uint32_t g = tid / (uint32_t)kWave; g < n_groups; g += kSegWaves) {  // uniform in the wavefront
-      const uint32_t g0 = g * gq;
-      quantise_group<Q, ASYM, false>(d, team, sh, g0, cnt - g0 < gq ? cnt - g0 : gq, first_group + g);
-    }
-  } else {
-    const Team<true> team{sh.meet};
-    for (uint32_t g = 0; g < n_groups; ++g) {  // uniform
-      const uint32_t g0 = g * gq;
-      quantise_group<Q, ASYM, true>(d, team, sh, g0, cnt - g0 < gq ? cnt - g0 : gq, first_group + g);
     }
   }
   __syncthreads();
-  // the codes leave an octet at a time (8 resp. 4 bytes; the segment starts on a multiple of 8 elements), what
-  // is left of a tensor's ragged end one by one
-  const uint32_t octs = cnt / (uint32_t)kOct;
-  if constexpr (Q == 128) {
-    uint8_t* out = d.codes + first_elem;
-    for (uint32_t o = tid; o < octs; o += kSegThreads)
-      *reinterpret_cast<uint2*>(out + o * kOct) = *reinterpret_cast<const uint2*>(sh.byte + o * kOct);
-    for (uint32_t i = octs * kOct + tid; i < cnt; i += kSegThreads) out[i] = sh.byte[i];
+  // the groups' extremes to g0 (g1); every thread then forms D / max (and the offset) of its octets' groups
+  // itself - once per change of group along its octets - instead of a few lanes doing it for all
+  if constexpr (!ASYM) {
+    groups_tree<uint32_t>(sh, sh.a, g.octs, opg, 0u, OpUMax(), [&](uint32_t grp, uint32_t mag) { sh.g0[grp] = mag; });
   } else {
-    uint8_t* out = d.codes + (first_elem >> 1);
-    for (uint32_t o = tid; o < octs; o += kSegThreads) {
-      const uint2 c = *reinterpret_cast<const uint2*>(sh.byte + o * kOct);
-      const uint32_t e = (c.x & 0x0F0F0F0Fu) | ((c.x >> 4) & 0x00F000F0u);   // bytes 0 and 2: the nibble pairs of elements 0..3
-      const uint32_t f = (c.y & 0x0F0F0F0Fu) | ((c.y >> 4) & 0x00F000F0u);
-      // pair (2j, 2j+1) -> one byte: low nibble the even element
-      const uint32_t lo = (e & 0xFFu) | ((e >> 8) & 0xFF00u);
-      const uint32_t hi = (f & 0xFFu) | ((f >> 8) & 0xFF00u);
-      *reinterpret_cast<uint32_t*>(out + o * 4u) = lo | (hi << 16);
-    }
-    for (uint32_t b = octs * 4u + tid; b < (cnt + 1u) / 2u; b += kSegThreads) {
-      const uint32_t lo = sh.byte[2u * b] & 0xFu;
-      const uint32_t hi = 2u * b + 1u < cnt ? (sh.byte[2u * b + 1u] & 0xFu) : 0u;  // an odd end: the high nibble is 0
-      out[b] = (uint8_t)(lo | (hi << 4));
+    groups_tree<int32_t>(sh, sh.a, g.octs, opg, (int32_t)0x80000000, OpIMax(), [&](uint32_t grp, int32_t hi) { sh.g0[grp] = (uint32_t)hi; });
+    groups_tree<int32_t>(sh, sh.b, g.octs, opg, (int32_t)0x7FFFFFFF, OpIMin(), [&](uint32_t grp, int32_t lo) { sh.g1[grp] = (uint32_t)lo; });
+  }
+  __syncthreads();
+  const float recip = group_reciprocal(opg);
+  uint32_t have = 0xFFFFFFFFu;  // the group the values below belong to
+  float scl = 0.0f, inv = 0.0f, off = 0.0f;
+#pragma unroll
+  for (int j = 0; j < SL; ++j) {
+    const uint32_t o = tid + (uint32_t)j * kSegThreads;
+    if (o < g.octs) {
+      const uint32_t grp = group_of(o, recip);
+      if (grp != have) {
+        if constexpr (!ASYM) group_scale<false>(d, mag_bits32(sh.g0[grp]), 0, 0, scl, inv, off);
+        else group_scale<true>(d, 0u, (int32_t)sh.g0[grp], (int32_t)sh.g1[grp], scl, inv, off);
+        have = grp;
+      }
+      if (grp * opg == o) {  // the group's first octet
+        d.scales[first_group + grp] = scl;
+        if constexpr (ASYM) d.zp[first_group + grp] = off;
+      }
+      uint32_t c[kOct];
+#pragma unroll
+      for (int e = 0; e < kOct; ++e) {
+        const float y = ADACC_ELEM_F32(raw[j], e);
+        c[e] = code_bits<Q, ASYM>(ASYM ? y - off : y, inv);  // symmetric codes cannot pass the lower bound
+      }
+      const uint32_t nv = octet_valid(g, o);
+      const uint64_t e0 = g.first_elem + (uint64_t)o * kOct;
+      if constexpr (BITS == 8) {
+        uint2 w8;
+        w8.x = pack_bytes4(c[0], c[1], c[2], c[3]);
+        w8.y = pack_bytes4(c[4], c[5], c[6], c[7]);
+        if (nv == (uint32_t)kOct) {
+          ADACC_STORE8(d.codes + e0, w8);
+        } else {  // the tensor's ragged end, byte by byte
+#pragma unroll
+          for (int e = 0; e < kOct - 1; ++e)
+            if ((uint32_t)e < nv) d.codes[e0 + e] = (uint8_t)((e < 4 ? w8.x : w8.y) >> (8 * (e & 3)));
+        }
+      } else {
+        const uint32_t w4 = pack_nibbles8(c);
+        if (nv == (uint32_t)kOct) {
+          ADACC_STORE4(d.codes + (e0 >> 1), w4);
+        } else {  // an odd end: the high nibble of the last byte is 0
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            if ((uint32_t)(2 * b) < nv) {
+              uint32_t v = (w4 >> (8 * b)) & 0xFFu;
+              if ((uint32_t)(2 * b + 1) >= nv) v &= 0x0Fu;
+              d.codes[(e0 >> 1) + b] = (uint8_t)v;
+            }
+          }
+        }
+      }
     }
   }
 }
 
-__device__ __forceinline__ void segment_quantise_any(const TensorDesc& d, SegmentShared& sh, uint32_t cnt, uint64_t first_elem) {
-  if (d.bits == 8u) {
-    if (d.asym) segment_quantise<128, true>(d, sh, cnt, first_elem); else segment_quantise<128, false>(d, sh, cnt, first_elem);
-  } else {
-    if (d.asym) segment_quantise<8, true>(d, sh, cnt, first_elem); else segment_quantise<8, false>(d, sh, cnt, first_elem);
-  }
-}
-
-// One segment (d.tile_elems elements, the last one of the tensor may be short).  COUNT: only the number of
-// its outliers, into d.cnt.
-template <bool COUNT, bool TOPK>
-__device__ __forceinline__ void compress_segment(const TensorDesc& d, SegmentShared& sh, uint32_t seg) {
+// One segment (d.tile_elems elements, the last one of the tensor may be short).
+// FIXUP: the second launch - only the outliers, straight to the stream at the offsets the placement kernel
+// has written, and only where the first launch could not place them.
+template <int SL, bool FIXUP>
+__device__ __forceinline__ void compress_segment(const TensorDesc& d, SegmentShared& sh, uint32_t seg, uint32_t epoch) {
   const uint32_t tid = threadIdx.x;
-  const uint64_t first_elem = (uint64_t)seg * d.tile_elems;
-  const uint64_t left = d.numel - first_elem;
-  const uint32_t cnt = left < (uint64_t)d.tile_elems ? (uint32_t)left : d.tile_elems;
-  // whole octets with one 16-byte load (the segment starts on a multiple of 8 elements), the rest one by one
-  const uint32_t octs = cnt / kOct;
-  for (uint32_t o = tid; o < octs; o += kSegThreads)
-    *reinterpret_cast<uint4*>(sh.raw + o * kOct) = *reinterpret_cast<const uint4*>(d.src + first_elem + o * kOct);
-  for (uint32_t i = octs * kOct + tid; i < cnt; i += kSegThreads) sh.raw[i] = d.src[first_elem + i];
-  __syncthreads();
-  if (d.mode != kModeNone) {
-    if (d.mode == kModeAbs || d.gs >= d.tile_elems) {  // ABS needs no statistics; or the segment is one group
-      const Team<true> team{sh.meet};
-      segment_select<true, TOPK>(d, team, sh.raw, sh.byte, cnt);
-    } else {  // several groups: each wavefront takes groups of its own
-      const Team<false> team{nullptr};
-      for (uint32_t g0 = (tid / (uint32_t)kWave) * d.gs; g0 < cnt; g0 += kSegWaves * d.gs)
-        segment_select<false, TOPK>(d, team, sh.raw + g0, sh.byte + g0, cnt - g0 < d.gs ? cnt - g0 : d.gs);
-      __syncthreads();
+  const bool topk = d.mode == kModeTopk;
+  if constexpr (FIXUP) {
+    if (topk) {
+      if (__hip_atomic_load(d.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) return;  // uniform
+    } else if (d.cnt[seg] <= (uint32_t)kSlot) {
+      return;  // uniform
     }
-    if constexpr (COUNT) {
-      const uint32_t total = segment_outliers(d, sh, cnt, false, 0u, 0ull);
-      if (tid == 0u) d.cnt[seg] = total;
-      return;
-    } else {
-      segment_outliers(d, sh, cnt, true, d.tile_ptr[seg], first_elem);
-    }
-  } else if (seg == 0u && tid == 0u) {
-    d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;
   }
-  segment_clear(d, sh, cnt);
-  segment_quantise_any(d, sh, cnt, first_elem);
+  SegmentGeo g;
+  g.first_elem = (uint64_t)seg * d.tile_elems;
+  const uint64_t left = d.numel - g.first_elem;
+  g.cnt = left < (uint64_t)d.tile_elems ? (uint32_t)left : d.tile_elems;
+  g.octs = (g.cnt + (uint32_t)kOct - 1u) / (uint32_t)kOct;
+  uint32_t raw[SL][4];
+  segment_load(d, g, raw);
+  uint32_t mask[SL], omag[SL];
+#pragma unroll
+  for (int j = 0; j < SL; ++j) omag[j] = octet_magnitude(raw[j]);
+  if (d.mode != kModeNone) {
+    segment_select(d, g, sh, raw, omag, mask);
+#pragma unroll
+    for (int j = 0; j < SL; ++j)  // what cannot be quantised at all is always kept exactly
+      if (omag[j] >= kNonfiniteMag) mask[j] |= octet_nonfinite(raw[j]);
+    if constexpr (FIXUP) {
+      const uint32_t pos0 = d.tile_ptr[seg], end = d.tile_ptr[seg + 1u];
+      segment_emit(g, sh, raw, mask, StreamSink{d.idx, d.val}, pos0, end < d.cap ? end : d.cap);
+      return;
+    } else if (topk) {
+      const uint32_t gps = d.tile_elems / d.gs;  // groups of a whole segment
+      const uint32_t pos0 = seg * gps * d.topk;
+      const uint32_t whole = g.cnt / d.gs, rest = g.cnt - whole * d.gs;
+      const uint32_t expected = whole * d.topk + (rest < d.topk ? rest : d.topk);
+      const uint32_t end = pos0 + expected;
+      const uint32_t total = segment_emit(g, sh, raw, mask, StreamSink{d.idx, d.val}, pos0, end < d.cap ? end : d.cap);
+      if (tid == 0u) {
+        d.tile_ptr[seg] = pos0;
+        d.cnt[seg] = total;
+        if (total != expected) *d.flag = epoch;
+        if (seg + 1u == d.n_tiles) {
+          d.tile_ptr[d.n_tiles] = end;
+          d.status[0] = end; d.status[1] = end > d.cap ? 1u : 0u; d.status[2] = 0u; d.status[3] = 0u;
+        }
+      }
+    } else {
+      const uint32_t total = segment_emit(g, sh, raw, mask, SlotSink{d.slot + (uint64_t)seg * (uint64_t)kSlot}, 0u, (uint32_t)kSlot);
+      if (tid == 0u) d.cnt[seg] = total;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < SL; ++j) mask[j] = omag[j] >= kNonfiniteMag ? octet_nonfinite(raw[j]) : 0u;
+    if (seg == 0u && tid == 0u) {
+      d.status[0] = 0u; d.status[1] = 0u; d.status[2] = 0u; d.status[3] = 0u;
+    }
+  }
+  if constexpr (!FIXUP) {
+    // a5: from here on the outliers, and every value that is not finite, count as zero
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      if (mask[j] != 0u) {
+        clear_elements(raw[j], mask[j]);
+        omag[j] = octet_magnitude(raw[j]);
+      }
+    }
+    if (d.bits == 8u) {
+      if (d.asym) segment_quantise<8, true, SL>(d, g, sh, raw, omag); else segment_quantise<8, false, SL>(d, g, sh, raw, omag);
+    } else {
+      if (d.asym) segment_quantise<4, true, SL>(d, g, sh, raw, omag); else segment_quantise<4, false, SL>(d, g, sh, raw, omag);
+    }
+  }
 }
 
 // a9 / a10 for one segment
@@ -476,11 +701,15 @@ __device__ __forceinline__ void decompress_segment(const TensorDesc& d, uint32_t
   }
 }
 
-template <bool COUNT, bool TOPK>
-__global__ __launch_bounds__(kSegThreads) void compress_generic_kernel(TensorDesc d) {
+// wavefronts per SIMD (= workgroups per CU) the registers are held to: the kernel is a chain of memory and LDS
+// round trips with barriers between, which only other resident workgroups can fill
+template <int SL>
+constexpr int generic_min_waves() { return SL <= 2 ? 8 : SL <= 4 ? 6 : SL <= 6 ? 4 : 3; }
+template <int SL, bool FIXUP>
+__global__ __launch_bounds__(kSegThreads, (generic_min_waves<SL>())) void compress_generic_kernel(TensorDesc d, uint32_t epoch) {
   extern __shared__ __attribute__((aligned(16))) unsigned char segment_lds[];
-  SegmentShared sh = segment_shared(segment_lds, d.tile_elems);
-  compress_segment<COUNT, TOPK>(d, sh, blockIdx.x);
+  SegmentShared sh = segment_shared(segment_lds, d.tile_elems, d.gq);
+  compress_segment<SL, FIXUP>(d, sh, blockIdx.x, epoch);
 }
 __global__ __launch_bounds__(kSegThreads) void decompress_generic_kernel(TensorDesc d) { decompress_segment(d, blockIdx.x); }
 

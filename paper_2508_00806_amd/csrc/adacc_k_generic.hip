@@ -5,13 +5,21 @@
 namespace adacc {
 namespace ADACC_DT_NS {
 
-TailFn compress_generic_fn(bool count_only, bool topk) {
-  if (topk) return count_only ? compress_generic_kernel<true, true> : compress_generic_kernel<false, true>;
-  return count_only ? compress_generic_kernel<true, false> : compress_generic_kernel<false, false>;
+CompressFn compress_generic_fn(uint32_t tile_elems, bool fixup) {
+  const uint32_t slices = ((tile_elems + 7u) / 8u + kSegThreads - 1u) / kSegThreads;  // octets per thread
+  if (slices <= 2u) return fixup ? compress_generic_kernel<2, true> : compress_generic_kernel<2, false>;
+  if (slices <= 4u) return fixup ? compress_generic_kernel<4, true> : compress_generic_kernel<4, false>;
+  if (slices <= 6u) return fixup ? compress_generic_kernel<6, true> : compress_generic_kernel<6, false>;
+  return fixup ? compress_generic_kernel<8, true> : compress_generic_kernel<8, false>;
 }
 TailFn decompress_generic_fn() { return decompress_generic_kernel; }
 uint32_t generic_threads() { return kSegThreads; }
-uint32_t generic_lds_bytes(uint32_t tile_elems) { return kSegHeadBytes + 3u * tile_elems; }
+uint32_t generic_lds_bytes(uint32_t tile_elems, uint32_t gq, bool topk_groups) {
+  const uint32_t n_oct = (tile_elems + 7u) / 8u, n_grp = (tile_elems + gq - 1u) / gq;
+  const uint32_t words = 8u * n_oct + 8u * n_grp;     // a, b, g0, g1
+  const uint32_t patterns = topk_groups ? 24u * n_oct : 0u;  // 16-bit patterns and a byte per element
+  return kSegHeadBytes + (words > patterns ? words : patterns);
+}
 
 }  // namespace ADACC_DT_NS
 }  // namespace adacc

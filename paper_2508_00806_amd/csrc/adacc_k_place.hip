@@ -9,9 +9,16 @@ namespace ADACC_DT_NS {
 __device__ __forceinline__ void place_dispatch(const TensorDesc& d, uint32_t block, uint32_t epoch, PlaceShared& sh) {
   const bool e8 = (d.variant & 1u) != 0u;
   const bool from_sums = d.n_blocks > kPlaceDirectBlocks;
-  if (d.generic != 0u) {  // the fallback kernels only ask for the offsets: they write the outliers themselves
-    uint32_t n_here, total;
-    place_offsets_block(d, block, from_sums, sh, n_here, total);
+  if (d.generic != 0u) {
+    // The fallback kernels select a segment's outliers again themselves (a second launch), where the slot did
+    // not hold them or a TOPK group was irregular: here the offsets, and what the slots hold.
+    uint32_t n_here;
+    if (d.mode == kModeTopk) {
+      if (__hip_atomic_load(d.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) return;
+      place_moves_block(d, block, false, false, sh, n_here);
+    } else {
+      place_moves_block(d, block, from_sums, true, sh, n_here);
+    }
     return;
   }
   switch (d.variant >> 3) {

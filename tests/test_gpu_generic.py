@@ -1,7 +1,7 @@
 """GPU parity for group sizes outside the fast kernels' shapes (Section 3.2 groups the flat activation;
 nothing makes the groups powers of two): quantisation groups of any multiple of 8, statistics groups of any
 multiple of those up to 16384 - a whole 11008-wide row as one STD / TOPK group.  These run in fallback
-kernels (a workgroup per segment, plain loops over LDS); the bar is the same as everywhere: every section
+kernels (a workgroup per segment, octets in registers, one word per octet in LDS); the bar is the same as everywhere: every section
 of the blob and both reconstructions against the oracle, bit for bit."""
 import numpy as np
 import pytest
@@ -118,3 +118,61 @@ def test_batch_with_both_kinds_of_kernels():
                 assert_f32_matches(d.cpu().numpy(), of32)
             else:
                 assert_bf16_matches(bits_of(d), o16, m.dtype)
+
+
+def test_segments_through_the_slots_and_segments_selected_again():
+    """ABS / STD: a segment's outliers travel through its slot of the workspace (32 records) or, when it has more,
+    are written by the second launch; thresholds that give segments of both kinds side by side, none at all,
+    and only crowded ones."""
+    g = torch.Generator().manual_seed(41)
+    n = 4080 * 300 + 1000
+    x = torch.randn(n, generator=g).to(torch.bfloat16)
+    for gq, gs in ((24, 4080), (120, 120), (11008, 11008)):
+        for mode, th in (("abs", 2.7), ("abs", 3.6), ("abs", 1.0), ("std", 2.7), ("std", 3.5)):
+            md = dict(bits=8, quant_group=gq, asym=0, outlier_mode=mode, stat_group=gs if mode == "std" else 0,
+                      thresh=th, topk=0)
+            log(f"[generic] slots and second launch gq={gq} gs={gs} mode={mode} thresh={th}")
+            oc, blob, L, m = run_parity(x, md)
+            per_seg = np.bincount(oc.out_idx // L.tile_elems, minlength=L.n_tiles)
+            log(f"          outliers per segment: min {per_seg.min()} max {per_seg.max()}")
+    # both kinds in one tensor for certain: quiet segments and crowded ones in turn
+    y = x.clone()
+    seg = 4080
+    for s in range(0, n // seg, 3):
+        y[s * seg:(s + 1) * seg] *= 0.2
+    md = dict(bits=4, quant_group=24, asym=1, outlier_mode="abs", stat_group=0, thresh=2.2, topk=0)
+    oc, blob, L, m = run_parity(y, md)
+    per_seg = np.bincount(oc.out_idx // L.tile_elems, minlength=L.n_tiles)
+    assert per_seg.min() <= 32 < per_seg.max()
+    # a capacity that ends inside the slots' part and inside a crowded segment
+    for cap in (oc.n_out // 3, oc.n_out - 5):
+        run_parity(y, md, cap=cap, decompress=False)
+
+
+def test_topk_groups_with_more_values_that_are_not_finite_than_k():
+    """TOPK in the fallback kernels writes at offsets known in advance; a group with another count than k sends
+    the tensor through the placement and the second launch."""
+    for gq, gs, n in ((128, 11008, 11008 * 9 + 40), (24, 96, 96 * 500 + 24), (1000, 1000, 1000 * 40)):
+        b = random_bits(17, n)
+        b[(b & 0x7FFF) >= 0x7F80] = 0x3F80
+        clean = b.copy()
+        md = dict(bits=4, quant_group=gq, asym=0, outlier_mode="topk", stat_group=gs, thresh=0.0, topk=3)
+        log(f"[generic] topk regular gq={gq} gs={gs}")
+        oc, *_ = run_parity(from_bits(clean), md)
+        assert oc.n_out == 3 * (n // gs) + min(3, n % gs)
+        # five values that are not finite in one group in the middle, four in the last (short) group
+        g0 = (n // gs // 2) * gs
+        b[g0 + 1], b[g0 + 2], b[g0 + 9], b[g0 + gs - 1], b[g0 + gs // 2] = 0x7F80, 0xFF80, 0x7FC0, 0xFFFF, 0x7F81
+        b[n - 1], b[n - 2], b[n - 3], b[n - 4] = 0x7F80, 0x7F80, 0xFF80, 0x7FFF
+        log(f"[generic] topk irregular gq={gq} gs={gs}")
+        oc2, blob, L, m = run_parity(from_bits(b), md)
+        assert oc2.n_out > oc.n_out
+        # the same workspace for irregular and regular tensors in turn: the flag of an earlier call must not count
+        ws = adacc.alloc_workspace(adacc.workspace_bytes(m, n))
+        for bits_now, full in ((b, oc2), (clean, oc), (b, oc2), (clean, oc)):
+            want = oracle.compress(oracle_method(md), bits_now, cap=m.max_outliers)
+            want._full_idx = full.out_idx.astype(np.int64)
+            blob, L = adacc.alloc_blob(m, n)
+            adacc.compress(m, from_bits(bits_now).cuda(), blob, ws)
+            torch.cuda.synchronize()
+            compare_blob_with_oracle(blob, L, m, n, want)
