@@ -66,7 +66,7 @@ typedef struct adacc_method {
   uint32_t quant_group;  /* Gq, elements per scale: a multiple of 8 in [8, 16384]; the groups are cut from the
                             start of the flat tensor, the last one may be short.  Powers of two up to 4096
                             (with a stat_group of that kind) run in the fast kernels, everything else in
-                            fallback kernels that are 3 to 12 times slower                      */
+                            fallback kernels that are 2 to 4 times slower                       */
   uint32_t asym;         /* 0: symmetric (Eq. 2), 1: asymmetric (Eq. 3, adds one offset per group) */
   uint32_t scale_rule;   /* ADACC_SCALE_*                                                    */
   uint32_t outlier_mode; /* ADACC_OUTLIER_*                                                  */
