@@ -39,7 +39,8 @@ constexpr int kSegOctsMax = 8;  // octets per thread at most: 16384 elements / 8
 constexpr uint32_t kSegHeadWords = 48u;
 constexpr uint32_t kSegHeadBytes = 4u * kSegHeadWords;
 
-// The LDS of a workgroup, sized by the host for the method's segment length (n_oct octets, n_grp quantisation groups):
+// The LDS of a workgroup, sized by the host for the method's segment length (n_oct = 256 * SL octets, one for each
+// octet the threads hold, so that nobody has to ask whether its octet exists before it writes; n_grp quantisation groups):
 // [head: 48 words][a: n_oct words][b: n_oct words][g0: n_grp words][g1: n_grp words]
 //   head[0..7]   the wavefronts' maxima of a TOPK round (two sets of four, used in turn)
 //   head[8..39]  outliers of every (octet slice, wavefront)
@@ -57,8 +58,9 @@ struct SegmentShared {
   uint8_t* byte;  // TOPK over several groups: 1 = among the k largest
 };
 __device__ __forceinline__ uint32_t segment_octets(uint32_t tile_elems) { return (tile_elems + 7u) / 8u; }
+template <int SL>
 __device__ __forceinline__ SegmentShared segment_shared(unsigned char* lds, uint32_t tile_elems, uint32_t gq) {
-  const uint32_t n_oct = segment_octets(tile_elems);
+  constexpr uint32_t n_oct = (uint32_t)SL * kSegThreads;
   const uint32_t n_grp = (tile_elems + gq - 1u) / gq;
   SegmentShared sh;
   sh.head = reinterpret_cast<uint32_t*>(lds);
@@ -77,6 +79,7 @@ struct SegmentGeo {
   uint64_t first_elem;  // tensor index of the segment's first element (a multiple of 8)
   uint32_t cnt;         // elements of the segment (the tensor's last one may be short)
   uint32_t octs;        // octets that hold any of them
+  bool full;            // uniform: cnt is the method's segment length (then every octet below octs is whole)
 };
 // octet o = tid + 256 * j is the thread's octet j
 
@@ -276,15 +279,13 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
     // the three lowest levels of the pairwise sums inside the octet, the rest over the octets' words
 #pragma unroll
     for (int j = 0; j < SL; ++j) {
-      const uint32_t o = tid + (uint32_t)j * kSegThreads;
-      if (o < g.octs) {
-        float v[kOct];
-        widen_row(raw[j], v);
-        sh.a[o] = __float_as_uint(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
+      const uint32_t o = tid + (uint32_t)j * kSegThreads;  // (an octet that does not exist holds zeros; its words are not read)
+      float v[kOct];
+      widen_row(raw[j], v);
+      sh.a[o] = __float_as_uint(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
 #pragma unroll
-        for (int e = 0; e < kOct; ++e) v[e] = v[e] * v[e];
-        sh.b[o] = __float_as_uint(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
-      }
+      for (int e = 0; e < kOct; ++e) v[e] = v[e] * v[e];
+      sh.b[o] = __float_as_uint(((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7])));
     }
     __syncthreads();
     const uint32_t opg = d.gs / (uint32_t)kOct;
@@ -303,18 +304,19 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
     });
     __syncthreads();
     const float r = group_reciprocal(opg);
+    const uint32_t last_grp = (g.octs - 1u) / opg;  // uniform
 #pragma unroll
     for (int j = 0; j < SL; ++j) {
       const uint32_t o = tid + (uint32_t)j * kSegThreads;
-      if (o < g.octs) {
-        const float limit = __uint_as_float(sh.g0[group_of(o, r)]);
-        const float top = widen_lo(omag[j]);
-        if (!(top * top <= limit)) {  // the square is monotonic: no element passes where the largest magnitude does not
+      // (zeros - what does not exist - pass no limit: a limit is never negative)
+      const uint32_t grp = group_of(o, r);
+      const float limit = __uint_as_float(sh.g0[grp < last_grp ? grp : last_grp]);
+      const float top = widen_lo(omag[j]);
+      if (!(top * top <= limit)) {  // the square is monotonic: no element passes where the largest magnitude does not
 #pragma unroll
-          for (int e = 0; e < kOct; ++e) {
-            const float v = ADACC_ELEM_F32(raw[j], e);
-            mask[j] |= (v * v > limit ? 1u : 0u) << e;
-          }
+        for (int e = 0; e < kOct; ++e) {
+          const float v = ADACC_ELEM_F32(raw[j], e);
+          mask[j] |= (v * v > limit ? 1u : 0u) << e;
         }
       }
     }
@@ -329,8 +331,8 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
       for (int j = 0; j < SL; ++j) {
         const uint32_t o = tid + (uint32_t)j * kSegThreads;
         // whole octets (all but a tensor's ragged end): every element exists, the largest magnitude is known
-        const uint32_t nv = octet_valid(g, o);
-        okey[j] = nv == (uint32_t)kOct ? (omag[j] << 16) | (0xFFFFu - o) : octet_key(raw[j], 0u, o, nv);
+        if (g.full) okey[j] = o < g.octs ? (omag[j] << 16) | (0xFFFFu - o) : 0u;  // uniform
+        else okey[j] = octet_key(raw[j], 0u, o, octet_valid(g, o));
         best = okey[j] > best ? okey[j] : best;
       }
       const uint32_t rounds = d.topk < g.cnt ? d.topk : g.cnt;
@@ -474,29 +476,37 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
   const uint32_t tid = threadIdx.x;
   const uint32_t opg = d.gq / (uint32_t)kOct;
   const uint64_t first_group = g.first_elem / d.gq;
+  // (an octet that does not exist writes a word that nobody reads)
 #pragma unroll
   for (int j = 0; j < SL; ++j) {
     const uint32_t o = tid + (uint32_t)j * kSegThreads;
-    if (o < g.octs) {
-      if constexpr (!ASYM) {
-        sh.a[o] = omag[j];  // what does not exist is zero and cannot raise the maximum
+    if constexpr (!ASYM) {
+      sh.a[o] = omag[j];  // elements that do not exist are zero and cannot raise the maximum
+    } else {
+      int32_t hi = float_key(widen_lo(raw[j][0])), lo = hi;  // element 0 of an octet that exists exists
+      if (g.full) {  // uniform
+#pragma unroll
+        for (int e = 1; e < kOct; ++e) {
+          const int32_t k = float_key(ADACC_ELEM_F32(raw[j], e));
+          hi = k > hi ? k : hi;
+          lo = k < lo ? k : lo;
+        }
       } else {
         const uint32_t nv = octet_valid(g, o);
-        int32_t hi = float_key(widen_lo(raw[j][0])), lo = hi;  // element 0 exists
 #pragma unroll
         for (int e = 1; e < kOct; ++e) {
           const int32_t k = float_key(ADACC_ELEM_F32(raw[j], e));
           hi = ((uint32_t)e < nv && k > hi) ? k : hi;
           lo = ((uint32_t)e < nv && k < lo) ? k : lo;
         }
-        sh.a[o] = (uint32_t)hi;
-        sh.b[o] = (uint32_t)lo;
       }
+      sh.a[o] = (uint32_t)hi;
+      sh.b[o] = (uint32_t)lo;
     }
   }
   __syncthreads();
-  // the groups' extremes to g0 (g1); every thread then forms D / max (and the offset) of its octets' groups
-  // itself - once per change of group along its octets - instead of a few lanes doing it for all
+  // the groups' extremes to g0 (g1); every thread then forms D / max (and the offset) for each of its octets
+  // itself instead of a few lanes doing it for all
   if constexpr (!ASYM) {
     groups_tree<uint32_t>(sh, sh.a, g.octs, opg, 0u, OpUMax(), [&](uint32_t grp, uint32_t mag) { sh.g0[grp] = mag; });
   } else {
@@ -505,34 +515,38 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
   }
   __syncthreads();
   const float recip = group_reciprocal(opg);
-  uint32_t have = 0xFFFFFFFFu;  // the group the values below belong to
-  float scl = 0.0f, inv = 0.0f, off = 0.0f;
+  const uint32_t last_grp = (g.octs - 1u) / opg;  // uniform
 #pragma unroll
   for (int j = 0; j < SL; ++j) {
     const uint32_t o = tid + (uint32_t)j * kSegThreads;
+    // everything but the stores also for an octet that does not exist (it takes the last group's values)
+    uint32_t grp = group_of(o, recip);
+    grp = grp < last_grp ? grp : last_grp;
+    float scl, inv, off = 0.0f;
+    if constexpr (!ASYM) scale_sym_clean(d, mag_bits32(sh.g0[grp]), scl, inv);
+    else group_scale<true>(d, 0u, (int32_t)sh.g0[grp], (int32_t)sh.g1[grp], scl, inv, off);
+    uint32_t c[kOct];
+#pragma unroll
+    for (int e = 0; e < kOct; ++e) {
+      const float y = ADACC_ELEM_F32(raw[j], e);
+      c[e] = code_bits<Q, ASYM>(ASYM ? y - off : y, inv);  // symmetric codes cannot pass the lower bound
+    }
+    uint2 w8 = make_uint2(0u, 0u);
+    uint32_t w4 = 0u;
+    if constexpr (BITS == 8) {
+      w8.x = pack_bytes4(c[0], c[1], c[2], c[3]);
+      w8.y = pack_bytes4(c[4], c[5], c[6], c[7]);
+    } else {
+      w4 = pack_nibbles8(c);
+    }
     if (o < g.octs) {
-      const uint32_t grp = group_of(o, recip);
-      if (grp != have) {
-        if constexpr (!ASYM) group_scale<false>(d, mag_bits32(sh.g0[grp]), 0, 0, scl, inv, off);
-        else group_scale<true>(d, 0u, (int32_t)sh.g0[grp], (int32_t)sh.g1[grp], scl, inv, off);
-        have = grp;
-      }
       if (grp * opg == o) {  // the group's first octet
         d.scales[first_group + grp] = scl;
         if constexpr (ASYM) d.zp[first_group + grp] = off;
       }
-      uint32_t c[kOct];
-#pragma unroll
-      for (int e = 0; e < kOct; ++e) {
-        const float y = ADACC_ELEM_F32(raw[j], e);
-        c[e] = code_bits<Q, ASYM>(ASYM ? y - off : y, inv);  // symmetric codes cannot pass the lower bound
-      }
-      const uint32_t nv = octet_valid(g, o);
       const uint64_t e0 = g.first_elem + (uint64_t)o * kOct;
+      const uint32_t nv = g.full ? (uint32_t)kOct : octet_valid(g, o);
       if constexpr (BITS == 8) {
-        uint2 w8;
-        w8.x = pack_bytes4(c[0], c[1], c[2], c[3]);
-        w8.y = pack_bytes4(c[4], c[5], c[6], c[7]);
         if (nv == (uint32_t)kOct) {
           ADACC_STORE8(d.codes + e0, w8);
         } else {  // the tensor's ragged end, byte by byte
@@ -541,7 +555,6 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
             if ((uint32_t)e < nv) d.codes[e0 + e] = (uint8_t)((e < 4 ? w8.x : w8.y) >> (8 * (e & 3)));
         }
       } else {
-        const uint32_t w4 = pack_nibbles8(c);
         if (nv == (uint32_t)kOct) {
           ADACC_STORE4(d.codes + (e0 >> 1), w4);
         } else {  // an odd end: the high nibble of the last byte is 0
@@ -559,9 +572,21 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
   }
 }
 
+// The kernel's first argument (the tensor's descriptor, about fifty words) read again from the kernel argument
+// segment, behind a barrier for the compiler: what a phase needs of it is then loaded (scalar loads) where the
+// phase begins.  Otherwise all of it is loaded ahead of everything and, more than the scalar registers hold, is
+// parked in lanes of vector registers, from where every use costs a lane read.
+__device__ __forceinline__ const TensorDesc& descriptor_again() {
+  typedef const __attribute__((address_space(4))) TensorDesc* KernargDesc;
+  KernargDesc p = (KernargDesc)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(p));
+  return *(const TensorDesc*)p;
+}
+
 // One segment (d.tile_elems elements, the last one of the tensor may be short).
 // FIXUP: the second launch - only the outliers, straight to the stream at the offsets the placement kernel
 // has written, and only where the first launch could not place them.
+// d: the kernel's first argument
 template <int SL, bool FIXUP>
 __device__ __forceinline__ void compress_segment(const TensorDesc& d, SegmentShared& sh, uint32_t seg, uint32_t epoch) {
   const uint32_t tid = threadIdx.x;
@@ -578,13 +603,14 @@ __device__ __forceinline__ void compress_segment(const TensorDesc& d, SegmentSha
   const uint64_t left = d.numel - g.first_elem;
   g.cnt = left < (uint64_t)d.tile_elems ? (uint32_t)left : d.tile_elems;
   g.octs = (g.cnt + (uint32_t)kOct - 1u) / (uint32_t)kOct;
+  g.full = g.cnt == d.tile_elems && (d.tile_elems & 7u) == 0u;
   uint32_t raw[SL][4];
   segment_load(d, g, raw);
   uint32_t mask[SL], omag[SL];
 #pragma unroll
   for (int j = 0; j < SL; ++j) omag[j] = octet_magnitude(raw[j]);
   if (d.mode != kModeNone) {
-    segment_select(d, g, sh, raw, omag, mask);
+    segment_select(descriptor_again(), g, sh, raw, omag, mask);
 #pragma unroll
     for (int j = 0; j < SL; ++j)  // what cannot be quantised at all is always kept exactly
       if (omag[j] >= kNonfiniteMag) mask[j] |= octet_nonfinite(raw[j]);
@@ -620,6 +646,7 @@ __device__ __forceinline__ void compress_segment(const TensorDesc& d, SegmentSha
     }
   }
   if constexpr (!FIXUP) {
+    const TensorDesc& d = descriptor_again();
     // a5: from here on the outliers, and every value that is not finite, count as zero
 #pragma unroll
     for (int j = 0; j < SL; ++j) {
@@ -708,7 +735,7 @@ constexpr int generic_min_waves() { return SL <= 2 ? 8 : SL <= 4 ? 6 : SL <= 6 ?
 template <int SL, bool FIXUP>
 __global__ __launch_bounds__(kSegThreads, (generic_min_waves<SL>())) void compress_generic_kernel(TensorDesc d, uint32_t epoch) {
   extern __shared__ __attribute__((aligned(16))) unsigned char segment_lds[];
-  SegmentShared sh = segment_shared(segment_lds, d.tile_elems, d.gq);
+  SegmentShared sh = segment_shared<SL>(segment_lds, d.tile_elems, d.gq);
   compress_segment<SL, FIXUP>(d, sh, blockIdx.x, epoch);
 }
 __global__ __launch_bounds__(kSegThreads) void decompress_generic_kernel(TensorDesc d) { decompress_segment(d, blockIdx.x); }

@@ -15,7 +15,9 @@ CompressFn compress_generic_fn(uint32_t tile_elems, bool fixup) {
 TailFn decompress_generic_fn() { return decompress_generic_kernel; }
 uint32_t generic_threads() { return kSegThreads; }
 uint32_t generic_lds_bytes(uint32_t tile_elems, uint32_t gq, bool topk_groups) {
-  const uint32_t n_oct = (tile_elems + 7u) / 8u, n_grp = (tile_elems + gq - 1u) / gq;
+  const uint32_t slices = ((tile_elems + 7u) / 8u + kSegThreads - 1u) / kSegThreads;
+  const uint32_t sl = slices <= 2u ? 2u : slices <= 4u ? 4u : slices <= 6u ? 6u : 8u;  // the kernel compress_generic_fn picks
+  const uint32_t n_oct = sl * kSegThreads, n_grp = (tile_elems + gq - 1u) / gq;
   const uint32_t words = 8u * n_oct + 8u * n_grp;     // a, b, g0, g1
   const uint32_t patterns = topk_groups ? 24u * n_oct : 0u;  // 16-bit patterns and a byte per element
   return kSegHeadBytes + (words > patterns ? words : patterns);
