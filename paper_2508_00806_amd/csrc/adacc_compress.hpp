@@ -1432,8 +1432,9 @@ __device__ __forceinline__ void reselect_tile(const TensorDesc& d, uint32_t tile
 // last tile the total and the overflow flag.  Leaves in sh.excl the offsets relative to the block (and the
 // block's total behind them).  Returns the number of outliers before the block; n_here: tiles of the block.
 // `from_sums`: the counts of the blocks are in d.block_sum (else the counts of the tiles are added up)
+// mine: outliers of this thread's tile
 __device__ __forceinline__ uint32_t place_offsets_block(const TensorDesc& d, uint32_t block, bool from_sums, PlaceShared& sh,
-                                                        uint32_t& n_here, uint32_t& total) {
+                                                        uint32_t& n_here, uint32_t& total, uint32_t& mine) {
   const uint32_t tid = threadIdx.x;
   const uint32_t first = block * (uint32_t)kPlaceTiles;
   // outliers of all tiles before this block
@@ -1441,6 +1442,7 @@ __device__ __forceinline__ uint32_t place_offsets_block(const TensorDesc& d, uin
   // this thread's tile
   const uint32_t t = first + tid;
   const uint32_t c = t < d.n_tiles ? d.cnt[t] : 0u;
+  mine = c;
   // exclusive scan over the workgroup: inside the wavefront by shuffles, across wavefronts through LDS
   uint32_t incl = c;
 #pragma unroll
@@ -1476,29 +1478,43 @@ __device__ __forceinline__ uint32_t place_offsets_block(const TensorDesc& d, uin
 // thread at a time, so that their loads overlap.  Tiles with more outliers than a slot takes are left out.
 // Returns the number of outliers before the block; n_here: tiles of the block.  `move`: false = offsets only
 __device__ __forceinline__ uint32_t place_moves_block(const TensorDesc& d, uint32_t block, bool from_sums, bool move,
-                                                      PlaceShared& sh, uint32_t& n_here) {
+                                                      PlaceShared& sh, uint32_t& n_here, uint32_t& mine) {
   const uint32_t tid = threadIdx.x;
   const uint32_t first = block * (uint32_t)kPlaceTiles;
   uint32_t total;
-  const uint32_t base = place_offsets_block(d, block, from_sums, sh, n_here, total);
+  const uint32_t base = place_offsets_block(d, block, from_sums, sh, n_here, total, mine);
   __syncthreads();
   if (move) {
     for (uint32_t p0 = 0u; p0 < total; p0 += 4u * (uint32_t)kPlaceThreads) {
       uint64_t src[4];
       uint32_t dst[4];
       bool ok[4];
+      // last tile j with excl[j] <= p (tiles without outliers share their successor's offset): the four
+      // bisections step together, so that a step is one round trip to LDS for all of them (a block has at
+      // most 2^8 tiles)
+      uint32_t lo[4], hi[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { lo[k] = 0u; hi[k] = n_here; }
+#pragma unroll
+      for (int step = 0; step < 8; ++step) {
+        uint32_t mid[4], at[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { mid[k] = (lo[k] + hi[k]) >> 1; at[k] = sh.excl[mid[k]]; }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t p = p0 + (uint32_t)k * (uint32_t)kPlaceThreads + tid;
+          if (hi[k] - lo[k] > 1u) {
+            if (at[k] <= p) lo[k] = mid[k]; else hi[k] = mid[k];
+          }
+        }
+      }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const uint32_t p = p0 + (uint32_t)k * (uint32_t)kPlaceThreads + tid;
-        uint32_t lo = 0u, hi = n_here;  // last tile j with excl[j] <= p (tiles without outliers share their successor's offset)
-        while (hi - lo > 1u) {
-          const uint32_t mid = (lo + hi) >> 1;
-          if (sh.excl[mid] <= p) lo = mid; else hi = mid;
-        }
-        const uint32_t n_tile = sh.excl[lo + 1u] - sh.excl[lo];
+        const uint32_t n_tile = sh.excl[lo[k] + 1u] - sh.excl[lo[k]];
         dst[k] = base + p;
         ok[k] = p < total && n_tile <= (uint32_t)kSlot && dst[k] < d.cap;
-        src[k] = ok[k] ? (uint64_t)(first + lo) * (uint64_t)kSlot + (p - sh.excl[lo]) : 0ull;
+        src[k] = ok[k] ? (uint64_t)(first + lo[k]) * (uint64_t)kSlot + (p - sh.excl[lo[k]]) : 0ull;
       }
       uint2 rec[4];
 #pragma unroll
@@ -1517,9 +1533,10 @@ __device__ __forceinline__ void place_block(const TensorDesc& d, uint32_t block,
                                             PlaceShared& sh) {
   const uint32_t tid = threadIdx.x;
   const uint32_t first = block * (uint32_t)kPlaceTiles;
-  uint32_t n_here;
-  const uint32_t base = place_moves_block(d, block, from_sums, !reselect_all, sh, n_here);
+  uint32_t n_here, mine;
+  const uint32_t base = place_moves_block(d, block, from_sums, !reselect_all, sh, n_here, mine);
   // tiles whose outliers are not (all) in a slot: once more from the source, a wavefront per tile
+  if (__syncthreads_or(mine > (reselect_all ? 0u : (uint32_t)kSlot) ? 1 : 0) == 0) return;  // the usual case: none
   const uint32_t w = __builtin_amdgcn_readfirstlane(tid / kWave);
   for (uint32_t j = w; j < n_here; j += (uint32_t)(kPlaceThreads / kWave)) {
     const uint32_t n_tile = sh.excl[j + 1u] - sh.excl[j];

@@ -12,12 +12,12 @@ __device__ __forceinline__ void place_dispatch(const TensorDesc& d, uint32_t blo
   if (d.generic != 0u) {
     // The fallback kernels select a segment's outliers again themselves (a second launch), where the slot did
     // not hold them or a TOPK group was irregular: here the offsets, and what the slots hold.
-    uint32_t n_here;
+    uint32_t n_here, mine;
     if (d.mode == kModeTopk) {
       if (__hip_atomic_load(d.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) return;
-      place_moves_block(d, block, false, false, sh, n_here);
+      place_moves_block(d, block, false, false, sh, n_here, mine);
     } else {
-      place_moves_block(d, block, from_sums, true, sh, n_here);
+      place_moves_block(d, block, from_sums, true, sh, n_here, mine);
     }
     return;
   }
