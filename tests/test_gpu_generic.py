@@ -176,3 +176,14 @@ def test_topk_groups_with_more_values_that_are_not_finite_than_k():
             adacc.compress(m, from_bits(bits_now).cuda(), blob, ws)
             torch.cuda.synchronize()
             compare_blob_with_oracle(blob, L, m, n, want)
+
+
+@pytest.mark.parametrize("mode", ["none", "abs", "std", "topk"])
+def test_tensors_shorter_than_an_octet_and_last_groups_shorter_than_k(mode):
+    for gq, gs, n in ((24, 24, 3), (24, 96, 8), (8, 16, 9), (128, 11008, 11008 * 2 + 3), (24, 96, 96 * 10 + 2),
+                      (16384, 16384, 16384 + 1), (8, 16384, 16384 * 2 - 7)):
+        for bits, asym in ((4, 0), (8, 1)):
+            md = dict(bits=bits, quant_group=gq, asym=asym, outlier_mode=mode, stat_group=gs,
+                      thresh={"abs": 1.5, "std": 1.5}.get(mode, 0.0), topk=5 if mode == "topk" else 0)
+            log(f"[generic] short ends mode={mode} gq={gq} gs={gs} n={n} bits={bits} asym={asym}")
+            run_parity(tensor(n % 1000 + 3, n, 0), md)
