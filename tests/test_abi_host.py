@@ -91,7 +91,8 @@ BAD = [
 
 def test_group_sizes_of_the_fallback_kernels(L):
     """Quantisation groups of any multiple of 8 and statistics groups up to 16384: the tile is the largest
-    multiple of the larger group up to 4096 (the group itself beyond that); no slots in the workspace."""
+    multiple of the larger group up to 4096 (the group itself beyond that); the workspace as for the tile kernels:
+    counts and the flag, and for ABS / STD the blocks' sums and a slot of 32 records per segment."""
     a = lambda v: (v + 255) // 256 * 256
     m = Method(bits=8, quant_group=48)
     lay = adacc.layout_of(m, 10000)
@@ -100,9 +101,10 @@ def test_group_sizes_of_the_fallback_kernels(L):
     row = Method(bits=4, quant_group=128, outlier_mode=adacc.OUTLIER_TOPK, stat_group=11008, topk=8, max_outliers=800)
     lay = adacc.layout_of(row, 11008 * 100)
     assert lay.tile_elems == 11008 and lay.n_tiles == 100
-    assert adacc.workspace_bytes(row, 11008 * 100) == a(4 * 100) + 256 + a(4 * 1)
+    assert adacc.workspace_bytes(row, 11008 * 100) == a(4 * 100) + 256
     big = Method(bits=8, quant_group=8192, outlier_mode=adacc.OUTLIER_ABS, thresh=1.0, max_outliers=10)
     assert adacc.layout_of(big, 8192 * 5 + 1).tile_elems == 8192 and adacc.layout_of(big, 8192 * 5 + 1).n_tiles == 6
+    assert adacc.workspace_bytes(big, 8192 * 5 + 1) == a(4 * 6) + 256 + a(4 * 1) + a(8 * 32 * 6)
     cm = adacc.ChannelMethod(bits=4, quant_group=48, max_channels=4)
     with pytest.raises(adacc.AdaccError):
         adacc.channel_layout_of(cm, 12, 96)  # the channel scheme keeps to powers of two
