@@ -356,3 +356,14 @@ def test_noalloc_limit_is_checked_on_the_host(L):
             assert rc == want and "limit" in adacc.strerror(rc)
         else:
             assert rc in (adacc.ENULL, adacc.EHIP)  # past the limit check: stopped by the NULL pointers (or by the missing device)
+
+
+def test_group_of_an_octet_by_reciprocal_is_exact():
+    """The fallback kernels find the group of octet o as (uint32)(float(o) * r), r = RN(1 / octets per group) moved up
+    three units in the last place.  Claimed exact for every o < 2048 and every group of 1 .. 2048 octets: all of them."""
+    import numpy as np
+    o = np.arange(2048, dtype=np.uint32)
+    for opg in range(1, 2049):
+        r = np.array([np.float32(1) / np.float32(opg)], dtype=np.float32)
+        r = (r.view(np.uint32) + np.uint32(3)).view(np.float32)[0]
+        assert np.array_equal((o.astype(np.float32) * r).astype(np.uint32), o // opg), opg
