@@ -9,10 +9,10 @@
 // registers (one 16-byte load each, a wavefront's load is 1 KiB of consecutive memory); what the groups need
 // from all their octets - the pairwise sums of the STD rule, the largest magnitude or the extremes of a
 // quantisation group - goes through one word per octet in LDS and is reduced there by as many adjacent lanes
-// as the group has octets (rounded up to a power of two; a wavefront per group beyond 64 octets).  The
-// definitions are those of the fast kernels: canonical pairwise sums (pad to a power of two, add neighbours
-// level by level), mean and variance over the group's own count, the k largest by (magnitude, lower index),
-// D / max by one IEEE division per group, the same rounding of the codes.
+// as the group has octets (rounded up to a power of two; a wavefront per group beyond 64 octets, the whole
+// workgroup beyond 128).  The definitions are those of the fast kernels: canonical pairwise sums (pad to a power
+// of two, add neighbours level by level), mean and variance over the group's own count, the k largest by
+// (magnitude, lower index), the correctly rounded D / max, the same rounding of the codes.
 //
 // Outliers take the ways of the tile kernels.  ABS / STD: a segment's outliers go to its slot of kSlot
 // records in the workspace and its count to cnt[]; the placement kernels turn the counts into offsets and move
@@ -33,7 +33,7 @@ namespace ADACC_DT_NS {
 
 constexpr uint32_t kSegThreads = (uint32_t)kThreads;
 constexpr uint32_t kSegWaves = kSegThreads / (uint32_t)kWave;
-constexpr int kSegOctsMax = 8;  // octets per thread at most: 16384 elements / 8 / 256 threads
+// octets per thread at most: 16384 elements / 8 / 256 threads = 8
 // (the kernels exist for 2, 4, 6 and 8 octets per thread - SL - so that short segments do not pay for the registers of long ones)
 // bytes of LDS before the segment's arrays: the words the wavefronts meet in
 constexpr uint32_t kSegHeadWords = 48u;
@@ -46,7 +46,8 @@ constexpr uint32_t kSegHeadBytes = 4u * kSegHeadWords;
 //   head[8..39]  outliers of every (octet slice, wavefront)
 //   head[40..47] the wavefronts' results of a group that the whole workgroup reduces (two sets of four, used in turn)
 //   a, b         one word per octet: sums / sums of squares (STD), largest magnitude or extreme keys (quantisation)
-//   g0, g1       one word per group: the STD limit of a statistics group; D / max and the offset of a quantisation group
+//   g0, g1       one word per group: the STD limit (and the mean) of a statistics group; the largest magnitude or the
+//                extreme keys of a quantisation group
 // TOPK over several groups of a segment keeps the segment's 16-bit patterns (16 bytes per octet, from a on) and
 // behind them a byte per element instead, before a .. g1 are used (generic_lds_bytes gives the larger size).
 struct SegmentShared {
