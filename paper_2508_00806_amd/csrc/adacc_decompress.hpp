@@ -126,7 +126,24 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
     }
   }
 
-  // this tile's slice of the outlier stream and its first 64 entries
+  // This tile's slice of the outlier stream and its first 64 entries.  The entries can only be asked for when
+  // the slice is known, a second round trip to memory behind the first - except for TOPK, where the slice of
+  // tile T is [T * k * groups per tile, + k * groups per tile) unless some group held more than k values that
+  // are not finite: there the entries of that slice are asked for at once, together with the tile's offsets,
+  // and are used if the offsets turn out to be those.
+  const bool guess = has_outliers && d.mode == kModeTopk;  // uniform
+  uint32_t g0 = 0u, g1 = 0u, o_idx = 0u, o_val = 0u;
+  if (guess) {
+    const uint32_t per_tile = d.topk << (d.lgt - d.lgs);
+    g0 = per_tile * (tile >> d.ptr_shift);
+    g1 = g0 + per_tile;
+    g0 = g0 < d.cap ? g0 : d.cap;
+    g1 = g1 < d.cap ? g1 : d.cap;
+    if (g0 + (uint32_t)lane < g1) {
+      o_idx = (uint32_t)d.idx[g0 + (uint32_t)lane];
+      o_val = d.val[g0 + (uint32_t)lane];
+    }
+  }
   uint32_t p0 = 0u, p1 = 0u;
   if (has_outliers) {
     p0 = d.tile_ptr[tile >> d.ptr_shift];
@@ -136,10 +153,12 @@ __device__ __forceinline__ void decompress_tile(const TensorDesc& d, uint32_t ti
     if (p1 < p0) p1 = p0;
   }
   const bool patch = p1 > p0;  // uniform over the wavefront
-  uint32_t o_idx = 0u, o_val = 0u;
-  if (patch && p0 + (uint32_t)lane < p1) {
-    o_idx = (uint32_t)d.idx[p0 + (uint32_t)lane];
-    o_val = d.val[p0 + (uint32_t)lane];
+  if (patch && !(guess && p0 == g0 && p1 == g1)) {  // uniform
+    o_idx = 0u; o_val = 0u;
+    if (p0 + (uint32_t)lane < p1) {
+      o_idx = (uint32_t)d.idx[p0 + (uint32_t)lane];
+      o_val = d.val[p0 + (uint32_t)lane];
+    }
   }
 
   // ---- a9: unpack, dequantise, store.  A complete piece whose tile has at most 64 outliers (TOPK tensors:
