@@ -40,10 +40,14 @@ WORKLOAD_TEXT = {
     # second readings of two configurations (same tensors, another method)
     "c2b": "c2 read as top-1 of every 128-group: [16x2048,2048] bf16, int4 group-128, top-1 per 128",
     "c4b": "c4 with symmetric codes: [4,32,2048,2048] bf16, symmetric int8 per row, outliers > 0.05",
+    # the paper's own formats (Section 3.2: FP16 activations to INT4): c2's tensor and method in binary16
+    "c2h": "c2 in binary16 (FP16 -> INT4): [16x2048,2048] float16, int4 group-128 absmax, top-2 outliers per 2048-row",
 }
+# name -> (configuration whose tensor it takes, method or None for that configuration's own, 16-bit format: 0 bf16, 1 binary16)
 SECOND_READINGS = {
-    "c2b": ("c2", dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=128, thresh=0.0, topk=1)),
-    "c4b": ("c4", dict(bits=8, quant_group=2048, asym=0, outlier_mode="abs", stat_group=0, thresh=0.05, topk=0)),
+    "c2b": ("c2", dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=128, thresh=0.0, topk=1), 0),
+    "c4b": ("c4", dict(bits=8, quant_group=2048, asym=0, outlier_mode="abs", stat_group=0, thresh=0.05, topk=0), 0),
+    "c2h": ("c2", None, 1),
 }
 
 
@@ -95,13 +99,16 @@ class Workload:
         if name == "c5":
             specs = [(f"L{layer}.{tname}", x.shape[-1], md, x) for layer, tname, x, md in workloads.c5("cuda")]
         else:
-            base, md = SECOND_READINGS.get(name, (name, None))
+            base, md, fmt = SECOND_READINGS.get(name, (name, None, 0))
             x = workloads.make(base, "cuda")
+            if fmt == 1:
+                x = x.to(torch.float16)
             specs = [(name, x.shape[-1], md or workloads.METHODS[base], x)]
         self.mds = [s[2] for s in specs]
         self.numels = [s[3].numel() for s in specs]
-        self.methods = [adacc.method_from_dict(md, workloads.outlier_capacity(md, n, h))
-                        for (_, h, md, _), n in zip(specs, self.numels)]
+        self.methods = [adacc.method_from_dict(md, workloads.outlier_capacity(md, n, h),
+                                               dtype=adacc.DTYPE_F16 if x.dtype == torch.float16 else adacc.DTYPE_BF16)
+                        for (_, h, md, x), n in zip(specs, self.numels)]
         self.layouts = [adacc.layout_of(m, n) for m, n in zip(self.methods, self.numels)]
         self.batched = len(specs) > 1
         in_bytes = sum(2 * n for n, md in zip(self.numels, self.mds) if md is not None)
@@ -116,8 +123,8 @@ class Workload:
             self.src.append([sp[3].view(-1) if s == 0 else sp[3].view(-1).clone() for sp in specs])
             self.blob.append([None if md is None else adacc.alloc_blob(m, n)[0]
                               for m, n, md in zip(self.methods, self.numels, self.mds)])
-            self.dst.append([None if md is None else torch.empty(n, dtype=torch.bfloat16, device="cuda")
-                             for n, md in zip(self.numels, self.mds)])
+            self.dst.append([None if md is None else torch.empty(n, dtype=sp[3].dtype, device="cuda")
+                             for n, md, sp in zip(self.numels, self.mds, specs)])
         if self.batched:
             wsb = adacc.batch_workspace_bytes(self.methods, self.numels)
         else:
@@ -350,6 +357,7 @@ def cpu_baseline(name, seconds):
     interpreter lock, and every group lies inside a row, so the blocks are independent)."""
     from concurrent.futures import ThreadPoolExecutor
     import numpy as np
+    import torch
     import workloads
     import oracle
     host = host_description()
@@ -359,9 +367,11 @@ def cpu_baseline(name, seconds):
         parts = [(workloads.c5_tensor(t, "cpu", rows=rows), md) for t, _h, md in workloads.C5_LAYER if md is not None]
         sample = f"first {rows} rows of each of the 4 compressed tensors of layer 0"
     else:
-        base, md2 = SECOND_READINGS.get(name, (name, None))
+        base, md2, fmt = SECOND_READINGS.get(name, (name, None, 0))
         rows = {"c1": 4096, "c2": 4096, "c3": 512, "c4": 4096}[base]
         x = workloads.make(base, "cpu", rows=rows)
+        if fmt == 1:
+            x = x.to(torch.float16)
         parts = [(x, md2 or workloads.METHODS[base])]
         sample = f"{rows} rows ({x.numel()} elements) of the workload, same generator"
     work = []  # (method, bits of a block of whole rows)
@@ -369,7 +379,7 @@ def cpu_baseline(name, seconds):
     for x, md in parts:
         b = bits_of(x).reshape(x.shape[0], -1)
         total += b.size
-        om = oracle.method_from_dict(md)
+        om = oracle.method_from_dict(md, 0, 1 if x.dtype == torch.float16 else 0)
         step = max(1, b.shape[0] // (4 * cores))
         step += (-step) % max(1, -(-md["stat_group"] // b.shape[1]))  # whole statistics groups per block
         for r0 in range(0, b.shape[0], step):
@@ -685,7 +695,9 @@ def main():
                                                                       f"{props.multi_processor_count} CUs, {props.total_memory >> 30} GiB)",
                    "buffer_sets": main_res["buffer_sets"],
                    "tensors": main_res["tensors"], "n_outliers": main_res["n_outliers"],
-                   "storage": "bf16 in and out; int8 / int4 codes, binary32 scales, (int32, bf16) outliers in between"},
+                   "storage": ("binary16 in and out; int4 codes, binary32 scales, (int32, binary16) outliers in between"
+                               if SECOND_READINGS.get(a.workload, (0, 0, 0))[2] == 1 else
+                               "bf16 in and out; int8 / int4 codes, binary32 scales, (int32, bf16) outliers in between")},
         "hbm_frac_of_peak_roundtrip": main_res["roundtrip_hbm_frac_of_peak"],
         "compress": main_res["compress"],
         "decompress": main_res["decompress"],
