@@ -469,44 +469,132 @@ __device__ __forceinline__ uint32_t segment_emit(const SegmentGeo& g, SegmentSha
 
 // ---- a6 .. a8: scales (offsets) of the quantisation groups and the codes of the thread's octets, from which
 // outliers and values that are not finite are gone
+
+// a7 / a8 for the thread's octet j = octet o of the segment, in group grp (of the segment), whose extremes are
+// known: gm (symmetric: the largest magnitude) or the keys hi, lo (asymmetric).  Everything but the stores also
+// for an octet that does not exist.
+template <int BITS, bool ASYM>
+__device__ __forceinline__ void octet_quantise(const TensorDesc& d, const SegmentGeo& g, const uint32_t (&oct)[4], uint32_t o,
+                                               uint32_t grp, uint32_t opg, uint64_t first_group, uint32_t gm, int32_t hi,
+                                               int32_t lo) {
+  constexpr int Q = 1 << (BITS - 1);
+  float scl, inv, off = 0.0f;
+  if constexpr (!ASYM) scale_sym_clean(d, mag_bits32(gm), scl, inv);
+  else group_scale<true>(d, 0u, hi, lo, scl, inv, off);
+  uint32_t c[kOct];
+#pragma unroll
+  for (int e = 0; e < kOct; ++e) {
+    const float y = ADACC_ELEM_F32(oct, e);
+    c[e] = code_bits<Q, ASYM>(ASYM ? y - off : y, inv);  // symmetric codes cannot pass the lower bound
+  }
+  uint2 w8 = make_uint2(0u, 0u);
+  uint32_t w4 = 0u;
+  if constexpr (BITS == 8) {
+    w8.x = pack_bytes4(c[0], c[1], c[2], c[3]);
+    w8.y = pack_bytes4(c[4], c[5], c[6], c[7]);
+  } else {
+    w4 = pack_nibbles8(c);
+  }
+  if (o < g.octs) {
+    if (grp * opg == o) {  // the group's first octet
+      d.scales[first_group + grp] = scl;
+      if constexpr (ASYM) d.zp[first_group + grp] = off;
+    }
+    const uint64_t e0 = g.first_elem + (uint64_t)o * kOct;
+    const uint32_t nv = g.full ? (uint32_t)kOct : octet_valid(g, o);
+    if constexpr (BITS == 8) {
+      if (nv == (uint32_t)kOct) {
+        ADACC_STORE8(d.codes + e0, w8);
+      } else {  // the tensor's ragged end, byte by byte
+#pragma unroll
+        for (int e = 0; e < kOct - 1; ++e)
+          if ((uint32_t)e < nv) d.codes[e0 + e] = (uint8_t)((e < 4 ? w8.x : w8.y) >> (8 * (e & 3)));
+      }
+    } else {
+      if (nv == (uint32_t)kOct) {
+        ADACC_STORE4(d.codes + (e0 >> 1), w4);
+      } else {  // an odd end: the high nibble of the last byte is 0
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          if ((uint32_t)(2 * b) < nv) {
+            uint32_t v = (w4 >> (8 * b)) & 0xFFu;
+            if ((uint32_t)(2 * b + 1) >= nv) v &= 0x0Fu;
+            d.codes[(e0 >> 1) + b] = (uint8_t)v;
+          }
+        }
+      }
+    }
+  }
+}
+
+// the extreme keys of an octet's elements that exist (element 0 of an octet that exists does)
+__device__ __forceinline__ void octet_extreme_keys(const SegmentGeo& g, const uint32_t (&oct)[4], uint32_t o, int32_t& hi,
+                                                   int32_t& lo) {
+  hi = float_key(widen_lo(oct[0]));
+  lo = hi;
+  if (g.full) {  // uniform
+#pragma unroll
+    for (int e = 1; e < kOct; ++e) {
+      const int32_t k = float_key(ADACC_ELEM_F32(oct, e));
+      hi = k > hi ? k : hi;
+      lo = k < lo ? k : lo;
+    }
+  } else {
+    const uint32_t nv = octet_valid(g, o);
+#pragma unroll
+    for (int e = 1; e < kOct; ++e) {
+      const int32_t k = float_key(ADACC_ELEM_F32(oct, e));
+      hi = ((uint32_t)e < nv && k > hi) ? k : hi;
+      lo = ((uint32_t)e < nv && k < lo) ? k : lo;
+    }
+  }
+}
+
 // omag[j]: the largest magnitude of octet j as it is now
 template <int BITS, bool ASYM, int SL>
 __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const SegmentGeo& g, SegmentShared& sh,
                                                  const uint32_t (&raw)[SL][4], const uint32_t (&omag)[SL]) {
-  constexpr int Q = 1 << (BITS - 1);
   const uint32_t tid = threadIdx.x;
   const uint32_t opg = d.gq / (uint32_t)kOct;
   const uint64_t first_group = g.first_elem / d.gq;
-  // (an octet that does not exist writes a word that nobody reads)
+  if ((opg & (opg - 1u)) == 0u && opg <= (uint32_t)kWave) {  // uniform
+    // A group of 1, 2, 4, .. 64 octets is as many adjacent lanes of one wavefront (the segment starts on a group,
+    // and 256 octets are whole groups): the extremes meet by the xor butterfly, in registers.  An octet that does
+    // not exist brings the identity.
+    const uint32_t lg = (uint32_t)__builtin_ctz(opg);
+#pragma unroll
+    for (int j = 0; j < SL; ++j) {
+      const uint32_t o = tid + (uint32_t)j * kSegThreads;
+      if constexpr (!ASYM) {
+        const uint32_t gm = lanes_reduce_lg(omag[j], lg, OpUMax());  // (zeros cannot raise the maximum)
+        octet_quantise<BITS, false>(d, g, raw[j], o, o >> lg, opg, first_group, gm, 0, 0);
+      } else {
+        int32_t hi, lo;
+        octet_extreme_keys(g, raw[j], o, hi, lo);
+        hi = o < g.octs ? hi : (int32_t)0x80000000;
+        lo = o < g.octs ? lo : (int32_t)0x7FFFFFFF;
+        hi = lanes_reduce_lg(hi, lg, OpIMax());
+        lo = lanes_reduce_lg(lo, lg, OpIMin());
+        octet_quantise<BITS, true>(d, g, raw[j], o, o >> lg, opg, first_group, 0u, hi, lo);
+      }
+    }
+    return;
+  }
+  // Other groups: one word (two) per octet to LDS (an octet that does not exist writes a word that nobody reads) ..
 #pragma unroll
   for (int j = 0; j < SL; ++j) {
     const uint32_t o = tid + (uint32_t)j * kSegThreads;
     if constexpr (!ASYM) {
       sh.a[o] = omag[j];  // elements that do not exist are zero and cannot raise the maximum
     } else {
-      int32_t hi = float_key(widen_lo(raw[j][0])), lo = hi;  // element 0 of an octet that exists exists
-      if (g.full) {  // uniform
-#pragma unroll
-        for (int e = 1; e < kOct; ++e) {
-          const int32_t k = float_key(ADACC_ELEM_F32(raw[j], e));
-          hi = k > hi ? k : hi;
-          lo = k < lo ? k : lo;
-        }
-      } else {
-        const uint32_t nv = octet_valid(g, o);
-#pragma unroll
-        for (int e = 1; e < kOct; ++e) {
-          const int32_t k = float_key(ADACC_ELEM_F32(raw[j], e));
-          hi = ((uint32_t)e < nv && k > hi) ? k : hi;
-          lo = ((uint32_t)e < nv && k < lo) ? k : lo;
-        }
-      }
+      int32_t hi, lo;
+      octet_extreme_keys(g, raw[j], o, hi, lo);
       sh.a[o] = (uint32_t)hi;
       sh.b[o] = (uint32_t)lo;
     }
   }
   __syncthreads();
-  // the groups' extremes to g0 (g1); every thread then forms D / max (and the offset) for each of its octets
+  // .. the groups' extremes to g0 (g1); every thread then forms D / max (and the offset) for each of its octets
   // itself instead of a few lanes doing it for all
   if constexpr (!ASYM) {
     groups_tree<uint32_t>(sh, sh.a, g.octs, opg, 0u, OpUMax(), [&](uint32_t grp, uint32_t mag) { sh.g0[grp] = mag; });
@@ -520,56 +608,10 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
 #pragma unroll
   for (int j = 0; j < SL; ++j) {
     const uint32_t o = tid + (uint32_t)j * kSegThreads;
-    // everything but the stores also for an octet that does not exist (it takes the last group's values)
-    uint32_t grp = group_of(o, recip);
+    uint32_t grp = group_of(o, recip);  // (an octet that does not exist takes the last group's values)
     grp = grp < last_grp ? grp : last_grp;
-    float scl, inv, off = 0.0f;
-    if constexpr (!ASYM) scale_sym_clean(d, mag_bits32(sh.g0[grp]), scl, inv);
-    else group_scale<true>(d, 0u, (int32_t)sh.g0[grp], (int32_t)sh.g1[grp], scl, inv, off);
-    uint32_t c[kOct];
-#pragma unroll
-    for (int e = 0; e < kOct; ++e) {
-      const float y = ADACC_ELEM_F32(raw[j], e);
-      c[e] = code_bits<Q, ASYM>(ASYM ? y - off : y, inv);  // symmetric codes cannot pass the lower bound
-    }
-    uint2 w8 = make_uint2(0u, 0u);
-    uint32_t w4 = 0u;
-    if constexpr (BITS == 8) {
-      w8.x = pack_bytes4(c[0], c[1], c[2], c[3]);
-      w8.y = pack_bytes4(c[4], c[5], c[6], c[7]);
-    } else {
-      w4 = pack_nibbles8(c);
-    }
-    if (o < g.octs) {
-      if (grp * opg == o) {  // the group's first octet
-        d.scales[first_group + grp] = scl;
-        if constexpr (ASYM) d.zp[first_group + grp] = off;
-      }
-      const uint64_t e0 = g.first_elem + (uint64_t)o * kOct;
-      const uint32_t nv = g.full ? (uint32_t)kOct : octet_valid(g, o);
-      if constexpr (BITS == 8) {
-        if (nv == (uint32_t)kOct) {
-          ADACC_STORE8(d.codes + e0, w8);
-        } else {  // the tensor's ragged end, byte by byte
-#pragma unroll
-          for (int e = 0; e < kOct - 1; ++e)
-            if ((uint32_t)e < nv) d.codes[e0 + e] = (uint8_t)((e < 4 ? w8.x : w8.y) >> (8 * (e & 3)));
-        }
-      } else {
-        if (nv == (uint32_t)kOct) {
-          ADACC_STORE4(d.codes + (e0 >> 1), w4);
-        } else {  // an odd end: the high nibble of the last byte is 0
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            if ((uint32_t)(2 * b) < nv) {
-              uint32_t v = (w4 >> (8 * b)) & 0xFFu;
-              if ((uint32_t)(2 * b + 1) >= nv) v &= 0x0Fu;
-              d.codes[(e0 >> 1) + b] = (uint8_t)v;
-            }
-          }
-        }
-      }
-    }
+    if constexpr (!ASYM) octet_quantise<BITS, false>(d, g, raw[j], o, grp, opg, first_group, sh.g0[grp], 0, 0);
+    else octet_quantise<BITS, true>(d, g, raw[j], o, grp, opg, first_group, 0u, (int32_t)sh.g0[grp], (int32_t)sh.g1[grp]);
   }
 }
 
