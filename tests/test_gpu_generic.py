@@ -187,3 +187,67 @@ def test_tensors_shorter_than_an_octet_and_last_groups_shorter_than_k(mode):
                       thresh={"abs": 1.5, "std": 1.5}.get(mode, 0.0), topk=5 if mode == "topk" else 0)
             log(f"[generic] short ends mode={mode} gq={gq} gs={gs} n={n} bits={bits} asym={asym}")
             run_parity(tensor(n % 1000 + 3, n, 0), md)
+
+
+def test_the_largest_sizes_through_the_fallback_kernels():
+    """More than 2^32 elements without outliers (64-bit element, code and group offsets in the fallback kernels too),
+    and nearly 2^31 elements with outliers (32-bit signed indices; 195 000 rows of 11008 as STD and as TOPK groups:
+    segments through 762 placement blocks).  Oracle on segments sampled over the whole range."""
+    from test_gpu_parity import check_sampled
+    n = (1 << 32) + 24 * 1000 + 8
+    log(f"[generic] {n} elements without outliers, int8 in groups of 24")
+    x = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(99)
+    step = 1 << 28
+    for i0 in range(0, n, step):
+        x[i0:i0 + step].normal_(0.0, 1.5, generator=g)
+    dst = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    md = dict(bits=8, quant_group=24, asym=1, outlier_mode="none", stat_group=0, thresh=0.0, topk=0)
+    m = adacc_method(md, 0)
+    blob, L = adacc.alloc_blob(m, n)
+    adacc.compress(m, x, blob, None)
+    adacc.decompress(m, blob, dst)
+    torch.cuda.synchronize()
+    assert L.tile_elems == 4080 and L.n_tiles == (n + 4079) // 4080
+    check_sampled("fallback beyond 2^32", x, md, m, blob, L, dst, 24, 3)
+    lo = (L.n_tiles - 1) * 4080  # the last, short segment and its short last group
+    oc = oracle.compress(oracle_method(md), bits_of(x[lo:]))
+    sec = adacc.blob_sections(blob, L, m, n)
+    assert np.array_equal(sec["codes"][lo:].cpu().numpy(), oc.packed)
+    assert np.array_equal(sec["scales"][lo // 24:].cpu().numpy().view(np.uint32), oc.scale.view(np.uint32))
+    assert np.array_equal(sec["zp"][lo // 24:].cpu().numpy().view(np.uint32), oc.zp.view(np.uint32))
+    assert np.array_equal(bits_of(dst[lo:]), oracle.decompress(oc)[1])
+    del blob
+    torch.cuda.empty_cache()
+
+    rows = 195000
+    n2 = rows * 11008
+    assert n2 < (1 << 31)
+    x2, dst2 = x[:n2], dst[:n2]
+    x2[n2 - 3] = 900.0  # an outlier whose index is close to 2^31
+    for md, cap in ((dict(bits=8, quant_group=11008, asym=0, outlier_mode="std", stat_group=11008, thresh=4.0, topk=0), n2 // 4096),
+                    (dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=11008, thresh=0.0, topk=4), 4 * rows)):
+        log(f"[generic] {n2} elements, {md['outlier_mode']} over rows of 11008")
+        m = adacc_method(md, cap)
+        blob, L = adacc.alloc_blob(m, n2)
+        ws = adacc.alloc_workspace(adacc.workspace_bytes(m, n2))
+        adacc.compress(m, x2, blob, ws)
+        adacc.decompress(m, blob, dst2)
+        torch.cuda.synchronize()
+        assert L.tile_elems == 11008 and L.n_tiles == rows
+        st = check_sampled("fallback longest with outliers", x2, md, m, blob, L, dst2, 24, 8)
+        sec = adacc.blob_sections(blob, L, m, n2)
+        assert st[1] == 0 and (n2 - 3) in sec["idx"][st[0] - 4:st[0]].cpu().tolist()
+        if md["outlier_mode"] == "topk":
+            assert st[0] == 4 * rows
+        # the last row against the oracle on that slice (check_sampled leaves the last tile out)
+        lo = n2 - 11008
+        oc = oracle.compress(oracle_method(md), bits_of(x2[lo:]))
+        p0 = int(sec["tile_ptr"][rows - 1])
+        assert st[0] - p0 == oc.n_out
+        assert np.array_equal(sec["idx"][p0:st[0]].cpu().numpy().astype(np.int64), oc.out_idx.astype(np.int64) + lo)
+        assert np.array_equal(bits_of(dst2[lo:]), oracle.decompress(oc)[1])
+        del blob, ws
+        torch.cuda.empty_cache()
+    del x, dst, x2, dst2
+    torch.cuda.empty_cache()
