@@ -29,7 +29,10 @@ def inputs(seed, n):
     dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=2048, thresh=0.0, topk=2),
     dict(bits=8, quant_group=256, asym=1, outlier_mode="abs", stat_group=0, thresh=20.0, topk=0),
     dict(bits=4, quant_group=128, asym=0, outlier_mode="none", stat_group=0, thresh=0.0, topk=0),
-], ids=["std", "topk", "abs", "none"])
+    # the fallback kernels (dynamic LDS, a second launch for what the first could not place)
+    dict(bits=4, quant_group=128, asym=0, outlier_mode="topk", stat_group=11008, thresh=0.0, topk=3),
+    dict(bits=8, quant_group=24, asym=1, outlier_mode="std", stat_group=4080, thresh=2.5, topk=0),
+], ids=["std", "topk", "abs", "none", "fallback-topk", "fallback-std"])
 def test_compress_and_decompress_replayed_from_a_graph(md):
     n = 2048 * 333 + 640
     m = adacc_method(md, n // 8)
