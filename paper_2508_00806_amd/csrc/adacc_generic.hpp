@@ -42,7 +42,7 @@ constexpr uint32_t kSegHeadBytes = 4u * kSegHeadWords;
 // The LDS of a workgroup, sized by the host for the method's segment length (n_oct = 256 * SL octets, one for each
 // octet the threads hold, so that nobody has to ask whether its octet exists before it writes; n_grp quantisation groups):
 // [head: 48 words][a: n_oct words][b: n_oct words][g0: n_grp words][g1: n_grp words]
-//   head[0..7]   the wavefronts' maxima of a TOPK round (two sets of four, used in turn)
+//   head[0]      TOPK over a segment-wide group: entries in use of the list of candidate octets (in b)
 //   head[8..39]  outliers of every (octet slice, wavefront)
 //   head[40..47] the wavefronts' results of a group that the whole workgroup reduces (two sets of four, used in turn)
 //   a, b         one word per octet: sums / sums of squares (STD), largest magnitude or extreme keys (quantisation)
@@ -324,42 +324,106 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
     __syncthreads();  // a, b, g0, g1 are free again
   } else if (d.mode == kModeTopk) {
     if (d.gs >= d.tile_elems) {
-      // The segment is one group.  Every thread knows the key of each of its octets; a round is one maximum over
-      // the workgroup (the wavefronts meet in head[], two sets of words used in turn, so one barrier per round);
-      // the winner's key is unique, its owner takes the element and forms the octet's key again.
-      uint32_t okey[SL], best = 0u;
+      // The segment is one group.  The k largest elements lie in the k octets with the largest octet maxima (an
+      // element outside them is beaten by one element of each of them), and those octets are among the k best
+      // octets of every wavefront.  So: (1) every wavefront picks its k best octets by k rounds of a maximum over
+      // its own lanes - keys in registers, the winner's owner only zeroes one key -, (2) the four lists meet in LDS
+      // and every wavefront finds the k best octets overall by k rounds over the 4 k keys; the owner of each
+      // of them (3) writes the keys of its 8 elements to an entry of a list in LDS, and (4) every wavefront finds
+      // the k-th largest of those 8 k element keys, the threshold: an element is an outlier if its key reaches
+      // it.  Three barriers whatever k is, and no step where one thread works while the workgroup waits.
+      // Keys: magnitude above the reversed octet number resp. element index; 0 = nothing.
+      const uint32_t lane = (uint32_t)lane_id(), wave = tid / (uint32_t)kWave;
+      const uint32_t rounds = d.topk < g.cnt ? d.topk : g.cnt;  // at most 32
+      uint32_t okey[SL];
 #pragma unroll
       for (int j = 0; j < SL; ++j) {
         const uint32_t o = tid + (uint32_t)j * kSegThreads;
-        // whole octets (all but a tensor's ragged end): every element exists, the largest magnitude is known
-        if (g.full) okey[j] = o < g.octs ? (omag[j] << 16) | (0xFFFFu - o) : 0u;  // uniform
-        else okey[j] = octet_key(raw[j], 0u, o, octet_valid(g, o));
-        best = okey[j] > best ? okey[j] : best;
+        okey[j] = o < g.octs ? (omag[j] << 16) | (0xFFFFu - o) : 0u;  // (elements that do not exist are zeros: they do not raise omag)
       }
-      const uint32_t rounds = d.topk < g.cnt ? d.topk : g.cnt;
-      for (uint32_t r = 0; r < rounds; ++r) {  // uniform
-        const uint32_t w = wave_max_u32_scalar(best);
-        uint32_t* meet = sh.head + (r & 1u) * kSegWaves;
-        if (lane_id() == 0) meet[tid / (uint32_t)kWave] = w;
-        __syncthreads();
-        uint32_t win = meet[0];
+      {  // (1)
+        uint32_t live[SL], cand = 0u;
 #pragma unroll
-        for (uint32_t k = 1; k < kSegWaves; ++k) win = meet[k] > win ? meet[k] : win;
-        if (best == win) {  // one thread of the workgroup (the key of an octet with an element left is never zero)
-          best = 0u;
+        for (int j = 0; j < SL; ++j) live[j] = okey[j];
+        for (uint32_t r = 0; r < rounds; ++r) {  // uniform
+          uint32_t best = 0u;
 #pragma unroll
-          for (int j = 0; j < SL; ++j) {
-            const uint32_t o = tid + (uint32_t)j * kSegThreads;
-            if (okey[j] == win) {
-              const uint32_t nv = octet_valid(g, o);
-              mask[j] |= 1u << octet_take(raw[j], mask[j], win, nv);
-              okey[j] = octet_key(raw[j], mask[j], o, nv);
-            }
-            best = okey[j] > best ? okey[j] : best;
+          for (int j = 0; j < SL; ++j) best = live[j] > best ? live[j] : best;
+          const uint32_t w = wave_max_u32_scalar(best);
+#pragma unroll
+          for (int j = 0; j < SL; ++j) live[j] = live[j] == w ? 0u : live[j];
+          cand = lane == r ? w : cand;
+        }
+        if (lane < 32u) sh.a[wave * 32u + lane] = cand;
+        sh.b[tid] = 0u;  // the list of (3): 8 keys for each of up to 32 octets
+        if (tid == 0u) sh.head[0] = 0u;  // and the number of its entries in use
+      }
+      __syncthreads();
+      uint32_t least = 0u;  // the smallest key among the k best octets overall (0: there are fewer octets, all are taken)
+      {  // (2)
+        if (rounds <= 16u) {  // uniform: the first 16 keys of the four lists, one per lane
+          uint32_t c0 = sh.a[(lane >> 4) * 32u + (lane & 15u)];  // lane = 16 * wavefront + entry
+          for (uint32_t r = 0; r < rounds; ++r) {
+            least = wave_max_u32_scalar(c0);
+            c0 = c0 == least ? 0u : c0;
+          }
+        } else {
+          uint32_t c0 = sh.a[lane], c1 = sh.a[(uint32_t)kWave + lane];
+          for (uint32_t r = 0; r < rounds; ++r) {
+            least = wave_max_u32_scalar(c0 > c1 ? c0 : c1);
+            c0 = c0 == least ? 0u : c0;
+            c1 = c1 == least ? 0u : c1;
           }
         }
       }
-      __syncthreads();  // head[] is free again
+      // (3): which entry of the list an octet gets does not matter, a counter in LDS hands them out
+#pragma unroll
+      for (int j = 0; j < SL; ++j) {
+        if (okey[j] != 0u && okey[j] >= least) {  // at most k octets of the workgroup
+          const uint32_t o = tid + (uint32_t)j * kSegThreads;
+          const uint32_t nv = octet_valid(g, o);
+          const uint32_t entry = atomicAdd(&sh.head[0], 1u);
+#pragma unroll
+          for (int e = 0; e < kOct; ++e)
+            sh.b[entry * (uint32_t)kOct + (uint32_t)e] =
+                (uint32_t)e < nv ? (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (o * (uint32_t)kOct + (uint32_t)e)) : 0u;
+        }
+      }
+      __syncthreads();
+      uint32_t limit = 0u;
+      {  // (4)
+        // (never 0: the octets of (2) hold at least `rounds` elements)
+        if (rounds <= 8u) {  // uniform: at most 64 keys, one per lane
+          uint32_t c = sh.b[lane];
+          for (uint32_t r = 0; r < rounds; ++r) {
+            limit = wave_max_u32_scalar(c);
+            c = c == limit ? 0u : c;
+          }
+        } else {
+          uint32_t c[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) c[k] = sh.b[(uint32_t)k * (uint32_t)kWave + lane];
+          for (uint32_t r = 0; r < rounds; ++r) {
+            const uint32_t m0 = c[0] > c[1] ? c[0] : c[1], m1 = c[2] > c[3] ? c[2] : c[3];
+            limit = wave_max_u32_scalar(m0 > m1 ? m0 : m1);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) c[k] = c[k] == limit ? 0u : c[k];
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < SL; ++j) {
+        if (okey[j] != 0u && ((omag[j] << 16) | 0xFFFFu) >= limit) {  // few octets get here
+          const uint32_t o = tid + (uint32_t)j * kSegThreads;
+          const uint32_t nv = octet_valid(g, o);
+#pragma unroll
+          for (int e = 0; e < kOct; ++e) {
+            const uint32_t key = (ADACC_ELEM_MAG(raw[j], e) << 16) | (0xFFFFu - (o * (uint32_t)kOct + (uint32_t)e));
+            mask[j] |= ((uint32_t)e < nv && key >= limit ? 1u : 0u) << e;
+          }
+        }
+      }
+      __syncthreads();  // a, b are free again
     } else {
       // Several groups (of at most 2048 elements): the patterns go to LDS, a wavefront takes a group at a time
       // with the keys of its elements in registers (32 per lane at most), k rounds of a maximum over the wavefront.

@@ -56,6 +56,20 @@ def test_whole_rows_of_a_llama_mlp_activation_as_groups():
             assert oc.n_out == 11 * 48
 
 
+def test_topk_of_a_row_for_every_number_of_outliers_kept():
+    """TOPK over a segment-wide group finds its threshold through lists whose length depends on k (up to 8, up to 16,
+    up to 32 keys per wavefront): k = 1 .. 32 on rows with many equal magnitudes, and on rows shorter than k octets."""
+    b = random_bits(23, 11008 * 3 + 100)
+    b[::7] = (b[::7] & 0x8000) | 0x4120          # every seventh value has the same magnitude, either sign
+    b[11008:11008 + 40] = 0x7F7F                 # forty times the largest finite magnitude at the start of the second row
+    for k in (1, 2, 7, 8, 9, 15, 16, 17, 31, 32):
+        for n, gs in ((11008 * 3 + 100, 11008), (4104 * 2 + 9, 4104)):
+            md = dict(bits=4, quant_group=8, asym=0, outlier_mode="topk", stat_group=gs, thresh=0.0, topk=k)
+            log(f"[generic] topk k={k} n={n} gs={gs}")
+            oc, *_ = run_parity(from_bits(b[:n]), md)
+            assert oc.n_out == k * (n // gs) + min(k, n % gs)
+
+
 def test_values_that_are_not_finite_and_degenerate_groups():
     n = 1000 * 6
     b = random_bits(3, n)
