@@ -58,7 +58,6 @@ struct SegmentShared {
   uint32_t* g1;
   uint8_t* byte;  // TOPK over several groups: 1 = among the k largest
 };
-__device__ __forceinline__ uint32_t segment_octets(uint32_t tile_elems) { return (tile_elems + 7u) / 8u; }
 template <int SL>
 __device__ __forceinline__ SegmentShared segment_shared(unsigned char* lds, uint32_t tile_elems, uint32_t gq) {
   constexpr uint32_t n_oct = (uint32_t)SL * kSegThreads;
@@ -72,8 +71,6 @@ __device__ __forceinline__ SegmentShared segment_shared(unsigned char* lds, uint
   sh.byte = reinterpret_cast<uint8_t*>(sh.a) + 16u * n_oct;
   return sh;
 }
-
-__device__ __forceinline__ bool pattern_nonfinite(uint32_t pattern) { return (pattern & 0x7FFFu) >= kNonfiniteMag; }
 
 // What a thread knows of the segment and of its own octets
 struct SegmentGeo {
@@ -229,33 +226,6 @@ __device__ __forceinline__ uint32_t octet_nonfinite(const uint32_t (&oct)[4]) {
 #pragma unroll
   for (int e = 0; e < kOct; ++e) m |= (ADACC_ELEM_MAG(oct, e) >= kNonfiniteMag ? 1u : 0u) << e;
   return m;
-}
-
-// TOPK works on one key per octet: the largest magnitude among the octet's elements that exist (nv of them) and
-// are not taken yet, above the reversed number of the octet (never zero while such an element is left; 0 when
-// none is).  Among equal magnitudes the lower octet wins, and inside the octet the lower element (octet_take):
-// together the lower index.
-__device__ __forceinline__ uint32_t octet_key(const uint32_t (&oct)[4], uint32_t taken, uint32_t o, uint32_t nv) {
-  uint32_t best = 0u;
-  bool any = false;
-#pragma unroll
-  for (int e = 0; e < kOct; ++e) {
-    const uint32_t mag = ADACC_ELEM_MAG(oct, e);
-    const bool live = (uint32_t)e < nv && ((taken >> e) & 1u) == 0u;
-    best = (live && mag > best) ? mag : best;
-    any = any || live;
-  }
-  return any ? (best << 16) | (0xFFFFu - o) : 0u;
-}
-// the first element of the octet that exists, is not taken and has the magnitude of `key`
-__device__ __forceinline__ uint32_t octet_take(const uint32_t (&oct)[4], uint32_t taken, uint32_t key, uint32_t nv) {
-  uint32_t first = 0u;
-#pragma unroll
-  for (int e = kOct - 1; e >= 0; --e) {
-    const bool hit = (uint32_t)e < nv && ((taken >> e) & 1u) == 0u && ADACC_ELEM_MAG(oct, e) == (key >> 16);
-    first = hit ? (uint32_t)e : first;
-  }
-  return first;
 }
 
 // ---- a2 / a3: mask[j] bit e = element e of the thread's octet j is an outlier by the method's rule
