@@ -108,21 +108,6 @@ __device__ __forceinline__ T lanes_reduce_lg(T v, uint32_t lg, Op op) {
   return v;
 }
 
-// Binary tree over values that arrive one by one: partial sums of 1, 2, 4, .. values wait in s[]; after 2^m
-// values the result sits in s[m].
-template <class T, class Op>
-__device__ __forceinline__ void carry_in(T (&s)[4], uint32_t i, T v, Op op) {
-  bool placed = false;
-#pragma unroll
-  for (int l = 0; l < 3; ++l) {
-    if (!placed) {
-      if ((i >> l) & 1u) v = op(s[l], v);  // the earlier values on the left
-      else { s[l] = v; placed = true; }
-    }
-  }
-  if (!placed) s[3] = v;
-}
-
 // For every group of `opg` consecutive octets (the last group of the segment may have fewer; n_oct octets in
 // all): the balanced binary tree `op` over the group's words w[], padded with `pad` to the next power of two;
 // finish(group, result) is called by one thread per group.  Groups of up to 64 octets are taken by as many
@@ -163,16 +148,14 @@ __device__ __forceinline__ void groups_tree(SegmentShared& sh, const uint32_t* w
     for (uint32_t g = 0; g < n_grp; ++g) {  // uniform
       const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
       const uint32_t* wg = w + g * opg;
-      T s[4];
+      // the thread's `per` consecutive words as the tree over 8 with `pad` for the rest (the identity: same value)
+      T t[8];
 #pragma unroll
-      for (int l = 0; l < 4; ++l) s[l] = pad;
-      for (uint32_t i = 0; i < per; ++i) {  // uniform
+      for (uint32_t i = 0; i < 8u; ++i) {
         const uint32_t o = threadIdx.x * per + i;
-        carry_in(s, i, o < left ? __builtin_bit_cast(T, wg[o]) : pad, op);
+        t[i] = (i < per && o < left) ? __builtin_bit_cast(T, wg[o]) : pad;
       }
-      T v = s[0];
-#pragma unroll
-      for (int l = 1; l < 4; ++l) v = per == (1u << l) ? s[l] : v;
+      T v = op(op(op(t[0], t[1]), op(t[2], t[3])), op(op(t[4], t[5]), op(t[6], t[7])));
       v = lanes_reduce<kWave>(v, op);
       uint32_t* meet = sh.head + 40u + (g & 1u) * kSegWaves;
       if (lane == 0u) meet[wave] = __builtin_bit_cast(uint32_t, v);
