@@ -36,15 +36,15 @@ constexpr uint32_t kSegWaves = kSegThreads / (uint32_t)kWave;
 // octets per thread at most: 16384 elements / 8 / 256 threads = 8
 // (the kernels exist for 2, 4, 6 and 8 octets per thread - SL - so that short segments do not pay for the registers of long ones)
 // bytes of LDS before the segment's arrays: the words the wavefronts meet in
-constexpr uint32_t kSegHeadWords = 48u;
+constexpr uint32_t kSegHeadWords = 64u;
 constexpr uint32_t kSegHeadBytes = 4u * kSegHeadWords;
 
 // The LDS of a workgroup, sized by the host for the method's segment length (n_oct = 256 * SL octets, one for each
 // octet the threads hold, so that nobody has to ask whether its octet exists before it writes; n_grp quantisation groups):
-// [head: 48 words][a: n_oct words][b: n_oct words][g0: n_grp words][g1: n_grp words]
+// [head: 64 words][a: n_oct words][b: n_oct words][g0: n_grp words][g1: n_grp words]
 //   head[0]      TOPK over a segment-wide group: entries in use of the list of candidate octets (in b)
 //   head[8..39]  outliers of every (octet slice, wavefront)
-//   head[40..47] the wavefronts' results of a group that the whole workgroup reduces (two sets of four, used in turn)
+//   head[40..55] the wavefronts' results of a group that the whole workgroup reduces (two sets of eight, used in turn)
 //   a, b         one word per octet: sums / sums of squares (STD), largest magnitude or extreme keys (quantisation)
 //   g0, g1       one word per group: the STD limit (and the mean) of a statistics group; the largest magnitude or the
 //                extreme keys of a quantisation group
@@ -115,9 +115,11 @@ __device__ __forceinline__ T lanes_reduce_lg(T v, uint32_t lg, Op op) {
 // wavefront each; longer ones by the whole workgroup in turn, every thread folding the padded group's consecutive
 // words that fall to it first, the wavefronts' results meeting in head[40..47] (two sets, used in turn).
 // Called by all threads of the workgroup.  (For sums the padding adds +0.0 to partial sums, which changes no value.)
-template <class T, class Op, class Finish>
-__device__ __forceinline__ void groups_tree(SegmentShared& sh, const uint32_t* w, uint32_t n_oct, uint32_t opg, T pad,
-                                            Op op, Finish finish) {
+// TWO: the same for a second array w1 with its own operation at the same time (sums and sums of squares; maxima
+// and minima): finish(group, result of w0, result of w1).
+template <bool TWO, class T, class Op0, class Op1, class Finish>
+__device__ __forceinline__ void groups_tree(SegmentShared& sh, const uint32_t* w0, const uint32_t* w1, uint32_t n_oct,
+                                            uint32_t opg, T pad0, T pad1, Op0 op0, Op1 op1, Finish finish) {
   const uint32_t lane = (uint32_t)lane_id(), wave = threadIdx.x / (uint32_t)kWave;
   const uint32_t n_grp = (n_oct + opg - 1u) / opg;
   uint32_t lg = 0u;
@@ -128,41 +130,67 @@ __device__ __forceinline__ void groups_tree(SegmentShared& sh, const uint32_t* w
     for (uint32_t g0 = wave * per_wave; g0 < n_grp; g0 += kSegWaves * per_wave) {  // uniform
       const uint32_t g = g0 + (lane >> lg);
       const uint32_t o = g * opg + leaf;
-      T v = pad;
-      if (g < n_grp && leaf < opg && o < n_oct) v = __builtin_bit_cast(T, w[o]);
-      v = lanes_reduce_lg(v, lg, op);
-      if (g < n_grp && leaf == 0u) finish(g, v);
+      const bool there = g < n_grp && leaf < opg && o < n_oct;
+      T v0 = pad0, v1 = pad1;
+      if (there) v0 = __builtin_bit_cast(T, w0[o]);
+      if constexpr (TWO) { if (there) v1 = __builtin_bit_cast(T, w1[o]); }
+      v0 = lanes_reduce_lg(v0, lg, op0);
+      if constexpr (TWO) v1 = lanes_reduce_lg(v1, lg, op1);
+      if (g < n_grp && leaf == 0u) finish(g, v0, v1);
     }
   } else if (lg == 7u) {
     for (uint32_t g = wave; g < n_grp; g += kSegWaves) {  // uniform
       const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
-      const uint32_t* wg = w + g * opg;
-      const T v0 = 2u * lane < left ? __builtin_bit_cast(T, wg[2u * lane]) : pad;
-      const T v1 = 2u * lane + 1u < left ? __builtin_bit_cast(T, wg[2u * lane + 1u]) : pad;
-      const T v = lanes_reduce<kWave>(op(v0, v1), op);
-      if (lane == 0u) finish(g, v);
+      const uint32_t first = g * opg;
+      const bool there0 = 2u * lane < left, there1 = 2u * lane + 1u < left;
+      T v0 = op0(there0 ? __builtin_bit_cast(T, w0[first + 2u * lane]) : pad0,
+                 there1 ? __builtin_bit_cast(T, w0[first + 2u * lane + 1u]) : pad0);
+      v0 = lanes_reduce<kWave>(v0, op0);
+      T v1 = pad1;
+      if constexpr (TWO) {
+        v1 = op1(there0 ? __builtin_bit_cast(T, w1[first + 2u * lane]) : pad1,
+                 there1 ? __builtin_bit_cast(T, w1[first + 2u * lane + 1u]) : pad1);
+        v1 = lanes_reduce<kWave>(v1, op1);
+      }
+      if (lane == 0u) finish(g, v0, v1);
     }
   } else {
     static_assert(kSegWaves == 4, "the wavefronts' results are combined as a tree of four");
     const uint32_t per = 1u << (lg - 8u);  // words per thread: 1 .. 8
     for (uint32_t g = 0; g < n_grp; ++g) {  // uniform
       const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
-      const uint32_t* wg = w + g * opg;
-      // the thread's `per` consecutive words as the tree over 8 with `pad` for the rest (the identity: same value)
-      T t[8];
+      const uint32_t first = g * opg;
+      // the thread's `per` consecutive words as the tree over 8 with the pad for the rest (the identity: same value)
+      T t[8], u[8];
 #pragma unroll
       for (uint32_t i = 0; i < 8u; ++i) {
         const uint32_t o = threadIdx.x * per + i;
-        t[i] = (i < per && o < left) ? __builtin_bit_cast(T, wg[o]) : pad;
+        const bool there = i < per && o < left;
+        t[i] = there ? __builtin_bit_cast(T, w0[first + o]) : pad0;
+        if constexpr (TWO) u[i] = there ? __builtin_bit_cast(T, w1[first + o]) : pad1;
       }
-      T v = op(op(op(t[0], t[1]), op(t[2], t[3])), op(op(t[4], t[5]), op(t[6], t[7])));
-      v = lanes_reduce<kWave>(v, op);
-      uint32_t* meet = sh.head + 40u + (g & 1u) * kSegWaves;
-      if (lane == 0u) meet[wave] = __builtin_bit_cast(uint32_t, v);
+      T v0 = op0(op0(op0(t[0], t[1]), op0(t[2], t[3])), op0(op0(t[4], t[5]), op0(t[6], t[7])));
+      v0 = lanes_reduce<kWave>(v0, op0);
+      T v1 = pad1;
+      if constexpr (TWO) {
+        v1 = op1(op1(op1(u[0], u[1]), op1(u[2], u[3])), op1(op1(u[4], u[5]), op1(u[6], u[7])));
+        v1 = lanes_reduce<kWave>(v1, op1);
+      }
+      uint32_t* meet = sh.head + 40u + (g & 1u) * 2u * kSegWaves;  // two sets of [w0: 4 words][w1: 4 words]
+      if (lane == 0u) {
+        meet[wave] = __builtin_bit_cast(uint32_t, v0);
+        if constexpr (TWO) meet[kSegWaves + wave] = __builtin_bit_cast(uint32_t, v1);
+      }
       __syncthreads();
-      if (threadIdx.x == 0u)
-        finish(g, op(op(__builtin_bit_cast(T, meet[0]), __builtin_bit_cast(T, meet[1])),
-                     op(__builtin_bit_cast(T, meet[2]), __builtin_bit_cast(T, meet[3]))));
+      if (threadIdx.x == 0u) {
+        const T r0 = op0(op0(__builtin_bit_cast(T, meet[0]), __builtin_bit_cast(T, meet[1])),
+                         op0(__builtin_bit_cast(T, meet[2]), __builtin_bit_cast(T, meet[3])));
+        T r1 = pad1;
+        if constexpr (TWO)
+          r1 = op1(op1(__builtin_bit_cast(T, meet[4]), __builtin_bit_cast(T, meet[5])),
+                   op1(__builtin_bit_cast(T, meet[6]), __builtin_bit_cast(T, meet[7])));
+        finish(g, r0, r1);
+      }
     }
     __syncthreads();  // the words in head[] are free for the next call
   }
@@ -243,16 +271,11 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
     }
     __syncthreads();
     const uint32_t opg = d.gs / (uint32_t)kOct;
-    float* mean = reinterpret_cast<float*>(sh.g1);
-    groups_tree<float>(sh, sh.a, g.octs, opg, 0.0f, OpAdd(), [&](uint32_t grp, float s1) {
+    groups_tree<true, float>(sh, sh.a, sh.b, g.octs, opg, 0.0f, 0.0f, OpAdd(), OpAdd(), [&](uint32_t grp, float s1, float s2) {
       const uint32_t left = g.cnt - grp * d.gs;
-      mean[grp] = __fdiv_rn(s1, (float)(left < d.gs ? left : d.gs));
-    });
-    // (a group's two words are written and read by the same thread)
-    groups_tree<float>(sh, sh.b, g.octs, opg, 0.0f, OpAdd(), [&](uint32_t grp, float s2) {
-      const uint32_t left = g.cnt - grp * d.gs;
-      const float m = mean[grp];
-      float var = __fmaf_rn(-m, m, __fdiv_rn(s2, (float)(left < d.gs ? left : d.gs)));
+      const float n = (float)(left < d.gs ? left : d.gs);
+      const float m = __fdiv_rn(s1, n);
+      float var = __fmaf_rn(-m, m, __fdiv_rn(s2, n));
       var = (var < 0.0f) ? 0.0f : var;  // a NaN stays a NaN: then nothing passes the test
       sh.g0[grp] = __float_as_uint(d.param * var);  // param = k * k
     });
@@ -597,6 +620,46 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
     }
     return;
   }
+  if (d.gq >= d.tile_elems) {  // uniform
+    // The segment is one group: the extremes meet thread by thread, wavefront by wavefront (any order does).
+    static_assert(kSegWaves == 4, "four words per extreme in head[]");
+    const uint32_t lane = (uint32_t)lane_id(), wave = tid / (uint32_t)kWave;
+    uint32_t gm = 0u;
+    int32_t hi = (int32_t)0x80000000, lo = (int32_t)0x7FFFFFFF;
+    if constexpr (!ASYM) {
+#pragma unroll
+      for (int j = 0; j < SL; ++j) gm = omag[j] > gm ? omag[j] : gm;
+      gm = wave_max_u32_scalar(gm);
+      if (lane == 0u) sh.head[40u + wave] = gm;
+    } else {
+#pragma unroll
+      for (int j = 0; j < SL; ++j) {
+        const uint32_t o = tid + (uint32_t)j * kSegThreads;
+        int32_t h, l;
+        octet_extreme_keys(g, raw[j], o, h, l);
+        hi = (o < g.octs && h > hi) ? h : hi;
+        lo = (o < g.octs && l < lo) ? l : lo;
+      }
+      hi = lanes_reduce<kWave>(hi, OpIMax());
+      lo = lanes_reduce<kWave>(lo, OpIMin());
+      if (lane == 0u) { sh.head[40u + wave] = (uint32_t)hi; sh.head[44u + wave] = (uint32_t)lo; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t w = 0; w < kSegWaves; ++w) {
+      if constexpr (!ASYM) {
+        gm = sh.head[40u + w] > gm ? sh.head[40u + w] : gm;
+      } else {
+        const int32_t h = (int32_t)sh.head[40u + w], l = (int32_t)sh.head[44u + w];
+        hi = h > hi ? h : hi;
+        lo = l < lo ? l : lo;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < SL; ++j)
+      octet_quantise<BITS, ASYM>(d, g, raw[j], tid + (uint32_t)j * kSegThreads, 0u, opg, first_group, gm, hi, lo);
+    return;
+  }
   // Other groups: one word (two) per octet to LDS (an octet that does not exist writes a word that nobody reads) ..
 #pragma unroll
   for (int j = 0; j < SL; ++j) {
@@ -614,10 +677,11 @@ __device__ __forceinline__ void segment_quantise(const TensorDesc& d, const Segm
   // .. the groups' extremes to g0 (g1); every thread then forms D / max (and the offset) for each of its octets
   // itself instead of a few lanes doing it for all
   if constexpr (!ASYM) {
-    groups_tree<uint32_t>(sh, sh.a, g.octs, opg, 0u, OpUMax(), [&](uint32_t grp, uint32_t mag) { sh.g0[grp] = mag; });
+    groups_tree<false, uint32_t>(sh, sh.a, sh.a, g.octs, opg, 0u, 0u, OpUMax(), OpUMax(),
+                                 [&](uint32_t grp, uint32_t mag, uint32_t) { sh.g0[grp] = mag; });
   } else {
-    groups_tree<int32_t>(sh, sh.a, g.octs, opg, (int32_t)0x80000000, OpIMax(), [&](uint32_t grp, int32_t hi) { sh.g0[grp] = (uint32_t)hi; });
-    groups_tree<int32_t>(sh, sh.b, g.octs, opg, (int32_t)0x7FFFFFFF, OpIMin(), [&](uint32_t grp, int32_t lo) { sh.g1[grp] = (uint32_t)lo; });
+    groups_tree<true, int32_t>(sh, sh.a, sh.b, g.octs, opg, (int32_t)0x80000000, (int32_t)0x7FFFFFFF, OpIMax(), OpIMin(),
+                               [&](uint32_t grp, int32_t hi, int32_t lo) { sh.g0[grp] = (uint32_t)hi; sh.g1[grp] = (uint32_t)lo; });
   }
   __syncthreads();
   const float recip = group_reciprocal(opg);
