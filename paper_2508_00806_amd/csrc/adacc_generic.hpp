@@ -10,7 +10,7 @@
 // from all their octets - the pairwise sums of the STD rule, the largest magnitude or the extremes of a
 // quantisation group - goes through one word per octet in LDS and is reduced there by as many adjacent lanes
 // as the group has octets (rounded up to a power of two; a wavefront per group beyond 64 octets, the whole
-// workgroup beyond 128).  The definitions are those of the fast kernels: canonical pairwise sums (pad to a power
+// workgroup beyond 256).  The definitions are those of the fast kernels: canonical pairwise sums (pad to a power
 // of two, add neighbours level by level), mean and variance over the group's own count, the k largest by
 // (magnitude, lower index), the correctly rounded D / max, the same rounding of the codes.
 //
@@ -111,7 +111,7 @@ __device__ __forceinline__ T lanes_reduce_lg(T v, uint32_t lg, Op op) {
 // For every group of `opg` consecutive octets (the last group of the segment may have fewer; n_oct octets in
 // all): the balanced binary tree `op` over the group's words w[], padded with `pad` to the next power of two;
 // finish(group, result) is called by one thread per group.  Groups of up to 64 octets are taken by as many
-// adjacent lanes as the padded group has octets, several groups to a wavefront; groups of up to 128 by a
+// adjacent lanes as the padded group has octets, several groups to a wavefront; groups of up to 256 by a
 // wavefront each; longer ones by the whole workgroup in turn, every thread folding the padded group's consecutive
 // words that fall to it first, the wavefronts' results meeting in head[40..47] (two sets, used in turn).
 // Called by all threads of the workgroup.  (For sums the padding adds +0.0 to partial sums, which changes no value.)
@@ -138,25 +138,28 @@ __device__ __forceinline__ void groups_tree(SegmentShared& sh, const uint32_t* w
       if constexpr (TWO) v1 = lanes_reduce_lg(v1, lg, op1);
       if (g < n_grp && leaf == 0u) finish(g, v0, v1);
     }
-  } else if (lg == 7u) {
+  } else if (lg <= 8u) {
+    const uint32_t per = 1u << (lg - 6u);  // consecutive words per lane: 2 or 4
     for (uint32_t g = wave; g < n_grp; g += kSegWaves) {  // uniform
       const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
       const uint32_t first = g * opg;
-      const bool there0 = 2u * lane < left, there1 = 2u * lane + 1u < left;
-      T v0 = op0(there0 ? __builtin_bit_cast(T, w0[first + 2u * lane]) : pad0,
-                 there1 ? __builtin_bit_cast(T, w0[first + 2u * lane + 1u]) : pad0);
-      v0 = lanes_reduce<kWave>(v0, op0);
-      T v1 = pad1;
-      if constexpr (TWO) {
-        v1 = op1(there0 ? __builtin_bit_cast(T, w1[first + 2u * lane]) : pad1,
-                 there1 ? __builtin_bit_cast(T, w1[first + 2u * lane + 1u]) : pad1);
-        v1 = lanes_reduce<kWave>(v1, op1);
+      // the lane's words as the tree over 4 with the pad for the rest (the identity: same value)
+      T t[4], u[4];
+#pragma unroll
+      for (uint32_t i = 0; i < 4u; ++i) {
+        const uint32_t o = lane * per + i;
+        const bool there = i < per && o < left;
+        t[i] = there ? __builtin_bit_cast(T, w0[first + o]) : pad0;
+        if constexpr (TWO) u[i] = there ? __builtin_bit_cast(T, w1[first + o]) : pad1;
       }
+      const T v0 = lanes_reduce<kWave>(op0(op0(t[0], t[1]), op0(t[2], t[3])), op0);
+      T v1 = pad1;
+      if constexpr (TWO) v1 = lanes_reduce<kWave>(op1(op1(u[0], u[1]), op1(u[2], u[3])), op1);
       if (lane == 0u) finish(g, v0, v1);
     }
   } else {
     static_assert(kSegWaves == 4, "the wavefronts' results are combined as a tree of four");
-    const uint32_t per = 1u << (lg - 8u);  // words per thread: 1 .. 8
+    const uint32_t per = 1u << (lg - 8u);  // words per thread: 2 .. 8
     for (uint32_t g = 0; g < n_grp; ++g) {  // uniform
       const uint32_t left = n_oct - g * opg < opg ? n_oct - g * opg : opg;
       const uint32_t first = g * opg;
@@ -402,7 +405,8 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
       __syncthreads();  // a, b are free again
     } else {
       // Several groups (of at most 2048 elements): the patterns go to LDS, a wavefront takes a group at a time
-      // with the keys of its elements in registers (32 per lane at most), k rounds of a maximum over the wavefront.
+      // with the keys of its elements in registers (2, 8 or 32 per lane by the size of the groups), k rounds of a
+      // maximum over the wavefront.
       uint16_t* pat = reinterpret_cast<uint16_t*>(sh.a);
 #pragma unroll
       for (int j = 0; j < SL; ++j) {
@@ -412,30 +416,36 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
       }
       __syncthreads();
       const uint32_t lane = (uint32_t)lane_id();
-      for (uint32_t e0 = (tid / (uint32_t)kWave) * d.gs; e0 < g.cnt; e0 += kSegWaves * d.gs) {  // uniform
-        const uint32_t n = g.cnt - e0 < d.gs ? g.cnt - e0 : d.gs;
-        constexpr int kCap = 32;
-        uint32_t key[kCap];
+      // KC: keys per lane, 64 * KC elements at most in a group
+      auto groups_of = [&](auto KCc) {
+        constexpr int KC = decltype(KCc)::value;
+        for (uint32_t e0 = (tid / (uint32_t)kWave) * d.gs; e0 < g.cnt; e0 += kSegWaves * d.gs) {  // uniform
+          const uint32_t n = g.cnt - e0 < d.gs ? g.cnt - e0 : d.gs;
+          uint32_t key[KC];
 #pragma unroll
-        for (int k = 0; k < kCap; ++k) {
-          const uint32_t i = lane + (uint32_t)k * (uint32_t)kWave;
-          key[k] = i < n ? (((uint32_t)(pat[e0 + i] & 0x7FFFu) << 16) | (0xFFFFu - i)) : 0u;
+          for (int k = 0; k < KC; ++k) {
+            const uint32_t i = lane + (uint32_t)k * (uint32_t)kWave;
+            key[k] = i < n ? (((uint32_t)(pat[e0 + i] & 0x7FFFu) << 16) | (0xFFFFu - i)) : 0u;
+          }
+          const uint32_t rounds = d.topk < n ? d.topk : n;
+          for (uint32_t r = 0; r < rounds; ++r) {
+            uint32_t best = 0u;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) best = key[k] > best ? key[k] : best;
+            const uint32_t win = wave_max_u32_scalar(best);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) key[k] = key[k] == win ? 0u : key[k];
+          }
+#pragma unroll
+          for (int k = 0; k < KC; ++k) {
+            const uint32_t i = lane + (uint32_t)k * (uint32_t)kWave;
+            if (i < n) sh.byte[e0 + i] = key[k] == 0u ? 1 : 0;
+          }
         }
-        const uint32_t rounds = d.topk < n ? d.topk : n;
-        for (uint32_t r = 0; r < rounds; ++r) {
-          uint32_t best = 0u;
-#pragma unroll
-          for (int k = 0; k < kCap; ++k) best = key[k] > best ? key[k] : best;
-          const uint32_t win = wave_max_u32_scalar(best);
-#pragma unroll
-          for (int k = 0; k < kCap; ++k) key[k] = key[k] == win ? 0u : key[k];
-        }
-#pragma unroll
-        for (int k = 0; k < kCap; ++k) {
-          const uint32_t i = lane + (uint32_t)k * (uint32_t)kWave;
-          if (i < n) sh.byte[e0 + i] = key[k] == 0u ? 1 : 0;
-        }
-      }
+      };
+      if (d.gs <= 2u * (uint32_t)kWave) groups_of(std::integral_constant<int, 2>());       // uniform
+      else if (d.gs <= 8u * (uint32_t)kWave) groups_of(std::integral_constant<int, 8>());
+      else groups_of(std::integral_constant<int, 32>());
       __syncthreads();
 #pragma unroll
       for (int j = 0; j < SL; ++j) {
