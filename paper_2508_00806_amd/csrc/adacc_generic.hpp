@@ -361,7 +361,7 @@ __device__ __forceinline__ void segment_select(const TensorDesc& d, const Segmen
         if (okey[j] != 0u && okey[j] >= least) {  // at most k octets of the workgroup
           const uint32_t o = tid + (uint32_t)j * kSegThreads;
           const uint32_t nv = octet_valid(g, o);
-          const uint32_t entry = atomicAdd(&sh.head[0], 1u);
+          const uint32_t entry = atomicAdd(&sh.head[0], 1u) & 31u;  // (below 32 anyway: keys are unique)
 #pragma unroll
           for (int e = 0; e < kOct; ++e)
             sh.b[entry * (uint32_t)kOct + (uint32_t)e] =
