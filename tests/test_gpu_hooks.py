@@ -104,6 +104,42 @@ def test_mlp_trains_one_step_with_compressed_activations():
         assert rel < 0.05, float(rel)
 
 
+def test_llama_shaped_mlp_with_whole_rows_as_groups():
+    """A gated MLP with LLaMA's ratio of widths (344 = 11008 / 32 is no power of two): the policy keeps the
+    4 largest values of every row exactly and gives the rest int4 in groups of 8 - group sizes that run in the
+    fallback kernels, forward and backward, under the hooks."""
+    print("[hooks] rows as groups", flush=True)
+    torch.manual_seed(9)
+
+    class Gated(torch.nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.up = torch.nn.Linear(128, 344)
+            self.gate = torch.nn.Linear(128, 344)
+            self.down = torch.nn.Linear(344, 128)
+
+        def forward(self, x):
+            return self.down(torch.nn.functional.silu(self.gate(x)) * self.up(x))
+
+    mlp = Gated().cuda().to(torch.bfloat16)
+    x = torch.randn(96, 128).to(torch.bfloat16).cuda()
+    ref = _grads(mlp, x, None)
+
+    def policy(t):
+        if t.shape[-1] != 344:
+            return None
+        return adacc.Method(bits=8, quant_group=8, outlier_mode=adacc.OUTLIER_TOPK, stat_group=344, topk=4,
+                            max_outliers=4 * (t.numel() // 344))
+    ctx = SavedActivationCompression(policy)
+    got = _grads(mlp, x, ctx)
+    rep = ctx.report()
+    assert len(rep) >= 3 and all(r["n_outliers"] == 4 * 96 and not r["overflow"] for r in rep), rep
+    for a, b in zip(got, ref):
+        assert torch.isfinite(a).all()
+        rel = (a.float() - b.float()).norm() / b.float().norm()
+        assert rel < 0.05, float(rel)
+
+
 def _grads(model, x, ctx):
     """Detached copies of the parameter gradients of one forward / backward pass."""
     for p in model.parameters():
