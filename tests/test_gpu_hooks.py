@@ -106,7 +106,7 @@ def test_mlp_trains_one_step_with_compressed_activations():
 
 def test_llama_shaped_mlp_with_whole_rows_as_groups():
     """A gated MLP with LLaMA's ratio of widths (344 = 11008 / 32 is no power of two): the policy keeps the
-    4 largest values of every row exactly and gives the rest int4 in groups of 8 - group sizes that run in the
+    4 largest values of every row exactly and gives the rest int8 in groups of 8 - group sizes that run in the
     fallback kernels, forward and backward, under the hooks."""
     print("[hooks] rows as groups", flush=True)
     torch.manual_seed(9)
