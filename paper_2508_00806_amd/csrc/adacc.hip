@@ -842,6 +842,15 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
     kind[i] = batch_kind(&methods[origin[i]], plans[origin[i]]) + (plans[origin[i]].half ? kBatchKinds : 0);
   }
   group_launches(units, kind, &members, &tiles);
+  // The table goes up in the order of the tile launches' member lists, so that the tile kernels find the entry
+  // of blockIdx.y at table + first_member without looking a number up first; the other kernels keep their lists.
+  const uint32_t n_listed = (uint32_t)members.size();
+  std::vector<uint32_t> place(nt, 0xFFFFFFFFu);
+  std::vector<TensorDesc> ordered;
+  ordered.reserve(nt);
+  for (uint32_t j = 0; j < n_listed; ++j) { place[members[j]] = j; ordered.push_back(descs[members[j]]); }
+  for (uint32_t i = 0; i < nt; ++i)
+    if (place[i] == 0xFFFFFFFFu) { place[i] = (uint32_t)ordered.size(); ordered.push_back(descs[i]); }
   for (uint32_t i = 0; i < nt; ++i) {
     units[i] = (!descs[i].generic && needs_block_sums(&methods[origin[i]], plans[origin[i]])) ? descs[i].n_blocks : 0u;
     kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
@@ -851,19 +860,20 @@ int adacc_compress_batch(uint32_t n, const adacc_method* methods, const void* co
   group_launches(units, kind, &members, &places);
   for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].tail != 0u ? 1u : 0u;
   group_launches(units, kind, &members, &tails);
+  for (uint32_t j = n_listed; j < (uint32_t)members.size(); ++j) members[j] = place[members[j]];
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   uint32_t epoch = 0;
   rc = next_epoch(ws, s, &epoch);
   if (rc != ADACC_OK) return rc;
   TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
   uint32_t* dm = reinterpret_cast<uint32_t*>(mem + bp.members_off);
-  rc = upload_table(descs, dt, s);
-  if (rc == ADACC_OK) rc = upload_words(members, dm, s);
+  rc = upload_table(ordered, dt, s);
+  if (rc == ADACC_OK && members.size() > n_listed) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : tiles)
     hipLaunchKernelGGL(compress_batch_fn(g.kind >= kBatchKinds, g.kind % kBatchKinds),
                        dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members),
-                       dim3(kThreads), 0, s, dt, dm + g.first_member, epoch);
+                       dim3(kThreads), 0, s, dt + g.first_member, static_cast<const uint32_t*>(nullptr), epoch);
   rc = launch_check("compress_batch_kernel");
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : sums)
@@ -916,20 +926,30 @@ int adacc_decompress_batch(uint32_t n, const adacc_method* methods, const void* 
     kind[i] = plans[origin[i]].half ? kBatchKinds : 0;
   }
   group_launches(units, kind, &members, &launches);
+  // The table goes up in the order of the launches' member lists, so that the main kernels find the entry of
+  // blockIdx.y at table + first_member without looking a number up first; the tail kernels keep their lists.
+  const uint32_t n_listed = (uint32_t)members.size();
+  std::vector<uint32_t> place(nt, 0xFFFFFFFFu);
+  std::vector<TensorDesc> ordered;
+  ordered.reserve(nt);
+  for (uint32_t j = 0; j < n_listed; ++j) { place[members[j]] = j; ordered.push_back(descs[members[j]]); }
+  for (uint32_t i = 0; i < nt; ++i)
+    if (place[i] == 0xFFFFFFFFu) { place[i] = (uint32_t)ordered.size(); ordered.push_back(descs[i]); }
   std::vector<GroupLaunch> tails;
   for (uint32_t i = 0; i < nt; ++i) units[i] = descs[i].tail != 0u ? 1u : 0u;
   group_launches(units, kind, &members, &tails);
+  for (uint32_t j = n_listed; j < (uint32_t)members.size(); ++j) members[j] = place[members[j]];
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   unsigned char* mem = static_cast<unsigned char*>(ws->device_mem);
   TensorDesc* dt = reinterpret_cast<TensorDesc*>(mem);
   uint32_t* dm = reinterpret_cast<uint32_t*>(mem + bp.members_off);
-  rc = upload_table(descs, dt, s);
-  if (rc == ADACC_OK) rc = upload_words(members, dm, s);
+  rc = upload_table(ordered, dt, s);
+  if (rc == ADACC_OK && members.size() > n_listed) rc = upload_words(members, dm, s);
   if (rc != ADACC_OK) return rc;
   for (const GroupLaunch& g : launches)
     hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, decompress_batch_fn(dst_dtype == ADACC_DST_F32)),
-                       dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members), dim3(kThreads), 0, s, dt,
-                       dm + g.first_member);
+                       dim3((g.max_units + kWavesPerWg - 1) / kWavesPerWg, g.n_members), dim3(kThreads), 0, s,
+                       dt + g.first_member, static_cast<const uint32_t*>(nullptr));
   for (const GroupLaunch& g : tails)
     hipLaunchKernelGGL(ADACC_PICK(g.kind >= kBatchKinds, decompress_tail_batch_fn()), dim3(g.n_members), dim3(kWave), 0, s, dt,
                        dm + g.first_member);

@@ -87,7 +87,9 @@ template <int KIND>
 __global__ __launch_bounds__(kThreads, (batch_min_waves<KIND>())) void compress_batch_kernel(const TensorDesc* table, const uint32_t* members,
                                                                   uint32_t epoch) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  const TensorDesc d = table[members[blockIdx.y]];
+  // members == nullptr: the group's entries are table[0 .. gridDim.y) themselves (the host lays the table out in the
+  // order of these launches): one round trip to memory less before the wavefront's first load
+  const TensorDesc d = table[members ? members[blockIdx.y] : blockIdx.y];
   const uint32_t tile = blockIdx.x * kWavesPerWg + wave;
   if (tile >= d.n_tiles) return;
   constexpr int E = (KIND == kBatchAny8 || KIND == kBatchTopk8) ? 8 : 4;
@@ -105,10 +107,12 @@ __global__ __launch_bounds__(kThreads, (batch_min_waves<KIND>())) void compress_
 }
 
 // Batch decompression: the same grouping, over the 2048-element pieces of the tensors.
+// members == nullptr: the group's entries are table[0 .. gridDim.y) themselves (the host lays the table out in
+// the order of the launches), which saves the wavefront one of its two round trips to memory before its first load.
 template <bool F32>
 __global__ __launch_bounds__(kThreads) void decompress_batch_kernel(const TensorDesc* table, const uint32_t* members) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform, and the compiler shall know it
-  const TensorDesc d = table[members[blockIdx.y]];
+  const TensorDesc d = table[members ? members[blockIdx.y] : blockIdx.y];
   const uint32_t piece = blockIdx.x * kWavesPerWg + wave;
   if (piece >= d.n_tiles) return;
   const bool ho = (d.variant >> 3) != kModeNone;
